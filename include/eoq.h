@@ -1,0 +1,148 @@
+/*
+ * eoq.h -- C ABI of the eOptShrinkQ KV-cache block compression library for
+ * AMD MI355X (gfx950).
+ *
+ * One "block" is n consecutive key (or value) vectors of one attention head,
+ * a row-major n x d matrix (paper Sec. 2.3 last paragraph: the cache is cut
+ * into blocks of n tokens, each processed independently; Alg. 3 takes one
+ * block).  A batch is B blocks stored back to back, [B][n][d].
+ *
+ * Every pointer argument is documented as HOST or DEVICE.  Device buffers are
+ * owned by the caller (e.g. torch tensors); the library allocates device
+ * memory only in eoq_create (rotation and codebook tables) and frees it in
+ * eoq_destroy.  eoq_compress / eoq_decompress / eoq_scores launch kernels on
+ * the given HIP stream and return without synchronising; they never allocate.
+ * All device pointers must be 16-byte aligned.  Functions return EOQ_OK or an
+ * error code; they never abort.  A human-readable reason for the last failure
+ * is kept per context (eoq_last_error).
+ */
+#ifndef EOQ_H_
+#define EOQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct eoq_ctx eoq_ctx;
+
+typedef enum {
+  EOQ_OK = 0,
+  EOQ_ERR_ARG = 1,          /* null / misaligned pointer, negative size */
+  EOQ_ERR_UNSUPPORTED = 2,  /* (n, d, bits, r_max, head grouping) outside the supported set */
+  EOQ_ERR_WORKSPACE = 3,    /* workspace smaller than eoq_workspace_bytes() */
+  EOQ_ERR_HIP = 4           /* a HIP runtime call failed */
+} eoq_status;
+
+typedef enum { EOQ_F16 = 0, EOQ_F32 = 1 } eoq_dtype;
+
+/* Flag bits of eoq_packed.flags[b]. */
+#define EOQ_FLAG_RANK_CLAMPED 1u /* estimated rank exceeded r_max and was cut to r_max */
+#define EOQ_FLAG_SHRINK_GUARD 2u /* a D-transform estimate was degenerate; that component got phi = 0 */
+#define EOQ_FLAG_NO_CONVERGE  4u /* the eigensolver hit its sweep limit */
+
+/*
+ * The compressed record of a batch (Alg. 3, "Store": shrunken SVD factors of
+ * the r^+ retained components, TQ indices and norms of the residual).  All
+ * members are DEVICE pointers, caller-owned.
+ *
+ *   codes [B][n][bits*d/8]  per token `bits` bit-planes of d/8 bytes; plane p
+ *                           holds bit p of the d code indices, coordinate j in
+ *                           bit (j mod 8) of byte j/8.  Index 0 is the most
+ *                           negative centroid (Alg. 1 line 5).
+ *   norms [B][n]            binary16 bit patterns of the residual row norms
+ *                           (Alg. 1 line 3; Remark 3.1: one FP16 norm per row).
+ *   rank  [B]               r^+ of Alg. 2 Step 1, clamped to r_max.
+ *   phi   [B][r_max]        shrunk singular values (Alg. 2 Step 3), first r^+ valid.
+ *   sigma [B][r_max]        observed singular values of the same components.
+ *   lfac  [B][r_max][n]     binary16 U diag(phi), one row per component
+ *                           (Alg. 2 Return); only the first r^+ rows are written.
+ *   rfac  [B][r_max][d]     binary16 right singular vectors, same convention.
+ *   flags [B]               EOQ_FLAG_* bits.
+ */
+typedef struct {
+  uint8_t*  codes;
+  uint16_t* norms;
+  int32_t*  rank;
+  float*    phi;
+  float*    sigma;
+  uint16_t* lfac;
+  uint16_t* rfac;
+  uint32_t* flags;
+} eoq_packed;
+
+/*
+ * Create a context for blocks of n x d, `bits` residual bits per entry (Alg. 3
+ * REQUIRE), a Haar rotation drawn from `rot_seed` (Alg. 1 REQUIRE: one rotation
+ * shared by all vectors) and at most r_max stored components per block.
+ * Builds on the host, in double precision, the rotation (QR of a seeded
+ * Gaussian matrix, R's diagonal made positive) and the Lloyd-Max codebook of
+ * N(0,1) (Sec. 2.2 item 3; used scaled by 1/sqrt(d)), and uploads both to the
+ * current HIP device.
+ * Supported: d = 128; n a multiple of 128 with 128 <= n <= 4096; bits in 1..4;
+ * 1 <= r_max <= 32.  On failure *out is NULL.
+ */
+eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, int r_max);
+void       eoq_destroy(eoq_ctx* ctx);
+
+/* Pilot parameter k = floor(d^c), c = min(1/2.01, 1/log log d) of Alg. 2 (11 at d = 128). */
+int        eoq_pilot_k(int d);
+
+/* Bytes of DEVICE scratch eoq_compress needs for B blocks. */
+size_t     eoq_workspace_bytes(const eoq_ctx* ctx, int64_t B);
+
+/* Copy the rotation Pi (row-major [d][d], z = Pi u) into HOST memory, as the float32 table the kernels use. */
+eoq_status eoq_rotation(const eoq_ctx* ctx, float* host_out);
+
+/* Copy the N(0,1) codebook into HOST memory: 2^bits ascending centroids and 2^bits-1 midpoints (float32). */
+eoq_status eoq_codebook(const eoq_ctx* ctx, float* host_centroids, float* host_bounds);
+
+/*
+ * Alg. 3 on B blocks: eOptShrink (Alg. 2: eigen-decomposition of the d x d Gram
+ * matrix, bulk edge and rank, imputed noise spectrum, D-transform shrinker),
+ * residual against the stored binary16 factors (the whole block when r^+ = 0),
+ * then TQ_MSE per residual row (Alg. 1 lines 3-5) and bit-packing.
+ *   blocks     DEVICE, [B][n][d] of `dtype` (binary16 or float32), read only.
+ *   out        DEVICE buffers as described at eoq_packed; fully overwritten
+ *              except lfac/rfac rows >= rank[b].
+ *   workspace  DEVICE, >= eoq_workspace_bytes(ctx, B) bytes.  After the call
+ *              completes its first B*d doubles hold every block's Gram
+ *              eigenvalues sigma_i^2 in descending order (diagnostic).
+ *   hip_stream hipStream_t (NULL = default stream).
+ */
+eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B,
+                        eoq_packed out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Inverse of eoq_compress: x_hat_t = rho_t Pi^T z_hat_t + (U diag(phi) V^T)[t,:]
+ * (Alg. 1 line 6 plus the low-rank part), rounded to binary16.
+ *   in        DEVICE record of B blocks, read only.
+ *   out_fp16  DEVICE, [B][n][d] binary16, overwritten.
+ */
+eoq_status eoq_decompress(eoq_ctx* ctx, eoq_packed in, int64_t B, void* out_fp16, void* hip_stream);
+
+/*
+ * Attention logits on compressed keys without materialising them (Sec. 2.1,
+ * Remark 6.5): scores[s][h][t] = <q[s][h], x_hat_t> / sqrt(d), split into the
+ * low-rank term and rho_t <Pi q, z_hat_t>.
+ *   keys             DEVICE record of n_seq*n_kv_heads*blocks_per_head blocks;
+ *                    block j of KV head g of sequence s is at index
+ *                    (s*n_kv_heads + g)*blocks_per_head + j.
+ *   q_fp16           DEVICE, [n_seq][n_q_heads][d] binary16.  Query head h
+ *                    reads KV head h / (n_q_heads / n_kv_heads).
+ *   scores           DEVICE, [n_seq][n_q_heads][blocks_per_head*n] float32, overwritten.
+ * Supported: n_q_heads a multiple of n_kv_heads with group size 1..8.
+ */
+eoq_status eoq_scores(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_heads,
+                      int64_t blocks_per_head, const void* q_fp16, int n_q_heads,
+                      float* scores, void* hip_stream);
+
+/* Reason for the last error on this context (HOST string owned by the context); "" if none. */
+const char* eoq_last_error(const eoq_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EOQ_H_ */

@@ -1,0 +1,445 @@
+"""Plain float64 reference of the eOptShrinkQ hot path (NumPy, one block at a time).
+
+TEST INFRASTRUCTURE ONLY -- slow on purpose, written to be checked against the
+paper by eye.  It shares no code with the HIP library and the product path never
+imports it.
+
+Every function cites the passage of the paper (arXiv 2605.02905) it follows.
+Where the paper is silent the reading taken is stated next to the code; the full
+list of readings lives in the design notes of the repository.
+
+Parity pins (tests/test_oracle_*.py): pilot k (Remark 3.1), Gaussian Lloyd-Max
+centroids, Haar-rotation orthogonality and sign convention, brute-force SVD on
+tiny blocks, Marchenko-Pastur bulk edge, planted-rank recovery, white-noise
+closed-form Frobenius shrinker, Prop. 6.1 / Cor. 6.3 residual properties, the
+sqrt(D_b) distortion the paper's Tables 1-4 print for TQ_MSE, bit accounting of
+Alg. 3 and Sec. 4.1, and the score identity of Remark 6.5.
+Parity unpinned (finer than ~1 %): the 1/M normalisation of the imputed noise
+measure and the labelling of the two Stieltjes transforms (see `shrink`).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+
+import numpy as np
+
+__all__ = [
+    "pilot_k", "rank_threshold", "EDGE_COEF",
+    "lloyd_max_gaussian", "Codebook",
+    "splitmix64", "gaussian_stream", "haar_rotation",
+    "bulk_edge", "estimate_rank", "impute_noise_spectrum", "shrink",
+    "EOptShrinkResult", "eoptshrink",
+    "tq_mse_encode", "tq_mse_decode",
+    "BlockRecord", "compress_block", "decompress_block", "score_block",
+    "pack_codes", "unpack_codes", "fp16_round", "fp16_bits", "bits_per_entry",
+    "FLAG_RANK_CLAMPED", "FLAG_SHRINK_GUARD",
+]
+
+FLAG_RANK_CLAMPED = 1
+FLAG_SHRINK_GUARD = 2
+
+# 1 / (2^{2/3} - 1): the constant of the square-root-edge extrapolation in
+# Alg. 2, Steps 1 and 2.
+EDGE_COEF = 1.0 / (2.0 ** (2.0 / 3.0) - 1.0)
+
+
+# --------------------------------------------------------------------------
+# constants of Alg. 2
+# --------------------------------------------------------------------------
+def pilot_k(d: int) -> int:
+    """k = floor(d^c), c = min(1/2.01, 1/log log d), natural logarithms.
+
+    Alg. 2 REQUIRE and Step 1; Remark 3.1 prints k = 11 for d = 128 and the
+    remark after Prop. 6.1's proof gives k ~ 7 for d = 64.
+    """
+    c = min(1.0 / 2.01, 1.0 / math.log(math.log(d)))
+    return int(math.floor(d ** c))
+
+
+def rank_threshold(d: int) -> float:
+    """d^{-1/3}, the relative margin above the bulk edge in Alg. 2 Step 1."""
+    return float(d) ** (-1.0 / 3.0)
+
+
+# --------------------------------------------------------------------------
+# Lloyd-Max codebook for a Gaussian marginal (Sec. 2.2 item 3, Alg. 1 REQUIRE)
+# --------------------------------------------------------------------------
+@dataclass
+class Codebook:
+    bits: int
+    centroids: np.ndarray      # float64, ascending, for N(0,1)
+    bounds: np.ndarray         # float64, ascending midpoints, 2^b - 1 of them
+    centroids_f32: np.ndarray  # the stored table
+    bounds_f32: np.ndarray
+    distortion: float          # E (x - Q(x))^2 for x ~ N(0,1)
+
+
+def _phi(x):
+    return math.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
+
+
+def _Phi(x):
+    return 0.5 * math.erfc(-x / math.sqrt(2.0))
+
+
+def lloyd_max_gaussian(bits: int, tol: float = 1e-15, max_iter: int = 200000) -> Codebook:
+    """MSE-optimal 2^b-level scalar quantizer of N(0,1) by the Lloyd iteration.
+
+    Sec. 2.2 item 3: the codebook is optimised for the N(0,1/d) marginal of a
+    rotated unit vector; that codebook is this one scaled by 1/sqrt(d).
+    Fixed point: boundaries are midpoints of neighbouring centroids, centroids
+    are conditional means  (phi(a) - phi(b)) / (Phi(b) - Phi(a))  of their cell.
+    """
+    L = 1 << bits
+    # start from equiprobable-cell means (any sorted start converges: the
+    # Gaussian density is log-concave, so the fixed point is unique)
+    c = np.array([(i + 0.5) / L * 6.0 - 3.0 for i in range(L)], dtype=np.float64)
+    for _ in range(max_iter):
+        b = 0.5 * (c[:-1] + c[1:])
+        edges = [-math.inf] + list(b) + [math.inf]
+        new = np.empty(L)
+        for i in range(L):
+            lo, hi = edges[i], edges[i + 1]
+            plo = 0.0 if lo == -math.inf else _phi(lo)
+            phi_ = 0.0 if hi == math.inf else _phi(hi)
+            if i >= L // 2:
+                # upper tail: use complementary CDFs so the mass keeps its
+                # relative accuracy
+                mass = 0.5 * (math.erfc(lo / math.sqrt(2.0)) - (0.0 if hi == math.inf else math.erfc(hi / math.sqrt(2.0))))
+            else:
+                mass = (1.0 if hi == math.inf else _Phi(hi)) - (0.0 if lo == -math.inf else _Phi(lo))
+            new[i] = (plo - phi_) / mass
+        # the optimum is symmetric; enforce it so both halves carry the same bits
+        new = 0.5 * (new - new[::-1])
+        delta = float(np.max(np.abs(new - c)))
+        c = new
+        if delta < tol:
+            break
+    b = 0.5 * (c[:-1] + c[1:])
+    # distortion  E x^2 - sum_i mass_i c_i^2  (centroid condition)
+    edges = [-math.inf] + list(b) + [math.inf]
+    ec2 = 0.0
+    for i in range(L):
+        lo, hi = edges[i], edges[i + 1]
+        mass = (1.0 if hi == math.inf else _Phi(hi)) - (0.0 if lo == -math.inf else _Phi(lo))
+        ec2 += mass * c[i] * c[i]
+    return Codebook(bits, c, b, c.astype(np.float32), b.astype(np.float32), 1.0 - ec2)
+
+
+# --------------------------------------------------------------------------
+# seeded Haar rotation (Sec. 2.2 item 2; Alg. 1 REQUIRE "shared Haar rotation")
+# --------------------------------------------------------------------------
+_M64 = (1 << 64) - 1
+
+
+def splitmix64(seed: int, counter: np.ndarray) -> np.ndarray:
+    """SplitMix64 output for state seed + (counter+1)*golden, vectorised.
+
+    Counter-based: value number `counter` of the stream `seed` (public-domain
+    generator of Steele, Lea & Flood / Vigna).
+    """
+    with np.errstate(over="ignore"):
+        z = (np.uint64(seed & _M64) + (counter.astype(np.uint64) + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15))
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        z = z ^ (z >> np.uint64(31))
+    return z
+
+
+def gaussian_stream(seed: int, count: int) -> np.ndarray:
+    """`count` iid N(0,1) draws: Box-Muller cosine branch on counters (2e, 2e+1)."""
+    e = np.arange(count, dtype=np.uint64)
+    a = splitmix64(seed, 2 * e)
+    b = splitmix64(seed, 2 * e + 1)
+    u1 = ((a >> np.uint64(11)).astype(np.float64) + 0.5) * (2.0 ** -53)
+    u2 = ((b >> np.uint64(11)).astype(np.float64) + 0.5) * (2.0 ** -53)
+    return np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * math.pi * u2)
+
+
+def haar_rotation(d: int, seed: int) -> np.ndarray:
+    """Haar-distributed orthogonal Pi (float64): QR of a d x d Gaussian matrix
+    filled row-major from `gaussian_stream`, columns of Q re-signed so that R
+    has a positive diagonal (this makes the law of Q exactly Haar).
+    """
+    g = gaussian_stream(seed, d * d).reshape(d, d)
+    q, r = np.linalg.qr(g)
+    s = np.sign(np.diag(r))
+    s[s == 0] = 1.0
+    return q * s[None, :]
+
+
+# --------------------------------------------------------------------------
+# Alg. 2 (eOptShrink)
+# --------------------------------------------------------------------------
+def bulk_edge(lam: np.ndarray, k: int) -> float:
+    """Alg. 2 Step 1: lambda_+ = lam_{k+1} + (lam_{k+1} - lam_{2k+1}) / (2^{2/3} - 1).
+
+    `lam` holds the eigenvalues sigma_i^2 in descending order; the paper's
+    subscripts are 1-based.  (Alg. 2 prints a square on the eigenvalue symbol;
+    Sec. 2.3 defines lambda_i := sigma_i^2 and Sec. 4.1 counts singular values
+    above sqrt(lambda_+), so the quantity is the eigenvalue itself.)
+    """
+    a = lam[k]          # lam_{k+1}
+    b = lam[2 * k]      # lam_{2k+1}
+    return a + EDGE_COEF * (a - b)
+
+
+def estimate_rank(lam: np.ndarray, d: int, k: int) -> tuple[int, float]:
+    """Alg. 2 Step 1: r^+ = #{ i : lam_i / lambda_+ - 1 > d^{-1/3} } (strict)."""
+    lp = bulk_edge(lam, k)
+    thr = rank_threshold(d)
+    r = int(np.count_nonzero(lam / lp - 1.0 > thr))
+    return r, lp
+
+
+def impute_noise_spectrum(lam: np.ndarray, r: int, k: int) -> np.ndarray:
+    """Alg. 2 Step 2 and Eq. (Fe): the estimated noise eigenvalues.
+
+    The r outliers are dropped; the next k values are replaced by
+        lam_{k+r+1} + (1 - (j/k)^{2/3}) / (2^{2/3}-1) * (lam_{k+r+1} - lam_{2k+r+1}),
+    j = 1..k; the rest are the observed eigenvalues.  Returns the N - r atoms
+    in descending order.
+    """
+    N = lam.shape[0]
+    a = lam[k + r]        # lam_{k+r+1}
+    b = lam[2 * k + r]    # lam_{2k+r+1}
+    atoms = np.empty(N - r)
+    for j in range(1, k + 1):
+        atoms[j - 1] = a + (1.0 - (j / k) ** (2.0 / 3.0)) * EDGE_COEF * (a - b)
+    atoms[k:] = lam[r + k:]
+    return atoms
+
+
+def shrink(lam_i: float, atoms: np.ndarray, n: int, d: int):
+    """Alg. 2 Step 3 for one outlier eigenvalue z = lam_i (Eqs. d_transform,
+    d_a_estimates, shrinkers/Frobenius).
+
+    m_s, m_s' : Stieltjes transform (and derivative) of the empirical measure of
+    the M = len(atoms) noise atoms, i.e. of the min(n,d)-sided Gram matrix.
+    m_l       : the transform of the max(n,d)-sided Gram matrix, which has the
+    same non-zero spectrum plus |n-d| zeros:  m_l = beta m_s - (1-beta)/z.
+    m_1 is the transform on the n x n side (Z Z^T, left vectors), m_2 on the
+    d x d side (Z^T Z, right vectors): (m_1, m_2) = (m_l, m_s) when n >= d.
+    T = z m_1 m_2;  d = T^{-1/2};  a_1 = m_1/(d^2 T'),  a_2 = m_2/(d^2 T');
+    phi = d sqrt(a_1 a_2).
+
+    Readings (the paper defers the estimators to its reference): the measure is
+    normalised by the number of atoms M; beta = min(n,d)/max(n,d).
+    Returns (phi, d_hat, a_1, a_2, ok).
+    """
+    z = float(lam_i)
+    beta = min(n, d) / max(n, d)
+    diff = atoms - z
+    m_s = float(np.mean(1.0 / diff))
+    dm_s = float(np.mean(1.0 / (diff * diff)))
+    m_l = beta * m_s - (1.0 - beta) / z
+    dm_l = beta * dm_s + (1.0 - beta) / (z * z)
+    if n >= d:
+        m_1, dm_1, m_2, dm_2 = m_l, dm_l, m_s, dm_s
+    else:
+        m_1, dm_1, m_2, dm_2 = m_s, dm_s, m_l, dm_l
+    T = z * m_1 * m_2
+    dT = m_1 * m_2 + z * dm_1 * m_2 + z * m_1 * dm_2
+    sigma = math.sqrt(z)
+    ok = math.isfinite(T) and math.isfinite(dT) and T > 0.0 and dT < 0.0
+    if not ok:
+        return 0.0, 0.0, 0.0, 0.0, False
+    d_hat = 1.0 / math.sqrt(T)
+    a1 = m_1 / (d_hat * d_hat * dT)
+    a2 = m_2 / (d_hat * d_hat * dT)
+    phi = d_hat * math.sqrt(a1 * a2)
+    if not math.isfinite(phi):
+        return 0.0, 0.0, 0.0, 0.0, False
+    phi = min(max(phi, 0.0), sigma)
+    return phi, d_hat, a1, a2, True
+
+
+@dataclass
+class EOptShrinkResult:
+    lam: np.ndarray            # all min(n,d) eigenvalues sigma^2, descending
+    k: int
+    lam_plus: float
+    rank: int                  # r^+ after clamping to r_max
+    rank_unclamped: int
+    atoms: np.ndarray          # estimated noise eigenvalues
+    sigma: np.ndarray          # observed singular values of the outliers [rank]
+    phi: np.ndarray            # shrunk singular values [rank]
+    d_hat: np.ndarray
+    a1: np.ndarray
+    a2: np.ndarray
+    U: np.ndarray              # [n, rank] left singular vectors
+    V: np.ndarray              # [d, rank] right singular vectors
+    flags: int
+
+
+def eoptshrink(S: np.ndarray, r_max: int = 32) -> EOptShrinkResult:
+    """Alg. 2 on one block S (n x d), Frobenius loss, from the direct SVD."""
+    S = np.asarray(S, dtype=np.float64)
+    n, d = S.shape
+    U, s, Vt = np.linalg.svd(S, full_matrices=False)
+    lam = s * s                                   # Sec. 2.3: lambda_i = sigma_i^2
+    k = pilot_k(d)
+    N = lam.shape[0]
+    if 2 * k + 1 > N:
+        raise ValueError("block too small for the pilot parameter: 2k+1 > min(n,d)")
+    r_raw, lp = estimate_rank(lam, d, k)
+    flags = 0
+    r = r_raw
+    # Step 2 reads lam_{2k+r+1}: the retained rank is cut so that this index exists
+    # (the paper assumes k >> r^+ and is silent about larger ranks)
+    r_cap = min(r_max, N - 2 * k - 1)
+    if r > r_cap:
+        r = r_cap
+        flags |= FLAG_RANK_CLAMPED
+    atoms = impute_noise_spectrum(lam, r, k)
+    phi = np.zeros(r)
+    dh = np.zeros(r)
+    a1 = np.zeros(r)
+    a2 = np.zeros(r)
+    for i in range(r):
+        phi[i], dh[i], a1[i], a2[i], ok = shrink(lam[i], atoms, n, d)
+        if not ok:
+            flags |= FLAG_SHRINK_GUARD
+    return EOptShrinkResult(lam, k, lp, r, r_raw, atoms, s[:r].copy(), phi, dh, a1, a2,
+                            U[:, :r].copy(), Vt[:r].T.copy(), flags)
+
+
+# --------------------------------------------------------------------------
+# Alg. 1 (TQ_MSE)
+# --------------------------------------------------------------------------
+def fp16_round(x: np.ndarray) -> np.ndarray:
+    """Round to nearest-even binary16, saturating at +-65504; returned as float64."""
+    x = np.clip(np.asarray(x, dtype=np.float64), -65504.0, 65504.0)
+    return x.astype(np.float16).astype(np.float64)
+
+
+def fp16_bits(x: np.ndarray) -> np.ndarray:
+    x = np.clip(np.asarray(x, dtype=np.float64), -65504.0, 65504.0)
+    return x.astype(np.float16).view(np.uint16)
+
+
+def tq_mse_encode(R: np.ndarray, Pi: np.ndarray, cb: Codebook):
+    """Alg. 1 lines 3-5 for every row of R.
+
+    rho = ||x||, u = x/rho, z = Pi u, code_j = index of the nearest centroid of
+    the N(0,1/d) codebook = number of N(0,1) boundaries <= z_j sqrt(d).
+    The comparison is taken in binary32 (the precision of the stored boundary
+    table): value and boundaries are both rounded to float32 first.
+    A zero row gets u = 0.  Returns (codes uint8 [n,d], rho float64 [n], z [n,d]).
+    """
+    R = np.asarray(R, dtype=np.float64)
+    n, d = R.shape
+    rho = np.sqrt(np.sum(R * R, axis=1))
+    safe = np.where(rho > 0.0, rho, 1.0)
+    u = R / safe[:, None]
+    z = u @ Pi.T                                   # row form of z = Pi u
+    t = (z * math.sqrt(d)).astype(np.float32)
+    codes = np.zeros((n, d), dtype=np.uint8)
+    for bm in cb.bounds_f32:
+        codes += (bm <= t).astype(np.uint8)
+    return codes, rho, z
+
+
+def tq_mse_decode(codes: np.ndarray, rho16: np.ndarray, Pi: np.ndarray, cb: Codebook) -> np.ndarray:
+    """Alg. 1 line 6: x_hat = rho * Pi^T z_hat, z_hat = centroid[code]/sqrt(d)
+    (stored float32 table), rho the stored binary16 norm."""
+    d = codes.shape[1]
+    zhat = cb.centroids_f32.astype(np.float64)[codes] / math.sqrt(d)
+    return rho16[:, None] * (zhat @ Pi)            # row form of Pi^T z_hat
+
+
+# --------------------------------------------------------------------------
+# Alg. 3 (eOptShrinkQ) on one block, decompression and scoring
+# --------------------------------------------------------------------------
+@dataclass
+class BlockRecord:
+    """What Alg. 3 line "Store" keeps for one block (factors in binary16)."""
+    n: int
+    d: int
+    bits: int
+    rank: int
+    flags: int
+    phi: np.ndarray      # [rank] float64 shrunk singular values
+    sigma: np.ndarray    # [rank] observed singular values
+    lfac: np.ndarray     # [rank, n] binary16 values (as float64) of U diag(phi)
+    rfac: np.ndarray     # [rank, d] binary16 values (as float64) of V
+    codes: np.ndarray    # [n, d] uint8
+    rho16: np.ndarray    # [n] stored norms (binary16 values as float64)
+    # diagnostics
+    lam: np.ndarray = field(default=None, repr=False)
+    lam_plus: float = 0.0
+    rho: np.ndarray = field(default=None, repr=False)
+    z: np.ndarray = field(default=None, repr=False)
+    R: np.ndarray = field(default=None, repr=False)
+
+
+def compress_block(S: np.ndarray, Pi: np.ndarray, cb: Codebook, r_max: int = 32,
+                   force_rank0: bool = False) -> BlockRecord:
+    """Alg. 3: eOptShrink, residual against the *stored* (binary16) factors,
+    TQ_MSE per row.  With r^+ = 0 the block goes to TQ_MSE unchanged."""
+    S = np.asarray(S, dtype=np.float64)
+    n, d = S.shape
+    es = eoptshrink(S, r_max)
+    r = 0 if force_rank0 else es.rank
+    if r > 0:
+        lfac = fp16_round((es.U[:, :r] * es.phi[None, :r]).T)   # [r, n]
+        rfac = fp16_round(es.V[:, :r].T)                        # [r, d]
+        R = S - lfac.T @ rfac
+    else:
+        lfac = np.zeros((0, n))
+        rfac = np.zeros((0, d))
+        R = S
+    codes, rho, z = tq_mse_encode(R, Pi, cb)
+    return BlockRecord(n, d, cb.bits, r, es.flags, es.phi[:r], es.sigma[:r], lfac, rfac, codes,
+                       fp16_round(rho), lam=es.lam, lam_plus=es.lam_plus, rho=rho, z=z, R=R)
+
+
+def decompress_block(rec: BlockRecord, Pi: np.ndarray, cb: Codebook) -> np.ndarray:
+    """x_hat_t = rho_t Pi^T z_hat_t + (U diag(phi) V^T)[t, :]  (Alg. 1 line 6 plus
+    the stored low-rank part of Alg. 2's Return), float64, before any rounding."""
+    x = tq_mse_decode(rec.codes, rec.rho16, Pi, cb)
+    if rec.rank > 0:
+        x = x + rec.lfac.T @ rec.rfac
+    return x
+
+
+def score_block(q: np.ndarray, rec: BlockRecord, Pi: np.ndarray, cb: Codebook) -> np.ndarray:
+    """<q, x_hat_t> / sqrt(d) for every query row of q and every token of the
+    block (Sec. 2.1 attention logits; Remark 6.5 split into low-rank + residual)."""
+    x = decompress_block(rec, Pi, cb)
+    return (np.asarray(q, dtype=np.float64) @ x.T) / math.sqrt(rec.d)
+
+
+# --------------------------------------------------------------------------
+# storage encoding of the codes (builder's format; the paper only says "indices")
+# --------------------------------------------------------------------------
+def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
+    """[n, d] codes -> [n, d*bits/8] bytes.
+
+    Each row is stored as `bits` bit-planes of d/8 bytes: plane p holds bit p of
+    the d codes, coordinate j in bit (j mod 8) of byte j // 8.
+    """
+    n, d = codes.shape
+    out = np.zeros((n, bits, d // 8), dtype=np.uint8)
+    for p in range(bits):
+        plane = (codes >> p) & 1
+        for j in range(d):
+            out[:, p, j // 8] |= (plane[:, j] << (j % 8)).astype(np.uint8)
+    return out.reshape(n, bits * d // 8)
+
+
+def unpack_codes(packed: np.ndarray, bits: int, d: int) -> np.ndarray:
+    n = packed.shape[0]
+    pk = packed.reshape(n, bits, d // 8)
+    codes = np.zeros((n, d), dtype=np.uint8)
+    for p in range(bits):
+        for j in range(d):
+            codes[:, j] |= (((pk[:, p, j // 8] >> (j % 8)) & 1) << p).astype(np.uint8)
+    return codes
+
+
+def bits_per_entry(n: int, d: int, bits: int, rank: int, b_s: int = 16) -> float:
+    """Alg. 3 last line plus the two shared costs of Remark 3.1: the binary16
+    norm per row (16/d) and the binary16 shrunk values (16 r / (n d))."""
+    return bits + rank * (n + d) * b_s / (n * d) + 16.0 / d + 16.0 * rank / (n * d)

@@ -1,0 +1,492 @@
+"""Pins of the float64 oracle against what the paper and the mathematics fix.
+
+None of these tests touches the HIP library.  Each names the passage or the
+closed form it pins and is chosen so that a plausible slip in the oracle (wrong
+index, dropped term, swapped side, transposed operand) fails it.
+"""
+import math
+
+import numpy as np
+import pytest
+from scipy import integrate, stats
+
+import oracle
+
+
+# ----------------------------------------------------------------- constants
+def test_pilot_k_printed_values(golden):
+    # Remark 3.1 prints k = 11 at d = 128; the appendix remark gives ~7 at d = 64
+    assert oracle.pilot_k(128) == int(golden["pilot_k_d128"][0])
+    assert oracle.pilot_k(64) == int(golden["pilot_k_d64"][0])
+
+
+def test_edge_constant():
+    assert abs(oracle.EDGE_COEF - 1.7024143839193153) < 1e-15
+    assert abs(oracle.rank_threshold(128) - 128 ** (-1 / 3)) < 1e-16
+    assert abs(oracle.rank_threshold(128) - 0.19842513149602492) < 1e-15
+
+
+# ------------------------------------------------------------------ codebook
+def test_lloyd_max_known_centroids(golden):
+    c1 = oracle.lloyd_max_gaussian(1)
+    assert np.allclose(c1.centroids, [-golden["lloyd_1bit"][0], golden["lloyd_1bit"][0]], atol=1e-9)
+    assert abs(c1.centroids[1] - math.sqrt(2 / math.pi)) < 1e-14
+    c2 = oracle.lloyd_max_gaussian(2)
+    a, b = golden["lloyd_2bit"]
+    assert np.allclose(c2.centroids, [-b, -a, a, b], atol=6e-4)   # printed to 4 significant digits
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_lloyd_max_fixed_point_by_quadrature(bits):
+    """Centroid = conditional mean of its cell, boundary = midpoint: checked with
+    numerical integration of the density, not with the erf formula the oracle uses."""
+    cb = oracle.lloyd_max_gaussian(bits)
+    assert cb.centroids.shape == (1 << bits,) and cb.bounds.shape == ((1 << bits) - 1,)
+    assert np.all(np.diff(cb.centroids) > 0)
+    assert np.allclose(cb.bounds, 0.5 * (cb.centroids[:-1] + cb.centroids[1:]), atol=1e-15)
+    assert np.allclose(cb.centroids, -cb.centroids[::-1], atol=1e-15)
+    edges = np.r_[-np.inf, cb.bounds, np.inf]
+    pdf = stats.norm.pdf
+    dist = 0.0
+    for i, c in enumerate(cb.centroids):
+        lo, hi = max(edges[i], -40.0), min(edges[i + 1], 40.0)
+        mass = integrate.quad(pdf, lo, hi, epsabs=1e-14, epsrel=1e-13)[0]
+        mean = integrate.quad(lambda x: x * pdf(x), lo, hi, epsabs=1e-14, epsrel=1e-13)[0] / mass
+        assert abs(mean - c) < 1e-10
+        dist += integrate.quad(lambda x: (x - c) ** 2 * pdf(x), lo, hi, epsabs=1e-14, epsrel=1e-13)[0]
+    assert abs(dist - cb.distortion) < 1e-10
+    assert cb.centroids_f32.dtype == np.float32 and cb.bounds_f32.dtype == np.float32
+    assert np.array_equal(cb.centroids_f32, cb.centroids.astype(np.float32))
+
+
+def test_lloyd_max_distortion_matches_paper_tables(golden):
+    """sqrt(D_b) is the relative L2 error of TQ_MSE on isotropic rows; Tables 1-4
+    print 34.1-34.2 / 18.4-18.5 / 9.7 percent for b = 2, 3, 4."""
+    for key in ("table1_tqmse_l2", "table2_tqmse_l2", "table3_tqmse_l2", "table4_tqmse_l2"):
+        for bits, printed in zip((2, 3, 4), golden[key]):
+            assert abs(100 * math.sqrt(oracle.lloyd_max_gaussian(bits).distortion) - printed) < 0.25
+
+
+def test_nearest_centroid_equals_boundary_count():
+    rng = np.random.default_rng(3)
+    d = 128
+    Pi = np.eye(d)
+    for bits in (1, 2, 3, 4):
+        cb = oracle.lloyd_max_gaussian(bits)
+        x = rng.standard_normal((16, d))
+        codes, rho, z = oracle.tq_mse_encode(x, Pi, cb)
+        t = z * math.sqrt(d)
+        brute = np.argmin(np.abs(t[:, :, None] - cb.centroids[None, None, :]), axis=2)
+        margin = np.min(np.abs(t[:, :, None] - cb.bounds[None, None, :]), axis=2)
+        ok = margin > 1e-6     # away from ties the two definitions agree
+        assert ok.mean() > 0.999 and np.array_equal(codes[ok], brute[ok])
+        assert codes.min() == 0 and codes.max() == (1 << bits) - 1
+
+
+# ------------------------------------------------------------------ rotation
+def test_gaussian_stream_is_standard_normal():
+    g = oracle.gaussian_stream(12345, 200000)
+    assert abs(g.mean()) < 0.01 and abs(g.var() - 1.0) < 0.01
+    assert stats.kstest(g, "norm").pvalue > 1e-3
+    # counter based: a prefix of a longer stream is the shorter stream
+    assert np.array_equal(g[:1000], oracle.gaussian_stream(12345, 1000))
+    assert not np.array_equal(g[:1000], oracle.gaussian_stream(12346, 1000))
+
+
+def test_splitmix64_reference_vector():
+    # first outputs of SplitMix64 seeded with 0 (published test vector of the generator)
+    out = oracle.splitmix64(0, np.arange(3, dtype=np.uint64))
+    assert [int(x) for x in out] == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+
+
+@pytest.mark.parametrize("d", [8, 128])
+def test_haar_rotation_orthogonal_and_sign_fixed(d):
+    seed = 260502906
+    Pi = oracle.haar_rotation(d, seed)
+    assert np.abs(Pi.T @ Pi - np.eye(d)).max() < 1e-13
+    assert np.abs(Pi @ Pi.T - np.eye(d)).max() < 1e-13
+    assert abs(abs(np.linalg.det(Pi)) - 1.0) < 1e-10
+    u = np.random.default_rng(0).standard_normal(d)
+    assert abs(np.linalg.norm(Pi @ u) - np.linalg.norm(u)) < 1e-12
+    # Q^T G must be upper triangular with a positive diagonal (the Haar sign convention)
+    G = oracle.gaussian_stream(seed, d * d).reshape(d, d)
+    R = Pi.T @ G
+    assert np.abs(np.tril(R, -1)).max() < 1e-10
+    assert np.all(np.diag(R) > 0)
+
+
+# ------------------------------------------------------------------ SVD step
+def _jacobi_eigh(A, sweeps=50):
+    """Textbook cyclic Jacobi on a small symmetric matrix, pure Python loops."""
+    A = A.copy()
+    m = A.shape[0]
+    V = np.eye(m)
+    for _ in range(sweeps):
+        for p in range(m - 1):
+            for q in range(p + 1, m):
+                if abs(A[p, q]) < 1e-300:
+                    continue
+                th = 0.5 * math.atan2(2 * A[p, q], A[q, q] - A[p, p])
+                c, s = math.cos(th), math.sin(th)
+                J = np.eye(m)
+                J[p, p] = c; J[q, q] = c; J[p, q] = s; J[q, p] = -s
+                A = J.T @ A @ J
+                V = V @ J
+    return np.diag(A), V
+
+
+@pytest.mark.parametrize("shape", [(8, 4), (6, 5), (12, 6)])
+def test_svd_against_brute_force_on_tiny_blocks(shape):
+    rng = np.random.default_rng(shape[0])
+    S = rng.standard_normal(shape)
+    es = oracle.eoptshrink(S, r_max=1)
+    lam_bf, V_bf = _jacobi_eigh(S.T @ S)
+    order = np.argsort(-lam_bf)
+    assert np.allclose(es.lam, lam_bf[order], rtol=1e-10)
+    # Sec. 2.3: lambda_i = sigma_i^2 are the eigenvalues of S S^T as well
+    assert np.allclose(np.sort(np.linalg.eigvalsh(S @ S.T))[::-1][:shape[1]], es.lam, rtol=1e-9)
+    # plant a strong direction so that at least one component is retained and its vectors can be checked
+    S2 = S + 8.0 * np.outer(rng.standard_normal(shape[0]), np.eye(shape[1])[0])
+    full = oracle.eoptshrink(S2, r_max=shape[1])
+    lam_bf, V_bf = _jacobi_eigh(S2.T @ S2)
+    order = np.argsort(-lam_bf)
+    assert full.rank >= 1 or shape[1] - 2 * full.k - 1 == 0
+    S = S2
+    for i in range(full.rank):
+        v_bf = V_bf[:, order[i]]
+        assert abs(abs(v_bf @ full.V[:, i]) - 1.0) < 1e-8
+        assert np.allclose(S @ full.V[:, i], full.sigma[i] * full.U[:, i], atol=1e-10)
+
+
+# ------------------------------------------------------- Alg. 2 Step 1: edge
+def _spiked(rng, n, d, strengths, channel=None):
+    r = len(strengths)
+    Z = rng.standard_normal((n, r))
+    W, _ = np.linalg.qr(rng.standard_normal((d, r)))
+    sig = (Z * np.asarray(strengths)) @ W.T if r else np.zeros((n, d))
+    E = rng.standard_normal((n, d))
+    if channel is not None:
+        E = E * channel
+    return sig + E, sig, E
+
+
+@pytest.mark.parametrize("n,d,tol", [(512, 128, 0.03), (1024, 128, 0.03), (128, 128, 0.09)])
+def test_bulk_edge_on_white_noise_is_marchenko_pastur_edge(n, d, tol):
+    """Sec. 2.3: for iid noise the bulk edge is sigma^2 (1 + sqrt(beta))^2, i.e.
+    (sqrt(n) + sqrt(d))^2 for unit-variance entries."""
+    k = oracle.pilot_k(d)
+    vals = []
+    for seed in range(24):
+        S = np.random.default_rng(1000 + seed).standard_normal((n, d))
+        lam = np.linalg.svd(S, compute_uv=False) ** 2
+        vals.append(oracle.bulk_edge(lam, k))
+    exact = (math.sqrt(n) + math.sqrt(d)) ** 2
+    # (the estimator extrapolates from the k+1-th and 2k+1-th of only 128 eigenvalues: a few percent of
+    # finite-size bias, largest for the square block whose spectrum is widest)
+    assert abs(np.mean(vals) / exact - 1.0) < tol
+    assert np.max(np.abs(np.array(vals) / exact - 1.0)) < tol + 0.08
+
+
+def test_bulk_edge_uses_the_printed_indices():
+    """Alg. 2 Step 1 on an exact square-root-edge spectrum lam_j = L - c j^{2/3}:
+    extrapolating from j = k+1 and 2k+1 must return L + c(k+1)^{2/3} ... exactly
+    the printed formula; with j measured from the edge itself (lam_j = L - c (j-1/2... )
+    it would not.  Use the model the constant 2^{2/3}-1 is exact for: positions k and 2k."""
+    k = 11
+    L, c = 100.0, 0.37
+    j = np.arange(0, 64, dtype=float)        # 0-based index i holds lam_{i+1}
+    # place the law so that entry k (lam_{k+1}) sits at offset k^{2/3}, entry 2k at (2k)^{2/3}
+    lam = L - c * j ** (2.0 / 3.0)
+    assert abs(oracle.bulk_edge(lam, k) - L) < 1e-12
+    # an off-by-one in either index breaks exactness
+    a, b = lam[k + 1], lam[2 * k]
+    assert abs(a + oracle.EDGE_COEF * (a - b) - L) > 1e-3
+
+
+# ------------------------------------------------------- Alg. 2 Step 1: rank
+def test_planted_rank_recovered_above_bbp_and_none_below():
+    n, d = 512, 128
+    u_bbp = (n * d) ** 0.25        # white-noise detection threshold on the singular-value scale
+    for seed in range(12):
+        rng = np.random.default_rng(seed)
+        S, _, _ = _spiked(rng, n, d, (6.0, 4.0, 2.5))         # singular values ~ (136, 90, 57) >> 16
+        assert oracle.eoptshrink(S).rank == 3
+    for seed in range(40):
+        S = np.random.default_rng(500 + seed).standard_normal((n, d))
+        assert oracle.eoptshrink(S).rank == 0                  # Remark 3.1: isotropic block -> r = 0
+    for seed in range(12):
+        rng = np.random.default_rng(900 + seed)
+        weak = 0.5 * u_bbp / math.sqrt(n)                      # half the BBP threshold: sticks to the bulk
+        S, _, _ = _spiked(rng, n, d, (6.0, weak, weak))
+        assert oracle.eoptshrink(S).rank == 1
+
+
+def test_rank_threshold_is_strict_and_relative():
+    d, k = 128, 11
+    lam = np.linspace(2.0, 1.0, 128)
+    lp = oracle.bulk_edge(lam, k)
+    thr = (1.0 + oracle.rank_threshold(d)) * lp
+    lam2 = lam.copy()
+    lam2[0] = thr * (1 + 1e-9)
+    assert oracle.estimate_rank(lam2, d, k)[0] == 1
+    lam2[0] = thr * (1 - 1e-9)
+    lam2[:2] = np.sort(lam2[:2])[::-1]
+    assert oracle.estimate_rank(lam2, d, k)[0] == 0
+    r1, _ = oracle.estimate_rank(lam2 * 37.0, d, k)           # scale free
+    assert r1 == 0
+
+
+# ------------------------------------------------ Alg. 2 Step 2: imputation
+def test_imputation_reproduces_a_square_root_edge():
+    k, r = 11, 3
+    L, c = 50.0, 0.2
+    N = 128
+    noise = L - c * np.arange(0, N - r, dtype=float) ** (2.0 / 3.0)     # noise atom j (1-based) at (j-1)... see below
+    # build an observed spectrum: r outliers, then noise atoms whose 1-based index j sits at offset j^{2/3}
+    jj = np.arange(1, N - r + 1, dtype=float)
+    noise = L - c * jj ** (2.0 / 3.0)
+    lam = np.r_[[500.0, 300.0, 200.0], noise]
+    atoms = oracle.impute_noise_spectrum(lam, r, k)
+    assert atoms.shape == (N - r,)
+    # the printed rule extrapolates from atoms k+1 and 2k+1 with offsets (k, 2k): atom j is placed at
+    # lam_{k+r+1} + c' (k^{2/3} - j^{2/3}); check the closed form and that untouched atoms are copied
+    a, b = lam[k + r], lam[2 * k + r]
+    for j in range(1, k + 1):
+        assert abs(atoms[j - 1] - (a + (1 - (j / k) ** (2 / 3)) * oracle.EDGE_COEF * (a - b))) < 1e-12
+    assert np.array_equal(atoms[k:], lam[r + k:])
+    assert abs(atoms[k - 1] - lam[k + r]) < 1e-12               # j = k reproduces lam_{k+r+1} (as printed)
+    assert np.all(np.diff(atoms[:k]) < 0)
+
+
+# --------------------------------------------------- Alg. 2 Step 3: shrinker
+def test_shrinker_matches_white_noise_closed_form_and_true_overlaps():
+    """White noise (A = B = I) is the special case with a textbook answer: for an observed singular value y
+    of an n x d matrix with unit-variance noise the Frobenius-optimal value is
+    sqrt((y^2 - n - d)^2 - 4 n d) / y.  The D-transform estimates must also recover the planted strengths
+    and the *measured* overlaps |<u_i, xi_i>|^2 (left, a_1) and |<v_i, zeta_i>|^2 (right, a_2) of Eq. (overlaps)."""
+    n, d = 512, 128
+    rows = []
+    for seed in range(24):
+        rng = np.random.default_rng(seed)
+        S, sig, _ = _spiked(rng, n, d, (6.0, 4.0, 2.5))
+        Us, ss, Vts = np.linalg.svd(sig, full_matrices=False)
+        es = oracle.eoptshrink(S)
+        assert es.rank == 3 and es.flags == 0
+        y = es.sigma
+        closed = np.sqrt((y ** 2 - n - d) ** 2 - 4 * n * d) / y
+        o1 = np.array([(Us[:, i] @ es.U[:, i]) ** 2 for i in range(3)])
+        o2 = np.array([(Vts[i] @ es.V[:, i]) ** 2 for i in range(3)])
+        rows.append(np.r_[es.phi / closed, es.d_hat / ss[:3], es.a1 - o1, es.a2 - o2])
+        assert np.all(es.phi < es.sigma) and np.all(es.phi > 0)
+    m = np.mean(rows, axis=0)
+    assert np.all(np.abs(m[0:3] - 1.0) < 0.006)        # shrunk values vs closed form
+    assert np.all(np.abs(m[3:6] - 1.0) < 0.01)         # d_hat vs planted strength
+    assert np.all(np.abs(m[6:9]) < 0.01)               # a_1 vs measured left overlap
+    assert np.all(np.abs(m[9:12]) < 0.01)              # a_2 vs measured right overlap
+    # the two overlaps differ by much more than the tolerance, so a swapped labelling fails
+    assert np.all(np.array(rows)[:, 9:12].mean(0) + 0.0 < 0.01)
+    assert (es.a2 - es.a1).min() > 0.015
+
+
+def test_shrinker_tall_and_wide_blocks_agree():
+    """A block and its transpose have the same singular values; the shrunk values must agree and the
+    overlap estimates swap sides."""
+    rng = np.random.default_rng(5)
+    S, _, _ = _spiked(rng, 256, 128, (5.0, 3.0))
+    es = oracle.eoptshrink(S)
+    lam = es.lam
+    for i in range(es.rank):
+        p1, d1, a1, a2, ok1 = oracle.shrink(lam[i], es.atoms, 256, 128)
+        p2, d2, b1, b2, ok2 = oracle.shrink(lam[i], es.atoms, 128, 256)
+        assert ok1 and ok2
+        assert abs(p1 - p2) < 1e-12 * p1 and abs(d1 - d2) < 1e-12 * d1
+        assert abs(a1 - b2) < 1e-12 and abs(a2 - b1) < 1e-12
+
+
+def test_shrinker_identity_and_scale_equivariance():
+    rng = np.random.default_rng(11)
+    ch = np.exp(0.7 * rng.standard_normal(128))
+    S, _, _ = _spiked(rng, 512, 128, (9.0, 6.0, 4.0, 3.0), channel=ch)
+    es = oracle.eoptshrink(S)
+    assert es.rank >= 3
+    es2 = oracle.eoptshrink(3.5 * S)
+    assert es2.rank == es.rank
+    assert np.allclose(es2.phi, 3.5 * es.phi, rtol=1e-10)
+    assert np.allclose(es2.a1, es.a1, rtol=1e-9) and np.allclose(es2.a2, es.a2, rtol=1e-9)
+    # phi = d sqrt(a1 a2) must equal -T / (sigma T'), with T' taken by central differences of T here
+    n, d = S.shape
+    beta = d / n
+    for i in range(es.rank):
+        z = es.lam[i]
+
+        def T(zz):
+            ms = np.mean(1.0 / (es.atoms - zz))
+            return zz * ms * (beta * ms - (1 - beta) / zz)
+        h = 1e-5 * z
+        dT = (T(z + h) - T(z - h)) / (2 * h)
+        assert abs(-T(z) / (math.sqrt(z) * dT) - es.phi[i]) < 1e-6 * es.phi[i]
+        assert abs(1.0 / math.sqrt(T(z)) - es.d_hat[i]) < 1e-12 * es.d_hat[i]
+
+
+def test_shrinker_guard_on_degenerate_input():
+    atoms = np.linspace(10.0, 1.0, 100)
+    phi, dh, a1, a2, ok = oracle.shrink(5.05, atoms, 512, 128)     # "outlier" inside the bulk
+    assert (phi == 0.0 and not ok) or (0.0 <= phi <= math.sqrt(5.05))
+    with np.errstate(divide="ignore", invalid="ignore"):
+        phi, dh, a1, a2, ok = oracle.shrink(5.0, np.r_[atoms, 5.0], 512, 128)   # exactly on an atom
+    assert phi == 0.0 and not ok
+
+
+# -------------------------------------------------- Prop. 6.1 and Cor. 6.3
+def test_residual_has_no_outliers_and_noise_energy():
+    n, d = 512, 128
+    k = oracle.pilot_k(d)
+    ratios = []
+    for seed in range(10):
+        rng = np.random.default_rng(40 + seed)
+        S, sig, E = _spiked(rng, n, d, (12.0, 8.0, 6.0))
+        es = oracle.eoptshrink(S)
+        assert es.rank == 3
+        R = S - (es.U * es.phi) @ es.V.T
+        lamR = np.linalg.svd(R, compute_uv=False) ** 2
+        # Prop. 6.1(1): the residual's spectrum is the noise bulk, nothing sticks out of it
+        assert oracle.estimate_rank(lamR, d, k)[0] == 0
+        assert math.sqrt(lamR[0]) < 1.1 * (math.sqrt(n) + math.sqrt(d))
+        # the leftover of each shrunk component, sigma - phi, lies inside the bulk (proof of Prop. 6.1, Part 1)
+        assert np.all(es.sigma - es.phi < math.sqrt(es.lam_plus))
+        ratios.append(np.sum(R * R) / np.sum(E * E))
+        # Cor. 6.3: no coordinate of a residual row carries disproportionate energy
+        assert np.max(np.abs(R).max(1) / np.linalg.norm(R, axis=1)) < 3.0 * math.sqrt(math.log(d) / d)
+        assert np.sum(R * R) < 0.5 * np.sum(S * S)
+    # Prop. 6.1(2): ||R||_F^2 = ||Z||_F^2 up to O(d^{-1/2}) (~0.09 here); the three removed directions carry
+    # about 3 (n + d) / (n d) = 2.9 % of the noise energy, which is the deficit seen
+    assert abs(np.mean(ratios) - (1.0 - 3 * (n + d) / (n * d))) < 0.01
+    # separable (per-channel) noise covariance: the energy statement still holds
+    ratios = []
+    for seed in range(10):
+        rng = np.random.default_rng(80 + seed)
+        ch = np.exp(0.3 * rng.standard_normal(d))
+        S, sig, E = _spiked(rng, n, d, (12.0, 8.0, 6.0), channel=ch)
+        es = oracle.eoptshrink(S)
+        R = S - (es.U * es.phi) @ es.V.T
+        ratios.append(np.sum(R * R) / np.sum(E * E))
+    assert abs(np.mean(ratios) - 1.0) < 0.06
+
+
+# ------------------------------------------------------------ Alg. 1, Alg. 3
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_tq_mse_distortion_on_isotropic_rows(bits, golden):
+    d = 128
+    rng = np.random.default_rng(bits)
+    X = rng.standard_normal((512, d))
+    Pi = oracle.haar_rotation(d, 77)
+    cb = oracle.lloyd_max_gaussian(bits)
+    codes, rho, z = oracle.tq_mse_encode(X, Pi, cb)
+    Xh = oracle.tq_mse_decode(codes, rho, Pi, cb)
+    rel = np.linalg.norm(X - Xh) / np.linalg.norm(X)
+    # (coordinates of a rotated unit vector have slightly lighter tails than N(0,1/d): up to ~2 % below sqrt(D_b))
+    assert abs(rel / math.sqrt(cb.distortion) - 1.0) < 0.03
+    assert abs(100 * rel - golden["table1_tqmse_l2"][bits - 2]) < 0.5
+    assert np.allclose(np.linalg.norm(z, axis=1), 1.0, atol=1e-12)     # rotation keeps the unit norm
+    # decoding with the transpose of the wrong orientation would not invert the rotation
+    bad = rho[:, None] * ((cb.centroids[codes] / math.sqrt(d)) @ Pi.T)
+    assert np.linalg.norm(X - bad) / np.linalg.norm(X) > 1.0
+
+
+def test_bit_accounting(golden):
+    assert abs(16 / 128 - golden["norm_overhead_d128"][0]) < 1e-12
+    f = lambda r: r * (128 + 128) * 4 / (128 * 128)
+    assert round(f(1), 2) == golden["factor_overhead_r1"][0]
+    assert round(f(5.6), 2) == golden["factor_overhead_r5p6"][0]
+    for b, printed in zip((2, 3, 4), golden["table1_bits_rank5p6"]):
+        assert round(b + f(5.6), 2) == printed
+    for b, printed in zip((2, 3, 4), golden["table2_bits_rank5p0"]):
+        assert round(b + f(5.0), 2) == printed
+    # the record this build stores keeps binary16 factors: b_s = 16
+    assert abs(oracle.bits_per_entry(128, 128, 2, 1, b_s=4) - (2 + f(1) + 0.125 + 16 / 16384)) < 1e-12
+    assert abs(oracle.bits_per_entry(512, 128, 2, 5) - (2 + 5 * 640 * 16 / 65536 + 0.125 + 80 / 65536)) < 1e-12
+
+
+def test_pipeline_closed_loop_and_rank0_bypass():
+    n, d = 512, 128
+    Pi = oracle.haar_rotation(d, 260502906)
+    cb = oracle.lloyd_max_gaussian(2)
+    rng = np.random.default_rng(8)
+    S, _, _ = _spiked(rng, n, d, (6.0, 4.0, 2.5))
+    S = S.astype(np.float16).astype(np.float64)
+    rec = oracle.compress_block(S, Pi, cb)
+    X = oracle.decompress_block(rec, Pi, cb)
+    assert rec.rank == 3 and rec.lfac.shape == (3, n) and rec.rfac.shape == (3, d)
+    # stored factors are binary16 values
+    assert np.array_equal(rec.lfac, rec.lfac.astype(np.float16).astype(np.float64))
+    # closed loop: S - X_hat = R - R_hat, so the total error is the residual's quantisation error
+    Rh = oracle.tq_mse_decode(rec.codes, rec.rho16, Pi, cb)
+    assert np.allclose(S - X, rec.R - Rh, atol=1e-9)
+    rel_res = np.linalg.norm(rec.R - Rh) / np.linalg.norm(rec.R)
+    assert abs(rel_res / math.sqrt(cb.distortion) - 1.0) < 0.02
+    assert np.linalg.norm(S - X) / np.linalg.norm(S) < 0.85 * math.sqrt(cb.distortion)   # better than TQ alone
+    # Alg. 3 else-branch: pure noise goes to TQ_MSE unchanged
+    N0 = np.random.default_rng(9).standard_normal((n, d))
+    rec0 = oracle.compress_block(N0, Pi, cb)
+    assert rec0.rank == 0 and rec0.lfac.shape[0] == 0 and np.array_equal(rec0.R, N0)
+    c0, rho0, _ = oracle.tq_mse_encode(N0, Pi, cb)
+    assert np.array_equal(rec0.codes, c0)
+    assert np.allclose(rec0.rho16, rho0, rtol=1e-3)
+
+
+def test_zero_row_and_norm_saturation():
+    d = 128
+    Pi = oracle.haar_rotation(d, 1)
+    cb = oracle.lloyd_max_gaussian(2)
+    X = np.zeros((3, d))
+    X[1, 0] = 1e6
+    X[2] = 1e-3
+    codes, rho, _ = oracle.tq_mse_encode(X, Pi, cb)
+    assert rho[0] == 0 and np.all(codes[0] == 2)        # 0 sits in the first non-negative cell
+    assert oracle.fp16_round(rho)[1] == 65504.0
+    assert oracle.fp16_bits(np.array([1.0]))[0] == 0x3C00
+
+
+def test_scores_equal_fused_form():
+    """Remark 6.5: <q, x_hat> = <q, s_hat> + <q, r_hat>, and <q, Pi^T z> = <Pi q, z>."""
+    n, d = 512, 128
+    Pi = oracle.haar_rotation(d, 260502906)
+    cb = oracle.lloyd_max_gaussian(2)
+    rng = np.random.default_rng(21)
+    S, _, _ = _spiked(rng, n, d, (6.0, 4.0, 2.5))
+    rec = oracle.compress_block(S, Pi, cb)
+    q = rng.standard_normal((64, d))
+    sc = oracle.score_block(q, rec, Pi, cb)
+    qp = q @ Pi.T                                         # rows are Pi q
+    zhat = cb.centroids_f32.astype(np.float64)[rec.codes] / math.sqrt(d)
+    fused = (qp @ zhat.T) * rec.rho16[None, :] + (q @ rec.rfac.T) @ rec.lfac
+    assert np.allclose(sc, fused / math.sqrt(d), atol=1e-10)
+    exact = q @ S.T / math.sqrt(d)
+    assert np.corrcoef(sc.ravel(), exact.ravel())[0, 1] > 0.9
+
+
+# ------------------------------------------------------------------ encoding
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_pack_unpack_exhaustive(bits):
+    d = 128
+    L = 1 << bits
+    # every code value at every coordinate, all other coordinates at a different value
+    for other in (0, L - 1):
+        codes = np.full((d * L, d), other, dtype=np.uint8)
+        for j in range(d):
+            for v in range(L):
+                codes[j * L + v, j] = v
+        pk = oracle.pack_codes(codes, bits)
+        assert pk.shape == (d * L, bits * d // 8) and pk.dtype == np.uint8
+        assert np.array_equal(oracle.unpack_codes(pk, bits, d), codes)
+    # layout: coordinate j, bit p of its code -> plane p, byte j // 8, bit j % 8
+    one = np.zeros((1, d), dtype=np.uint8)
+    one[0, 77] = L - 1
+    pk = oracle.pack_codes(one, bits).reshape(bits, d // 8)
+    for p in range(bits):
+        expect = np.zeros(d // 8, dtype=np.uint8)
+        expect[77 // 8] = 1 << (77 % 8)
+        assert np.array_equal(pk[p], expect)
+    rng = np.random.default_rng(bits)
+    codes = rng.integers(0, L, (64, d), dtype=np.uint8)
+    assert np.array_equal(oracle.unpack_codes(oracle.pack_codes(codes, bits), bits, d), codes)
