@@ -82,7 +82,9 @@ typedef struct {
  * N(0,1) (Sec. 2.2 item 3; used scaled by 1/sqrt(d)), and uploads both to the
  * current HIP device.
  * Supported: d = 128; n a multiple of 128 with 128 <= n <= 4096; bits in 1..4;
- * 1 <= r_max <= 32.  On failure *out is NULL.
+ * 1 <= r_max <= 32.  On failure *out is NULL.  When the process sees no HIP
+ * device the context is created host-only: eoq_rotation / eoq_codebook work,
+ * the three hot calls return EOQ_ERR_HIP.
  */
 eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, int r_max);
 void       eoq_destroy(eoq_ctx* ctx);

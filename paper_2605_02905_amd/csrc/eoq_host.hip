@@ -1,0 +1,311 @@
+// Host side of the eOptShrinkQ library: context, table construction, argument
+// checks and the C ABI.  Kernels live in eoq_kernels.hip.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "eoq_internal.h"
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// Seeded Gaussian stream: SplitMix64 evaluated at a counter, Box-Muller cosine
+// branch on the counter pair (2e, 2e+1) for draw number e.
+// ---------------------------------------------------------------------------
+inline uint64_t mix64(uint64_t seed, uint64_t counter) {
+  uint64_t z = seed + (counter + 1ull) * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+inline double unit_open(uint64_t bits) {  // (0,1), 53 bits
+  return ((double)(bits >> 11) + 0.5) * 0x1.0p-53;
+}
+
+inline double gaussian_draw(uint64_t seed, uint64_t e) {
+  const double u1 = unit_open(mix64(seed, 2 * e));
+  const double u2 = unit_open(mix64(seed, 2 * e + 1));
+  return std::sqrt(-2.0 * std::log(u1)) * std::cos(2.0 * M_PI * u2);
+}
+
+// ---------------------------------------------------------------------------
+// Haar rotation (Alg. 1 REQUIRE; Sec. 2.2 item 2): Householder QR of a d x d
+// Gaussian matrix filled row-major, Q's columns re-signed so that R's diagonal
+// is positive.  Double precision; returned row-major as q[c*d + j].
+// ---------------------------------------------------------------------------
+std::vector<double> haar_rotation(int d, uint64_t seed) {
+  std::vector<double> a((size_t)d * d), q((size_t)d * d, 0.0), v(d), rdiag(d);
+  for (int i = 0; i < d * d; ++i) a[i] = gaussian_draw(seed, (uint64_t)i);
+  for (int i = 0; i < d; ++i) q[(size_t)i * d + i] = 1.0;
+  for (int j = 0; j < d; ++j) {
+    double nrm = 0.0;
+    for (int i = j; i < d; ++i) nrm += a[(size_t)i * d + j] * a[(size_t)i * d + j];
+    nrm = std::sqrt(nrm);
+    const double x0 = a[(size_t)j * d + j];
+    const double alpha = (x0 >= 0.0) ? -nrm : nrm;  // R[j][j]
+    rdiag[j] = alpha;
+    double vn = 0.0;
+    for (int i = j; i < d; ++i) {
+      v[i] = a[(size_t)i * d + j] - (i == j ? alpha : 0.0);
+      vn += v[i] * v[i];
+    }
+    if (vn == 0.0) continue;
+    const double s = 2.0 / vn;
+    // A <- (I - s v v^T) A on rows j.., columns j..
+    for (int c = j; c < d; ++c) {
+      double dot = 0.0;
+      for (int i = j; i < d; ++i) dot += v[i] * a[(size_t)i * d + c];
+      dot *= s;
+      for (int i = j; i < d; ++i) a[(size_t)i * d + c] -= dot * v[i];
+    }
+    // Q <- Q (I - s v v^T)
+    for (int r = 0; r < d; ++r) {
+      double dot = 0.0;
+      for (int i = j; i < d; ++i) dot += q[(size_t)r * d + i] * v[i];
+      dot *= s;
+      for (int i = j; i < d; ++i) q[(size_t)r * d + i] -= dot * v[i];
+    }
+  }
+  for (int j = 0; j < d; ++j)
+    if (rdiag[j] < 0.0)
+      for (int r = 0; r < d; ++r) q[(size_t)r * d + j] = -q[(size_t)r * d + j];
+  return q;
+}
+
+// ---------------------------------------------------------------------------
+// Lloyd-Max quantizer of N(0,1) with 2^bits levels (Sec. 2.2 item 3).  The
+// optimum is symmetric, so only the positive half is iterated: cells
+// [t_0 = 0, t_1), ..., [t_{h-1}, inf) with centroids c_0 < ... < c_{h-1}.
+// ---------------------------------------------------------------------------
+inline double npdf(double x) { return std::exp(-0.5 * x * x) * 0.3989422804014326779; }
+inline double ntail(double x) { return 0.5 * std::erfc(x * 0.7071067811865475244); }
+
+void lloyd_max(int bits, std::vector<double>& cent, std::vector<double>& bnd) {
+  const int L = 1 << bits, h = L / 2;
+  std::vector<double> c(h), t(h + 1);
+  for (int i = 0; i < h; ++i) c[i] = (i + 0.5) * 3.0 / h;
+  for (int it = 0; it < 400000; ++it) {
+    t[0] = 0.0;
+    for (int i = 1; i < h; ++i) t[i] = 0.5 * (c[i - 1] + c[i]);
+    double delta = 0.0;
+    for (int i = 0; i < h; ++i) {
+      const double lo = t[i];
+      const double num = npdf(lo) - (i + 1 < h ? npdf(t[i + 1]) : 0.0);
+      const double den = ntail(lo) - (i + 1 < h ? ntail(t[i + 1]) : 0.0);
+      const double nc = num / den;
+      delta = std::fmax(delta, std::fabs(nc - c[i]));
+      c[i] = nc;
+    }
+    if (delta < 1e-16) break;
+  }
+  cent.assign(L, 0.0);
+  bnd.assign(L - 1, 0.0);
+  for (int i = 0; i < h; ++i) {
+    cent[h + i] = c[i];
+    cent[h - 1 - i] = -c[i];
+  }
+  for (int i = 0; i + 1 < L; ++i) bnd[i] = 0.5 * (cent[i] + cent[i + 1]);
+  bnd[h - 1] = 0.0;
+}
+
+eoq_status fail(eoq_ctx* ctx, eoq_status st, const char* msg) {
+  if (ctx) ctx->err = msg;
+  return st;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+eoq_status check_packed(eoq_ctx* ctx, const eoq_packed& p) {
+  const void* ptrs[] = {p.codes, p.norms, p.rank, p.phi, p.sigma, p.lfac, p.rfac, p.flags};
+  for (const void* q : ptrs) {
+    if (!q) return fail(ctx, EOQ_ERR_ARG, "eoq_packed has a null member");
+    if (!aligned16(q)) return fail(ctx, EOQ_ERR_ARG, "eoq_packed member not 16-byte aligned");
+  }
+  return EOQ_OK;
+}
+
+EoqLaunch make_launch(const eoq_ctx* ctx, void* stream) {
+  EoqLaunch L;
+  L.n = ctx->n;
+  L.bits = ctx->bits;
+  L.r_max = ctx->r_max;
+  L.k = ctx->k;
+  L.rank_thr = ctx->rank_thr;
+  L.pi = ctx->d_pi;
+  L.pit = ctx->d_pit;
+  L.tab = ctx->d_tab;
+  L.stream = static_cast<hipStream_t>(stream);
+  return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+int eoq_pilot_k(int d) {
+  if (d < 3) return 0;
+  const double c = std::fmin(1.0 / 2.01, 1.0 / std::log(std::log((double)d)));
+  return (int)std::floor(std::pow((double)d, c));
+}
+
+eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, int r_max) {
+  if (!out) return EOQ_ERR_ARG;
+  *out = nullptr;
+  if (d != EOQ_D || n < 128 || n > 4096 || (n % 128) != 0 || bits < 1 || bits > 4 || r_max < 1 ||
+      r_max > EOQ_RMAX_CAP)
+    return EOQ_ERR_UNSUPPORTED;
+  eoq_ctx* ctx = new (std::nothrow) eoq_ctx;
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->n = n;
+  ctx->d = d;
+  ctx->bits = bits;
+  ctx->r_max = r_max;
+  ctx->seed = rot_seed;
+  ctx->k = eoq_pilot_k(d);
+  ctx->rank_thr = std::pow((double)d, -1.0 / 3.0);
+  if (2 * ctx->k + r_max + 1 > d) {  // Alg. 2 Step 2 reads eigenvalue number 2k + r + 1
+    delete ctx;
+    return EOQ_ERR_UNSUPPORTED;
+  }
+
+  const std::vector<double> q = haar_rotation(d, rot_seed);
+  ctx->pi_host.resize((size_t)d * d);
+  std::vector<float> pit((size_t)d * d);
+  for (int c = 0; c < d; ++c)
+    for (int j = 0; j < d; ++j) {
+      const float v = (float)q[(size_t)c * d + j];
+      ctx->pi_host[(size_t)c * d + j] = v;
+      pit[(size_t)j * d + c] = v;
+    }
+  std::vector<double> cent, bnd;
+  lloyd_max(bits, cent, bnd);
+  ctx->cent_host.assign(cent.begin(), cent.end());
+  ctx->bnd_host.assign(bnd.begin(), bnd.end());
+  float tab[32];
+  for (int i = 0; i < 16; ++i) tab[i] = (i < (1 << bits)) ? ctx->cent_host[i] : 0.0f;
+  for (int i = 0; i < 16; ++i) tab[16 + i] = (i < (1 << bits) - 1) ? ctx->bnd_host[i] : INFINITY;
+
+  // Without a HIP device the context is host-only: the tables can be read back, the hot calls fail.
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+    (void)hipGetLastError();
+    ctx->device = -1;
+    *out = ctx;
+    return EOQ_OK;
+  }
+  hipError_t e = hipGetDevice(&ctx->device);
+  const size_t mat_bytes = (size_t)d * d * sizeof(float);
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pi, mat_bytes);
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pit, mat_bytes);
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_tab, sizeof(tab));
+  if (e == hipSuccess) e = hipMemcpy(ctx->d_pi, ctx->pi_host.data(), mat_bytes, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(ctx->d_pit, pit.data(), mat_bytes, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(ctx->d_tab, tab, sizeof(tab), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    std::fprintf(stderr, "eoq_create: %s\n", hipGetErrorString(e));
+    eoq_destroy(ctx);
+    return EOQ_ERR_HIP;
+  }
+  *out = ctx;
+  return EOQ_OK;
+}
+
+void eoq_destroy(eoq_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->d_pi) (void)hipFree(ctx->d_pi);
+  if (ctx->d_pit) (void)hipFree(ctx->d_pit);
+  if (ctx->d_tab) (void)hipFree(ctx->d_tab);
+  delete ctx;
+}
+
+size_t eoq_workspace_bytes(const eoq_ctx* ctx, int64_t B) {
+  if (!ctx || B < 0) return 0;
+  return eoq_ws_lam_bytes(B) + eoq_ws_wfac_bytes(B, ctx->r_max);
+}
+
+eoq_status eoq_rotation(const eoq_ctx* ctx, float* host_out) {
+  if (!ctx || !host_out) return EOQ_ERR_ARG;
+  std::memcpy(host_out, ctx->pi_host.data(), ctx->pi_host.size() * sizeof(float));
+  return EOQ_OK;
+}
+
+eoq_status eoq_codebook(const eoq_ctx* ctx, float* host_centroids, float* host_bounds) {
+  if (!ctx || !host_centroids || !host_bounds) return EOQ_ERR_ARG;
+  std::memcpy(host_centroids, ctx->cent_host.data(), ctx->cent_host.size() * sizeof(float));
+  std::memcpy(host_bounds, ctx->bnd_host.data(), ctx->bnd_host.size() * sizeof(float));
+  return EOQ_OK;
+}
+
+eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_packed out,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (B < 0) return fail(ctx, EOQ_ERR_ARG, "negative block count");
+  if (dtype != EOQ_F16 && dtype != EOQ_F32) return fail(ctx, EOQ_ERR_UNSUPPORTED, "dtype must be EOQ_F16 or EOQ_F32");
+  if (B == 0) return EOQ_OK;
+  if (!blocks || !workspace) return fail(ctx, EOQ_ERR_ARG, "null blocks or workspace pointer");
+  if (!aligned16(blocks) || !aligned16(workspace)) return fail(ctx, EOQ_ERR_ARG, "blocks/workspace not 16-byte aligned");
+  if (eoq_status st = check_packed(ctx, out)) return st;
+  if (workspace_bytes < eoq_workspace_bytes(ctx, B)) return fail(ctx, EOQ_ERR_WORKSPACE, "workspace too small");
+  if (B > (int64_t)1 << 24) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  double* lam = static_cast<double*>(workspace);
+  float* wfac = reinterpret_cast<float*>(static_cast<char*>(workspace) + eoq_ws_lam_bytes(B));
+  hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, out);
+  if (e == hipSuccess) e = eoq_launch_encode(L, blocks, (int)dtype, B, wfac, out);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+eoq_status eoq_decompress(eoq_ctx* ctx, eoq_packed in, int64_t B, void* out_fp16, void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (B < 0) return fail(ctx, EOQ_ERR_ARG, "negative block count");
+  if (B == 0) return EOQ_OK;
+  if (!out_fp16 || !aligned16(out_fp16)) return fail(ctx, EOQ_ERR_ARG, "null or misaligned output pointer");
+  if (eoq_status st = check_packed(ctx, in)) return st;
+  if (B > (int64_t)1 << 24) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  hipError_t e = eoq_launch_decode(L, in, B, out_fp16);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+eoq_status eoq_scores(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_heads, int64_t blocks_per_head,
+                      const void* q_fp16, int n_q_heads, float* scores, void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (n_seq < 0 || blocks_per_head < 0 || n_kv_heads < 1 || n_q_heads < 1)
+    return fail(ctx, EOQ_ERR_ARG, "negative or zero size");
+  if (n_q_heads % n_kv_heads != 0 || n_q_heads / n_kv_heads > 8)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "query heads must be a multiple (1..8) of KV heads");
+  if (n_seq == 0 || blocks_per_head == 0) return EOQ_OK;
+  if (!q_fp16 || !scores || !aligned16(q_fp16) || !aligned16(scores))
+    return fail(ctx, EOQ_ERR_ARG, "null or misaligned query/score pointer");
+  if (eoq_status st = check_packed(ctx, keys)) return st;
+  if (n_seq * n_kv_heads * blocks_per_head > (int64_t)1 << 24)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  hipError_t e = eoq_launch_scores(L, keys, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+const char* eoq_last_error(const eoq_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+}  // extern "C"

@@ -1,0 +1,52 @@
+// Internal declarations shared by the host part (eoq_host.hip) and the kernels
+// (eoq_kernels.hip) of the eOptShrinkQ library.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "eoq.h"
+
+constexpr int EOQ_D = 128;        // head dimension handled by the kernels
+constexpr int EOQ_RMAX_CAP = 32;  // upper limit of r_max
+
+struct eoq_ctx {
+  int n = 0, d = 0, bits = 0, r_max = 0;
+  int k = 0;              // pilot parameter of Alg. 2
+  double rank_thr = 0.0;  // d^{-1/3}
+  uint64_t seed = 0;
+  int device = 0;
+  std::vector<float> pi_host;    // [d][d], z = Pi u
+  std::vector<float> cent_host;  // 2^bits centroids of N(0,1)
+  std::vector<float> bnd_host;   // 2^bits - 1 midpoints
+  float* d_pi = nullptr;         // device Pi   [c][j]
+  float* d_pit = nullptr;        // device Pi^T [j][c]
+  float* d_tab = nullptr;        // device: 16 centroids then 16 bounds (padded)
+  std::string err;
+};
+
+// Device-side view of everything a launch needs.
+struct EoqLaunch {
+  int n, bits, r_max, k;
+  double rank_thr;
+  const float* pi;
+  const float* pit;
+  const float* tab;
+  hipStream_t stream;
+};
+
+// Workspace layout for B blocks: lam[B][128] f64, then wfac[B][r_max][128] f32
+// (right singular vectors scaled by phi/sigma, the projection operand).
+inline size_t eoq_ws_lam_bytes(int64_t B) { return (size_t)B * EOQ_D * sizeof(double); }
+inline size_t eoq_ws_wfac_bytes(int64_t B, int r_max) { return (size_t)B * r_max * EOQ_D * sizeof(float); }
+
+hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, double* lam,
+                               float* wfac, eoq_packed out);
+hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, const float* wfac,
+                             eoq_packed out);
+hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void* out_fp16);
+hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq, int n_kv_heads,
+                             int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores);

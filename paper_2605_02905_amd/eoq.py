@@ -1,0 +1,190 @@
+"""ctypes binding of the C-ABI library (include/eoq.h).  Argument marshalling only:
+every step of the path runs in the HIP kernels of libeoq.so.  PyTorch supplies device
+memory and the current stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libeoq.so")
+
+EOQ_OK, EOQ_ERR_ARG, EOQ_ERR_UNSUPPORTED, EOQ_ERR_WORKSPACE, EOQ_ERR_HIP = range(5)
+EOQ_F16, EOQ_F32 = 0, 1
+FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE = 1, 2, 4
+
+EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_codebook",
+           "eoq_compress", "eoq_decompress", "eoq_scores", "eoq_last_error"]
+
+
+class EoqError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"eoq status {status}: {msg}")
+        self.status = status
+
+
+class _Packed(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("norms", C.c_void_p), ("rank", C.c_void_p), ("phi", C.c_void_p),
+                ("sigma", C.c_void_p), ("lfac", C.c_void_p), ("rfac", C.c_void_p), ("flags", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libeoq.so (built by `__graft_entry__.build()`); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = C.CDLL(LIB_PATH)
+        L.eoq_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_int]
+        L.eoq_create.restype = C.c_int
+        L.eoq_destroy.argtypes = [C.c_void_p]
+        L.eoq_destroy.restype = None
+        L.eoq_pilot_k.argtypes = [C.c_int]
+        L.eoq_pilot_k.restype = C.c_int
+        L.eoq_workspace_bytes.argtypes = [C.c_void_p, C.c_int64]
+        L.eoq_workspace_bytes.restype = C.c_size_t
+        L.eoq_rotation.argtypes = [C.c_void_p, C.c_void_p]
+        L.eoq_rotation.restype = C.c_int
+        L.eoq_codebook.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.eoq_codebook.restype = C.c_int
+        L.eoq_compress.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, _Packed, C.c_void_p, C.c_size_t,
+                                   C.c_void_p]
+        L.eoq_compress.restype = C.c_int
+        L.eoq_decompress.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_void_p, C.c_void_p]
+        L.eoq_decompress.restype = C.c_int
+        L.eoq_scores.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_int, C.c_int64, C.c_void_p, C.c_int,
+                                 C.c_void_p, C.c_void_p]
+        L.eoq_scores.restype = C.c_int
+        L.eoq_last_error.argtypes = [C.c_void_p]
+        L.eoq_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def eoq_pilot_k(d: int) -> int:
+    return lib().eoq_pilot_k(d)
+
+
+@dataclass
+class Packed:
+    """Device tensors of a compressed batch (layout: include/eoq.h, eoq_packed)."""
+    codes: torch.Tensor   # uint8  [B, n, bits*d/8]
+    norms: torch.Tensor   # int16  [B, n]  (binary16 bit patterns; .view(torch.float16) to read)
+    rank: torch.Tensor    # int32  [B]
+    phi: torch.Tensor     # float32 [B, r_max]
+    sigma: torch.Tensor   # float32 [B, r_max]
+    lfac: torch.Tensor    # float16 [B, r_max, n]
+    rfac: torch.Tensor    # float16 [B, r_max, d]
+    flags: torch.Tensor   # int32  [B]
+
+    def c_struct(self) -> _Packed:
+        return _Packed(*(t.data_ptr() for t in (self.codes, self.norms, self.rank, self.phi, self.sigma,
+                                                 self.lfac, self.rfac, self.flags)))
+
+    @staticmethod
+    def empty(B: int, n: int, d: int, bits: int, r_max: int, device) -> "Packed":
+        kw = dict(device=device)
+        return Packed(torch.empty(B, n, bits * d // 8, dtype=torch.uint8, **kw),
+                      torch.empty(B, n, dtype=torch.float16, **kw),
+                      torch.empty(B, dtype=torch.int32, **kw),
+                      torch.empty(B, r_max, dtype=torch.float32, **kw),
+                      torch.empty(B, r_max, dtype=torch.float32, **kw),
+                      torch.zeros(B, r_max, n, dtype=torch.float16, **kw),
+                      torch.zeros(B, r_max, d, dtype=torch.float16, **kw),
+                      torch.empty(B, dtype=torch.int32, **kw))
+
+    def nbytes(self) -> int:
+        return sum(t.numel() * t.element_size() for t in (self.codes, self.norms, self.rank, self.phi, self.sigma,
+                                                          self.lfac, self.rfac, self.flags))
+
+
+def _stream_ptr(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+class Context:
+    """eoq_create / eoq_destroy plus the calls that take the context."""
+
+    def __init__(self, n: int, d: int = 128, bits: int = 2, rot_seed: int = 260502906, r_max: int = 32):
+        self.n, self.d, self.bits, self.r_max, self.rot_seed = n, d, bits, r_max, rot_seed
+        self._h = C.c_void_p()
+        st = lib().eoq_create(C.byref(self._h), n, d, bits, rot_seed, r_max)
+        if st != EOQ_OK:
+            self._h = C.c_void_p()
+            raise EoqError(st, "eoq_create failed")
+
+    def close(self):
+        if self._h:
+            lib().eoq_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != EOQ_OK:
+            raise EoqError(st, lib().eoq_last_error(self._h).decode())
+
+    # -- tables ------------------------------------------------------------
+    def eoq_rotation(self) -> np.ndarray:
+        out = np.empty((self.d, self.d), dtype=np.float32)
+        self._check(lib().eoq_rotation(self._h, out.ctypes.data))
+        return out
+
+    def eoq_codebook(self):
+        cent = np.empty(1 << self.bits, dtype=np.float32)
+        bnd = np.empty((1 << self.bits) - 1, dtype=np.float32)
+        self._check(lib().eoq_codebook(self._h, cent.ctypes.data, bnd.ctypes.data))
+        return cent, bnd
+
+    def eoq_workspace_bytes(self, B: int) -> int:
+        return lib().eoq_workspace_bytes(self._h, B)
+
+    # -- hot calls ---------------------------------------------------------
+    def eoq_compress(self, blocks: torch.Tensor, out: Packed | None = None, workspace: torch.Tensor | None = None):
+        """blocks: device tensor [B, n, d], float16 or float32, contiguous.  Returns (Packed, workspace)."""
+        assert blocks.is_cuda and blocks.is_contiguous() and blocks.shape[1:] == (self.n, self.d)
+        B = blocks.shape[0]
+        dtype = {torch.float16: EOQ_F16, torch.float32: EOQ_F32}[blocks.dtype]
+        if out is None:
+            out = Packed.empty(B, self.n, self.d, self.bits, self.r_max, blocks.device)
+        need = self.eoq_workspace_bytes(B)
+        if workspace is None:
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=blocks.device)
+        self._check(lib().eoq_compress(self._h, blocks.data_ptr(), dtype, B, out.c_struct(), workspace.data_ptr(),
+                                       workspace.numel(), _stream_ptr(blocks.device)))
+        return out, workspace
+
+    def eoq_decompress(self, rec: Packed, out: torch.Tensor | None = None) -> torch.Tensor:
+        B = rec.rank.shape[0]
+        if out is None:
+            out = torch.empty(B, self.n, self.d, dtype=torch.float16, device=rec.codes.device)
+        self._check(lib().eoq_decompress(self._h, rec.c_struct(), B, out.data_ptr(), _stream_ptr(out.device)))
+        return out
+
+    def eoq_scores(self, keys: Packed, q: torch.Tensor, n_kv_heads: int, out: torch.Tensor | None = None):
+        """q: [n_seq, n_q_heads, d] float16 device.  Returns [n_seq, n_q_heads, blocks_per_head * n] float32."""
+        assert q.is_cuda and q.is_contiguous() and q.dtype == torch.float16
+        n_seq, n_q_heads, _ = q.shape
+        B = keys.rank.shape[0]
+        bph = B // (n_seq * n_kv_heads)
+        assert bph * n_seq * n_kv_heads == B
+        if out is None:
+            out = torch.empty(n_seq, n_q_heads, bph * self.n, dtype=torch.float32, device=q.device)
+        self._check(lib().eoq_scores(self._h, keys.c_struct(), n_seq, n_kv_heads, bph, q.data_ptr(), n_q_heads,
+                                     out.data_ptr(), _stream_ptr(q.device)))
+        return out
+
+    def spectrum(self, workspace: torch.Tensor, B: int) -> torch.Tensor:
+        """Gram eigenvalues [B, d] (float64) that eoq_compress leaves at the head of its workspace."""
+        return workspace[: B * self.d * 8].view(torch.float64).view(B, self.d)

@@ -1,0 +1,133 @@
+"""Helpers shared by the GPU parity tests: run the CPU oracle over blocks (process pool) and
+move records between the oracle's per-block form and the library's batched device layout."""
+from __future__ import annotations
+
+import math
+import multiprocessing
+import os
+from concurrent.futures import ProcessPoolExecutor
+
+import numpy as np
+
+import oracle
+
+ROT_SEED = 260502906
+_CACHE = {}
+
+
+def oracle_tables(bits: int, d: int = 128, seed: int = ROT_SEED):
+    key = (bits, d, seed)
+    if key not in _CACHE:
+        Pi = oracle.haar_rotation(d, seed).astype(np.float32).astype(np.float64)   # the stored float32 table
+        _CACHE[key] = (Pi, oracle.lloyd_max_gaussian(bits))
+    return _CACHE[key]
+
+
+def _init_worker():
+    # one BLAS thread per worker: the pool is the parallelism
+    try:
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(1)
+    except Exception:
+        pass
+
+
+def _one(args):
+    S, bits, r_max, seed = args
+    Pi, cb = oracle_tables(bits, S.shape[1], seed)
+    rec = oracle.compress_block(S, Pi, cb, r_max)
+    rec.R = None
+    rec.z = None
+    return rec
+
+
+def oracle_compress(blocks: np.ndarray, bits: int, r_max: int = 32, seed: int = ROT_SEED, workers: int | None = None):
+    """blocks: [B, n, d] float64 (exactly the values handed to the GPU). Returns a list of BlockRecord."""
+    jobs = [(blocks[b], bits, r_max, seed) for b in range(blocks.shape[0])]
+    workers = workers or min(8, os.cpu_count() or 1)
+    if len(jobs) <= 2 or workers == 1:
+        return [_one(j) for j in jobs]
+    # spawn, not fork: the parent may already hold a HIP context, which a forked child cannot use or inherit safely
+    with ProcessPoolExecutor(workers, mp_context=multiprocessing.get_context("spawn"), initializer=_init_worker) as ex:
+        return list(ex.map(_one, jobs, chunksize=max(1, len(jobs) // (4 * workers))))
+
+
+def records_to_packed(recs, r_max: int, device):
+    """Oracle records -> the library's device layout (eoq.Packed)."""
+    import torch
+    from paper_2605_02905_amd import eoq
+    B, n, d, bits = len(recs), recs[0].n, recs[0].d, recs[0].bits
+    codes = np.stack([oracle.pack_codes(r.codes, bits) for r in recs])
+    norms = np.stack([oracle.fp16_bits(r.rho16) for r in recs]).view(np.float16)
+    rank = np.array([r.rank for r in recs], dtype=np.int32)
+    phi = np.zeros((B, r_max), dtype=np.float32)
+    sigma = np.zeros((B, r_max), dtype=np.float32)
+    lfac = np.zeros((B, r_max, n), dtype=np.float16)
+    rfac = np.zeros((B, r_max, d), dtype=np.float16)
+    for b, r in enumerate(recs):
+        phi[b, :r.rank] = r.phi
+        sigma[b, :r.rank] = r.sigma
+        lfac[b, :r.rank] = r.lfac
+        rfac[b, :r.rank] = r.rfac
+    t = lambda a: torch.from_numpy(a).to(device)
+    return eoq.Packed(t(codes), t(norms), t(rank), t(phi), t(sigma), t(lfac), t(rfac),
+                      torch.zeros(B, dtype=torch.int32, device=device))
+
+
+def rel_fro(a: np.ndarray, b: np.ndarray) -> float:
+    return float(np.linalg.norm(a - b) / np.linalg.norm(a))
+
+
+def compare_compress(blocks64: np.ndarray, rec, lam_gpu: np.ndarray, recs, bits: int, r_max: int = 32):
+    """Parity of eoq_compress against oracle records.  Returns a dict of statistics; asserts the bars:
+    ranks bit-exact, shrunk values within 1e-3 relative, code mismatches <= 0.1 % of entries."""
+    B, n, d = blocks64.shape
+    rank_g = rec.rank.cpu().numpy()
+    rank_o = np.array([r.rank for r in recs])
+    assert np.array_equal(rank_g, rank_o), f"rank mismatch at blocks {np.nonzero(rank_g != rank_o)[0][:10]}: " \
+        f"gpu {rank_g[rank_g != rank_o][:10]} oracle {rank_o[rank_g != rank_o][:10]}"
+    flags = rec.flags.cpu().numpy()
+    flags_o = np.array([r.flags for r in recs])
+    assert np.array_equal(flags & 3, flags_o & 3)
+    assert not np.any(flags & 4), "eigensolver hit its sweep limit"
+    phi_g = rec.phi.cpu().numpy().astype(np.float64)
+    sig_g = rec.sigma.cpu().numpy().astype(np.float64)
+    codes_g = rec.codes.cpu().numpy()
+    norms_g = rec.norms.cpu().numpy().astype(np.float64)
+    lfac_g = rec.lfac.cpu().numpy().astype(np.float64)
+    rfac_g = rec.rfac.cpu().numpy().astype(np.float64)
+    stats = dict(max_phi_rel=0.0, max_sigma_rel=0.0, max_lam_rel=0.0, mismatches=0, entries=0, max_lowrank_abs=0.0,
+                 norm_ulp_diffs=0)
+    for b, r in enumerate(recs):
+        lam_o = r.lam
+        stats["max_lam_rel"] = max(stats["max_lam_rel"], float(np.max(np.abs(lam_gpu[b] - lam_o)) / lam_o[0]) if lam_o[0] > 0 else 0.0)
+        if r.rank:
+            stats["max_phi_rel"] = max(stats["max_phi_rel"], float(np.max(np.abs(phi_g[b, :r.rank] - r.phi) / np.maximum(r.phi, 1e-300))))
+            stats["max_sigma_rel"] = max(stats["max_sigma_rel"], float(np.max(np.abs(sig_g[b, :r.rank] - r.sigma) / r.sigma)))
+            # eigenvector signs are arbitrary: compare the product of the stored factors
+            lo_g = lfac_g[b, :r.rank].T @ rfac_g[b, :r.rank]
+            lo_o = r.lfac.T @ r.rfac
+            stats["max_lowrank_abs"] = max(stats["max_lowrank_abs"], float(np.max(np.abs(lo_g - lo_o)) / np.max(np.abs(lo_o))))
+        cg = oracle.unpack_codes(codes_g[b], bits, d)
+        stats["mismatches"] += int(np.count_nonzero(cg != r.codes))
+        stats["entries"] += n * d
+        # stored norms: binary16 of the same real number up to the kernel's float32 rounding
+        dn = np.abs(norms_g[b] - r.rho16)
+        stats["norm_ulp_diffs"] += int(np.count_nonzero(dn > 0))
+        assert np.all(dn <= 2e-3 * np.maximum(r.rho16, 1e-30) + 1e-7), b
+    assert stats["max_phi_rel"] <= 1e-3, stats
+    assert stats["max_sigma_rel"] <= 1e-3, stats
+    assert stats["mismatches"] <= 1e-3 * stats["entries"], stats
+    assert stats["max_lowrank_abs"] <= 5e-3, stats
+    return stats
+
+
+def log_stats(name: str, stats: dict):
+    """Append parity statistics to gpurun_out/parity_stats.jsonl when that folder exists (GPU runs)."""
+    import json
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = os.path.join(root, "gpurun_out")
+    if os.path.isdir(out):
+        with open(os.path.join(out, "parity_stats.jsonl"), "a") as fh:
+            fh.write(json.dumps({"case": name, **{k: (float(v) if isinstance(v, (float, np.floating)) else int(v))
+                                                  for k, v in stats.items()}}) + "\n")

@@ -1,0 +1,223 @@
+"""GPU parity: the HIP path (through the C ABI) against the float64 CPU oracle on the same seeded inputs.
+
+Bars (from the benchmark definition): estimated ranks and codebooks bit-exact; shrunk singular values within
+1e-3 relative; relative Frobenius reconstruction errors of the two paths agree within 1e-3; code indices may
+differ only at decision boundaries, at most 0.1 % of entries."""
+import math
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from paper_2605_02905_amd import eoq, synth
+from tests import _util as U
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+
+
+def _gpu_compress(blocks_t, bits, n, r_max=32):
+    ctx = eoq.Context(n=n, bits=bits, r_max=r_max)
+    rec, ws = ctx.eoq_compress(blocks_t.to(DEV).contiguous())
+    torch.cuda.synchronize()
+    lam = ctx.spectrum(ws, blocks_t.shape[0]).cpu().numpy()
+    return ctx, rec, lam
+
+
+def _recon_agreement(ctx, rec, blocks64, recs, bits):
+    Pi, cb = U.oracle_tables(bits)
+    xg = ctx.eoq_decompress(rec)
+    torch.cuda.synchronize()
+    xg = xg.cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for b, r in enumerate(recs):
+        S = blocks64[b]
+        if not np.any(S):
+            assert not np.any(xg[b])
+            continue
+        xo = oracle.decompress_block(r, Pi, cb)
+        e_g, e_o = U.rel_fro(S, xg[b]), U.rel_fro(S, xo)
+        worst = max(worst, abs(e_g - e_o) / e_o)
+    assert worst <= 1e-3, worst
+    return worst
+
+
+def test_tables_bit_exact_on_device_context():
+    for bits in (1, 2, 3, 4):
+        ctx = eoq.Context(n=512, bits=bits)
+        Pi, cb = U.oracle_tables(bits)
+        cent, bnd = ctx.eoq_codebook()
+        assert np.array_equal(cent, cb.centroids_f32) and np.array_equal(bnd, cb.bounds_f32)
+        P = ctx.eoq_rotation().astype(np.float64)
+        assert np.max(np.abs(P - Pi)) <= 2 ** -24
+        assert np.max(np.abs(P.T @ P - np.eye(128))) <= 1e-6
+
+
+def test_config1_single_block_fp32():
+    """Config 1: one 512 x 128 float32 block, spikes (6, 4, 2.5) sqrt(n), white noise, b = 2; rank 3 is
+    recovered and the inner products with 64 N(0, I) queries match the oracle's."""
+    spec = synth.config(1)
+    blocks, planted = synth.make_blocks(spec)
+    assert blocks.dtype == torch.float32
+    b64 = blocks.double().numpy()
+    recs = U.oracle_compress(b64, 2)
+    assert recs[0].rank == 3
+    ctx, rec, lam = _gpu_compress(blocks, 2, spec.n)
+    st = U.compare_compress(b64, rec, lam, recs, 2)
+    U.log_stats("cfg1", st)
+    assert int(rec.rank[0]) == 3
+    assert st["max_lam_rel"] < 1e-10 and st["max_phi_rel"] < 1e-5
+    _recon_agreement(ctx, rec, b64, recs, 2)
+    # 64 queries iid N(0, I): 8 calls of one 8-head group against the same key block
+    Pi, cb = U.oracle_tables(2)
+    q = synth.make_queries(8, 8, scale=1.0)
+    so = oracle.score_block(q.reshape(64, 128).double().numpy(), recs[0], Pi, cb)
+    worst = 0.0
+    for i in range(8):
+        sg = ctx.eoq_scores(rec, q[i:i + 1].to(DEV).contiguous(), n_kv_heads=1)
+        worst = max(worst, float(np.max(np.abs(sg[0].double().cpu().numpy() - so[8 * i:8 * i + 8]))))
+    # both sides score their own reconstruction; they differ where codes differ (<= 0.1 % of entries)
+    assert worst <= 2e-2 * np.max(np.abs(so)), worst
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_config2_blocks_against_oracle(bits):
+    """Two head-tensors (128 blocks) of the Llama-shaped layer, every block checked."""
+    spec = synth.config(2)
+    blocks, _ = synth.make_blocks(spec, tensors=range(2))
+    b64 = blocks.double().numpy()
+    recs = U.oracle_compress(b64, bits)
+    ctx, rec, lam = _gpu_compress(blocks, bits, spec.n)
+    st = U.compare_compress(b64, rec, lam, recs, bits)
+    U.log_stats(f"cfg2-2tensors-b{bits}", st)
+    assert st["max_lam_rel"] < 1e-9
+    _recon_agreement(ctx, rec, b64, recs, bits)
+
+
+def test_config4_blocks_with_pure_noise():
+    """n = 1024, ranks 1..12 and 10 % pure-noise blocks (the r = 0 bypass of Alg. 3)."""
+    spec = synth.config(4)
+    blocks, planted = synth.make_blocks(spec, tensors=range(1))
+    blocks = blocks[:48]
+    b64 = blocks.double().numpy()
+    recs = U.oracle_compress(b64, 2)
+    ctx, rec, lam = _gpu_compress(blocks, 2, spec.n)
+    U.compare_compress(b64, rec, lam, recs, 2)
+    _recon_agreement(ctx, rec, b64, recs, 2)
+
+
+def test_white_noise_blocks_take_the_rank0_path():
+    gen = torch.Generator().manual_seed(5)
+    blocks = torch.randn(5, 512, 128, generator=gen).to(torch.float16)
+    b64 = blocks.double().numpy()
+    recs = U.oracle_compress(b64, 2)
+    assert all(r.rank == 0 for r in recs)
+    ctx, rec, lam = _gpu_compress(blocks, 2, 512)
+    U.compare_compress(b64, rec, lam, recs, 2)
+    assert int(rec.rank.abs().sum()) == 0
+    _recon_agreement(ctx, rec, b64, recs, 2)
+
+
+@pytest.mark.parametrize("n,bits,B,r_max", [(128, 2, 3, 32), (256, 1, 1, 32), (512, 4, 2, 32), (512, 2, 7, 2)])
+def test_shapes_bits_and_rank_clamp(n, bits, B, r_max):
+    spec = synth.BlockSpec("edge", n=n, n_tensors=1, blocks_per_tensor=B, rank_lo=3, rank_hi=6)
+    blocks, _ = synth.make_blocks(spec, seed=99)
+    b64 = blocks.double().numpy()
+    recs = U.oracle_compress(b64, bits, r_max=r_max)
+    ctx, rec, lam = _gpu_compress(blocks, bits, n, r_max=r_max)
+    U.compare_compress(b64, rec, lam, recs, bits, r_max=r_max)
+    if r_max == 2:
+        assert np.all(rec.flags.cpu().numpy() & eoq.FLAG_RANK_CLAMPED)
+    _recon_agreement(ctx, rec, b64, recs, bits)
+
+
+def test_degenerate_blocks():
+    """All-zero block, a block with zero rows, and a block with huge entries (norm saturates binary16)."""
+    gen = torch.Generator().manual_seed(7)
+    blocks = torch.randn(3, 512, 128, generator=gen)
+    blocks[0] = 0
+    blocks[1, 10:20] = 0
+    blocks[2] *= 8000.0
+    blocks = blocks.to(torch.float16)
+    b64 = blocks.double().numpy()
+    with np.errstate(all="ignore"):
+        recs = U.oracle_compress(b64, 2, workers=1)
+    ctx, rec, lam = _gpu_compress(blocks, 2, 512)
+    U.compare_compress(b64, rec, lam, recs, 2)
+    norms = rec.norms.cpu().numpy()
+    assert not np.any(norms[0]) and not np.any(norms[1, 10:20])
+    assert np.all(norms[2] == np.float16(65504.0))
+    codes0 = oracle.unpack_codes(rec.codes[0].cpu().numpy(), 2, 128)
+    assert np.all(codes0 == 2)
+
+
+def test_decompress_of_oracle_records_elementwise():
+    """eoq_decompress fed with records produced by the oracle: element-wise agreement to binary16 rounding."""
+    spec = synth.config(2)
+    blocks, _ = synth.make_blocks(spec, tensors=range(1))
+    blocks = blocks[:6]
+    for bits in (2, 3):
+        Pi, cb = U.oracle_tables(bits)
+        recs = U.oracle_compress(blocks.double().numpy(), bits)
+        ctx = eoq.Context(n=spec.n, bits=bits)
+        packed = U.records_to_packed(recs, 32, DEV)
+        xg = ctx.eoq_decompress(packed)
+        torch.cuda.synchronize()
+        xg = xg.cpu().numpy().astype(np.float64)
+        for b, r in enumerate(recs):
+            xo = oracle.decompress_block(r, Pi, cb)
+            # float32 accumulation error plus one binary16 rounding of the result
+            assert np.max(np.abs(xg[b] - xo) - 2.0 ** -10 * np.abs(xo)) <= 1e-4 * np.max(np.abs(xo)), (bits, b)
+
+
+def test_scores_of_oracle_records():
+    """Config-5 layout in small: 2 sequences x 2 KV heads x 3 blocks, 4 query heads per KV head."""
+    n_seq, n_kv, bph, group = 2, 2, 3, 4
+    spec = synth.BlockSpec("keys", n=512, n_tensors=n_seq * n_kv, blocks_per_tensor=bph, rank_lo=2, rank_hi=8)
+    blocks, _ = synth.make_blocks(spec, seed=123)
+    Pi, cb = U.oracle_tables(2)
+    recs = U.oracle_compress(blocks.double().numpy(), 2)
+    ctx = eoq.Context(n=512, bits=2)
+    packed = U.records_to_packed(recs, 32, DEV)
+    q = synth.make_queries(n_seq, n_kv * group)
+    sg = ctx.eoq_scores(packed, q.to(DEV), n_kv_heads=n_kv)
+    torch.cuda.synchronize()
+    sg = sg.cpu().numpy().astype(np.float64)
+    assert sg.shape == (n_seq, n_kv * group, bph * 512)
+    q64 = q.double().numpy()
+    for s in range(n_seq):
+        for g in range(n_kv):
+            for j in range(bph):
+                r = recs[(s * n_kv + g) * bph + j]
+                so = oracle.score_block(q64[s, g * group:(g + 1) * group], r, Pi, cb)
+                got = sg[s, g * group:(g + 1) * group, j * 512:(j + 1) * 512]
+                assert np.max(np.abs(got - so)) <= 1e-5 * max(1.0, np.max(np.abs(so))), (s, g, j)
+
+
+def test_argument_errors_on_device():
+    ctx = eoq.Context(n=512, bits=2)
+    x = torch.zeros(2, 512, 128, dtype=torch.float16, device=DEV)
+    rec = eoq.Packed.empty(2, 512, 128, 2, 32, DEV)
+    small = torch.empty(16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(eoq.EoqError) as ei:
+        ctx.eoq_compress(x, rec, small)
+    assert ei.value.status == eoq.EOQ_ERR_WORKSPACE
+    L = eoq.lib()
+    ws = torch.empty(ctx.eoq_workspace_bytes(2), dtype=torch.uint8, device=DEV)
+    assert L.eoq_compress(ctx._h, x.data_ptr() + 2, 0, 2, rec.c_struct(), ws.data_ptr(), ws.numel(), None) == eoq.EOQ_ERR_ARG
+    assert L.eoq_compress(ctx._h, None, 0, 2, rec.c_struct(), ws.data_ptr(), ws.numel(), None) == eoq.EOQ_ERR_ARG
+    assert L.eoq_compress(ctx._h, x.data_ptr(), 7, 2, rec.c_struct(), ws.data_ptr(), ws.numel(), None) == eoq.EOQ_ERR_UNSUPPORTED
+    assert L.eoq_compress(ctx._h, x.data_ptr(), 0, 0, rec.c_struct(), ws.data_ptr(), ws.numel(), None) == eoq.EOQ_OK
+    q = torch.zeros(1, 6, 128, dtype=torch.float16, device=DEV)
+    out = torch.zeros(1, 6, 1024, device=DEV)
+    assert L.eoq_scores(ctx._h, rec.c_struct(), 1, 4, 1, q.data_ptr(), 6, out.data_ptr(), None) == eoq.EOQ_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
