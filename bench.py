@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the eOptShrinkQ hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic KV blocks resident in HBM:
+eoq_compress (Gram + eigensolve + rank + shrinkage + residual + rotate/quantize/pack), eoq_decompress of
+the record, and eoq_scores of decode queries against the compressed keys of the batch.  The default
+workload is the Llama-3.1-8B-shaped layer (8 KV heads x {K,V} x T=32768, blocks of 512 x 128, fp16,
+2 residual bits).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import multiprocessing
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+FP64_VECTOR_PEAK_TFLOPS = 78.6     # 256 CUs x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz
+D = 128
+
+
+def spectral_flops_per_block(n: int, sweeps: float) -> float:
+    """Algorithmic flops of the dominant kernel per block: Gram 2 n d^2 plus, per Jacobi sweep, d(d-1)/2 column
+    pairs at 2d (one inner product) + 6d (rotating two columns of length d)."""
+    pairs = D * (D - 1) // 2
+    return 2.0 * n * D * D + sweeps * pairs * (2 * D + 6 * D)
+
+
+# ---- CPU baseline (the float64 oracle, untouched, fanned out over host cores) ---------------------------
+def _cpu_init():
+    # one BLAS thread per worker (the pool is the parallelism); must be in place before NumPy loads its BLAS
+    for var in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
+        os.environ[var] = "1"
+    import numpy  # noqa: F401
+    try:
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(1)
+    except Exception:
+        pass
+
+
+def _cpu_job(args):
+    import numpy as np
+    import oracle
+    blocks16, bits, seed, q = args
+    Pi = oracle.haar_rotation(D, seed).astype(np.float32).astype(np.float64)
+    cb = oracle.lloyd_max_gaussian(bits)
+    n = 0
+    for S in blocks16:
+        rec = oracle.compress_block(S.astype(np.float64), Pi, cb)
+        x = oracle.decompress_block(rec, Pi, cb).astype(np.float16)
+        if q is not None:
+            oracle.score_block(q, rec, Pi, cb)
+        n += 1
+    return n
+
+
+def cpu_baseline(blocks_cpu, bits: int, seed: int, q_cpu, sample_blocks: int):
+    import numpy as np
+    cores = min(os.cpu_count() or 1, 16)
+    B = min(sample_blocks, blocks_cpu.shape[0])
+    arr = blocks_cpu[:B].numpy()
+    q = None if q_cpu is None else q_cpu.double().numpy()
+    per = max(1, B // (cores * 4))
+    jobs = [(arr[i:i + per], bits, seed, q) for i in range(0, B, per)]
+    ctx = multiprocessing.get_context("spawn")
+    with ctx.Pool(cores, initializer=_cpu_init) as pool:
+        pool.map(_cpu_job, [(arr[:1], bits, seed, q)] * cores)      # start the workers before the clock
+        t0 = time.perf_counter()
+        done = sum(pool.map(_cpu_job, jobs))
+        dt = time.perf_counter() - t0
+    nbytes = done * arr.shape[1] * arr.shape[2] * 2
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {done} of the batch's blocks, whole path (compress+decompress+scores), float64 NumPy, "
+                      f"one single-threaded worker per core", "seconds": dt, "blocks_per_s": done / dt}
+
+
+def log(msg: str):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    import faulthandler
+    faulthandler.enable()
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--bits", type=int, default=2)
+    ap.add_argument("--cpu-blocks", type=int, default=1024, help="blocks in the CPU-baseline sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (blocks are independent; see the sharding note in "
+              "DESIGN.md); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2605_02905_amd import eoq, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    cfg = int(args.workload[3])
+    spec = synth.config(cfg)
+    bits = args.bits
+    log(f"generating {spec.name} on the GPU")
+    blocks, _ = synth.make_blocks(spec, device=dev)
+    torch.cuda.synchronize()
+    log(f"{blocks.shape[0]} blocks ready")
+    B, n = blocks.shape[0], spec.n
+    # decode queries against the key half of the batch: tensors are (head, K/V) pairs -> even tensors are keys
+    if cfg == 5:
+        n_seq, n_kv, group = 16, 8, 4
+        keys_sel = None
+    else:
+        n_seq, n_kv, group = 1, 8, 4
+    ctx = eoq.Context(n=n, bits=bits)
+    ctx.eoq_profile(True)
+    rec = eoq.Packed.empty(B, n, D, bits, ctx.r_max, dev)
+    ws = torch.empty(ctx.eoq_workspace_bytes(B), dtype=torch.uint8, device=dev)
+    xhat = torch.empty(B, n, D, dtype=torch.float16, device=dev)
+    if cfg == 5:
+        key_blocks = B
+        bph = B // (n_seq * n_kv)
+    else:
+        # layout [head][K/V][block]: score the first 8*bph blocks as one sequence of 8 KV heads
+        bph = spec.blocks_per_tensor
+        key_blocks = n_kv * bph
+    keys = eoq.Packed(rec.codes[:key_blocks], rec.norms[:key_blocks], rec.rank[:key_blocks], rec.phi[:key_blocks],
+                      rec.sigma[:key_blocks], rec.lfac[:key_blocks], rec.rfac[:key_blocks], rec.flags[:key_blocks])
+    q = synth.make_queries(n_seq, n_kv * group, device=dev)
+    scores = torch.empty(n_seq, n_kv * group, bph * n, dtype=torch.float32, device=dev)
+
+    def step():
+        ctx.eoq_compress(blocks, rec, ws)
+        ctx.eoq_decompress(rec, xhat)
+        ctx.eoq_scores(keys, q, n_kv, scores)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    log("warmup done")
+    stage = {"spectral": 0.0, "encode": 0.0, "decode": 0.0, "scores": 0.0}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+        ms = ctx.eoq_stage_ms()          # waits for this step's events: per-kernel durations on the launch stream
+        for k_ in stage:
+            stage[k_] += ms[k_]
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    ms_per_step = total_s * 1e3 / args.steps
+    log(f"timed {args.steps} steps: {ms_per_step:.3f} ms/step")
+    for k_ in stage:
+        stage[k_] /= args.steps
+
+    in_bytes = B * n * D * 2
+    flags = rec.flags.cpu()
+    sweeps = ((flags >> 8) & 0xFF).double().mean().item()
+    ranks = rec.rank.cpu().double()
+    rec_bytes = (B * n * (bits * D // 8) + B * n * 2 + int(ranks.sum().item()) * (n + D) * 2 + B * 12)
+    flops = spectral_flops_per_block(n, sweeps) * B
+    achieved_tflops = flops / (stage["spectral"] * 1e-3) / 1e12
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"traffic_spectral_{args.workload}.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split("=")[1])
+    key_rec_bytes = key_blocks * n * (bits * D // 8 + 2) + int(ranks[:key_blocks].sum().item()) * (n + D) * 2
+    score_bytes = key_rec_bytes + scores.numel() * 4
+    out = {
+        "metric": "KV compress GB/s (fp16 in) at d=128, 2-bit; dequant GB/s; % of roofline",
+        "value": in_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": f"{spec.name}: {B} blocks of {n}x{D} fp16, b={bits}, whole path per step "
+                               f"(compress + decompress + scores of {n_seq}x{n_kv * group} queries on "
+                               f"{key_blocks} key blocks)",
+                   "blocks": B, "n": n, "d": D, "bits": bits, "input_bytes": in_bytes},
+        "stages": {
+            "compress_GBps_fp16_in": in_bytes / ((stage["spectral"] + stage["encode"]) * 1e-3) / 1e9,
+            "spectral_ms": stage["spectral"], "encode_ms": stage["encode"],
+            "encode_GBps_moved": (in_bytes + rec_bytes) / (stage["encode"] * 1e-3) / 1e9,
+            "dequant_ms": stage["decode"],
+            "dequant_GBps_out": in_bytes / (stage["decode"] * 1e-3) / 1e9,
+            "dequant_GBps_moved": (in_bytes + rec_bytes) / (stage["decode"] * 1e-3) / 1e9,
+            "dequant_frac_hbm": (in_bytes + rec_bytes) / (stage["decode"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "scores_ms": stage["scores"],
+            "scores_GBps_moved": score_bytes / (stage["scores"] * 1e-3) / 1e9,
+            "scores_frac_hbm": score_bytes / (stage["scores"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "mean_rank": ranks.mean().item(), "mean_jacobi_sweeps": sweeps,
+            "record_bytes": rec_bytes,
+        },
+        "roofline": {"kernel": "eoq_spectral_kernel", "bound": "alu", "achieved": achieved_tflops,
+                     "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS,
+                     "traffic": traffic},
+    }
+    if args.cpu_blocks > 0:
+        blocks_cpu = blocks[:args.cpu_blocks].cpu()
+        q_cpu = q[0, :group].cpu()
+        log("timing the CPU oracle")
+        out["cpu_baseline"] = cpu_baseline(blocks_cpu, bits, ctx.rot_seed, q_cpu, args.cpu_blocks)
+        log("CPU oracle done")
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -42,6 +42,7 @@ typedef enum { EOQ_F16 = 0, EOQ_F32 = 1 } eoq_dtype;
 #define EOQ_FLAG_RANK_CLAMPED 1u /* estimated rank exceeded r_max and was cut to r_max */
 #define EOQ_FLAG_SHRINK_GUARD 2u /* a D-transform estimate was degenerate; that component got phi = 0 */
 #define EOQ_FLAG_NO_CONVERGE  4u /* the eigensolver hit its sweep limit */
+#define EOQ_FLAG_SWEEPS_SHIFT 8  /* bits 8..15: number of Jacobi sweeps the eigensolver ran (diagnostic) */
 
 /*
  * The compressed record of a batch (Alg. 3, "Store": shrunken SVD factors of
@@ -140,6 +141,17 @@ eoq_status eoq_decompress(eoq_ctx* ctx, eoq_packed in, int64_t B, void* out_fp16
 eoq_status eoq_scores(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_heads,
                       int64_t blocks_per_head, const void* q_fp16, int n_q_heads,
                       float* scores, void* hip_stream);
+
+/*
+ * Per-kernel timing for benchmarks (not part of the paper's method).  With profiling enabled every
+ * hot call records HIP events on its stream around each kernel it launches; eoq_stage_ms waits for
+ * those events and returns the duration, in milliseconds, of the kernels of the most recent
+ * eoq_compress (out[0] spectral, out[1] encode), eoq_decompress (out[2]) and eoq_scores (out[3]);
+ * a stage that has not run since profiling was enabled reports -1.  `out` is HOST memory, 4 floats.
+ * Events are created by eoq_profile, never inside a hot call.
+ */
+eoq_status eoq_profile(eoq_ctx* ctx, int enable);
+eoq_status eoq_stage_ms(eoq_ctx* ctx, float* out);
 
 /* Reason for the last error on this context (HOST string owned by the context); "" if none. */
 const char* eoq_last_error(const eoq_ctx* ctx);

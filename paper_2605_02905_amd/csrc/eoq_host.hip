@@ -137,6 +137,7 @@ EoqLaunch make_launch(const eoq_ctx* ctx, void* stream) {
   L.pit = ctx->d_pit;
   L.tab = ctx->d_tab;
   L.stream = static_cast<hipStream_t>(stream);
+  L.ev = ctx->profile ? ctx->ev : nullptr;
   return L;
 }
 
@@ -217,6 +218,8 @@ void eoq_destroy(eoq_ctx* ctx) {
   if (ctx->d_pi) (void)hipFree(ctx->d_pi);
   if (ctx->d_pit) (void)hipFree(ctx->d_pit);
   if (ctx->d_tab) (void)hipFree(ctx->d_tab);
+  if (ctx->profile)
+    for (hipEvent_t& e : ctx->ev) (void)hipEventDestroy(e);
   delete ctx;
 }
 
@@ -257,6 +260,7 @@ eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64
   float* wfac = reinterpret_cast<float*>(static_cast<char*>(workspace) + eoq_ws_lam_bytes(B));
   hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, out);
   if (e == hipSuccess) e = eoq_launch_encode(L, blocks, (int)dtype, B, wfac, out);
+  if (ctx->profile) ctx->ev_valid[0] = ctx->ev_valid[1] = (e == hipSuccess);
   if (e != hipSuccess) {
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);
     return EOQ_ERR_HIP;
@@ -275,6 +279,7 @@ eoq_status eoq_decompress(eoq_ctx* ctx, eoq_packed in, int64_t B, void* out_fp16
   if (B > (int64_t)1 << 24) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
   const EoqLaunch L = make_launch(ctx, hip_stream);
   hipError_t e = eoq_launch_decode(L, in, B, out_fp16);
+  if (ctx->profile) ctx->ev_valid[2] = (e == hipSuccess);
   if (e != hipSuccess) {
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);
     return EOQ_ERR_HIP;
@@ -299,9 +304,47 @@ eoq_status eoq_scores(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_hea
     return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
   const EoqLaunch L = make_launch(ctx, hip_stream);
   hipError_t e = eoq_launch_scores(L, keys, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores);
+  if (ctx->profile) ctx->ev_valid[3] = (e == hipSuccess);
   if (e != hipSuccess) {
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);
     return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+eoq_status eoq_profile(eoq_ctx* ctx, int enable) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (enable && !ctx->profile) {
+    for (int i = 0; i < 8; ++i) {
+      if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
+        for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->ev[j]);
+        return fail(ctx, EOQ_ERR_HIP, "hipEventCreate failed");
+      }
+    }
+    ctx->profile = true;
+  } else if (!enable && ctx->profile) {
+    for (hipEvent_t& e : ctx->ev) (void)hipEventDestroy(e);
+    ctx->profile = false;
+  }
+  for (bool& v : ctx->ev_valid) v = false;
+  return EOQ_OK;
+}
+
+eoq_status eoq_stage_ms(eoq_ctx* ctx, float* out) {
+  if (!ctx || !out) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (!ctx->profile) return fail(ctx, EOQ_ERR_ARG, "profiling is not enabled");
+  for (int i = 0; i < 4; ++i) {
+    out[i] = -1.0f;
+    if (!ctx->ev_valid[i]) continue;
+    hipError_t e = hipEventSynchronize(ctx->ev[2 * i + 1]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&out[i], ctx->ev[2 * i], ctx->ev[2 * i + 1]);
+    if (e != hipSuccess) {
+      ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+      return EOQ_ERR_HIP;
+    }
   }
   return EOQ_OK;
 }

@@ -26,6 +26,10 @@ struct eoq_ctx {
   float* d_pit = nullptr;        // device Pi^T [j][c]
   float* d_tab = nullptr;        // device: 16 centroids then 16 bounds (padded)
   std::string err;
+  // optional per-kernel timing: events [2*i], [2*i+1] bracket stage i (spectral, encode, decode, scores)
+  bool profile = false;
+  hipEvent_t ev[8] = {};
+  bool ev_valid[4] = {false, false, false, false};
 };
 
 // Device-side view of everything a launch needs.
@@ -36,6 +40,7 @@ struct EoqLaunch {
   const float* pit;
   const float* tab;
   hipStream_t stream;
+  const hipEvent_t* ev;  // null unless profiling
 };
 
 // Workspace layout for B blocks: lam[B][128] f64, then wfac[B][r_max][128] f32

@@ -306,7 +306,7 @@ __global__ __launch_bounds__(SPEC_THREADS) void eoq_spectral_kernel(
   }
   if (tid == 0) {
     rank_out[blk] = r;
-    flags_out[blk] = flag_s;
+    flags_out[blk] = flag_s | ((unsigned)sweeps << EOQ_FLAG_SWEEPS_SHIFT);
   }
 }
 
@@ -615,14 +615,17 @@ __global__ __launch_bounds__(SC_THREADS) void eoq_scores_kernel(
 // ---------------------------------------------------------------------------
 hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, double* lam,
                                float* wfac, eoq_packed out) {
+  if (L.ev) (void)hipEventRecord(L.ev[0], L.stream);
   hipLaunchKernelGGL(eoq_spectral_kernel, dim3((unsigned)B), dim3(SPEC_THREADS), 0, L.stream, blocks, dtype, L.n, L.k,
                      L.rank_thr, L.r_max, lam, wfac, out.rank, out.phi, out.sigma, out.rfac, out.flags);
+  if (L.ev) (void)hipEventRecord(L.ev[1], L.stream);
   return hipGetLastError();
 }
 
 hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, const float* wfac,
                              eoq_packed out) {
   // gridDim.y is limited to 65535: split long batches
+  if (L.ev) (void)hipEventRecord(L.ev[2], L.stream);
   for (int64_t b0 = 0; b0 < B; b0 += 32768) {
     const int64_t nb = (B - b0 < 32768) ? B - b0 : 32768;
     const size_t esz = (dtype == EOQ_F16) ? 2 : 4;
@@ -634,10 +637,12 @@ hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
+  if (L.ev) (void)hipEventRecord(L.ev[3], L.stream);
   return hipSuccess;
 }
 
 hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void* out_fp16) {
+  if (L.ev) (void)hipEventRecord(L.ev[4], L.stream);
   for (int64_t b0 = 0; b0 < B; b0 += 32768) {
     const int64_t nb = (B - b0 < 32768) ? B - b0 : 32768;
     hipLaunchKernelGGL(eoq_decode_kernel, dim3(L.n / ENC_ROWS, (unsigned)nb), dim3(ENC_THREADS), 0, L.stream, L.n,
@@ -647,6 +652,7 @@ hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void*
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
+  if (L.ev) (void)hipEventRecord(L.ev[5], L.stream);
   return hipSuccess;
 }
 
@@ -655,9 +661,11 @@ hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq,
   const int64_t chunks = (blocks_per_head + SC_CHUNK - 1) / SC_CHUNK;
   const int64_t sg_total = n_seq * n_kv_heads;
   if (sg_total > 65535 || chunks > 0x7FFFFFFF) return hipErrorInvalidValue;
+  if (L.ev) (void)hipEventRecord(L.ev[6], L.stream);
   hipLaunchKernelGGL(eoq_scores_kernel, dim3((unsigned)chunks, (unsigned)sg_total), dim3(SC_THREADS), 0, L.stream,
                      L.n, L.bits, L.r_max, n_kv_heads, n_q_heads / n_kv_heads, blocks_per_head, L.pit, L.tab,
                      keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, static_cast<const uint16_t*>(q_fp16),
                      scores);
+  if (L.ev) (void)hipEventRecord(L.ev[7], L.stream);
   return hipGetLastError();
 }

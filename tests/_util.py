@@ -25,6 +25,8 @@ def oracle_tables(bits: int, d: int = 128, seed: int = ROT_SEED):
 
 def _init_worker():
     # one BLAS thread per worker: the pool is the parallelism
+    for var in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
+        os.environ[var] = "1"
     try:
         from threadpoolctl import threadpool_limits
         threadpool_limits(1)
@@ -89,6 +91,7 @@ def compare_compress(blocks64: np.ndarray, rec, lam_gpu: np.ndarray, recs, bits:
     flags = rec.flags.cpu().numpy()
     flags_o = np.array([r.flags for r in recs])
     assert np.array_equal(flags & 3, flags_o & 3)
+    stats_sweeps = (flags >> 8) & 0xFF
     assert not np.any(flags & 4), "eigensolver hit its sweep limit"
     phi_g = rec.phi.cpu().numpy().astype(np.float64)
     sig_g = rec.sigma.cpu().numpy().astype(np.float64)
@@ -97,7 +100,7 @@ def compare_compress(blocks64: np.ndarray, rec, lam_gpu: np.ndarray, recs, bits:
     lfac_g = rec.lfac.cpu().numpy().astype(np.float64)
     rfac_g = rec.rfac.cpu().numpy().astype(np.float64)
     stats = dict(max_phi_rel=0.0, max_sigma_rel=0.0, max_lam_rel=0.0, mismatches=0, entries=0, max_lowrank_abs=0.0,
-                 norm_ulp_diffs=0)
+                 norm_ulp_diffs=0, max_sweeps=int(stats_sweeps.max()), mean_sweeps=float(stats_sweeps.mean()))
     for b, r in enumerate(recs):
         lam_o = r.lam
         stats["max_lam_rel"] = max(stats["max_lam_rel"], float(np.max(np.abs(lam_gpu[b] - lam_o)) / lam_o[0]) if lam_o[0] > 0 else 0.0)
