@@ -41,8 +41,8 @@ typedef enum { EOQ_F16 = 0, EOQ_F32 = 1 } eoq_dtype;
 /* Flag bits of eoq_packed.flags[b]. */
 #define EOQ_FLAG_RANK_CLAMPED 1u /* estimated rank exceeded r_max and was cut to r_max */
 #define EOQ_FLAG_SHRINK_GUARD 2u /* a D-transform estimate was degenerate; that component got phi = 0 */
-#define EOQ_FLAG_NO_CONVERGE  4u /* the eigensolver hit its sweep limit */
-#define EOQ_FLAG_SWEEPS_SHIFT 8  /* bits 8..15: number of Jacobi sweeps the eigensolver ran (diagnostic) */
+#define EOQ_FLAG_NO_CONVERGE  4u /* the eigensolver hit its sweep limit or produced a non-finite vector */
+#define EOQ_FLAG_SWEEPS_SHIFT 8  /* bits 8..15: Jacobi sweeps run on this block (0: tridiagonal solver) (diagnostic) */
 
 /*
  * The compressed record of a batch (Alg. 3, "Store": shrunken SVD factors of
@@ -141,6 +141,14 @@ eoq_status eoq_decompress(eoq_ctx* ctx, eoq_packed in, int64_t B, void* out_fp16
 eoq_status eoq_scores(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_heads,
                       int64_t blocks_per_head, const void* q_fp16, int n_q_heads,
                       float* scores, void* hip_stream);
+
+/*
+ * Eigensolver used by eoq_compress for the d x d Gram matrix (the paper only asks for the SVD of the
+ * block, Alg. 2 REQUIRE).  0 (default): Householder tridiagonalisation + Sturm multisection + twisted
+ * factorisation, with blocks whose retained eigenvalues are numerically repeated handed to the Jacobi
+ * solver; 1: LDS-resident one-sided Jacobi for every block.  Both give the same record up to rounding.
+ */
+eoq_status eoq_set_solver(eoq_ctx* ctx, int solver);
 
 /*
  * Per-kernel timing for benchmarks (not part of the paper's method).  With profiling enabled every

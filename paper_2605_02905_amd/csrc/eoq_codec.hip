@@ -1,314 +1,16 @@
-// HIP kernels (gfx950) of the eOptShrinkQ block-compression path.
-//
-//   spectral : per block, Gram matrix G = S^T S, one-sided Jacobi eigensolve of G
-//              resident in LDS, bulk edge + rank (Alg. 2 Step 1), imputed noise
-//              spectrum (Step 2), D-transform shrinker (Step 3), right singular
-//              vectors of the retained components.
-//   encode   : projection C = S V diag(phi/sigma) = U diag(phi), residual against
-//              the stored binary16 factors (Alg. 3), then per row norm, rotation,
-//              Lloyd-Max index and bit-plane packing (Alg. 1 lines 3-5).
-//   decode   : Alg. 1 line 6 plus the stored low-rank part.
-//   scores   : <q, x_hat>/sqrt(d) from the record without forming x_hat (Remark 6.5).
+// HIP kernels (gfx950) of the residual coder of eOptShrinkQ and its inverse:
+//   encode : projection C = S V diag(phi/sigma) = U diag(phi), residual against the stored binary16 factors
+//            (Alg. 3), then per row norm, rotation, Lloyd-Max index and bit-plane packing (Alg. 1 lines 3-5).
+//   decode : Alg. 1 line 6 plus the stored low-rank part.
+//   scores : <q, x_hat>/sqrt(d) from the record without forming x_hat (Remark 6.5).
+#include "eoq_device.h"
 #include "eoq_internal.h"
 
 namespace {
 
+using namespace eoqdev;
+
 constexpr int D = EOQ_D;
-constexpr int LDA = D + 1;  // padded column stride of the LDS-resident matrix
-
-typedef _Float16 half_t;
-
-// ---------------------------------------------------------------------------
-// small device helpers
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ double quad_xchg(double v, int which) {
-  // exchange within groups of 4 lanes: which = 1 -> lane^1, which = 2 -> lane^2
-  int lo = __double2loint(v), hi = __double2hiint(v);
-  if (which == 1) {
-    lo = __builtin_amdgcn_mov_dpp(lo, 0xB1, 0xF, 0xF, true);
-    hi = __builtin_amdgcn_mov_dpp(hi, 0xB1, 0xF, 0xF, true);
-  } else {
-    lo = __builtin_amdgcn_mov_dpp(lo, 0x4E, 0xF, 0xF, true);
-    hi = __builtin_amdgcn_mov_dpp(hi, 0x4E, 0xF, 0xF, true);
-  }
-  return __hiloint2double(hi, lo);
-}
-__device__ __forceinline__ double quad_sum(double v) {
-  v += quad_xchg(v, 1);
-  v += quad_xchg(v, 2);
-  return v;
-}
-__device__ __forceinline__ float quad_sum(float v) {
-  v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));
-  v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x4E, 0xF, 0xF, true));
-  return v;
-}
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-  return v;
-}
-
-// double -> binary16 with a single rounding (round-to-odd into binary32 first)
-__device__ __forceinline__ uint16_t double_to_half_bits(double x) {
-  float f = __double2float_rz(x);
-  if ((double)f != x) f = __int_as_float(__float_as_int(f) | 1);
-  half_t h = (half_t)f;
-  return *reinterpret_cast<uint16_t*>(&h);
-}
-__device__ __forceinline__ uint16_t float_to_half_bits(float f) {
-  f = fminf(fmaxf(f, -65504.0f), 65504.0f);
-  half_t h = (half_t)f;
-  return *reinterpret_cast<uint16_t*>(&h);
-}
-__device__ __forceinline__ float half_bits_to_float(uint16_t b) {
-  half_t h = *reinterpret_cast<half_t*>(&b);
-  return (float)h;
-}
-
-// Load 8 consecutive elements of a block row as floats.
-__device__ __forceinline__ void load8(const void* base, int dtype, size_t elem, float (&v)[8]) {
-  if (dtype == EOQ_F16) {
-    const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem);
-    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      v[2 * i] = half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
-      v[2 * i + 1] = half_bits_to_float((uint16_t)(w[i] >> 16));
-    }
-  } else {
-    const float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem);
-    const float4 b = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem + 4);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-  }
-}
-
-// ---------------------------------------------------------------------------
-// spectral kernel: one workgroup of 256 lanes per block, everything in double.
-// ---------------------------------------------------------------------------
-constexpr int SPEC_THREADS = 256;
-constexpr int STAGE_ROWS = 32;
-constexpr int MAX_SWEEPS = 30;
-constexpr double JACOBI_TOL = 5e-14;  // a pair is orthogonal when |<a_p,a_q>| <= tol |a_p||a_q|
-
-__global__ __launch_bounds__(SPEC_THREADS) void eoq_spectral_kernel(
-    const void* __restrict__ blocks, int dtype, int n, int k, double rank_thr, int r_max, double* __restrict__ lam_out,
-    float* __restrict__ wfac, int32_t* __restrict__ rank_out, float* __restrict__ phi_out,
-    float* __restrict__ sigma_out, uint16_t* __restrict__ rfac, uint32_t* __restrict__ flags_out) {
-  __shared__ double A[D * LDA];                 // column s of the working matrix at A[s*LDA ...]
-  __shared__ float stage[STAGE_ROWS * D];       // a strip of the block, as float
-  __shared__ double lam_s[D];                   // eigenvalues in descending order
-  __shared__ double atoms[D];                   // estimated noise eigenvalues
-  __shared__ double colnorm[D];                 // |a_s| per slot
-  __shared__ int slot_of[D];                    // slot holding the i-th largest eigenvalue
-  __shared__ double scale_s[EOQ_RMAX_CAP];      // phi_i / sigma_i
-  __shared__ unsigned flag_s;
-
-  const int tid = threadIdx.x;
-  const size_t blk = blockIdx.x;
-  const size_t base_elem = blk * (size_t)n * D;
-  if (tid == 0) flag_s = 0u;
-
-  // ---- Gram matrix G = S^T S (Sec. 2.3: lambda_i = sigma_i^2 are its eigenvalues) ----
-  {
-    const int ty = tid >> 4, tx = tid & 15;
-    double acc[8][8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) acc[i][j] = 0.0;
-    for (int t0 = 0; t0 < n; t0 += STAGE_ROWS) {
-      __syncthreads();
-      // 32 rows x 128 = 4096 elements, 16 per lane as two groups of 8
-#pragma unroll
-      for (int g = 0; g < 2; ++g) {
-        const int e = (g * SPEC_THREADS + tid) * 8;  // element within the strip
-        float v[8];
-        load8(blocks, dtype, base_elem + (size_t)t0 * D + e, v);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) stage[e + i] = v[i];
-      }
-      __syncthreads();
-      for (int t = 0; t < STAGE_ROWS; ++t) {
-        double a[8], b[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          a[i] = (double)stage[t * D + ty * 8 + i];
-          b[i] = (double)stage[t * D + tx * 8 + i];
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) A[(tx * 8 + j) * LDA + ty * 8 + i] = acc[i][j];
-  }
-  __syncthreads();
-
-  // ---- one-sided Jacobi on the columns of A = G: A V -> V Lambda ----
-  // 64 pairs per step, one per group of 4 lanes; pair p works on slots 2p, 2p+1 and
-  // writes its rotated columns to the slots the round-robin schedule pairs next.
-  const int pr = tid >> 2, ql = tid & 3;
-  const int m_pairs = D / 2;
-  const int dst_top = (pr == 0) ? 0 : (pr == m_pairs - 1 ? 2 * (m_pairs - 1) + 1 : 2 * (pr + 1));
-  const int dst_bot = (pr == 0) ? 2 : 2 * (pr - 1) + 1;
-  int sweeps = 0;
-  bool converged = false;
-  for (; sweeps < MAX_SWEEPS && !converged; ++sweeps) {
-    int sweep_rot = 0;
-    for (int step = 0; step < D - 1; ++step) {
-      double xp[D / 4], xq[D / 4];
-      double alpha = 0.0, beta = 0.0, gamma = 0.0;
-#pragma unroll
-      for (int m = 0; m < D / 4; ++m) {
-        xp[m] = A[(2 * pr) * LDA + ql + 4 * m];
-        xq[m] = A[(2 * pr + 1) * LDA + ql + 4 * m];
-        alpha = fma(xp[m], xp[m], alpha);
-        beta = fma(xq[m], xq[m], beta);
-        gamma = fma(xp[m], xq[m], gamma);
-      }
-      alpha = quad_sum(alpha);
-      beta = quad_sum(beta);
-      gamma = quad_sum(gamma);
-      const bool rot = fabs(gamma) > JACOBI_TOL * sqrt(alpha * beta);
-      double c = 1.0, s = 0.0;
-      if (rot) {
-        const double zeta = (beta - alpha) / (2.0 * gamma);
-        const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-        c = 1.0 / sqrt(1.0 + t * t);
-        s = c * t;
-      }
-      __syncthreads();  // every lane holds its operands; slots may now be overwritten
-#pragma unroll
-      for (int m = 0; m < D / 4; ++m) {
-        A[dst_top * LDA + ql + 4 * m] = c * xp[m] - s * xq[m];
-        A[dst_bot * LDA + ql + 4 * m] = s * xp[m] + c * xq[m];
-      }
-      sweep_rot |= __syncthreads_or(rot ? 1 : 0);
-    }
-    converged = (sweep_rot == 0);
-  }
-  if (!converged && tid == 0) flag_s |= EOQ_FLAG_NO_CONVERGE;
-
-  // ---- eigenvalues = column norms; order them ----
-  {
-    double alpha = 0.0;
-#pragma unroll
-    for (int m = 0; m < D / 4; ++m) {
-      const double x = A[(tid >> 1) * LDA + (tid & 1) * 64 + m * 2 + 0];
-      const double y = A[(tid >> 1) * LDA + (tid & 1) * 64 + m * 2 + 1];
-      alpha = fma(x, x, alpha);
-      alpha = fma(y, y, alpha);
-    }
-    alpha += __shfl_xor(alpha, 1, 64);
-    if ((tid & 1) == 0) colnorm[tid >> 1] = sqrt(alpha);
-  }
-  __syncthreads();
-  if (tid < D) {
-    const double mine = colnorm[tid];
-    int pos = 0;
-    for (int t = 0; t < D; ++t) {
-      const double o = colnorm[t];
-      pos += (o > mine || (o == mine && t < tid)) ? 1 : 0;
-    }
-    lam_s[pos] = mine;
-    slot_of[pos] = tid;
-  }
-  __syncthreads();
-  if (tid < D) lam_out[blk * D + tid] = lam_s[tid];
-
-  // ---- Alg. 2 Step 1: bulk edge and rank ----
-  const double edge_coef = 1.0 / (cbrt(4.0) - 1.0);  // 1 / (2^{2/3} - 1)
-  const double lam_k1 = lam_s[k], lam_2k1 = lam_s[2 * k];
-  const double lam_plus = lam_k1 + edge_coef * (lam_k1 - lam_2k1);
-  const int above = (tid < D) ? ((lam_s[tid] / lam_plus - 1.0 > rank_thr) ? 1 : 0) : 0;
-  int r = __syncthreads_count(above);
-  if (r > r_max) {
-    r = r_max;
-    if (tid == 0) flag_s |= EOQ_FLAG_RANK_CLAMPED;
-  }
-
-  // ---- Alg. 2 Step 2: noise atoms (r outliers dropped, next k imputed) ----
-  const int M = D - r;
-  if (tid < M) {
-    double v;
-    if (tid < k) {
-      const double a = lam_s[k + r], b = lam_s[2 * k + r];
-      const double j = (double)(tid + 1);
-      v = a + (1.0 - pow(j / (double)k, 2.0 / 3.0)) * edge_coef * (a - b);
-    } else {
-      v = lam_s[r + tid];
-    }
-    atoms[tid] = v;
-  }
-  __syncthreads();
-
-  // ---- Alg. 2 Step 3: D-transform shrinker, one wave per outlier ----
-  {
-    const int wave = tid >> 6, lane = tid & 63;
-    const double beta = (n >= D) ? (double)D / (double)n : (double)n / (double)D;
-    for (int i = wave; i < r; i += SPEC_THREADS / 64) {
-      const double z = lam_s[i];
-      double s1 = 0.0, s2 = 0.0;
-      for (int j = lane; j < M; j += 64) {
-        const double inv = 1.0 / (atoms[j] - z);
-        s1 += inv;
-        s2 = fma(inv, inv, s2);
-      }
-      s1 = wave_sum(s1);
-      s2 = wave_sum(s2);
-      if (lane == 0) {
-        const double m_s = s1 / (double)M, dm_s = s2 / (double)M;
-        const double m_l = beta * m_s - (1.0 - beta) / z;
-        const double dm_l = beta * dm_s + (1.0 - beta) / (z * z);
-        const double T = z * m_s * m_l;
-        const double dT = m_s * m_l + z * dm_s * m_l + z * m_s * dm_l;
-        const double sig = sqrt(z);
-        double phi = 0.0;
-        bool ok = isfinite(T) && isfinite(dT) && T > 0.0 && dT < 0.0;
-        if (ok) {
-          // phi = d sqrt(a_1 a_2) with d = T^{-1/2}, a_x = m_x / (d^2 T')
-          const double dh = 1.0 / sqrt(T);
-          const double a1 = m_l / (dh * dh * dT), a2 = m_s / (dh * dh * dT);
-          phi = dh * sqrt(a1 * a2);
-          ok = isfinite(phi);
-          if (ok) phi = fmin(fmax(phi, 0.0), sig);
-        }
-        if (!ok) {
-          phi = 0.0;
-          atomicOr(&flag_s, EOQ_FLAG_SHRINK_GUARD);
-        }
-        phi_out[blk * r_max + i] = (float)phi;
-        sigma_out[blk * r_max + i] = (float)sig;
-        scale_s[i] = (sig > 0.0) ? phi / sig : 0.0;
-      }
-    }
-    // unused tail of the per-block tables
-    for (int i = r + tid; i < r_max; i += SPEC_THREADS) {
-      phi_out[blk * r_max + i] = 0.0f;
-      sigma_out[blk * r_max + i] = 0.0f;
-    }
-  }
-  __syncthreads();
-
-  // ---- right singular vectors v_i = a_slot / lambda_i of the retained components ----
-  for (int e = tid; e < r * D; e += SPEC_THREADS) {
-    const int i = e >> 7, j = e & (D - 1);
-    const double li = lam_s[i];
-    const double v = (li > 0.0) ? A[slot_of[i] * LDA + j] / li : 0.0;
-    rfac[(blk * r_max + i) * D + j] = double_to_half_bits(v);
-    wfac[(blk * r_max + i) * D + j] = (float)(v * scale_s[i]);
-  }
-  if (tid == 0) {
-    rank_out[blk] = r;
-    flags_out[blk] = flag_s | ((unsigned)sweeps << EOQ_FLAG_SWEEPS_SHIFT);
-  }
-}
 
 // ---------------------------------------------------------------------------
 // encode kernel: 64 rows of one block per workgroup.
@@ -613,15 +315,6 @@ __global__ __launch_bounds__(SC_THREADS) void eoq_scores_kernel(
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
-hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, double* lam,
-                               float* wfac, eoq_packed out) {
-  if (L.ev) (void)hipEventRecord(L.ev[0], L.stream);
-  hipLaunchKernelGGL(eoq_spectral_kernel, dim3((unsigned)B), dim3(SPEC_THREADS), 0, L.stream, blocks, dtype, L.n, L.k,
-                     L.rank_thr, L.r_max, lam, wfac, out.rank, out.phi, out.sigma, out.rfac, out.flags);
-  if (L.ev) (void)hipEventRecord(L.ev[1], L.stream);
-  return hipGetLastError();
-}
-
 hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, const float* wfac,
                              eoq_packed out) {
   // gridDim.y is limited to 65535: split long batches

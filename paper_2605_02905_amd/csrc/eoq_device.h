@@ -1,0 +1,100 @@
+// Device-side helpers shared by the kernels of the eOptShrinkQ library (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "eoq.h"
+
+namespace eoqdev {
+
+typedef _Float16 half_t;
+
+// ---- cross-lane moves (DPP) -------------------------------------------------------------------
+// ctrl: 0xB1 = lane^1 and 0x4E = lane^2 inside groups of 4; 0x120+n = rotate by n inside rows of 16.
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov(double v) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_mov_dpp(lo, CTRL, 0xF, 0xF, true);
+  hi = __builtin_amdgcn_mov_dpp(hi, CTRL, 0xF, 0xF, true);
+  return __hiloint2double(hi, lo);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int v) {
+  return __builtin_amdgcn_mov_dpp(v, CTRL, 0xF, 0xF, true);
+}
+
+// sum over the 2 / 4 lanes of an aligned group; every lane of the group gets the total
+template <typename T>
+__device__ __forceinline__ T pair_sum(T v) { return v + dpp_mov<0xB1>(v); }
+template <typename T>
+__device__ __forceinline__ T quad_sum(T v) {
+  v += dpp_mov<0xB1>(v);
+  v += dpp_mov<0x4E>(v);
+  return v;
+}
+// sum over a row of 16 lanes; every lane of the row gets a total (association may differ by lane)
+__device__ __forceinline__ double row16_sum(double v) {
+  v += dpp_mov<0xB1>(v);
+  v += dpp_mov<0x4E>(v);
+  v += dpp_mov<0x124>(v);
+  v += dpp_mov<0x128>(v);
+  return v;
+}
+__device__ __forceinline__ double readlane_f64(double v, int lane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+  return __hiloint2double(hi, lo);
+}
+// sum over the 64 lanes of the wave; bit-identical in every lane
+__device__ __forceinline__ double wave_sum_uniform(double v) {
+  v = row16_sum(v);
+  return (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
+}
+__device__ __forceinline__ double wave_sum_shfl(double v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+// ---- number formats ---------------------------------------------------------------------------
+// double -> binary16 with a single rounding (round-to-odd into binary32 first)
+__device__ __forceinline__ uint16_t double_to_half_bits(double x) {
+  float f = __double2float_rz(x);
+  if ((double)f != x) f = __int_as_float(__float_as_int(f) | 1);
+  half_t h = (half_t)f;
+  return *reinterpret_cast<uint16_t*>(&h);
+}
+__device__ __forceinline__ uint16_t float_to_half_bits(float f) {
+  f = fminf(fmaxf(f, -65504.0f), 65504.0f);
+  half_t h = (half_t)f;
+  return *reinterpret_cast<uint16_t*>(&h);
+}
+__device__ __forceinline__ float half_bits_to_float(uint16_t b) {
+  half_t h = *reinterpret_cast<half_t*>(&b);
+  return (float)h;
+}
+
+// Load 8 consecutive elements of a block (binary16 or float32) as floats.
+__device__ __forceinline__ void load8(const void* base, int dtype, size_t elem, float (&v)[8]) {
+  if (dtype == EOQ_F16) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem);
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
+      v[2 * i + 1] = half_bits_to_float((uint16_t)(w[i] >> 16));
+    }
+  } else {
+    const float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem);
+    const float4 b = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+}
+
+}  // namespace eoqdev

@@ -138,6 +138,7 @@ EoqLaunch make_launch(const eoq_ctx* ctx, void* stream) {
   L.tab = ctx->d_tab;
   L.stream = static_cast<hipStream_t>(stream);
   L.ev = ctx->profile ? ctx->ev : nullptr;
+  L.solver = ctx->solver;
   return L;
 }
 
@@ -225,7 +226,7 @@ void eoq_destroy(eoq_ctx* ctx) {
 
 size_t eoq_workspace_bytes(const eoq_ctx* ctx, int64_t B) {
   if (!ctx || B < 0) return 0;
-  return eoq_ws_lam_bytes(B) + eoq_ws_wfac_bytes(B, ctx->r_max);
+  return eoq_ws_lam_bytes(B) + eoq_ws_wfac_bytes(B, ctx->r_max) + eoq_ws_list_bytes(B);
 }
 
 eoq_status eoq_rotation(const eoq_ctx* ctx, float* host_out) {
@@ -257,8 +258,11 @@ eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64
 
   const EoqLaunch L = make_launch(ctx, hip_stream);
   double* lam = static_cast<double*>(workspace);
-  float* wfac = reinterpret_cast<float*>(static_cast<char*>(workspace) + eoq_ws_lam_bytes(B));
-  hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, out);
+  char* ws = static_cast<char*>(workspace);
+  float* wfac = reinterpret_cast<float*>(ws + eoq_ws_lam_bytes(B));
+  int* fb_count = reinterpret_cast<int*>(ws + eoq_ws_lam_bytes(B) + eoq_ws_wfac_bytes(B, ctx->r_max));
+  int* fb_list = fb_count + 4;
+  hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, fb_count, fb_list, out);
   if (e == hipSuccess) e = eoq_launch_encode(L, blocks, (int)dtype, B, wfac, out);
   if (ctx->profile) ctx->ev_valid[0] = ctx->ev_valid[1] = (e == hipSuccess);
   if (e != hipSuccess) {
@@ -309,6 +313,14 @@ eoq_status eoq_scores(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_hea
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);
     return EOQ_ERR_HIP;
   }
+  return EOQ_OK;
+}
+
+eoq_status eoq_set_solver(eoq_ctx* ctx, int solver) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (solver != 0 && solver != 1) return fail(ctx, EOQ_ERR_UNSUPPORTED, "solver must be 0 or 1");
+  ctx->solver = solver;
   return EOQ_OK;
 }
 

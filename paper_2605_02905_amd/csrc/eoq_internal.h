@@ -26,6 +26,7 @@ struct eoq_ctx {
   float* d_pit = nullptr;        // device Pi^T [j][c]
   float* d_tab = nullptr;        // device: 16 centroids then 16 bounds (padded)
   std::string err;
+  int solver = 0;  // 0: tridiagonal eigensolver with Jacobi for repeated eigenvalues, 1: Jacobi for every block
   // optional per-kernel timing: events [2*i], [2*i+1] bracket stage i (spectral, encode, decode, scores)
   bool profile = false;
   hipEvent_t ev[8] = {};
@@ -41,15 +42,18 @@ struct EoqLaunch {
   const float* tab;
   hipStream_t stream;
   const hipEvent_t* ev;  // null unless profiling
+  int solver;
 };
 
-// Workspace layout for B blocks: lam[B][128] f64, then wfac[B][r_max][128] f32
-// (right singular vectors scaled by phi/sigma, the projection operand).
+// Workspace layout for B blocks: lam[B][128] f64, then wfac[B][r_max][128] f32 (right singular vectors
+// scaled by phi/sigma, the projection operand), then a counter (16 bytes) and a list of B block numbers
+// (the blocks handed from the tridiagonal eigensolver to the Jacobi one).
 inline size_t eoq_ws_lam_bytes(int64_t B) { return (size_t)B * EOQ_D * sizeof(double); }
 inline size_t eoq_ws_wfac_bytes(int64_t B, int r_max) { return (size_t)B * r_max * EOQ_D * sizeof(float); }
+inline size_t eoq_ws_list_bytes(int64_t B) { return 16 + (((size_t)B * sizeof(int) + 15) & ~(size_t)15); }
 
 hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, double* lam,
-                               float* wfac, eoq_packed out);
+                               float* wfac, int* fb_count, int* fb_list, eoq_packed out);
 hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, const float* wfac,
                              eoq_packed out);
 hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void* out_fp16);

@@ -18,7 +18,7 @@ EOQ_F16, EOQ_F32 = 0, 1
 FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE = 1, 2, 4
 
 EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_codebook",
-           "eoq_compress", "eoq_decompress", "eoq_scores", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
+           "eoq_compress", "eoq_decompress", "eoq_scores", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
 
 
 class EoqError(RuntimeError):
@@ -62,6 +62,8 @@ def lib():
         L.eoq_scores.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_int, C.c_int64, C.c_void_p, C.c_int,
                                  C.c_void_p, C.c_void_p]
         L.eoq_scores.restype = C.c_int
+        L.eoq_set_solver.argtypes = [C.c_void_p, C.c_int]
+        L.eoq_set_solver.restype = C.c_int
         L.eoq_profile.argtypes = [C.c_void_p, C.c_int]
         L.eoq_profile.restype = C.c_int
         L.eoq_stage_ms.argtypes = [C.c_void_p, C.c_void_p]
@@ -188,6 +190,9 @@ class Context:
         self._check(lib().eoq_scores(self._h, keys.c_struct(), n_seq, n_kv_heads, bph, q.data_ptr(), n_q_heads,
                                      out.data_ptr(), _stream_ptr(q.device)))
         return out
+
+    def eoq_set_solver(self, solver: int):
+        self._check(lib().eoq_set_solver(self._h, solver))
 
     def eoq_profile(self, enable: bool = True):
         self._check(lib().eoq_profile(self._h, 1 if enable else 0))

@@ -25,8 +25,9 @@ def _need_gpu():
         pytest.skip("no GPU")
 
 
-def _gpu_compress(blocks_t, bits, n, r_max=32):
+def _gpu_compress(blocks_t, bits, n, r_max=32, solver=0):
     ctx = eoq.Context(n=n, bits=bits, r_max=r_max)
+    ctx.eoq_set_solver(solver)
     rec, ws = ctx.eoq_compress(blocks_t.to(DEV).contiguous())
     torch.cuda.synchronize()
     lam = ctx.spectrum(ws, blocks_t.shape[0]).cpu().numpy()
@@ -89,16 +90,18 @@ def test_config1_single_block_fp32():
     assert worst <= 2e-2 * np.max(np.abs(so)), worst
 
 
-@pytest.mark.parametrize("bits", [2, 3])
-def test_config2_blocks_against_oracle(bits):
-    """Two head-tensors (128 blocks) of the Llama-shaped layer, every block checked."""
+@pytest.mark.parametrize("bits,solver", [(2, 0), (3, 0), (2, 1)])
+def test_config2_blocks_against_oracle(bits, solver):
+    """Two head-tensors (128 blocks) of the Llama-shaped layer, every block checked; both eigensolvers."""
     spec = synth.config(2)
     blocks, _ = synth.make_blocks(spec, tensors=range(2))
     b64 = blocks.double().numpy()
     recs = U.oracle_compress(b64, bits)
-    ctx, rec, lam = _gpu_compress(blocks, bits, spec.n)
+    ctx, rec, lam = _gpu_compress(blocks, bits, spec.n, solver=solver)
     st = U.compare_compress(b64, rec, lam, recs, bits)
-    U.log_stats(f"cfg2-2tensors-b{bits}", st)
+    U.log_stats(f"cfg2-2tensors-b{bits}-solver{solver}", st)
+    sweeps = (rec.flags.cpu().numpy() >> 8) & 0xFF
+    assert np.all(sweeps > 0) if solver == 1 else not np.any(sweeps)
     assert st["max_lam_rel"] < 1e-9
     _recon_agreement(ctx, rec, b64, recs, bits)
 
@@ -158,6 +161,37 @@ def test_degenerate_blocks():
     assert np.all(norms[2] == np.float16(65504.0))
     codes0 = oracle.unpack_codes(rec.codes[0].cpu().numpy(), 2, 128)
     assert np.all(codes0 == 2)
+
+
+def test_repeated_singular_values_go_to_the_jacobi_solver():
+    """Two exactly equal leading singular values: any orthonormal basis of their plane is a valid answer, so only
+    what is unique is compared (spectrum, rank, shrunk values, the low-rank product) and the record is checked
+    to reconstruct the block.  The tridiagonal solver hands such blocks to the Jacobi solver."""
+    S = torch.zeros(2, 512, 128)
+    S[0, :256, 0] = 100.0
+    S[0, 256:, 1] = 100.0
+    gen = torch.Generator().manual_seed(3)
+    S[1] = torch.randn(512, 128, generator=gen)           # an ordinary block next to it
+    S = S.to(torch.float16)
+    b64 = S.double().numpy()
+    with np.errstate(all="ignore"):
+        recs = U.oracle_compress(b64, 2, workers=1)
+    assert recs[0].rank == 2
+    ctx, rec, lam = _gpu_compress(S, 2, 512)
+    assert rec.rank.cpu().tolist() == [2, recs[1].rank]
+    flags = rec.flags.cpu().numpy()
+    assert (flags[0] >> 8) & 0xFF > 0 and (flags[1] >> 8) & 0xFF == 0     # Jacobi ran on block 0 only
+    assert np.allclose(lam[0], recs[0].lam, atol=1e-9 * recs[0].lam[0])
+    assert np.allclose(rec.phi[0, :2].cpu().numpy(), recs[0].phi, rtol=1e-6)
+    lo = rec.lfac[0, :2].double().cpu().numpy().T @ rec.rfac[0, :2].double().cpu().numpy()
+    assert np.max(np.abs(lo - b64[0])) < 0.2                               # binary16 factors of entries ~100
+    rf = rec.rfac[0, :2].double().cpu().numpy()
+    assert np.max(np.abs(rf @ rf.T - np.eye(2))) < 2e-3
+    x = ctx.eoq_decompress(rec)
+    torch.cuda.synchronize()
+    assert U.rel_fro(b64[0], x[0].double().cpu().numpy()) < 5e-3
+    U.compare_compress(b64[1:], eoq.Packed(*(t[1:] for t in (rec.codes, rec.norms, rec.rank, rec.phi, rec.sigma,
+                                                             rec.lfac, rec.rfac, rec.flags))), lam[1:], recs[1:], 2)
 
 
 def test_decompress_of_oracle_records_elementwise():
