@@ -1,7 +1,6 @@
 // HIP kernels (gfx950) of the residual coder of eOptShrinkQ and its inverse:
 //   encode : projection C = S V diag(phi/sigma) = U diag(phi), residual against the stored binary16 factors
 //            (Alg. 3), then per row norm, rotation, Lloyd-Max index and bit-plane packing (Alg. 1 lines 3-5).
-//   decode : Alg. 1 line 6 plus the stored low-rank part.
 //   scores : <q, x_hat>/sqrt(d) from the record without forming x_hat (Remark 6.5).
 #include "eoq_device.h"
 #include "eoq_internal.h"
@@ -149,84 +148,6 @@ __global__ __launch_bounds__(ENC_THREADS) void eoq_encode_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// decode kernel: 64 rows of one block per workgroup.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(ENC_THREADS) void eoq_decode_kernel(
-    int n, int bits, int r_max, const float* __restrict__ pi, const float* __restrict__ tab,
-    const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms, const int32_t* __restrict__ rank_in,
-    const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac, uint16_t* __restrict__ out) {
-  __shared__ float Z[ENC_ROWS * LDS_X];   // rho_t * centroid[code] / sqrt(d)
-  __shared__ float P[D * D];              // Pi[c][j]
-  __shared__ float Vl[EOQ_RMAX_CAP * D];
-  __shared__ float Cl[ENC_ROWS * (EOQ_RMAX_CAP + 1)];
-
-  const int tid = threadIdx.x;
-  const size_t blk = blockIdx.y;
-  const int row0 = blockIdx.x * ENC_ROWS;
-  const int r = rank_in[blk];
-
-  for (int e = tid; e < D * D / 4; e += ENC_THREADS)
-    reinterpret_cast<float4*>(P)[e] = reinterpret_cast<const float4*>(pi)[e];
-  for (int e = tid; e < r * D; e += ENC_THREADS) Vl[e] = half_bits_to_float(rfac[blk * r_max * D + e]);
-  for (int e = tid; e < r * ENC_ROWS; e += ENC_THREADS) {
-    const int i = e >> 6, t = e & 63;
-    Cl[t * (EOQ_RMAX_CAP + 1) + i] = half_bits_to_float(lfac[(blk * r_max + i) * (size_t)n + row0 + t]);
-  }
-  {
-    const int t = tid >> 2, q = tid & 3;
-    const float rho = half_bits_to_float(norms[blk * (size_t)n + row0 + t]);
-    const float sc = rho / sqrtf((float)D);
-    const uint32_t* src =
-        reinterpret_cast<const uint32_t*>(codes + (blk * (size_t)n + row0 + t) * (size_t)(bits * D / 8));
-    uint32_t plane[4] = {0u, 0u, 0u, 0u};
-    for (int p = 0; p < bits; ++p) plane[p] = src[p * 4 + q];
-    for (int j = 0; j < 32; ++j) {
-      int c = 0;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) c |= ((plane[p] >> j) & 1u) << p;
-      Z[t * LDS_X + q * 32 + j] = sc * tab[c];
-    }
-  }
-  __syncthreads();
-
-  const int tr = tid >> 5, tc = tid & 31;
-  float acc[8][4];
-#pragma unroll
-  for (int a = 0; a < 8; ++a)
-#pragma unroll
-    for (int m = 0; m < 4; ++m) acc[a][m] = 0.0f;
-  // rho Pi^T z_hat (Alg. 1 line 6), row form: sum_c z[c] Pi[c][j]
-  for (int c = 0; c < D; ++c) {
-    float p[4], z[8];
-#pragma unroll
-    for (int m = 0; m < 4; ++m) p[m] = P[c * D + tc + 32 * m];
-#pragma unroll
-    for (int a = 0; a < 8; ++a) z[a] = Z[(tr * 8 + a) * LDS_X + c];
-#pragma unroll
-    for (int a = 0; a < 8; ++a)
-#pragma unroll
-      for (int m = 0; m < 4; ++m) acc[a][m] = fmaf(z[a], p[m], acc[a][m]);
-  }
-  // plus the stored low-rank part (Alg. 2 Return)
-  for (int i = 0; i < r; ++i) {
-    float v[4];
-#pragma unroll
-    for (int m = 0; m < 4; ++m) v[m] = Vl[i * D + tc + 32 * m];
-#pragma unroll
-    for (int a = 0; a < 8; ++a) {
-      const float c = Cl[(tr * 8 + a) * (EOQ_RMAX_CAP + 1) + i];
-#pragma unroll
-      for (int m = 0; m < 4; ++m) acc[a][m] = fmaf(c, v[m], acc[a][m]);
-    }
-  }
-#pragma unroll
-  for (int a = 0; a < 8; ++a)
-#pragma unroll
-    for (int m = 0; m < 4; ++m)
-      out[(blk * (size_t)n + row0 + tr * 8 + a) * D + tc + 32 * m] = float_to_half_bits(acc[a][m]);
-}
-
-// ---------------------------------------------------------------------------
 // scores: one workgroup per (sequence, KV head, run of SC_CHUNK blocks).  The group's
 // queries are rotated once (q' = Pi q), then every token of the run is scored from
 // its codes, norm and low-rank coefficients.
@@ -331,21 +252,6 @@ hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, 
     if (e != hipSuccess) return e;
   }
   if (L.ev) (void)hipEventRecord(L.ev[3], L.stream);
-  return hipSuccess;
-}
-
-hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void* out_fp16) {
-  if (L.ev) (void)hipEventRecord(L.ev[4], L.stream);
-  for (int64_t b0 = 0; b0 < B; b0 += 32768) {
-    const int64_t nb = (B - b0 < 32768) ? B - b0 : 32768;
-    hipLaunchKernelGGL(eoq_decode_kernel, dim3(L.n / ENC_ROWS, (unsigned)nb), dim3(ENC_THREADS), 0, L.stream, L.n,
-                       L.bits, L.r_max, L.pi, L.tab, in.codes + (size_t)b0 * L.n * (L.bits * D / 8),
-                       in.norms + (size_t)b0 * L.n, in.rank + b0, in.lfac + (size_t)b0 * L.r_max * L.n,
-                       in.rfac + (size_t)b0 * L.r_max * D, static_cast<uint16_t*>(out_fp16) + (size_t)b0 * L.n * D);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  if (L.ev) (void)hipEventRecord(L.ev[5], L.stream);
   return hipSuccess;
 }
 

@@ -136,6 +136,7 @@ EoqLaunch make_launch(const eoq_ctx* ctx, void* stream) {
   L.pi = ctx->d_pi;
   L.pit = ctx->d_pit;
   L.tab = ctx->d_tab;
+  L.pih = ctx->d_pih;
   L.stream = static_cast<hipStream_t>(stream);
   L.ev = ctx->profile ? ctx->ev : nullptr;
   L.solver = ctx->solver;
@@ -202,6 +203,24 @@ eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, 
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pi, mat_bytes);
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pit, mat_bytes);
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_tab, sizeof(tab));
+  // binary16 hi/lo split of the rotation for the matrix-core kernels: Pi = hi + lo to ~2^-24 absolute
+  // (lo is subnormal for most entries; the matrix cores take subnormal operands)
+  std::vector<uint16_t> split((size_t)4 * d * d);
+  for (int c = 0; c < d; ++c)
+    for (int j = 0; j < d; ++j) {
+      const float v = ctx->pi_host[(size_t)c * d + j];
+      const _Float16 hi = (_Float16)v;
+      const _Float16 lo = (_Float16)(v - (float)hi);
+      uint16_t hb, lb;
+      std::memcpy(&hb, &hi, 2);
+      std::memcpy(&lb, &lo, 2);
+      split[(size_t)0 * d * d + (size_t)c * d + j] = hb;   // Pi hi   [c][j]
+      split[(size_t)1 * d * d + (size_t)c * d + j] = lb;   // Pi lo   [c][j]
+      split[(size_t)2 * d * d + (size_t)j * d + c] = hb;   // Pi^T hi [j][c]
+      split[(size_t)3 * d * d + (size_t)j * d + c] = lb;   // Pi^T lo [j][c]
+    }
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pih, split.size() * 2);
+  if (e == hipSuccess) e = hipMemcpy(ctx->d_pih, split.data(), split.size() * 2, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(ctx->d_pi, ctx->pi_host.data(), mat_bytes, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(ctx->d_pit, pit.data(), mat_bytes, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(ctx->d_tab, tab, sizeof(tab), hipMemcpyHostToDevice);
@@ -219,6 +238,7 @@ void eoq_destroy(eoq_ctx* ctx) {
   if (ctx->d_pi) (void)hipFree(ctx->d_pi);
   if (ctx->d_pit) (void)hipFree(ctx->d_pit);
   if (ctx->d_tab) (void)hipFree(ctx->d_tab);
+  if (ctx->d_pih) (void)hipFree(ctx->d_pih);
   if (ctx->profile)
     for (hipEvent_t& e : ctx->ev) (void)hipEventDestroy(e);
   delete ctx;

@@ -25,6 +25,7 @@ struct eoq_ctx {
   float* d_pi = nullptr;         // device Pi   [c][j]
   float* d_pit = nullptr;        // device Pi^T [j][c]
   float* d_tab = nullptr;        // device: 16 centroids then 16 bounds (padded)
+  uint16_t* d_pih = nullptr;     // device binary16: Pi hi [c][j], Pi lo [c][j], Pi^T hi [j][c], Pi^T lo [j][c]
   std::string err;
   int solver = 0;  // 0: tridiagonal eigensolver with Jacobi for repeated eigenvalues, 1: Jacobi for every block
   // optional per-kernel timing: events [2*i], [2*i+1] bracket stage i (spectral, encode, decode, scores)
@@ -40,6 +41,7 @@ struct EoqLaunch {
   const float* pi;
   const float* pit;
   const float* tab;
+  const uint16_t* pih;
   hipStream_t stream;
   const hipEvent_t* ev;  // null unless profiling
   int solver;
