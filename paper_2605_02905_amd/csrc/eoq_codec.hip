@@ -1,7 +1,6 @@
 // HIP kernels (gfx950) of the residual coder of eOptShrinkQ and its inverse:
 //   encode : projection C = S V diag(phi/sigma) = U diag(phi), residual against the stored binary16 factors
 //            (Alg. 3), then per row norm, rotation, Lloyd-Max index and bit-plane packing (Alg. 1 lines 3-5).
-//   scores : <q, x_hat>/sqrt(d) from the record without forming x_hat (Remark 6.5).
 #include "eoq_device.h"
 #include "eoq_internal.h"
 
@@ -147,90 +146,6 @@ __global__ __launch_bounds__(ENC_THREADS) void eoq_encode_kernel(
   }
 }
 
-// ---------------------------------------------------------------------------
-// scores: one workgroup per (sequence, KV head, run of SC_CHUNK blocks).  The group's
-// queries are rotated once (q' = Pi q), then every token of the run is scored from
-// its codes, norm and low-rank coefficients.
-// ---------------------------------------------------------------------------
-constexpr int SC_THREADS = 256;
-constexpr int SC_MAXG = 8;
-constexpr int SC_CHUNK = 8;
-
-__global__ __launch_bounds__(SC_THREADS) void eoq_scores_kernel(
-    int n, int bits, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, const float* __restrict__ pit,
-    const float* __restrict__ tab, const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
-    const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac,
-    const uint16_t* __restrict__ q, float* __restrict__ scores) {
-  __shared__ float qr[SC_MAXG * D];               // rotated queries of the group
-  __shared__ float qraw[SC_MAXG * D];
-  __shared__ float w[SC_MAXG * EOQ_RMAX_CAP];     // <v_i, q_h> of the current block
-
-  const int tid = threadIdx.x;
-  const size_t sg = blockIdx.y;                   // s*n_kv_heads + g
-  const size_t s = sg / n_kv_heads, g = sg % n_kv_heads;
-  const int n_q_heads = n_kv_heads * group;
-  const size_t q0 = (s * n_q_heads + g * group) * D;   // first query of the group
-  const size_t T = (size_t)blocks_per_head * n;
-
-  for (int e = tid; e < group * D; e += SC_THREADS) qraw[e] = half_bits_to_float(q[q0 + e]);
-  __syncthreads();
-  for (int e = tid; e < group * D; e += SC_THREADS) {
-    const int h = e >> 7, c = e & (D - 1);
-    float acc = 0.0f;
-    for (int j = 0; j < D; ++j) acc = fmaf(pit[j * D + c], qraw[h * D + j], acc);
-    qr[e] = acc;
-  }
-
-  const float inv_sqrt_d = 1.0f / sqrtf((float)D);
-  const int row_bytes = bits * D / 8;
-  const int64_t j_end = min((int64_t)(blockIdx.x + 1) * SC_CHUNK, blocks_per_head);
-  for (int64_t jblk = (int64_t)blockIdx.x * SC_CHUNK; jblk < j_end; ++jblk) {
-    const size_t blk = sg * (size_t)blocks_per_head + jblk;
-    const int r = rank_in[blk];
-    __syncthreads();
-    for (int e = tid; e < group * r; e += SC_THREADS) {
-      const int h = e / r, i = e % r;
-      float acc = 0.0f;
-      for (int j = 0; j < D; ++j)
-        acc = fmaf(half_bits_to_float(rfac[(blk * r_max + i) * D + j]), qraw[h * D + j], acc);
-      w[h * EOQ_RMAX_CAP + i] = acc;
-    }
-    __syncthreads();
-    for (int t = tid; t < n; t += SC_THREADS) {
-      const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + (blk * (size_t)n + t) * (size_t)row_bytes);
-      float acc[SC_MAXG];
-#pragma unroll
-      for (int h = 0; h < SC_MAXG; ++h) acc[h] = 0.0f;
-      for (int qd = 0; qd < 4; ++qd) {
-        uint32_t plane[4] = {0u, 0u, 0u, 0u};
-        for (int p = 0; p < bits; ++p) plane[p] = src[p * 4 + qd];
-        for (int j = 0; j < 32; ++j) {
-          int c = 0;
-#pragma unroll
-          for (int p = 0; p < 4; ++p) c |= ((plane[p] >> j) & 1u) << p;
-          const float zc = tab[c];
-#pragma unroll
-          for (int h = 0; h < SC_MAXG; ++h)
-            if (h < group) acc[h] = fmaf(zc, qr[h * D + qd * 32 + j], acc[h]);
-        }
-      }
-      const float rho = half_bits_to_float(norms[blk * (size_t)n + t]);
-      // rho <Pi q, z_hat> with z_hat = centroid / sqrt(d)
-#pragma unroll
-      for (int h = 0; h < SC_MAXG; ++h) acc[h] *= rho * inv_sqrt_d;
-      for (int i = 0; i < r; ++i) {
-        const float c = half_bits_to_float(lfac[(blk * r_max + i) * (size_t)n + t]);
-#pragma unroll
-        for (int h = 0; h < SC_MAXG; ++h)
-          if (h < group) acc[h] = fmaf(c, w[h * EOQ_RMAX_CAP + i], acc[h]);
-      }
-#pragma unroll
-      for (int h = 0; h < SC_MAXG; ++h)
-        if (h < group) scores[((s * n_q_heads + g * group + h) * T) + jblk * n + t] = acc[h] * inv_sqrt_d;
-    }
-  }
-}
-
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -255,16 +170,3 @@ hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, 
   return hipSuccess;
 }
 
-hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq, int n_kv_heads,
-                             int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores) {
-  const int64_t chunks = (blocks_per_head + SC_CHUNK - 1) / SC_CHUNK;
-  const int64_t sg_total = n_seq * n_kv_heads;
-  if (sg_total > 65535 || chunks > 0x7FFFFFFF) return hipErrorInvalidValue;
-  if (L.ev) (void)hipEventRecord(L.ev[6], L.stream);
-  hipLaunchKernelGGL(eoq_scores_kernel, dim3((unsigned)chunks, (unsigned)sg_total), dim3(SC_THREADS), 0, L.stream,
-                     L.n, L.bits, L.r_max, n_kv_heads, n_q_heads / n_kv_heads, blocks_per_head, L.pit, L.tab,
-                     keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, static_cast<const uint16_t*>(q_fp16),
-                     scores);
-  if (L.ev) (void)hipEventRecord(L.ev[7], L.stream);
-  return hipGetLastError();
-}
