@@ -153,8 +153,13 @@ __global__ __launch_bounds__(ENC_THREADS) void eoq_encode_kernel(
 // ---------------------------------------------------------------------------
 hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, const float* wfac,
                              eoq_packed out) {
-  // gridDim.y is limited to 65535: split long batches
   if (L.ev) (void)hipEventRecord(L.ev[2], L.stream);
+  if (dtype == EOQ_F16) {  // binary16 blocks go to the matrix-core kernel
+    const hipError_t e = eoq_launch_encode_f16(L, blocks, B, wfac, out);
+    if (L.ev) (void)hipEventRecord(L.ev[3], L.stream);
+    return e;
+  }
+  // gridDim.y is limited to 65535: split long batches
   for (int64_t b0 = 0; b0 < B; b0 += 32768) {
     const int64_t nb = (B - b0 < 32768) ? B - b0 : 32768;
     const size_t esz = (dtype == EOQ_F16) ? 2 : 4;

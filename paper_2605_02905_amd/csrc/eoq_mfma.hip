@@ -1,4 +1,6 @@
 // Matrix-core (MFMA, gfx950) kernels of the residual coder for binary16 blocks:
+//   encode : projection, residual against the stored factors, norm, rotation, Lloyd-Max index, packing
+//            (Alg. 3 with Alg. 1 lines 3-5)
 //   decode : x_hat = (rho/sqrt(d)) z_hat Pi + C V^T  (Alg. 1 line 6 plus the stored low-rank part)
 //   scores : <q, x_hat>/sqrt(d) from the record without forming x_hat (Sec. 2.1, Remark 6.5)
 //
@@ -347,6 +349,213 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// encode (binary16 blocks): one workgroup per block, 128 tokens per pass.
+//   phase 1 (wave w, its own 32 tokens, v_mfma_f32_32x32x8_f16 so that every result feeds the next product
+//            without leaving the registers):
+//     C^T = W S^T          W = V diag(phi/sigma) as hi + lo binary16, S from the LDS tile
+//     R^T = S^T - V16 C16^T  accumulator preloaded with S (the registers that were the B operand above)
+//     rho_t = |R_t|, u = R sqrt(d)/rho as binary16 into the LDS tile (in place of S)
+//   phase 2 (wave w = coordinates 32w .. 32w+31, rotation stationary in registers):
+//     z = u Pi^T with Pi as hi + lo, Lloyd-Max index by binary search on the boundaries; the comparison
+//     masks are the packed bit-planes (32 coordinates of two tokens per compare).
+// ---------------------------------------------------------------------------------------------
+typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+union H4 {
+  half4v h;
+  uint2 u;
+  uint16_t s[4];
+};
+__device__ __forceinline__ float16v mfma8(const H4& a, const H4& b, float16v c) {
+  return __builtin_amdgcn_mfma_f32_32x32x8f16(a.h, b.h, c, 0, 0, 0);
+}
+constexpr int VLD = EOQ_RMAX_CAP + 8;  // row stride (halfs) of V^T in LDS
+
+template <int BITS>
+__global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
+    const uint16_t* __restrict__ blocks, int n, int r_max, const uint16_t* __restrict__ pih,
+    const float* __restrict__ tab, const float* __restrict__ wfac, const int32_t* __restrict__ rank_in,
+    const uint16_t* __restrict__ rfac, uint16_t* __restrict__ lfac, uint16_t* __restrict__ norms,
+    uint8_t* __restrict__ codes) {
+  __shared__ __align__(16) uint16_t X[CHUNK * ZLD];                 // S tiles, then u tiles: [token][j]
+  __shared__ __align__(16) uint16_t Wh[EOQ_RMAX_CAP * ZLD];         // W hi  [component][j]
+  __shared__ __align__(16) uint16_t Wl[EOQ_RMAX_CAP * ZLD];         // W lo
+  __shared__ __align__(16) uint16_t VT[D * VLD];                    // V16^T [j][component]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, hf = lane >> 5;
+  const size_t blk = blockIdx.x;
+  const int r = rank_in[blk];
+  constexpr int ROWB = BITS * D / 8;
+
+  // stationary rotation operand: rows c = 32w + l32 of Pi, hi and lo
+  H8 Bhi[8], Blo[8];
+  {
+    const int c = 32 * wave + l32;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      Bhi[kk].u = *reinterpret_cast<const uint4*>(pih + c * D + 16 * kk + 8 * hf);
+      Blo[kk].u = *reinterpret_cast<const uint4*>(pih + D * D + c * D + 16 * kk + 8 * hf);
+    }
+  }
+  float bnd[(1 << BITS) - 1];
+#pragma unroll
+  for (int i = 0; i < (1 << BITS) - 1; ++i) bnd[i] = tab[16 + i];
+
+  // factors of the block: W = V diag(phi/sigma) split into hi + lo, and V16^T
+  for (int e = tid; e < EOQ_RMAX_CAP * D; e += THREADS) {
+    const int i = e >> 7, j = e & (D - 1);
+    uint16_t hi = 0, lo = 0, v16 = 0;
+    if (i < r) {
+      split_half(wfac[(blk * r_max + i) * D + j], hi, lo);
+      v16 = rfac[(blk * r_max + i) * D + j];
+    }
+    Wh[i * ZLD + j] = hi;
+    Wl[i * ZLD + j] = lo;
+    VT[j * VLD + i] = v16;
+  }
+  const float sqrt_d = sqrtf((float)D);
+
+  for (int t0 = 0; t0 < n; t0 += CHUNK) {
+    __syncthreads();  // previous chunk's tiles consumed (and the factor tables written)
+    // ---- phase 1 ----
+    {
+      uint16_t* tile = X + 32 * wave * ZLD;
+      const uint16_t* src = blocks + (blk * (size_t)n + t0 + 32 * wave) * D;
+      // 32 rows x 256 B, 16 B per lane and load: 4 rows per instruction
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = 4 * it + (lane >> 4), col = (lane & 15) * 8;
+        const uint4 v = *reinterpret_cast<const uint4*>(src + row * D + col);
+        *reinterpret_cast<uint4*>(tile + row * ZLD + col) = v;
+      }
+      __builtin_amdgcn_s_waitcnt(0);   // the tile is private to this wave: wait for its own LDS writes
+      __builtin_amdgcn_wave_barrier();
+      H4 Sreg[16];
+#pragma unroll
+      for (int kk = 0; kk < 16; ++kk) Sreg[kk].u = *reinterpret_cast<const uint2*>(tile + l32 * ZLD + 8 * kk + 4 * hf);
+      float16v Racc[4];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Racc[mt][v] = (float)Sreg[4 * mt + (v >> 2)].h[v & 3];
+      if (r > 0) {
+        float16v Cacc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Cacc[v] = 0.0f;
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+          H4 ah, al;
+          ah.u = *reinterpret_cast<const uint2*>(Wh + l32 * ZLD + 8 * kk + 4 * hf);
+          al.u = *reinterpret_cast<const uint2*>(Wl + l32 * ZLD + 8 * kk + 4 * hf);
+          Cacc = mfma8(ah, Sreg[kk], Cacc);
+          Cacc = mfma8(al, Sreg[kk], Cacc);
+        }
+        // stored coefficients C16 = binary16(U diag(phi)); their negatives are the next B operand
+        H4 Cneg[4];
+        const size_t tg = (size_t)t0 + 32 * wave + l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
+          const uint16_t hb = float_to_half_bits(Cacc[v]);
+          if (i < r) lfac[(blk * r_max + i) * (size_t)n + tg] = hb;
+          Cneg[v >> 2].s[v & 3] = hb ^ 0x8000u;
+        }
+#pragma unroll
+        for (int k2 = 0; k2 < 4; ++k2) {
+          if (8 * k2 < r) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+              H4 a;
+              a.u = *reinterpret_cast<const uint2*>(VT + (32 * mt + l32) * VLD + 8 * k2 + 4 * hf);
+              Racc[mt] = mfma8(a, Cneg[k2], Racc[mt]);
+            }
+          }
+        }
+      }
+      // rho_t and u = sqrt(d) R_t / rho_t (Alg. 1 line 3); this lane holds 64 of the 128 entries of token l32
+      float ss = 0.0f;
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ss = fmaf(Racc[mt][v], Racc[mt][v], ss);
+      ss += __shfl_xor(ss, 32, 64);
+      const float rho = sqrtf(ss);
+      if (hf == 0) norms[blk * (size_t)n + t0 + 32 * wave + l32] = float_to_half_bits(rho);
+      const float sc = (rho > 0.0f) ? sqrt_d / rho : 0.0f;
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          H4 u;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) u.s[e] = float_to_half_bits(Racc[mt][4 * q + e] * sc);
+          *reinterpret_cast<uint2*>(tile + l32 * ZLD + 32 * mt + 8 * q + 4 * hf) = u.u;
+        }
+    }
+    __syncthreads();
+    // ---- phase 2 ----
+#pragma unroll 1
+    for (int tau = 0; tau < CHUNK / 32; ++tau) {
+      float16v acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        H8 a;
+        a.u = *reinterpret_cast<const uint4*>(X + (32 * tau + l32) * ZLD + 16 * kk + 8 * hf);
+        acc = mfma16(a, Bhi[kk], acc);
+        acc = mfma16(a, Blo[kk], acc);
+      }
+      // index = number of boundaries <= z, found from the top bit down; every comparison mask holds one
+      // bit-plane of coordinates 32w..32w+31 for the tokens 8q+e (low word) and 8q+4+e (high word)
+      uint32_t outw[BITS];
+#pragma unroll
+      for (int p = 0; p < BITS; ++p) outw[p] = 0u;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float z = acc[v];
+        unsigned long long m[BITS];
+        if constexpr (BITS == 1) {
+          m[0] = __ballot(z >= bnd[0]);
+        } else if constexpr (BITS == 2) {
+          const bool b1 = z >= bnd[1];
+          m[1] = __ballot(b1);
+          m[0] = __ballot(z >= (b1 ? bnd[2] : bnd[0]));
+        } else if constexpr (BITS == 3) {
+          const bool b2 = z >= bnd[3];
+          m[2] = __ballot(b2);
+          const bool b1 = z >= (b2 ? bnd[5] : bnd[1]);
+          m[1] = __ballot(b1);
+          const float t0b = b2 ? (b1 ? bnd[6] : bnd[4]) : (b1 ? bnd[2] : bnd[0]);
+          m[0] = __ballot(z >= t0b);
+        } else {
+          const bool b3 = z >= bnd[7];
+          m[3] = __ballot(b3);
+          const bool b2 = z >= (b3 ? bnd[11] : bnd[3]);
+          m[2] = __ballot(b2);
+          const float t1 = b3 ? (b2 ? bnd[13] : bnd[9]) : (b2 ? bnd[5] : bnd[1]);
+          const bool b1 = z >= t1;
+          m[1] = __ballot(b1);
+          const float lo0 = b3 ? (b2 ? bnd[12] : bnd[8]) : (b2 ? bnd[4] : bnd[0]);
+          const float lo1 = b3 ? (b2 ? bnd[14] : bnd[10]) : (b2 ? bnd[6] : bnd[2]);
+          m[0] = __ballot(z >= (b1 ? lo1 : lo0));
+        }
+        const int row_lo = 8 * (v >> 2) + (v & 3);   // token of the low word; the high word is row_lo + 4
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) {
+          outw[p] = (lane == row_lo) ? (uint32_t)m[p] : ((lane == row_lo + 4) ? (uint32_t)(m[p] >> 32) : outw[p]);
+        }
+      }
+      if (lane < 32) {
+        uint8_t* dst = codes + (blk * (size_t)n + t0 + 32 * tau + lane) * ROWB + 4 * wave;
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) *reinterpret_cast<uint32_t*>(dst + p * 16) = outw[p];
+      }
+    }
+  }
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -390,5 +599,22 @@ hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq,
   }
 #undef EOQ_SCORES
   if (L.ev) (void)hipEventRecord(L.ev[7], L.stream);
+  return hipGetLastError();
+}
+
+hipError_t eoq_launch_encode_f16(const EoqLaunch& L, const void* blocks, int64_t B, const float* wfac,
+                                 eoq_packed out) {
+  const dim3 grid((unsigned)B), block(THREADS);
+  const uint16_t* src = static_cast<const uint16_t*>(blocks);
+#define EOQ_ENCODE(BITS)                                                                                         \
+  hipLaunchKernelGGL(eoq_encode_mfma_kernel<BITS>, grid, block, 0, L.stream, src, L.n, L.r_max, L.pih, L.tab,    \
+                     wfac, out.rank, out.rfac, out.lfac, out.norms, out.codes)
+  switch (L.bits) {
+    case 1: EOQ_ENCODE(1); break;
+    case 2: EOQ_ENCODE(2); break;
+    case 3: EOQ_ENCODE(3); break;
+    default: EOQ_ENCODE(4); break;
+  }
+#undef EOQ_ENCODE
   return hipGetLastError();
 }
