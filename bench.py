@@ -99,6 +99,9 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--bits", type=int, default=2)
     ap.add_argument("--cpu-blocks", type=int, default=1024, help="blocks in the CPU-baseline sample (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of the input batch (2 x input_bytes of HBM traffic) before the "
+                         "timed region: the reference dispatch that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (blocks are independent; see the sharding note in "
@@ -152,6 +155,9 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     log("warmup done")
+    if args.copy_calibration:
+        xhat.view(-1).copy_(blocks.view(-1))      # one elementwise copy kernel: reads and writes input_bytes each
+        torch.cuda.synchronize()
     stage = {"spectral": 0.0, "encode": 0.0, "decode": 0.0, "scores": 0.0}
     t0 = time.perf_counter()
     for _ in range(args.steps):
