@@ -11,7 +11,8 @@ namespace eoqdev {
 typedef _Float16 half_t;
 
 // ---- cross-lane moves (DPP) -------------------------------------------------------------------
-// ctrl: 0xB1 = lane^1 and 0x4E = lane^2 inside groups of 4; 0x120+n = rotate by n inside rows of 16.
+// ctrl: 0xB1 = lane^1 and 0x4E = lane^2 inside groups of 4; 0x120+n = rotate by n inside rows of 16;
+// 0x140 = mirror of a row of 16 (lane -> 15 - lane), 0x141 = mirror of each half row (lane -> 7 - lane).
 template <int CTRL>
 __device__ __forceinline__ double dpp_mov(double v) {
   int lo = __double2loint(v), hi = __double2hiint(v);
@@ -43,6 +44,15 @@ __device__ __forceinline__ double row16_sum(double v) {
   v += dpp_mov<0x4E>(v);
   v += dpp_mov<0x124>(v);
   v += dpp_mov<0x128>(v);
+  return v;
+}
+// the same with a butterfly of commutative pair sums (lane^1, lane^2, 7-lane, 15-lane): bit-identical in all
+// 16 lanes
+__device__ __forceinline__ double row16_sum_uniform(double v) {
+  v += dpp_mov<0xB1>(v);
+  v += dpp_mov<0x4E>(v);
+  v += dpp_mov<0x141>(v);
+  v += dpp_mov<0x140>(v);
   return v;
 }
 __device__ __forceinline__ double readlane_f64(double v, int lane) {

@@ -246,7 +246,7 @@ void eoq_destroy(eoq_ctx* ctx) {
 
 size_t eoq_workspace_bytes(const eoq_ctx* ctx, int64_t B) {
   if (!ctx || B < 0) return 0;
-  return eoq_ws_lam_bytes(B) + eoq_ws_wfac_bytes(B, ctx->r_max) + eoq_ws_list_bytes(B);
+  return eoq_ws_lam_bytes(B) + eoq_ws_wfac_bytes(B, ctx->r_max) + eoq_ws_list_bytes(B) + eoq_ws_tri_bytes(B);
 }
 
 eoq_status eoq_rotation(const eoq_ctx* ctx, float* host_out) {
@@ -282,7 +282,9 @@ eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64
   float* wfac = reinterpret_cast<float*>(ws + eoq_ws_lam_bytes(B));
   int* fb_count = reinterpret_cast<int*>(ws + eoq_ws_lam_bytes(B) + eoq_ws_wfac_bytes(B, ctx->r_max));
   int* fb_list = fb_count + 4;
-  hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, fb_count, fb_list, out);
+  const uintptr_t tri_at = reinterpret_cast<uintptr_t>(reinterpret_cast<char*>(fb_count) + eoq_ws_list_bytes(B));
+  double* tri = reinterpret_cast<double*>((tri_at + 63) & ~(uintptr_t)63);
+  hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, fb_count, fb_list, tri, out);
   if (e == hipSuccess) e = eoq_launch_encode(L, blocks, (int)dtype, B, wfac, out);
   if (ctx->profile) ctx->ev_valid[0] = ctx->ev_valid[1] = (e == hipSuccess);
   if (e != hipSuccess) {

@@ -49,13 +49,16 @@ struct EoqLaunch {
 
 // Workspace layout for B blocks: lam[B][128] f64, then wfac[B][r_max][128] f32 (right singular vectors
 // scaled by phi/sigma, the projection operand), then a counter (16 bytes) and a list of B block numbers
-// (the blocks handed from the tridiagonal eigensolver to the Jacobi one).
+// (the blocks handed from the tridiagonal eigensolver to the Jacobi one), then, from the next 64-byte boundary,
+// tri[B][128] pairs of doubles (the scaled tridiagonal matrix of every block, which the eigenvalue search reads
+// back through the scalar cache: a block's 2 KB must not share a cache line with its neighbours').
 inline size_t eoq_ws_lam_bytes(int64_t B) { return (size_t)B * EOQ_D * sizeof(double); }
 inline size_t eoq_ws_wfac_bytes(int64_t B, int r_max) { return (size_t)B * r_max * EOQ_D * sizeof(float); }
 inline size_t eoq_ws_list_bytes(int64_t B) { return 16 + (((size_t)B * sizeof(int) + 15) & ~(size_t)15); }
+inline size_t eoq_ws_tri_bytes(int64_t B) { return B > 0 ? 64 + (size_t)B * EOQ_D * 2 * sizeof(double) : 0; }
 
 hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, double* lam,
-                               float* wfac, int* fb_count, int* fb_list, eoq_packed out);
+                               float* wfac, int* fb_count, int* fb_list, double* tri, eoq_packed out);
 hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, const float* wfac,
                              eoq_packed out);
 hipError_t eoq_launch_encode_f16(const EoqLaunch& L, const void* blocks, int64_t B, const float* wfac,

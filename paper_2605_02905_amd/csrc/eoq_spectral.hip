@@ -284,98 +284,241 @@ __global__ __launch_bounds__(THREADS) void eoq_spectral_jacobi_kernel(
 // =============================================================================================
 // Tridiagonal solver
 // =============================================================================================
-// Row layout of the working matrix: lane pair (2i, 2i+1) owns row i; lane parity h holds the columns
-// j = 2c + h in A[c], c = 0..63.  Vectors that are read along columns live in LDS in "split" order:
-// element j at position (j & 1) * 64 + (j >> 1), so a lane reads its 64 columns contiguously.
-__device__ __forceinline__ int split_pos(int j) { return ((j & 1) << 6) | (j >> 1); }
+// Cyclic layout of the working matrix: lane (ty, tx) = (tid / 16, tid % 16) owns the 8 x 8 entries
+// A[a * 8 + b] = G[ty + 16 a][tx + 16 b].  Rows and columns are dealt round-robin, so the trailing submatrix
+// of the reduction stays spread over all lanes while it shrinks: during steps 16 s .. 16 s + 15 every lane's
+// live part is the sub-tile a, b >= s.  The 16 lanes of one DPP row share ty.
+constexpr int GRAM_STRIP = 32;  // block rows staged per pass
+// Position of column j in a staged row: the 8 columns {c + 16 m} that one lane needs are split into two groups
+// of four consecutive floats, the groups of the 16 lanes side by side (16-byte reads without bank conflicts).
+__device__ __forceinline__ int stage_pos(int j) { return ((j >> 6) << 6) | ((j & 15) << 2) | ((j >> 4) & 3); }
+constexpr int XPAD = 17;  // row stride of a 16 x 16 exchange plane: transposed reads hit distinct banks
+// the 28 sub-tiles above the diagonal, in the order they are mirrored
+constexpr int PAIR_A[28] = {0, 0, 0, 0, 0, 0, 0, 1, 1, 1, 1, 1, 1, 2, 2, 2, 2, 2, 3, 3, 3, 3, 4, 4, 4, 5, 5, 6};
+constexpr int PAIR_B[28] = {1, 2, 3, 4, 5, 6, 7, 2, 3, 4, 5, 6, 7, 3, 4, 5, 6, 7, 4, 5, 6, 7, 5, 6, 7, 6, 7, 7};
+
 // packed reflector storage: reflector k has entries i = k+1 .. 127
 __device__ __forceinline__ int refl_off(int k) { return k * (D - 1) - (k * (k - 1)) / 2; }
 constexpr int REFL_LEN = (D - 1) * D / 2;  // 8128
-constexpr int TPAD = D + 2;                // row stride of the transposition buffer
-constexpr int U1_BYTES = 4 * 8 * TPAD * 8; // 33280: also covers the Gram strip (16 KB) and the twisted scratch (32 KB)
 constexpr int MULTISECT_ITERS = 34;        // 3^34 > 2^53
 constexpr int EV_BATCH = 8;                // eigenvectors per twisted-factorisation pass
+constexpr int U1_BYTES = EV_BATCH * 4 * D * 8;  // 32 KB: twisted-factorisation scratch; also the Gram strip (16 KB)
 constexpr double CLUSTER_TOL = 1e-10;      // relative gap below which retained eigenvalues count as repeated
 
-// A[c] with a wave-uniform run-time index c: a two-level switch over values that are already in registers
-// (all other accesses to the array use compile-time indices, so it never exists in memory).
-// Keeps a value in a register at this point: stops the optimiser from merging the per-case loads / stores of
-// the switches below into one access through a selected address (which would force the array into memory).
-__device__ __forceinline__ double pinned(double v) {
-  asm volatile("" : "+v"(v));
-  return v;
-}
-template <int G>
-__device__ __forceinline__ double pick8(const double (&A)[64], int e) {
-  switch (e) {
-    case 0: return pinned(A[G * 8 + 0]);
-    case 1: return pinned(A[G * 8 + 1]);
-    case 2: return pinned(A[G * 8 + 2]);
-    case 3: return pinned(A[G * 8 + 3]);
-    case 4: return pinned(A[G * 8 + 4]);
-    case 5: return pinned(A[G * 8 + 5]);
-    case 6: return pinned(A[G * 8 + 6]);
-    default: return pinned(A[G * 8 + 7]);
+// G = S^T S in the cyclic layout.  Only the sub-tiles a <= b are accumulated (36 of 64 products per block row);
+// the others are mirrored from the lane that holds the transposed position, through LDS.
+__device__ __forceinline__ void gram_cyclic(const void* __restrict__ blocks, int dtype, size_t base_elem, int n,
+                                            float* stage, int tid, double (&A)[64]) {
+  const int ty = tid >> 4, tx = tid & 15;
+  EOQ_SFOR(i, 64, A[i] = 0.0;);
+  float nxt[2][8];
+  load8(blocks, dtype, base_elem + (size_t)tid * 8, nxt[0]);
+  load8(blocks, dtype, base_elem + (size_t)(THREADS + tid) * 8, nxt[1]);
+  const int wrow = tid >> 4, wcol = (tid & 15) * 8;
+#pragma unroll 1
+  for (int t0 = 0; t0 < n; t0 += GRAM_STRIP) {
+    __syncthreads();  // the previous strip has been consumed
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) stage[(g * 16 + wrow) * D + stage_pos(wcol + i)] = nxt[g][i];
+    __syncthreads();
+    if (t0 + GRAM_STRIP < n) {  // next strip on its way while this one is multiplied
+      const size_t e = base_elem + (size_t)(t0 + GRAM_STRIP) * D;
+      load8(blocks, dtype, e + (size_t)tid * 8, nxt[0]);
+      load8(blocks, dtype, e + (size_t)(THREADS + tid) * 8, nxt[1]);
+    }
+#pragma unroll 2
+    for (int t = 0; t < GRAM_STRIP; ++t) {
+      const float4 a0 = *reinterpret_cast<const float4*>(stage + t * D + ty * 4);
+      const float4 a1 = *reinterpret_cast<const float4*>(stage + t * D + 64 + ty * 4);
+      const float4 b0 = *reinterpret_cast<const float4*>(stage + t * D + tx * 4);
+      const float4 b1 = *reinterpret_cast<const float4*>(stage + t * D + 64 + tx * 4);
+      const double a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+      const double b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+      EOQ_SFOR(e, 64, if constexpr ((e >> 3) <= (e & 7)) A[e] = fma(a[e >> 3], b[e & 7], A[e]););
+    }
   }
+  // mirror: G[ty+16b][tx+16a] (a < b) is what lane (tx, ty) accumulated as its sub-tile (a, b)
+  double* X = reinterpret_cast<double*>(stage);
+  EOQ_SFOR(round, 4,
+    __syncthreads();
+    EOQ_SFOR(q, 7, X[q * 16 * XPAD + ty * XPAD + tx] = A[PAIR_A[round * 7 + q] * 8 + PAIR_B[round * 7 + q]];);
+    __syncthreads();
+    EOQ_SFOR(q, 7, A[PAIR_B[round * 7 + q] * 8 + PAIR_A[round * 7 + q]] = X[q * 16 * XPAD + tx * XPAD + ty];);
+  );
 }
-__device__ __forceinline__ double pick(const double (&A)[64], int c) {
-  const int e = c & 7;
-  switch (c >> 3) {
-    case 0: return pick8<0>(A, e);
-    case 1: return pick8<1>(A, e);
-    case 2: return pick8<2>(A, e);
-    case 3: return pick8<3>(A, e);
-    case 4: return pick8<4>(A, e);
-    case 5: return pick8<5>(A, e);
-    case 6: return pick8<6>(A, e);
-    default: return pick8<7>(A, e);
+
+// Sum over the 16 lanes of a DPP row of 8 values per lane, transposing as it folds: on return lane tx holds the
+// row total of value number tx / 2 (so each total sits in two adjacent lanes).  Partners: 15 - tx, tx ^ 7, tx ^ 2,
+// tx ^ 1; at each of the first three folds a lane keeps the half of its values selected by one bit of tx and
+// hands the other half to its partner.
+__device__ __forceinline__ double row16_fold8(const double (&p)[8], int tx) {
+  const bool b3 = (tx & 8) != 0, b2 = (tx & 4) != 0, b1 = (tx & 2) != 0;
+  double r1[4], r2[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const double send = b3 ? p[i] : p[4 + i];
+    const double keep = b3 ? p[4 + i] : p[i];
+    r1[i] = keep + dpp_mov<0x140>(send);  // row_mirror
   }
-}
-template <int G>
-__device__ __forceinline__ void add8(double (&A)[64], int e, double delta) {
-  switch (e) {
-    case 0: A[G * 8 + 0] = pinned(A[G * 8 + 0] + delta); break;
-    case 1: A[G * 8 + 1] = pinned(A[G * 8 + 1] + delta); break;
-    case 2: A[G * 8 + 2] = pinned(A[G * 8 + 2] + delta); break;
-    case 3: A[G * 8 + 3] = pinned(A[G * 8 + 3] + delta); break;
-    case 4: A[G * 8 + 4] = pinned(A[G * 8 + 4] + delta); break;
-    case 5: A[G * 8 + 5] = pinned(A[G * 8 + 5] + delta); break;
-    case 6: A[G * 8 + 6] = pinned(A[G * 8 + 6] + delta); break;
-    default: A[G * 8 + 7] = pinned(A[G * 8 + 7] + delta); break;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const double send = b2 ? r1[i] : r1[2 + i];
+    const double keep = b2 ? r1[2 + i] : r1[i];
+    r2[i] = keep + dpp_mov<0x141>(send);  // row_half_mirror
   }
+  const double send = b1 ? r2[0] : r2[1];
+  const double keep = b1 ? r2[1] : r2[0];
+  const double r3 = keep + dpp_mov<0x4E>(send);
+  return r3 + dpp_mov<0xB1>(r3);
 }
-__device__ __forceinline__ void add_at(double (&A)[64], int c, double delta) {
-  const int e = c & 7;
-  switch (c >> 3) {
-    case 0: add8<0>(A, e, delta); break;
-    case 1: add8<1>(A, e, delta); break;
-    case 2: add8<2>(A, e, delta); break;
-    case 3: add8<3>(A, e, delta); break;
-    case 4: add8<4>(A, e, delta); break;
-    case 5: add8<5>(A, e, delta); break;
-    case 6: add8<6>(A, e, delta); break;
-    default: add8<7>(A, e, delta); break;
+
+// Square root and reciprocal by Newton steps from the hardware estimates (good to a few ulp: the reduction only
+// needs alpha^2 = x^T x and beta = 2 / v^T v to hold to rounding level).
+__device__ __forceinline__ double newton_sqrt(double s) {
+  const double y = __builtin_amdgcn_rsq(s);
+  double g = s * y, h = 0.5 * y;
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const double r = fma(-h, g, 0.5);
+    g = fma(g, r, g);
+    h = fma(h, r, h);
+  }
+  return fma(fma(-g, g, s), h, g);
+}
+__device__ __forceinline__ double newton_rcp(double s) {
+  double y = __builtin_amdgcn_rcp(s);
+#pragma unroll
+  for (int it = 0; it < 2; ++it) y = fma(fma(-s, y, 1.0), y, y);
+  return y;
+}
+
+// Steps k = 16 S .. 16 S + 15 of the Householder reduction G = Q T Q^T, Q = H_0 H_1 ... H_125,
+// H_k = I - beta_k v_k v_k^T.  Per step: the 16 lanes that own row k form v and beta (the other lanes wait),
+// all lanes multiply p = beta A v over their live sub-tile (partial sums folded across the DPP row), then apply
+// A <- A - v w^T - w v^T with w = p - (beta/2)(v^T p) v.
+template <int S>
+__device__ __forceinline__ void householder_stage(double (&A)[64], int tid, double (*vbuf)[D], double* pbuf,
+                                                  float* refl, double* dT, double* eT, double* betaT) {
+  const int lane = tid & 63, wave = tid >> 6, ty = tid >> 4, tx = tid & 15;
+  constexpr int KK_END = (S == 7) ? 14 : 16;
+#pragma unroll 1
+  for (int kk = 0; kk < KK_END; ++kk) {
+    const int k = 16 * S + kk;
+    double* vb = vbuf[kk & 1];
+    if (wave == (kk >> 2)) {
+      // every 16-lane row of this wave runs the arithmetic on its own matrix row; only the row k stores
+      const bool owner = ((lane >> 4) == (kk & 3));
+      double x[8];
+      EOQ_SFOR(b, 8, x[b] = (b >= S) ? A[S * 8 + b] : 0.0;);
+      if (owner && tx == kk) dT[k] = x[S];
+      x[S] = (tx > kk) ? x[S] : 0.0;  // columns j = tx + 16 b > k only
+      double ss = 0.0;
+      EOQ_SFOR(b, 8, if constexpr (b >= S) ss = fma(x[b], x[b], ss););
+      ss = row16_sum(ss);
+      double xsel = x[S];
+      if constexpr (S < 7) xsel = (kk == 15) ? x[S + 1] : xsel;
+      const double x0 = readlane_f64(xsel, 16 * (kk & 3) + ((kk + 1) & 15));  // x_{k+1} of row k
+      double alpha = 0.0, beta = 0.0;
+      if (ss > 0x1.0p-960) {
+        const double sigma = newton_sqrt(ss);
+        alpha = (x0 >= 0.0) ? -sigma : sigma;                 // H_k x = alpha e_1
+        beta = newton_rcp(fma(sigma, fabs(x0), ss));          // 2 / (v^T v), v = x - alpha e_1
+      }
+      if (owner) {
+        EOQ_SFOR(b, 8,
+          const int j = tx + 16 * b;
+          const double v = (b >= S) ? x[b] - ((j == k + 1) ? alpha : 0.0) : 0.0;
+          vb[j] = v;
+          if (b >= S && j > k) refl[refl_off(k) + j - k - 1] = (float)v;
+        );
+        if (tx == 0) {
+          eT[k] = alpha;
+          betaT[k] = beta;
+        }
+      }
+    }
+    __syncthreads();
+    const double beta = betaT[k];
+    double vj[8];
+    EOQ_SFOR(b, 8, vj[b] = (b >= S) ? vb[tx + 16 * b] : 0.0;);
+    {
+      double part[8];
+      EOQ_SFOR(a, 8,
+        if constexpr (a >= S) {
+          double s0 = 0.0, s1 = 0.0;
+          EOQ_SFOR(b, 8,
+            if constexpr (b >= S) {
+              if constexpr ((b & 1) == 0) s0 = fma(A[a * 8 + b], vj[b], s0);
+              else s1 = fma(A[a * 8 + b], vj[b], s1);
+            });
+          part[a] = s0 + s1;
+        } else {
+          part[a] = 0.0;
+        });
+      const double tot = row16_fold8(part, tx);
+      if ((tx & 1) == 0) pbuf[ty + 16 * (tx >> 1)] = beta * tot;
+    }
+    __syncthreads();
+    // v^T p from the column entries this lane holds anyway, summed over its DPP row (every row of 16 lanes covers
+    // all 128 columns and gets the same bits)
+    double wj[8], vi[8], wi[8];
+    EOQ_SFOR(b, 8, wj[b] = (b >= S) ? pbuf[tx + 16 * b] : 0.0;);
+    double dl0 = 0.0, dl1 = 0.0;
+    EOQ_SFOR(b, 8,
+      if constexpr (b >= S) {
+        if constexpr ((b & 1) == 0) dl0 = fma(vj[b], wj[b], dl0);
+        else dl1 = fma(vj[b], wj[b], dl1);
+      });
+    const double K = 0.5 * beta * row16_sum_uniform(dl0 + dl1);
+    EOQ_SFOR(b, 8, if constexpr (b >= S) wj[b] = fma(-K, vj[b], wj[b]););
+    EOQ_SFOR(a, 8, vi[a] = (a >= S) ? vb[ty + 16 * a] : 0.0;);
+    EOQ_SFOR(a, 8, wi[a] = (a >= S) ? fma(-K, vi[a], pbuf[ty + 16 * a]) : 0.0;);
+    EOQ_SFOR(e, 64,
+      if constexpr ((e >> 3) >= S && (e & 7) >= S)
+        A[e] = fma(-vi[e >> 3], wj[e & 7], fma(-wi[e >> 3], vj[e & 7], A[e])););
   }
 }
 
-// Number of eigenvalues of the (scaled) tridiagonal matrix below x.  de[i] = (d_i, e_{i-1}^2), e_{-1} = 0.
-// Sign changes of the leading principal minors p_i(x) = (d_i - x) p_{i-1} - e_{i-1}^2 p_{i-2}.
-__device__ __forceinline__ int sturm_count(const double2* de, double x) {
-  double pm = 1.0, p = de[0].x - x;
-  int cnt = (int)((unsigned)__double2hiint(p) >> 31);
-#pragma unroll 8
-  for (int i = 1; i < D; ++i) {
-    const double2 t = de[i];
-    const double pn = fma(t.x - x, p, -(t.y * pm));
-    cnt += (int)(((unsigned)(__double2hiint(pn) ^ __double2hiint(p))) >> 31);
+// Number of eigenvalues of the (scaled) tridiagonal matrix below x: sign changes of the leading principal minors
+// p_i(x) = (d_i - x) p_{i-1} - e_{i-1}^2 p_{i-2}.  de[2 i] = d_i, de[2 i + 1] = e_{i-1}^2 (e_{-1} = 0), read from
+// global memory with wave-uniform addresses (scalar loads: the operands cost no vector or LDS bandwidth).
+// The signs are shifted into a mask, 32 per word, and the changes counted per word.
+typedef __attribute__((address_space(4))) const double sc_double;
+// eight steps of the recurrence with the operands t[2 s] = d, t[2 s + 1] = e^2
+__device__ __forceinline__ void sturm_steps8(const double (&t)[16], double x, double& pm, double& p, unsigned& m) {
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const double pn = fma(t[2 * s] - x, p, -(t[2 * s + 1] * pm));
+    m = __builtin_amdgcn_alignbit(m, (unsigned)__double2hiint(pn), 31);  // m = (m << 1) | sign(pn)
     pm = p;
     p = pn;
-    if ((i & 7) == 7) {  // keep the pair in range; the matrix is scaled so |d - x| <= 2, e^2 <= 1
-      const double a = fabs(p);
-      const double s = (a > 0x1.0p+200) ? 0x1.0p-200 : ((a < 0x1.0p-200) ? 0x1.0p+200 : 1.0);
-      p *= s;
-      pm *= s;
+  }
+  // renormalise the pair: |p| into [1/2, 1)
+  const int e = __builtin_amdgcn_frexp_exp(p);
+  p = ldexp(p, -e);
+  pm = ldexp(pm, -e);
+}
+__device__ __forceinline__ int sturm_count(sc_double* de, double x) {
+  double pm = 0.0, p = 1.0;  // p_{-2}, p_{-1}
+  unsigned m = 0u;           // sign history, newest in bit 0; p_{-1} > 0
+  int cnt = 0;
+  double ta[16], tb[16];
+#pragma unroll
+  for (int q = 0; q < 16; ++q) ta[q] = de[q];
+#pragma unroll 1
+  for (int c = 0; c < D / 16; ++c) {
+    // two groups of eight steps; the operands of each group are requested one group ahead
+#pragma unroll
+    for (int q = 0; q < 16; ++q) tb[q] = de[32 * c + 16 + q];
+    sturm_steps8(ta, x, pm, p, m);
+    if (c + 1 < D / 16) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) ta[q] = de[32 * c + 32 + q];
     }
+    sturm_steps8(tb, x, pm, p, m);
+    cnt += __popc((m ^ (m >> 1)) & 0xFFFFu);  // bit 16 is the sign that preceded these 16
   }
   return cnt;
 }
@@ -383,12 +526,12 @@ __device__ __forceinline__ int sturm_count(const double2* de, double x) {
 __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     const void* __restrict__ blocks, int dtype, int n, int k_pilot, double rank_thr, int r_max,
     int* __restrict__ fb_list, int* __restrict__ fb_count, double* __restrict__ lam_out, float* __restrict__ wfac,
-    int32_t* __restrict__ rank_out, float* __restrict__ phi_out, float* __restrict__ sigma_out,
+    double* __restrict__ tri, int32_t* __restrict__ rank_out, float* __restrict__ phi_out, float* __restrict__ sigma_out,
     uint16_t* __restrict__ rfac, uint32_t* __restrict__ flags_out) {
   __shared__ __align__(16) unsigned char u1[U1_BYTES];
   __shared__ float refl[REFL_LEN];
-  __shared__ __align__(16) double xbuf[2][D];
-  __shared__ __align__(16) double pbuf[2][D];
+  __shared__ __align__(16) double vbuf[2][D];
+  __shared__ __align__(16) double pbuf[D];
   __shared__ __align__(16) double2 de[D];  // (d_i, e_{i-1}^2) of the scaled tridiagonal matrix
   __shared__ double dT[D], eT[D], betaT[D];
   __shared__ double lam_s[D], atoms[D];
@@ -401,104 +544,16 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   const int lane = tid & 63, wave = tid >> 6;
   if (tid == 0) flag_s = 0u;
 
-  double A[64];
-  // ---- Gram matrix as 8x8 tiles, then into the row layout through LDS (8 rows per wave and round) ----
-  gram_tile(blocks, dtype, blk * (size_t)n * D, n, reinterpret_cast<float*>(u1), tid, A);
   {
-    double* tb = reinterpret_cast<double*>(u1) + wave * (8 * TPAD);
-    const int sub = lane >> 4, tx = lane & 15;
-#pragma unroll 1
-    for (int s = 0; s < 4; ++s) {
-      __syncthreads();
-      if (sub == s) {
-        EOQ_SFOR(e, 64, tb[(e >> 3) * TPAD + tx * 8 + (e & 7)] = A[e];);
-      }
-      __syncthreads();
-      if (sub == s) {
-        const int rho = tx >> 1, hh = tx & 1;
-        EOQ_SFOR(c, 64, A[c] = tb[rho * TPAD + 2 * c + hh];);
-      }
-    }
+    double A[64];
+    gram_cyclic(blocks, dtype, blk * (size_t)n * D, n, reinterpret_cast<float*>(u1), tid, A);
+    EOQ_SFOR(s, 8, householder_stage<s>(A, tid, vbuf, pbuf, refl, dT, eT, betaT););
+    // the last 2x2 block of T: rows and columns 126, 127 sit in the sub-tile (7, 7) of lanes ty, tx >= 14
+    const int ty = tid >> 4, tx = tid & 15;
+    if (ty == 14 && tx == 14) dT[D - 2] = A[63];
+    if (ty == 15 && tx == 14) eT[D - 2] = A[63];
+    if (ty == 15 && tx == 15) dT[D - 1] = A[63];
   }
-  const int row = tid >> 1, h = tid & 1;
-
-  // ---- Householder reduction G = Q T Q^T, Q = H_0 H_1 ... H_125, H_k = I - beta_k v_k v_k^T ----
-#pragma unroll 1
-  for (int k = 0; k < D - 2; ++k) {
-    const int par = k & 1;
-    double* xb = xbuf[par];
-    double* pb = pbuf[par];
-    {
-      // column k below the diagonal = A[i][k], held by the lanes of parity k&1 at c = k>>1
-      const double xi = pick(A, k >> 1);
-      if (h == par) {
-        xb[split_pos(row)] = (row > k) ? xi : 0.0;
-        if (row == k) dT[k] = xi;
-      }
-    }
-    __syncthreads();
-    const double ss = wave_sum_uniform(fma(xb[lane], xb[lane], xb[lane + 64] * xb[lane + 64]));
-    const double x0 = xb[split_pos(k + 1)];
-    double alpha = 0.0, beta = 0.0;
-    if (ss > 0.0) {
-      const double sigma = sqrt(ss);
-      alpha = (x0 >= 0.0) ? -sigma : sigma;          // H_k x = alpha e_1
-      beta = 1.0 / (ss + sigma * fabs(x0));          // 2 / (v^T v), v = x - alpha e_1
-    }
-    const double v_i = xb[split_pos(row)] - ((row == k + 1) ? alpha : 0.0);
-    if (h == 1 && row > k) refl[refl_off(k) + row - k - 1] = (float)v_i;
-    if (tid == 0) {
-      eT[k] = alpha;
-      betaT[k] = beta;
-    }
-    // p = beta A v over the trailing columns; the entry v_{k+1} = x_0 - alpha is applied as a correction
-    const int g0 = (k + 1) >> 4;  // first chunk of 8 columns (per parity) that still has live entries
-    const double* xh = xb + h * 64;
-    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-    EOQ_SFOR(g, 8,
-      if (g >= g0) {
-        a0 = fma(A[g * 8 + 0], xh[g * 8 + 0], a0);
-        a1 = fma(A[g * 8 + 1], xh[g * 8 + 1], a1);
-        a2 = fma(A[g * 8 + 2], xh[g * 8 + 2], a2);
-        a3 = fma(A[g * 8 + 3], xh[g * 8 + 3], a3);
-        a0 = fma(A[g * 8 + 4], xh[g * 8 + 4], a0);
-        a1 = fma(A[g * 8 + 5], xh[g * 8 + 5], a1);
-        a2 = fma(A[g * 8 + 6], xh[g * 8 + 6], a2);
-        a3 = fma(A[g * 8 + 7], xh[g * 8 + 7], a3);
-      });
-    double acc = (a0 + a1) + (a2 + a3);
-    const int c1 = (k + 1) >> 1, h1 = (k + 1) & 1;
-    {
-      const double ak1 = pick(A, c1);
-      if (h == h1) acc = fma(-alpha, ak1, acc);
-    }
-    acc = pair_sum(acc);
-    const double p_i = beta * acc;
-    if (h == 0) pb[split_pos(row)] = p_i;
-    __syncthreads();
-    // K = (beta/2) v^T p ;  w = p - K v ;  A <- A - v w^T - w v^T
-    const int pk1 = split_pos(k + 1);
-    const double va = xb[lane] - ((lane == pk1) ? alpha : 0.0);
-    const double vb = xb[lane + 64] - ((lane + 64 == pk1) ? alpha : 0.0);
-    const double dot = wave_sum_uniform(fma(va, pb[lane], vb * pb[lane + 64]));
-    const double K = 0.5 * beta * dot;
-    const double w_i = fma(-K, v_i, p_i);
-    const double* ph = pb + h * 64;
-    EOQ_SFOR(g, 8,
-      if (g >= g0) {
-        EOQ_SFOR(e, 8,
-          const double xj = xh[g * 8 + e];
-          const double wj = fma(-K, xj, ph[g * 8 + e]);
-          A[g * 8 + e] = fma(-w_i, xj, fma(-v_i, wj, A[g * 8 + e]));
-        );
-      });
-    // the loop used v_{k+1} = x_0: add the part that belongs to -alpha
-    if (h == h1) add_at(A, c1, alpha * fma(-K, v_i, w_i));
-  }
-  // the last 2x2 block of T
-  if (row == D - 2 && h == 0) dT[D - 2] = A[63];
-  if (row == D - 1 && h == 0) eT[D - 2] = A[63];
-  if (row == D - 1 && h == 1) dT[D - 1] = A[63];
   __syncthreads();
 
   // ---- eigenvalues of T by Sturm-count multisection: lane pair j brackets the j-th smallest ----
@@ -515,18 +570,27 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     }
     __syncthreads();
     const double sc = tscale_s;
+    double2* tri_blk = reinterpret_cast<double2*>(tri) + blk * D;
     if (tid < D) {
       const double e = (tid > 0) ? eT[tid - 1] * sc : 0.0;
-      de[tid] = make_double2(dT[tid] * sc, e * e);
+      const double2 t = make_double2(dT[tid] * sc, e * e);
+      de[tid] = t;
+      tri_blk[tid] = t;
     }
+    __threadfence();
     __syncthreads();
+    // the copy in global memory, addressed through the scalar unit; the address passes through an opaque
+    // register move placed after the barrier so that none of these loads can be scheduled before the stores
+    unsigned long long tri_addr = reinterpret_cast<unsigned long long>(tri_blk);
+    asm volatile("" : "+s"(tri_addr) : : "memory");
+    sc_double* sde = reinterpret_cast<sc_double*>(tri_addr);
     const int j = tid >> 1, sub = tid & 1;
     double lo = -0x1.0p-40, hi = 1.0 + 0x1.0p-40;   // G is positive semi-definite; Gershgorin bounds the top by 1
 #pragma unroll 1
     for (int it = 0; it < MULTISECT_ITERS; ++it) {
       const double third = (hi - lo) * (1.0 / 3.0);
       const double x1 = lo + third, x2 = hi - third;
-      const int mine = sturm_count(de, sub ? x2 : x1);
+      const int mine = sturm_count(sde, sub ? x2 : x1);
       const int other = dpp_mov<0xB1>(mine);
       const int c1 = sub ? other : mine, c2 = sub ? mine : other;
       if (c1 > j) {
@@ -698,7 +762,7 @@ __global__ void eoq_zero_counter_kernel(int* counter) {
 // launcher
 // ---------------------------------------------------------------------------------------------
 hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, double* lam,
-                               float* wfac, int* fb_count, int* fb_list, eoq_packed out) {
+                               float* wfac, int* fb_count, int* fb_list, double* tri, eoq_packed out) {
   if (L.ev) (void)hipEventRecord(L.ev[0], L.stream);
   if (L.solver == 1) {
     hipLaunchKernelGGL(eoq_spectral_jacobi_kernel, dim3((unsigned)B), dim3(THREADS), 0, L.stream, blocks, dtype, L.n,
@@ -707,7 +771,7 @@ hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype
   } else {
     hipLaunchKernelGGL(eoq_zero_counter_kernel, dim3(1), dim3(64), 0, L.stream, fb_count);
     hipLaunchKernelGGL(eoq_spectral_tridiag_kernel, dim3((unsigned)B), dim3(THREADS), 0, L.stream, blocks, dtype, L.n,
-                       L.k, L.rank_thr, L.r_max, fb_list, fb_count, lam, wfac, out.rank, out.phi, out.sigma, out.rfac,
+                       L.k, L.rank_thr, L.r_max, fb_list, fb_count, lam, wfac, tri, out.rank, out.phi, out.sigma, out.rfac,
                        out.flags);
     const unsigned grid = (unsigned)((B < 256) ? B : 256);
     hipLaunchKernelGGL(eoq_spectral_jacobi_kernel, dim3(grid), dim3(THREADS), 0, L.stream, blocks, dtype, L.n, L.k,

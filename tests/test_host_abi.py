@@ -68,7 +68,7 @@ def test_unsupported_shapes_are_rejected(lib):
 def test_workspace_size_and_host_only_context(lib):
     ctx = eoq.Context(n=512, bits=2, r_max=32)
     assert ctx.eoq_workspace_bytes(0) == 16
-    assert ctx.eoq_workspace_bytes(10) == 10 * (128 * 8 + 32 * 128 * 4) + 16 + 48
+    assert ctx.eoq_workspace_bytes(10) == 10 * (128 * 8 + 32 * 128 * 4) + 16 + 48 + 64 + 10 * 128 * 16
     assert lib.eoq_last_error(ctx._h) == b""
     assert lib.eoq_rotation(ctx._h, None) == eoq.EOQ_ERR_ARG
     import torch
