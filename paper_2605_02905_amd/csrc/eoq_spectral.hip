@@ -486,39 +486,39 @@ __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, doub
 // global memory with wave-uniform addresses (scalar loads: the operands cost no vector or LDS bandwidth).
 // The signs are shifted into a mask, 32 per word, and the changes counted per word.
 typedef __attribute__((address_space(4))) const double sc_double;
-// eight steps of the recurrence with the operands t[2 s] = d, t[2 s + 1] = e^2
-__device__ __forceinline__ void sturm_steps8(const double (&t)[16], double x, double& pm, double& p, unsigned& m) {
+// four steps of the recurrence with the operands t[2 s] = d, t[2 s + 1] = e^2
+__device__ __forceinline__ void sturm_steps4(const double (&t)[8], double x, double& pm, double& p, unsigned& m) {
 #pragma unroll
-  for (int s = 0; s < 8; ++s) {
+  for (int s = 0; s < 4; ++s) {
     const double pn = fma(t[2 * s] - x, p, -(t[2 * s + 1] * pm));
     m = __builtin_amdgcn_alignbit(m, (unsigned)__double2hiint(pn), 31);  // m = (m << 1) | sign(pn)
     pm = p;
     p = pn;
   }
-  // renormalise the pair: |p| into [1/2, 1)
-  const int e = __builtin_amdgcn_frexp_exp(p);
-  p = ldexp(p, -e);
-  pm = ldexp(pm, -e);
 }
 __device__ __forceinline__ int sturm_count(sc_double* de, double x) {
   double pm = 0.0, p = 1.0;  // p_{-2}, p_{-1}
   unsigned m = 0u;           // sign history, newest in bit 0; p_{-1} > 0
   int cnt = 0;
-  double ta[16], tb[16];
+  double ta[8], tb[8];
 #pragma unroll
-  for (int q = 0; q < 16; ++q) ta[q] = de[q];
+  for (int q = 0; q < 8; ++q) ta[q] = de[q];
 #pragma unroll 1
-  for (int c = 0; c < D / 16; ++c) {
-    // two groups of eight steps; the operands of each group are requested one group ahead
+  for (int c = 0; c < D / 8; ++c) {
+    // two groups of four steps; the operands of each group (64 bytes) are requested one group ahead
 #pragma unroll
-    for (int q = 0; q < 16; ++q) tb[q] = de[32 * c + 16 + q];
-    sturm_steps8(ta, x, pm, p, m);
-    if (c + 1 < D / 16) {
+    for (int q = 0; q < 8; ++q) tb[q] = de[16 * c + 8 + q];
+    sturm_steps4(ta, x, pm, p, m);
+    if (c + 1 < D / 8) {
 #pragma unroll
-      for (int q = 0; q < 16; ++q) ta[q] = de[32 * c + 32 + q];
+      for (int q = 0; q < 8; ++q) ta[q] = de[16 * c + 16 + q];
     }
-    sturm_steps8(tb, x, pm, p, m);
-    cnt += __popc((m ^ (m >> 1)) & 0xFFFFu);  // bit 16 is the sign that preceded these 16
+    sturm_steps4(tb, x, pm, p, m);
+    // renormalise the pair: |p| into [1/2, 1)
+    const int e = __builtin_amdgcn_frexp_exp(p);
+    p = ldexp(p, -e);
+    pm = ldexp(pm, -e);
+    cnt += __popc((m ^ (m >> 1)) & 0xFFu);  // bit 8 is the sign that preceded these eight
   }
   return cnt;
 }
@@ -532,8 +532,11 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   __shared__ float refl[REFL_LEN];
   __shared__ __align__(16) double vbuf[2][D];
   __shared__ __align__(16) double pbuf[D];
-  __shared__ __align__(16) double2 de[D];  // (d_i, e_{i-1}^2) of the scaled tridiagonal matrix
+  __shared__ __align__(16) double2 de[D + 1];  // (d_i, e_{i-1}^2) of the scaled tridiagonal matrix; de[D] = 0
   __shared__ double dT[D], eT[D], betaT[D];
+  __shared__ double cW[(D / 4) * 6];  // inner products of the reflectors inside each group of four
+  __shared__ double norm_s[EV_BATCH];
+  __shared__ int twist_s[EV_BATCH];
   __shared__ double lam_s[D], atoms[D];
   __shared__ double scale_s[EOQ_RMAX_CAP];
   __shared__ double tscale_s;
@@ -542,7 +545,11 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   const int tid = threadIdx.x;
   const size_t blk = blockIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) flag_s = 0u;
+  if (tid == 0) {
+    flag_s = 0u;
+    betaT[D - 2] = betaT[D - 1] = 0.0;  // reflectors 126, 127 do not exist
+    de[D] = make_double2(0.0, 0.0);
+  }
 
   {
     double A[64];
@@ -555,6 +562,27 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     if (ty == 15 && tx == 15) dT[D - 1] = A[63];
   }
   __syncthreads();
+  // inner products of the reflectors of each group {4b, .., 4b+3}, in the order the back-transformation applies
+  // them (u_1 = v_{4b+3} .. u_4 = v_{4b}): c21 c31 c32 c41 c42 c43; one row of 16 lanes per product
+  {
+    const int row = tid >> 4, l = tid & 15;
+#pragma unroll 1
+    for (int q = row; q < (D / 4) * 6; q += THREADS / 16) {
+      const int bb = q / 6, pr = q - 6 * bb;
+      const int a = (pr == 0) ? 2 : ((pr < 3) ? 3 : 4), b2 = (pr == 0) ? 1 : ((pr < 3) ? pr : pr - 2);
+      const int ka = 4 * bb + 4 - a, kb = 4 * bb + 4 - b2;  // ka < kb
+      const int roa = refl_off(ka) - (ka + 1), rob = refl_off(kb) - (kb + 1);
+      double acc = 0.0;
+#pragma unroll
+      for (int m = 0; m < 8; ++m) {
+        const int i = l + 16 * m;
+        const float ra = refl[min(max(roa + i, 0), REFL_LEN - 1)], rb = refl[min(max(rob + i, 0), REFL_LEN - 1)];
+        acc = fma((kb < D - 2 && i > kb) ? (double)ra : 0.0, (double)rb, acc);
+      }
+      acc = row16_sum_uniform(acc);
+      if (l == 0) cW[q] = acc;
+    }
+  }
 
   // ---- eigenvalues of T by Sturm-count multisection: lane pair j brackets the j-th smallest ----
   {
@@ -624,116 +652,160 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   }
 
   // ---- eigenvectors of the retained components ----
-  double* tw = reinterpret_cast<double*>(u1);  // per eigenvector of the batch: Dp[128] Lp[128] Dm[128] Um[128]
+  // For a retained eigenvalue mu the vector comes from the twisted factorisation of T - mu I.  Its pivots are
+  // ratios of consecutive minors, D+_i = p_i / p_{i-1} (leading minors, from the top) and D-_i = q_i / q_{i+1}
+  // (trailing minors, from the bottom), so the two sequential sweeps are division-free three-term recurrences and
+  // every division happens afterwards, all rows in parallel.  The twist index minimises
+  // |gamma_i| = |D+_i + D-_i - (d_i - mu)|; z_twist = 1, z_i = -(e_i / D+_i) z_{i+1} above it and
+  // z_i = -(e_{i-1} / D-_i) z_{i-1} below it.
+  double2* tw = reinterpret_cast<double2*>(u1);  // per eigenvector of a batch: F[128] (top-down) then Bk[128] (bottom-up)
   const double sc = tscale_s;
 #pragma unroll 1
   for (int b0 = 0; b0 < r; b0 += EV_BATCH) {
     __syncthreads();
-    // twisted factorisation of T - mu I: lane pair (forward, backward) per eigenvector, first wave only
+    // (1) minors: lane pair (top-down, bottom-up) per eigenvector; F[i] = (p_i, p_{i-1}), Bk[i] = (q_i, q_{i+1})
     if (tid < 2 * EV_BATCH && b0 + (tid >> 1) < r) {
       const int ev = tid >> 1, role = tid & 1;
       const double mu = lam_s[b0 + ev] * sc;
-      double* Dp = tw + ev * 4 * D;
-      double* Lp = Dp + D;
-      double* Dm = Dp + 2 * D;
-      double* Um = Dp + 3 * D;
-      const double piv = 0x1.0p-100;
-      if (role == 0) {
-        double dcur = de[0].x - mu;
-        for (int i = 0; i < D - 1; ++i) {
-          if (fabs(dcur) < piv) dcur = (dcur < 0.0) ? -piv : piv;
-          Dp[i] = dcur;
-          const double e = eT[i] * sc;
-          const double l = e / dcur;
-          Lp[i] = l;
-          dcur = (de[i + 1].x - mu) - l * e;
+      double2* out = tw + (ev * 2 + role) * D;
+      double pm = 0.0, p = 1.0;
+#pragma unroll 1
+      for (int s0 = 0; s0 < D; s0 += 8) {
+        double dmu[8], e2[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          const int i = role ? D - 1 - (s0 + s) : s0 + s;
+          dmu[s] = de[i].x - mu;
+          e2[s] = de[i + role].y;  // e_{i-1}^2 going down, e_i^2 going up (de[D].y = 0)
         }
-        Dp[D - 1] = dcur;
-      } else {
-        double dcur = de[D - 1].x - mu;
-        for (int i = D - 2; i >= 0; --i) {
-          if (fabs(dcur) < piv) dcur = (dcur < 0.0) ? -piv : piv;
-          Dm[i + 1] = dcur;
-          const double e = eT[i] * sc;
-          const double u = e / dcur;
-          Um[i] = u;
-          dcur = (de[i].x - mu) - u * e;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          const int i = role ? D - 1 - (s0 + s) : s0 + s;
+          const double pn = fma(dmu[s], p, -(e2[s] * pm));
+          out[i] = make_double2(pn, p);
+          pm = p;
+          p = pn;
         }
-        Dm[0] = dcur;
+        const int e = __builtin_amdgcn_frexp_exp(p);  // the ratios are unchanged by a common factor
+        p = ldexp(p, -e);
+        pm = ldexp(pm, -e);
       }
     }
     __syncthreads();
+    // (2) pivots, multipliers and twist index: 16 lanes per eigenvector, rows i = l + 16 m
+    if (tid < 16 * EV_BATCH && b0 + (tid >> 4) < r) {
+      const int ev = tid >> 4, l = tid & 15;
+      const double mu = lam_s[b0 + ev] * sc;
+      double2* F = tw + ev * 2 * D;
+      double2* Bk = F + D;
+      const double piv = 0x1.0p-100;  // smallest pivot magnitude (the matrix is scaled to norm <= 1)
+      double best = INFINITY;
+#pragma unroll
+      for (int m = 0; m < 8; ++m) {
+        const int i = l + 16 * m;
+        const double2 f = F[i], bq = Bk[i];
+        const double fn = (fabs(f.x) < piv * fabs(f.y)) ? copysign(piv * fabs(f.y), f.x) : f.x;
+        const double bn = (fabs(bq.x) < piv * fabs(bq.y)) ? copysign(piv * fabs(bq.y), bq.x) : bq.x;
+        double g = fabs(fma(fn, newton_rcp(f.y), fma(bn, newton_rcp(bq.y), -(de[i].x - mu))));
+        if (!(g == g)) g = INFINITY;
+        double lmul = (i < D - 1) ? eT[i] * sc * f.y * newton_rcp(fn) : 0.0;   // e_i / D+_i
+        double umul = (i > 0) ? eT[i - 1] * sc * bq.y * newton_rcp(bn) : 0.0;  // e_{i-1} / D-_i
+        if (!isfinite(lmul)) lmul = 0.0;
+        if (!isfinite(umul)) umul = 0.0;
+        F[i].x = lmul;
+        Bk[i].x = umul;
+        // the row index rides in the low mantissa bits: the minimum of the keys carries its own position
+        const double key = __hiloint2double(__double2hiint(g), (__double2loint(g) & ~127) | i);
+        best = fmin(best, key);
+      }
+      best = fmin(best, dpp_mov<0xB1>(best));
+      best = fmin(best, dpp_mov<0x4E>(best));
+      best = fmin(best, dpp_mov<0x141>(best));
+      best = fmin(best, dpp_mov<0x140>(best));
+      if (l == 0) twist_s[ev] = __double2loint(best) & 127;
+    }
+    __syncthreads();
+    // (3) the vector itself, upwards and downwards from the twist index; z_i goes to F[i].y
     if (tid < 2 * EV_BATCH && b0 + (tid >> 1) < r) {
       const int ev = tid >> 1, role = tid & 1;
-      const double mu = lam_s[b0 + ev] * sc;
-      double* Dp = tw + ev * 4 * D;
-      const double* Lp = Dp + D;
-      const double* Dm = Dp + 2 * D;
-      const double* Um = Dp + 3 * D;
-      // twist index: smallest |gamma_i|, gamma_i = D+_i + D-_i - (d_i - mu)
-      int rt = 0;
-      double best = INFINITY;
-      for (int i = 0; i < D; ++i) {
-        const double g = fabs(Dp[i] + Dm[i] - (de[i].x - mu));
-        if (g < best) {
-          best = g;
-          rt = i;
-        }
-      }
-      // z_rt = 1, upwards with the forward multipliers, downwards with the backward ones; written over Dp,
-      // which is dead once both lanes of the pair (they run in lockstep) have finished the scan above
-      double ssq = 0.0;
-      if (role == 0) {
-        double z = 1.0;
-        for (int i = rt - 1; i >= 0; --i) {
-          z = -Lp[i] * z;
-          Dp[i] = z;
-          ssq = fma(z, z, ssq);
-        }
-      } else {
-        double z = 1.0;
-        Dp[rt] = 1.0;
+      double2* F = tw + ev * 2 * D;
+      const double2* Bk = F + D;
+      const int rt = twist_s[ev];
+      const int count = role ? D - 1 - rt : rt;
+      const int dir = role ? 1 : -1;
+      double z = 1.0, ssq = 0.0;
+      if (role) {
+        F[rt].y = 1.0;
         ssq = 1.0;
-        for (int i = rt; i < D - 1; ++i) {
-          z = -Um[i] * z;
-          Dp[i + 1] = z;
-          ssq = fma(z, z, ssq);
+      }
+#pragma unroll 1
+      for (int s0 = 0; s0 < count; s0 += 4) {
+        double mlt[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const int i = min(max(rt + dir * (s0 + s + 1), 0), D - 1);
+          mlt[s] = role ? Bk[i].x : F[i].x;
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const int i = rt + dir * (s0 + s + 1);
+          if (s0 + s < count) {
+            z = -mlt[s] * z;
+            F[i].y = z;
+            ssq = fma(z, z, ssq);
+          }
         }
       }
       ssq = pair_sum(ssq);
       if (role == 0) {
-        Dp[D + 0] = ssq;   // first slot of Lp: squared norm (Lp is dead now)
+        norm_s[ev] = ssq;
         if (!(ssq > 0.0) || !isfinite(ssq)) atomicOr(&flag_s, EOQ_FLAG_NO_CONVERGE);
       }
     }
     __syncthreads();
-    // back-transformation v = H_0 H_1 ... H_125 z: 16 lanes per eigenvector, 8 elements (i = l + 16 m) each
+    // (4) back-transformation v = H_0 H_1 ... H_125 z, four reflectors at a time: 16 lanes per eigenvector, 8
+    // entries (i = l + 16 m) each.  With u_1 .. u_4 = v_{4b+3} .. v_{4b} (order of application), d_a = u_a^T y and
+    // c_ab = u_a^T u_b (prepared once per block), the four coefficients follow from a triangular recurrence and
+    // y <- y - sum_a f_a u_a.
     if (tid < 16 * EV_BATCH) {
       const int ev = tid >> 4, l = tid & 15;
       const bool live = (b0 + ev < r);
-      const double* Dp = tw + ev * 4 * D;
+      const double2* F = tw + ev * 2 * D;
       double y[8];
       {
-        const double ssq = live ? Dp[D] : 1.0;
+        const double ssq = live ? norm_s[ev] : 1.0;
         const double inv = (ssq > 0.0 && isfinite(ssq)) ? 1.0 / sqrt(ssq) : 0.0;
 #pragma unroll
-        for (int m = 0; m < 8; ++m) y[m] = live ? Dp[l + 16 * m] * inv : 0.0;
+        for (int m = 0; m < 8; ++m) y[m] = live ? F[l + 16 * m].y * inv : 0.0;
       }
 #pragma unroll 1
-      for (int k = D - 3; k >= 0; --k) {
-        const int ro = refl_off(k) - (k + 1);
-        double v[8];
-        double dot = 0.0;
+      for (int bb = D / 4 - 1; bb >= 0; --bb) {
+        double u[4][8], dt[4];
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
-          const int i = l + 16 * m;
-          v[m] = (i > k) ? (double)refl[ro + i] : 0.0;
-          dot = fma(v[m], y[m], dot);
+        for (int a = 0; a < 4; ++a) {
+          const int k = 4 * bb + 3 - a;
+          const int kc = min(k, D - 3);  // reflectors 126, 127 do not exist: any address, value forced to zero
+          const int ro = refl_off(kc) - (kc + 1);
+          double acc = 0.0;
+#pragma unroll
+          for (int m = 0; m < 8; ++m) {
+            const int i = l + 16 * m;
+            const float raw = refl[max(ro + i, 0)];  // unconditional load (in range), masked afterwards
+            u[a][m] = (k < D - 2 && i > k) ? (double)raw : 0.0;
+            acc = fma(u[a][m], y[m], acc);
+          }
+          dt[a] = acc;
         }
-        dot = row16_sum(dot);
-        const double f = betaT[k] * dot;
 #pragma unroll
-        for (int m = 0; m < 8; ++m) y[m] = fma(-f, v[m], y[m]);
+        for (int a = 0; a < 4; ++a) dt[a] = row16_sum_uniform(dt[a]);
+        const double* c = cW + bb * 6;
+        const double f1 = betaT[4 * bb + 3] * dt[0];
+        const double f2 = betaT[4 * bb + 2] * fma(-c[0], f1, dt[1]);
+        const double f3 = betaT[4 * bb + 1] * fma(-c[2], f2, fma(-c[1], f1, dt[2]));
+        const double f4 = betaT[4 * bb] * fma(-c[5], f3, fma(-c[4], f2, fma(-c[3], f1, dt[3])));
+#pragma unroll
+        for (int m = 0; m < 8; ++m)
+          y[m] = fma(-f4, u[3][m], fma(-f3, u[2][m], fma(-f2, u[1][m], fma(-f1, u[0][m], y[m]))));
       }
       if (live) {
         const double s = scale_s[b0 + ev];
