@@ -304,6 +304,8 @@ constexpr int MULTISECT_ITERS = 34;        // 3^34 > 2^53
 constexpr int EV_BATCH = 8;                // eigenvectors per twisted-factorisation pass
 constexpr int U1_BYTES = EV_BATCH * 4 * D * 8;  // 32 KB: twisted-factorisation scratch; also the Gram strip (16 KB)
 constexpr double CLUSTER_TOL = 1e-10;      // relative gap below which retained eigenvalues count as repeated
+constexpr int REFL_BYTES = REFL_LEN * 4;   // 32512 (a multiple of 16)
+constexpr int POOL_BYTES = REFL_BYTES + U1_BYTES;
 
 // G = S^T S in the cyclic layout.  Only the sub-tiles a <= b are accumulated (36 of 64 products per block row);
 // the others are mirrored from the lane that holds the transposed position, through LDS.
@@ -346,6 +348,166 @@ __device__ __forceinline__ void gram_cyclic(const void* __restrict__ blocks, int
     EOQ_SFOR(q, 7, X[q * 16 * XPAD + ty * XPAD + tx] = A[PAIR_A[round * 7 + q] * 8 + PAIR_B[round * 7 + q]];);
     __syncthreads();
     EOQ_SFOR(q, 7, A[PAIR_B[round * 7 + q] * 8 + PAIR_A[round * 7 + q]] = X[q * 16 * XPAD + tx * XPAD + ty];);
+  );
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gram matrix of a binary16 block by exact integer arithmetic on the matrix cores.
+//
+// Per pass of 64 tokens every column j gets the exponent E_j of its largest entry and its entries become
+// integers I = trunc(x 2^(29 - E_j)), |I| < 2^30: exact for every entry within a factor 2^19 of the column
+// maximum (binary16 carries 11 significant bits), truncated below 2^(E_j - 29) otherwise.  I is split into four
+// signed bytes, I = s0 + 2^8 s1 + 2^16 s2 + 2^24 s3, and the byte planes are multiplied with
+// v_mfma_i32_16x16x64_i8 (exact int32 sums over the 64 tokens); the sixteen plane pairs go to seven accumulators,
+// one per weight 2^(8 (p + q)).  The pass result, scaled by 2^(E_i + E_j - 58), is added to a double-precision
+// accumulator.  Only the 36 tiles of 16 x 16 on and above the diagonal are computed, nine per wave.  Element
+// (ty, tx) of tile (a, b) is entry A[a * 8 + b] of lane (ty, tx) in the cyclic layout, so at the end the tiles
+// only change lanes (through LDS), the mirrored ones read transposed.
+// ---------------------------------------------------------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+
+constexpr int GI_TOK = 64;                       // tokens per pass = depth of one matrix instruction
+constexpr int GI_ROW = GI_TOK + 16;              // bytes per (plane, column): 16 consecutive columns -> 16 distinct 16-byte bank groups
+constexpr int GI_PLANE = D * GI_ROW;             // 10240
+constexpr int GI_NPLANE = 4;
+constexpr int GI_CMAX_OFF = GI_NPLANE * GI_PLANE;  // 16 x 64 words: per-loader column maxima
+constexpr int GI_CEXP_OFF = GI_CMAX_OFF + 4096;  // 128 ints: exponent of the integer unit of each column
+constexpr int GI_BYTES = GI_CEXP_OFF + 512;
+constexpr int GI_TILES = 36;                     // upper tiles, row-major: (0,0) .. (0,7), (1,1) .. (7,7)
+constexpr int UT_I[GI_TILES] = {0, 0, 0, 0, 0, 0, 0, 0, 1, 1, 1, 1, 1, 1, 1, 2, 2, 2, 2, 2, 2, 3, 3, 3, 3, 3, 4, 4, 4, 4, 5, 5, 5, 6, 6, 7};
+constexpr int UT_J[GI_TILES] = {0, 1, 2, 3, 4, 5, 6, 7, 1, 2, 3, 4, 5, 6, 7, 2, 3, 4, 5, 6, 7, 3, 4, 5, 6, 7, 4, 5, 6, 7, 5, 6, 7, 6, 7, 7};
+__device__ const int ut_i_dev[GI_TILES] = {0, 0, 0, 0, 0, 0, 0, 0, 1, 1, 1, 1, 1, 1, 1, 2, 2, 2, 2, 2, 2, 3, 3, 3, 3, 3, 4, 4, 4, 4, 5, 5, 5, 6, 6, 7};
+__device__ const int ut_j_dev[GI_TILES] = {0, 1, 2, 3, 4, 5, 6, 7, 1, 2, 3, 4, 5, 6, 7, 2, 3, 4, 5, 6, 7, 3, 4, 5, 6, 7, 4, 5, 6, 7, 5, 6, 7, 6, 7, 7};
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  const ushort2v r = __builtin_elementwise_max(*reinterpret_cast<ushort2v*>(&a), *reinterpret_cast<ushort2v*>(&b));
+  return *reinterpret_cast<const uint32_t*>(&r);
+}
+// byte K of x0 .. x3 -> one word
+template <int K>
+__device__ __forceinline__ uint32_t gather_bytes(int x0, int x1, int x2, int x3) {
+  constexpr uint32_t sel = 0x0c0c0000u | ((4u + K) << 8) | (uint32_t)K;
+  const uint32_t t01 = __builtin_amdgcn_perm((uint32_t)x1, (uint32_t)x0, sel);
+  const uint32_t t23 = __builtin_amdgcn_perm((uint32_t)x3, (uint32_t)x2, sel);
+  return t01 | (t23 << 16);
+}
+
+__device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, int n, unsigned char* pool, int tid,
+                                          double (&A)[64]) {
+  const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m = tid & 15, q = tid >> 4;  // loader: columns 8m .. 8m+7, tokens 4q .. 4q+3 of the pass
+  uint32_t* cmax = reinterpret_cast<uint32_t*>(pool + GI_CMAX_OFF);
+  int* cexp = reinterpret_cast<int*>(pool + GI_CEXP_OFF);
+  double Gacc[9][4];  // tile number wave + 4 s, rows 4 kg + v, column l16
+  EOQ_SFOR(s, 9, EOQ_SFOR(v, 4, Gacc[s][v] = 0.0;););
+
+  uint4 raw[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) raw[it] = *reinterpret_cast<const uint4*>(src + (size_t)(4 * q + it) * D + 8 * m);
+
+#pragma unroll 1
+  for (int t0 = 0; t0 < n; t0 += GI_TOK) {
+    // ---- column maxima of the pass ----
+    uint32_t mx[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      mx[0] = pk_max_u16(mx[0], raw[it].x & 0x7FFF7FFFu);
+      mx[1] = pk_max_u16(mx[1], raw[it].y & 0x7FFF7FFFu);
+      mx[2] = pk_max_u16(mx[2], raw[it].z & 0x7FFF7FFFu);
+      mx[3] = pk_max_u16(mx[3], raw[it].w & 0x7FFF7FFFu);
+    }
+    __syncthreads();  // the previous pass no longer reads planes, maxima or exponents
+    *reinterpret_cast<uint4*>(cmax + q * 64 + m * 4) = make_uint4(mx[0], mx[1], mx[2], mx[3]);
+    __syncthreads();
+#pragma unroll
+    for (int rr = 0; rr < 16; ++rr) {
+      const uint4 o = *reinterpret_cast<const uint4*>(cmax + rr * 64 + m * 4);
+      mx[0] = pk_max_u16(mx[0], o.x);
+      mx[1] = pk_max_u16(mx[1], o.y);
+      mx[2] = pk_max_u16(mx[2], o.z);
+      mx[3] = pk_max_u16(mx[3], o.w);
+    }
+    // ---- integers, byte planes ----
+    EOQ_SFOR(c, 8,
+      const uint32_t hmax = (mx[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
+      const int ef = max((int)(hmax >> 10), 1);               // biased exponent of the column maximum (subnormals: 1)
+      const float scale = __int_as_float((171 - ef) << 23);   // 2^(29 - (ef - 15))
+      if (q == 0) cexp[8 * m + c] = ef - 44;                  // one integer unit = 2^(ef - 15 - 29)
+      int i0[4]; int i1[4]; int i2[4]; int i3[4];
+      EOQ_SFOR(it, 4,
+        const uint32_t w = (c >> 1) == 0 ? raw[it].x : ((c >> 1) == 1 ? raw[it].y : ((c >> 1) == 2 ? raw[it].z : raw[it].w));
+        const uint16_t hb = (uint16_t)(w >> (16 * (c & 1)));
+        const int I = (int)(half_bits_to_float(hb) * scale);   // truncation towards zero
+        const int r1 = I - __builtin_amdgcn_sbfe(I, 0, 8);     // multiple of 2^8
+        const int r2 = r1 - (__builtin_amdgcn_sbfe(r1, 8, 8) << 8);    // multiple of 2^16
+        i0[it] = I;
+        i1[it] = r1;
+        i2[it] = r2;
+        i3[it] = r2 - (__builtin_amdgcn_sbfe(r2, 16, 8) << 16);        // multiple of 2^24
+      );
+      unsigned char* dst = pool + (8 * m + c) * GI_ROW + 4 * q;
+      *reinterpret_cast<uint32_t*>(dst) = gather_bytes<0>(i0[0], i0[1], i0[2], i0[3]);
+      *reinterpret_cast<uint32_t*>(dst + GI_PLANE) = gather_bytes<1>(i1[0], i1[1], i1[2], i1[3]);
+      *reinterpret_cast<uint32_t*>(dst + 2 * GI_PLANE) = gather_bytes<2>(i2[0], i2[1], i2[2], i2[3]);
+      *reinterpret_cast<uint32_t*>(dst + 3 * GI_PLANE) = gather_bytes<3>(i3[0], i3[1], i3[2], i3[3]);
+    );
+    if (t0 + GI_TOK < n) {  // next pass on its way during the products
+#pragma unroll
+      for (int it = 0; it < 4; ++it)
+        raw[it] = *reinterpret_cast<const uint4*>(src + (size_t)(t0 + GI_TOK + 4 * q + it) * D + 8 * m);
+    }
+    __syncthreads();
+    // ---- products, one tile at a time: lane supplies row / column l16 of the tile, tokens 16 kg .. 16 kg + 15 ----
+    EOQ_SFOR(s, 9,
+      const int tile = wave + 4 * s;
+      const int tI = ut_i_dev[tile]; const int tJ = ut_j_dev[tile];
+      v4i acc[7];  // acc[c]: plane pairs (p, q) with p + q = c, weight 2^(8 c)
+      EOQ_SFOR(cc, 7, EOQ_SFOR(v, 4, acc[cc][v] = 0;););
+      const unsigned char* pa = pool + (16 * tI + l16) * GI_ROW + 16 * kg;
+      const unsigned char* pb = pool + (16 * tJ + l16) * GI_ROW + 16 * kg;
+      v4i a[4]; v4i b[4];
+      EOQ_SFOR(pl, 4,
+        a[pl] = *reinterpret_cast<const v4i*>(pa + pl * GI_PLANE);
+        b[pl] = *reinterpret_cast<const v4i*>(pb + pl * GI_PLANE);
+      );
+      // order: consecutive instructions hit different accumulators
+      EOQ_SFOR(rot, 4,
+        EOQ_SFOR(pl, 4,
+          constexpr int ql = (pl + rot) & 3;
+          acc[pl + ql] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[pl], b[ql], acc[pl + ql], 0, 0, 0);
+        );
+      );
+      // into double precision with the exponents of rows 4 kg + v (tile I) and column l16 (tile J)
+      const int ej = cexp[16 * tJ + l16];
+      const int4 ei = *reinterpret_cast<const int4*>(cexp + 16 * tI + 4 * kg);
+      const int eiv[4] = {ei.x, ei.y, ei.z, ei.w};
+      EOQ_SFOR(v, 4,
+        double val = (double)acc[6][v];
+        EOQ_SFOR(cd, 6, val = fma(val, 256.0, (double)acc[5 - cd][v]););
+        Gacc[s][v] += ldexp(val, eiv[v] + ej);
+      );
+    );
+  }
+  // ---- tiles change lanes: three rounds of twelve tiles through LDS; lane (ty, tx) takes element (ty, tx) of tile
+  // (a, b) as A[a * 8 + b] and, for a < b, element (tx, ty) as A[b * 8 + a] ----
+  double* Tl = reinterpret_cast<double*>(pool);
+  const int ty = tid >> 4, tx = tid & 15;
+  EOQ_SFOR(rd, 3,
+    __syncthreads();
+    EOQ_SFOR(s3, 3,
+      constexpr int s = 3 * rd + s3;
+      double* dst = Tl + (wave + 4 * s3) * 16 * XPAD;
+      EOQ_SFOR(v, 4, dst[(4 * kg + v) * XPAD + l16] = Gacc[s][v];);
+    );
+    __syncthreads();
+    EOQ_SFOR(pp, 12,
+      constexpr int tile = 12 * rd + pp;
+      constexpr int a = UT_I[tile]; constexpr int b = UT_J[tile];
+      A[a * 8 + b] = Tl[pp * 16 * XPAD + ty * XPAD + tx];
+      if constexpr (a != b) A[b * 8 + a] = Tl[pp * 16 * XPAD + tx * XPAD + ty];
+    );
   );
 }
 
@@ -528,8 +690,11 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     int* __restrict__ fb_list, int* __restrict__ fb_count, double* __restrict__ lam_out, float* __restrict__ wfac,
     double* __restrict__ tri, int32_t* __restrict__ rank_out, float* __restrict__ phi_out, float* __restrict__ sigma_out,
     uint16_t* __restrict__ rfac, uint32_t* __restrict__ flags_out) {
-  __shared__ __align__(16) unsigned char u1[U1_BYTES];
-  __shared__ float refl[REFL_LEN];
+  // one pool, used in turn by the Gram stage (byte planes / float strip), the reduction (reflectors) and the
+  // eigenvector stage (u1)
+  __shared__ __align__(16) unsigned char pool[POOL_BYTES];
+  float* refl = reinterpret_cast<float*>(pool);
+  unsigned char* u1 = pool + REFL_BYTES;
   __shared__ __align__(16) double vbuf[2][D];
   __shared__ __align__(16) double pbuf[D];
   __shared__ __align__(16) double2 de[D + 1];  // (d_i, e_{i-1}^2) of the scaled tridiagonal matrix; de[D] = 0
@@ -553,7 +718,11 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
 
   {
     double A[64];
-    gram_cyclic(blocks, dtype, blk * (size_t)n * D, n, reinterpret_cast<float*>(u1), tid, A);
+    if (dtype == EOQ_F16)
+      gram_int8(static_cast<const uint16_t*>(blocks) + blk * (size_t)n * D, n, pool, tid, A);
+    else
+      gram_cyclic(blocks, dtype, blk * (size_t)n * D, n, reinterpret_cast<float*>(u1), tid, A);
+    __syncthreads();  // the pool changes hands
     EOQ_SFOR(s, 8, householder_stage<s>(A, tid, vbuf, pbuf, refl, dT, eT, betaT););
     // the last 2x2 block of T: rows and columns 126, 127 sit in the sub-tile (7, 7) of lanes ty, tx >= 14
     const int ty = tid >> 4, tx = tid & 15;
@@ -577,7 +746,8 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       for (int m = 0; m < 8; ++m) {
         const int i = l + 16 * m;
         const float ra = refl[min(max(roa + i, 0), REFL_LEN - 1)], rb = refl[min(max(rob + i, 0), REFL_LEN - 1)];
-        acc = fma((kb < D - 2 && i > kb) ? (double)ra : 0.0, (double)rb, acc);
+        const bool in = (kb < D - 2 && i > kb);  // both factors masked: what lies outside a reflector is arbitrary
+        acc = fma(in ? (double)ra : 0.0, in ? (double)rb : 0.0, acc);
       }
       acc = row16_sum_uniform(acc);
       if (l == 0) cW[q] = acc;
