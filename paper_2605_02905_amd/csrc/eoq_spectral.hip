@@ -658,30 +658,40 @@ __device__ __forceinline__ void sturm_steps4(const double (&t)[8], double x, dou
     p = pn;
   }
 }
+__device__ __forceinline__ void sturm_renorm(double& pm, double& p) {  // |p| into [1/2, 1), same factor on both
+  const int e = __builtin_amdgcn_frexp_exp(p);
+  p = ldexp(p, -e);
+  pm = ldexp(pm, -e);
+}
 __device__ __forceinline__ int sturm_count(sc_double* de, double x) {
   double pm = 0.0, p = 1.0;  // p_{-2}, p_{-1}
   unsigned m = 0u;           // sign history, newest in bit 0; p_{-1} > 0
   int cnt = 0;
-  double ta[8], tb[8];
+  // operands in groups of four steps (64 bytes), requested two groups ahead: three buffers in rotation
+  double t0[8], t1[8], t2[8];
 #pragma unroll
-  for (int q = 0; q < 8; ++q) ta[q] = de[q];
-#pragma unroll 1
-  for (int c = 0; c < D / 8; ++c) {
-    // two groups of four steps; the operands of each group (64 bytes) are requested one group ahead
-#pragma unroll
-    for (int q = 0; q < 8; ++q) tb[q] = de[16 * c + 8 + q];
-    sturm_steps4(ta, x, pm, p, m);
-    if (c + 1 < D / 8) {
-#pragma unroll
-      for (int q = 0; q < 8; ++q) ta[q] = de[16 * c + 16 + q];
-    }
-    sturm_steps4(tb, x, pm, p, m);
-    // renormalise the pair: |p| into [1/2, 1)
-    const int e = __builtin_amdgcn_frexp_exp(p);
-    p = ldexp(p, -e);
-    pm = ldexp(pm, -e);
-    cnt += __popc((m ^ (m >> 1)) & 0xFFu);  // bit 8 is the sign that preceded these eight
+  for (int q = 0; q < 8; ++q) {
+    t0[q] = de[q];
+    t1[q] = de[8 + q];
   }
+#pragma unroll 1
+  for (int c = 0; c < 10; ++c) {  // groups 3c, 3c+1, 3c+2
+    sc_double* g = de + 24 * c;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t2[q] = g[16 + q];
+    sturm_steps4(t0, x, pm, p, m);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t0[q] = g[24 + q];
+    sturm_steps4(t1, x, pm, p, m);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t1[q] = g[32 + q];
+    sturm_steps4(t2, x, pm, p, m);
+    sturm_renorm(pm, p);
+    cnt += __popc((m ^ (m >> 1)) & 0xFFFu);  // bit 12 is the sign that preceded these twelve
+  }
+  sturm_steps4(t0, x, pm, p, m);  // groups 30 and 31
+  sturm_steps4(t1, x, pm, p, m);
+  cnt += __popc((m ^ (m >> 1)) & 0xFFu);
   return cnt;
 }
 
