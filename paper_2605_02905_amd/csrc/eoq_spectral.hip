@@ -300,7 +300,8 @@ constexpr int PAIR_B[28] = {1, 2, 3, 4, 5, 6, 7, 2, 3, 4, 5, 6, 7, 3, 4, 5, 6, 7
 // packed reflector storage: reflector k has entries i = k+1 .. 127
 __device__ __forceinline__ int refl_off(int k) { return k * (D - 1) - (k * (k - 1)) / 2; }
 constexpr int REFL_LEN = (D - 1) * D / 2;  // 8128
-constexpr int MULTISECT_ITERS = 34;        // 3^34 > 2^53
+constexpr int GRID_POINTS = 256;           // first localisation: one Sturm count per lane on a uniform grid
+constexpr int MULTISECT_ITERS = 26;        // then trisection: 3^26 * 257 > 2^49 (the reduction itself is good to ~2^-48)
 constexpr int EV_BATCH = 8;                // eigenvectors per twisted-factorisation pass
 constexpr int U1_BYTES = EV_BATCH * 4 * D * 8;  // 32 KB: twisted-factorisation scratch; also the Gram strip (16 KB)
 constexpr double CLUSTER_TOL = 1e-10;      // relative gap below which retained eigenvalues count as repeated
@@ -794,6 +795,21 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     sc_double* sde = reinterpret_cast<sc_double*>(tri_addr);
     const int j = tid >> 1, sub = tid & 1;
     double lo = -0x1.0p-40, hi = 1.0 + 0x1.0p-40;   // G is positive semi-definite; Gershgorin bounds the top by 1
+    {
+      // every lane counts at one point of a uniform grid; each eigenvalue then starts from its grid cell
+      int* cnt_s = reinterpret_cast<int*>(atoms);
+      const double step = 1.0 / (GRID_POINTS + 1);
+      cnt_s[tid] = sturm_count(sde, (tid + 1) * step);
+      __syncthreads();
+      int gl = -1, gh = GRID_POINTS;  // counts at these grid points: <= j and > j
+#pragma unroll
+      for (int b = 0; b < 8; ++b) {
+        const int mid = (gl + gh) >> 1;
+        if (cnt_s[mid] > j) gh = mid; else gl = mid;
+      }
+      if (gl >= 0) lo = (gl + 1) * step;
+      if (gh < GRID_POINTS) hi = (gh + 1) * step;
+    }
 #pragma unroll 1
     for (int it = 0; it < MULTISECT_ITERS; ++it) {
       const double third = (hi - lo) * (1.0 / 3.0);
