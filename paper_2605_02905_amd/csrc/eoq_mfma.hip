@@ -111,11 +111,51 @@ __device__ __forceinline__ H8 centroids_of(const uint32_t (&byte)[BITS], const u
 }
 
 // ---------------------------------------------------------------------------------------------
-// decode: one workgroup per block
+// decode: persistent workgroups, each walking blocks blockIdx.x, blockIdx.x + gridDim.x, ...  The rotation
+// operands are loaded once per workgroup; the record bytes of the next 128 tokens (of this block or the next) are
+// requested while the current 128 go through the matrix cores, so reads stay in flight across the barriers.
 // ---------------------------------------------------------------------------------------------
+// What one thread requests of a chunk of 128 tokens: lane (l32, hf) of wave w unpacks half of token 32 w + l32;
+// thread tid also carries 8 tokens of row (tid + 256 u) / 16 of the left factors, u = 0, 1.
+template <int BITS>
+struct DecodeFetch {
+  uint4 pl[BITS];  // the token's bit-planes
+  uint4 cf[2];     // left factors C[i][8 seg .. 8 seg + 7], (i, seg) = ((tid + 256 u) / 16, tid % 16), if i < r
+  uint16_t rho;    // the token's stored norm
+  int r;           // rank of the block the chunk belongs to
+};
+template <int BITS>
+__device__ __forceinline__ void decode_fetch(DecodeFetch<BITS>& f, int64_t blk, int t0, int n, int r_max, int tid, int tl,
+                                             const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
+                                             const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac) {
+  constexpr int ROWB = BITS * D / 8;
+  const size_t tok = (size_t)blk * n + t0 + tl;
+  f.r = rank_in[blk];
+#pragma unroll
+  for (int p = 0; p < BITS; ++p) f.pl[p] = *reinterpret_cast<const uint4*>(codes + tok * ROWB + p * 16);
+  f.rho = norms[tok];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int i = (tid + THREADS * u) >> 4, seg = tid & 15;
+    f.cf[u] = (i < f.r) ? *reinterpret_cast<const uint4*>(lfac + ((size_t)blk * r_max + i) * n + t0 + 8 * seg)
+                        : make_uint4(0u, 0u, 0u, 0u);
+  }
+}
+// right factors of a block as B operand of the low-rank product: V[i][jcol], i = 16 k2 + 8 hf + e
+__device__ __forceinline__ void decode_fetch_v(H8 (&Bv)[2], int64_t blk, int r, int r_max, int jcol, int hf,
+                                               const uint16_t* __restrict__ rfac) {
+#pragma unroll
+  for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int i = 16 * k2 + 8 * hf + e;
+      Bv[k2].s[e] = (i < r) ? rfac[((size_t)blk * r_max + i) * D + jcol] : (uint16_t)0;
+    }
+}
+
 template <int BITS>
 __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
-    int n, int r_max, const uint16_t* __restrict__ pih, const float* __restrict__ tab,
+    int n, int r_max, int64_t B, const uint16_t* __restrict__ pih, const float* __restrict__ tab,
     const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms, const int32_t* __restrict__ rank_in,
     const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac, uint16_t* __restrict__ out) {
   __shared__ __align__(16) uint16_t Z[CHUNK * ZLD];    // centroid values of the chunk, [token][coordinate]
@@ -125,15 +165,16 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
-  const size_t blk = blockIdx.x;
-  const int r = rank_in[blk];
   const int jcol = 32 * wave + l32;  // output column of this lane
+  const int tl = 32 * wave + l32;    // token of the chunk this lane unpacks
 
   build_mask_table(mask_tab, tid);
+  // components beyond a block's rank meet a zero right factor: whatever Ct holds there only has to be finite
+  for (int e = tid; e < CHUNK * CLD / 8; e += THREADS) *reinterpret_cast<uint4*>(&Ct[e * 8]) = make_uint4(0u, 0u, 0u, 0u);
   Mags<BITS> mg;
   mg.load(tab);
 
-  // stationary operands: Pi^T rows j (hi, lo) and the stored right factors V[i][j]
+  // stationary operands: Pi^T rows j (hi, lo)
   const uint16_t* pit_hi = pih + 2 * D * D;
   const uint16_t* pit_lo = pih + 3 * D * D;
   H8 Bhi[8], Blo[8];
@@ -142,87 +183,106 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
     Bhi[kk].u = *reinterpret_cast<const uint4*>(pit_hi + jcol * D + 16 * kk + 8 * hf);
     Blo[kk].u = *reinterpret_cast<const uint4*>(pit_lo + jcol * D + 16 * kk + 8 * hf);
   }
-  H8 Bv[2];
-#pragma unroll
-  for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int i = 16 * k2 + 8 * hf + e;
-      Bv[k2].s[e] = (i < r) ? rfac[(blk * r_max + i) * D + jcol] : (uint16_t)0;
-    }
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
-  constexpr int ROWB = BITS * D / 8;
 
-  for (int t0 = 0; t0 < n; t0 += CHUNK) {
-    __syncthreads();  // previous chunk consumed; also orders the mask table before its first use
-    // ---- phase 1: wave w prepares tile w (tokens t0 + 32w + l32) ----
-    {
-      const int tl = 32 * wave + l32;  // token within the chunk
-      const size_t tok = blk * (size_t)n + t0 + tl;
-      uint4 pl[BITS];
-#pragma unroll
-      for (int p = 0; p < BITS; ++p) pl[p] = *reinterpret_cast<const uint4*>(codes + tok * ROWB + p * 16);
+  DecodeFetch<BITS> cur, nxt;
+  H8 Bv[2], Bvn[2];
+  if ((int64_t)blockIdx.x < B) {
+    decode_fetch<BITS>(cur, blockIdx.x, 0, n, r_max, tid, tl, codes, norms, rank_in, lfac);
+    decode_fetch_v(Bv, blockIdx.x, cur.r, r_max, jcol, hf, rfac);
+  }
+  for (int64_t blk = blockIdx.x; blk < B; blk += gridDim.x) {
+    const int r = cur.r;
+    for (int t0 = 0; t0 < n; t0 += CHUNK) {
+      __syncthreads();  // previous chunk consumed; also orders the mask table and the cleared Ct before first use
+      // ---- phase 1: wave w prepares tile w (tokens t0 + 32w + l32) from the prefetched record bytes ----
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         uint32_t byte[BITS];
 #pragma unroll
         for (int p = 0; p < BITS; ++p) {
-          const uint32_t wsel = (kk < 2) ? pl[p].x : (kk < 4) ? pl[p].y : (kk < 6) ? pl[p].z : pl[p].w;
+          const uint32_t wsel = (kk < 2) ? cur.pl[p].x : (kk < 4) ? cur.pl[p].y : (kk < 6) ? cur.pl[p].z : cur.pl[p].w;
           byte[p] = (wsel >> (16 * (kk & 1) + 8 * hf)) & 0xFFu;   // plane byte 2 kk + hf
         }
         const H8 c = centroids_of<BITS>(byte, mask_tab, mg);
         *reinterpret_cast<uint4*>(&Z[tl * ZLD + 16 * kk + 8 * hf]) = c.u;
       }
-      if (hf == 0) rho_s[tl] = half_bits_to_float(norms[tok]) * inv_sqrt_d;
+      if (hf == 0) rho_s[tl] = half_bits_to_float(cur.rho) * inv_sqrt_d;
 #pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2) {
-        H8 c;
+      for (int u = 0; u < 2; ++u) {
+        const int i = (tid + THREADS * u) >> 4, seg = tid & 15;
+        if (i < r) {
+          H8 c;
+          c.u = cur.cf[u];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int i = 16 * k2 + 8 * hf + e;
-          c.s[e] = (i < r) ? lfac[(blk * r_max + i) * (size_t)n + t0 + tl] : (uint16_t)0;
+          for (int x = 0; x < 8; ++x) Ct[(8 * seg + x) * CLD + i] = c.s[x];
         }
-        *reinterpret_cast<uint4*>(&Ct[tl * CLD + 16 * k2 + 8 * hf]) = c.u;
       }
-    }
-    __syncthreads();
-    // ---- phase 2: wave w produces columns 32w .. 32w+31 of every tile ----
+      // ---- request the next chunk (of this block or of the next one) ----
+      const bool last = (t0 + CHUNK >= n);
+      {
+        const int64_t nb = last ? blk + gridDim.x : blk;
+        if (nb < B) {
+          decode_fetch<BITS>(nxt, nb, last ? 0 : t0 + CHUNK, n, r_max, tid, tl, codes, norms, rank_in, lfac);
+          if (last) decode_fetch_v(Bvn, nb, nxt.r, r_max, jcol, hf, rfac);
+        }
+      }
+      __syncthreads();
+      // ---- phase 2: wave w produces columns 32w .. 32w+31 of every tile; two tiles at a time so that consecutive
+      // matrix instructions never wait for each other's accumulator ----
 #pragma unroll 1
-    for (int tau = 0; tau < CHUNK / 32; ++tau) {
-      float16v acc;
+      for (int tau = 0; tau < CHUNK / 32; tau += 2) {
+        float16v acc[2];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-      const int arow = 32 * tau + l32;
+        for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.0f;
+        const int arow = 32 * tau + l32;
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        H8 a;
-        a.u = *reinterpret_cast<const uint4*>(&Z[arow * ZLD + 16 * kk + 8 * hf]);
-        acc = mfma16(a, Bhi[kk], acc);
-        acc = mfma16(a, Blo[kk], acc);
-      }
+        for (int kk = 0; kk < 8; ++kk) {
+          H8 a0, a1;
+          a0.u = *reinterpret_cast<const uint4*>(&Z[arow * ZLD + 16 * kk + 8 * hf]);
+          a1.u = *reinterpret_cast<const uint4*>(&Z[(arow + 32) * ZLD + 16 * kk + 8 * hf]);
+          acc[0] = mfma16(a0, Bhi[kk], acc[0]);
+          acc[1] = mfma16(a1, Bhi[kk], acc[1]);
+          acc[0] = mfma16(a0, Blo[kk], acc[0]);
+          acc[1] = mfma16(a1, Blo[kk], acc[1]);
+        }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 s = *reinterpret_cast<const float4*>(&rho_s[32 * tau + 8 * q + 4 * hf]);
-        acc[4 * q + 0] *= s.x;
-        acc[4 * q + 1] *= s.y;
-        acc[4 * q + 2] *= s.z;
-        acc[4 * q + 3] *= s.w;
-      }
-      if (r > 0) {
+        for (int h2 = 0; h2 < 2; ++h2) {
 #pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) {
-          if (16 * k2 < r) {
-            H8 a;
-            a.u = *reinterpret_cast<const uint4*>(&Ct[arow * CLD + 16 * k2 + 8 * hf]);
-            acc = mfma16(a, Bv[k2], acc);
+          for (int q = 0; q < 4; ++q) {
+            const float4 s = *reinterpret_cast<const float4*>(&rho_s[32 * (tau + h2) + 8 * q + 4 * hf]);
+            acc[h2][4 * q + 0] *= s.x;
+            acc[h2][4 * q + 1] *= s.y;
+            acc[h2][4 * q + 2] *= s.z;
+            acc[h2][4 * q + 3] *= s.w;
+          }
+        }
+        if (r > 0) {
+#pragma unroll
+          for (int k2 = 0; k2 < 2; ++k2) {
+            if (16 * k2 < r) {
+              H8 a0, a1;
+              a0.u = *reinterpret_cast<const uint4*>(&Ct[arow * CLD + 16 * k2 + 8 * hf]);
+              a1.u = *reinterpret_cast<const uint4*>(&Ct[(arow + 32) * CLD + 16 * k2 + 8 * hf]);
+              acc[0] = mfma16(a0, Bv[k2], acc[0]);
+              acc[1] = mfma16(a1, Bv[k2], acc[1]);
+            }
+          }
+        }
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          uint16_t* dst = out + ((size_t)blk * n + t0 + 32 * (tau + h2)) * D + jcol;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = 8 * (v >> 2) + 4 * hf + (v & 3);
+            dst[(size_t)row * D] = float_to_half_bits(acc[h2][v]);
           }
         }
       }
-      uint16_t* dst = out + (blk * (size_t)n + t0 + 32 * tau) * D + jcol;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = 8 * (v >> 2) + 4 * hf + (v & 3);
-        dst[(size_t)row * D] = float_to_half_bits(acc[v]);
+      cur = nxt;
+      if (last) {
+        Bv[0] = Bvn[0];
+        Bv[1] = Bvn[1];
       }
     }
   }
@@ -563,10 +623,11 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
 // ---------------------------------------------------------------------------------------------
 hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void* out_fp16) {
   if (L.ev) (void)hipEventRecord(L.ev[4], L.stream);
-  const dim3 grid((unsigned)B), block(THREADS);
+  // persistent workgroups: two per compute unit, each walks the blocks with that stride
+  const dim3 grid((unsigned)(B < 512 ? B : 512)), block(THREADS);
   uint16_t* out = static_cast<uint16_t*>(out_fp16);
-#define EOQ_DECODE(BITS)                                                                                          \
-  hipLaunchKernelGGL(eoq_decode_mfma_kernel<BITS>, grid, block, 0, L.stream, L.n, L.r_max, L.pih, L.tab, in.codes, \
+#define EOQ_DECODE(BITS)                                                                                             \
+  hipLaunchKernelGGL(eoq_decode_mfma_kernel<BITS>, grid, block, 0, L.stream, L.n, L.r_max, B, L.pih, L.tab, in.codes, \
                      in.norms, in.rank, in.lfac, in.rfac, out)
   switch (L.bits) {
     case 1: EOQ_DECODE(1); break;
