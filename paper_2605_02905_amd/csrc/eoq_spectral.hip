@@ -512,28 +512,58 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, int 
   );
 }
 
-// Sum over the 16 lanes of a DPP row of 8 values per lane, transposing as it folds: on return lane tx holds the
-// row total of value number tx / 2 (so each total sits in two adjacent lanes).  Partners: 15 - tx, tx ^ 7, tx ^ 2,
-// tx ^ 1; at each of the first three folds a lane keeps the half of its values selected by one bit of tx and
-// hands the other half to its partner.
-__device__ __forceinline__ double row16_fold8(const double (&p)[8], int tx) {
+// Sum over the 16 lanes of a DPP row of the values p[S .. 7] of every lane (the values below S are dead),
+// transposing as it folds: on return lane tx holds the row total of value number fold_index<S>(tx), and the lanes
+// with fold_writer<S>(tx) hold each live total exactly once.  Partners: 15 - tx, tx ^ 7, tx ^ 2, tx ^ 1; at a
+// transposing fold a lane keeps the half of its values selected by one bit of tx and hands the other half to its
+// partner; once only half of the values are live that fold is a plain sum.
+template <int S>
+__device__ __forceinline__ int fold_index(int tx) {
+  if constexpr (S < 4) return tx >> 1;
+  else if constexpr (S < 6) return 4 + ((tx >> 1) & 3);
+  else if constexpr (S == 6) return 6 + ((tx >> 1) & 1);
+  else return 7;
+}
+template <int S>
+__device__ __forceinline__ bool fold_writer(int tx) {
+  if constexpr (S < 4) return (tx & 1) == 0;
+  else if constexpr (S < 6) return (tx & 9) == 0;
+  else if constexpr (S == 6) return (tx & 13) == 0;
+  else return tx == 0;
+}
+template <int S>
+__device__ __forceinline__ double row16_fold(const double (&p)[8], int tx) {
   const bool b3 = (tx & 8) != 0, b2 = (tx & 4) != 0, b1 = (tx & 2) != 0;
-  double r1[4], r2[2];
+  double r1[4], r2[2], r3;
+  if constexpr (S < 4) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const double send = b3 ? p[i] : p[4 + i];
-    const double keep = b3 ? p[4 + i] : p[i];
-    r1[i] = keep + dpp_mov<0x140>(send);  // row_mirror
-  }
+    for (int i = 0; i < 4; ++i) {
+      const double send = b3 ? p[i] : p[4 + i];
+      const double keep = b3 ? p[4 + i] : p[i];
+      r1[i] = keep + dpp_mov<0x140>(send);  // row_mirror
+    }
+  } else {
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const double send = b2 ? r1[i] : r1[2 + i];
-    const double keep = b2 ? r1[2 + i] : r1[i];
-    r2[i] = keep + dpp_mov<0x141>(send);  // row_half_mirror
+    for (int i = 0; i < 4; ++i) r1[i] = (4 + i >= S) ? p[4 + i] + dpp_mov<0x140>(p[4 + i]) : 0.0;
   }
-  const double send = b1 ? r2[0] : r2[1];
-  const double keep = b1 ? r2[1] : r2[0];
-  const double r3 = keep + dpp_mov<0x4E>(send);
+  if constexpr (S < 6) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const double send = b2 ? r1[i] : r1[2 + i];
+      const double keep = b2 ? r1[2 + i] : r1[i];
+      r2[i] = keep + dpp_mov<0x141>(send);  // row_half_mirror
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) r2[i] = (6 + i >= S) ? r1[2 + i] + dpp_mov<0x141>(r1[2 + i]) : 0.0;
+  }
+  if constexpr (S < 7) {
+    const double send = b1 ? r2[0] : r2[1];
+    const double keep = b1 ? r2[1] : r2[0];
+    r3 = keep + dpp_mov<0x4E>(send);
+  } else {
+    r3 = r2[1] + dpp_mov<0x4E>(r2[1]);
+  }
   return r3 + dpp_mov<0xB1>(r3);
 }
 
@@ -620,8 +650,8 @@ __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, doub
         } else {
           part[a] = 0.0;
         });
-      const double tot = row16_fold8(part, tx);
-      if ((tx & 1) == 0) pbuf[ty + 16 * (tx >> 1)] = beta * tot;
+      const double tot = row16_fold<S>(part, tx);
+      if (fold_writer<S>(tx)) pbuf[ty + 16 * fold_index<S>(tx)] = beta * tot;
     }
     __syncthreads();
     // v^T p from the column entries this lane holds anyway, summed over its DPP row (every row of 16 lanes covers
