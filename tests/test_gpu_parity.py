@@ -255,3 +255,96 @@ def test_argument_errors_on_device():
     out = torch.zeros(1, 6, 1024, device=DEV)
     assert L.eoq_scores(ctx._h, rec.c_struct(), 1, 4, 1, q.data_ptr(), 6, out.data_ptr(), None) == eoq.EOQ_ERR_UNSUPPORTED
     torch.cuda.synchronize()
+
+
+def _subset(rec, idx):
+    sel = torch.as_tensor(idx, device=rec.rank.device)
+    return eoq.Packed(*(t.index_select(0, sel) for t in (rec.codes, rec.norms, rec.rank, rec.phi, rec.sigma, rec.lfac,
+                                                         rec.rfac, rec.flags)))
+
+
+@pytest.mark.parametrize("cfg,stride", [(2, 37), (5, 331)])
+def test_full_size_batches_in_the_bench_launch_configuration(cfg, stride):
+    """The whole batch of a benchmark workload in ONE eoq_compress / eoq_decompress / eoq_scores launch each, as
+    bench.py issues them (config 2: 1024 blocks, config 5: 16384 blocks); a strided sample of the blocks is checked
+    against the oracle to the same bars, and every block against properties that hold at any size."""
+    spec = synth.config(cfg)
+    blocks, _ = synth.make_blocks(spec, device=DEV)
+    B, n, bits = blocks.shape[0], spec.n, 2
+    ctx = eoq.Context(n=n, bits=bits)
+    rec, ws = ctx.eoq_compress(blocks)
+    xhat = ctx.eoq_decompress(rec)
+    torch.cuda.synchronize()
+    # properties of every block: rank within range, flags clean, finite outputs, reconstruction error below the
+    # error of the uncompressed zero estimate, eigenvalues ordered and non-negative
+    rank = rec.rank.cpu().numpy()
+    assert rank.min() >= 0 and rank.max() <= ctx.r_max
+    assert not np.any(rec.flags.cpu().numpy() & 4)
+    assert bool(torch.isfinite(xhat).all())
+    err = (xhat.float() - blocks.float()).flatten(1).norm(dim=1) / blocks.float().flatten(1).norm(dim=1).clamp_min(1e-30)
+    assert float(err.max()) < 0.7, float(err.max())
+    lam_all = ctx.spectrum(ws, B)
+    assert bool((lam_all[:, :-1] >= lam_all[:, 1:]).all()) and float(lam_all.min()) >= 0.0
+    # sampled blocks against the oracle
+    idx = list(range(0, B, stride))
+    b64 = blocks[idx].double().cpu().numpy()
+    recs = U.oracle_compress(b64, bits)
+    st = U.compare_compress(b64, _subset(rec, idx), lam_all[idx].cpu().numpy(), recs, bits)
+    U.log_stats(f"cfg{cfg}-full-sampled{len(idx)}", st)
+    assert st["max_lam_rel"] < 1e-9
+    Pi, cb = U.oracle_tables(bits)
+    xs = xhat[idx].cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for k_, r in enumerate(recs):
+        e_g, e_o = U.rel_fro(b64[k_], xs[k_]), U.rel_fro(b64[k_], oracle.decompress_block(r, Pi, cb))
+        worst = max(worst, abs(e_g - e_o) / e_o)
+    assert worst <= 1e-3, worst
+    # scores of the first sequence's first KV head over all its blocks, one launch over the whole key set
+    n_kv, group = 8, 4
+    bph = spec.blocks_per_tensor if cfg != 5 else B // (16 * n_kv)
+    n_seq = 1 if cfg != 5 else 16
+    key_blocks = n_seq * n_kv * bph
+    keys = _subset(rec, list(range(key_blocks)))
+    q = synth.make_queries(n_seq, n_kv * group, device=DEV)
+    sc = ctx.eoq_scores(keys, q, n_kv)
+    torch.cuda.synchronize()
+    sc = sc.cpu().numpy()
+    qn = q.double().cpu().numpy()
+    scale = math.sqrt(128.0)
+    for blk in [b for b in idx if b < key_blocks][:8]:
+        r = recs[idx.index(blk)]
+        s_, kv, jb = blk // (n_kv * bph), (blk // bph) % n_kv, blk % bph
+        xb = xhat[blk].double().cpu().numpy()
+        for h in range(group):
+            got = sc[s_, kv * group + h, jb * n:(jb + 1) * n]
+            # the fused scores against the decompressed block of the same record (binary16 rounding of x_hat apart)
+            ref_g = xb @ qn[s_, kv * group + h] / scale
+            assert np.max(np.abs(got - ref_g)) <= 2e-3 * max(1.0, float(np.max(np.abs(ref_g)))), (blk, h)
+            # and against the oracle's scores of its own record (the records differ in a few code indices)
+            ref_o = oracle.score_block(qn[s_, kv * group + h], r, Pi, cb)
+            assert np.max(np.abs(got - ref_o)) <= 5e-2 * max(1.0, float(np.max(np.abs(ref_o)))), (blk, h)
+
+
+def test_second_call_reuses_the_workspace_with_other_data():
+    """Two calls in a row on the same context, record and workspace with different blocks: nothing of the first
+    call (eigenvalues, tridiagonal scratch read through the scalar cache, hand-over list) leaks into the second."""
+    spec = synth.config(2)
+    a, _ = synth.make_blocks(spec, tensors=range(1))
+    b, _ = synth.make_blocks(spec, seed=synth.SEED_BASE + 77, tensors=range(1))
+    assert not torch.equal(a, b)
+    ctx = eoq.Context(n=spec.n, bits=2)
+    rec, ws = ctx.eoq_compress(a.to(DEV).contiguous())
+    rec, ws = ctx.eoq_compress(b.to(DEV).contiguous(), rec, ws)
+    torch.cuda.synchronize()
+    lam = ctx.spectrum(ws, b.shape[0]).cpu().numpy()
+    b64 = b.double().numpy()
+    recs = U.oracle_compress(b64, 2)
+    st = U.compare_compress(b64, rec, lam, recs, 2)
+    assert st["max_lam_rel"] < 1e-9
+    # and bit for bit what a fresh context, record and workspace give
+    ctx2 = eoq.Context(n=spec.n, bits=2)
+    rec2, ws2 = ctx2.eoq_compress(b.to(DEV).contiguous())
+    torch.cuda.synchronize()
+    for t1, t2 in ((rec.codes, rec2.codes), (rec.norms, rec2.norms), (rec.rank, rec2.rank), (rec.phi, rec2.phi)):
+        assert torch.equal(t1, t2)
+    assert torch.equal(ctx.spectrum(ws, b.shape[0]), ctx2.spectrum(ws2, b.shape[0]))
