@@ -296,7 +296,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
 // ---------------------------------------------------------------------------------------------
 typedef float float4v __attribute__((ext_vector_type(4)));
 constexpr int SC_MAXG = 8;
-constexpr int SC_RUN = 16;  // blocks per workgroup
+constexpr int SC_RUN_MAX = 16;  // most blocks per workgroup (the run is shortened until the grid fills the chip)
 
 __device__ __forceinline__ float4v mfma32(const H8& a, const H8& b, float4v c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c, 0, 0, 0);
@@ -308,7 +308,7 @@ __device__ __forceinline__ void split_half(float v, uint16_t& hi, uint16_t& lo) 
 
 template <int BITS>
 __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
-    int n, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, const float* __restrict__ pit,
+    int n, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, int run, const float* __restrict__ pit,
     const float* __restrict__ tab, const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
     const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac,
     const uint16_t* __restrict__ q, float* __restrict__ scores) {
@@ -349,8 +349,8 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
     }
 
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
-  const int64_t j_end = min((int64_t)(blockIdx.x + 1) * SC_RUN, blocks_per_head);
-  for (int64_t jb = (int64_t)blockIdx.x * SC_RUN; jb < j_end; ++jb) {
+  const int64_t j_end = min((int64_t)(blockIdx.x + 1) * run, blocks_per_head);
+  for (int64_t jb = (int64_t)blockIdx.x * run; jb < j_end; ++jb) {
     const size_t blk = sg * (size_t)blocks_per_head + jb;
     const int r = rank_in[blk];
     __syncthreads();
@@ -370,40 +370,60 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
       const float v = (l16 < group && i < r) ? wbuf[l16 * EOQ_RMAX_CAP + i] : 0.0f;
       split_half(v, Aw_hi.s[e], Aw_lo.s[e]);
     }
-    for (int tile = wave; tile < n / 16; tile += THREADS / 64) {
-      const int t = 16 * tile + l16;
-      const size_t tok = blk * (size_t)n + t;
-      uint32_t word[BITS];
+    // two tiles of 16 tokens per pass (n / 16 is a multiple of 8): their loads are issued together and their
+    // accumulator chains are independent
+    for (int tile = wave; tile < n / 16; tile += 2 * (THREADS / 64)) {
+      uint32_t word[2][BITS];
+      H8 c[2];
+      float rho[2];
 #pragma unroll
-      for (int p = 0; p < BITS; ++p) word[p] = *reinterpret_cast<const uint32_t*>(codes + tok * ROWB + p * 16 + 4 * g);
-      float4v acc1 = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};
+      for (int u = 0; u < 2; ++u) {
+        const int t = 16 * (tile + u * (THREADS / 64)) + l16;
+        const size_t tok = blk * (size_t)n + t;
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) word[u][p] = *reinterpret_cast<const uint32_t*>(codes + tok * ROWB + p * 16 + 4 * g);
+        if (r > 0) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int i = 8 * g + e;
+            c[u].s[e] = (i < r) ? lfac[(blk * r_max + i) * (size_t)n + t] : (uint16_t)0;
+          }
+        }
+        rho[u] = half_bits_to_float(norms[tok]) * inv_sqrt_d;
+      }
+      float4v acc1[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        uint32_t byte[BITS];
+        H8 bhi[2], blo[2];
 #pragma unroll
-        for (int p = 0; p < BITS; ++p) byte[p] = (word[p] >> (8 * kk)) & 0xFFu;
-        H8 blo;
-        const H8 bhi = centroids_of<BITS, true>(byte, mask_tab, mg, &blo);
-        acc1 = mfma32(Aq_hi[kk], bhi, acc1);
-        acc1 = mfma32(Aq_lo[kk], bhi, acc1);
-        acc1 = mfma32(Aq_hi[kk], blo, acc1);
+        for (int u = 0; u < 2; ++u) {
+          uint32_t byte[BITS];
+#pragma unroll
+          for (int p = 0; p < BITS; ++p) byte[p] = (word[u][p] >> (8 * kk)) & 0xFFu;
+          bhi[u] = centroids_of<BITS, true>(byte, mask_tab, mg, &blo[u]);
+        }
+        acc1[0] = mfma32(Aq_hi[kk], bhi[0], acc1[0]);
+        acc1[1] = mfma32(Aq_hi[kk], bhi[1], acc1[1]);
+        acc1[0] = mfma32(Aq_lo[kk], bhi[0], acc1[0]);
+        acc1[1] = mfma32(Aq_lo[kk], bhi[1], acc1[1]);
+        acc1[0] = mfma32(Aq_hi[kk], blo[0], acc1[0]);
+        acc1[1] = mfma32(Aq_hi[kk], blo[1], acc1[1]);
       }
       if (r > 0) {
-        H8 c;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int i = 8 * g + e;
-          c.s[e] = (i < r) ? lfac[(blk * r_max + i) * (size_t)n + t] : (uint16_t)0;
-        }
-        acc2 = mfma32(Aw_hi, c, acc2);
-        acc2 = mfma32(Aw_lo, c, acc2);
+        acc2[0] = mfma32(Aw_hi, c[0], acc2[0]);
+        acc2[1] = mfma32(Aw_hi, c[1], acc2[1]);
+        acc2[0] = mfma32(Aw_lo, c[0], acc2[0]);
+        acc2[1] = mfma32(Aw_lo, c[1], acc2[1]);
       }
-      const float rho = half_bits_to_float(norms[tok]) * inv_sqrt_d;
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int h = 4 * g + v;
-        if (h < group)
-          scores[(sq * n_q_heads + kv * group + h) * T + (size_t)jb * n + t] = fmaf(acc1[v], rho, acc2[v]) * inv_sqrt_d;
+      for (int u = 0; u < 2; ++u) {
+        const int t = 16 * (tile + u * (THREADS / 64)) + l16;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int h = 4 * g + v;
+          if (h < group)
+            scores[(sq * n_q_heads + kv * group + h) * T + (size_t)jb * n + t] = fmaf(acc1[u][v], rho[u], acc2[u][v]) * inv_sqrt_d;
+        }
       }
     }
   }
@@ -642,15 +662,19 @@ hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void*
 
 hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq, int n_kv_heads,
                              int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores) {
-  const int64_t runs = (blocks_per_head + SC_RUN - 1) / SC_RUN;
   const int64_t sg_total = n_seq * n_kv_heads;
+  // blocks per workgroup: up to 16 (the query set-up is paid once per workgroup), shorter when that leaves fewer than ~16
+  // workgroups per compute unit
+  int64_t run = (sg_total * blocks_per_head) / 4096;
+  run = run < 1 ? 1 : (run > SC_RUN_MAX ? SC_RUN_MAX : run);
+  const int64_t runs = (blocks_per_head + run - 1) / run;
   if (sg_total > 65535 || runs > 0x7FFFFFFF) return hipErrorInvalidValue;
   if (L.ev) (void)hipEventRecord(L.ev[6], L.stream);
   const dim3 grid((unsigned)runs, (unsigned)sg_total), block(THREADS);
   const uint16_t* q = static_cast<const uint16_t*>(q_fp16);
 #define EOQ_SCORES(BITS)                                                                                          \
   hipLaunchKernelGGL(eoq_scores_mfma_kernel<BITS>, grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads,            \
-                     n_q_heads / n_kv_heads, blocks_per_head, L.pit, L.tab, keys.codes, keys.norms, keys.rank,    \
+                     n_q_heads / n_kv_heads, blocks_per_head, (int)run, L.pit, L.tab, keys.codes, keys.norms, keys.rank,    \
                      keys.lfac, keys.rfac, q, scores)
   switch (L.bits) {
     case 1: EOQ_SCORES(1); break;
