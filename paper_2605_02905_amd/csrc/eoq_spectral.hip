@@ -306,7 +306,8 @@ constexpr int COARSE_ITERS = 17;           // for eigenvalues that only enter th
 constexpr int EV_BATCH = 8;                // eigenvectors per twisted-factorisation pass
 constexpr int U1_BYTES = EV_BATCH * 4 * D * 8;  // 32 KB: twisted-factorisation scratch; also the Gram strip (16 KB)
 constexpr double CLUSTER_TOL = 1e-10;      // relative gap below which retained eigenvalues count as repeated
-constexpr int REFL_BYTES = REFL_LEN * 4;   // 32512 (a multiple of 16)
+constexpr int REFL_SLACK = 16;             // floats in front of the reflectors (masked reads may reach them)
+constexpr int REFL_BYTES = (REFL_LEN + REFL_SLACK) * 4;   // 32576 (a multiple of 16)
 constexpr int POOL_BYTES = REFL_BYTES + U1_BYTES;
 
 // G = S^T S in the cyclic layout.  Only the sub-tiles a <= b are accumulated (36 of 64 products per block row);
@@ -727,6 +728,44 @@ __device__ __forceinline__ int sturm_count(sc_double* de, double x) {
   return cnt;
 }
 
+// Back-transformation through the reflectors 16 SG .. 16 SG + 15, four at a time, of the vector whose entries
+// i = l + 16 m this lane holds in y[m].  All sixteen reflectors vanish on the entries m < SG, are full on m > SG, and
+// reflector k starts inside m = SG (entries l > k % 16); so only that one entry needs a mask and the dead ones are
+// skipped.  `refl` has 16 floats of slack in front, which the masked reads of the first reflectors may touch.
+template <int SG>
+__device__ __forceinline__ void backtransform_stage(double (&y)[8], const float* refl, const double* betaT,
+                                                    const double* cW, int l) {
+#pragma unroll 1
+  for (int bl = 3; bl >= 0; --bl) {
+    const int bb = 4 * SG + bl;
+    double u[4][8], dt[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int k = 4 * bb + 3 - a;                           // k / 16 == SG
+      const float* rp = refl + refl_off(k) - (k + 1) + l;     // entry i at rp[i - l]
+      const bool head = (l > (k & 15)) && (SG < 7 || k < D - 2);  // reflectors 126, 127 do not exist
+      double acc = 0.0;
+#pragma unroll
+      for (int m = SG; m < 8; ++m) {
+        const float raw = rp[16 * m];
+        u[a][m] = (m == SG) ? (head ? (double)raw : 0.0) : (double)raw;
+        acc = fma(u[a][m], y[m], acc);
+      }
+      dt[a] = acc;
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a) dt[a] = row16_sum_uniform(dt[a]);
+    const double* c = cW + bb * 6;
+    const double f1 = betaT[4 * bb + 3] * dt[0];
+    const double f2 = betaT[4 * bb + 2] * fma(-c[0], f1, dt[1]);
+    const double f3 = betaT[4 * bb + 1] * fma(-c[2], f2, fma(-c[1], f1, dt[2]));
+    const double f4 = betaT[4 * bb] * fma(-c[5], f3, fma(-c[4], f2, fma(-c[3], f1, dt[3])));
+#pragma unroll
+    for (int m = SG; m < 8; ++m)
+      y[m] = fma(-f4, u[3][m], fma(-f3, u[2][m], fma(-f2, u[1][m], fma(-f1, u[0][m], y[m]))));
+  }
+}
+
 __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     const void* __restrict__ blocks, int dtype, int n, int k_pilot, double rank_thr, int r_max,
     int* __restrict__ fb_list, int* __restrict__ fb_count, double* __restrict__ lam_out, float* __restrict__ wfac,
@@ -735,7 +774,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   // one pool, used in turn by the Gram stage (byte planes / float strip), the reduction (reflectors) and the
   // eigenvector stage (u1)
   __shared__ __align__(16) unsigned char pool[POOL_BYTES];
-  float* refl = reinterpret_cast<float*>(pool);
+  float* refl = reinterpret_cast<float*>(pool) + REFL_SLACK;
   unsigned char* u1 = pool + REFL_BYTES;
   __shared__ __align__(16) double vbuf[2][D];
   __shared__ __align__(16) double pbuf[D];
@@ -1009,35 +1048,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
 #pragma unroll
         for (int m = 0; m < 8; ++m) y[m] = live ? F[l + 16 * m].y * inv : 0.0;
       }
-#pragma unroll 1
-      for (int bb = D / 4 - 1; bb >= 0; --bb) {
-        double u[4][8], dt[4];
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          const int k = 4 * bb + 3 - a;
-          const int kc = min(k, D - 3);  // reflectors 126, 127 do not exist: any address, value forced to zero
-          const int ro = refl_off(kc) - (kc + 1);
-          double acc = 0.0;
-#pragma unroll
-          for (int m = 0; m < 8; ++m) {
-            const int i = l + 16 * m;
-            const float raw = refl[max(ro + i, 0)];  // unconditional load (in range), masked afterwards
-            u[a][m] = (k < D - 2 && i > k) ? (double)raw : 0.0;
-            acc = fma(u[a][m], y[m], acc);
-          }
-          dt[a] = acc;
-        }
-#pragma unroll
-        for (int a = 0; a < 4; ++a) dt[a] = row16_sum_uniform(dt[a]);
-        const double* c = cW + bb * 6;
-        const double f1 = betaT[4 * bb + 3] * dt[0];
-        const double f2 = betaT[4 * bb + 2] * fma(-c[0], f1, dt[1]);
-        const double f3 = betaT[4 * bb + 1] * fma(-c[2], f2, fma(-c[1], f1, dt[2]));
-        const double f4 = betaT[4 * bb] * fma(-c[5], f3, fma(-c[4], f2, fma(-c[3], f1, dt[3])));
-#pragma unroll
-        for (int m = 0; m < 8; ++m)
-          y[m] = fma(-f4, u[3][m], fma(-f3, u[2][m], fma(-f2, u[1][m], fma(-f1, u[0][m], y[m]))));
-      }
+      EOQ_SFOR(sgr, 8, backtransform_stage<7 - sgr>(y, refl, betaT, cW, l););
       if (live) {
         const double s = scale_s[b0 + ev];
 #pragma unroll
