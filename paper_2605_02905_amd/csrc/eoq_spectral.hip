@@ -302,7 +302,6 @@ __device__ __forceinline__ int refl_off(int k) { return k * (D - 1) - (k * (k - 
 constexpr int REFL_LEN = (D - 1) * D / 2;  // 8128
 constexpr int GRID_POINTS = 256;           // first localisation: one Sturm count per lane on a uniform grid
 constexpr int MULTISECT_ITERS = 26;        // then trisection: 3^26 * 257 > 2^49 (the reduction itself is good to ~2^-48)
-constexpr int COARSE_ITERS = 17;           // for eigenvalues that only enter the Stieltjes sums of Alg. 2 Step 3: 3^-17 / 257 = 3e-11
 constexpr int EV_BATCH = 8;                // eigenvectors per twisted-factorisation pass
 constexpr int U1_BYTES = EV_BATCH * 4 * D * 8;  // 32 KB: twisted-factorisation scratch; also the Gram strip (16 KB)
 constexpr double CLUSTER_TOL = 1e-10;      // relative gap below which retained eigenvalues count as repeated
@@ -486,9 +485,11 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, int 
       const int ej = cexp[16 * tJ + l16];
       const int4 ei = *reinterpret_cast<const int4*>(cexp + 16 * tI + 4 * kg);
       const int eiv[4] = {ei.x, ei.y, ei.z, ei.w};
+      // neighbouring weights are merged in int32 first (a class holds at most 4 * 64 * 128 * 128 < 2^23 in magnitude,
+      // so c_even + 2^8 c_odd stays below 2^31), then four conversions and a Horner pass in double
       EOQ_SFOR(v, 4,
-        double val = (double)acc[6][v];
-        EOQ_SFOR(cd, 6, val = fma(val, 256.0, (double)acc[5 - cd][v]););
+        const int m01 = acc[0][v] + (acc[1][v] << 8), m23 = acc[2][v] + (acc[3][v] << 8), m45 = acc[4][v] + (acc[5][v] << 8);
+        const double val = fma(fma(fma((double)acc[6][v], 65536.0, (double)m45), 65536.0, (double)m23), 65536.0, (double)m01);
         Gacc[s][v] += ldexp(val, eiv[v] + ej);
       );
     );
@@ -880,12 +881,8 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       if (gl >= 0) lo = (gl + 1) * step;
       if (gh < GRID_POINTS) hi = (gh + 1) * step;
     }
-    // Full resolution for every eigenvalue that can decide the rank or the imputation (descending index up to
-    // 2k + r_max: the outliers, lambda_{k+1}, lambda_{2k+1}, lambda_{k+r}, lambda_{2k+r}); the rest of the bulk only
-    // enters the sums of 1 / (lambda_j - z) and (lambda_j - z)^-2, where 3e-11 of the norm is far below the bars.
-    const int my_iters = (D - 1 - j <= 2 * k_pilot + r_max) ? MULTISECT_ITERS : COARSE_ITERS;
 #pragma unroll 1
-    for (int it = 0; it < my_iters; ++it) {
+    for (int it = 0; it < MULTISECT_ITERS; ++it) {
       const double third = (hi - lo) * (1.0 / 3.0);
       const double x1 = lo + third, x2 = hi - third;
       const int mine = sturm_count(sde, sub ? x2 : x1);
