@@ -23,6 +23,7 @@ constexpr int THREADS = 256;
 constexpr int CHUNK = 128;          // tokens per pass of a workgroup: one tile of 32 per wave
 constexpr int ZLD = D + 8;          // row stride (halfs) of the token tiles in LDS: 272 B, conflict-free b128 reads
 constexpr int CLD = EOQ_RMAX_CAP + 8;
+constexpr int OLD = 32 + 8;         // row stride (halfs) of an output tile in LDS: 80 B, 16-byte aligned rows
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
@@ -162,6 +163,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
   __shared__ __align__(16) uint16_t Ct[CHUNK * CLD];   // low-rank coefficients, [token][component]
   __shared__ __align__(16) float rho_s[CHUNK];         // rho / sqrt(d)
   __shared__ __align__(16) uint4 mask_tab[256];
+  __shared__ __align__(16) uint16_t Ot[4 * 32 * OLD];  // per wave: one output tile, [token][column]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
@@ -269,14 +271,26 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
             }
           }
         }
+        // through a wave-private LDS tile so that a lane stores 16 bytes (8 columns of one token): 2 store
+        // instructions per tile instead of 16 two-byte ones
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) {
-          uint16_t* dst = out + ((size_t)blk * n + t0 + 32 * (tau + h2)) * D + jcol;
+          uint16_t* ot = Ot + wave * (32 * OLD);
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int row = 8 * (v >> 2) + 4 * hf + (v & 3);
-            dst[(size_t)row * D] = float_to_half_bits(acc[h2][v]);
+            ot[row * OLD + l32] = float_to_half_bits(acc[h2][v]);
           }
+          __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the tile is private to this wave
+          __builtin_amdgcn_wave_barrier();
+          uint16_t* dst = out + ((size_t)blk * n + t0 + 32 * (tau + h2)) * D + 32 * wave;
+#pragma unroll
+          for (int ps = 0; ps < 2; ++ps) {
+            const int row = 16 * ps + (lane >> 2), cg = (lane & 3) * 8;
+            const uint4 val = *reinterpret_cast<const uint4*>(ot + row * OLD + cg);
+            *reinterpret_cast<uint4*>(dst + (size_t)row * D + cg) = val;
+          }
+          __builtin_amdgcn_wave_barrier();
         }
       }
       cur = nxt;
