@@ -496,8 +496,10 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
 #pragma unroll
   for (int i = 0; i < (1 << BITS) - 1; ++i) bnd[i] = tab[16 + i];
 
-  // factors of the block: W = V diag(phi/sigma) split into hi + lo, and V16^T
-  for (int e = tid; e < EOQ_RMAX_CAP * D; e += THREADS) {
+  // factors of the block: W = V diag(phi/sigma) split into hi + lo, and V16^T.  Only the rows below the rank
+  // rounded up to a multiple of 8 are ever multiplied with something that is not forced to zero (see Cneg)
+  const int r_up = (r + 7) & ~7;
+  for (int e = tid; e < r_up * D; e += THREADS) {
     const int i = e >> 7, j = e & (D - 1);
     uint16_t hi = 0, lo = 0, v16 = 0;
     if (i < r) {
@@ -553,7 +555,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
           const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
           const uint16_t hb = float_to_half_bits(Cacc[v]);
           if (i < r) lfac[(blk * r_max + i) * (size_t)n + tg] = hb;
-          Cneg[v >> 2].s[v & 3] = hb ^ 0x8000u;
+          Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(hb ^ 0x8000u) : (uint16_t)0;  // rows >= r of W are not initialised
         }
 #pragma unroll
         for (int k2 = 0; k2 < 4; ++k2) {
