@@ -98,7 +98,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
     ap.add_argument("--bits", type=int, default=2)
     ap.add_argument("--cpu-blocks", type=int, default=1024, help="blocks in the CPU-baseline sample (0 = skip)")
     ap.add_argument("--cpu-passes", type=int, default=24, help="passes of the oracle over that sample (about 10-20 s of CPU work)")

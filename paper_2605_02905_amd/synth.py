@@ -42,7 +42,8 @@ class BlockSpec:
 
 
 def config(i: int) -> BlockSpec:
-    """The five workloads of the benchmark definition (1-based)."""
+    """The five workloads of the benchmark definition (1-based), and 6: the same layer as 2 cut into the
+    128 x 128 blocks of the paper's own experiments (Sec. 3, Tables 1-5)."""
     if i == 1:   # single block, fp32, three planted spikes, white noise
         return BlockSpec("cfg1-single-block", n=512, strengths=(6.0, 4.0, 2.5), channel_s=0.0,
                          dtype=torch.float32)
@@ -55,6 +56,8 @@ def config(i: int) -> BlockSpec:
                          frac_rank0=0.10)
     if i == 5:   # keys of 16 sequences x 8 KV heads x T=65536
         return BlockSpec("cfg5-decode-keys", n=512, n_tensors=16 * 8, blocks_per_tensor=128, rank_lo=2, rank_hi=8)
+    if i == 6:   # the Llama-shaped layer of config 2 in 128-token blocks
+        return BlockSpec("cfg6-llama-layer-n128", n=128, n_tensors=16, blocks_per_tensor=256, rank_lo=1, rank_hi=6)
     raise ValueError(i)
 
 

@@ -263,10 +263,11 @@ def _subset(rec, idx):
                                                          rec.rfac, rec.flags)))
 
 
-@pytest.mark.parametrize("cfg,stride", [(2, 37), (5, 331)])
+@pytest.mark.parametrize("cfg,stride", [(2, 37), (5, 331), (6, 29)])
 def test_full_size_batches_in_the_bench_launch_configuration(cfg, stride):
     """The whole batch of a benchmark workload in ONE eoq_compress / eoq_decompress / eoq_scores launch each, as
-    bench.py issues them (config 2: 1024 blocks, config 5: 16384 blocks); a strided sample of the blocks is checked
+    bench.py issues them (config 2: 1024 blocks, config 5: 16384 blocks, config 6: 4096 blocks of 128 x 128); a strided
+    sample of the blocks is checked
     against the oracle to the same bars, and every block against properties that hold at any size."""
     spec = synth.config(cfg)
     blocks, _ = synth.make_blocks(spec, device=DEV)
@@ -348,3 +349,17 @@ def test_second_call_reuses_the_workspace_with_other_data():
     for t1, t2 in ((rec.codes, rec2.codes), (rec.norms, rec2.norms), (rec.rank, rec2.rank), (rec.phi, rec2.phi)):
         assert torch.equal(t1, t2)
     assert torch.equal(ctx.spectrum(ws, b.shape[0]), ctx2.spectrum(ws2, b.shape[0]))
+
+
+def test_paper_shaped_blocks_of_128_tokens():
+    """128 x 128 blocks (the block shape of the paper's experiments): two head-tensors, every block checked."""
+    spec = synth.config(6)
+    blocks, _ = synth.make_blocks(spec, tensors=range(2))
+    b64 = blocks.double().numpy()
+    for bits in (2, 3):
+        recs = U.oracle_compress(b64, bits)
+        ctx, rec, lam = _gpu_compress(blocks, bits, spec.n)
+        st = U.compare_compress(b64, rec, lam, recs, bits)
+        U.log_stats(f"cfg6-2tensors-b{bits}", st)
+        assert st["max_lam_rel"] < 1e-9
+        _recon_agreement(ctx, rec, b64, recs, bits)
