@@ -34,6 +34,8 @@ __all__ = [
     "BlockRecord", "compress_block", "decompress_block", "score_block",
     "pack_codes", "unpack_codes", "fp16_round", "fp16_bits", "bits_per_entry",
     "FLAG_RANK_CLAMPED", "FLAG_SHRINK_GUARD",
+    "FACTOR_LEVELS", "FACTOR_LLOYD_ITERS", "adaptive_magnitudes", "factor_encode", "factor_decode",
+    "pack_nibbles", "unpack_nibbles", "quantize_factors",
 ]
 
 FLAG_RANK_CLAMPED = 1
@@ -372,17 +374,99 @@ class BlockRecord:
     rho: np.ndarray = field(default=None, repr=False)
     z: np.ndarray = field(default=None, repr=False)
     R: np.ndarray = field(default=None, repr=False)
+    # SVD factors stored at 4 bits (Alg. 3 line 3, Sec. 3.1); None when the factors are kept in binary16
+    factor_bits: int = 16
+    lcodes: np.ndarray = field(default=None, repr=False)   # [rank, n] uint8, 4-bit codes of U
+    rcodes: np.ndarray = field(default=None, repr=False)   # [rank, d] uint8, 4-bit codes of V
+    fbook: np.ndarray = field(default=None, repr=False)    # [2, 8] binary16 magnitudes (as float64): U's, V's
+    phi16: np.ndarray = field(default=None, repr=False)    # [rank] binary16 shrunk singular values
+
+
+# --------------------------------------------------------------------------
+# SVD factors at b_s = 4 bits (Alg. 3 line 3; Sec. 3.1 "data-adaptive Lloyd-Max codebooks")
+# --------------------------------------------------------------------------
+FACTOR_LEVELS = 8        # magnitudes; with the sign bit 16 levels = 4 bits
+FACTOR_LLOYD_ITERS = 8
+
+
+def adaptive_magnitudes(x: np.ndarray, levels: int = FACTOR_LEVELS, iters: int = FACTOR_LLOYD_ITERS,
+                        round16: bool = True) -> np.ndarray:
+    """Lloyd's algorithm on the magnitudes |x| of the entries of one factor matrix.
+    Start: the Lloyd-Max levels of a Gaussian with the entries' root mean square
+    (entries of singular vectors are close to Gaussian, so this start is already
+    near the fixed point); then `iters` times assign every |x| to the nearest level
+    (midpoint boundaries, a tie goes to the upper cell) and move every level to the
+    mean of its cell (an empty cell keeps its level).  The codebook is {+-m_k}:
+    symmetric, so it does not depend on the arbitrary sign of a singular vector.
+    Returned ascending, in binary16."""
+    a = np.abs(np.asarray(x, dtype=np.float64)).ravel()
+    rms = math.sqrt(float(np.mean(a * a))) if a.size else 0.0
+    nbits = int(round(math.log2(2 * levels)))
+    m = lloyd_max_gaussian(nbits).centroids[levels:] * rms
+    for _ in range(iters):
+        cell = np.searchsorted(0.5 * (m[:-1] + m[1:]), a, side="right")
+        for k in range(levels):
+            sel = cell == k
+            if sel.any():
+                m[k] = a[sel].mean()
+    return fp16_round(m) if round16 else m
+
+
+def factor_encode(x: np.ndarray, mags: np.ndarray) -> np.ndarray:
+    """4-bit code of every entry: bits 0-2 = index of the nearest magnitude (tie ->
+    upper cell), bit 3 = 1 for x >= 0."""
+    x = np.asarray(x, dtype=np.float64)
+    cell = np.searchsorted(0.5 * (mags[:-1] + mags[1:]), np.abs(x), side="right").astype(np.uint8)
+    return (cell | ((x >= 0).astype(np.uint8) << 3)).astype(np.uint8)
+
+
+def factor_decode(codes: np.ndarray, mags: np.ndarray) -> np.ndarray:
+    v = np.asarray(mags, dtype=np.float64)[codes & 7]
+    return np.where(codes & 8, v, -v)
+
+
+def pack_nibbles(codes: np.ndarray) -> np.ndarray:
+    """[..., m] 4-bit codes -> [..., m/2] bytes, entry e in the low (e even) or high nibble of byte e // 2."""
+    c = np.asarray(codes, dtype=np.uint8)
+    return (c[..., 0::2] | (c[..., 1::2] << 4)).astype(np.uint8)
+
+
+def unpack_nibbles(packed: np.ndarray) -> np.ndarray:
+    p = np.asarray(packed, dtype=np.uint8)
+    out = np.empty(p.shape[:-1] + (2 * p.shape[-1],), dtype=np.uint8)
+    out[..., 0::2] = p & 15
+    out[..., 1::2] = p >> 4
+    return out
+
+
+def quantize_factors(U: np.ndarray, V: np.ndarray, phi: np.ndarray):
+    """U [n, r], V [d, r] (orthonormal columns), phi [r] -> codes, codebooks and the
+    binary16 factors every later step uses: lfac = fp16(U_hat * phi16), rfac = V_hat."""
+    mu, mv = adaptive_magnitudes(U), adaptive_magnitudes(V)
+    lcodes, rcodes = factor_encode(U.T, mu), factor_encode(V.T, mv)          # [r, n], [r, d]
+    phi16 = fp16_round(phi)
+    lfac = fp16_round(factor_decode(lcodes, mu) * phi16[:, None])
+    rfac = factor_decode(rcodes, mv)
+    return lcodes, rcodes, np.stack([mu, mv]), phi16, lfac, rfac
 
 
 def compress_block(S: np.ndarray, Pi: np.ndarray, cb: Codebook, r_max: int = 32,
-                   force_rank0: bool = False) -> BlockRecord:
-    """Alg. 3: eOptShrink, residual against the *stored* (binary16) factors,
-    TQ_MSE per row.  With r^+ = 0 the block goes to TQ_MSE unchanged."""
+                   force_rank0: bool = False, factor_bits: int = 16) -> BlockRecord:
+    """Alg. 3: eOptShrink, residual against the *stored* factors (binary16, or
+    4-bit codes with per-block codebooks), TQ_MSE per row.  With r^+ = 0 the block
+    goes to TQ_MSE unchanged."""
+    if factor_bits not in (16, 4):
+        raise ValueError("factor_bits must be 16 or 4")
     S = np.asarray(S, dtype=np.float64)
     n, d = S.shape
     es = eoptshrink(S, r_max)
     r = 0 if force_rank0 else es.rank
-    if r > 0:
+    extra = {}
+    if r > 0 and factor_bits == 4:
+        lcodes, rcodes, fbook, phi16, lfac, rfac = quantize_factors(es.U[:, :r], es.V[:, :r], es.phi[:r])
+        extra = dict(factor_bits=4, lcodes=lcodes, rcodes=rcodes, fbook=fbook, phi16=phi16)
+        R = S - lfac.T @ rfac
+    elif r > 0:
         lfac = fp16_round((es.U[:, :r] * es.phi[None, :r]).T)   # [r, n]
         rfac = fp16_round(es.V[:, :r].T)                        # [r, d]
         R = S - lfac.T @ rfac
@@ -390,9 +474,12 @@ def compress_block(S: np.ndarray, Pi: np.ndarray, cb: Codebook, r_max: int = 32,
         lfac = np.zeros((0, n))
         rfac = np.zeros((0, d))
         R = S
+        if factor_bits == 4:
+            extra = dict(factor_bits=4, lcodes=np.zeros((0, n), np.uint8), rcodes=np.zeros((0, d), np.uint8),
+                         fbook=np.zeros((2, FACTOR_LEVELS)), phi16=np.zeros(0))
     codes, rho, z = tq_mse_encode(R, Pi, cb)
     return BlockRecord(n, d, cb.bits, r, es.flags, es.phi[:r], es.sigma[:r], lfac, rfac, codes,
-                       fp16_round(rho), lam=es.lam, lam_plus=es.lam_plus, rho=rho, z=z, R=R)
+                       fp16_round(rho), lam=es.lam, lam_plus=es.lam_plus, rho=rho, z=z, R=R, **extra)
 
 
 def decompress_block(rec: BlockRecord, Pi: np.ndarray, cb: Codebook) -> np.ndarray:

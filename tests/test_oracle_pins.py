@@ -490,3 +490,84 @@ def test_pack_unpack_exhaustive(bits):
     rng = np.random.default_rng(bits)
     codes = rng.integers(0, L, (64, d), dtype=np.uint8)
     assert np.array_equal(oracle.unpack_codes(oracle.pack_codes(codes, bits), bits, d), codes)
+
+
+# ---------------------------------------------------------------------------------------------
+# SVD factors at 4 bits (Alg. 3 line 3, Sec. 3.1): data-adaptive Lloyd-Max codebooks
+# ---------------------------------------------------------------------------------------------
+def test_adaptive_codebook_converges_to_the_gaussian_lloyd_max_levels():
+    """On a large Gaussian sample Lloyd's iteration on |x| must reach the 16-level Lloyd-Max codebook of N(0,1)
+    (whose values are pinned above to the printed table): a wrong update rule or boundary would settle elsewhere."""
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal(400_000) * 3.0
+    m = oracle.adaptive_magnitudes(x, iters=200, round16=False)
+    ref = 3.0 * oracle.lloyd_max_gaussian(4).centroids[8:]
+    assert np.max(np.abs(m - ref) / ref) < 0.02, (m, ref)
+    # on data that is not Gaussian it leaves the Gaussian start for that data's own fixed point: every level
+    # with a non-empty cell is the mean of its cell (levels above max|y| keep their start: their cells are empty)
+    y = rng.uniform(-1.0, 1.0, 200_000)
+    my = oracle.adaptive_magnitudes(y, iters=300, round16=False)
+    cell = np.searchsorted(0.5 * (my[:-1] + my[1:]), np.abs(y), side="right")
+    for k_ in range(8):
+        if np.any(cell == k_):
+            assert abs(my[k_] - np.abs(y)[cell == k_].mean()) < 1e-3
+    assert np.count_nonzero(np.bincount(cell, minlength=8)) >= 6
+
+
+def test_adaptive_codebook_lloyd_steps_never_increase_the_distortion():
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal(5000) * 0.09
+    prev = np.inf
+    for it in range(0, 10):
+        m = oracle.adaptive_magnitudes(x, iters=it, round16=False)
+        xq = oracle.factor_decode(oracle.factor_encode(x, m), m)
+        dist = float(np.mean((x - xq) ** 2))
+        assert dist <= prev * (1 + 1e-12)
+        prev = dist
+    # after the fixed 8 iterations the distortion is close to the 4-bit optimum D_4 = 0.009497 sigma^2
+    assert prev / np.var(x) < 1.03 * 0.009497
+    # brute force: every entry is coded to the nearest of the 16 levels
+    m = oracle.adaptive_magnitudes(x)
+    levels = np.concatenate([-m[::-1], m])
+    codes = oracle.factor_encode(x, m)
+    xq = oracle.factor_decode(codes, m)
+    nearest = levels[np.argmin(np.abs(x[:, None] - levels[None, :]), axis=1)]
+    assert np.allclose(np.abs(x - xq), np.abs(x - nearest), rtol=0, atol=1e-15)
+
+
+def test_factor_codes_do_not_depend_on_the_sign_of_a_singular_vector():
+    rng = np.random.default_rng(13)
+    U, _ = np.linalg.qr(rng.standard_normal((128, 3)))
+    m1, m2 = oracle.adaptive_magnitudes(U), oracle.adaptive_magnitudes(U * np.array([1.0, -1.0, 1.0]))
+    assert np.array_equal(m1, m2)
+    c1, c2 = oracle.factor_encode(U, m1), oracle.factor_encode(U * np.array([1.0, -1.0, 1.0]), m1)
+    assert np.array_equal(c1 & 7, c2 & 7) and np.array_equal(c1[:, 1] ^ c2[:, 1], np.full(128, 8))
+    assert np.array_equal(oracle.unpack_nibbles(oracle.pack_nibbles(c1.T)), c1.T)
+
+
+def test_factor_overhead_matches_the_printed_figure():
+    """Sec. 3.3: r(n + d) b_s / (n d) with r = 5.6, n = d = 128, b_s = 4 is 'approximately 0.35 bits'; with r = 1
+    'approximately 0.06'."""
+    assert abs(5.6 * 256 * 4 / 16384 - 0.35) < 1e-12
+    assert abs(oracle.bits_per_entry(128, 128, 2, 1, b_s=4) - (2 + 0.0625 + 0.125 + 16.0 / 16384)) < 1e-12
+
+
+def test_four_bit_factors_closed_loop_and_expansion():
+    """The residual is taken against the stored 4-bit factors (closed loop): decompress reproduces S up to the
+    TQ error of the residual, the record's binary16 factors are exactly what the codes expand to, and the
+    low-rank part keeps ~99 % of what binary16 factors keep (4-bit distortion 0.95 % per factor)."""
+    S, _, _ = _spiked(np.random.default_rng(21), 512, 128, (6.0, 4.0, 2.5))
+    Pi = oracle.haar_rotation(128, 7)
+    cb = oracle.lloyd_max_gaussian(2)
+    r16 = oracle.compress_block(S, Pi, cb)
+    r4 = oracle.compress_block(S, Pi, cb, factor_bits=4)
+    assert r4.rank == r16.rank == 3 and r4.factor_bits == 4
+    lf = oracle.fp16_round(oracle.factor_decode(r4.lcodes, r4.fbook[0]) * r4.phi16[:, None])
+    assert np.array_equal(lf, r4.lfac) and np.array_equal(oracle.factor_decode(r4.rcodes, r4.fbook[1]), r4.rfac)
+    x4 = oracle.decompress_block(r4, Pi, cb)
+    e4 = np.linalg.norm(S - x4) / np.linalg.norm(r4.R)
+    assert abs(e4 - math.sqrt(0.117482)) < 0.02          # TQ error of the residual, 2 bits
+    low16, low4 = r16.lfac.T @ r16.rfac, r4.lfac.T @ r4.rfac
+    assert np.linalg.norm(low16 - low4) / np.linalg.norm(low16) < 0.2
+    # 4-bit factors leave sqrt(2 D_4) = 14 % of the low-rank part in the residual: here 1 % more residual energy
+    assert np.linalg.norm(r4.R) < 1.02 * np.linalg.norm(r16.R)
