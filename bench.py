@@ -52,13 +52,13 @@ def _cpu_init():
 def _cpu_job(args):
     import numpy as np
     import oracle
-    blocks16, bits, seed, q, passes = args
+    blocks16, bits, seed, q, passes, factor_bits = args
     Pi = oracle.haar_rotation(D, seed).astype(np.float32).astype(np.float64)
     cb = oracle.lloyd_max_gaussian(bits)
     n = 0
     for _ in range(passes):
         for S in blocks16:
-            rec = oracle.compress_block(S.astype(np.float64), Pi, cb)
+            rec = oracle.compress_block(S.astype(np.float64), Pi, cb, factor_bits=factor_bits)
             x = oracle.decompress_block(rec, Pi, cb).astype(np.float16)
             if q is not None:
                 oracle.score_block(q, rec, Pi, cb)
@@ -66,17 +66,17 @@ def _cpu_job(args):
     return n
 
 
-def cpu_baseline(blocks_cpu, bits: int, seed: int, q_cpu, sample_blocks: int, passes: int):
+def cpu_baseline(blocks_cpu, bits: int, seed: int, q_cpu, sample_blocks: int, passes: int, factor_bits: int = 16):
     import numpy as np
     cores = min(os.cpu_count() or 1, 16)
     B = min(sample_blocks, blocks_cpu.shape[0])
     arr = blocks_cpu[:B].numpy()
     q = None if q_cpu is None else q_cpu.double().numpy()
     per = max(1, B // (cores * 4))
-    jobs = [(arr[i:i + per], bits, seed, q, passes) for i in range(0, B, per)]
+    jobs = [(arr[i:i + per], bits, seed, q, passes, factor_bits) for i in range(0, B, per)]
     ctx = multiprocessing.get_context("spawn")
     with ctx.Pool(cores, initializer=_cpu_init) as pool:
-        pool.map(_cpu_job, [(arr[:1], bits, seed, q, 1)] * cores)   # start the workers before the clock
+        pool.map(_cpu_job, [(arr[:1], bits, seed, q, 1, factor_bits)] * cores)   # start the workers before the clock
         t0 = time.perf_counter()
         done = sum(pool.map(_cpu_job, jobs))
         dt = time.perf_counter() - t0
@@ -100,6 +100,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
     ap.add_argument("--bits", type=int, default=2)
+    ap.add_argument("--factor-bits", type=int, default=16, choices=[16, 4],
+                    help="storage of the SVD factors: binary16 (default) or 4-bit codes with per-block Lloyd-Max codebooks")
     ap.add_argument("--cpu-blocks", type=int, default=1024, help="blocks in the CPU-baseline sample (0 = skip)")
     ap.add_argument("--cpu-passes", type=int, default=24, help="passes of the oracle over that sample (about 10-20 s of CPU work)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -149,8 +151,13 @@ def main() -> int:
     q = synth.make_queries(n_seq, n_kv * group, device=dev)
     scores = torch.empty(n_seq, n_kv * group, bph * n, dtype=torch.float32, device=dev)
 
+    fq = eoq.FactorCodes.empty(B, n, D, ctx.r_max, dev) if args.factor_bits == 4 else None
+
     def step():
-        ctx.eoq_compress(blocks, rec, ws)
+        if fq is None:
+            ctx.eoq_compress(blocks, rec, ws)
+        else:
+            ctx.eoq_compress_q4(blocks, rec, fq, ws)      # its factor-fitting kernel is timed with the encoder
         ctx.eoq_decompress(rec, xhat)
         ctx.eoq_scores(keys, q, n_kv, scores)
 
@@ -179,7 +186,13 @@ def main() -> int:
     flags = rec.flags.cpu()
     sweeps = ((flags >> 8) & 0xFF).double().mean().item()
     ranks = rec.rank.cpu().double()
-    rec_bytes = (B * n * (bits * D // 8) + B * n * 2 + int(ranks.sum().item()) * (n + D) * 2 + B * 12)
+    # bytes a stored record needs: residual codes, norms, the factors (binary16, or 4-bit codes + binary16 phi per
+    # component + two 8-level binary16 codebooks per block), rank / flags
+    comp_bytes = (n + D) * 2 if fq is None else (n + D) // 2 + 2
+    book_bytes = 0 if fq is None else 32
+    rec_bytes = (B * n * (bits * D // 8) + B * n * 2 + int(ranks.sum().item()) * comp_bytes + B * (12 + book_bytes))
+    # the decoder and the scores read the expanded binary16 factors in either case
+    moved_bytes = B * n * (bits * D // 8) + B * n * 2 + int(ranks.sum().item()) * (n + D) * 2 + B * 12
     flops = spectral_flops_per_block(n, ranks.mean().item(), sweeps) * B
     achieved_tflops = flops / (stage["spectral"] * 1e-3) / 1e12
     traffic = None
@@ -201,20 +214,20 @@ def main() -> int:
         "config": {"workload": f"{spec.name}: {B} blocks of {n}x{D} fp16, b={bits}, whole path per step "
                                f"(compress + decompress + scores of {n_seq}x{n_kv * group} queries on "
                                f"{key_blocks} key blocks)",
-                   "blocks": B, "n": n, "d": D, "bits": bits, "input_bytes": in_bytes},
+                   "blocks": B, "n": n, "d": D, "bits": bits, "factor_bits": args.factor_bits, "input_bytes": in_bytes},
         "stages": {
             "compress_GBps_fp16_in": in_bytes / ((stage["spectral"] + stage["encode"]) * 1e-3) / 1e9,
             "spectral_ms": stage["spectral"], "encode_ms": stage["encode"],
-            "encode_GBps_moved": (in_bytes + rec_bytes) / (stage["encode"] * 1e-3) / 1e9,
+            "encode_GBps_moved": (in_bytes + moved_bytes) / (stage["encode"] * 1e-3) / 1e9,
             "dequant_ms": stage["decode"],
             "dequant_GBps_out": in_bytes / (stage["decode"] * 1e-3) / 1e9,
-            "dequant_GBps_moved": (in_bytes + rec_bytes) / (stage["decode"] * 1e-3) / 1e9,
-            "dequant_frac_hbm": (in_bytes + rec_bytes) / (stage["decode"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "dequant_GBps_moved": (in_bytes + moved_bytes) / (stage["decode"] * 1e-3) / 1e9,
+            "dequant_frac_hbm": (in_bytes + moved_bytes) / (stage["decode"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "scores_ms": stage["scores"],
             "scores_GBps_moved": score_bytes / (stage["scores"] * 1e-3) / 1e9,
             "scores_frac_hbm": score_bytes / (stage["scores"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "mean_rank": ranks.mean().item(), "mean_jacobi_sweeps": sweeps,
-            "record_bytes": rec_bytes,
+            "record_bytes": rec_bytes, "stored_bits_per_entry": rec_bytes * 8.0 / (B * n * D),
         },
         "roofline": {"kernel": "eoq_spectral_jacobi_kernel" if sweeps > 0 else "eoq_spectral_tridiag_kernel", "bound": "alu", "achieved": achieved_tflops,
                      "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS,
@@ -224,7 +237,8 @@ def main() -> int:
         blocks_cpu = blocks[:args.cpu_blocks].cpu()
         q_cpu = q[0, :group].cpu()
         log("timing the CPU oracle")
-        out["cpu_baseline"] = cpu_baseline(blocks_cpu, bits, ctx.rot_seed, q_cpu, args.cpu_blocks, args.cpu_passes)
+        out["cpu_baseline"] = cpu_baseline(blocks_cpu, bits, ctx.rot_seed, q_cpu, args.cpu_blocks, args.cpu_passes,
+                                           args.factor_bits)
         log("CPU oracle done")
     print(json.dumps(out))
     return 0

@@ -75,6 +75,27 @@ typedef struct {
 } eoq_packed;
 
 /*
+ * SVD factors at 4 bits (Alg. 3 line 3 with b_s = 4; Sec. 3.1: data-adaptive Lloyd-Max codebooks, shrunk
+ * singular values in binary16).  All members are DEVICE pointers, caller-owned.  Per block and factor matrix
+ * the codebook is {+-m_0 .. +-m_7} (eight binary16 magnitudes fitted to the |entries| of that matrix); a code
+ * is 3 bits of magnitude index plus the sign in bit 3 (set for x >= 0); two codes per byte, entry e in the low
+ * (e even) or high nibble of byte e/2.
+ *
+ *   lcodes [B][r_max][n/2]  codes of the left singular vectors U (unit columns), one row per component.
+ *   rcodes [B][r_max][d/2]  codes of the right singular vectors V.
+ *   fbook  [B][2][8]        binary16 magnitudes: [0] for U, [1] for V.
+ *   phi16  [B][r_max]       binary16 shrunk singular values.
+ * Only the first r^+ rows of a block are written.  The record's lfac / rfac then hold what these codes expand
+ * to, binary16(U_hat phi16) and V_hat: a cache that eoq_expand_factors rebuilds from the codes.
+ */
+typedef struct {
+  uint8_t*  lcodes;
+  uint8_t*  rcodes;
+  uint16_t* fbook;
+  uint16_t* phi16;
+} eoq_factor_codes;
+
+/*
  * Create a context for blocks of n x d, `bits` residual bits per entry (Alg. 3
  * REQUIRE), a Haar rotation drawn from `rot_seed` (Alg. 1 REQUIRE: one rotation
  * shared by all vectors) and at most r_max stored components per block.
@@ -117,6 +138,21 @@ eoq_status eoq_codebook(const eoq_ctx* ctx, float* host_centroids, float* host_b
  */
 eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B,
                         eoq_packed out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * eoq_compress with the SVD factors stored at 4 bits (see eoq_factor_codes): the residual is taken against
+ * the expanded 4-bit factors (closed loop), which are also left in out.lfac / out.rfac.  binary16 blocks only
+ * (dtype must be EOQ_F16) and n * r_max <= 32768 (the left vectors of a block are fitted in LDS), otherwise
+ * EOQ_ERR_UNSUPPORTED.  Everything else as eoq_compress.
+ */
+eoq_status eoq_compress_q4(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_packed out,
+                           eoq_factor_codes fq, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Rebuild rec.lfac / rec.rfac (rows below rec.rank[b]) from the 4-bit codes, codebooks and phi16 of `fq`, e.g.
+ * after loading a record that was stored without them.  Reads rec.rank, writes rec.lfac and rec.rfac.
+ */
+eoq_status eoq_expand_factors(eoq_ctx* ctx, eoq_packed rec, eoq_factor_codes fq, int64_t B, void* hip_stream);
 
 /*
  * Inverse of eoq_compress: x_hat_t = rho_t Pi^T z_hat_t + (U diag(phi) V^T)[t,:]

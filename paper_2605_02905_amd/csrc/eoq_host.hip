@@ -183,6 +183,8 @@ eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, 
       pit[(size_t)j * d + c] = v;
     }
   std::vector<double> cent, bnd;
+  lloyd_max(4, cent, bnd);
+  for (int i = 0; i < 8; ++i) ctx->gauss16[i] = cent[8 + i];
   lloyd_max(bits, cent, bnd);
   ctx->cent_host.assign(cent.begin(), cent.end());
   ctx->bnd_host.assign(bnd.begin(), bnd.end());
@@ -287,6 +289,60 @@ eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64
   hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, fb_count, fb_list, tri, out);
   if (e == hipSuccess) e = eoq_launch_encode(L, blocks, (int)dtype, B, wfac, out);
   if (ctx->profile) ctx->ev_valid[0] = ctx->ev_valid[1] = (e == hipSuccess);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+eoq_status eoq_compress_q4(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_packed out,
+                           eoq_factor_codes fq, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (B < 0) return fail(ctx, EOQ_ERR_ARG, "negative block count");
+  if (dtype != EOQ_F16) return fail(ctx, EOQ_ERR_UNSUPPORTED, "4-bit factors: dtype must be EOQ_F16");
+  if ((int64_t)ctx->n * ctx->r_max > 32768) return fail(ctx, EOQ_ERR_UNSUPPORTED, "4-bit factors: n * r_max exceeds 32768");
+  if (B == 0) return EOQ_OK;
+  if (!blocks || !workspace) return fail(ctx, EOQ_ERR_ARG, "null blocks or workspace pointer");
+  if (!aligned16(blocks) || !aligned16(workspace)) return fail(ctx, EOQ_ERR_ARG, "blocks/workspace not 16-byte aligned");
+  if (eoq_status st = check_packed(ctx, out)) return st;
+  if (!fq.lcodes || !fq.rcodes || !fq.fbook || !fq.phi16) return fail(ctx, EOQ_ERR_ARG, "eoq_factor_codes has a null member");
+  if (workspace_bytes < eoq_workspace_bytes(ctx, B)) return fail(ctx, EOQ_ERR_WORKSPACE, "workspace too small");
+  if (B > (int64_t)1 << 24) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  double* lam = static_cast<double*>(workspace);
+  char* ws = static_cast<char*>(workspace);
+  float* wfac = reinterpret_cast<float*>(ws + eoq_ws_lam_bytes(B));
+  int* fb_count = reinterpret_cast<int*>(ws + eoq_ws_lam_bytes(B) + eoq_ws_wfac_bytes(B, ctx->r_max));
+  int* fb_list = fb_count + 4;
+  const uintptr_t tri_at = reinterpret_cast<uintptr_t>(reinterpret_cast<char*>(fb_count) + eoq_ws_list_bytes(B));
+  double* tri = reinterpret_cast<double*>((tri_at + 63) & ~(uintptr_t)63);
+  hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, fb_count, fb_list, tri, out);
+  if (L.ev && e == hipSuccess) (void)hipEventRecord(L.ev[2], L.stream);  // the factor stage counts as encode time
+  if (e == hipSuccess) e = eoq_launch_factor_quant(L, blocks, B, wfac, out, fq, ctx->gauss16);
+  if (e == hipSuccess) e = eoq_launch_encode_f16(L, blocks, B, wfac, out, true);
+  if (L.ev && e == hipSuccess) (void)hipEventRecord(L.ev[3], L.stream);
+  if (ctx->profile) ctx->ev_valid[0] = ctx->ev_valid[1] = (e == hipSuccess);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+eoq_status eoq_expand_factors(eoq_ctx* ctx, eoq_packed rec, eoq_factor_codes fq, int64_t B, void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (B < 0) return fail(ctx, EOQ_ERR_ARG, "negative block count");
+  if (B == 0) return EOQ_OK;
+  if (eoq_status st = check_packed(ctx, rec)) return st;
+  if (!fq.lcodes || !fq.rcodes || !fq.fbook || !fq.phi16) return fail(ctx, EOQ_ERR_ARG, "eoq_factor_codes has a null member");
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  const hipError_t e = eoq_launch_factor_expand(L, rec, fq, B);
   if (e != hipSuccess) {
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);
     return EOQ_ERR_HIP;

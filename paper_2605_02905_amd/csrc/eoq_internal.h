@@ -27,6 +27,7 @@ struct eoq_ctx {
   float* d_tab = nullptr;        // device: 16 centroids then 16 bounds (padded)
   uint16_t* d_pih = nullptr;     // device binary16: Pi hi [c][j], Pi lo [c][j], Pi^T hi [j][c], Pi^T lo [j][c]
   std::string err;
+  double gauss16[8] = {};  // Lloyd-Max magnitudes of N(0,1) at 16 levels: start of the per-block factor codebooks
   int solver = 0;  // 0: tridiagonal eigensolver with Jacobi for repeated eigenvalues, 1: Jacobi for every block
   // optional per-kernel timing: events [2*i], [2*i+1] bracket stage i (spectral, encode, decode, scores)
   bool profile = false;
@@ -62,7 +63,10 @@ hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype
 hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, int64_t B, const float* wfac,
                              eoq_packed out);
 hipError_t eoq_launch_encode_f16(const EoqLaunch& L, const void* blocks, int64_t B, const float* wfac,
-                                 eoq_packed out);
+                                 eoq_packed out, bool stored_factors = false);
+hipError_t eoq_launch_factor_quant(const EoqLaunch& L, const void* blocks_fp16, int64_t B, const float* wfac,
+                                   eoq_packed out, eoq_factor_codes fq, const double* gauss_levels);
+hipError_t eoq_launch_factor_expand(const EoqLaunch& L, eoq_packed rec, eoq_factor_codes fq, int64_t B);
 hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void* out_fp16);
 hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq, int n_kv_heads,
                              int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores);

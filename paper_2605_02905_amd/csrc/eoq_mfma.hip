@@ -465,11 +465,13 @@ __device__ __forceinline__ float16v mfma8(const H4& a, const H4& b, float16v c) 
 }
 constexpr int VLD = EOQ_RMAX_CAP + 8;  // row stride (halfs) of V^T in LDS
 
-template <int BITS>
+// FQ: the factors are already stored (4-bit codes expanded into lfac / rfac): the coefficients are read, not
+// projected, and the residual is taken against them.
+template <int BITS, bool FQ>
 __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
     const uint16_t* __restrict__ blocks, int n, int r_max, const uint16_t* __restrict__ pih,
     const float* __restrict__ tab, const float* __restrict__ wfac, const int32_t* __restrict__ rank_in,
-    const uint16_t* __restrict__ rfac, uint16_t* __restrict__ lfac, uint16_t* __restrict__ norms,
+    const uint16_t* __restrict__ rfac, uint16_t* lfac, uint16_t* __restrict__ norms,
     uint8_t* __restrict__ codes) {
   __shared__ __align__(16) uint16_t X[CHUNK * ZLD];                 // S tiles, then u tiles: [token][j]
   __shared__ __align__(16) uint16_t Wh[EOQ_RMAX_CAP * ZLD];         // W hi  [component][j]
@@ -503,11 +505,13 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
     const int i = e >> 7, j = e & (D - 1);
     uint16_t hi = 0, lo = 0, v16 = 0;
     if (i < r) {
-      split_half(wfac[(blk * r_max + i) * D + j], hi, lo);
+      if constexpr (!FQ) split_half(wfac[(blk * r_max + i) * D + j], hi, lo);
       v16 = rfac[(blk * r_max + i) * D + j];
     }
-    Wh[i * ZLD + j] = hi;
-    Wl[i * ZLD + j] = lo;
+    if constexpr (!FQ) {
+      Wh[i * ZLD + j] = hi;
+      Wl[i * ZLD + j] = lo;
+    }
     VT[j * VLD + i] = v16;
   }
   const float sqrt_d = sqrtf((float)D);
@@ -536,26 +540,35 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) Racc[mt][v] = (float)Sreg[4 * mt + (v >> 2)].h[v & 3];
       if (r > 0) {
-        float16v Cacc;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) Cacc[v] = 0.0f;
-#pragma unroll
-        for (int kk = 0; kk < 16; ++kk) {
-          H4 ah, al;
-          ah.u = *reinterpret_cast<const uint2*>(Wh + l32 * ZLD + 8 * kk + 4 * hf);
-          al.u = *reinterpret_cast<const uint2*>(Wl + l32 * ZLD + 8 * kk + 4 * hf);
-          Cacc = mfma8(ah, Sreg[kk], Cacc);
-          Cacc = mfma8(al, Sreg[kk], Cacc);
-        }
-        // stored coefficients C16 = binary16(U diag(phi)); their negatives are the next B operand
         H4 Cneg[4];
         const size_t tg = (size_t)t0 + 32 * wave + l32;
+        if constexpr (FQ) {
+          // the stored coefficients of this token, negated: the next B operand
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
-          const uint16_t hb = float_to_half_bits(Cacc[v]);
-          if (i < r) lfac[(blk * r_max + i) * (size_t)n + tg] = hb;
-          Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(hb ^ 0x8000u) : (uint16_t)0;  // rows >= r of W are not initialised
+          for (int v = 0; v < 16; ++v) {
+            const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
+            Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(lfac[(blk * r_max + i) * (size_t)n + tg] ^ 0x8000u) : (uint16_t)0;
+          }
+        } else {
+          float16v Cacc;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) Cacc[v] = 0.0f;
+#pragma unroll
+          for (int kk = 0; kk < 16; ++kk) {
+            H4 ah, al;
+            ah.u = *reinterpret_cast<const uint2*>(Wh + l32 * ZLD + 8 * kk + 4 * hf);
+            al.u = *reinterpret_cast<const uint2*>(Wl + l32 * ZLD + 8 * kk + 4 * hf);
+            Cacc = mfma8(ah, Sreg[kk], Cacc);
+            Cacc = mfma8(al, Sreg[kk], Cacc);
+          }
+          // stored coefficients C16 = binary16(U diag(phi)); their negatives are the next B operand
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
+            const uint16_t hb = float_to_half_bits(Cacc[v]);
+            if (i < r) lfac[(blk * r_max + i) * (size_t)n + tg] = hb;
+            Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(hb ^ 0x8000u) : (uint16_t)0;  // rows >= r of W are not initialised
+          }
         }
 #pragma unroll
         for (int k2 = 0; k2 < 4; ++k2) {
@@ -704,12 +717,18 @@ hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq,
 }
 
 hipError_t eoq_launch_encode_f16(const EoqLaunch& L, const void* blocks, int64_t B, const float* wfac,
-                                 eoq_packed out) {
+                                 eoq_packed out, bool stored_factors) {
   const dim3 grid((unsigned)B), block(THREADS);
   const uint16_t* src = static_cast<const uint16_t*>(blocks);
-#define EOQ_ENCODE(BITS)                                                                                         \
-  hipLaunchKernelGGL(eoq_encode_mfma_kernel<BITS>, grid, block, 0, L.stream, src, L.n, L.r_max, L.pih, L.tab,    \
-                     wfac, out.rank, out.rfac, out.lfac, out.norms, out.codes)
+#define EOQ_ENCODE(BITS)                                                                                            \
+  do {                                                                                                              \
+    if (stored_factors)                                                                                             \
+      hipLaunchKernelGGL((eoq_encode_mfma_kernel<BITS, true>), grid, block, 0, L.stream, src, L.n, L.r_max, L.pih,  \
+                         L.tab, wfac, out.rank, out.rfac, out.lfac, out.norms, out.codes);                          \
+    else                                                                                                            \
+      hipLaunchKernelGGL((eoq_encode_mfma_kernel<BITS, false>), grid, block, 0, L.stream, src, L.n, L.r_max, L.pih, \
+                         L.tab, wfac, out.rank, out.rfac, out.lfac, out.norms, out.codes);                          \
+  } while (0)
   switch (L.bits) {
     case 1: EOQ_ENCODE(1); break;
     case 2: EOQ_ENCODE(2); break;

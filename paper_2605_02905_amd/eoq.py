@@ -18,7 +18,7 @@ EOQ_F16, EOQ_F32 = 0, 1
 FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE = 1, 2, 4
 
 EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_codebook",
-           "eoq_compress", "eoq_decompress", "eoq_scores", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
+           "eoq_compress", "eoq_compress_q4", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
 
 
 class EoqError(RuntimeError):
@@ -30,6 +30,10 @@ class EoqError(RuntimeError):
 class _Packed(C.Structure):
     _fields_ = [("codes", C.c_void_p), ("norms", C.c_void_p), ("rank", C.c_void_p), ("phi", C.c_void_p),
                 ("sigma", C.c_void_p), ("lfac", C.c_void_p), ("rfac", C.c_void_p), ("flags", C.c_void_p)]
+
+
+class _FactorCodes(C.Structure):
+    _fields_ = [("lcodes", C.c_void_p), ("rcodes", C.c_void_p), ("fbook", C.c_void_p), ("phi16", C.c_void_p)]
 
 
 _lib = None
@@ -57,6 +61,11 @@ def lib():
         L.eoq_compress.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, _Packed, C.c_void_p, C.c_size_t,
                                    C.c_void_p]
         L.eoq_compress.restype = C.c_int
+        L.eoq_compress_q4.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, _Packed, _FactorCodes, C.c_void_p,
+                                      C.c_size_t, C.c_void_p]
+        L.eoq_compress_q4.restype = C.c_int
+        L.eoq_expand_factors.argtypes = [C.c_void_p, _Packed, _FactorCodes, C.c_int64, C.c_void_p]
+        L.eoq_expand_factors.restype = C.c_int
         L.eoq_decompress.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_void_p, C.c_void_p]
         L.eoq_decompress.restype = C.c_int
         L.eoq_scores.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_int, C.c_int64, C.c_void_p, C.c_int,
@@ -109,6 +118,29 @@ class Packed:
     def nbytes(self) -> int:
         return sum(t.numel() * t.element_size() for t in (self.codes, self.norms, self.rank, self.phi, self.sigma,
                                                           self.lfac, self.rfac, self.flags))
+
+
+@dataclass
+class FactorCodes:
+    """Device tensors of the 4-bit SVD factors of a batch (layout: include/eoq.h, eoq_factor_codes)."""
+    lcodes: torch.Tensor  # uint8   [B, r_max, n/2]
+    rcodes: torch.Tensor  # uint8   [B, r_max, d/2]
+    fbook: torch.Tensor   # float16 [B, 2, 8]
+    phi16: torch.Tensor   # float16 [B, r_max]
+
+    def c_struct(self) -> _FactorCodes:
+        return _FactorCodes(*(t.data_ptr() for t in (self.lcodes, self.rcodes, self.fbook, self.phi16)))
+
+    @staticmethod
+    def empty(B: int, n: int, d: int, r_max: int, device) -> "FactorCodes":
+        kw = dict(device=device)
+        return FactorCodes(torch.zeros(B, r_max, n // 2, dtype=torch.uint8, **kw),
+                           torch.zeros(B, r_max, d // 2, dtype=torch.uint8, **kw),
+                           torch.zeros(B, 2, 8, dtype=torch.float16, **kw),
+                           torch.zeros(B, r_max, dtype=torch.float16, **kw))
+
+    def nbytes(self) -> int:
+        return sum(t.numel() * t.element_size() for t in (self.lcodes, self.rcodes, self.fbook, self.phi16))
 
 
 def _stream_ptr(device) -> int:
@@ -170,6 +202,28 @@ class Context:
         self._check(lib().eoq_compress(self._h, blocks.data_ptr(), dtype, B, out.c_struct(), workspace.data_ptr(),
                                        workspace.numel(), _stream_ptr(blocks.device)))
         return out, workspace
+
+    def eoq_compress_q4(self, blocks: torch.Tensor, out: Packed | None = None, fq: FactorCodes | None = None,
+                        workspace: torch.Tensor | None = None):
+        """blocks: device tensor [B, n, d], float16, contiguous.  Returns (Packed, FactorCodes, workspace)."""
+        assert blocks.is_cuda and blocks.is_contiguous() and blocks.shape[1:] == (self.n, self.d)
+        B = blocks.shape[0]
+        dtype = {torch.float16: EOQ_F16, torch.float32: EOQ_F32}[blocks.dtype]
+        if out is None:
+            out = Packed.empty(B, self.n, self.d, self.bits, self.r_max, blocks.device)
+        if fq is None:
+            fq = FactorCodes.empty(B, self.n, self.d, self.r_max, blocks.device)
+        if workspace is None:
+            workspace = torch.empty(max(self.eoq_workspace_bytes(B), 16), dtype=torch.uint8, device=blocks.device)
+        self._check(lib().eoq_compress_q4(self._h, blocks.data_ptr(), dtype, B, out.c_struct(), fq.c_struct(),
+                                          workspace.data_ptr(), workspace.numel(), _stream_ptr(blocks.device)))
+        return out, fq, workspace
+
+    def eoq_expand_factors(self, rec: Packed, fq: FactorCodes):
+        B = rec.rank.shape[0]
+        self._check(lib().eoq_expand_factors(self._h, rec.c_struct(), fq.c_struct(), B,
+                                             _stream_ptr(rec.codes.device)))
+        return rec
 
     def eoq_decompress(self, rec: Packed, out: torch.Tensor | None = None) -> torch.Tensor:
         B = rec.rank.shape[0]

@@ -363,3 +363,72 @@ def test_paper_shaped_blocks_of_128_tokens():
         U.log_stats(f"cfg6-2tensors-b{bits}", st)
         assert st["max_lam_rel"] < 1e-9
         _recon_agreement(ctx, rec, b64, recs, bits)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# SVD factors at 4 bits (Alg. 3 line 3 with b_s = 4, data-adaptive Lloyd-Max codebooks of Sec. 3.1)
+# ---------------------------------------------------------------------------------------------------------------
+def _q4_case(blocks, bits, n, r_max, name):
+    b64 = blocks.double().cpu().numpy()
+    recs = U.oracle_compress(b64, bits, r_max=r_max, factor_bits=4)
+    ctx = eoq.Context(n=n, bits=bits, r_max=r_max)
+    rec, fq, ws = ctx.eoq_compress_q4(blocks.to(DEV).contiguous())
+    torch.cuda.synchronize()
+    lam = ctx.spectrum(ws, blocks.shape[0]).cpu().numpy()
+    # one factor code on the other side of a cell boundary moves an entry of the product by a whole level:
+    # the product is compared through the codes (compare_factor_codes), not to the 16-bit bar
+    st = U.compare_compress(b64, rec, lam, recs, bits, r_max=r_max, lowrank_tol=float("inf"))
+    sf = U.compare_factor_codes(rec, fq, recs)
+    U.log_stats(name, {**st, **{"factor_" + k: v for k, v in sf.items()}})
+    _recon_agreement(ctx, rec, b64, recs, bits)
+    return ctx, rec, fq, recs
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_q4_factors_against_oracle(bits):
+    """Two head-tensors (128 blocks of 512 x 128) with the factors at 4 bits: ranks, shrunk values, residual codes
+    and norms to the bars of the 16-bit path; codebooks, phi16 and factor codes against the oracle's; the closed
+    loop (residual taken against the expanded 4-bit factors) shows in the residual codes agreeing."""
+    spec = synth.config(2)
+    blocks, _ = synth.make_blocks(spec, tensors=range(2))
+    ctx, rec, fq, recs = _q4_case(blocks, bits, spec.n, 32, f"cfg2-2tensors-q4-b{bits}")
+    # eoq_expand_factors rebuilds the cached factors from the codes bit for bit
+    keep_l, keep_r = rec.lfac.clone(), rec.rfac.clone()
+    rank = rec.rank.cpu().numpy()
+    rec.lfac.zero_()
+    rec.rfac.zero_()
+    ctx.eoq_expand_factors(rec, fq)
+    torch.cuda.synchronize()
+    for b in range(blocks.shape[0]):
+        k = int(rank[b])
+        assert torch.equal(rec.lfac[b, :k].view(torch.int16), keep_l[b, :k].view(torch.int16)), b
+        assert torch.equal(rec.rfac[b, :k].view(torch.int16), keep_r[b, :k].view(torch.int16)), b
+        assert not bool(rec.lfac[b, k:].any()) and not bool(rec.rfac[b, k:].any())
+
+
+@pytest.mark.parametrize("n,B,r_max,rank_hi", [(128, 40, 32, 6), (1024, 12, 32, 12), (512, 9, 3, 6)])
+def test_q4_shapes_rank0_and_clamp(n, B, r_max, rank_hi):
+    """Blocks of 128 tokens (the paper's block shape), of 1024 tokens with pure-noise blocks among them (rank 0:
+    nothing to quantise, the codebook is written as zeros), and a clamped rank."""
+    spec = synth.BlockSpec("q4edge", n=n, n_tensors=1, blocks_per_tensor=B, rank_lo=1, rank_hi=rank_hi,
+                           frac_rank0=0.25 if n == 1024 else 0.0)
+    blocks, _ = synth.make_blocks(spec, seed=41)
+    _q4_case(blocks, 2, n, r_max, f"q4-n{n}-rmax{r_max}")
+
+
+def test_q4_argument_errors():
+    ctx = eoq.Context(n=512, bits=2)
+    x32 = torch.zeros(1, 512, 128, dtype=torch.float32, device=DEV)
+    with pytest.raises(eoq.EoqError) as ei:
+        ctx.eoq_compress_q4(x32)
+    assert ei.value.status == eoq.EOQ_ERR_UNSUPPORTED
+    big = eoq.Context(n=2048, bits=2, r_max=32)
+    x = torch.zeros(1, 2048, 128, dtype=torch.float16, device=DEV)
+    with pytest.raises(eoq.EoqError) as ei:
+        big.eoq_compress_q4(x)
+    assert ei.value.status == eoq.EOQ_ERR_UNSUPPORTED
+    rec = eoq.Packed.empty(1, 512, 128, 2, 32, DEV)
+    fq = eoq.FactorCodes.empty(1, 512, 128, 32, DEV)
+    bad = eoq._FactorCodes(fq.lcodes.data_ptr(), None, fq.fbook.data_ptr(), fq.phi16.data_ptr())
+    assert eoq.lib().eoq_expand_factors(ctx._h, rec.c_struct(), bad, 1, None) == eoq.EOQ_ERR_ARG
+    torch.cuda.synchronize()
