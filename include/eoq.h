@@ -149,6 +149,37 @@ eoq_status eoq_compress_q4(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, in
                            eoq_factor_codes fq, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Placement of a batch that is not stored block after block: chunk-at-a-time compression while a cache is being
+ * filled (Sec. 3.1: blocks of 128 tokens compressed as soon as they are complete; Sec. 5: chunked prefill), with
+ * the keys or values in the layout the model produced them in, written into a record store that is laid out for
+ * scoring ([tensor][block]).  Strides are in ELEMENTS of the input dtype.
+ *   input block b starts at  (b / in_group_size) * in_group_stride + (b % in_group_size) * in_block_stride,
+ *   its token t at           + t * in_token_stride            (d contiguous entries per token),
+ *   its record goes to slot  out_first + b * out_stride       of every array of the eoq_packed / eoq_factor_codes.
+ * Example: a chunk of n tokens of L tensors [L][n][H][d] (token-major, H heads interleaved), records
+ * [L*H][blocks_per_tensor], chunk number c:  {n*H*d, H, d, H*d, c, blocks_per_tensor}.
+ * Input strides must be multiples of 8, in_token_stride >= d, in_group_size >= 1, out_first >= 0, out_stride >= 1.
+ */
+typedef struct {
+  int64_t in_group_stride;
+  int32_t in_group_size;
+  int64_t in_block_stride;
+  int64_t in_token_stride;
+  int64_t out_first;
+  int64_t out_stride;
+} eoq_chunk_layout;
+
+/*
+ * eoq_compress (fq == NULL) or eoq_compress_q4 (fq != NULL) on B blocks placed by `lay`.  `out` and `fq` hold the
+ * BASE pointers of the whole record store; only the slots `lay` names are written, and the caller guarantees that
+ * they exist and are distinct.  The workspace is indexed by b (eoq_workspace_bytes(ctx, B) bytes), its first B*d
+ * doubles hold the eigenvalues of input block b.  Results are bit-identical to the dense calls on the same blocks.
+ */
+eoq_status eoq_compress_chunk(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_chunk_layout lay,
+                              eoq_packed out, const eoq_factor_codes* fq, void* workspace, size_t workspace_bytes,
+                              void* hip_stream);
+
+/*
  * Rebuild rec.lfac / rec.rfac (rows below rec.rank[b]) from the 4-bit codes, codebooks and phi16 of `fq`, e.g.
  * after loading a record that was stored without them.  Reads rec.rank, writes rec.lfac and rec.rfac.
  */
@@ -177,6 +208,23 @@ eoq_status eoq_decompress(eoq_ctx* ctx, eoq_packed in, int64_t B, void* out_fp16
 eoq_status eoq_scores(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_heads,
                       int64_t blocks_per_head, const void* q_fp16, int n_q_heads,
                       float* scores, void* hip_stream);
+
+/*
+ * eoq_scores over a cache that is still being filled (Sec. 3.1 / Sec. 7: blocks are compressed as they complete, the
+ * newest fewer-than-n tokens of every head wait uncompressed in binary16): the record store has room for
+ * block_capacity blocks per (sequence, KV head), of which the first blocks_filled are valid, and the tail buffer
+ * holds tail_len valid tokens per head.
+ *   keys       DEVICE record store, block j of KV head g of sequence s at slot (s*n_kv_heads + g)*block_capacity + j.
+ *   tail_fp16  DEVICE, [n_seq][n_kv_heads][tail_capacity][d] binary16; may be NULL when tail_len = 0.
+ *   scores     DEVICE, [n_seq][n_q_heads][score_stride] float32: entries 0 .. blocks_filled*n - 1 of a row are the
+ *              blocks' tokens, the next tail_len entries <q, tail token>/sqrt(d); the rest of the row is untouched.
+ * blocks_filled <= block_capacity, tail_len <= tail_capacity, tail_len < n, score_stride >= blocks_filled*n + tail_len.
+ * Everything else as eoq_scores.
+ */
+eoq_status eoq_scores_stream(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_heads, int64_t block_capacity,
+                             int64_t blocks_filled, const void* tail_fp16, int64_t tail_capacity, int64_t tail_len,
+                             const void* q_fp16, int n_q_heads, float* scores, int64_t score_stride,
+                             void* hip_stream);
 
 /*
  * Eigensolver used by eoq_compress for the d x d Gram matrix (the paper only asks for the SVD of the

@@ -31,7 +31,7 @@ __all__ = [
     "bulk_edge", "estimate_rank", "impute_noise_spectrum", "shrink",
     "EOptShrinkResult", "eoptshrink",
     "tq_mse_encode", "tq_mse_decode",
-    "BlockRecord", "compress_block", "decompress_block", "score_block",
+    "BlockRecord", "compress_block", "decompress_block", "score_block", "score_stream",
     "pack_codes", "unpack_codes", "fp16_round", "fp16_bits", "bits_per_entry",
     "FLAG_RANK_CLAMPED", "FLAG_SHRINK_GUARD",
     "FACTOR_LEVELS", "FACTOR_LLOYD_ITERS", "adaptive_magnitudes", "factor_encode", "factor_decode",
@@ -496,6 +496,19 @@ def score_block(q: np.ndarray, rec: BlockRecord, Pi: np.ndarray, cb: Codebook) -
     block (Sec. 2.1 attention logits; Remark 6.5 split into low-rank + residual)."""
     x = decompress_block(rec, Pi, cb)
     return (np.asarray(q, dtype=np.float64) @ x.T) / math.sqrt(rec.d)
+
+
+def score_stream(q: np.ndarray, recs, tail: np.ndarray, Pi: np.ndarray, cb: Codebook) -> np.ndarray:
+    """Logits of one KV head whose cache is still being filled (Sec. 3.1: blocks are
+    compressed as they complete; Sec. 7: the newest fewer-than-n tokens stay in
+    FP16): the compressed blocks `recs` in token order, then the uncompressed
+    tail [t, d], whose logits are the plain <q, k_t> / sqrt(d) of Sec. 2.1."""
+    q = np.asarray(q, dtype=np.float64)
+    parts = [score_block(q, r, Pi, cb) for r in recs]
+    tail = np.asarray(tail, dtype=np.float64)
+    if tail.shape[0]:
+        parts.append((q @ tail.T) / math.sqrt(tail.shape[1]))
+    return np.concatenate(parts, axis=-1) if parts else np.zeros(q.shape[:-1] + (0,))
 
 
 # --------------------------------------------------------------------------

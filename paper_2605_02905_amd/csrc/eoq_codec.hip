@@ -18,7 +18,8 @@ constexpr int ENC_THREADS = 256;
 constexpr int LDS_X = D + 1;
 
 __global__ __launch_bounds__(ENC_THREADS) void eoq_encode_kernel(
-    const void* __restrict__ blocks, int dtype, int n, int bits, int r_max, const float* __restrict__ pit,
+    const void* __restrict__ blocks, EoqBlockMap map, int64_t b0, int dtype, int n, int bits, int r_max,
+    const float* __restrict__ pit,
     const float* __restrict__ tab, const float* __restrict__ wfac, const int32_t* __restrict__ rank_in,
     const uint16_t* __restrict__ rfac, uint16_t* __restrict__ lfac, uint16_t* __restrict__ norms,
     uint8_t* __restrict__ codes) {
@@ -30,16 +31,17 @@ __global__ __launch_bounds__(ENC_THREADS) void eoq_encode_kernel(
   __shared__ float rho_s[ENC_ROWS];
 
   const int tid = threadIdx.x;
-  const size_t blk = blockIdx.y;
+  const size_t blk = (size_t)b0 + blockIdx.y;
+  const size_t slot = map.slot(blk);
   const int row0 = blockIdx.x * ENC_ROWS;
-  const int r = rank_in[blk];
+  const int r = rank_in[slot];
 
   // stage the strip, the rotation and the factors
   for (int g = tid; g < ENC_ROWS * D / 8; g += ENC_THREADS) {
     const int e = g * 8;
     float v[8];
-    load8(blocks, dtype, (blk * (size_t)n + row0) * D + e, v);
     const int t = e >> 7, j = e & (D - 1);
+    load8(blocks, dtype, map.in_base(blk) + (size_t)(row0 + t) * (size_t)map.token_stride + j, v);
 #pragma unroll
     for (int i = 0; i < 8; ++i) X[t * LDS_X + j + i] = v[i];
   }
@@ -47,7 +49,7 @@ __global__ __launch_bounds__(ENC_THREADS) void eoq_encode_kernel(
     reinterpret_cast<float4*>(PT)[e] = reinterpret_cast<const float4*>(pit)[e];
   for (int e = tid; e < r * D; e += ENC_THREADS) {
     Wl[e] = wfac[blk * r_max * D + e];
-    Vl[e] = half_bits_to_float(rfac[blk * r_max * D + e]);
+    Vl[e] = half_bits_to_float(rfac[slot * r_max * D + e]);
   }
   __syncthreads();
 
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(ENC_THREADS) void eoq_encode_kernel(
       float acc = 0.0f;
       for (int j = 0; j < D; ++j) acc = fmaf(X[t * LDS_X + j], Wl[i * D + j], acc);
       const uint16_t hb = float_to_half_bits(acc);
-      lfac[(blk * r_max + i) * (size_t)n + row0 + t] = hb;
+      lfac[(slot * r_max + i) * (size_t)n + row0 + t] = hb;
       Cl[t * (EOQ_RMAX_CAP + 1) + i] = half_bits_to_float(hb);
     }
   }
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(ENC_THREADS) void eoq_encode_kernel(
     const float rho = sqrtf(ss);
     const float sc = (rho > 0.0f) ? sqrtf((float)D) / rho : 0.0f;
     for (int m = 0; m < D / 4; ++m) X[t * LDS_X + q + 4 * m] *= sc;
-    if (q == 0) norms[blk * (size_t)n + row0 + t] = float_to_half_bits(rho);
+    if (q == 0) norms[slot * (size_t)n + row0 + t] = float_to_half_bits(rho);
   }
   __syncthreads();
 
@@ -141,7 +143,7 @@ __global__ __launch_bounds__(ENC_THREADS) void eoq_encode_kernel(
 #pragma unroll
       for (int p = 0; p < 4; ++p) plane[p] |= ((c >> p) & 1u) << j;
     }
-    uint32_t* dst = reinterpret_cast<uint32_t*>(codes + (blk * (size_t)n + row0 + t) * (size_t)(bits * D / 8));
+    uint32_t* dst = reinterpret_cast<uint32_t*>(codes + (slot * (size_t)n + row0 + t) * (size_t)(bits * D / 8));
     for (int p = 0; p < bits; ++p) dst[p * 4 + q] = plane[p];
   }
 }
@@ -162,12 +164,9 @@ hipError_t eoq_launch_encode(const EoqLaunch& L, const void* blocks, int dtype, 
   // gridDim.y is limited to 65535: split long batches
   for (int64_t b0 = 0; b0 < B; b0 += 32768) {
     const int64_t nb = (B - b0 < 32768) ? B - b0 : 32768;
-    const size_t esz = (dtype == EOQ_F16) ? 2 : 4;
-    hipLaunchKernelGGL(eoq_encode_kernel, dim3(L.n / ENC_ROWS, (unsigned)nb), dim3(ENC_THREADS), 0, L.stream,
-                       static_cast<const char*>(blocks) + (size_t)b0 * L.n * D * esz, dtype, L.n, L.bits, L.r_max,
-                       L.pit, L.tab, wfac + (size_t)b0 * L.r_max * D, out.rank + b0, out.rfac + (size_t)b0 * L.r_max * D,
-                       out.lfac + (size_t)b0 * L.r_max * L.n, out.norms + (size_t)b0 * L.n,
-                       out.codes + (size_t)b0 * L.n * (L.bits * D / 8));
+    hipLaunchKernelGGL(eoq_encode_kernel, dim3(L.n / ENC_ROWS, (unsigned)nb), dim3(ENC_THREADS), 0, L.stream, blocks,
+                       L.map, b0, dtype, L.n, L.bits, L.r_max, L.pit, L.tab, wfac, out.rank, out.rfac, out.lfac,
+                       out.norms, out.codes);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -103,7 +103,7 @@ __device__ __forceinline__ void lloyd_scan(const float* x, int count, const doub
 
 template <int RCAP>
 __global__ __launch_bounds__(THREADS) void eoq_factor_quant_kernel(
-    const uint16_t* __restrict__ blocks, int n, int r_max, GaussLevels g, const int32_t* __restrict__ rank_in,
+    const uint16_t* __restrict__ blocks, EoqBlockMap map, int n, int r_max, GaussLevels g, const int32_t* __restrict__ rank_in,
     const float* __restrict__ phi, const float* __restrict__ sigma, const float* __restrict__ wfac,
     uint16_t* __restrict__ rfac, uint16_t* __restrict__ lfac, uint8_t* __restrict__ lcodes,
     uint8_t* __restrict__ rcodes, uint16_t* __restrict__ fbook, uint16_t* __restrict__ phi16) {
@@ -111,7 +111,8 @@ __global__ __launch_bounds__(THREADS) void eoq_factor_quant_kernel(
   __shared__ __align__(16) double red[2][4][16];   // [parity][wave][U: 8 sums, V: 8 sums]
   __shared__ int redc[2][4][16];                   // [parity][wave][U: 7 counts, pad, V: 7 counts, pad]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const size_t blk = blockIdx.x;
+  const size_t wblk = blockIdx.x;            // number in the batch: workspace and input
+  const size_t blk = map.slot(wblk);         // record slot: everything that is stored
   const int r = rank_in[blk];
   // the launch with the small table takes the blocks of rank 1 .. 8 (and clears the codebook of rank-0 blocks), the
   // launch with the large one the rest
@@ -128,12 +129,12 @@ __global__ __launch_bounds__(THREADS) void eoq_factor_quant_kernel(
   for (int e = tid; e < r * D; e += THREADS) {
     const int i = e >> 7;
     const float ph = phi[blk * r_max + i], sg = sigma[blk * r_max + i];
-    Vs[e] = (ph > 0.0f) ? wfac[blk * (size_t)r_max * D + e] * (sg / ph) : half_bits_to_float(rfac[blk * (size_t)r_max * D + e]);
+    Vs[e] = (ph > 0.0f) ? wfac[wblk * (size_t)r_max * D + e] * (sg / ph) : half_bits_to_float(rfac[blk * (size_t)r_max * D + e]);
   }
   __syncthreads();
   // left vectors U = S V / sigma, one token per lane and pass, four components at a time
   for (int t = tid; t < n; t += THREADS) {
-    const uint16_t* row = blocks + (blk * (size_t)n + t) * D;
+    const uint16_t* row = blocks + map.in_base(wblk) + (size_t)t * (size_t)map.token_stride;
     for (int i0 = 0; i0 < r; i0 += 4) {
       const float* vrow[4];
 #pragma unroll
@@ -320,7 +321,7 @@ __global__ __launch_bounds__(THREADS) void eoq_factor_expand_kernel(
     uint16_t* __restrict__ lfac, uint16_t* __restrict__ rfac) {
   const int tid = threadIdx.x;
   const size_t blk = blockIdx.x;
-  const int r = rank_in[blk];
+  const int r = min(max(rank_in[blk], 0), r_max);   // a record read back from storage: never index past r_max rows
   __shared__ uint16_t book[2 * LEVELS];
   if (tid < 2 * LEVELS) book[tid] = fbook[blk * 2 * LEVELS + tid];
   __syncthreads();
@@ -362,7 +363,7 @@ hipError_t eoq_launch_factor_quant(const EoqLaunch& L, const void* blocks_fp16, 
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds8);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(eoq_factor_quant_kernel<8>, dim3((unsigned)B), dim3(THREADS), lds8, L.stream,
-                     static_cast<const uint16_t*>(blocks_fp16), L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
+                     static_cast<const uint16_t*>(blocks_fp16), L.map, L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
                      out.rfac, out.lfac, fq.lcodes, fq.rcodes, fq.fbook, fq.phi16);
   e = hipGetLastError();
   if (e != hipSuccess || L.r_max <= 8) return e;
@@ -371,7 +372,7 @@ hipError_t eoq_launch_factor_quant(const EoqLaunch& L, const void* blocks_fp16, 
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(eoq_factor_quant_kernel<32>, dim3((unsigned)B), dim3(THREADS), lds, L.stream,
-                     static_cast<const uint16_t*>(blocks_fp16), L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
+                     static_cast<const uint16_t*>(blocks_fp16), L.map, L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
                      out.rfac, out.lfac, fq.lcodes, fq.rcodes, fq.fbook, fq.phi16);
   return hipGetLastError();
 }

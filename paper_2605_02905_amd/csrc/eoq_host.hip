@@ -140,6 +140,7 @@ EoqLaunch make_launch(const eoq_ctx* ctx, void* stream) {
   L.stream = static_cast<hipStream_t>(stream);
   L.ev = ctx->profile ? ctx->ev : nullptr;
   L.solver = ctx->solver;
+  L.map = eoq_dense_map(ctx->n);
   return L;
 }
 
@@ -264,21 +265,34 @@ eoq_status eoq_codebook(const eoq_ctx* ctx, float* host_centroids, float* host_b
   return EOQ_OK;
 }
 
-eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_packed out,
-                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// eoq_compress, eoq_compress_q4 and eoq_compress_chunk: `fq` null = binary16 factors
+eoq_status compress_impl(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, const EoqBlockMap& map,
+                         eoq_packed out, const eoq_factor_codes* fq, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
   if (!ctx) return EOQ_ERR_ARG;
   ctx->err.clear();
   if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
   if (B < 0) return fail(ctx, EOQ_ERR_ARG, "negative block count");
   if (dtype != EOQ_F16 && dtype != EOQ_F32) return fail(ctx, EOQ_ERR_UNSUPPORTED, "dtype must be EOQ_F16 or EOQ_F32");
+  if (fq) {
+    if (dtype != EOQ_F16) return fail(ctx, EOQ_ERR_UNSUPPORTED, "4-bit factors: dtype must be EOQ_F16");
+    if ((int64_t)ctx->n * ctx->r_max > 32768) return fail(ctx, EOQ_ERR_UNSUPPORTED, "4-bit factors: n * r_max exceeds 32768");
+  }
   if (B == 0) return EOQ_OK;
   if (!blocks || !workspace) return fail(ctx, EOQ_ERR_ARG, "null blocks or workspace pointer");
   if (!aligned16(blocks) || !aligned16(workspace)) return fail(ctx, EOQ_ERR_ARG, "blocks/workspace not 16-byte aligned");
   if (eoq_status st = check_packed(ctx, out)) return st;
+  if (fq && (!fq->lcodes || !fq->rcodes || !fq->fbook || !fq->phi16))
+    return fail(ctx, EOQ_ERR_ARG, "eoq_factor_codes has a null member");
   if (workspace_bytes < eoq_workspace_bytes(ctx, B)) return fail(ctx, EOQ_ERR_WORKSPACE, "workspace too small");
   if (B > (int64_t)1 << 24) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
 
-  const EoqLaunch L = make_launch(ctx, hip_stream);
+  EoqLaunch L = make_launch(ctx, hip_stream);
+  L.map = map;
   double* lam = static_cast<double*>(workspace);
   char* ws = static_cast<char*>(workspace);
   float* wfac = reinterpret_cast<float*>(ws + eoq_ws_lam_bytes(B));
@@ -287,7 +301,14 @@ eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64
   const uintptr_t tri_at = reinterpret_cast<uintptr_t>(reinterpret_cast<char*>(fb_count) + eoq_ws_list_bytes(B));
   double* tri = reinterpret_cast<double*>((tri_at + 63) & ~(uintptr_t)63);
   hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, fb_count, fb_list, tri, out);
-  if (e == hipSuccess) e = eoq_launch_encode(L, blocks, (int)dtype, B, wfac, out);
+  if (fq) {
+    if (L.ev && e == hipSuccess) (void)hipEventRecord(L.ev[2], L.stream);  // the factor stage counts as encode time
+    if (e == hipSuccess) e = eoq_launch_factor_quant(L, blocks, B, wfac, out, *fq, ctx->gauss16);
+    if (e == hipSuccess) e = eoq_launch_encode_f16(L, blocks, B, wfac, out, true);
+    if (L.ev && e == hipSuccess) (void)hipEventRecord(L.ev[3], L.stream);
+  } else if (e == hipSuccess) {
+    e = eoq_launch_encode(L, blocks, (int)dtype, B, wfac, out);
+  }
   if (ctx->profile) ctx->ev_valid[0] = ctx->ev_valid[1] = (e == hipSuccess);
   if (e != hipSuccess) {
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);
@@ -296,41 +317,37 @@ eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64
   return EOQ_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_packed out,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  return compress_impl(ctx, blocks, dtype, B, eoq_dense_map(ctx->n), out, nullptr, workspace, workspace_bytes,
+                       hip_stream);
+}
+
 eoq_status eoq_compress_q4(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_packed out,
                            eoq_factor_codes fq, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!ctx) return EOQ_ERR_ARG;
-  ctx->err.clear();
-  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
-  if (B < 0) return fail(ctx, EOQ_ERR_ARG, "negative block count");
-  if (dtype != EOQ_F16) return fail(ctx, EOQ_ERR_UNSUPPORTED, "4-bit factors: dtype must be EOQ_F16");
-  if ((int64_t)ctx->n * ctx->r_max > 32768) return fail(ctx, EOQ_ERR_UNSUPPORTED, "4-bit factors: n * r_max exceeds 32768");
-  if (B == 0) return EOQ_OK;
-  if (!blocks || !workspace) return fail(ctx, EOQ_ERR_ARG, "null blocks or workspace pointer");
-  if (!aligned16(blocks) || !aligned16(workspace)) return fail(ctx, EOQ_ERR_ARG, "blocks/workspace not 16-byte aligned");
-  if (eoq_status st = check_packed(ctx, out)) return st;
-  if (!fq.lcodes || !fq.rcodes || !fq.fbook || !fq.phi16) return fail(ctx, EOQ_ERR_ARG, "eoq_factor_codes has a null member");
-  if (workspace_bytes < eoq_workspace_bytes(ctx, B)) return fail(ctx, EOQ_ERR_WORKSPACE, "workspace too small");
-  if (B > (int64_t)1 << 24) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  return compress_impl(ctx, blocks, dtype, B, eoq_dense_map(ctx->n), out, &fq, workspace, workspace_bytes,
+                       hip_stream);
+}
 
-  const EoqLaunch L = make_launch(ctx, hip_stream);
-  double* lam = static_cast<double*>(workspace);
-  char* ws = static_cast<char*>(workspace);
-  float* wfac = reinterpret_cast<float*>(ws + eoq_ws_lam_bytes(B));
-  int* fb_count = reinterpret_cast<int*>(ws + eoq_ws_lam_bytes(B) + eoq_ws_wfac_bytes(B, ctx->r_max));
-  int* fb_list = fb_count + 4;
-  const uintptr_t tri_at = reinterpret_cast<uintptr_t>(reinterpret_cast<char*>(fb_count) + eoq_ws_list_bytes(B));
-  double* tri = reinterpret_cast<double*>((tri_at + 63) & ~(uintptr_t)63);
-  hipError_t e = eoq_launch_spectral(L, blocks, (int)dtype, B, lam, wfac, fb_count, fb_list, tri, out);
-  if (L.ev && e == hipSuccess) (void)hipEventRecord(L.ev[2], L.stream);  // the factor stage counts as encode time
-  if (e == hipSuccess) e = eoq_launch_factor_quant(L, blocks, B, wfac, out, fq, ctx->gauss16);
-  if (e == hipSuccess) e = eoq_launch_encode_f16(L, blocks, B, wfac, out, true);
-  if (L.ev && e == hipSuccess) (void)hipEventRecord(L.ev[3], L.stream);
-  if (ctx->profile) ctx->ev_valid[0] = ctx->ev_valid[1] = (e == hipSuccess);
-  if (e != hipSuccess) {
-    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
-    return EOQ_ERR_HIP;
-  }
-  return EOQ_OK;
+eoq_status eoq_compress_chunk(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_chunk_layout lay,
+                              eoq_packed out, const eoq_factor_codes* fq, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (lay.in_group_size < 1 || lay.in_token_stride < ctx->d || lay.in_group_stride < 0 || lay.in_block_stride < 0 ||
+      lay.out_first < 0 || lay.out_stride < 1)
+    return fail(ctx, EOQ_ERR_ARG, "chunk layout: sizes and strides out of range");
+  if ((lay.in_token_stride | lay.in_group_stride | lay.in_block_stride) & 7)
+    return fail(ctx, EOQ_ERR_ARG, "chunk layout: input strides must be multiples of 8 elements");
+  const EoqBlockMap map{lay.in_group_stride, lay.in_block_stride, lay.in_token_stride, lay.out_first, lay.out_stride,
+                        lay.in_group_size};
+  return compress_impl(ctx, blocks, dtype, B, map, out, fq, workspace, workspace_bytes, hip_stream);
 }
 
 eoq_status eoq_expand_factors(eoq_ctx* ctx, eoq_packed rec, eoq_factor_codes fq, int64_t B, void* hip_stream) {
@@ -386,6 +403,41 @@ eoq_status eoq_scores(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_hea
     return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
   const EoqLaunch L = make_launch(ctx, hip_stream);
   hipError_t e = eoq_launch_scores(L, keys, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores);
+  if (ctx->profile) ctx->ev_valid[3] = (e == hipSuccess);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+eoq_status eoq_scores_stream(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_heads, int64_t block_capacity,
+                             int64_t blocks_filled, const void* tail_fp16, int64_t tail_capacity, int64_t tail_len,
+                             const void* q_fp16, int n_q_heads, float* scores, int64_t score_stride,
+                             void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (n_seq < 0 || blocks_filled < 0 || tail_len < 0 || n_kv_heads < 1 || n_q_heads < 1)
+    return fail(ctx, EOQ_ERR_ARG, "negative or zero size");
+  if (blocks_filled > block_capacity || tail_len > tail_capacity)
+    return fail(ctx, EOQ_ERR_ARG, "more blocks or tail tokens than the stores hold");
+  if (score_stride < blocks_filled * ctx->n + tail_len)
+    return fail(ctx, EOQ_ERR_ARG, "score rows shorter than the blocks' tokens plus the tail");
+  if (n_q_heads % n_kv_heads != 0 || n_q_heads / n_kv_heads > 8)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "query heads must be a multiple (1..8) of KV heads");
+  if (tail_len >= ctx->n) return fail(ctx, EOQ_ERR_UNSUPPORTED, "the tail holds fewer than n tokens");
+  if (n_seq == 0 || (blocks_filled == 0 && tail_len == 0)) return EOQ_OK;
+  if (!q_fp16 || !scores || !aligned16(q_fp16) || !aligned16(scores))
+    return fail(ctx, EOQ_ERR_ARG, "null or misaligned query/score pointer");
+  if (tail_len > 0 && (!tail_fp16 || !aligned16(tail_fp16))) return fail(ctx, EOQ_ERR_ARG, "null or misaligned tail pointer");
+  if (blocks_filled > 0)
+    if (eoq_status st = check_packed(ctx, keys)) return st;
+  if (n_seq * n_kv_heads * block_capacity > (int64_t)1 << 24)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  hipError_t e = eoq_launch_scores(L, keys, n_seq, n_kv_heads, blocks_filled, q_fp16, n_q_heads, scores, block_capacity,
+                                   score_stride, tail_fp16, tail_capacity, (int)tail_len);
   if (ctx->profile) ctx->ev_valid[3] = (e == hipSuccess);
   if (e != hipSuccess) {
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);

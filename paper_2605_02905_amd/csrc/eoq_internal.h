@@ -35,8 +35,23 @@ struct eoq_ctx {
   bool ev_valid[4] = {false, false, false, false};
 };
 
+// Where the blocks of a batch sit in memory and which record slots they fill.  Input block b starts at element
+// (b / group_size) * group_stride + (b % group_size) * block_stride, its token t at + t * token_stride; its
+// record goes to slot out_first + b * out_stride.  Workspace arrays are always indexed by b.
+struct EoqBlockMap {
+  int64_t group_stride, block_stride, token_stride, out_first, out_stride;
+  int32_t group_size;
+  __host__ __device__ size_t in_base(size_t b) const {
+    const unsigned g = (unsigned)b / (unsigned)group_size;
+    return (size_t)g * (size_t)group_stride + (size_t)((unsigned)b - g * (unsigned)group_size) * (size_t)block_stride;
+  }
+  __host__ __device__ size_t slot(size_t b) const { return (size_t)out_first + b * (size_t)out_stride; }
+};
+inline EoqBlockMap eoq_dense_map(int n) { return EoqBlockMap{(int64_t)n * 128, 0, 128, 0, 1, 1}; }
+
 // Device-side view of everything a launch needs.
 struct EoqLaunch {
+  EoqBlockMap map;
   int n, bits, r_max, k;
   double rank_thr;
   const float* pi;
@@ -68,5 +83,9 @@ hipError_t eoq_launch_factor_quant(const EoqLaunch& L, const void* blocks_fp16, 
                                    eoq_packed out, eoq_factor_codes fq, const double* gauss_levels);
 hipError_t eoq_launch_factor_expand(const EoqLaunch& L, eoq_packed rec, eoq_factor_codes fq, int64_t B);
 hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void* out_fp16);
+// block_capacity / score_stride <= 0: the dense case (blocks_per_head slots per head, rows of blocks_per_head * n);
+// tail_len > 0 adds the scores of the binary16 tail behind the blocks' scores
 hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq, int n_kv_heads,
-                             int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores);
+                             int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
+                             int64_t block_capacity = 0, int64_t score_stride = 0, const void* tail_fp16 = nullptr,
+                             int64_t tail_capacity = 0, int tail_len = 0);

@@ -131,7 +131,7 @@ __device__ __forceinline__ void decode_fetch(DecodeFetch<BITS>& f, int64_t blk, 
                                              const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac) {
   constexpr int ROWB = BITS * D / 8;
   const size_t tok = (size_t)blk * n + t0 + tl;
-  f.r = rank_in[blk];
+  f.r = min(max(rank_in[blk], 0), r_max);   // records may come from storage: never index past r_max rows
 #pragma unroll
   for (int p = 0; p < BITS; ++p) f.pl[p] = *reinterpret_cast<const uint4*>(codes + tok * ROWB + p * 16);
   f.rho = norms[tok];
@@ -322,7 +322,8 @@ __device__ __forceinline__ void split_half(float v, uint16_t& hi, uint16_t& lo) 
 
 template <int BITS>
 __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
-    int n, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, int run, const float* __restrict__ pit,
+    int n, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, int64_t block_capacity, int64_t score_stride,
+    int run, const float* __restrict__ pit,
     const float* __restrict__ tab, const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
     const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac,
     const uint16_t* __restrict__ q, float* __restrict__ scores) {
@@ -337,7 +338,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   const size_t sq = sg / n_kv_heads, kv = sg % n_kv_heads;
   const int n_q_heads = n_kv_heads * group;
   const size_t q0 = (sq * n_q_heads + kv * group) * D;
-  const size_t T = (size_t)blocks_per_head * n;
+  const size_t T = (size_t)score_stride;   // entries per score row (>= blocks_per_head * n)
   constexpr int ROWB = BITS * D / 8;
 
   build_mask_table(mask_tab, tid);
@@ -365,8 +366,8 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   const int64_t j_end = min((int64_t)(blockIdx.x + 1) * run, blocks_per_head);
   for (int64_t jb = (int64_t)blockIdx.x * run; jb < j_end; ++jb) {
-    const size_t blk = sg * (size_t)blocks_per_head + jb;
-    const int r = rank_in[blk];
+    const size_t blk = sg * (size_t)block_capacity + jb;   // the store holds block_capacity slots per head
+    const int r = min(max(rank_in[blk], 0), r_max);   // records may come from storage: never index past r_max rows
     __syncthreads();
     // w[h][i] = <v_i, q_h>: the low-rank term is <C_t, w_h>
     for (int e = tid; e < group * r; e += THREADS) {
@@ -443,6 +444,37 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   }
 }
 
+// Scores of the uncompressed tail (the newest tokens of every head, binary16, not yet a full block):
+// scores[s][h][offset + t] = <q[s][h], tail[s][g][t]> / sqrt(d).  One workgroup per (sequence, KV head); 16 lanes
+// share a token (16 bytes each), float32 accumulation of exact binary16 products.
+__global__ __launch_bounds__(THREADS) void eoq_scores_tail_kernel(
+    int n_kv_heads, int group, int64_t tail_capacity, int tail_len, const uint16_t* __restrict__ tail,
+    const uint16_t* __restrict__ q, float* __restrict__ scores, int64_t score_stride, int64_t offset) {
+  __shared__ float qs[SC_MAXG * D];
+  const int tid = threadIdx.x, l16 = tid & 15;
+  const size_t sg = blockIdx.x;
+  const size_t sq = sg / n_kv_heads, kv = sg % n_kv_heads;
+  const int n_q_heads = n_kv_heads * group;
+  for (int e = tid; e < group * D; e += THREADS) qs[e] = half_bits_to_float(q[(sq * n_q_heads + kv * group) * D + e]);
+  __syncthreads();
+  const float inv_sqrt_d = 1.0f / sqrtf((float)D);
+  for (int t0 = 0; t0 < tail_len; t0 += THREADS / 16) {   // uniform trip count: the row sums need whole rows
+    const int t = t0 + (tid >> 4);
+    float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (t < tail_len) load8(tail, EOQ_F16, (sg * (size_t)tail_capacity + t) * D + 8 * l16, x);
+    for (int h = 0; h < group; ++h) {
+      float acc = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc = fmaf(x[e], qs[h * D + 8 * l16 + e], acc);
+      acc += dpp_mov<0xB1>(acc);
+      acc += dpp_mov<0x4E>(acc);
+      acc += dpp_mov<0x141>(acc);
+      acc += dpp_mov<0x140>(acc);
+      if (l16 == 0 && t < tail_len) scores[(sq * n_q_heads + kv * group + h) * (size_t)score_stride + offset + t] = acc * inv_sqrt_d;
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // encode (binary16 blocks): one workgroup per block, 128 tokens per pass.
 //   phase 1 (wave w, its own 32 tokens, v_mfma_f32_32x32x8_f16 so that every result feeds the next product
@@ -469,7 +501,7 @@ constexpr int VLD = EOQ_RMAX_CAP + 8;  // row stride (halfs) of V^T in LDS
 // projected, and the residual is taken against them.
 template <int BITS, bool FQ>
 __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
-    const uint16_t* __restrict__ blocks, int n, int r_max, const uint16_t* __restrict__ pih,
+    const uint16_t* __restrict__ blocks, EoqBlockMap map, int n, int r_max, const uint16_t* __restrict__ pih,
     const float* __restrict__ tab, const float* __restrict__ wfac, const int32_t* __restrict__ rank_in,
     const uint16_t* __restrict__ rfac, uint16_t* lfac, uint16_t* __restrict__ norms,
     uint8_t* __restrict__ codes) {
@@ -481,7 +513,8 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
   const size_t blk = blockIdx.x;
-  const int r = rank_in[blk];
+  const size_t slot = map.slot(blk);
+  const int r = rank_in[slot];
   constexpr int ROWB = BITS * D / 8;
 
   // stationary rotation operand: rows c = 32w + l32 of Pi, hi and lo
@@ -506,7 +539,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
     uint16_t hi = 0, lo = 0, v16 = 0;
     if (i < r) {
       if constexpr (!FQ) split_half(wfac[(blk * r_max + i) * D + j], hi, lo);
-      v16 = rfac[(blk * r_max + i) * D + j];
+      v16 = rfac[(slot * r_max + i) * D + j];
     }
     if constexpr (!FQ) {
       Wh[i * ZLD + j] = hi;
@@ -521,12 +554,13 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
     // ---- phase 1 ----
     {
       uint16_t* tile = X + 32 * wave * ZLD;
-      const uint16_t* src = blocks + (blk * (size_t)n + t0 + 32 * wave) * D;
+      const size_t tok = (size_t)map.token_stride;
+      const uint16_t* src = blocks + map.in_base(blk) + (size_t)(t0 + 32 * wave) * tok;
       // 32 rows x 256 B, 16 B per lane and load: 4 rows per instruction
 #pragma unroll
       for (int it = 0; it < 8; ++it) {
         const int row = 4 * it + (lane >> 4), col = (lane & 15) * 8;
-        const uint4 v = *reinterpret_cast<const uint4*>(src + row * D + col);
+        const uint4 v = *reinterpret_cast<const uint4*>(src + row * tok + col);
         *reinterpret_cast<uint4*>(tile + row * ZLD + col) = v;
       }
       __builtin_amdgcn_s_waitcnt(0);   // the tile is private to this wave: wait for its own LDS writes
@@ -547,7 +581,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
-            Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(lfac[(blk * r_max + i) * (size_t)n + tg] ^ 0x8000u) : (uint16_t)0;
+            Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(lfac[(slot * r_max + i) * (size_t)n + tg] ^ 0x8000u) : (uint16_t)0;
           }
         } else {
           float16v Cacc;
@@ -566,7 +600,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
           for (int v = 0; v < 16; ++v) {
             const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
             const uint16_t hb = float_to_half_bits(Cacc[v]);
-            if (i < r) lfac[(blk * r_max + i) * (size_t)n + tg] = hb;
+            if (i < r) lfac[(slot * r_max + i) * (size_t)n + tg] = hb;
             Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(hb ^ 0x8000u) : (uint16_t)0;  // rows >= r of W are not initialised
           }
         }
@@ -590,7 +624,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
         for (int v = 0; v < 16; ++v) ss = fmaf(Racc[mt][v], Racc[mt][v], ss);
       ss += __shfl_xor(ss, 32, 64);
       const float rho = sqrtf(ss);
-      if (hf == 0) norms[blk * (size_t)n + t0 + 32 * wave + l32] = float_to_half_bits(rho);
+      if (hf == 0) norms[slot * (size_t)n + t0 + 32 * wave + l32] = float_to_half_bits(rho);
       const float sc = (rho > 0.0f) ? sqrt_d / rho : 0.0f;
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt)
@@ -657,7 +691,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
         }
       }
       if (lane < 32) {
-        uint8_t* dst = codes + (blk * (size_t)n + t0 + 32 * tau + lane) * ROWB + 4 * wave;
+        uint8_t* dst = codes + (slot * (size_t)n + t0 + 32 * tau + lane) * ROWB + 4 * wave;
 #pragma unroll
         for (int p = 0; p < BITS; ++p) *reinterpret_cast<uint32_t*>(dst + p * 16) = outw[p];
       }
@@ -690,20 +724,32 @@ hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void*
 }
 
 hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq, int n_kv_heads,
-                             int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores) {
+                             int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
+                             int64_t block_capacity, int64_t score_stride, const void* tail_fp16,
+                             int64_t tail_capacity, int tail_len) {
   const int64_t sg_total = n_seq * n_kv_heads;
+  if (block_capacity <= 0) block_capacity = blocks_per_head;
+  if (score_stride <= 0) score_stride = blocks_per_head * L.n;
+  if (L.ev) (void)hipEventRecord(L.ev[6], L.stream);
+  if (tail_len > 0)
+    hipLaunchKernelGGL(eoq_scores_tail_kernel, dim3((unsigned)sg_total), dim3(THREADS), 0, L.stream, n_kv_heads,
+                       n_q_heads / n_kv_heads, tail_capacity, tail_len, static_cast<const uint16_t*>(tail_fp16),
+                       static_cast<const uint16_t*>(q_fp16), scores, score_stride, blocks_per_head * L.n);
+  if (blocks_per_head == 0) {
+    if (L.ev) (void)hipEventRecord(L.ev[7], L.stream);
+    return hipGetLastError();
+  }
   // blocks per workgroup: up to 16 (the query set-up is paid once per workgroup), shorter when that leaves fewer than ~16
   // workgroups per compute unit
   int64_t run = (sg_total * blocks_per_head) / 4096;
   run = run < 1 ? 1 : (run > SC_RUN_MAX ? SC_RUN_MAX : run);
   const int64_t runs = (blocks_per_head + run - 1) / run;
   if (sg_total > 65535 || runs > 0x7FFFFFFF) return hipErrorInvalidValue;
-  if (L.ev) (void)hipEventRecord(L.ev[6], L.stream);
   const dim3 grid((unsigned)runs, (unsigned)sg_total), block(THREADS);
   const uint16_t* q = static_cast<const uint16_t*>(q_fp16);
 #define EOQ_SCORES(BITS)                                                                                          \
   hipLaunchKernelGGL(eoq_scores_mfma_kernel<BITS>, grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads,            \
-                     n_q_heads / n_kv_heads, blocks_per_head, (int)run, L.pit, L.tab, keys.codes, keys.norms, keys.rank,    \
+                     n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pit, L.tab, keys.codes, keys.norms, keys.rank,    \
                      keys.lfac, keys.rfac, q, scores)
   switch (L.bits) {
     case 1: EOQ_SCORES(1); break;
@@ -723,11 +769,11 @@ hipError_t eoq_launch_encode_f16(const EoqLaunch& L, const void* blocks, int64_t
 #define EOQ_ENCODE(BITS)                                                                                            \
   do {                                                                                                              \
     if (stored_factors)                                                                                             \
-      hipLaunchKernelGGL((eoq_encode_mfma_kernel<BITS, true>), grid, block, 0, L.stream, src, L.n, L.r_max, L.pih,  \
-                         L.tab, wfac, out.rank, out.rfac, out.lfac, out.norms, out.codes);                          \
+      hipLaunchKernelGGL((eoq_encode_mfma_kernel<BITS, true>), grid, block, 0, L.stream, src, L.map, L.n, L.r_max,  \
+                         L.pih, L.tab, wfac, out.rank, out.rfac, out.lfac, out.norms, out.codes);                   \
     else                                                                                                            \
-      hipLaunchKernelGGL((eoq_encode_mfma_kernel<BITS, false>), grid, block, 0, L.stream, src, L.n, L.r_max, L.pih, \
-                         L.tab, wfac, out.rank, out.rfac, out.lfac, out.norms, out.codes);                          \
+      hipLaunchKernelGGL((eoq_encode_mfma_kernel<BITS, false>), grid, block, 0, L.stream, src, L.map, L.n, L.r_max, \
+                         L.pih, L.tab, wfac, out.rank, out.rfac, out.lfac, out.norms, out.codes);                   \
   } while (0)
   switch (L.bits) {
     case 1: EOQ_ENCODE(1); break;

@@ -40,7 +40,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 #define EOQ_SFOR(var, n, ...) static_for<0, n>([&](auto var##_ic) __attribute__((always_inline)) { \
   constexpr int var = decltype(var##_ic)::value; __VA_ARGS__ })
 
-__device__ __forceinline__ void gram_tile(const void* __restrict__ blocks, int dtype, size_t base_elem, int n,
+__device__ __forceinline__ void gram_tile(const void* __restrict__ blocks, int dtype, size_t base_elem, size_t tok, int n,
                                           float* stage, int tid, double (&acc)[64]) {
   const int ty = tid >> 4, tx = tid & 15;
   EOQ_SFOR(i, 64, acc[i] = 0.0;);
@@ -50,7 +50,7 @@ __device__ __forceinline__ void gram_tile(const void* __restrict__ blocks, int d
     for (int g = 0; g < 2; ++g) {
       const int e = (g * THREADS + tid) * 8;
       float v[8];
-      load8(blocks, dtype, base_elem + (size_t)t0 * D + e, v);
+      load8(blocks, dtype, base_elem + (size_t)(t0 + (e >> 7)) * tok + (e & (D - 1)), v);
 #pragma unroll
       for (int i = 0; i < 8; ++i) stage[e + i] = v[i];
     }
@@ -73,7 +73,7 @@ __device__ __forceinline__ void gram_tile(const void* __restrict__ blocks, int d
 // bits, returns the (clamped) rank to every lane.  Must be called by all 256 lanes.
 // ---------------------------------------------------------------------------------------------
 __device__ int rank_and_shrink(const double* lam_s, double* atoms, double* scale_s, unsigned* flag_s, int n, int k,
-                               double rank_thr, int r_max, size_t blk, double* __restrict__ lam_out,
+                               double rank_thr, int r_max, size_t blk, size_t slot, double* __restrict__ lam_out,
                                float* __restrict__ phi_out, float* __restrict__ sigma_out) {
   const int tid = threadIdx.x;
   if (tid < D) lam_out[blk * D + tid] = lam_s[tid];
@@ -140,14 +140,14 @@ __device__ int rank_and_shrink(const double* lam_s, double* atoms, double* scale
           phi = 0.0;
           atomicOr(flag_s, EOQ_FLAG_SHRINK_GUARD);
         }
-        phi_out[blk * r_max + i] = (float)phi;
-        sigma_out[blk * r_max + i] = (float)sig;
+        phi_out[slot * r_max + i] = (float)phi;
+        sigma_out[slot * r_max + i] = (float)sig;
         scale_s[i] = (sig > 0.0) ? phi / sig : 0.0;
       }
     }
     for (int i = r + tid; i < r_max; i += THREADS) {
-      phi_out[blk * r_max + i] = 0.0f;
-      sigma_out[blk * r_max + i] = 0.0f;
+      phi_out[slot * r_max + i] = 0.0f;
+      sigma_out[slot * r_max + i] = 0.0f;
     }
   }
   __syncthreads();
@@ -164,7 +164,7 @@ constexpr double JACOBI_TOL = 5e-14;  // a pair is orthogonal when |<a_p,a_q>| <
 // With `list` non-null the workgroups walk the block numbers list[0 .. *count) (grid-stride); otherwise
 // workgroup b handles block b.
 __global__ __launch_bounds__(THREADS) void eoq_spectral_jacobi_kernel(
-    const void* __restrict__ blocks, int dtype, int n, int k, double rank_thr, int r_max, int64_t B,
+    const void* __restrict__ blocks, EoqBlockMap map, int dtype, int n, int k, double rank_thr, int r_max, int64_t B,
     const int* __restrict__ list, const int* __restrict__ count, double* __restrict__ lam_out,
     float* __restrict__ wfac, int32_t* __restrict__ rank_out, float* __restrict__ phi_out,
     float* __restrict__ sigma_out, uint16_t* __restrict__ rfac, uint32_t* __restrict__ flags_out) {
@@ -181,12 +181,13 @@ __global__ __launch_bounds__(THREADS) void eoq_spectral_jacobi_kernel(
   const int64_t total = list ? (int64_t)*count : B;
   for (int64_t item = blockIdx.x; item < total; item += gridDim.x) {
     const size_t blk = list ? (size_t)list[item] : (size_t)item;
+    const size_t slot = map.slot(blk);
     __syncthreads();
     if (tid == 0) flag_s = 0u;
 
     {
       double acc[64];
-      gram_tile(blocks, dtype, blk * (size_t)n * D, n, stage, tid, acc);
+      gram_tile(blocks, dtype, map.in_base(blk), (size_t)map.token_stride, n, stage, tid, acc);
       const int ty = tid >> 4, tx = tid & 15;
       EOQ_SFOR(e, 64, A[(tx * 8 + (e & 7)) * LDA + ty * 8 + (e >> 3)] = acc[e];);
     }
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(THREADS) void eoq_spectral_jacobi_kernel(
     }
     __syncthreads();
 
-    const int r = rank_and_shrink(lam_s, atoms, scale_s, &flag_s, n, k, rank_thr, r_max, blk, lam_out, phi_out,
+    const int r = rank_and_shrink(lam_s, atoms, scale_s, &flag_s, n, k, rank_thr, r_max, blk, slot, lam_out, phi_out,
                                   sigma_out);
 
     // right singular vectors v_i = a_slot / lambda_i of the retained components
@@ -271,12 +272,12 @@ __global__ __launch_bounds__(THREADS) void eoq_spectral_jacobi_kernel(
       const int i = e >> 7, j = e & (D - 1);
       const double li = lam_s[i];
       const double v = (li > 0.0) ? A[slot_of[i] * LDA + j] / li : 0.0;
-      rfac[(blk * r_max + i) * D + j] = double_to_half_bits(v);
+      rfac[(slot * r_max + i) * D + j] = double_to_half_bits(v);
       wfac[(blk * r_max + i) * D + j] = (float)(v * scale_s[i]);
     }
     if (tid == 0) {
-      rank_out[blk] = r;
-      flags_out[blk] = flag_s | ((unsigned)sweeps << EOQ_FLAG_SWEEPS_SHIFT);
+      rank_out[slot] = r;
+      flags_out[slot] = flag_s | ((unsigned)sweeps << EOQ_FLAG_SWEEPS_SHIFT);
     }
   }
 }
@@ -311,14 +312,14 @@ constexpr int POOL_BYTES = REFL_BYTES + U1_BYTES;
 
 // G = S^T S in the cyclic layout.  Only the sub-tiles a <= b are accumulated (36 of 64 products per block row);
 // the others are mirrored from the lane that holds the transposed position, through LDS.
-__device__ __forceinline__ void gram_cyclic(const void* __restrict__ blocks, int dtype, size_t base_elem, int n,
+__device__ __forceinline__ void gram_cyclic(const void* __restrict__ blocks, int dtype, size_t base_elem, size_t tok, int n,
                                             float* stage, int tid, double (&A)[64]) {
   const int ty = tid >> 4, tx = tid & 15;
   EOQ_SFOR(i, 64, A[i] = 0.0;);
   float nxt[2][8];
-  load8(blocks, dtype, base_elem + (size_t)tid * 8, nxt[0]);
-  load8(blocks, dtype, base_elem + (size_t)(THREADS + tid) * 8, nxt[1]);
   const int wrow = tid >> 4, wcol = (tid & 15) * 8;
+  load8(blocks, dtype, base_elem + (size_t)wrow * tok + wcol, nxt[0]);
+  load8(blocks, dtype, base_elem + (size_t)(16 + wrow) * tok + wcol, nxt[1]);
 #pragma unroll 1
   for (int t0 = 0; t0 < n; t0 += GRAM_STRIP) {
     __syncthreads();  // the previous strip has been consumed
@@ -328,9 +329,9 @@ __device__ __forceinline__ void gram_cyclic(const void* __restrict__ blocks, int
       for (int i = 0; i < 8; ++i) stage[(g * 16 + wrow) * D + stage_pos(wcol + i)] = nxt[g][i];
     __syncthreads();
     if (t0 + GRAM_STRIP < n) {  // next strip on its way while this one is multiplied
-      const size_t e = base_elem + (size_t)(t0 + GRAM_STRIP) * D;
-      load8(blocks, dtype, e + (size_t)tid * 8, nxt[0]);
-      load8(blocks, dtype, e + (size_t)(THREADS + tid) * 8, nxt[1]);
+      const size_t e = base_elem + (size_t)(t0 + GRAM_STRIP + wrow) * tok + wcol;
+      load8(blocks, dtype, e, nxt[0]);
+      load8(blocks, dtype, e + 16 * tok, nxt[1]);
     }
 #pragma unroll 2
     for (int t = 0; t < GRAM_STRIP; ++t) {
@@ -395,7 +396,7 @@ __device__ __forceinline__ uint32_t gather_bytes(int x0, int x1, int x2, int x3)
   return t01 | (t23 << 16);
 }
 
-__device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, int n, unsigned char* pool, int tid,
+__device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size_t tok, int n, unsigned char* pool, int tid,
                                           double (&A)[64]) {
   const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -407,7 +408,7 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, int 
 
   uint4 raw[4];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) raw[it] = *reinterpret_cast<const uint4*>(src + (size_t)(4 * q + it) * D + 8 * m);
+  for (int it = 0; it < 4; ++it) raw[it] = *reinterpret_cast<const uint4*>(src + (size_t)(4 * q + it) * tok + 8 * m);
 
 #pragma unroll 1
   for (int t0 = 0; t0 < n; t0 += GI_TOK) {
@@ -458,7 +459,7 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, int 
     if (t0 + GI_TOK < n) {  // next pass on its way during the products
 #pragma unroll
       for (int it = 0; it < 4; ++it)
-        raw[it] = *reinterpret_cast<const uint4*>(src + (size_t)(t0 + GI_TOK + 4 * q + it) * D + 8 * m);
+        raw[it] = *reinterpret_cast<const uint4*>(src + (size_t)(t0 + GI_TOK + 4 * q + it) * tok + 8 * m);
     }
     __syncthreads();
     // ---- products, one tile at a time: lane supplies row / column l16 of the tile, tokens 16 kg .. 16 kg + 15 ----
@@ -768,7 +769,7 @@ __device__ __forceinline__ void backtransform_stage(double (&y)[8], const float*
 }
 
 __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
-    const void* __restrict__ blocks, int dtype, int n, int k_pilot, double rank_thr, int r_max,
+    const void* __restrict__ blocks, EoqBlockMap map, int dtype, int n, int k_pilot, double rank_thr, int r_max,
     int* __restrict__ fb_list, int* __restrict__ fb_count, double* __restrict__ lam_out, float* __restrict__ wfac,
     double* __restrict__ tri, int32_t* __restrict__ rank_out, float* __restrict__ phi_out, float* __restrict__ sigma_out,
     uint16_t* __restrict__ rfac, uint32_t* __restrict__ flags_out) {
@@ -791,6 +792,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
 
   const int tid = threadIdx.x;
   const size_t blk = blockIdx.x;
+  const size_t slot = map.slot(blk);
   const int lane = tid & 63, wave = tid >> 6;
   if (tid == 0) {
     flag_s = 0u;
@@ -801,9 +803,9 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   {
     double A[64];
     if (dtype == EOQ_F16)
-      gram_int8(static_cast<const uint16_t*>(blocks) + blk * (size_t)n * D, n, pool, tid, A);
+      gram_int8(static_cast<const uint16_t*>(blocks) + map.in_base(blk), (size_t)map.token_stride, n, pool, tid, A);
     else
-      gram_cyclic(blocks, dtype, blk * (size_t)n * D, n, reinterpret_cast<float*>(u1), tid, A);
+      gram_cyclic(blocks, dtype, map.in_base(blk), (size_t)map.token_stride, n, reinterpret_cast<float*>(u1), tid, A);
     __syncthreads();  // the pool changes hands
     EOQ_SFOR(s, 8, householder_stage<s>(A, tid, vbuf, pbuf, refl, dT, eT, betaT););
     // the last 2x2 block of T: rows and columns 126, 127 sit in the sub-tile (7, 7) of lanes ty, tx >= 14
@@ -901,7 +903,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   }
   __syncthreads();
 
-  const int r = rank_and_shrink(lam_s, atoms, scale_s, &flag_s, n, k_pilot, rank_thr, r_max, blk, lam_out, phi_out,
+  const int r = rank_and_shrink(lam_s, atoms, scale_s, &flag_s, n, k_pilot, rank_thr, r_max, blk, slot, lam_out, phi_out,
                                 sigma_out);
 
   // repeated retained eigenvalues: leave the block to the Jacobi solver
@@ -910,10 +912,10 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     if (lam_s[i] - lam_s[i + 1] <= CLUSTER_TOL * lam_s[0]) repeated = true;
   if (repeated) {
     if (tid == 0) {
-      const int slot = atomicAdd(fb_count, 1);
-      fb_list[slot] = (int)blk;
-      rank_out[blk] = r;
-      flags_out[blk] = flag_s;
+      const int fb_slot = atomicAdd(fb_count, 1);
+      fb_list[fb_slot] = (int)blk;
+      rank_out[slot] = r;
+      flags_out[slot] = flag_s;
     }
     return;
   }
@@ -1051,15 +1053,15 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
           const int i = l + 16 * m;
-          rfac[(blk * r_max + b0 + ev) * D + i] = double_to_half_bits(y[m]);
+          rfac[(slot * r_max + b0 + ev) * D + i] = double_to_half_bits(y[m]);
           wfac[(blk * r_max + b0 + ev) * D + i] = (float)(y[m] * s);
         }
       }
     }
   }
   if (tid == 0) {
-    rank_out[blk] = r;
-    flags_out[blk] = flag_s;
+    rank_out[slot] = r;
+    flags_out[slot] = flag_s;
   }
 }
 
@@ -1076,16 +1078,16 @@ hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype
                                float* wfac, int* fb_count, int* fb_list, double* tri, eoq_packed out) {
   if (L.ev) (void)hipEventRecord(L.ev[0], L.stream);
   if (L.solver == 1) {
-    hipLaunchKernelGGL(eoq_spectral_jacobi_kernel, dim3((unsigned)B), dim3(THREADS), 0, L.stream, blocks, dtype, L.n,
+    hipLaunchKernelGGL(eoq_spectral_jacobi_kernel, dim3((unsigned)B), dim3(THREADS), 0, L.stream, blocks, L.map, dtype, L.n,
                        L.k, L.rank_thr, L.r_max, B, (const int*)nullptr, (const int*)nullptr, lam, wfac, out.rank,
                        out.phi, out.sigma, out.rfac, out.flags);
   } else {
     hipLaunchKernelGGL(eoq_zero_counter_kernel, dim3(1), dim3(64), 0, L.stream, fb_count);
-    hipLaunchKernelGGL(eoq_spectral_tridiag_kernel, dim3((unsigned)B), dim3(THREADS), 0, L.stream, blocks, dtype, L.n,
+    hipLaunchKernelGGL(eoq_spectral_tridiag_kernel, dim3((unsigned)B), dim3(THREADS), 0, L.stream, blocks, L.map, dtype, L.n,
                        L.k, L.rank_thr, L.r_max, fb_list, fb_count, lam, wfac, tri, out.rank, out.phi, out.sigma, out.rfac,
                        out.flags);
     const unsigned grid = (unsigned)((B < 256) ? B : 256);
-    hipLaunchKernelGGL(eoq_spectral_jacobi_kernel, dim3(grid), dim3(THREADS), 0, L.stream, blocks, dtype, L.n, L.k,
+    hipLaunchKernelGGL(eoq_spectral_jacobi_kernel, dim3(grid), dim3(THREADS), 0, L.stream, blocks, L.map, dtype, L.n, L.k,
                        L.rank_thr, L.r_max, B, (const int*)fb_list, (const int*)fb_count, lam, wfac, out.rank, out.phi,
                        out.sigma, out.rfac, out.flags);
   }

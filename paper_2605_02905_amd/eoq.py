@@ -18,7 +18,7 @@ EOQ_F16, EOQ_F32 = 0, 1
 FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE = 1, 2, 4
 
 EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_codebook",
-           "eoq_compress", "eoq_compress_q4", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
+           "eoq_compress", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
 
 
 class EoqError(RuntimeError):
@@ -34,6 +34,12 @@ class _Packed(C.Structure):
 
 class _FactorCodes(C.Structure):
     _fields_ = [("lcodes", C.c_void_p), ("rcodes", C.c_void_p), ("fbook", C.c_void_p), ("phi16", C.c_void_p)]
+
+
+class ChunkLayout(C.Structure):
+    """eoq_chunk_layout of include/eoq.h (strides in elements, record slots in blocks)."""
+    _fields_ = [("in_group_stride", C.c_int64), ("in_group_size", C.c_int32), ("in_block_stride", C.c_int64),
+                ("in_token_stride", C.c_int64), ("out_first", C.c_int64), ("out_stride", C.c_int64)]
 
 
 _lib = None
@@ -64,6 +70,9 @@ def lib():
         L.eoq_compress_q4.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, _Packed, _FactorCodes, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
         L.eoq_compress_q4.restype = C.c_int
+        L.eoq_compress_chunk.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, ChunkLayout, _Packed,
+                                         C.POINTER(_FactorCodes), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.eoq_compress_chunk.restype = C.c_int
         L.eoq_expand_factors.argtypes = [C.c_void_p, _Packed, _FactorCodes, C.c_int64, C.c_void_p]
         L.eoq_expand_factors.restype = C.c_int
         L.eoq_decompress.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_void_p, C.c_void_p]
@@ -71,6 +80,9 @@ def lib():
         L.eoq_scores.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_int, C.c_int64, C.c_void_p, C.c_int,
                                  C.c_void_p, C.c_void_p]
         L.eoq_scores.restype = C.c_int
+        L.eoq_scores_stream.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_int, C.c_int64, C.c_int64, C.c_void_p,
+                                        C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
+        L.eoq_scores_stream.restype = C.c_int
         L.eoq_set_solver.argtypes = [C.c_void_p, C.c_int]
         L.eoq_set_solver.restype = C.c_int
         L.eoq_profile.argtypes = [C.c_void_p, C.c_int]
@@ -219,6 +231,25 @@ class Context:
                                           workspace.data_ptr(), workspace.numel(), _stream_ptr(blocks.device)))
         return out, fq, workspace
 
+    def eoq_compress_chunk(self, chunk: torch.Tensor, B: int, layout: ChunkLayout, out: Packed,
+                           fq: FactorCodes | None = None, workspace: torch.Tensor | None = None):
+        """B blocks placed by `layout` inside the device tensor `chunk` (any shape, float16 or float32), written to
+        the record slots `layout` names of the store `out` (and `fq`).  Returns the workspace."""
+        assert chunk.is_cuda and chunk.is_contiguous()
+        dtype = {torch.float16: EOQ_F16, torch.float32: EOQ_F32}[chunk.dtype]
+        last = B - 1
+        reach = ((last // layout.in_group_size) * layout.in_group_stride + (last % layout.in_group_size) * layout.in_block_stride
+                 + (self.n - 1) * layout.in_token_stride + self.d)
+        assert B == 0 or reach <= chunk.numel(), "layout reaches past the end of the chunk tensor"
+        assert B == 0 or layout.out_first + last * layout.out_stride < out.rank.shape[0], "layout names a slot past the store"
+        if workspace is None:
+            workspace = torch.empty(max(self.eoq_workspace_bytes(B), 16), dtype=torch.uint8, device=chunk.device)
+        fqs = fq.c_struct() if fq is not None else None
+        self._check(lib().eoq_compress_chunk(self._h, chunk.data_ptr(), dtype, B, layout, out.c_struct(),
+                                             C.byref(fqs) if fqs is not None else None, workspace.data_ptr(),
+                                             workspace.numel(), _stream_ptr(chunk.device)))
+        return workspace
+
     def eoq_expand_factors(self, rec: Packed, fq: FactorCodes):
         B = rec.rank.shape[0]
         self._check(lib().eoq_expand_factors(self._h, rec.c_struct(), fq.c_struct(), B,
@@ -243,6 +274,28 @@ class Context:
             out = torch.empty(n_seq, n_q_heads, bph * self.n, dtype=torch.float32, device=q.device)
         self._check(lib().eoq_scores(self._h, keys.c_struct(), n_seq, n_kv_heads, bph, q.data_ptr(), n_q_heads,
                                      out.data_ptr(), _stream_ptr(q.device)))
+        return out
+
+    def eoq_scores_stream(self, keys: Packed, q: torch.Tensor, n_kv_heads: int, block_capacity: int,
+                          blocks_filled: int, tail: torch.Tensor | None, tail_len: int, out: torch.Tensor | None = None):
+        """keys: store of [n_seq * n_kv_heads * block_capacity] slots; tail: [n_seq, n_kv_heads, tail_capacity, d]
+        float16 device (or None).  Returns [n_seq, n_q_heads, score_stride] float32 with score_stride = out's last
+        dimension (blocks_filled * n + tail_len when `out` is not given)."""
+        assert q.is_cuda and q.is_contiguous() and q.dtype == torch.float16
+        n_seq, n_q_heads, _ = q.shape
+        assert keys.rank.shape[0] >= n_seq * n_kv_heads * block_capacity
+        tail_cap = 0
+        if tail is not None:
+            assert tail.is_cuda and tail.is_contiguous() and tail.dtype == torch.float16
+            assert tail.shape[0] == n_seq and tail.shape[1] == n_kv_heads and tail.shape[3] == self.d
+            tail_cap = tail.shape[2]
+        if out is None:
+            out = torch.empty(n_seq, n_q_heads, blocks_filled * self.n + tail_len, dtype=torch.float32, device=q.device)
+        assert out.is_contiguous() and out.shape[:2] == (n_seq, n_q_heads)
+        self._check(lib().eoq_scores_stream(self._h, keys.c_struct(), n_seq, n_kv_heads, block_capacity, blocks_filled,
+                                            tail.data_ptr() if tail is not None else None, tail_cap, tail_len,
+                                            q.data_ptr(), n_q_heads, out.data_ptr(), out.shape[2],
+                                            _stream_ptr(q.device)))
         return out
 
     def eoq_set_solver(self, solver: int):

@@ -43,7 +43,8 @@ class BlockSpec:
 
 def config(i: int) -> BlockSpec:
     """The five workloads of the benchmark definition (1-based), and 6: the same layer as 2 cut into the
-    128 x 128 blocks of the paper's own experiments (Sec. 3, Tables 1-5)."""
+    128 x 128 blocks of the paper's own experiments (Sec. 3, Tables 1-5), and 7: what one step of a chunked prefill
+    hands over, the newest 128 tokens of every layer and head (Sec. 5)."""
     if i == 1:   # single block, fp32, three planted spikes, white noise
         return BlockSpec("cfg1-single-block", n=512, strengths=(6.0, 4.0, 2.5), channel_s=0.0,
                          dtype=torch.float32)
@@ -58,6 +59,8 @@ def config(i: int) -> BlockSpec:
         return BlockSpec("cfg5-decode-keys", n=512, n_tensors=16 * 8, blocks_per_tensor=128, rank_lo=2, rank_hi=8)
     if i == 6:   # the Llama-shaped layer of config 2 in 128-token blocks
         return BlockSpec("cfg6-llama-layer-n128", n=128, n_tensors=16, blocks_per_tensor=256, rank_lo=1, rank_hi=6)
+    if i == 7:   # one 128-token chunk of the whole Llama-3.1-8B-shaped model: 32 layers x {K,V} x 8 heads
+        return BlockSpec("cfg7-llama-chunk-n128", n=128, n_tensors=32 * 16, blocks_per_tensor=1, rank_lo=1, rank_hi=6)
     raise ValueError(i)
 
 

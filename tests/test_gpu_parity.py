@@ -432,3 +432,197 @@ def test_q4_argument_errors():
     bad = eoq._FactorCodes(fq.lcodes.data_ptr(), None, fq.fbook.data_ptr(), fq.phi16.data_ptr())
     assert eoq.lib().eoq_expand_factors(ctx._h, rec.c_struct(), bad, 1, None) == eoq.EOQ_ERR_ARG
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("cfg,stride", [(2, 41), (6, 67)])
+def test_q4_full_size_batches_in_the_bench_launch_configuration(cfg, stride):
+    """The whole batch of a benchmark workload in one eoq_compress_q4 launch sequence, as `bench.py --factor-bits 4`
+    issues it; every block against properties that hold at any size (the cached factors are what the codes expand
+    to, codebooks ascending, reconstruction error bounded), a strided sample against the oracle to the bars."""
+    spec = synth.config(cfg)
+    blocks, _ = synth.make_blocks(spec, device=DEV)
+    B, n, bits = blocks.shape[0], spec.n, 2
+    ctx = eoq.Context(n=n, bits=bits)
+    rec, fq, ws = ctx.eoq_compress_q4(blocks)
+    xhat = ctx.eoq_decompress(rec)
+    torch.cuda.synchronize()
+    keep_l, keep_r = rec.lfac.clone(), rec.rfac.clone()
+    rec.lfac.zero_()
+    rec.rfac.zero_()
+    ctx.eoq_expand_factors(rec, fq)
+    torch.cuda.synchronize()
+    assert torch.equal(rec.lfac.view(torch.int16), keep_l.view(torch.int16))
+    assert torch.equal(rec.rfac.view(torch.int16), keep_r.view(torch.int16))
+    rank = rec.rank.cpu().numpy()
+    book = fq.fbook.float().cpu().numpy()
+    assert np.all(np.diff(book[rank > 0], axis=2) > 0) and not np.any(book[rank == 0])
+    assert bool(torch.isfinite(xhat).all())
+    err = (xhat.float() - blocks.float()).flatten(1).norm(dim=1) / blocks.float().flatten(1).norm(dim=1).clamp_min(1e-30)
+    assert float(err.max()) < 0.7, float(err.max())
+    idx = list(range(0, B, stride))
+    b64 = blocks[idx].double().cpu().numpy()
+    recs = U.oracle_compress(b64, bits, factor_bits=4)
+    lam = ctx.spectrum(ws, B)[idx].cpu().numpy()
+    sub = _subset(rec, idx)
+    sel = torch.as_tensor(idx, device=DEV)
+    fsub = eoq.FactorCodes(*(t.index_select(0, sel) for t in (fq.lcodes, fq.rcodes, fq.fbook, fq.phi16)))
+    st = U.compare_compress(b64, sub, lam, recs, bits, lowrank_tol=float("inf"))
+    sf = U.compare_factor_codes(sub, fsub, recs)
+    U.log_stats(f"cfg{cfg}-q4-full-sampled{len(idx)}", {**st, **{"factor_" + k: v for k, v in sf.items()}})
+    Pi, cb = U.oracle_tables(bits)
+    xs = xhat[idx].cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for k_, r in enumerate(recs):
+        e_g, e_o = U.rel_fro(b64[k_], xs[k_]), U.rel_fro(b64[k_], oracle.decompress_block(r, Pi, cb))
+        worst = max(worst, abs(e_g - e_o) / e_o)
+    assert worst <= 1e-3, worst
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Streaming use (Sec. 3.1 blocks of 128 tokens compressed as they complete, Sec. 7 FP16 tail): chunk-at-a-time
+# compression from the model's token-major layout into a [tensor][block] store, scores over blocks + tail
+# ---------------------------------------------------------------------------------------------------------------
+_FIELDS = ("codes", "norms", "rank", "phi", "sigma", "lfac", "rfac", "flags")
+
+
+def _bits_equal(a, b):
+    a, b = a.contiguous(), b.contiguous()
+    return torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+@pytest.mark.parametrize("n,dtype,q4", [(128, torch.float16, False), (128, torch.float16, True), (256, torch.float32, False)])
+def test_chunked_compression_fills_the_store_like_the_dense_call(n, dtype, q4):
+    """Three chunks of n tokens of 2 x 4 head-tensors, each handed over as the model produced it ([K/V][token][head][d])
+    and written to slot c of every tensor's row in a store of 4 slots per tensor: every slot is bit-identical to the
+    record of the dense call on the same block, the unused slot stays untouched, and the store passes the oracle
+    comparison."""
+    L2, H, chunks, cap, bits = 2, 4, 3, 4, 2
+    spec = synth.BlockSpec("stream", n=n, n_tensors=L2 * H, blocks_per_tensor=chunks, rank_lo=1, rank_hi=6)
+    blocks, _ = synth.make_blocks(spec, seed=77)
+    blocks = blocks.to(dtype)
+    ctx = eoq.Context(n=n, bits=bits)
+    dev_blocks = blocks.to(DEV).contiguous()
+    if q4:
+        dense, dfq, _ = ctx.eoq_compress_q4(dev_blocks)
+    else:
+        dense, _ = ctx.eoq_compress(dev_blocks)
+        dfq = None
+    store = eoq.Packed.empty(L2 * H * cap, n, 128, bits, ctx.r_max, DEV)
+    for f in _FIELDS:
+        getattr(store, f).view(torch.uint8).fill_(0x5A)
+    store.lfac.zero_()
+    store.rfac.zero_()
+    sfq = eoq.FactorCodes.empty(L2 * H * cap, n, 128, ctx.r_max, DEV) if q4 else None
+    view = blocks.view(L2, H, chunks, n, 128)
+    for c in range(chunks):
+        chunk = view[:, :, c].permute(0, 2, 1, 3).contiguous().to(DEV)          # [L2][n][H][d]
+        lay = eoq.ChunkLayout(n * H * 128, H, 128, H * 128, c, cap)
+        ctx.eoq_compress_chunk(chunk, L2 * H, lay, store, sfq)
+    torch.cuda.synchronize()
+    slots = torch.as_tensor([t * cap + c for t in range(L2 * H) for c in range(chunks)], device=DEV)
+    for f in _FIELDS:
+        assert _bits_equal(getattr(store, f).index_select(0, slots), getattr(dense, f)), f
+    if q4:
+        rank = dense.rank.cpu().numpy()
+        for f in ("lcodes", "rcodes", "phi16"):
+            got, want = getattr(sfq, f).index_select(0, slots), getattr(dfq, f)
+            for b in range(rank.shape[0]):
+                assert _bits_equal(got[b, :rank[b]], want[b, :rank[b]]), (f, b)
+        assert _bits_equal(sfq.fbook.index_select(0, slots), dfq.fbook)
+    spare = torch.as_tensor([t * cap + chunks for t in range(L2 * H)], device=DEV)
+    assert bool((store.codes.index_select(0, spare) == 0x5A).all()) and bool((store.rank.index_select(0, spare) == 0x5A5A5A5A).all())
+    b64 = blocks.double().numpy()
+    recs = U.oracle_compress(b64, bits, factor_bits=4 if q4 else 16)
+    sub = eoq.Packed(*(getattr(store, f).index_select(0, slots) for f in _FIELDS))
+    lam = np.stack([r.lam for r in recs])         # the workspace of the last chunk only holds that chunk's spectra
+    U.compare_compress(b64, sub, lam, recs, bits, lowrank_tol=float("inf") if q4 else 5e-3)
+
+
+def test_chunk_layout_argument_errors():
+    ctx = eoq.Context(n=128, bits=2)
+    x = torch.zeros(128, 4, 128, dtype=torch.float16, device=DEV)
+    store = eoq.Packed.empty(8, 128, 128, 2, 32, DEV)
+    ws = torch.empty(ctx.eoq_workspace_bytes(4), dtype=torch.uint8, device=DEV)
+    L = eoq.lib()
+
+    def call(lay):
+        return L.eoq_compress_chunk(ctx._h, x.data_ptr(), 0, 4, lay, store.c_struct(), None, ws.data_ptr(), ws.numel(), None)
+
+    assert call(eoq.ChunkLayout(0, 4, 128, 512, 0, 2)) == eoq.EOQ_OK
+    assert call(eoq.ChunkLayout(0, 0, 128, 512, 0, 2)) == eoq.EOQ_ERR_ARG       # group size
+    assert call(eoq.ChunkLayout(0, 4, 128, 64, 0, 2)) == eoq.EOQ_ERR_ARG        # tokens overlap
+    assert call(eoq.ChunkLayout(0, 4, 132, 512, 0, 2)) == eoq.EOQ_ERR_ARG       # stride not a multiple of 8
+    assert call(eoq.ChunkLayout(0, 4, 128, 512, -1, 2)) == eoq.EOQ_ERR_ARG
+    assert call(eoq.ChunkLayout(0, 4, 128, 512, 0, 0)) == eoq.EOQ_ERR_ARG
+    torch.cuda.synchronize()
+
+
+def test_scores_over_a_partly_filled_store_and_the_tail():
+    """2 sequences x 2 KV heads, a store of 4 slots per head with 3 blocks filled (oracle records) and 37
+    uncompressed tail tokens: the score rows hold the blocks' logits, then the tail's, and nothing else is written."""
+    n_seq, n_kv, group, cap, filled, tail_len, tail_cap, n = 2, 2, 4, 4, 3, 37, 64, 128
+    spec = synth.BlockSpec("skeys", n=n, n_tensors=n_seq * n_kv, blocks_per_tensor=filled, rank_lo=1, rank_hi=5)
+    blocks, _ = synth.make_blocks(spec, seed=321)
+    Pi, cb = U.oracle_tables(2)
+    recs = U.oracle_compress(blocks.double().numpy(), 2)
+    ctx = eoq.Context(n=n, bits=2)
+    dense = U.records_to_packed(recs, 32, DEV)
+    store = eoq.Packed.empty(n_seq * n_kv * cap, n, 128, 2, 32, DEV)
+    slots = torch.as_tensor([t * cap + c for t in range(n_seq * n_kv) for c in range(filled)], device=DEV)
+    for f in _FIELDS:
+        getattr(store, f).zero_()
+        getattr(store, f).index_copy_(0, slots, getattr(dense, f))
+    gen = torch.Generator().manual_seed(9)
+    tail = torch.randn(n_seq, n_kv, tail_cap, 128, generator=gen).to(torch.float16)
+    q = synth.make_queries(n_seq, n_kv * group)
+    stride = filled * n + tail_len + 11
+    out = torch.full((n_seq, n_kv * group, stride), -7.0, dtype=torch.float32, device=DEV)
+    ctx.eoq_scores_stream(store, q.to(DEV), n_kv, cap, filled, tail.to(DEV), tail_len, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.all(got[:, :, filled * n + tail_len:] == -7.0)
+    q64, t64 = q.double().numpy(), tail.double().numpy()
+    for s in range(n_seq):
+        for g in range(n_kv):
+            want = oracle.score_stream(q64[s, g * group:(g + 1) * group], recs[(s * n_kv + g) * filled:(s * n_kv + g + 1) * filled],
+                                       t64[s, g, :tail_len], Pi, cb)
+            have = got[s, g * group:(g + 1) * group, :filled * n + tail_len]
+            assert np.max(np.abs(have - want)) <= 1e-5 * max(1.0, np.max(np.abs(want))), (s, g)
+    # the tail alone (nothing compressed yet) and the blocks alone (tail just flushed)
+    only_tail = ctx.eoq_scores_stream(store, q.to(DEV), n_kv, cap, 0, tail.to(DEV), tail_len)
+    only_blocks = ctx.eoq_scores_stream(store, q.to(DEV), n_kv, cap, filled, None, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(only_tail, out[:, :, filled * n:filled * n + tail_len])
+    assert torch.equal(only_blocks, out[:, :, :filled * n])
+    L = eoq.lib()
+    qd = q.to(DEV)
+    assert L.eoq_scores_stream(ctx._h, store.c_struct(), n_seq, n_kv, cap, cap + 1, None, 0, 0, qd.data_ptr(), n_kv * group,
+                               out.data_ptr(), stride, None) == eoq.EOQ_ERR_ARG
+    assert L.eoq_scores_stream(ctx._h, store.c_struct(), n_seq, n_kv, cap, filled, None, 0, 0, qd.data_ptr(), n_kv * group,
+                               out.data_ptr(), filled * n - 1, None) == eoq.EOQ_ERR_ARG
+    torch.cuda.synchronize()
+
+
+def test_rank_fields_out_of_range_are_clamped_by_the_readers():
+    """A record read back from storage may hold anything in its rank field.  eoq_decompress, eoq_scores and
+    eoq_expand_factors bound it to 0 .. r_max before indexing the factor rows: the other blocks' results do not change
+    and every output stays finite."""
+    spec = synth.BlockSpec("clamp", n=128, n_tensors=1, blocks_per_tensor=6, rank_lo=1, rank_hi=5)
+    blocks, _ = synth.make_blocks(spec, seed=5)
+    ctx = eoq.Context(n=128, bits=2, r_max=8)
+    rec, fq, _ = ctx.eoq_compress_q4(blocks.to(DEV).contiguous())
+    q = synth.make_queries(1, 4, device=DEV)
+    x0 = ctx.eoq_decompress(rec).clone()
+    s0 = ctx.eoq_scores(rec, q, n_kv_heads=1).clone()
+    l0 = rec.lfac.clone()
+    rec.rank[1] = 1000
+    rec.rank[4] = -5
+    x1 = ctx.eoq_decompress(rec)
+    s1 = ctx.eoq_scores(rec, q, n_kv_heads=1)
+    ctx.eoq_expand_factors(rec, fq)
+    torch.cuda.synchronize()
+    keep = [0, 2, 3, 5]
+    assert torch.equal(x1[keep], x0[keep]) and bool(torch.isfinite(x1).all())
+    s0v, s1v = s0.view(4, 6, 128), s1.view(4, 6, 128)
+    assert torch.equal(s1v[:, keep], s0v[:, keep]) and bool(torch.isfinite(s1).all())
+    assert torch.equal(rec.lfac[keep].view(torch.int16), l0[keep].view(torch.int16))

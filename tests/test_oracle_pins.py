@@ -571,3 +571,23 @@ def test_four_bit_factors_closed_loop_and_expansion():
     assert np.linalg.norm(low16 - low4) / np.linalg.norm(low16) < 0.2
     # 4-bit factors leave sqrt(2 D_4) = 14 % of the low-rank part in the residual: here 1 % more residual energy
     assert np.linalg.norm(r4.R) < 1.02 * np.linalg.norm(r16.R)
+
+
+def test_score_stream_is_the_logit_of_the_concatenated_cache():
+    """A cache of two compressed blocks and an uncompressed tail: the streamed logits are the logits of the
+    reconstructed cache [x_hat_0; x_hat_1; tail] (Sec. 2.1), and with an empty tail those of the blocks alone."""
+    rng = np.random.default_rng(11)
+    Pi = oracle.haar_rotation(128, 5)
+    cb = oracle.lloyd_max_gaussian(2)
+    blocks = [rng.standard_normal((128, 128)) + 3.0 * np.outer(rng.standard_normal(128), rng.standard_normal(128)) / 11.0
+              for _ in range(2)]
+    recs = [oracle.compress_block(S, Pi, cb) for S in blocks]
+    tail = rng.standard_normal((37, 128))
+    q = rng.standard_normal((4, 128))
+    cache = np.concatenate([oracle.decompress_block(r, Pi, cb) for r in recs] + [tail])
+    want = q @ cache.T / math.sqrt(128.0)
+    got = oracle.score_stream(q, recs, tail, Pi, cb)
+    assert got.shape == (4, 2 * 128 + 37) and np.allclose(got, want, rtol=0, atol=1e-12)
+    assert np.array_equal(oracle.score_stream(q, recs, tail[:0], Pi, cb), got[:, :256])
+    # the tail part alone is the exact logit of the uncompressed keys
+    assert np.allclose(oracle.score_stream(q, [], tail, Pi, cb), q @ tail.T / math.sqrt(128.0), rtol=0, atol=1e-13)
