@@ -31,7 +31,7 @@ __all__ = [
     "bulk_edge", "estimate_rank", "impute_noise_spectrum", "shrink",
     "EOptShrinkResult", "eoptshrink",
     "tq_mse_encode", "tq_mse_decode",
-    "BlockRecord", "compress_block", "decompress_block", "score_block", "score_stream",
+    "BlockRecord", "compress_block", "decompress_block", "score_block", "score_stream", "softmax_rows", "attend_blocks",
     "pack_codes", "unpack_codes", "fp16_round", "fp16_bits", "bits_per_entry",
     "FLAG_RANK_CLAMPED", "FLAG_SHRINK_GUARD",
     "FACTOR_LEVELS", "FACTOR_LLOYD_ITERS", "adaptive_magnitudes", "factor_encode", "factor_decode",
@@ -509,6 +509,30 @@ def score_stream(q: np.ndarray, recs, tail: np.ndarray, Pi: np.ndarray, cb: Code
     if tail.shape[0]:
         parts.append((q @ tail.T) / math.sqrt(tail.shape[1]))
     return np.concatenate(parts, axis=-1) if parts else np.zeros(q.shape[:-1] + (0,))
+
+
+def softmax_rows(scores: np.ndarray) -> np.ndarray:
+    """softmax along the last axis (the attention weights of Sec. 2.1, Eq. for
+    Attention(Q, K, V)), with the row maximum subtracted first."""
+    s = np.asarray(scores, dtype=np.float64)
+    e = np.exp(s - np.max(s, axis=-1, keepdims=True))
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def attend_blocks(weights: np.ndarray, recs, Pi: np.ndarray, cb: Codebook) -> np.ndarray:
+    """Attention output of one KV head on compressed values (Sec. 2.1:
+    softmax(QK^T / sqrt(d)) V with V replaced by its reconstruction): weights
+    [h, T] over the tokens of the blocks `recs` in order, T = sum of their n;
+    returns sum_t weights[:, t] x_hat_t, [h, d]."""
+    w = np.asarray(weights, dtype=np.float64)
+    out = np.zeros((w.shape[0], recs[0].d if recs else 0))
+    t0 = 0
+    for r in recs:
+        out += w[:, t0:t0 + r.n] @ decompress_block(r, Pi, cb)
+        t0 += r.n
+    if t0 != w.shape[1]:
+        raise ValueError("weights do not cover the blocks' tokens")
+    return out
 
 
 # --------------------------------------------------------------------------

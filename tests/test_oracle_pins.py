@@ -591,3 +591,47 @@ def test_score_stream_is_the_logit_of_the_concatenated_cache():
     assert np.array_equal(oracle.score_stream(q, recs, tail[:0], Pi, cb), got[:, :256])
     # the tail part alone is the exact logit of the uncompressed keys
     assert np.allclose(oracle.score_stream(q, [], tail, Pi, cb), q @ tail.T / math.sqrt(128.0), rtol=0, atol=1e-13)
+
+
+def test_softmax_rows_against_scipy_and_its_invariants():
+    from scipy import special
+    rng = np.random.default_rng(2)
+    s = rng.standard_normal((5, 300)) * 6.0
+    p = oracle.softmax_rows(s)
+    assert np.allclose(p, special.softmax(s, axis=-1), rtol=1e-13, atol=0)
+    assert np.allclose(p.sum(-1), 1.0, rtol=0, atol=1e-14) and np.all(p > 0)
+    assert np.allclose(oracle.softmax_rows(s + 1000.0), p, rtol=1e-12, atol=0)         # shift invariance, no overflow
+    assert np.allclose(np.log(p[:, 1:] / p[:, :1]), s[:, 1:] - s[:, :1], rtol=0, atol=1e-10)
+
+
+def test_attend_blocks_is_the_weighted_sum_of_the_reconstructed_values():
+    """One-hot weights pick single reconstructed rows; general weights agree with the split the fused kernel
+    uses (rotated-codebook term through one inverse rotation of the summed codes plus the low-rank term), written
+    out here independently of decompress_block."""
+    rng = np.random.default_rng(4)
+    Pi = oracle.haar_rotation(128, 9)
+    cb = oracle.lloyd_max_gaussian(2)
+    blocks = [rng.standard_normal((128, 128)) + np.outer(rng.standard_normal(128), rng.standard_normal(128)) * 0.4
+              for _ in range(3)]
+    recs = [oracle.compress_block(S, Pi, cb) for S in blocks]
+    assert all(r.rank >= 1 for r in recs)
+    x = np.concatenate([oracle.decompress_block(r, Pi, cb) for r in recs])
+    onehot = np.zeros((2, 384))
+    onehot[0, 5] = 1.0
+    onehot[1, 300] = 1.0
+    got = oracle.attend_blocks(onehot, recs, Pi, cb)
+    assert np.array_equal(got[0], x[5]) and np.array_equal(got[1], x[300])
+    w = oracle.softmax_rows(rng.standard_normal((4, 384)) * 3.0)
+    got = oracle.attend_blocks(w, recs, Pi, cb)
+    acc_rot = np.zeros((4, 128))
+    acc_lin = np.zeros((4, 128))
+    for j, r in enumerate(recs):
+        wj = w[:, 128 * j:128 * (j + 1)]
+        zhat = cb.centroids_f32.astype(np.float64)[r.codes] / math.sqrt(128.0)   # the stored table, rotated domain
+        acc_rot += (wj * r.rho16[None, :]) @ zhat
+        acc_lin += (wj @ r.lfac.T) @ r.rfac
+    want = acc_rot @ Pi + acc_lin                                           # x_hat = rho Pi^T z_hat + C V
+    assert np.allclose(got, want, rtol=0, atol=1e-12 * np.max(np.abs(want)) + 1e-13)
+    assert np.allclose(got, w @ x, rtol=0, atol=1e-13)
+    with pytest.raises(ValueError):
+        oracle.attend_blocks(w[:, :-1], recs, Pi, cb)
