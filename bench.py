@@ -265,6 +265,21 @@ def main() -> int:
     for k_ in stage:
         stage[k_] /= args.steps
 
+    # decode attention on the same compressed blocks taken as values (outside the timed step: the step and `value`
+    # stay the compress + decompress + scores path): softmax of the logits in place, then the fused attention output
+    att_ws = torch.empty(max(ctx.eoq_attend_workspace_bytes(n_seq, n_kv, bph), 16), dtype=torch.uint8, device=dev)
+    att_out = torch.empty(n_seq, n_kv * group, D, dtype=torch.float32, device=dev)
+    att = {"softmax": 0.0, "attend": 0.0}
+    for it in range(args.warmup + args.steps):
+        ctx.eoq_scores(keys, q, n_kv, scores)
+        ctx.eoq_softmax(scores)
+        ctx.eoq_attend(keys, scores, n_kv, bph, bph, att_out, att_ws)
+        ms = ctx.eoq_stage_ms()
+        if it >= args.warmup:
+            for k_ in att:
+                att[k_] += ms[k_] / args.steps
+    torch.cuda.synchronize()
+
     in_bytes = B * n * D * 2
     flags = rec.flags.cpu()
     sweeps = ((flags >> 8) & 0xFF).double().mean().item()
@@ -309,6 +324,9 @@ def main() -> int:
             "scores_ms": stage["scores"],
             "scores_GBps_moved": score_bytes / (stage["scores"] * 1e-3) / 1e9,
             "scores_frac_hbm": score_bytes / (stage["scores"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "softmax_ms": att["softmax"], "attend_ms": att["attend"],
+            "attend_GBps_moved": score_bytes / (att["attend"] * 1e-3) / 1e9,
+            "attend_frac_hbm": score_bytes / (att["attend"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "mean_rank": ranks.mean().item(), "mean_jacobi_sweeps": sweeps,
             "record_bytes": rec_bytes, "stored_bits_per_entry": rec_bytes * 8.0 / (B * n * D),
         },

@@ -227,6 +227,30 @@ eoq_status eoq_scores_stream(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n
                              void* hip_stream);
 
 /*
+ * Attention weights: softmax over each of `rows` rows of `len` float32 logits, in place (Sec. 2.1, the softmax of
+ * Attention(Q, K, V); the row maximum is subtracted first).  scores is DEVICE memory, row r at scores + r*row_stride,
+ * row_stride >= len.
+ */
+eoq_status eoq_softmax(eoq_ctx* ctx, float* scores, int64_t rows, int64_t len, int64_t row_stride, void* hip_stream);
+
+/*
+ * Attention output on compressed values without materialising them (Sec. 2.1 with V replaced by its
+ * reconstruction; the split of Remark 6.5 applied to the values): out[s][h] = sum_t weights[s][h][t] x_hat_t over
+ * the tokens of the first blocks_filled blocks of KV head h / (n_q_heads / n_kv_heads) of sequence s.
+ *   values         DEVICE record store, block j of KV head g of sequence s at slot (s*n_kv_heads + g)*block_capacity + j.
+ *   weights        DEVICE, [n_seq][n_q_heads][weight_stride] float32 (e.g. eoq_softmax of eoq_scores' output); entry
+ *                  j*n + t of a row weighs token t of block j.  weight_stride >= blocks_filled*n.
+ *   out            DEVICE, [n_seq][n_q_heads][d] float32, overwritten.
+ *   workspace      DEVICE, >= eoq_attend_workspace_bytes(ctx, n_seq, n_kv_heads, blocks_filled) bytes (partial sums;
+ *                  they are added in a fixed order: the result does not depend on scheduling).
+ * Supported group sizes as eoq_scores.  blocks_filled = 0 writes zeros.
+ */
+size_t     eoq_attend_workspace_bytes(const eoq_ctx* ctx, int64_t n_seq, int n_kv_heads, int64_t blocks_per_head);
+eoq_status eoq_attend(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_heads, int64_t block_capacity,
+                      int64_t blocks_filled, const float* weights, int64_t weight_stride, int n_q_heads, float* out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Eigensolver used by eoq_compress for the d x d Gram matrix (the paper only asks for the SVD of the
  * block, Alg. 2 REQUIRE).  0 (default): Householder tridiagonalisation + Sturm multisection + twisted
  * factorisation, with blocks whose retained eigenvalues are numerically repeated handed to the Jacobi
@@ -238,8 +262,9 @@ eoq_status eoq_set_solver(eoq_ctx* ctx, int solver);
  * Per-kernel timing for benchmarks (not part of the paper's method).  With profiling enabled every
  * hot call records HIP events on its stream around each kernel it launches; eoq_stage_ms waits for
  * those events and returns the duration, in milliseconds, of the kernels of the most recent
- * eoq_compress (out[0] spectral, out[1] encode), eoq_decompress (out[2]) and eoq_scores (out[3]);
- * a stage that has not run since profiling was enabled reports -1.  `out` is HOST memory, 4 floats.
+ * eoq_compress* (out[0] spectral, out[1] encode, with the factor fit of eoq_compress_q4), eoq_decompress (out[2]),
+ * eoq_scores* (out[3]), eoq_attend (out[4]) and eoq_softmax (out[5]); a stage that has not run since profiling was
+ * enabled reports -1.  `out` is HOST memory, 6 floats.
  * Events are created by eoq_profile, never inside a hot call.
  */
 eoq_status eoq_profile(eoq_ctx* ctx, int enable);

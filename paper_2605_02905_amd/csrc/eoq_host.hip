@@ -446,6 +446,63 @@ eoq_status eoq_scores_stream(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n
   return EOQ_OK;
 }
 
+size_t eoq_attend_workspace_bytes(const eoq_ctx* ctx, int64_t n_seq, int n_kv_heads, int64_t blocks_per_head) {
+  if (!ctx || n_seq <= 0 || n_kv_heads <= 0 || blocks_per_head <= 0) return 0;
+  int run = 1;
+  const int64_t runs = eoq_attend_runs(n_seq * n_kv_heads, blocks_per_head, &run);
+  return (size_t)(n_seq * n_kv_heads) * (size_t)runs * 16 * EOQ_D * sizeof(float);
+}
+
+eoq_status eoq_softmax(eoq_ctx* ctx, float* scores, int64_t rows, int64_t len, int64_t row_stride, void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (rows < 0 || len < 0 || row_stride < len) return fail(ctx, EOQ_ERR_ARG, "negative size or rows that overlap");
+  if (rows == 0 || len == 0) return EOQ_OK;
+  if (!scores) return fail(ctx, EOQ_ERR_ARG, "null score pointer");
+  if (rows > 0x7FFFFFFF) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^31 - 1 rows");
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  const hipError_t e = eoq_launch_softmax(L, scores, rows, len, row_stride);
+  if (ctx->profile) ctx->ev_valid[5] = (e == hipSuccess);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+eoq_status eoq_attend(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_heads, int64_t block_capacity,
+                      int64_t blocks_filled, const float* weights, int64_t weight_stride, int n_q_heads, float* out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (n_seq < 0 || blocks_filled < 0 || n_kv_heads < 1 || n_q_heads < 1) return fail(ctx, EOQ_ERR_ARG, "negative or zero size");
+  if (blocks_filled > block_capacity) return fail(ctx, EOQ_ERR_ARG, "more blocks than the store holds");
+  if (weight_stride < blocks_filled * ctx->n) return fail(ctx, EOQ_ERR_ARG, "weight rows shorter than the blocks' tokens");
+  if (n_q_heads % n_kv_heads != 0 || n_q_heads / n_kv_heads > 8)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "query heads must be a multiple (1..8) of KV heads");
+  if (n_seq == 0) return EOQ_OK;
+  if (!weights || !out || !aligned16(out)) return fail(ctx, EOQ_ERR_ARG, "null or misaligned weight/output pointer");
+  if (blocks_filled > 0) {
+    if (eoq_status st = check_packed(ctx, values)) return st;
+    if (!workspace || !aligned16(workspace)) return fail(ctx, EOQ_ERR_ARG, "null or misaligned workspace");
+    if (workspace_bytes < eoq_attend_workspace_bytes(ctx, n_seq, n_kv_heads, blocks_filled))
+      return fail(ctx, EOQ_ERR_WORKSPACE, "workspace too small");
+  }
+  if (n_seq * n_kv_heads * block_capacity > (int64_t)1 << 24)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  const hipError_t e = eoq_launch_attend(L, values, n_seq, n_kv_heads, blocks_filled, block_capacity, weights,
+                                         weight_stride, n_q_heads, out, static_cast<float*>(workspace));
+  if (ctx->profile) ctx->ev_valid[4] = (e == hipSuccess);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
 eoq_status eoq_set_solver(eoq_ctx* ctx, int solver) {
   if (!ctx) return EOQ_ERR_ARG;
   ctx->err.clear();
@@ -459,7 +516,7 @@ eoq_status eoq_profile(eoq_ctx* ctx, int enable) {
   ctx->err.clear();
   if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
   if (enable && !ctx->profile) {
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 12; ++i) {
       if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
         for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->ev[j]);
         return fail(ctx, EOQ_ERR_HIP, "hipEventCreate failed");
@@ -478,7 +535,7 @@ eoq_status eoq_stage_ms(eoq_ctx* ctx, float* out) {
   if (!ctx || !out) return EOQ_ERR_ARG;
   ctx->err.clear();
   if (!ctx->profile) return fail(ctx, EOQ_ERR_ARG, "profiling is not enabled");
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 6; ++i) {
     out[i] = -1.0f;
     if (!ctx->ev_valid[i]) continue;
     hipError_t e = hipEventSynchronize(ctx->ev[2 * i + 1]);

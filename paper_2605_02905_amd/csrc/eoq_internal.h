@@ -29,10 +29,11 @@ struct eoq_ctx {
   std::string err;
   double gauss16[8] = {};  // Lloyd-Max magnitudes of N(0,1) at 16 levels: start of the per-block factor codebooks
   int solver = 0;  // 0: tridiagonal eigensolver with Jacobi for repeated eigenvalues, 1: Jacobi for every block
-  // optional per-kernel timing: events [2*i], [2*i+1] bracket stage i (spectral, encode, decode, scores)
+  // optional per-kernel timing: events [2*i], [2*i+1] bracket stage i (spectral, encode, decode, scores, attend,
+  // softmax)
   bool profile = false;
-  hipEvent_t ev[8] = {};
-  bool ev_valid[4] = {false, false, false, false};
+  hipEvent_t ev[12] = {};
+  bool ev_valid[6] = {false, false, false, false, false, false};
 };
 
 // Where the blocks of a batch sit in memory and which record slots they fill.  Input block b starts at element
@@ -89,3 +90,10 @@ hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq,
                              int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
                              int64_t block_capacity = 0, int64_t score_stride = 0, const void* tail_fp16 = nullptr,
                              int64_t tail_capacity = 0, int tail_len = 0);
+
+// attention output on compressed values: number of partial-sum runs per (sequence, KV head) and the launches
+int64_t eoq_attend_runs(int64_t sg_total, int64_t blocks_per_head, int* run_out);
+hipError_t eoq_launch_attend(const EoqLaunch& L, eoq_packed values, int64_t n_seq, int n_kv_heads,
+                             int64_t blocks_per_head, int64_t block_capacity, const float* weights,
+                             int64_t weight_stride, int n_q_heads, float* out, float* partial);
+hipError_t eoq_launch_softmax(const EoqLaunch& L, float* x, int64_t rows, int64_t len, int64_t stride);

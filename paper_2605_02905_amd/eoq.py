@@ -18,7 +18,7 @@ EOQ_F16, EOQ_F32 = 0, 1
 FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE = 1, 2, 4
 
 EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_codebook",
-           "eoq_compress", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
+           "eoq_compress", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_softmax", "eoq_attend_workspace_bytes", "eoq_attend", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
 
 
 class EoqError(RuntimeError):
@@ -83,6 +83,13 @@ def lib():
         L.eoq_scores_stream.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_int, C.c_int64, C.c_int64, C.c_void_p,
                                         C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
         L.eoq_scores_stream.restype = C.c_int
+        L.eoq_softmax.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
+        L.eoq_softmax.restype = C.c_int
+        L.eoq_attend_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int64]
+        L.eoq_attend_workspace_bytes.restype = C.c_size_t
+        L.eoq_attend.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_int, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
+                                 C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.eoq_attend.restype = C.c_int
         L.eoq_set_solver.argtypes = [C.c_void_p, C.c_int]
         L.eoq_set_solver.restype = C.c_int
         L.eoq_profile.argtypes = [C.c_void_p, C.c_int]
@@ -298,6 +305,40 @@ class Context:
                                             _stream_ptr(q.device)))
         return out
 
+    def eoq_softmax(self, scores: torch.Tensor, length: int | None = None) -> torch.Tensor:
+        """In-place softmax over the first `length` entries (default: all) of every row of a contiguous float32
+        device tensor [..., row_stride]."""
+        assert scores.is_cuda and scores.is_contiguous() and scores.dtype == torch.float32
+        stride = scores.shape[-1]
+        rows = scores.numel() // stride if stride else 0
+        self._check(lib().eoq_softmax(self._h, scores.data_ptr(), rows, stride if length is None else length, stride,
+                                      _stream_ptr(scores.device)))
+        return scores
+
+    def eoq_attend_workspace_bytes(self, n_seq: int, n_kv_heads: int, blocks_per_head: int) -> int:
+        return lib().eoq_attend_workspace_bytes(self._h, n_seq, n_kv_heads, blocks_per_head)
+
+    def eoq_attend(self, values: Packed, weights: torch.Tensor, n_kv_heads: int, block_capacity: int | None = None,
+                   blocks_filled: int | None = None, out: torch.Tensor | None = None,
+                   workspace: torch.Tensor | None = None) -> torch.Tensor:
+        """weights: [n_seq, n_q_heads, weight_stride] float32 device.  Returns [n_seq, n_q_heads, d] float32."""
+        assert weights.is_cuda and weights.is_contiguous() and weights.dtype == torch.float32
+        n_seq, n_q_heads, stride = weights.shape
+        if block_capacity is None:
+            block_capacity = values.rank.shape[0] // (n_seq * n_kv_heads)
+        if blocks_filled is None:
+            blocks_filled = block_capacity
+        assert values.rank.shape[0] >= n_seq * n_kv_heads * block_capacity
+        if out is None:
+            out = torch.empty(n_seq, n_q_heads, self.d, dtype=torch.float32, device=weights.device)
+        need = self.eoq_attend_workspace_bytes(n_seq, n_kv_heads, blocks_filled)
+        if workspace is None:
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=weights.device)
+        self._check(lib().eoq_attend(self._h, values.c_struct(), n_seq, n_kv_heads, block_capacity, blocks_filled,
+                                     weights.data_ptr(), stride, n_q_heads, out.data_ptr(), workspace.data_ptr(),
+                                     workspace.numel(), _stream_ptr(weights.device)))
+        return out
+
     def eoq_set_solver(self, solver: int):
         self._check(lib().eoq_set_solver(self._h, solver))
 
@@ -305,9 +346,9 @@ class Context:
         self._check(lib().eoq_profile(self._h, 1 if enable else 0))
 
     def eoq_stage_ms(self) -> dict:
-        out = (C.c_float * 4)()
+        out = (C.c_float * 6)()
         self._check(lib().eoq_stage_ms(self._h, out))
-        return dict(zip(("spectral", "encode", "decode", "scores"), (float(x) for x in out)))
+        return dict(zip(("spectral", "encode", "decode", "scores", "attend", "softmax"), (float(x) for x in out)))
 
     def spectrum(self, workspace: torch.Tensor, B: int) -> torch.Tensor:
         """Gram eigenvalues [B, d] (float64) that eoq_compress leaves at the head of its workspace."""

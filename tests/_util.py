@@ -183,3 +183,18 @@ def compare_factor_codes(rec, fq, recs):
 
 def rec_np(t):
     return t.detach().cpu().numpy()
+
+
+def packed_to_records(rec, idx, bits: int):
+    """Blocks `idx` of a device record (eoq.Packed) as oracle BlockRecords, field for field: what a reader of the
+    stored record sees."""
+    out = []
+    rank = rec_np(rec.rank)
+    for b in idx:
+        k = int(rank[b])
+        n, d = rec.norms.shape[1], rec.rfac.shape[2]
+        out.append(oracle.BlockRecord(
+            n, d, bits, k, 0, rec_np(rec.phi[b, :k]).astype(np.float64), rec_np(rec.sigma[b, :k]).astype(np.float64),
+            rec_np(rec.lfac[b, :k]).astype(np.float64), rec_np(rec.rfac[b, :k]).astype(np.float64),
+            oracle.unpack_codes(rec_np(rec.codes[b]), bits, d), rec_np(rec.norms[b]).astype(np.float64)))
+    return out

@@ -626,3 +626,122 @@ def test_rank_fields_out_of_range_are_clamped_by_the_readers():
     s0v, s1v = s0.view(4, 6, 128), s1.view(4, 6, 128)
     assert torch.equal(s1v[:, keep], s0v[:, keep]) and bool(torch.isfinite(s1).all())
     assert torch.equal(rec.lfac[keep].view(torch.int16), l0[keep].view(torch.int16))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Attention weights and attention output on compressed values (Sec. 2.1 with V replaced by its reconstruction)
+# ---------------------------------------------------------------------------------------------------------------
+def test_softmax_rows_against_the_oracle():
+    gen = torch.Generator().manual_seed(12)
+    s = (torch.randn(3, 5, 1011, generator=gen) * 5.0).to(DEV)
+    s[0, 0, :1000] += 80.0                                   # large logits: the maximum is subtracted first
+    ref = s.clone()
+    ctx = eoq.Context(n=128, bits=2)
+    ctx.eoq_softmax(s, 1000)
+    torch.cuda.synchronize()
+    want = oracle.softmax_rows(ref[..., :1000].double().cpu().numpy())
+    got = s[..., :1000].double().cpu().numpy()
+    assert np.max(np.abs(got - want) / want) <= 2e-5
+    assert np.max(np.abs(got.sum(-1) - 1.0)) <= 1e-5
+    assert torch.equal(s[..., 1000:], ref[..., 1000:])       # entries behind the row's length are not touched
+
+
+@pytest.mark.parametrize("n,bits,n_seq,n_kv,group,cap,filled,r_max", [(512, 2, 2, 2, 4, 3, 3, 32), (128, 3, 1, 1, 8, 5, 4, 8),
+                                                                      (256, 4, 1, 3, 1, 2, 2, 32), (128, 1, 1, 2, 2, 40, 37, 32)])
+def test_attention_output_of_oracle_records(n, bits, n_seq, n_kv, group, cap, filled, r_max):
+    """Values given as oracle records in a store of `cap` slots per head, `filled` of them valid; weights = softmax of
+    random logits.  The fused kernel against sum_t w_t x_hat_t of the oracle, element by element."""
+    heads = n_seq * n_kv
+    spec = synth.BlockSpec("vals", n=n, n_tensors=heads, blocks_per_tensor=filled, rank_lo=1, rank_hi=6, frac_rank0=0.2)
+    blocks, _ = synth.make_blocks(spec, seed=500 + n)
+    Pi, cb = U.oracle_tables(bits)
+    recs = U.oracle_compress(blocks.double().numpy(), bits, r_max=r_max)
+    dense = U.records_to_packed(recs, r_max, DEV)
+    store = eoq.Packed.empty(heads * cap, n, 128, bits, r_max, DEV)
+    slots = torch.as_tensor([t * cap + c for t in range(heads) for c in range(filled)], device=DEV)
+    for f in _FIELDS:
+        getattr(store, f).zero_()
+        getattr(store, f).index_copy_(0, slots, getattr(dense, f))
+    gen = torch.Generator().manual_seed(3)
+    T = filled * n
+    logits = torch.randn(n_seq, n_kv * group, T + 5, generator=gen) * 2.5
+    w = torch.zeros_like(logits)
+    w[..., :T] = torch.softmax(logits[..., :T].double(), dim=-1).float()
+    ctx = eoq.Context(n=n, bits=bits, r_max=r_max)
+    out = ctx.eoq_attend(store, w.to(DEV), n_kv, cap, filled)
+    torch.cuda.synchronize()
+    got = out.double().cpu().numpy()
+    w64 = w.double().numpy()
+    for s in range(n_seq):
+        for g in range(n_kv):
+            want = oracle.attend_blocks(w64[s, g * group:(g + 1) * group, :T], recs[(s * n_kv + g) * filled:(s * n_kv + g + 1) * filled],
+                                        Pi, cb)
+            have = got[s, g * group:(g + 1) * group]
+            assert np.max(np.abs(have - want)) <= 2e-5 * max(np.max(np.abs(want)), 1e-3), (s, g)
+    empty = ctx.eoq_attend(store, w.to(DEV), n_kv, cap, 0)
+    torch.cuda.synchronize()
+    assert not bool(empty.any())
+
+
+def test_decode_step_scores_softmax_attend_in_the_bench_launch_configuration():
+    """Config 2 at full size as one decode step: keys = the K tensors, values = the V tensors of the compressed batch
+    (8 KV heads x 64 blocks of 512 tokens), 32 query heads: eoq_scores -> eoq_softmax -> eoq_attend in the launch shapes
+    bench.py times.  Two heads are followed through the oracle on the same stored records (read back field by field):
+    logits, weights and the attention output."""
+    spec = synth.config(2)
+    blocks, _ = synth.make_blocks(spec, device=DEV)
+    B, n, bits, n_kv, group, bph = blocks.shape[0], spec.n, 2, 8, 4, spec.blocks_per_tensor
+    ctx = eoq.Context(n=n, bits=bits)
+    rec, _ = ctx.eoq_compress(blocks)
+    # tensor order of the workload: (head, K/V) pairs -> even tensors are keys, odd ones values
+    sel_k = torch.as_tensor([t * bph + j for t in range(0, 16, 2) for j in range(bph)], device=DEV)
+    sel_v = sel_k + bph
+    keys, vals = _subset(rec, sel_k), _subset(rec, sel_v)
+    q = synth.make_queries(1, n_kv * group, device=DEV)
+    sc = ctx.eoq_scores(keys, q, n_kv)
+    logits = sc.clone()
+    ctx.eoq_softmax(sc)
+    out = ctx.eoq_attend(vals, sc, n_kv)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    Pi, cb = U.oracle_tables(bits)
+    q64 = q.double().cpu().numpy()
+    for g in (0, 5):
+        krecs = U.packed_to_records(keys, range(g * bph, (g + 1) * bph), bits)
+        vrecs = U.packed_to_records(vals, range(g * bph, (g + 1) * bph), bits)
+        qs = q64[0, g * group:(g + 1) * group]
+        lo = np.concatenate([oracle.score_block(qs, r, Pi, cb) for r in krecs], axis=-1)
+        have_l = logits[0, g * group:(g + 1) * group].double().cpu().numpy()
+        assert np.max(np.abs(have_l - lo)) <= 1e-5 * max(1.0, np.max(np.abs(lo))), g
+        wo = oracle.softmax_rows(have_l)                     # the kernel's own logits: isolates the softmax
+        have_w = sc[0, g * group:(g + 1) * group].double().cpu().numpy()
+        assert np.max(np.abs(have_w - wo)) <= 2e-5 * np.max(wo), g
+        oo = oracle.attend_blocks(have_w, vrecs, Pi, cb)     # the kernel's own weights: isolates the attention output
+        have_o = out[0, g * group:(g + 1) * group].double().cpu().numpy()
+        assert np.max(np.abs(have_o - oo)) <= 2e-5 * max(np.max(np.abs(oo)), 1e-3), g
+        # end to end against the oracle chain on the same records
+        ee = oracle.attend_blocks(oracle.softmax_rows(lo), vrecs, Pi, cb)
+        assert np.max(np.abs(have_o - ee)) <= 1e-3 * max(np.max(np.abs(ee)), 1e-3), g
+
+
+def test_attend_argument_errors():
+    ctx = eoq.Context(n=128, bits=2)
+    store = eoq.Packed.empty(4, 128, 128, 2, 32, DEV)
+    for f in _FIELDS:
+        getattr(store, f).zero_()
+    w = torch.zeros(1, 4, 256, device=DEV)
+    out = torch.zeros(1, 4, 128, device=DEV)
+    ws = torch.empty(max(ctx.eoq_attend_workspace_bytes(1, 2, 2), 16), dtype=torch.uint8, device=DEV)
+    L = eoq.lib()
+
+    def call(cap, filled, stride, nq, wsb):
+        return L.eoq_attend(ctx._h, store.c_struct(), 1, 2, cap, filled, w.data_ptr(), stride, nq, out.data_ptr(),
+                            ws.data_ptr(), wsb, None)
+
+    assert call(2, 2, 256, 4, ws.numel()) == eoq.EOQ_OK
+    assert call(2, 3, 256, 4, ws.numel()) == eoq.EOQ_ERR_ARG            # more blocks than slots
+    assert call(2, 2, 255, 4, ws.numel()) == eoq.EOQ_ERR_ARG            # weight rows too short
+    assert call(2, 2, 256, 3, ws.numel()) == eoq.EOQ_ERR_UNSUPPORTED    # heads not a multiple
+    assert call(2, 2, 256, 4, 16) == eoq.EOQ_ERR_WORKSPACE
+    assert L.eoq_softmax(ctx._h, w.data_ptr(), 4, 300, 256, None) == eoq.EOQ_ERR_ARG
+    torch.cuda.synchronize()
