@@ -32,6 +32,7 @@ __all__ = [
     "EOptShrinkResult", "eoptshrink",
     "tq_mse_encode", "tq_mse_decode",
     "BlockRecord", "compress_block", "decompress_block", "score_block", "score_stream", "softmax_rows", "attend_blocks",
+    "gaussian_projection", "QjlRecord", "qjl_encode", "qjl_correction", "score_block_prod", "pack_signs", "unpack_signs",
     "pack_codes", "unpack_codes", "fp16_round", "fp16_bits", "bits_per_entry",
     "FLAG_RANK_CLAMPED", "FLAG_SHRINK_GUARD",
     "FACTOR_LEVELS", "FACTOR_LLOYD_ITERS", "adaptive_magnitudes", "factor_encode", "factor_decode",
@@ -509,6 +510,62 @@ def score_stream(q: np.ndarray, recs, tail: np.ndarray, Pi: np.ndarray, cb: Code
     if tail.shape[0]:
         parts.append((q @ tail.T) / math.sqrt(tail.shape[1]))
     return np.concatenate(parts, axis=-1) if parts else np.zeros(q.shape[:-1] + (0,))
+
+
+# --------------------------------------------------------------------------
+# TQ_prod: the 1-bit QJL correction of Alg. 1 (lines "TQ_prod") and Eq. (qjl)
+# --------------------------------------------------------------------------
+def gaussian_projection(d: int, seed: int) -> np.ndarray:
+    """Phi of Alg. 1 REQUIRE: d x d with iid N(0,1) entries, filled row-major
+    from `gaussian_stream` (the generator that also feeds the rotation)."""
+    return gaussian_stream(seed, d * d).reshape(d, d)
+
+
+@dataclass
+class QjlRecord:
+    """Alg. 1 "Store" of TQ_prod for the rows of one block."""
+    signs: np.ndarray    # [n, d] uint8 in {0, 1}: 1 where (Phi r_x)_i >= 0
+    gamma16: np.ndarray  # [n] stored residual norms |r_x| (binary16 values as float64)
+    gamma: np.ndarray = field(default=None, repr=False)   # unrounded norms (diagnostic)
+    proj: np.ndarray = field(default=None, repr=False)    # Phi r_x (diagnostic: distance of every sign decision from 0)
+
+
+def qjl_encode(S: np.ndarray, rec: BlockRecord, Pi: np.ndarray, cb: Codebook, Phi: np.ndarray) -> QjlRecord:
+    """Alg. 1 lines "r_x <- x - x_hat_MSE" and "Store |r_x| and sign(Phi r_x)",
+    applied where Alg. 3 applies TurboQuant: to the rows of the residual R.  The
+    quantisation residual of row t is r_x = R_t - R_hat_t = S_t - x_hat_t with
+    x_hat the reconstruction of the stored record (stored norm, stored factors).
+    sign(0) counts as +1; the norm is stored in binary16 like the row norms."""
+    S = np.asarray(S, dtype=np.float64)
+    rx = S - decompress_block(rec, Pi, cb)
+    proj = rx @ Phi.T
+    gamma = np.linalg.norm(rx, axis=1)
+    return QjlRecord((proj >= 0).astype(np.uint8), fp16_round(gamma), gamma=gamma, proj=proj)
+
+
+def qjl_correction(q: np.ndarray, qjl: QjlRecord, Phi: np.ndarray) -> np.ndarray:
+    """Second term of Eq. (qjl) for every query row of q and every token:
+    |r_x| sqrt(pi/2)/d <Phi y, sign(Phi r_x)>, with the stored norm."""
+    q = np.asarray(q, dtype=np.float64)
+    d = Phi.shape[1]
+    sgn = 2.0 * qjl.signs.astype(np.float64) - 1.0
+    return (q @ Phi.T) @ sgn.T * (math.sqrt(math.pi / 2.0) / d) * qjl.gamma16[None, :]
+
+
+def score_block_prod(q: np.ndarray, rec: BlockRecord, qjl: QjlRecord, Pi: np.ndarray, cb: Codebook,
+                     Phi: np.ndarray) -> np.ndarray:
+    """Attention logits with the TQ_prod estimator of Eq. (qjl) in place of the
+    MSE reconstruction: (<q, x_hat_t> + correction) / sqrt(d)."""
+    return score_block(q, rec, Pi, cb) + qjl_correction(q, qjl, Phi) / math.sqrt(rec.d)
+
+
+def pack_signs(signs: np.ndarray) -> np.ndarray:
+    """[n, d] sign bits -> [n, d/8] bytes, coordinate j in bit (j mod 8) of byte j // 8 (one more bit-plane)."""
+    return np.packbits(np.asarray(signs, dtype=np.uint8), axis=1, bitorder="little")
+
+
+def unpack_signs(packed: np.ndarray, d: int) -> np.ndarray:
+    return np.unpackbits(np.asarray(packed, dtype=np.uint8), axis=1, bitorder="little")[:, :d]
 
 
 def softmax_rows(scores: np.ndarray) -> np.ndarray:

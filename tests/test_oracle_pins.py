@@ -635,3 +635,79 @@ def test_attend_blocks_is_the_weighted_sum_of_the_reconstructed_values():
     assert np.allclose(got, w @ x, rtol=0, atol=1e-13)
     with pytest.raises(ValueError):
         oracle.attend_blocks(w[:, :-1], recs, Pi, cb)
+
+
+# ---- TQ_prod / QJL (Alg. 1 lines "TQ_prod", Eq. (qjl)) ------------------------------------------------------------
+def test_qjl_identity_behind_the_estimator():
+    """For g ~ N(0, I): E[sign(<g, a>) <g, y>] = sqrt(2/pi) <a, y> / |a|, which is why Eq. (qjl) scales by
+    sqrt(pi/2)/d.  Checked by the closed form in 2 dimensions (numerical integration over the angle) and by brute
+    force over many rows of Phi."""
+    a = np.array([0.3, -1.1])
+    y = np.array([0.7, 0.2])
+    # in polar form g = rho (cos t, sin t): E = E[rho] * mean over t of sign(cos(t - ta)) (y . unit(t)), E[rho] = sqrt(pi/2)
+    f = lambda t: np.sign(a[0] * np.cos(t) + a[1] * np.sin(t)) * (y[0] * np.cos(t) + y[1] * np.sin(t)) / (2 * np.pi)
+    val, _ = integrate.quad(f, 0.0, 2 * np.pi, points=[np.arctan2(a[1], a[0]) + np.pi / 2, np.arctan2(a[1], a[0]) + 1.5 * np.pi],
+                            limit=200)
+    assert abs(math.sqrt(math.pi / 2) * val - math.sqrt(2 / math.pi) * (a @ y) / np.linalg.norm(a)) < 1e-9
+    rng = np.random.default_rng(0)
+    d = 16
+    a, y = rng.standard_normal(d), rng.standard_normal(d)
+    g = rng.standard_normal((400000, d))
+    mc = np.mean(np.sign(g @ a) * (g @ y))
+    assert abs(mc - math.sqrt(2 / math.pi) * (a @ y) / np.linalg.norm(a)) < 4 * np.linalg.norm(y) / math.sqrt(400000)
+
+
+def test_qjl_estimator_is_unbiased_over_the_projection():
+    """Eq. (qjl): averaged over independent Phi the corrected inner product equals <y, x>; the MSE reconstruction
+    alone is biased low in magnitude along x (the quantiser shrinks)."""
+    Pi = oracle.haar_rotation(128, 3)
+    cb = oracle.lloyd_max_gaussian(2)
+    rng = np.random.default_rng(1)
+    S = rng.standard_normal((128, 128))
+    rec = oracle.compress_block(S, Pi, cb, force_rank0=True)
+    q = S[:4] / np.linalg.norm(S[:4], axis=1, keepdims=True) + 0.3 * rng.standard_normal((4, 128)) / math.sqrt(128)
+    exact = q @ S.T
+    mse = oracle.score_block(q, rec, Pi, cb) * math.sqrt(128.0)
+    acc = np.zeros_like(exact)
+    reps = 300
+    for s in range(reps):
+        Phi = oracle.gaussian_projection(128, 1000 + s)
+        acc += oracle.qjl_correction(q, oracle.qjl_encode(S, rec, Pi, cb, Phi), Phi)
+    est = mse + acc / reps
+    rx = S - oracle.decompress_block(rec, Pi, cb)
+    # standard error of the mean of one correction: |r_x| sqrt(pi/2)/d * sqrt(d) |q| at most
+    se = np.linalg.norm(rx, axis=1)[None, :] * math.sqrt(math.pi / 2 / 128) * np.linalg.norm(q, axis=1)[:, None] / math.sqrt(reps)
+    assert np.all(np.abs(est - exact) < 5 * se + 2e-3 * np.abs(exact))
+    diag = np.arange(4)
+    assert np.all(np.abs(mse[diag, diag]) < np.abs(exact[diag, diag]))                 # shrinkage bias of TQ_MSE
+    assert np.mean(np.abs(est[diag, diag] - exact[diag, diag])) < 0.3 * np.mean(np.abs(mse[diag, diag] - exact[diag, diag]))
+
+
+def test_qjl_record_definition_and_packing():
+    Pi = oracle.haar_rotation(128, 3)
+    cb = oracle.lloyd_max_gaussian(3)
+    Phi = oracle.gaussian_projection(128, 4)
+    assert Phi.shape == (128, 128) and abs(Phi.mean()) < 0.03 and abs(Phi.std() - 1.0) < 0.02
+    assert np.array_equal(Phi.ravel()[:5], oracle.gaussian_stream(4, 5))
+    rng = np.random.default_rng(6)
+    S = rng.standard_normal((128, 128)) + 2.0 * np.outer(rng.standard_normal(128), rng.standard_normal(128)) / 11.3
+    rec = oracle.compress_block(S, Pi, cb)
+    assert rec.rank >= 1
+    qj = oracle.qjl_encode(S, rec, Pi, cb, Phi)
+    rx = S - oracle.decompress_block(rec, Pi, cb)
+    t = 17
+    assert np.array_equal(qj.signs[t], (Phi @ rx[t] >= 0).astype(np.uint8))            # one row, written out
+    assert qj.gamma16[t] == float(np.float16(np.linalg.norm(rx[t])))
+    # the residual of the stored record is the quantisation residual of the residual row (Alg. 3 + Alg. 1)
+    R = S - rec.lfac.T @ rec.rfac
+    Rhat = oracle.tq_mse_decode(rec.codes, rec.rho16, Pi, cb)
+    assert np.allclose(rx, R - Rhat, rtol=0, atol=1e-12)
+    packed = oracle.pack_signs(qj.signs)
+    assert packed.shape == (128, 16) and np.array_equal(oracle.unpack_signs(packed, 128), qj.signs)
+    assert packed[t, 0] == sum(int(qj.signs[t, j]) << j for j in range(8))
+    # bits per entry of TQ_prod: b + 1 + 16/d (Alg. 1 last line), one more bit-plane than TQ_MSE
+    assert oracle.bits_per_entry(128, 128, 3, 0) + 1.0 == 3 + 1 + 16 / 128
+    # zero residual row: sign(0) = +1, norm 0, no correction
+    q = rng.standard_normal((2, 128))
+    z = oracle.QjlRecord(np.ones((1, 128), np.uint8), np.zeros(1))
+    assert not np.any(oracle.qjl_correction(q, z, Phi))
