@@ -279,6 +279,22 @@ def main() -> int:
             for k_ in att:
                 att[k_] += ms[k_] / args.steps
     torch.cuda.synchronize()
+    # TQ_prod (optional 1-bit correction of Eq. (qjl)), also outside the timed step: side information of the whole batch,
+    # then the corrected scores on the key set.  The library launches on torch's current stream, which these events see.
+    qj = eoq.Qjl.empty(B, n, D, dev)
+    kq = eoq.Qjl(qj.signs[:key_blocks], qj.norms[:key_blocks])
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    prod = {"qjl": 0.0, "scores_prod": 0.0}
+    for it in range(args.warmup + args.steps):
+        ev[0].record()
+        ctx.eoq_qjl_encode(blocks, rec, qj)
+        ev[1].record()
+        ctx.eoq_scores_prod(keys, kq, q, n_kv, scores)
+        ev[2].record()
+        torch.cuda.synchronize()
+        if it >= args.warmup:
+            prod["qjl"] += ev[0].elapsed_time(ev[1]) / args.steps
+            prod["scores_prod"] += ev[1].elapsed_time(ev[2]) / args.steps
 
     in_bytes = B * n * D * 2
     flags = rec.flags.cpu()
@@ -324,6 +340,7 @@ def main() -> int:
             "scores_ms": stage["scores"],
             "scores_GBps_moved": score_bytes / (stage["scores"] * 1e-3) / 1e9,
             "scores_frac_hbm": score_bytes / (stage["scores"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "qjl_encode_ms": prod["qjl"], "scores_prod_ms": prod["scores_prod"],
             "softmax_ms": att["softmax"], "attend_ms": att["attend"],
             "attend_GBps_moved": score_bytes / (att["attend"] * 1e-3) / 1e9,
             "attend_frac_hbm": score_bytes / (att["attend"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,

@@ -96,6 +96,18 @@ typedef struct {
 } eoq_factor_codes;
 
 /*
+ * TQ_prod side information of B blocks (Alg. 1 lines "TQ_prod": the norm of the quantisation residual and the signs
+ * of its Gaussian projection).  DEVICE pointers, caller-owned, 16-byte aligned.
+ *   signs [B][n][d/8]  bit (j mod 8) of byte j/8 of a token's row is set when (Phi r_x)_j >= 0 (sign(0) = +1);
+ *   norms [B][n]       binary16 |r_x|.
+ * One more bit per entry and 16/d for the norm (Alg. 1 last line counts b + 1 + 16/d).
+ */
+typedef struct {
+  uint8_t*  signs;
+  uint16_t* norms;
+} eoq_qjl;
+
+/*
  * Create a context for blocks of n x d, `bits` residual bits per entry (Alg. 3
  * REQUIRE), a Haar rotation drawn from `rot_seed` (Alg. 1 REQUIRE: one rotation
  * shared by all vectors) and at most r_max stored components per block.
@@ -119,6 +131,10 @@ size_t     eoq_workspace_bytes(const eoq_ctx* ctx, int64_t B);
 
 /* Copy the rotation Pi (row-major [d][d], z = Pi u) into HOST memory, as the float32 table the kernels use. */
 eoq_status eoq_rotation(const eoq_ctx* ctx, float* host_out);
+
+/* Copy the Gaussian projection Phi of TQ_prod (Alg. 1 REQUIRE; iid N(0,1) drawn from rot_seed + 1, row-major
+ * [d][d], w = Phi r) into HOST memory, as the float32 table the kernels use. */
+eoq_status eoq_projection(const eoq_ctx* ctx, float* host_out);
 
 /* Copy the N(0,1) codebook into HOST memory: 2^bits ascending centroids and 2^bits-1 midpoints (float32). */
 eoq_status eoq_codebook(const eoq_ctx* ctx, float* host_centroids, float* host_bounds);
@@ -225,6 +241,24 @@ eoq_status eoq_scores_stream(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n
                              int64_t blocks_filled, const void* tail_fp16, int64_t tail_capacity, int64_t tail_len,
                              const void* q_fp16, int n_q_heads, float* scores, int64_t score_stride,
                              void* hip_stream);
+
+/*
+ * TQ_prod for stored records (Alg. 1 lines "TQ_prod" where Alg. 3 applies TurboQuant, i.e. on the residual rows):
+ * r_x = S_t - x_hat_t with x_hat the reconstruction of `rec` (what eoq_decompress returns before its rounding),
+ * out.norms = binary16(|r_x|), out.signs = sign(Phi r_x).  Call after eoq_compress* on the same blocks.
+ *   blocks_fp16  DEVICE, [B][n][d] binary16, the blocks `rec` was made from.  rec is read only.
+ */
+eoq_status eoq_qjl_encode(eoq_ctx* ctx, const void* blocks_fp16, int64_t B, eoq_packed rec, eoq_qjl out,
+                          void* hip_stream);
+
+/*
+ * eoq_scores with the unbiased inner-product estimator of Eq. (qjl): every logit gets
+ * |r_x| sqrt(pi/2)/d <Phi q, sign(Phi r_x)> / sqrt(d) added.  `qjl` holds the side information of the same blocks, in
+ * the same order as `keys`.  Everything else as eoq_scores.
+ */
+eoq_status eoq_scores_prod(eoq_ctx* ctx, eoq_packed keys, eoq_qjl qjl, int64_t n_seq, int n_kv_heads,
+                           int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
+                           void* hip_stream);
 
 /*
  * Attention weights: softmax over each of `rows` rows of `len` float32 logits, in place (Sec. 2.1, the softmax of

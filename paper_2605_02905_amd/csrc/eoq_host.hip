@@ -137,6 +137,8 @@ EoqLaunch make_launch(const eoq_ctx* ctx, void* stream) {
   L.pit = ctx->d_pit;
   L.tab = ctx->d_tab;
   L.pih = ctx->d_pih;
+  L.phit = ctx->d_phit;
+  L.phih = ctx->d_phih;
   L.stream = static_cast<hipStream_t>(stream);
   L.ev = ctx->profile ? ctx->ev : nullptr;
   L.solver = ctx->solver;
@@ -183,6 +185,9 @@ eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, 
       ctx->pi_host[(size_t)c * d + j] = v;
       pit[(size_t)j * d + c] = v;
     }
+  // Phi of TQ_prod: iid N(0,1) from the same generator, seeded with rot_seed + 1; used as a float32 table
+  ctx->phi_host.resize((size_t)d * d);
+  for (int i = 0; i < d * d; ++i) ctx->phi_host[i] = (float)gaussian_draw(rot_seed + 1, (uint64_t)i);
   std::vector<double> cent, bnd;
   lloyd_max(4, cent, bnd);
   for (int i = 0; i < 8; ++i) ctx->gauss16[i] = cent[8 + i];
@@ -222,6 +227,21 @@ eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, 
       split[(size_t)2 * d * d + (size_t)j * d + c] = hb;   // Pi^T hi [j][c]
       split[(size_t)3 * d * d + (size_t)j * d + c] = lb;   // Pi^T lo [j][c]
     }
+  std::vector<float> phit((size_t)d * d);
+  std::vector<uint16_t> psplit((size_t)2 * d * d);
+  for (int i = 0; i < d; ++i)
+    for (int j = 0; j < d; ++j) {
+      const float v = ctx->phi_host[(size_t)i * d + j];
+      phit[(size_t)j * d + i] = v;
+      const _Float16 hi = (_Float16)v;
+      const _Float16 lo = (_Float16)(v - (float)hi);
+      std::memcpy(&psplit[(size_t)i * d + j], &hi, 2);
+      std::memcpy(&psplit[(size_t)d * d + (size_t)i * d + j], &lo, 2);
+    }
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_phit, mat_bytes);
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_phih, psplit.size() * 2);
+  if (e == hipSuccess) e = hipMemcpy(ctx->d_phit, phit.data(), mat_bytes, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(ctx->d_phih, psplit.data(), psplit.size() * 2, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pih, split.size() * 2);
   if (e == hipSuccess) e = hipMemcpy(ctx->d_pih, split.data(), split.size() * 2, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(ctx->d_pi, ctx->pi_host.data(), mat_bytes, hipMemcpyHostToDevice);
@@ -242,6 +262,8 @@ void eoq_destroy(eoq_ctx* ctx) {
   if (ctx->d_pit) (void)hipFree(ctx->d_pit);
   if (ctx->d_tab) (void)hipFree(ctx->d_tab);
   if (ctx->d_pih) (void)hipFree(ctx->d_pih);
+  if (ctx->d_phit) (void)hipFree(ctx->d_phit);
+  if (ctx->d_phih) (void)hipFree(ctx->d_phih);
   if (ctx->profile)
     for (hipEvent_t& e : ctx->ev) (void)hipEventDestroy(e);
   delete ctx;
@@ -255,6 +277,12 @@ size_t eoq_workspace_bytes(const eoq_ctx* ctx, int64_t B) {
 eoq_status eoq_rotation(const eoq_ctx* ctx, float* host_out) {
   if (!ctx || !host_out) return EOQ_ERR_ARG;
   std::memcpy(host_out, ctx->pi_host.data(), ctx->pi_host.size() * sizeof(float));
+  return EOQ_OK;
+}
+
+eoq_status eoq_projection(const eoq_ctx* ctx, float* host_out) {
+  if (!ctx || !host_out) return EOQ_ERR_ARG;
+  std::memcpy(host_out, ctx->phi_host.data(), ctx->phi_host.size() * sizeof(float));
   return EOQ_OK;
 }
 
@@ -496,6 +524,55 @@ eoq_status eoq_attend(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_h
   const hipError_t e = eoq_launch_attend(L, values, n_seq, n_kv_heads, blocks_filled, block_capacity, weights,
                                          weight_stride, n_q_heads, out, static_cast<float*>(workspace));
   if (ctx->profile) ctx->ev_valid[4] = (e == hipSuccess);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+eoq_status eoq_qjl_encode(eoq_ctx* ctx, const void* blocks_fp16, int64_t B, eoq_packed rec, eoq_qjl out,
+                          void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (B < 0) return fail(ctx, EOQ_ERR_ARG, "negative block count");
+  if (B == 0) return EOQ_OK;
+  if (!blocks_fp16 || !aligned16(blocks_fp16)) return fail(ctx, EOQ_ERR_ARG, "null or misaligned blocks pointer");
+  if (eoq_status st = check_packed(ctx, rec)) return st;
+  if (!out.signs || !out.norms || !aligned16(out.signs) || !aligned16(out.norms))
+    return fail(ctx, EOQ_ERR_ARG, "eoq_qjl has a null or misaligned member");
+  if (B > (int64_t)1 << 24) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  const hipError_t e = eoq_launch_qjl(L, blocks_fp16, B, rec, out);
+  if (e != hipSuccess) {
+    ctx->err = std::string("HIP: ") + hipGetErrorString(e);
+    return EOQ_ERR_HIP;
+  }
+  return EOQ_OK;
+}
+
+eoq_status eoq_scores_prod(eoq_ctx* ctx, eoq_packed keys, eoq_qjl qjl, int64_t n_seq, int n_kv_heads,
+                           int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
+                           void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (n_seq < 0 || blocks_per_head < 0 || n_kv_heads < 1 || n_q_heads < 1)
+    return fail(ctx, EOQ_ERR_ARG, "negative or zero size");
+  if (n_q_heads % n_kv_heads != 0 || n_q_heads / n_kv_heads > 8)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "query heads must be a multiple (1..8) of KV heads");
+  if (n_seq == 0 || blocks_per_head == 0) return EOQ_OK;
+  if (!q_fp16 || !scores || !aligned16(q_fp16) || !aligned16(scores))
+    return fail(ctx, EOQ_ERR_ARG, "null or misaligned query/score pointer");
+  if (eoq_status st = check_packed(ctx, keys)) return st;
+  if (!qjl.signs || !qjl.norms || !aligned16(qjl.signs) || !aligned16(qjl.norms))
+    return fail(ctx, EOQ_ERR_ARG, "eoq_qjl has a null or misaligned member");
+  if (n_seq * n_kv_heads * blocks_per_head > (int64_t)1 << 24)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  const EoqLaunch L = make_launch(ctx, hip_stream);
+  const hipError_t e = eoq_launch_scores_prod(L, keys, qjl, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores);
+  if (ctx->profile) ctx->ev_valid[3] = (e == hipSuccess);
   if (e != hipSuccess) {
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);
     return EOQ_ERR_HIP;

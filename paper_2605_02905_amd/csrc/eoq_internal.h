@@ -26,6 +26,9 @@ struct eoq_ctx {
   float* d_pit = nullptr;        // device Pi^T [j][c]
   float* d_tab = nullptr;        // device: 16 centroids then 16 bounds (padded)
   uint16_t* d_pih = nullptr;     // device binary16: Pi hi [c][j], Pi lo [c][j], Pi^T hi [j][c], Pi^T lo [j][c]
+  std::vector<float> phi_host;   // [d][d] Gaussian projection Phi of TQ_prod (Alg. 1 REQUIRE), float32
+  float* d_phit = nullptr;       // device Phi^T [j][i]
+  uint16_t* d_phih = nullptr;    // device binary16: Phi hi [i][j], Phi lo [i][j]
   std::string err;
   double gauss16[8] = {};  // Lloyd-Max magnitudes of N(0,1) at 16 levels: start of the per-block factor codebooks
   int solver = 0;  // 0: tridiagonal eigensolver with Jacobi for repeated eigenvalues, 1: Jacobi for every block
@@ -59,6 +62,8 @@ struct EoqLaunch {
   const float* pit;
   const float* tab;
   const uint16_t* pih;
+  const float* phit;
+  const uint16_t* phih;
   hipStream_t stream;
   const hipEvent_t* ev;  // null unless profiling
   int solver;
@@ -97,3 +102,8 @@ hipError_t eoq_launch_attend(const EoqLaunch& L, eoq_packed values, int64_t n_se
                              int64_t blocks_per_head, int64_t block_capacity, const float* weights,
                              int64_t weight_stride, int n_q_heads, float* out, float* partial);
 hipError_t eoq_launch_softmax(const EoqLaunch& L, float* x, int64_t rows, int64_t len, int64_t stride);
+
+// TQ_prod side information of stored records and scores with the correction of Eq. (qjl)
+hipError_t eoq_launch_qjl(const EoqLaunch& L, const void* blocks_fp16, int64_t B, eoq_packed rec, eoq_qjl out);
+hipError_t eoq_launch_scores_prod(const EoqLaunch& L, eoq_packed keys, eoq_qjl qjl, int64_t n_seq, int n_kv_heads,
+                                  int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores);

@@ -39,6 +39,11 @@ __device__ __forceinline__ float16v mfma16(const H8& a, const H8& b, float16v c)
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, c, 0, 0, 0);
 }
 
+__device__ __forceinline__ void split_half(float v, uint16_t& hi, uint16_t& lo) {
+  hi = float_to_half_bits(v);
+  lo = float_to_half_bits(v - half_bits_to_float(hi));
+}
+
 // Mask table: entry m (a byte of one bit-plane) -> 8 halfwords, halfword e = 0xFFFF if bit e of m is set.
 __device__ __forceinline__ void build_mask_table(uint4* tab, int tid) {
   if (tid < 256) {
@@ -303,6 +308,192 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// TQ_prod side information (Alg. 1 lines "TQ_prod"): one workgroup per block.  The reconstruction of the record is
+// formed as in the decoder, tile by tile in float32 accumulators (centroids as binary16 hi + lo here: the residual
+// is a small difference), r_x = S - x_hat goes to LDS as binary16 hi + lo, its norm is taken there, and one more
+// product with the stationary-free operand Phi (hi + lo, read through the caches) gives Phi r_x, of which only the
+// signs are kept, packed like one more bit-plane.
+// ---------------------------------------------------------------------------------------------
+template <int BITS>
+__global__ __launch_bounds__(THREADS, 1) void eoq_qjl_kernel(
+    const uint16_t* __restrict__ blocks, int n, int r_max, const uint16_t* __restrict__ pih,
+    const uint16_t* __restrict__ phih, const float* __restrict__ tab, const uint8_t* __restrict__ codes,
+    const uint16_t* __restrict__ norms, const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac,
+    const uint16_t* __restrict__ rfac, uint8_t* __restrict__ qsigns, uint16_t* __restrict__ qnorms) {
+  __shared__ __align__(16) uint16_t Z[CHUNK * ZLD];     // centroid values (hi) of the chunk, [token][coordinate]
+  __shared__ __align__(16) uint16_t Zl[CHUNK * ZLD];    // their low parts
+  __shared__ __align__(16) uint16_t Ct[CHUNK * CLD];    // low-rank coefficients, [token][component]
+  __shared__ __align__(16) float rho_s[CHUNK];          // rho / sqrt(d)
+  __shared__ __align__(16) uint4 mask_tab[256];
+  __shared__ __align__(16) uint16_t Eh[32 * ZLD];       // residual tile of 32 tokens, hi
+  __shared__ __align__(16) uint16_t El[32 * ZLD];       // and lo
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int jcol = 32 * wave + l32;
+  const int tl = 32 * wave + l32;
+  const size_t blk = blockIdx.x;
+
+  build_mask_table(mask_tab, tid);
+  for (int e = tid; e < CHUNK * CLD / 8; e += THREADS) *reinterpret_cast<uint4*>(&Ct[e * 8]) = make_uint4(0u, 0u, 0u, 0u);
+  Mags<BITS> mg;
+  mg.load(tab);
+  const uint16_t* pit_hi = pih + 2 * D * D;
+  const uint16_t* pit_lo = pih + 3 * D * D;
+  H8 Bhi[8], Blo[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    Bhi[kk].u = *reinterpret_cast<const uint4*>(pit_hi + jcol * D + 16 * kk + 8 * hf);
+    Blo[kk].u = *reinterpret_cast<const uint4*>(pit_lo + jcol * D + 16 * kk + 8 * hf);
+  }
+  // Phi rows i = 32 wave + l32 as the second stationary operand (one workgroup per CU: the register file allows it)
+  H8 Fhi[8], Flo[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    Fhi[kk].u = *reinterpret_cast<const uint4*>(phih + jcol * D + 16 * kk + 8 * hf);
+    Flo[kk].u = *reinterpret_cast<const uint4*>(phih + D * D + jcol * D + 16 * kk + 8 * hf);
+  }
+  const float inv_sqrt_d = 1.0f / sqrtf((float)D);
+  DecodeFetch<BITS> cur;
+  H8 Bv[2];
+  const int r = min(max(rank_in[blk], 0), r_max);
+  decode_fetch_v(Bv, blk, r, r_max, jcol, hf, rfac);
+
+  for (int t0 = 0; t0 < n; t0 += CHUNK) {
+    decode_fetch<BITS>(cur, blk, t0, n, r_max, tid, tl, codes, norms, rank_in, lfac);
+    __syncthreads();  // previous chunk consumed; orders the mask table and the cleared Ct before first use
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      uint32_t byte[BITS];
+#pragma unroll
+      for (int p = 0; p < BITS; ++p) {
+        const uint32_t wsel = (kk < 2) ? cur.pl[p].x : (kk < 4) ? cur.pl[p].y : (kk < 6) ? cur.pl[p].z : cur.pl[p].w;
+        byte[p] = (wsel >> (16 * (kk & 1) + 8 * hf)) & 0xFFu;
+      }
+      H8 clo;
+      const H8 c = centroids_of<BITS, true>(byte, mask_tab, mg, &clo);
+      *reinterpret_cast<uint4*>(&Z[tl * ZLD + 16 * kk + 8 * hf]) = c.u;
+      *reinterpret_cast<uint4*>(&Zl[tl * ZLD + 16 * kk + 8 * hf]) = clo.u;
+    }
+    if (hf == 0) rho_s[tl] = half_bits_to_float(cur.rho) * inv_sqrt_d;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int i = (tid + THREADS * u) >> 4, seg = tid & 15;
+      if (i < r) {
+        H8 c;
+        c.u = cur.cf[u];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) Ct[(8 * seg + x) * CLD + i] = c.s[x];
+      }
+    }
+    __syncthreads();
+    // the block's own entries S[row][jcol] of a tile, requested one tile ahead
+    uint16_t sv[16], svn[16];
+    {
+      const uint16_t* srow = blocks + (blk * (size_t)n + t0) * D + jcol;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sv[v] = srow[(size_t)(8 * (v >> 2) + 4 * hf + (v & 3)) * D];
+    }
+#pragma unroll 1
+    for (int tau = 0; tau < CHUNK / 32; ++tau) {
+      if (tau + 1 < CHUNK / 32) {
+        const uint16_t* srow = blocks + (blk * (size_t)n + t0 + 32 * (tau + 1)) * D + jcol;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) svn[v] = srow[(size_t)(8 * (v >> 2) + 4 * hf + (v & 3)) * D];
+      }
+      // ---- x_hat of tokens 32 tau .. 32 tau + 31, columns 32 wave .. 32 wave + 31 ----
+      float16v acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+      const int arow = 32 * tau + l32;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        H8 a0, a1;
+        a0.u = *reinterpret_cast<const uint4*>(&Z[arow * ZLD + 16 * kk + 8 * hf]);
+        a1.u = *reinterpret_cast<const uint4*>(&Zl[arow * ZLD + 16 * kk + 8 * hf]);
+        acc = mfma16(a0, Bhi[kk], acc);
+        acc = mfma16(a0, Blo[kk], acc);
+        acc = mfma16(a1, Bhi[kk], acc);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 s = *reinterpret_cast<const float4*>(&rho_s[32 * tau + 8 * q + 4 * hf]);
+        acc[4 * q + 0] *= s.x;
+        acc[4 * q + 1] *= s.y;
+        acc[4 * q + 2] *= s.z;
+        acc[4 * q + 3] *= s.w;
+      }
+      if (r > 0) {
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+          if (16 * k2 < r) {
+            H8 a0;
+            a0.u = *reinterpret_cast<const uint4*>(&Ct[arow * CLD + 16 * k2 + 8 * hf]);
+            acc = mfma16(a0, Bv[k2], acc);
+          }
+        }
+      }
+      // ---- r_x = S - x_hat into the tile, hi + lo ----
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = 8 * (v >> 2) + 4 * hf + (v & 3);
+        const float e = half_bits_to_float(sv[v]) - acc[v];
+        uint16_t hi, lo;
+        split_half(e, hi, lo);
+        Eh[row * ZLD + jcol] = hi;
+        El[row * ZLD + jcol] = lo;
+      }
+      __syncthreads();  // the tile is complete
+      // ---- norms: 8 lanes per token, 16 columns each ----
+      {
+        const int row = tid >> 3, seg = tid & 7;
+        float ss = 0.0f;
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          H8 a, b;
+          a.u = *reinterpret_cast<const uint4*>(&Eh[row * ZLD + 16 * seg + 8 * h2]);
+          b.u = *reinterpret_cast<const uint4*>(&El[row * ZLD + 16 * seg + 8 * h2]);
+#pragma unroll
+          for (int x = 0; x < 8; ++x) {
+            const float e = half_bits_to_float(a.s[x]) + half_bits_to_float(b.s[x]);
+            ss = fmaf(e, e, ss);
+          }
+        }
+        ss += dpp_mov<0xB1>(ss);
+        ss += dpp_mov<0x4E>(ss);
+        ss += dpp_mov<0x141>(ss);   // lane -> 7 - lane inside each group of 8
+        if (seg == 0) qnorms[blk * (size_t)n + t0 + 32 * tau + row] = float_to_half_bits(sqrtf(ss));
+      }
+      // ---- Phi r_x for outputs i = 32 wave + l32, signs only ----
+      float16v pr;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) pr[v] = 0.0f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        H8 a0, a1;
+        a0.u = *reinterpret_cast<const uint4*>(&Eh[l32 * ZLD + 16 * kk + 8 * hf]);
+        a1.u = *reinterpret_cast<const uint4*>(&El[l32 * ZLD + 16 * kk + 8 * hf]);
+        pr = mfma16(a0, Fhi[kk], pr);
+        pr = mfma16(a0, Flo[kk], pr);
+        pr = mfma16(a1, Fhi[kk], pr);
+      }
+      uint32_t outw = 0u;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const unsigned long long m = __ballot(pr[v] >= 0.0f);
+        const int row_lo = 8 * (v >> 2) + (v & 3);   // token of the low word; the high word is row_lo + 4
+        outw = (lane == row_lo) ? (uint32_t)m : ((lane == row_lo + 4) ? (uint32_t)(m >> 32) : outw);
+      }
+      if (lane < 32)
+        *reinterpret_cast<uint32_t*>(qsigns + (blk * (size_t)n + t0 + 32 * tau + lane) * (D / 8) + 4 * wave) = outw;
+      __syncthreads();  // the tile may be overwritten
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sv[v] = svn[v];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // scores: one workgroup per (sequence, KV head, run of blocks).  v_mfma_f32_16x16x32_f16: lane l supplies
 // A[row = l%16][k = 8*(l/16) .. +7] and B[k = 8*(l/16) .. +7][col = l%16], receives D[row = 4*(l/16)+v][col = l%16].
 // Rows are the query heads of the group (padded to 16), columns are 16 tokens; the 128 coordinates are
@@ -315,18 +506,17 @@ constexpr int SC_RUN_MAX = 16;  // most blocks per workgroup (the run is shorten
 __device__ __forceinline__ float4v mfma32(const H8& a, const H8& b, float4v c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c, 0, 0, 0);
 }
-__device__ __forceinline__ void split_half(float v, uint16_t& hi, uint16_t& lo) {
-  hi = float_to_half_bits(v);
-  lo = float_to_half_bits(v - half_bits_to_float(hi));
-}
 
-template <int BITS>
+// QJL: the logits get the correction of Eq. (qjl), |r_x| sqrt(pi/2)/d <Phi q, sign(Phi r_x)>, from one more bit-plane
+// (the signs, expanded to +-1) and the stored residual norm; Phi q is formed once per workgroup like Pi q.
+template <int BITS, bool QJL>
 __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
     int n, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, int64_t block_capacity, int64_t score_stride,
     int run, const float* __restrict__ pit,
     const float* __restrict__ tab, const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
     const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac,
-    const uint16_t* __restrict__ q, float* __restrict__ scores) {
+    const uint16_t* __restrict__ q, float* __restrict__ scores, const float* __restrict__ phit,
+    const uint8_t* __restrict__ qsigns, const uint16_t* __restrict__ qnorms) {
   __shared__ float qraw[SC_MAXG * D];
   __shared__ float qrot[SC_MAXG * D];
   __shared__ float wbuf[SC_MAXG * EOQ_RMAX_CAP];
@@ -362,6 +552,25 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
       const float v = (l16 < group) ? qrot[l16 * D + 32 * g + 8 * kk + e] : 0.0f;
       split_half(v, Aq_hi[kk].s[e], Aq_lo[kk].s[e]);
     }
+  H8 Ap_hi[QJL ? 4 : 1], Ap_lo[QJL ? 4 : 1];
+  if constexpr (QJL) {
+    __syncthreads();  // qrot has been read: reuse it for Phi q
+    for (int e = tid; e < group * D; e += THREADS) {
+      const int h = e >> 7, i = e & (D - 1);
+      float acc = 0.0f;
+      for (int j = 0; j < D; ++j) acc = fmaf(phit[j * D + i], qraw[h * D + j], acc);
+      qrot[e] = acc;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float v = (l16 < group) ? qrot[l16 * D + 32 * g + 8 * kk + e] : 0.0f;
+        split_half(v, Ap_hi[kk].s[e], Ap_lo[kk].s[e]);
+      }
+  }
+  const float qjl_scale = sqrtf(1.5707963267948966f) / (float)D;
 
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   const int64_t j_end = min((int64_t)(blockIdx.x + 1) * run, blocks_per_head);
@@ -389,6 +598,8 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
     // accumulator chains are independent
     for (int tile = wave; tile < n / 16; tile += 2 * (THREADS / 64)) {
       uint32_t word[2][BITS];
+      uint32_t sword[2] = {0u, 0u};
+      float gam[2] = {0.0f, 0.0f};
       H8 c[2];
       float rho[2];
 #pragma unroll
@@ -397,6 +608,10 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
         const size_t tok = blk * (size_t)n + t;
 #pragma unroll
         for (int p = 0; p < BITS; ++p) word[u][p] = *reinterpret_cast<const uint32_t*>(codes + tok * ROWB + p * 16 + 4 * g);
+        if constexpr (QJL) {
+          sword[u] = *reinterpret_cast<const uint32_t*>(qsigns + tok * (D / 8) + 4 * g);
+          gam[u] = half_bits_to_float(qnorms[tok]) * qjl_scale;
+        }
         if (r > 0) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
@@ -429,6 +644,25 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
         acc2[1] = mfma32(Aw_hi, c[1], acc2[1]);
         acc2[0] = mfma32(Aw_lo, c[0], acc2[0]);
         acc2[1] = mfma32(Aw_lo, c[1], acc2[1]);
+      }
+      if constexpr (QJL) {
+        float4v acc3[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            H8 m, sg;
+            m.u = mask_tab[(sword[u] >> (8 * kk)) & 0xFFu];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) sg.w[w] = (m.w[w] & 0x80008000u) ^ 0xBC00BC00u;   // bit set: +1.0, clear: -1.0
+            acc3[u] = mfma32(Ap_hi[kk], sg, acc3[u]);
+            acc3[u] = mfma32(Ap_lo[kk], sg, acc3[u]);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc2[u][v] = fmaf(acc3[u][v], gam[u], acc2[u][v]);
       }
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
@@ -723,10 +957,11 @@ hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void*
   return hipGetLastError();
 }
 
-hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq, int n_kv_heads,
-                             int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
-                             int64_t block_capacity, int64_t score_stride, const void* tail_fp16,
-                             int64_t tail_capacity, int tail_len) {
+namespace {
+hipError_t launch_scores_impl(const EoqLaunch& L, eoq_packed keys, const eoq_qjl* qjl, int64_t n_seq, int n_kv_heads,
+                              int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
+                              int64_t block_capacity, int64_t score_stride, const void* tail_fp16,
+                              int64_t tail_capacity, int tail_len) {
   const int64_t sg_total = n_seq * n_kv_heads;
   if (block_capacity <= 0) block_capacity = blocks_per_head;
   if (score_stride <= 0) score_stride = blocks_per_head * L.n;
@@ -747,10 +982,19 @@ hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq,
   if (sg_total > 65535 || runs > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)runs, (unsigned)sg_total), block(THREADS);
   const uint16_t* q = static_cast<const uint16_t*>(q_fp16);
-#define EOQ_SCORES(BITS)                                                                                          \
-  hipLaunchKernelGGL(eoq_scores_mfma_kernel<BITS>, grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads,            \
-                     n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pit, L.tab, keys.codes, keys.norms, keys.rank,    \
-                     keys.lfac, keys.rfac, q, scores)
+#define EOQ_SCORES(BITS)                                                                                            \
+  do {                                                                                                              \
+    if (qjl)                                                                                                        \
+      hipLaunchKernelGGL((eoq_scores_mfma_kernel<BITS, true>), grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads,  \
+                         n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pit,    \
+                         L.tab, keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, q, scores, L.phit,         \
+                         qjl->signs, qjl->norms);                                                                   \
+    else                                                                                                            \
+      hipLaunchKernelGGL((eoq_scores_mfma_kernel<BITS, false>), grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads, \
+                         n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pit,    \
+                         L.tab, keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, q, scores,                 \
+                         (const float*)nullptr, (const uint8_t*)nullptr, (const uint16_t*)nullptr);                 \
+  } while (0)
   switch (L.bits) {
     case 1: EOQ_SCORES(1); break;
     case 2: EOQ_SCORES(2); break;
@@ -759,6 +1003,37 @@ hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq,
   }
 #undef EOQ_SCORES
   if (L.ev) (void)hipEventRecord(L.ev[7], L.stream);
+  return hipGetLastError();
+}
+}  // namespace
+
+hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq, int n_kv_heads,
+                             int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
+                             int64_t block_capacity, int64_t score_stride, const void* tail_fp16,
+                             int64_t tail_capacity, int tail_len) {
+  return launch_scores_impl(L, keys, nullptr, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores,
+                            block_capacity, score_stride, tail_fp16, tail_capacity, tail_len);
+}
+
+hipError_t eoq_launch_scores_prod(const EoqLaunch& L, eoq_packed keys, eoq_qjl qjl, int64_t n_seq, int n_kv_heads,
+                                  int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores) {
+  return launch_scores_impl(L, keys, &qjl, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores, 0, 0, nullptr,
+                            0, 0);
+}
+
+hipError_t eoq_launch_qjl(const EoqLaunch& L, const void* blocks_fp16, int64_t B, eoq_packed rec, eoq_qjl out) {
+  const dim3 grid((unsigned)B), block(THREADS);
+  const uint16_t* src = static_cast<const uint16_t*>(blocks_fp16);
+#define EOQ_QJL(BITS)                                                                                              \
+  hipLaunchKernelGGL(eoq_qjl_kernel<BITS>, grid, block, 0, L.stream, src, L.n, L.r_max, L.pih, L.phih, L.tab,      \
+                     rec.codes, rec.norms, rec.rank, rec.lfac, rec.rfac, out.signs, out.norms)
+  switch (L.bits) {
+    case 1: EOQ_QJL(1); break;
+    case 2: EOQ_QJL(2); break;
+    case 3: EOQ_QJL(3); break;
+    default: EOQ_QJL(4); break;
+  }
+#undef EOQ_QJL
   return hipGetLastError();
 }
 

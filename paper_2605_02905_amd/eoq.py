@@ -17,7 +17,8 @@ EOQ_OK, EOQ_ERR_ARG, EOQ_ERR_UNSUPPORTED, EOQ_ERR_WORKSPACE, EOQ_ERR_HIP = range
 EOQ_F16, EOQ_F32 = 0, 1
 FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE = 1, 2, 4
 
-EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_codebook",
+EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_projection",
+           "eoq_codebook", "eoq_qjl_encode", "eoq_scores_prod",
            "eoq_compress", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_softmax", "eoq_attend_workspace_bytes", "eoq_attend", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
 
 
@@ -34,6 +35,10 @@ class _Packed(C.Structure):
 
 class _FactorCodes(C.Structure):
     _fields_ = [("lcodes", C.c_void_p), ("rcodes", C.c_void_p), ("fbook", C.c_void_p), ("phi16", C.c_void_p)]
+
+
+class _Qjl(C.Structure):
+    _fields_ = [("signs", C.c_void_p), ("norms", C.c_void_p)]
 
 
 class ChunkLayout(C.Structure):
@@ -62,6 +67,13 @@ def lib():
         L.eoq_workspace_bytes.restype = C.c_size_t
         L.eoq_rotation.argtypes = [C.c_void_p, C.c_void_p]
         L.eoq_rotation.restype = C.c_int
+        L.eoq_projection.argtypes = [C.c_void_p, C.c_void_p]
+        L.eoq_projection.restype = C.c_int
+        L.eoq_qjl_encode.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, _Packed, _Qjl, C.c_void_p]
+        L.eoq_qjl_encode.restype = C.c_int
+        L.eoq_scores_prod.argtypes = [C.c_void_p, _Packed, _Qjl, C.c_int64, C.c_int, C.c_int64, C.c_void_p, C.c_int,
+                                      C.c_void_p, C.c_void_p]
+        L.eoq_scores_prod.restype = C.c_int
         L.eoq_codebook.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.eoq_codebook.restype = C.c_int
         L.eoq_compress.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, _Packed, C.c_void_p, C.c_size_t,
@@ -162,6 +174,21 @@ class FactorCodes:
         return sum(t.numel() * t.element_size() for t in (self.lcodes, self.rcodes, self.fbook, self.phi16))
 
 
+@dataclass
+class Qjl:
+    """Device tensors of the TQ_prod side information of a batch (layout: include/eoq.h, eoq_qjl)."""
+    signs: torch.Tensor   # uint8   [B, n, d/8]
+    norms: torch.Tensor   # float16 [B, n]
+
+    def c_struct(self) -> _Qjl:
+        return _Qjl(self.signs.data_ptr(), self.norms.data_ptr())
+
+    @staticmethod
+    def empty(B: int, n: int, d: int, device) -> "Qjl":
+        return Qjl(torch.empty(B, n, d // 8, dtype=torch.uint8, device=device),
+                   torch.empty(B, n, dtype=torch.float16, device=device))
+
+
 def _stream_ptr(device) -> int:
     return torch.cuda.current_stream(device).cuda_stream
 
@@ -196,6 +223,11 @@ class Context:
     def eoq_rotation(self) -> np.ndarray:
         out = np.empty((self.d, self.d), dtype=np.float32)
         self._check(lib().eoq_rotation(self._h, out.ctypes.data))
+        return out
+
+    def eoq_projection(self) -> np.ndarray:
+        out = np.empty((self.d, self.d), dtype=np.float32)
+        self._check(lib().eoq_projection(self._h, out.ctypes.data))
         return out
 
     def eoq_codebook(self):
@@ -303,6 +335,29 @@ class Context:
                                             tail.data_ptr() if tail is not None else None, tail_cap, tail_len,
                                             q.data_ptr(), n_q_heads, out.data_ptr(), out.shape[2],
                                             _stream_ptr(q.device)))
+        return out
+
+    def eoq_qjl_encode(self, blocks: torch.Tensor, rec: Packed, out: Qjl | None = None) -> Qjl:
+        """blocks: the float16 device blocks `rec` was compressed from.  Returns the TQ_prod side information."""
+        assert blocks.is_cuda and blocks.is_contiguous() and blocks.dtype == torch.float16
+        assert blocks.shape[1:] == (self.n, self.d) and rec.rank.shape[0] == blocks.shape[0]
+        B = blocks.shape[0]
+        if out is None:
+            out = Qjl.empty(B, self.n, self.d, blocks.device)
+        self._check(lib().eoq_qjl_encode(self._h, blocks.data_ptr(), B, rec.c_struct(), out.c_struct(),
+                                         _stream_ptr(blocks.device)))
+        return out
+
+    def eoq_scores_prod(self, keys: Packed, qjl: Qjl, q: torch.Tensor, n_kv_heads: int, out: torch.Tensor | None = None):
+        assert q.is_cuda and q.is_contiguous() and q.dtype == torch.float16
+        n_seq, n_q_heads, _ = q.shape
+        B = keys.rank.shape[0]
+        bph = B // (n_seq * n_kv_heads)
+        assert bph * n_seq * n_kv_heads == B and qjl.norms.shape[0] == B
+        if out is None:
+            out = torch.empty(n_seq, n_q_heads, bph * self.n, dtype=torch.float32, device=q.device)
+        self._check(lib().eoq_scores_prod(self._h, keys.c_struct(), qjl.c_struct(), n_seq, n_kv_heads, bph,
+                                          q.data_ptr(), n_q_heads, out.data_ptr(), _stream_ptr(q.device)))
         return out
 
     def eoq_softmax(self, scores: torch.Tensor, length: int | None = None) -> torch.Tensor:

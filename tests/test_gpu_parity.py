@@ -745,3 +745,120 @@ def test_attend_argument_errors():
     assert call(2, 2, 256, 4, 16) == eoq.EOQ_ERR_WORKSPACE
     assert L.eoq_softmax(ctx._h, w.data_ptr(), 4, 300, 256, None) == eoq.EOQ_ERR_ARG
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# TQ_prod: the 1-bit QJL correction (Alg. 1 lines "TQ_prod", Eq. (qjl)) on stored records
+# ---------------------------------------------------------------------------------------------------------------
+def _oracle_phi(ctx):
+    return oracle.gaussian_projection(128, ctx.rot_seed + 1).astype(np.float32).astype(np.float64)   # the stored table
+
+
+@pytest.mark.parametrize("n,bits,B,rank_hi", [(512, 2, 6, 8), (128, 4, 9, 5), (256, 3, 4, 6), (128, 1, 5, 3)])
+def test_qjl_side_information_of_oracle_records(n, bits, B, rank_hi):
+    """eoq_qjl_encode on records made by the oracle: the stored residual norms to one binary16 unit, the sign bits
+    equal except where |Phi r_x| is within rounding of zero (<= 0.1 % of the bits, and every differing bit has a
+    projection below 1e-3 of the row's scale)."""
+    spec = synth.BlockSpec("qjl", n=n, n_tensors=1, blocks_per_tensor=B, rank_lo=1, rank_hi=rank_hi, frac_rank0=0.2)
+    blocks, _ = synth.make_blocks(spec, seed=900 + n)
+    b64 = blocks.double().numpy()
+    Pi, cb = U.oracle_tables(bits)
+    recs = U.oracle_compress(b64, bits)
+    ctx = eoq.Context(n=n, bits=bits)
+    assert np.array_equal(ctx.eoq_projection().astype(np.float64), _oracle_phi(ctx)) or \
+        np.max(np.abs(ctx.eoq_projection() - _oracle_phi(ctx))) < 1e-6
+    Phi = ctx.eoq_projection().astype(np.float64)
+    packed = U.records_to_packed(recs, 32, DEV)
+    qj = ctx.eoq_qjl_encode(blocks.to(DEV).contiguous(), packed)
+    torch.cuda.synchronize()
+    signs_g = qj.signs.cpu().numpy()
+    norms_g = qj.norms.cpu().numpy().astype(np.float64)
+    bad = total = 0
+    for b, r in enumerate(recs):
+        oq = oracle.qjl_encode(b64[b], r, Pi, cb, Phi)
+        dn = np.abs(norms_g[b] - oq.gamma16)
+        assert np.all(dn <= np.spacing(oq.gamma16.astype(np.float16)).astype(np.float64)), b
+        sg = oracle.unpack_signs(signs_g[b], 128)
+        diff = sg != oq.signs
+        bad += int(diff.sum())
+        total += diff.size
+        scale = oq.gamma[:, None] * math.sqrt(128.0) + 1e-30            # |Phi r_x| is about |r_x| sqrt(d)
+        assert np.all(np.abs(oq.proj[diff]) <= 1e-3 * np.broadcast_to(scale, diff.shape)[diff]), b
+    assert bad <= 1e-3 * total, (bad, total)
+    U.log_stats(f"qjl-n{n}-b{bits}", dict(sign_mismatches=bad, sign_bits=total))
+
+
+def test_scores_prod_of_oracle_records():
+    """eoq_scores_prod fed with oracle records and oracle side information against Eq. (qjl) written out in the
+    oracle; the same call without correction equals eoq_scores."""
+    n_seq, n_kv, bph, group, n, bits = 2, 2, 3, 4, 256, 2
+    spec = synth.BlockSpec("pkeys", n=n, n_tensors=n_seq * n_kv, blocks_per_tensor=bph, rank_lo=1, rank_hi=6)
+    blocks, _ = synth.make_blocks(spec, seed=31)
+    b64 = blocks.double().numpy()
+    Pi, cb = U.oracle_tables(bits)
+    recs = U.oracle_compress(b64, bits)
+    ctx = eoq.Context(n=n, bits=bits)
+    Phi = ctx.eoq_projection().astype(np.float64)
+    oqs = [oracle.qjl_encode(b64[b], r, Pi, cb, Phi) for b, r in enumerate(recs)]
+    packed = U.records_to_packed(recs, 32, DEV)
+    qj = eoq.Qjl(torch.from_numpy(np.stack([oracle.pack_signs(o.signs) for o in oqs])).to(DEV),
+                 torch.from_numpy(np.stack([o.gamma16 for o in oqs]).astype(np.float16)).to(DEV))
+    q = synth.make_queries(n_seq, n_kv * group)
+    sp = ctx.eoq_scores_prod(packed, qj, q.to(DEV), n_kv)
+    s0 = ctx.eoq_scores(packed, q.to(DEV), n_kv)
+    torch.cuda.synchronize()
+    sp, s0 = sp.cpu().numpy().astype(np.float64), s0.cpu().numpy().astype(np.float64)
+    q64 = q.double().numpy()
+    for s in range(n_seq):
+        for g in range(n_kv):
+            for j in range(bph):
+                b = (s * n_kv + g) * bph + j
+                qs = q64[s, g * group:(g + 1) * group]
+                want = oracle.score_block_prod(qs, recs[b], oqs[b], Pi, cb, Phi)
+                got = sp[s, g * group:(g + 1) * group, j * n:(j + 1) * n]
+                assert np.max(np.abs(got - want)) <= 2e-5 * max(1.0, np.max(np.abs(want))), (s, g, j)
+                base = oracle.score_block(qs, recs[b], Pi, cb)
+                assert np.max(np.abs(s0[s, g * group:(g + 1) * group, j * n:(j + 1) * n] - base)) <= 1e-5 * max(1.0, np.max(np.abs(base)))
+    assert np.max(np.abs(sp - s0)) > 1e-3                               # the correction is there
+
+
+def test_tq_prod_end_to_end_in_the_bench_launch_configuration():
+    """Config 6 (4096 blocks of 128 x 128) through eoq_compress -> eoq_qjl_encode -> eoq_scores_prod in single launches;
+    a strided sample of blocks is followed through the oracle on the stored records, and over the whole key set the
+    corrected logits are closer to the exact <q, k>/sqrt(d) than the uncorrected ones are biased: the mean signed
+    error along the key direction shrinks (Eq. (qjl) is unbiased, TQ_MSE shrinks)."""
+    spec = synth.config(6)
+    blocks, _ = synth.make_blocks(spec, device=DEV)
+    B, n, bits, n_kv, group, bph = blocks.shape[0], spec.n, 2, 8, 4, spec.blocks_per_tensor
+    ctx = eoq.Context(n=n, bits=bits)
+    rec, _ = ctx.eoq_compress(blocks)
+    qj = ctx.eoq_qjl_encode(blocks, rec)
+    torch.cuda.synchronize()
+    Pi, cb = U.oracle_tables(bits)
+    Phi = ctx.eoq_projection().astype(np.float64)
+    idx = list(range(0, B, 173))
+    b64 = blocks[idx].double().cpu().numpy()
+    srecs = U.packed_to_records(rec, idx, bits)
+    bad = total = 0
+    for k_, b in enumerate(idx):
+        oq = oracle.qjl_encode(b64[k_], srecs[k_], Pi, cb, Phi)
+        sg = oracle.unpack_signs(qj.signs[b].cpu().numpy(), 128)
+        bad += int((sg != oq.signs).sum())
+        total += sg.size
+        assert np.all(np.abs(qj.norms[b].double().cpu().numpy() - oq.gamma16) <= np.spacing(oq.gamma16.astype(np.float16)).astype(np.float64))
+    assert bad <= 1e-3 * total, (bad, total)
+    key_blocks = n_kv * bph
+    keys = _subset(rec, list(range(key_blocks)))
+    kq = eoq.Qjl(qj.signs[:key_blocks], qj.norms[:key_blocks])
+    # queries along keys: q_h = key token (h * 97) of head g, so that <q, k> of that token is large and the shrinkage shows
+    q = torch.stack([blocks[g * bph, h * 31] for g in range(n_kv) for h in range(group)]).view(1, n_kv * group, 128).contiguous()
+    sp = ctx.eoq_scores_prod(keys, kq, q, n_kv)
+    s0 = ctx.eoq_scores(keys, q, n_kv)
+    torch.cuda.synchronize()
+    exact = torch.einsum("ghd,gtd->ght", q.view(n_kv, group, 128).double(), blocks[:key_blocks].view(n_kv, bph * n, 128).double()) / math.sqrt(128.0)
+    e0 = (s0.view(n_kv, group, -1).double() - exact)
+    ep = (sp.view(n_kv, group, -1).double() - exact)
+    own = torch.as_tensor([h * 31 for h in range(group)], device=DEV)
+    b0 = torch.stack([e0[:, h, own[h]] / exact[:, h, own[h]] for h in range(group)]).mean().item()
+    bp = torch.stack([ep[:, h, own[h]] / exact[:, h, own[h]] for h in range(group)]).mean().item()
+    assert b0 < -1e-3 and abs(bp) < abs(b0), (b0, bp)
