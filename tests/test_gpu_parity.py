@@ -862,3 +862,42 @@ def test_tq_prod_end_to_end_in_the_bench_launch_configuration():
     b0 = torch.stack([e0[:, h, own[h]] / exact[:, h, own[h]] for h in range(group)]).mean().item()
     bp = torch.stack([ep[:, h, own[h]] / exact[:, h, own[h]] for h in range(group)]).mean().item()
     assert b0 < -1e-3 and abs(bp) < abs(b0), (b0, bp)
+
+
+def test_prefill_chunk_in_the_bench_launch_configuration():
+    """Config 7 as bench.py issues it: one chunk of 512 blocks of 128 x 128 handed over token-major
+    ([64][128][8][128]) and written to slot 3 of 16 of every head-tensor, then eoq_scores_stream over one layer's store
+    plus a 64-token tail.  The written slots equal the dense call bit for bit; a sample of them goes through the
+    oracle; the streamed logits of the filled slot agree with eoq_scores on the dense record."""
+    spec = synth.config(7)
+    blocks, _ = synth.make_blocks(spec, device=DEV)
+    B, n, bits, H, L2, cap, slot = blocks.shape[0], spec.n, 2, 8, 64, 16, 3
+    chunk = blocks.view(L2, H, n, 128).permute(0, 2, 1, 3).contiguous()
+    ctx = eoq.Context(n=n, bits=bits)
+    dense, ws = ctx.eoq_compress(blocks)
+    store = eoq.Packed.empty(B * cap, n, 128, bits, ctx.r_max, DEV)
+    for f in _FIELDS:
+        getattr(store, f).zero_()
+    ctx.eoq_compress_chunk(chunk, B, eoq.ChunkLayout(n * H * 128, H, 128, H * 128, slot, cap), store)
+    torch.cuda.synchronize()
+    slots = torch.arange(B, device=DEV) * cap + slot
+    for f in _FIELDS:
+        assert _bits_equal(getattr(store, f).index_select(0, slots), getattr(dense, f)), f
+    others = torch.ones(B * cap, dtype=torch.bool, device=DEV)
+    others[slots] = False
+    assert not bool(store.codes[others].any()) and not bool(store.rank[others].any())
+    idx = list(range(0, B, 23))
+    b64 = blocks[idx].double().cpu().numpy()
+    recs = U.oracle_compress(b64, bits)
+    U.compare_compress(b64, _subset(store, [i * cap + slot for i in idx]), ctx.spectrum(ws, B)[idx].cpu().numpy(), recs, bits)
+    # layer 0 keys = tensors 0..7; only slot 3 is filled: score slots 0..3 (the empty ones reconstruct to zero)
+    q = synth.make_queries(1, H * 4, device=DEV)
+    tail = blocks[:H, :64].contiguous().view(1, H, 64, 128)
+    sc = ctx.eoq_scores_stream(store, q, H, cap, slot + 1, tail, 64)
+    ref = ctx.eoq_scores(_subset(dense, list(range(H))), q, H)
+    torch.cuda.synchronize()
+    assert torch.equal(sc[:, :, slot * n:(slot + 1) * n], ref)
+    assert not bool(sc[:, :, :slot * n].any())
+    want_tail = torch.einsum("ghd,gtd->ght", q.view(H, 4, 128).double(), tail.view(H, 64, 128).double()) / math.sqrt(128.0)
+    got_tail = sc[0, :, (slot + 1) * n:].view(H, 4, 64).double()
+    assert float((got_tail - want_tail).abs().max()) <= 1e-5 * max(1.0, float(want_tail.abs().max()))
