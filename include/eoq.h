@@ -285,6 +285,18 @@ eoq_status eoq_attend(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_h
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * eoq_attend over a cache that is still being filled (see eoq_scores_stream): the uncompressed binary16 tail values
+ * [n_seq][n_kv_heads][tail_capacity][d] contribute sum_t weights[s][h][blocks_filled*n + t] tail[s][g][t] for
+ * t < tail_len, so a weight row covers the blocks' tokens and then the tail, exactly as eoq_scores_stream lays the
+ * logits out.  tail_len < n, tail_len <= tail_capacity, weight_stride >= blocks_filled*n + tail_len; tail_fp16 may
+ * be NULL when tail_len = 0.  Everything else as eoq_attend.
+ */
+eoq_status eoq_attend_stream(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_heads, int64_t block_capacity,
+                             int64_t blocks_filled, const void* tail_fp16, int64_t tail_capacity, int64_t tail_len,
+                             const float* weights, int64_t weight_stride, int n_q_heads, float* out, void* workspace,
+                             size_t workspace_bytes, void* hip_stream);
+
+/*
  * Eigensolver used by eoq_compress for the d x d Gram matrix (the paper only asks for the SVD of the
  * block, Alg. 2 REQUIRE).  0 (default): Householder tridiagonalisation + Sturm multisection + twisted
  * factorisation, with blocks whose retained eigenvalues are numerically repeated handed to the Jacobi

@@ -31,7 +31,7 @@ __all__ = [
     "bulk_edge", "estimate_rank", "impute_noise_spectrum", "shrink",
     "EOptShrinkResult", "eoptshrink",
     "tq_mse_encode", "tq_mse_decode",
-    "BlockRecord", "compress_block", "decompress_block", "score_block", "score_stream", "softmax_rows", "attend_blocks",
+    "BlockRecord", "compress_block", "decompress_block", "score_block", "score_stream", "softmax_rows", "attend_blocks", "attend_stream",
     "gaussian_projection", "QjlRecord", "qjl_encode", "qjl_correction", "score_block_prod", "pack_signs", "unpack_signs",
     "pack_codes", "unpack_codes", "fp16_round", "fp16_bits", "bits_per_entry",
     "FLAG_RANK_CLAMPED", "FLAG_SHRINK_GUARD",
@@ -590,6 +590,19 @@ def attend_blocks(weights: np.ndarray, recs, Pi: np.ndarray, cb: Codebook) -> np
     if t0 != w.shape[1]:
         raise ValueError("weights do not cover the blocks' tokens")
     return out
+
+
+def attend_stream(weights: np.ndarray, recs, tail: np.ndarray, Pi: np.ndarray, cb: Codebook) -> np.ndarray:
+    """attend_blocks over a cache that is still being filled: the weights cover
+    the compressed blocks' tokens and then the uncompressed tail values [t, d]
+    (Sec. 7: the newest tokens stay in FP16), which enter as they are."""
+    w = np.asarray(weights, dtype=np.float64)
+    tail = np.asarray(tail, dtype=np.float64)
+    T = sum(r.n for r in recs)
+    if w.shape[1] != T + tail.shape[0]:
+        raise ValueError("weights do not cover the blocks' tokens plus the tail")
+    out = attend_blocks(w[:, :T], recs, Pi, cb) if recs else np.zeros((w.shape[0], tail.shape[1]))
+    return out + w[:, T:] @ tail
 
 
 # --------------------------------------------------------------------------

@@ -151,10 +151,15 @@ __global__ __launch_bounds__(THREADS) void eoq_attend_partial_kernel(
 }
 
 // out[s][h][j] = sum_c Pi[c][j] a_h[c] + lin_h[j], the runs added in order.  One workgroup per (sequence, KV head).
+// With tail_len > 0 the uncompressed binary16 tail values are added: + sum_t weights[.., tail_offset + t] tail[t].
 __global__ __launch_bounds__(THREADS) void eoq_attend_finish_kernel(int n_kv_heads, int group, int runs,
                                                                     const float* __restrict__ pi,
                                                                     const float* __restrict__ partial,
-                                                                    float* __restrict__ out) {
+                                                                    float* __restrict__ out,
+                                                                    const float* __restrict__ weights,
+                                                                    int64_t weight_stride, int64_t tail_offset,
+                                                                    const uint16_t* __restrict__ tail,
+                                                                    int64_t tail_capacity, int tail_len) {
   __shared__ float a_s[MAXG * D];
   const int tid = threadIdx.x;
   const int j = tid & (D - 1), th = tid >> 7;
@@ -185,6 +190,17 @@ __global__ __launch_bounds__(THREADS) void eoq_attend_finish_kernel(int n_kv_hea
     const float p = pi[cc * D + j];
 #pragma unroll
     for (int k = 0; k < MAXG / 2; ++k) acc[k] = fmaf(p, a_s[(th + 2 * k) * D + cc], acc[k]);
+  }
+  if (tail_len > 0) {
+#pragma unroll 4
+    for (int t = 0; t < tail_len; ++t) {
+      const float v = half_bits_to_float(tail[(sg * (size_t)tail_capacity + t) * D + j]);
+#pragma unroll
+      for (int k = 0; k < MAXG / 2; ++k) {
+        const int h = min(th + 2 * k, group - 1);   // heads past the group repeat the last one and are not stored
+        lin[k] = fmaf(weights[(sq * n_q_heads + kv * group + h) * (size_t)weight_stride + tail_offset + t], v, lin[k]);
+      }
+    }
   }
 #pragma unroll
   for (int k = 0; k < MAXG / 2; ++k) {
@@ -272,13 +288,16 @@ int64_t eoq_attend_runs(int64_t sg_total, int64_t blocks_per_head, int* run_out)
 
 hipError_t eoq_launch_attend(const EoqLaunch& L, eoq_packed values, int64_t n_seq, int n_kv_heads,
                              int64_t blocks_per_head, int64_t block_capacity, const float* weights,
-                             int64_t weight_stride, int n_q_heads, float* out, float* partial) {
+                             int64_t weight_stride, int n_q_heads, float* out, float* partial, const void* tail_fp16,
+                             int64_t tail_capacity, int tail_len) {
+  const uint16_t* tail = static_cast<const uint16_t*>(tail_fp16);
+  const int64_t tail_offset = blocks_per_head * L.n;
   const int64_t sg_total = n_seq * n_kv_heads;
   const int group = n_q_heads / n_kv_heads;
   if (L.ev) (void)hipEventRecord(L.ev[8], L.stream);
   if (blocks_per_head == 0) {  // nothing stored yet: the finishing kernel with no runs writes zeros
     hipLaunchKernelGGL(eoq_attend_finish_kernel, dim3((unsigned)sg_total), dim3(THREADS), 0, L.stream, n_kv_heads, group, 0,
-                       L.pi, partial, out);
+                       L.pi, partial, out, weights, weight_stride, tail_offset, tail, tail_capacity, tail_len);
     if (L.ev) (void)hipEventRecord(L.ev[9], L.stream);
     return hipGetLastError();
   }
@@ -300,7 +319,7 @@ hipError_t eoq_launch_attend(const EoqLaunch& L, eoq_packed values, int64_t n_se
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(eoq_attend_finish_kernel, dim3((unsigned)sg_total), block, 0, L.stream, n_kv_heads, group,
-                     (int)runs, L.pi, partial, out);
+                     (int)runs, L.pi, partial, out, weights, weight_stride, tail_offset, tail, tail_capacity, tail_len);
   if (L.ev) (void)hipEventRecord(L.ev[9], L.stream);
   return hipGetLastError();
 }

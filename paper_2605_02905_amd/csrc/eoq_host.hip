@@ -499,15 +499,20 @@ eoq_status eoq_softmax(eoq_ctx* ctx, float* scores, int64_t rows, int64_t len, i
   return EOQ_OK;
 }
 
-eoq_status eoq_attend(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_heads, int64_t block_capacity,
-                      int64_t blocks_filled, const float* weights, int64_t weight_stride, int n_q_heads, float* out,
-                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+static eoq_status attend_impl(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_heads, int64_t block_capacity,
+                              int64_t blocks_filled, const void* tail_fp16, int64_t tail_capacity, int64_t tail_len,
+                              const float* weights, int64_t weight_stride, int n_q_heads, float* out, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
   if (!ctx) return EOQ_ERR_ARG;
   ctx->err.clear();
   if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
   if (n_seq < 0 || blocks_filled < 0 || n_kv_heads < 1 || n_q_heads < 1) return fail(ctx, EOQ_ERR_ARG, "negative or zero size");
   if (blocks_filled > block_capacity) return fail(ctx, EOQ_ERR_ARG, "more blocks than the store holds");
-  if (weight_stride < blocks_filled * ctx->n) return fail(ctx, EOQ_ERR_ARG, "weight rows shorter than the blocks' tokens");
+  if (tail_len < 0 || tail_len > tail_capacity) return fail(ctx, EOQ_ERR_ARG, "more tail tokens than the tail buffer holds");
+  if (tail_len >= ctx->n) return fail(ctx, EOQ_ERR_UNSUPPORTED, "the tail holds fewer than n tokens");
+  if (tail_len > 0 && (!tail_fp16 || !aligned16(tail_fp16))) return fail(ctx, EOQ_ERR_ARG, "null or misaligned tail pointer");
+  if (weight_stride < blocks_filled * ctx->n + tail_len)
+    return fail(ctx, EOQ_ERR_ARG, "weight rows shorter than the blocks' tokens plus the tail");
   if (n_q_heads % n_kv_heads != 0 || n_q_heads / n_kv_heads > 8)
     return fail(ctx, EOQ_ERR_UNSUPPORTED, "query heads must be a multiple (1..8) of KV heads");
   if (n_seq == 0) return EOQ_OK;
@@ -522,7 +527,8 @@ eoq_status eoq_attend(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_h
     return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
   const EoqLaunch L = make_launch(ctx, hip_stream);
   const hipError_t e = eoq_launch_attend(L, values, n_seq, n_kv_heads, blocks_filled, block_capacity, weights,
-                                         weight_stride, n_q_heads, out, static_cast<float*>(workspace));
+                                         weight_stride, n_q_heads, out, static_cast<float*>(workspace), tail_fp16,
+                                         tail_capacity, (int)tail_len);
   if (ctx->profile) ctx->ev_valid[4] = (e == hipSuccess);
   if (e != hipSuccess) {
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);
@@ -578,6 +584,21 @@ eoq_status eoq_scores_prod(eoq_ctx* ctx, eoq_packed keys, eoq_qjl qjl, int64_t n
     return EOQ_ERR_HIP;
   }
   return EOQ_OK;
+}
+
+eoq_status eoq_attend(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_heads, int64_t block_capacity,
+                      int64_t blocks_filled, const float* weights, int64_t weight_stride, int n_q_heads, float* out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return attend_impl(ctx, values, n_seq, n_kv_heads, block_capacity, blocks_filled, nullptr, 0, 0, weights, weight_stride,
+                     n_q_heads, out, workspace, workspace_bytes, hip_stream);
+}
+
+eoq_status eoq_attend_stream(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int n_kv_heads, int64_t block_capacity,
+                             int64_t blocks_filled, const void* tail_fp16, int64_t tail_capacity, int64_t tail_len,
+                             const float* weights, int64_t weight_stride, int n_q_heads, float* out, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+  return attend_impl(ctx, values, n_seq, n_kv_heads, block_capacity, blocks_filled, tail_fp16, tail_capacity, tail_len,
+                     weights, weight_stride, n_q_heads, out, workspace, workspace_bytes, hip_stream);
 }
 
 eoq_status eoq_set_solver(eoq_ctx* ctx, int solver) {

@@ -100,7 +100,8 @@ hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq,
 int64_t eoq_attend_runs(int64_t sg_total, int64_t blocks_per_head, int* run_out);
 hipError_t eoq_launch_attend(const EoqLaunch& L, eoq_packed values, int64_t n_seq, int n_kv_heads,
                              int64_t blocks_per_head, int64_t block_capacity, const float* weights,
-                             int64_t weight_stride, int n_q_heads, float* out, float* partial);
+                             int64_t weight_stride, int n_q_heads, float* out, float* partial,
+                             const void* tail_fp16 = nullptr, int64_t tail_capacity = 0, int tail_len = 0);
 hipError_t eoq_launch_softmax(const EoqLaunch& L, float* x, int64_t rows, int64_t len, int64_t stride);
 
 // TQ_prod side information of stored records and scores with the correction of Eq. (qjl)

@@ -19,7 +19,7 @@ FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE = 1, 2, 4
 
 EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_projection",
            "eoq_codebook", "eoq_qjl_encode", "eoq_scores_prod",
-           "eoq_compress", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_softmax", "eoq_attend_workspace_bytes", "eoq_attend", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
+           "eoq_compress", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_softmax", "eoq_attend_workspace_bytes", "eoq_attend", "eoq_attend_stream", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
 
 
 class EoqError(RuntimeError):
@@ -102,6 +102,10 @@ def lib():
         L.eoq_attend.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_int, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
                                  C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.eoq_attend.restype = C.c_int
+        L.eoq_attend_stream.argtypes = [C.c_void_p, _Packed, C.c_int64, C.c_int, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
+                                        C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
+                                        C.c_void_p]
+        L.eoq_attend_stream.restype = C.c_int
         L.eoq_set_solver.argtypes = [C.c_void_p, C.c_int]
         L.eoq_set_solver.restype = C.c_int
         L.eoq_profile.argtypes = [C.c_void_p, C.c_int]
@@ -392,6 +396,29 @@ class Context:
         self._check(lib().eoq_attend(self._h, values.c_struct(), n_seq, n_kv_heads, block_capacity, blocks_filled,
                                      weights.data_ptr(), stride, n_q_heads, out.data_ptr(), workspace.data_ptr(),
                                      workspace.numel(), _stream_ptr(weights.device)))
+        return out
+
+    def eoq_attend_stream(self, values: Packed, weights: torch.Tensor, n_kv_heads: int, block_capacity: int,
+                          blocks_filled: int, tail: torch.Tensor | None, tail_len: int, out: torch.Tensor | None = None,
+                          workspace: torch.Tensor | None = None) -> torch.Tensor:
+        """eoq_attend plus the float16 tail values [n_seq, n_kv_heads, tail_capacity, d] (weights behind the blocks')."""
+        assert weights.is_cuda and weights.is_contiguous() and weights.dtype == torch.float32
+        n_seq, n_q_heads, stride = weights.shape
+        assert values.rank.shape[0] >= n_seq * n_kv_heads * block_capacity
+        tail_cap = 0
+        if tail is not None:
+            assert tail.is_cuda and tail.is_contiguous() and tail.dtype == torch.float16
+            assert tail.shape[0] == n_seq and tail.shape[1] == n_kv_heads and tail.shape[3] == self.d
+            tail_cap = tail.shape[2]
+        if out is None:
+            out = torch.empty(n_seq, n_q_heads, self.d, dtype=torch.float32, device=weights.device)
+        if workspace is None:
+            need = self.eoq_attend_workspace_bytes(n_seq, n_kv_heads, blocks_filled)
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=weights.device)
+        self._check(lib().eoq_attend_stream(self._h, values.c_struct(), n_seq, n_kv_heads, block_capacity, blocks_filled,
+                                            tail.data_ptr() if tail is not None else None, tail_cap, tail_len,
+                                            weights.data_ptr(), stride, n_q_heads, out.data_ptr(), workspace.data_ptr(),
+                                            workspace.numel(), _stream_ptr(weights.device)))
         return out
 
     def eoq_set_solver(self, solver: int):

@@ -901,3 +901,99 @@ def test_prefill_chunk_in_the_bench_launch_configuration():
     want_tail = torch.einsum("ghd,gtd->ght", q.view(H, 4, 128).double(), tail.view(H, 64, 128).double()) / math.sqrt(128.0)
     got_tail = sc[0, :, (slot + 1) * n:].view(H, 4, 64).double()
     assert float((got_tail - want_tail).abs().max()) <= 1e-5 * max(1.0, float(want_tail.abs().max()))
+
+
+def test_streaming_decode_step_scores_softmax_attend_with_tails():
+    """A decode step over a partly filled cache: keys and values as oracle records in stores of 5 slots per head with 3
+    filled, 41 uncompressed tail tokens each: eoq_scores_stream -> eoq_softmax over the valid part of the rows ->
+    eoq_attend_stream, against the same chain in the oracle."""
+    n_seq, n_kv, group, cap, filled, tail_len, tail_cap, n, bits = 2, 2, 4, 5, 3, 41, 48, 128, 2
+    heads = n_seq * n_kv
+    kspec = synth.BlockSpec("dk", n=n, n_tensors=heads, blocks_per_tensor=filled, rank_lo=1, rank_hi=5)
+    vspec = synth.BlockSpec("dv", n=n, n_tensors=heads, blocks_per_tensor=filled, rank_lo=1, rank_hi=5)
+    kb, _ = synth.make_blocks(kspec, seed=1)
+    vb, _ = synth.make_blocks(vspec, seed=2)
+    Pi, cb = U.oracle_tables(bits)
+    krecs = U.oracle_compress(kb.double().numpy(), bits)
+    vrecs = U.oracle_compress(vb.double().numpy(), bits)
+    slots = torch.as_tensor([t * cap + c for t in range(heads) for c in range(filled)], device=DEV)
+
+    def to_store(recs):
+        dense = U.records_to_packed(recs, 32, DEV)
+        st = eoq.Packed.empty(heads * cap, n, 128, bits, 32, DEV)
+        for f in _FIELDS:
+            getattr(st, f).zero_()
+            getattr(st, f).index_copy_(0, slots, getattr(dense, f))
+        return st
+
+    kstore, vstore = to_store(krecs), to_store(vrecs)
+    gen = torch.Generator().manual_seed(4)
+    ktail = torch.randn(n_seq, n_kv, tail_cap, 128, generator=gen).to(torch.float16)
+    vtail = torch.randn(n_seq, n_kv, tail_cap, 128, generator=gen).to(torch.float16)
+    q = synth.make_queries(n_seq, n_kv * group)
+    ctx = eoq.Context(n=n, bits=bits)
+    T = filled * n + tail_len
+    rows = torch.full((n_seq, n_kv * group, T + 4), 3.0, dtype=torch.float32, device=DEV)   # stride a multiple of 4
+    ctx.eoq_scores_stream(kstore, q.to(DEV), n_kv, cap, filled, ktail.to(DEV), tail_len, rows)
+    ctx.eoq_softmax(rows, T)
+    out = ctx.eoq_attend_stream(vstore, rows, n_kv, cap, filled, vtail.to(DEV), tail_len)
+    torch.cuda.synchronize()
+    assert bool((rows[..., T:] == 3.0).all())
+    got = out.double().cpu().numpy()
+    q64 = q.double().numpy()
+    for s in range(n_seq):
+        for g in range(n_kv):
+            h0 = (s * n_kv + g) * filled
+            qs = q64[s, g * group:(g + 1) * group]
+            lo = oracle.score_stream(qs, krecs[h0:h0 + filled], ktail[s, g, :tail_len].double().numpy(), Pi, cb)
+            w = oracle.softmax_rows(lo)
+            want = oracle.attend_stream(w, vrecs[h0:h0 + filled], vtail[s, g, :tail_len].double().numpy(), Pi, cb)
+            assert np.max(np.abs(got[s, g * group:(g + 1) * group] - want)) <= 1e-4 * max(np.max(np.abs(want)), 1e-3), (s, g)
+            have_w = rows[s, g * group:(g + 1) * group, :T].double().cpu().numpy()
+            assert np.max(np.abs(have_w - w)) <= 1e-4 * np.max(w), (s, g)
+
+
+def test_hot_calls_replay_from_a_captured_graph():
+    """The hot calls allocate nothing and never synchronise, so a whole step can be captured once and replayed: compress,
+    decompress, scores, softmax, attention output of a small batch in one graph, replayed three times with new inputs
+    copied in between and other work on the device in between; every replay equals the eager result bit for bit."""
+    spec = synth.BlockSpec("graph", n=128, n_tensors=4, blocks_per_tensor=4, rank_lo=1, rank_hi=5)
+    ctx = eoq.Context(n=128, bits=2)
+    B, n_kv, group = 16, 4, 2
+    blocks = torch.empty(B, 128, 128, dtype=torch.float16, device=DEV)
+    rec = eoq.Packed.empty(B, 128, 128, 2, 32, DEV)
+    ws = torch.empty(ctx.eoq_workspace_bytes(B), dtype=torch.uint8, device=DEV)
+    xhat = torch.empty(B, 128, 128, dtype=torch.float16, device=DEV)
+    q = synth.make_queries(1, n_kv * group, device=DEV)
+    sc = torch.empty(1, n_kv * group, 4 * 128, dtype=torch.float32, device=DEV)
+    att = torch.empty(1, n_kv * group, 128, dtype=torch.float32, device=DEV)
+    aws = torch.empty(max(ctx.eoq_attend_workspace_bytes(1, n_kv, 4), 16), dtype=torch.uint8, device=DEV)
+
+    def step():
+        ctx.eoq_compress(blocks, rec, ws)
+        ctx.eoq_decompress(rec, xhat)
+        ctx.eoq_scores(rec, q, n_kv, sc)
+        ctx.eoq_softmax(sc)
+        ctx.eoq_attend(rec, sc, n_kv, 4, 4, att, aws)
+
+    first, _ = synth.make_blocks(spec, seed=10, device=DEV)
+    blocks.copy_(first)
+    step()                                   # eager warm-up (loads the code objects before the capture)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for seed in (11, 12, 13):
+        new, _ = synth.make_blocks(spec, seed=seed, device=DEV)
+        blocks.copy_(new)
+        step()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (rec.codes, rec.norms.view(torch.int16), rec.rank, xhat.view(torch.int16), sc, att)]
+        for t in (rec.codes, rec.norms, xhat, sc, att):
+            t.zero_()
+        (torch.randn(512, 512, device=DEV) @ torch.randn(512, 512, device=DEV)).sum().item()   # unrelated eager work
+        graph.replay()
+        torch.cuda.synchronize()
+        have = (rec.codes, rec.norms.view(torch.int16), rec.rank, xhat.view(torch.int16), sc, att)
+        for a, b in zip(have, want):
+            assert torch.equal(a, b), seed

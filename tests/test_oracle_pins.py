@@ -711,3 +711,17 @@ def test_qjl_record_definition_and_packing():
     q = rng.standard_normal((2, 128))
     z = oracle.QjlRecord(np.ones((1, 128), np.uint8), np.zeros(1))
     assert not np.any(oracle.qjl_correction(q, z, Phi))
+
+
+def test_attend_stream_is_attention_over_the_concatenated_values():
+    rng = np.random.default_rng(8)
+    Pi = oracle.haar_rotation(128, 9)
+    cb = oracle.lloyd_max_gaussian(2)
+    recs = [oracle.compress_block(rng.standard_normal((128, 128)), Pi, cb) for _ in range(2)]
+    tail = rng.standard_normal((19, 128))
+    w = oracle.softmax_rows(rng.standard_normal((3, 256 + 19)))
+    vals = np.concatenate([oracle.decompress_block(r, Pi, cb) for r in recs] + [tail])
+    assert np.allclose(oracle.attend_stream(w, recs, tail, Pi, cb), w @ vals, rtol=0, atol=1e-13)
+    assert np.allclose(oracle.attend_stream(w[:, 256:], [], tail, Pi, cb), w[:, 256:] @ tail, rtol=0, atol=1e-14)
+    with pytest.raises(ValueError):
+        oracle.attend_stream(w[:, :-1], recs, tail, Pi, cb)
