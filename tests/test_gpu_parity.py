@@ -997,3 +997,50 @@ def test_hot_calls_replay_from_a_captured_graph():
         have = (rec.codes, rec.norms.view(torch.int16), rec.rank, xhat.view(torch.int16), sc, att)
         for a, b in zip(have, want):
             assert torch.equal(a, b), seed
+
+
+def test_maximum_block_length_through_every_call():
+    """n = 4096 (the longest block the library takes), r_max = 8 so that the 4-bit factor table is at its limit
+    n * r_max = 32768: compress (both factor formats), decompress, scores, TQ_prod side information and the attention
+    output against the oracle."""
+    n, bits, r_max, B = 4096, 2, 8, 2
+    spec = synth.BlockSpec("long", n=n, n_tensors=1, blocks_per_tensor=B, rank_lo=3, rank_hi=6)
+    blocks, _ = synth.make_blocks(spec, seed=4096)
+    b64 = blocks.double().numpy()
+    Pi, cb = U.oracle_tables(bits)
+    ctx = eoq.Context(n=n, bits=bits, r_max=r_max)
+    dev_blocks = blocks.to(DEV).contiguous()
+    for fb in (16, 4):
+        recs = U.oracle_compress(b64, bits, r_max=r_max, factor_bits=fb, workers=1)
+        if fb == 16:
+            rec, ws = ctx.eoq_compress(dev_blocks)
+        else:
+            rec, fq, ws = ctx.eoq_compress_q4(dev_blocks)
+        torch.cuda.synchronize()
+        lam = ctx.spectrum(ws, B).cpu().numpy()
+        U.compare_compress(b64, rec, lam, recs, bits, r_max=r_max, lowrank_tol=5e-3 if fb == 16 else float("inf"))
+        if fb == 4:
+            U.compare_factor_codes(rec, fq, recs)
+        _recon_agreement(ctx, rec, b64, recs, bits)
+    # readers on oracle records of this length
+    recs = U.oracle_compress(b64, bits, r_max=r_max, workers=1)
+    packed = U.records_to_packed(recs, r_max, DEV)
+    q = synth.make_queries(1, 4)
+    sg = ctx.eoq_scores(packed, q.to(DEV), n_kv_heads=1)
+    Phi = ctx.eoq_projection().astype(np.float64)
+    qj = ctx.eoq_qjl_encode(dev_blocks, packed)
+    gen = torch.Generator().manual_seed(1)
+    w = torch.softmax(torch.randn(1, 4, B * n, generator=gen).double() * 2.0, dim=-1).float()
+    att = ctx.eoq_attend(packed, w.to(DEV), 1)
+    torch.cuda.synchronize()
+    q64 = q.double().numpy()[0]
+    so = np.concatenate([oracle.score_block(q64, r, Pi, cb) for r in recs], axis=-1)
+    assert np.max(np.abs(sg[0].double().cpu().numpy() - so)) <= 1e-5 * max(1.0, np.max(np.abs(so)))
+    ao = oracle.attend_blocks(w[0].double().numpy(), recs, Pi, cb)
+    assert np.max(np.abs(att[0].double().cpu().numpy() - ao)) <= 2e-5 * max(np.max(np.abs(ao)), 1e-3)
+    bad = 0
+    for b, r in enumerate(recs):
+        oq = oracle.qjl_encode(b64[b], r, Pi, cb, Phi)
+        bad += int((oracle.unpack_signs(qj.signs[b].cpu().numpy(), 128) != oq.signs).sum())
+        assert np.all(np.abs(qj.norms[b].double().cpu().numpy() - oq.gamma16) <= np.spacing(oq.gamma16.astype(np.float16)).astype(np.float64))
+    assert bad <= 1e-3 * B * n * 128
