@@ -501,10 +501,67 @@ __global__ __launch_bounds__(THREADS, 1) void eoq_qjl_kernel(
 // ---------------------------------------------------------------------------------------------
 typedef float float4v __attribute__((ext_vector_type(4)));
 constexpr int SC_MAXG = 8;
+constexpr int SC_DEPTH = 2;     // passes of record bytes in flight per wave
 constexpr int SC_RUN_MAX = 16;  // most blocks per workgroup (the run is shortened until the grid fills the chip)
 
 __device__ __forceinline__ float4v mfma32(const H8& a, const H8& b, float4v c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c, 0, 0, 0);
+}
+
+// out[h][c] = sum_j table[c][j] q[h][j] for the heads of one group (rows above the group are zero), the table given as
+// binary16 hi + lo parts [c][j]: the query side of the rotation (<q, Pi^T z> = <Pi q, z>) and of the projection Phi q.
+// q is binary16, so every product is exact; 16 matrix instructions and 20 sixteen-byte loads per wave, all in flight
+// together.  `out` is LDS, [SC_MAXG][D]; the caller synchronises.
+__device__ __forceinline__ void rotate_query(const uint16_t* __restrict__ tab_hi, const uint16_t* __restrict__ tab_lo,
+                                             const uint16_t* __restrict__ qg, int group, float* out, int wave, int l16,
+                                             int g) {
+  H8 a[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    a[ks].u = (l16 < group) ? *reinterpret_cast<const uint4*>(qg + l16 * D + 32 * ks + 8 * g) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    const int c = 16 * (2 * wave + tt) + l16;
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      H8 bh, bl;
+      bh.u = *reinterpret_cast<const uint4*>(tab_hi + c * D + 32 * ks + 8 * g);
+      bl.u = *reinterpret_cast<const uint4*>(tab_lo + c * D + 32 * ks + 8 * g);
+      acc = mfma32(a[ks], bh, acc);
+      acc = mfma32(a[ks], bl, acc);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+      if (4 * g + v < SC_MAXG) out[(4 * g + v) * D + c] = acc[v];
+  }
+}
+
+// What a lane requests of one pass of the scores kernel: for its token of each of the two tiles the 32-bit word g of
+// every bit-plane and the stored norm (with QJL also the sign word and the residual norm).
+template <int BITS, bool QJL>
+struct ScoreFetch {
+  uint32_t word[2][BITS];
+  uint16_t rho[2];
+  uint32_t sword[2];
+  uint16_t gam[2];
+};
+template <int BITS, bool QJL>
+__device__ __forceinline__ void score_fetch(ScoreFetch<BITS, QJL>& f, size_t blk, int n, int tile, int l16, int g,
+                                            const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
+                                            const uint8_t* __restrict__ qsigns, const uint16_t* __restrict__ qnorms) {
+  constexpr int ROWB = BITS * D / 8;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const size_t tok = blk * (size_t)n + 16 * (tile + u * (THREADS / 64)) + l16;
+#pragma unroll
+    for (int p = 0; p < BITS; ++p) f.word[u][p] = *reinterpret_cast<const uint32_t*>(codes + tok * ROWB + p * 16 + 4 * g);
+    f.rho[u] = norms[tok];
+    if constexpr (QJL) {
+      f.sword[u] = *reinterpret_cast<const uint32_t*>(qsigns + tok * (D / 8) + 4 * g);
+      f.gam[u] = qnorms[tok];
+    }
+  }
 }
 
 // QJL: the logits get the correction of Eq. (qjl), |r_x| sqrt(pi/2)/d <Phi q, sign(Phi r_x)>, from one more bit-plane
@@ -512,14 +569,15 @@ __device__ __forceinline__ float4v mfma32(const H8& a, const H8& b, float4v c) {
 template <int BITS, bool QJL>
 __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
     int n, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, int64_t block_capacity, int64_t score_stride,
-    int run, const float* __restrict__ pit,
+    int run, const uint16_t* __restrict__ pih,
     const float* __restrict__ tab, const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
     const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac,
-    const uint16_t* __restrict__ q, float* __restrict__ scores, const float* __restrict__ phit,
+    const uint16_t* __restrict__ q, float* __restrict__ scores, const uint16_t* __restrict__ phih,
     const uint8_t* __restrict__ qsigns, const uint16_t* __restrict__ qnorms) {
   __shared__ float qraw[SC_MAXG * D];
   __shared__ float qrot[SC_MAXG * D];
-  __shared__ float wbuf[SC_MAXG * EOQ_RMAX_CAP];
+  __shared__ __align__(16) float wbuf[SC_RUN_MAX * EOQ_RMAX_CAP * SC_MAXG];   // [block of the run][component][head]: <v_i, q_h>
+  __shared__ int rank_s[SC_RUN_MAX];
   __shared__ __align__(16) uint4 mask_tab[256];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -534,15 +592,10 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   build_mask_table(mask_tab, tid);
   Mags<BITS> mg;
   mg.load(tab);
-  for (int e = tid; e < group * D; e += THREADS) qraw[e] = half_bits_to_float(q[q0 + e]);
+  for (int e = tid; e < SC_MAXG * D; e += THREADS) qraw[e] = (e < group * D) ? half_bits_to_float(q[q0 + e]) : 0.0f;
   __syncthreads();
   // q' = Pi q (the rotation moved to the query side: <q, Pi^T z> = <Pi q, z>)
-  for (int e = tid; e < group * D; e += THREADS) {
-    const int h = e >> 7, c = e & (D - 1);
-    float acc = 0.0f;
-    for (int j = 0; j < D; ++j) acc = fmaf(pit[j * D + c], qraw[h * D + j], acc);
-    qrot[e] = acc;
-  }
+  rotate_query(pih, pih + D * D, q + q0, group, qrot, wave, l16, g);
   __syncthreads();
   H8 Aq_hi[4], Aq_lo[4];
 #pragma unroll
@@ -555,12 +608,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   H8 Ap_hi[QJL ? 4 : 1], Ap_lo[QJL ? 4 : 1];
   if constexpr (QJL) {
     __syncthreads();  // qrot has been read: reuse it for Phi q
-    for (int e = tid; e < group * D; e += THREADS) {
-      const int h = e >> 7, i = e & (D - 1);
-      float acc = 0.0f;
-      for (int j = 0; j < D; ++j) acc = fmaf(phit[j * D + i], qraw[h * D + j], acc);
-      qrot[e] = acc;
-    }
+    rotate_query(phih, phih + D * D, q + q0, group, qrot, wave, l16, g);
     __syncthreads();
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
@@ -571,57 +619,145 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
       }
   }
   const float qjl_scale = sqrtf(1.5707963267948966f) / (float)D;
+  // inner positive centroid and the step to the outer one (tab: 2^BITS ascending centroids of N(0,1))
+  const float cent_in = tab[(1 << BITS) / 2];
+  const float cent_step = (BITS >= 2) ? tab[(1 << BITS) / 2 + 1] - tab[(1 << BITS) / 2] : 0.0f;
 
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
-  const int64_t j_end = min((int64_t)(blockIdx.x + 1) * run, blocks_per_head);
-  for (int64_t jb = (int64_t)blockIdx.x * run; jb < j_end; ++jb) {
-    const size_t blk = sg * (size_t)block_capacity + jb;   // the store holds block_capacity slots per head
-    const int r = min(max(rank_in[blk], 0), r_max);   // records may come from storage: never index past r_max rows
-    __syncthreads();
-    // w[h][i] = <v_i, q_h>: the low-rank term is <C_t, w_h>
-    for (int e = tid; e < group * r; e += THREADS) {
-      const int h = e / r, i = e % r;
-      float acc = 0.0f;
-      for (int j = 0; j < D; ++j)
-        acc = fmaf(half_bits_to_float(rfac[(blk * r_max + i) * D + j]), qraw[h * D + j], acc);
-      wbuf[h * EOQ_RMAX_CAP + i] = acc;
+  // The work of this workgroup as a flat list of passes: pass p covers two tiles of 16 tokens per wave (tiles
+  // wave + 8 q and wave + 8 q + 4 of block jb0 + p / ppb, q = p % ppb).  The record bytes of a pass are requested
+  // SC_DEPTH passes ahead into a ring of registers (the loop is unrolled over the ring, so nothing is copied and a pass
+  // only waits for its own bytes), the stored coefficients one pass ahead.
+  const int64_t jb0 = (int64_t)blockIdx.x * run;
+  const int nblk = (int)(min(jb0 + run, blocks_per_head) - jb0);
+  const int ppb = n / 128;
+  const int P = nblk * ppb;
+  const size_t blk0 = sg * (size_t)block_capacity + jb0;   // the store holds block_capacity slots per head
+
+  // w[b][i][h] = <v_i, q_h> of every block of the run, up front (the low-rank term is <C_t, w_h>): all loads of the
+  // set-up are in flight together and the pass loop below has no barrier.  16 lanes per (component, head): one
+  // 16-byte load of eight entries of v_i each, then a sum over the DPP row.
+  if (tid < nblk) rank_s[tid] = min(max(rank_in[blk0 + tid], 0), r_max);   // records may come from storage: never index past r_max rows
+  __syncthreads();
+  int rtop = 0;
+  for (int b = 0; b < nblk; ++b) rtop = max(rtop, rank_s[b]);
+  for (int e0 = 0; e0 < nblk * rtop * (SC_MAXG * 16); e0 += THREADS) {   // uniform trip count: whole rows reduce together
+    const int e = e0 + tid;
+    const int seg = e & 15, h = (e >> 4) & (SC_MAXG - 1);
+    const int bi = e >> 7, b = bi / rtop, i = bi - b * rtop;
+    const int rb = rank_s[min(b, nblk - 1)];
+    float acc = 0.0f;
+    if (b < nblk && i < rb) {
+      float v[8];
+      load8(rfac, EOQ_F16, ((blk0 + b) * r_max + i) * (size_t)D + 8 * seg, v);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) acc = fmaf(v[x], qraw[h * D + 8 * seg + x], acc);
     }
-    __syncthreads();
-    H8 Aw_hi, Aw_lo;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int i = 8 * g + e;
-      const float v = (l16 < group && i < r) ? wbuf[l16 * EOQ_RMAX_CAP + i] : 0.0f;
-      split_half(v, Aw_hi.s[e], Aw_lo.s[e]);
+    acc += dpp_mov<0xB1>(acc);
+    acc += dpp_mov<0x4E>(acc);
+    acc += dpp_mov<0x141>(acc);
+    acc += dpp_mov<0x140>(acc);
+    if (seg == 0 && b < nblk && i < rb) wbuf[(b * EOQ_RMAX_CAP + i) * SC_MAXG + h] = acc;
+  }
+  __syncthreads();
+
+  ScoreFetch<BITS, QJL> ring[SC_DEPTH];
+  uint16_t cbr[2][2][4];   // [parity of the pass][tile][component of the group of four]
+  int fb = 0, fq = 0;      // block and pass-in-block of the next pass to request
+  auto request = [&](ScoreFetch<BITS, QJL>& f) __attribute__((always_inline)) {
+    score_fetch<BITS, QJL>(f, blk0 + fb, n, wave + 8 * fq, l16, g, codes, norms, qsigns, qnorms);
+    if (++fq == ppb) {
+      fq = 0;
+      ++fb;
     }
-    // two tiles of 16 tokens per pass (n / 16 is a multiple of 8): their loads are issued together and their
-    // accumulator chains are independent
-    for (int tile = wave; tile < n / 16; tile += 2 * (THREADS / 64)) {
-      uint32_t word[2][BITS];
-      uint32_t sword[2] = {0u, 0u};
-      float gam[2] = {0.0f, 0.0f};
-      H8 c[2];
-      float rho[2];
+  };
+  // coefficients C[i][token] of the first four components of pass (cb_b, cb_q); row 0 is read when the rank is 0
+  auto request_cb = [&](uint16_t (&cb)[2][4], int cb_b, int cb_q) __attribute__((always_inline)) {
+    const size_t bk = blk0 + cb_b;
+    const int rr = max(rank_s[cb_b], 1);
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int t = 16 * (tile + u * (THREADS / 64)) + l16;
-        const size_t tok = blk * (size_t)n + t;
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int p = 0; p < BITS; ++p) word[u][p] = *reinterpret_cast<const uint32_t*>(codes + tok * ROWB + p * 16 + 4 * g);
-        if constexpr (QJL) {
-          sword[u] = *reinterpret_cast<const uint32_t*>(qsigns + tok * (D / 8) + 4 * g);
-          gam[u] = half_bits_to_float(qnorms[tok]) * qjl_scale;
-        }
-        if (r > 0) {
+      for (int a = 0; a < 4; ++a)
+        cb[u][a] = lfac[(bk * r_max + min(a, rr - 1)) * (size_t)n + 16 * (wave + 8 * cb_q + 4 * u) + l16];
+  };
+  if (P > 0) request_cb(cbr[0], 0, 0);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int i = 8 * g + e;
-            c[u].s[e] = (i < r) ? lfac[(blk * r_max + i) * (size_t)n + t] : (uint16_t)0;
+  for (int dd = 0; dd < SC_DEPTH; ++dd)
+    if (dd < P) request(ring[dd]);
+
+  int cb_blk = 0, cq = 0;   // block and pass-in-block of the pass being worked on
+  int r = 0;
+  size_t blk = blk0;
+  const float* wrow = wbuf;
+  auto work = [&](ScoreFetch<BITS, QJL>& cur, uint16_t (&cb)[2][4], uint16_t (&cbn)[2][4], bool more) __attribute__((always_inline)) {
+    if (cq == 0) {
+      blk = blk0 + cb_blk;
+      r = rank_s[cb_blk];
+      wrow = wbuf + cb_blk * (EOQ_RMAX_CAP * SC_MAXG);
+    }
+    const int tile = wave + 8 * cq;
+    const int64_t jb = jb0 + cb_blk;
+    // the coefficients of the next pass go out before this pass's matrix products
+    {
+      int nb = cb_blk, nq = cq + 1;
+      if (nq == ppb) {
+        nq = 0;
+        ++nb;
+      }
+      if (more) request_cb(cbn, nb, nq);
+    }
+    uint32_t word[2][BITS];
+    uint32_t sword[2] = {0u, 0u};
+    float gam[2] = {0.0f, 0.0f};
+    float rho[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+      for (int p = 0; p < BITS; ++p) word[u][p] = cur.word[u][p];
+      rho[u] = half_bits_to_float(cur.rho[u]) * inv_sqrt_d;
+      if constexpr (QJL) {
+        sword[u] = cur.sword[u];
+        gam[u] = half_bits_to_float(cur.gam[u]) * qjl_scale;
+      }
+    }
+    float4v acc1[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    if constexpr (BITS <= 2) {
+      // The codebook is symmetric: centroid = s (c_0 + (c_1 - c_0) m) with s = +-1 from the top plane and m = 1 on
+      // the outer level.  <q', z_hat> = c_0 <q', s> + (c_1 - c_0) <q', s m>: the operands +-1 and 0 are exact in
+      // binary16 and cost two logic operations per register instead of a centroid selection with a low part.
+      float4v accS[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, accT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        H8 sg2[2], tm[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          H8 top, low;
+          top.u = mask_tab[(word[u][BITS - 1] >> (8 * kk)) & 0xFFu];
+          if constexpr (BITS == 2) low.u = mask_tab[(word[u][0] >> (8 * kk)) & 0xFFu];
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            sg2[u].w[w] = (top.w[w] & 0x80008000u) ^ 0xBC00BC00u;          // plane bit set: +1.0, clear: -1.0
+            if constexpr (BITS == 2) tm[u].w[w] = sg2[u].w[w] & ~(low.w[w] ^ top.w[w]);   // outer level only
           }
         }
-        rho[u] = half_bits_to_float(norms[tok]) * inv_sqrt_d;
+        accS[0] = mfma32(Aq_hi[kk], sg2[0], accS[0]);
+        accS[1] = mfma32(Aq_hi[kk], sg2[1], accS[1]);
+        accS[0] = mfma32(Aq_lo[kk], sg2[0], accS[0]);
+        accS[1] = mfma32(Aq_lo[kk], sg2[1], accS[1]);
+        if constexpr (BITS == 2) {
+          accT[0] = mfma32(Aq_hi[kk], tm[0], accT[0]);
+          accT[1] = mfma32(Aq_hi[kk], tm[1], accT[1]);
+          accT[0] = mfma32(Aq_lo[kk], tm[0], accT[0]);
+          accT[1] = mfma32(Aq_lo[kk], tm[1], accT[1]);
+        }
       }
-      float4v acc1[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+      const float c0 = cent_in, dc = cent_step;
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc1[u][v] = (BITS == 2) ? fmaf(dc, accT[u][v], c0 * accS[u][v]) : c0 * accS[u][v];
+    } else {
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         H8 bhi[2], blo[2];
@@ -639,43 +775,82 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
         acc1[0] = mfma32(Aq_hi[kk], blo[0], acc1[0]);
         acc1[1] = mfma32(Aq_hi[kk], blo[1], acc1[1]);
       }
-      if (r > 0) {
-        acc2[0] = mfma32(Aw_hi, c[0], acc2[0]);
-        acc2[1] = mfma32(Aw_hi, c[1], acc2[1]);
-        acc2[0] = mfma32(Aw_lo, c[0], acc2[0]);
-        acc2[1] = mfma32(Aw_lo, c[1], acc2[1]);
-      }
-      if constexpr (QJL) {
-        float4v acc3[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            H8 m, sg;
-            m.u = mask_tab[(sword[u] >> (8 * kk)) & 0xFFu];
-#pragma unroll
-            for (int w = 0; w < 4; ++w) sg.w[w] = (m.w[w] & 0x80008000u) ^ 0xBC00BC00u;   // bit set: +1.0, clear: -1.0
-            acc3[u] = mfma32(Ap_hi[kk], sg, acc3[u]);
-            acc3[u] = mfma32(Ap_lo[kk], sg, acc3[u]);
-          }
-        }
+    }
+    // low-rank term on the vector ALU: lane (token, g) has C[i][token] and reads w[i][heads 4g .. 4g+3]
+    if (r > 0) {
+      for (int i0 = 0; i0 < r; i0 += 4) {
+        uint16_t cx[2][4];
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) acc2[u][v] = fmaf(acc3[u][v], gam[u], acc2[u][v]);
-      }
+          for (int a = 0; a < 4; ++a)
+            cx[u][a] = (i0 == 0) ? cb[u][a]
+                                 : lfac[(blk * r_max + min(i0 + a, r - 1)) * (size_t)n + 16 * (tile + 4 * u) + l16];
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int t = 16 * (tile + u * (THREADS / 64)) + l16;
+        for (int a = 0; a < 4; ++a) {
+          float4 w = *reinterpret_cast<const float4*>(wrow + min(i0 + a, r - 1) * SC_MAXG + 4 * g);
+          if (i0 + a >= r) w = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int h = 4 * g + v;
-          if (h < group)
-            scores[(sq * n_q_heads + kv * group + h) * T + (size_t)jb * n + t] = fmaf(acc1[u][v], rho[u], acc2[u][v]) * inv_sqrt_d;
+          for (int u = 0; u < 2; ++u) {
+            const float cv = half_bits_to_float(cx[u][a]);
+            acc2[u][0] = fmaf(w.x, cv, acc2[u][0]);
+            acc2[u][1] = fmaf(w.y, cv, acc2[u][1]);
+            acc2[u][2] = fmaf(w.z, cv, acc2[u][2]);
+            acc2[u][3] = fmaf(w.w, cv, acc2[u][3]);
+          }
         }
       }
     }
+    if constexpr (QJL) {
+      float4v acc3[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          H8 m, sgn;
+          m.u = mask_tab[(sword[u] >> (8 * kk)) & 0xFFu];
+#pragma unroll
+          for (int w = 0; w < 4; ++w) sgn.w[w] = (m.w[w] & 0x80008000u) ^ 0xBC00BC00u;   // bit set: +1.0, clear: -1.0
+          acc3[u] = mfma32(Ap_hi[kk], sgn, acc3[u]);
+          acc3[u] = mfma32(Ap_lo[kk], sgn, acc3[u]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc2[u][v] = fmaf(acc3[u][v], gam[u], acc2[u][v]);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int t = 16 * (tile + 4 * u) + l16;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int h = 4 * g + v;
+        if (h < group)
+          scores[(sq * n_q_heads + kv * group + h) * T + (size_t)jb * n + t] = fmaf(acc1[u][v], rho[u], acc2[u][v]) * inv_sqrt_d;
+      }
+    }
+    if (++cq == ppb) {
+      cq = 0;
+      ++cb_blk;
+    }
+  };
+
+  // the ring has SC_DEPTH stages and the coefficient buffers two: the loop is unrolled over 2 * SC_DEPTH passes
+  static_assert(SC_DEPTH == 2, "the stages below are written out for a ring of two");
+#define EOQ_SC_STAGE(dd)                                                                       \
+  {                                                                                            \
+    const int p = p0 + dd;                                                                     \
+    if (p < P) {                                                                               \
+      work(ring[dd % SC_DEPTH], cbr[dd & 1], cbr[(dd + 1) & 1], p + 1 < P);                    \
+      if (p + SC_DEPTH < P) request(ring[dd % SC_DEPTH]);                                      \
+    }                                                                                          \
   }
+  for (int p0 = 0; p0 < P; p0 += SC_DEPTH) {
+    EOQ_SC_STAGE(0)
+    EOQ_SC_STAGE(1)
+  }
+#undef EOQ_SC_STAGE
 }
 
 // Scores of the uncompressed tail (the newest tokens of every head, binary16, not yet a full block):
@@ -986,14 +1161,14 @@ hipError_t launch_scores_impl(const EoqLaunch& L, eoq_packed keys, const eoq_qjl
   do {                                                                                                              \
     if (qjl)                                                                                                        \
       hipLaunchKernelGGL((eoq_scores_mfma_kernel<BITS, true>), grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads,  \
-                         n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pit,    \
-                         L.tab, keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, q, scores, L.phit,         \
+                         n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pih,    \
+                         L.tab, keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, q, scores, L.phih,         \
                          qjl->signs, qjl->norms);                                                                   \
     else                                                                                                            \
       hipLaunchKernelGGL((eoq_scores_mfma_kernel<BITS, false>), grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads, \
-                         n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pit,    \
+                         n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pih,    \
                          L.tab, keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, q, scores,                 \
-                         (const float*)nullptr, (const uint8_t*)nullptr, (const uint16_t*)nullptr);                 \
+                         (const uint16_t*)nullptr, (const uint8_t*)nullptr, (const uint16_t*)nullptr);              \
   } while (0)
   switch (L.bits) {
     case 1: EOQ_SCORES(1); break;
