@@ -21,7 +21,8 @@ constexpr int CHUNK = 128;   // tokens staged per pass (n is a multiple of 128)
 
 // One workgroup: blocks [blockIdx.x * run, ...) of (sequence, KV head) blockIdx.y.  Lane (c, th) = (tid % 128,
 // tid / 128) owns coordinate c and the tokens of parity-half th of every chunk.
-template <int BITS>
+// GH: heads accumulated per lane (4 when the group has at most four query heads: half the multiply-adds and LDS reads).
+template <int BITS, int GH>
 __global__ __launch_bounds__(THREADS) void eoq_attend_partial_kernel(
     int n, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, int64_t block_capacity, int64_t weight_stride,
     int run, const float* __restrict__ tab, const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
@@ -44,9 +45,9 @@ __global__ __launch_bounds__(THREADS) void eoq_attend_partial_kernel(
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   if (tid < (1 << BITS)) cent_s[tid] = tab[tid];
 
-  float rot[MAXG], lin[MAXG];
+  float rot[GH], lin[GH];
 #pragma unroll
-  for (int h = 0; h < MAXG; ++h) rot[h] = lin[h] = 0.0f;
+  for (int h = 0; h < GH; ++h) rot[h] = lin[h] = 0.0f;
 
   const int64_t j_end = min((int64_t)(blockIdx.x + 1) * run, blocks_per_head);
   for (int64_t jb = (int64_t)blockIdx.x * run; jb < j_end; ++jb) {
@@ -90,15 +91,17 @@ __global__ __launch_bounds__(THREADS) void eoq_attend_partial_kernel(
         }
         const float cv = cent_s[idx];
         const float4 wa = *reinterpret_cast<const float4*>(wr_s + t * MAXG);
-        const float4 wb = *reinterpret_cast<const float4*>(wr_s + t * MAXG + 4);
         rot[0] = fmaf(wa.x, cv, rot[0]);
         rot[1] = fmaf(wa.y, cv, rot[1]);
         rot[2] = fmaf(wa.z, cv, rot[2]);
         rot[3] = fmaf(wa.w, cv, rot[3]);
-        rot[4] = fmaf(wb.x, cv, rot[4]);
-        rot[5] = fmaf(wb.y, cv, rot[5]);
-        rot[6] = fmaf(wb.z, cv, rot[6]);
-        rot[7] = fmaf(wb.w, cv, rot[7]);
+        if constexpr (GH == 8) {
+          const float4 wb = *reinterpret_cast<const float4*>(wr_s + t * MAXG + 4);
+          rot[4] = fmaf(wb.x, cv, rot[4]);
+          rot[5] = fmaf(wb.y, cv, rot[5]);
+          rot[6] = fmaf(wb.z, cv, rot[6]);
+          rot[7] = fmaf(wb.w, cv, rot[7]);
+        }
       }
       // low-rank weights: component bi, head bh, 8 tokens per load
       if (bi < r) {
@@ -127,14 +130,14 @@ __global__ __launch_bounds__(THREADS) void eoq_attend_partial_kernel(
     for (int i = th; i < r; i += 2) {
       const float v = half_bits_to_float(rfac[(blk * r_max + i) * D + c]);
 #pragma unroll
-      for (int h = 0; h < MAXG; ++h) lin[h] = fmaf(bsum_s[h * EOQ_RMAX_CAP + i], v, lin[h]);
+      for (int h = 0; h < GH; ++h) lin[h] = fmaf(bsum_s[h * EOQ_RMAX_CAP + i], v, lin[h]);
     }
   }
   // fold the two lane halves and write the partial sums of this run: [rot | lin][h][c]
   __syncthreads();
   if (th == 1) {
 #pragma unroll
-    for (int h = 0; h < MAXG; ++h) {
+    for (int h = 0; h < GH; ++h) {
       fold_s[h * D + c] = rot[h];
       fold_s[(MAXG + h) * D + c] = lin[h];
     }
@@ -143,9 +146,9 @@ __global__ __launch_bounds__(THREADS) void eoq_attend_partial_kernel(
   if (th == 0) {
     float* dst = partial + ((sg * gridDim.x + blockIdx.x) * 2 * MAXG) * D;
 #pragma unroll
-    for (int h = 0; h < MAXG; ++h) {
-      dst[h * D + c] = rot[h] + fold_s[h * D + c];
-      dst[(MAXG + h) * D + c] = lin[h] + fold_s[(MAXG + h) * D + c];
+    for (int h = 0; h < MAXG; ++h) {   // heads past GH are written as zeros: the finishing kernel sums all eight
+      dst[h * D + c] = (h < GH) ? rot[h < GH ? h : 0] + fold_s[h * D + c] : 0.0f;
+      dst[(MAXG + h) * D + c] = (h < GH) ? lin[h < GH ? h : 0] + fold_s[(MAXG + h) * D + c] : 0.0f;
     }
   }
 }
@@ -305,10 +308,17 @@ hipError_t eoq_launch_attend(const EoqLaunch& L, eoq_packed values, int64_t n_se
   const int64_t runs = eoq_attend_runs(sg_total, blocks_per_head, &run);
   if (sg_total > 65535 || runs > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)runs, (unsigned)sg_total), block(THREADS);
-#define EOQ_ATTEND(BITS)                                                                                          \
-  hipLaunchKernelGGL(eoq_attend_partial_kernel<BITS>, grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads, group,  \
-                     blocks_per_head, block_capacity, weight_stride, run, L.tab, values.codes, values.norms,      \
-                     values.rank, values.lfac, values.rfac, weights, partial)
+#define EOQ_ATTEND(BITS)                                                                                              \
+  do {                                                                                                                \
+    if (group <= 4)                                                                                                   \
+      hipLaunchKernelGGL((eoq_attend_partial_kernel<BITS, 4>), grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads,    \
+                         group, blocks_per_head, block_capacity, weight_stride, run, L.tab, values.codes,             \
+                         values.norms, values.rank, values.lfac, values.rfac, weights, partial);                      \
+    else                                                                                                              \
+      hipLaunchKernelGGL((eoq_attend_partial_kernel<BITS, 8>), grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads,    \
+                         group, blocks_per_head, block_capacity, weight_stride, run, L.tab, values.codes,             \
+                         values.norms, values.rank, values.lfac, values.rfac, weights, partial);                      \
+  } while (0)
   switch (L.bits) {
     case 1: EOQ_ATTEND(1); break;
     case 2: EOQ_ATTEND(2); break;
