@@ -26,7 +26,7 @@ D = 128
 
 
 def spectral_flops_per_block(n: int, mean_rank: float, jacobi_sweeps: float) -> float:
-    """Algorithmic double-precision flops of the spectral kernel per block (stated in the design doc):
+    """Algorithmic double-precision flops of the spectral kernel per block:
     symmetric Gram n d (d+1), Householder tridiagonalisation 4/3 d^3, Sturm bisection of d eigenvalues to 53 bits
     at 3 flops per matrix row (3 * 53 * d^2), and per retained component the twisted factorisation (~10 d) plus
     the back-transformation through d-2 reflectors (2 d^2).  When the Jacobi solver is selected instead, each
@@ -190,8 +190,8 @@ def main() -> int:
                          "timed region: the reference dispatch that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (blocks are independent; see the sharding note in "
-              "DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (blocks are independent: a multi-GPU run would shard the "
+              "block list and replicate the tables); --gpus must be 1", file=sys.stderr)
         return 2
 
     import torch
