@@ -128,7 +128,7 @@ def compare_compress(blocks64: np.ndarray, rec, lam_gpu: np.ndarray, recs, bits:
 
 
 def log_stats(name: str, stats: dict):
-    """Append parity statistics to <repo>/gpurun_out/parity_stats.jsonl when that output folder exists."""
+    """Append parity statistics to parity_stats.jsonl in the run-output folder at the repository root, if present."""
     import json
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     out = os.path.join(root, "gpurun_out")
