@@ -103,7 +103,8 @@ __device__ __forceinline__ void lloyd_scan(const float* x, int count, const doub
 
 template <int RCAP>
 __global__ __launch_bounds__(THREADS) void eoq_factor_quant_kernel(
-    const uint16_t* __restrict__ blocks, EoqBlockMap map, int n, int r_max, GaussLevels g, const int32_t* __restrict__ rank_in,
+    const uint16_t* __restrict__ blocks, EoqBlockMap map, int64_t B, int n, int r_max, GaussLevels g,
+    const int32_t* __restrict__ rank_in,
     const float* __restrict__ phi, const float* __restrict__ sigma, const float* __restrict__ wfac,
     uint16_t* __restrict__ rfac, uint16_t* __restrict__ lfac, uint8_t* __restrict__ lcodes,
     uint8_t* __restrict__ rcodes, uint16_t* __restrict__ fbook, uint16_t* __restrict__ phi16) {
@@ -111,16 +112,19 @@ __global__ __launch_bounds__(THREADS) void eoq_factor_quant_kernel(
   __shared__ __align__(16) double red[2][4][16];   // [parity][wave][U: 8 sums, V: 8 sums]
   __shared__ int redc[2][4][16];                   // [parity][wave][U: 7 counts, pad, V: 7 counts, pad]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const size_t wblk = blockIdx.x;            // number in the batch: workspace and input
+  // The workgroups walk the batch with the grid's stride.  The launch with the small table has one workgroup per block
+  // and takes the blocks of rank 1 .. 8 (and clears the codebook of rank-0 blocks); the launch with the large table is
+  // a few persistent workgroups that look for the rest (usually there are none: a grid of B would only spend its
+  // time placing workgroups with a large LDS allocation that return at once).
+  for (size_t wblk = blockIdx.x; wblk < (size_t)B; wblk += gridDim.x) {   // number in the batch: workspace and input
+  __syncthreads();                           // LDS of the previous block has been consumed
   const size_t blk = map.slot(wblk);         // record slot: everything that is stored
   const int r = rank_in[blk];
-  // the launch with the small table takes the blocks of rank 1 .. 8 (and clears the codebook of rank-0 blocks), the
-  // launch with the large one the rest
   if (RCAP == 8) {
     if (r == 0 && tid < 2 * LEVELS) fbook[blk * 2 * LEVELS + tid] = 0;
-    if (r == 0 || r > 8) return;
+    if (r == 0 || r > 8) continue;
   } else {
-    if (r <= 8) return;
+    if (r <= 8) continue;
   }
   float* Vs = dyn;
   float* Us = dyn + (size_t)r * D;
@@ -221,26 +225,31 @@ __global__ __launch_bounds__(THREADS) void eoq_factor_quant_kernel(
       for (int k = 0; k < LEVELS - 1; ++k) redc[par][wave][8 + k] = cnt[k];
     }
     __syncthreads();
+    // Lane l < 16 of every wave moves one level: matrix f = l / 8, level k = l % 8 (the waves repeat the work and agree
+    // bit for bit, so no second barrier).  Cell sum = difference of two "at or above" sums, T[0] = all (value 7),
+    // T[j] = value j - 1, T[8] = 0; counts likewise.
+    {
+      const int f = (lane >> 3) & 1, k = lane & 7;
+      const int ia = 8 * f + ((k == 0) ? 7 : k - 1), ib = 8 * f + min(k, LEVELS - 2);
+      const double sa = (red[par][0][ia] + red[par][1][ia]) + (red[par][2][ia] + red[par][3][ia]);
+      double sb = (red[par][0][ib] + red[par][1][ib]) + (red[par][2][ib] + red[par][3][ib]);
+      const int ja = 8 * f + max(k - 1, 0);
+      int ca = (redc[par][0][ja] + redc[par][1][ja]) + (redc[par][2][ja] + redc[par][3][ja]);
+      int cb = (redc[par][0][ib] + redc[par][1][ib]) + (redc[par][2][ib] + redc[par][3][ib]);
+      if (k == 0) ca = f ? cv : cu;
+      if (k == LEVELS - 1) {
+        sb = 0.0;
+        cb = 0;
+      }
+      const int ck = ca - cb;
+      double mine = 0.0;   // this lane's level before the round
 #pragma unroll
-    for (int f = 0; f < 2; ++f) {
-      double S[LEVELS + 1];   // S[k]: sum of the entries at or above boundary k - 1 (S[0]: all), S[8] = 0
-      int C[LEVELS + 1];
+      for (int q = 0; q < LEVELS; ++q) mine = (k == q) ? (f ? mv[q] : mu[q]) : mine;
+      const double moved = (ck > 0) ? (sa - sb) / (double)ck : mine;   // an empty cell keeps its level
 #pragma unroll
-      for (int k = 0; k < 8; ++k)
-        S[(k + 1) & 7] = (red[par][0][8 * f + k] + red[par][1][8 * f + k]) + (red[par][2][8 * f + k] + red[par][3][8 * f + k]);
-      // value 7 (the sum of all entries) landed in S[0] through the "& 7", values 0..6 in S[1..7]
-      S[LEVELS] = 0.0;
-      C[0] = f ? cv : cu;
-#pragma unroll
-      for (int k = 0; k < LEVELS - 1; ++k)
-        C[k + 1] = (redc[par][0][8 * f + k] + redc[par][1][8 * f + k]) + (redc[par][2][8 * f + k] + redc[par][3][8 * f + k]);
-      C[LEVELS] = 0;
-#pragma unroll
-      for (int k = 0; k < LEVELS; ++k) {
-        const int ck = C[k] - C[k + 1];
-        const double mk = (S[k] - S[k + 1]) / (double)ck;
-        if (f == 0) mu[k] = (ck > 0) ? mk : mu[k];   // an empty cell keeps its level
-        else mv[k] = (ck > 0) ? mk : mv[k];
+      for (int q = 0; q < LEVELS; ++q) {
+        mu[q] = readlane_f64(moved, q);
+        mv[q] = readlane_f64(moved, LEVELS + q);
       }
     }
     par ^= 1;
@@ -312,6 +321,7 @@ __global__ __launch_bounds__(THREADS) void eoq_factor_quant_kernel(
     *reinterpret_cast<uint32_t*>(rfac + (blk * r_max + i) * (size_t)D + j) = (uint32_t)outv[0] | ((uint32_t)outv[1] << 16);
     rcodes[(blk * r_max + i) * (size_t)(D / 2) + (j >> 1)] = (uint8_t)(code[0] | (code[1] << 4));
   }
+  }  // blocks of this workgroup
 }
 
 // codes + codebooks + phi16 -> lfac = binary16(U_hat phi16), rfac = V_hat (rows below the rank)
@@ -363,7 +373,7 @@ hipError_t eoq_launch_factor_quant(const EoqLaunch& L, const void* blocks_fp16, 
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds8);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(eoq_factor_quant_kernel<8>, dim3((unsigned)B), dim3(THREADS), lds8, L.stream,
-                     static_cast<const uint16_t*>(blocks_fp16), L.map, L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
+                     static_cast<const uint16_t*>(blocks_fp16), L.map, B, L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
                      out.rfac, out.lfac, fq.lcodes, fq.rcodes, fq.fbook, fq.phi16);
   e = hipGetLastError();
   if (e != hipSuccess || L.r_max <= 8) return e;
@@ -371,8 +381,8 @@ hipError_t eoq_launch_factor_quant(const EoqLaunch& L, const void* blocks_fp16, 
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(eoq_factor_quant_kernel<32>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(eoq_factor_quant_kernel<32>, dim3((unsigned)B), dim3(THREADS), lds, L.stream,
-                     static_cast<const uint16_t*>(blocks_fp16), L.map, L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
+  hipLaunchKernelGGL(eoq_factor_quant_kernel<32>, dim3((unsigned)(B < 512 ? B : 512)), dim3(THREADS), lds, L.stream,
+                     static_cast<const uint16_t*>(blocks_fp16), L.map, B, L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
                      out.rfac, out.lfac, fq.lcodes, fq.rcodes, fq.fbook, fq.phi16);
   return hipGetLastError();
 }
