@@ -153,7 +153,10 @@ __global__ __launch_bounds__(THREADS) void eoq_attend_partial_kernel(
   }
 }
 
-// out[s][h][j] = sum_c Pi[c][j] a_h[c] + lin_h[j], the runs added in order.  One workgroup per (sequence, KV head).
+// out[s][h][j] = sum_c Pi[c][j] a_h[c] + lin_h[j], the runs added in order.  One workgroup per (sequence, KV head,
+// query head of the group): lane (j, half) sums the rotated-domain partials (half 0) or the low-rank partials (half 1)
+// of the runs, one load per run with sixteen in flight; the rotation back and the tail are split between the halves
+// (coordinates 64 half .. 64 half + 63, tail tokens of parity half) and met through LDS in a fixed order.
 // With tail_len > 0 the uncompressed binary16 tail values are added: + sum_t weights[.., tail_offset + t] tail[t].
 __global__ __launch_bounds__(THREADS) void eoq_attend_finish_kernel(int n_kv_heads, int group, int runs,
                                                                     const float* __restrict__ pi,
@@ -163,53 +166,34 @@ __global__ __launch_bounds__(THREADS) void eoq_attend_finish_kernel(int n_kv_hea
                                                                     int64_t weight_stride, int64_t tail_offset,
                                                                     const uint16_t* __restrict__ tail,
                                                                     int64_t tail_capacity, int tail_len) {
-  __shared__ float a_s[MAXG * D];
+  __shared__ float a_s[D];
+  __shared__ float meet_s[D];
   const int tid = threadIdx.x;
-  const int j = tid & (D - 1), th = tid >> 7;
+  const int j = tid & (D - 1), half = tid >> 7;
   const size_t sg = blockIdx.x;
+  const int h = blockIdx.y;
   const size_t sq = sg / n_kv_heads, kv = sg % n_kv_heads;
   const int n_q_heads = n_kv_heads * group;
-  // heads th, th + 2, ...: sum the runs
-  float lin[MAXG / 2];
-#pragma unroll
-  for (int k = 0; k < MAXG / 2; ++k) {
-    const int h = th + 2 * k;
-    float a = 0.0f, l = 0.0f;
-#pragma unroll 8
-    for (int rn = 0; rn < runs; ++rn) {   // unrolled: the loads of eight runs are in flight together
-      const float* src = partial + ((sg * runs + rn) * 2 * MAXG) * D;
-      a += src[h * D + j];
-      l += src[(MAXG + h) * D + j];
-    }
-    a_s[h * D + j] = a;
-    lin[k] = l;
-  }
-  __syncthreads();
-  float acc[MAXG / 2];
-#pragma unroll
-  for (int k = 0; k < MAXG / 2; ++k) acc[k] = 0.0f;
+  float sum = 0.0f;
+  {
+    const float* src = partial + (sg * runs * 2 * MAXG + (size_t)(half * MAXG + h)) * D + j;
 #pragma unroll 16
-  for (int cc = 0; cc < D; ++cc) {
-    const float p = pi[cc * D + j];
-#pragma unroll
-    for (int k = 0; k < MAXG / 2; ++k) acc[k] = fmaf(p, a_s[(th + 2 * k) * D + cc], acc[k]);
+    for (int rn = 0; rn < runs; ++rn) sum += src[(size_t)rn * 2 * MAXG * D];
   }
+  if (half == 0) a_s[j] = sum;
+  __syncthreads();
+  float acc = (half == 1) ? sum : 0.0f;   // half 1 starts from the low-rank term
+#pragma unroll 16
+  for (int cc = 64 * half; cc < 64 * half + 64; ++cc) acc = fmaf(pi[cc * D + j], a_s[cc], acc);
   if (tail_len > 0) {
-#pragma unroll 4
-    for (int t = 0; t < tail_len; ++t) {
-      const float v = half_bits_to_float(tail[(sg * (size_t)tail_capacity + t) * D + j]);
-#pragma unroll
-      for (int k = 0; k < MAXG / 2; ++k) {
-        const int h = min(th + 2 * k, group - 1);   // heads past the group repeat the last one and are not stored
-        lin[k] = fmaf(weights[(sq * n_q_heads + kv * group + h) * (size_t)weight_stride + tail_offset + t], v, lin[k]);
-      }
-    }
+    const float* wrow = weights + (sq * n_q_heads + kv * group + h) * (size_t)weight_stride + tail_offset;
+#pragma unroll 8
+    for (int t = half; t < tail_len; t += 2)
+      acc = fmaf(wrow[t], half_bits_to_float(tail[(sg * (size_t)tail_capacity + t) * D + j]), acc);
   }
-#pragma unroll
-  for (int k = 0; k < MAXG / 2; ++k) {
-    const int h = th + 2 * k;
-    if (h < group) out[(sq * n_q_heads + kv * group + h) * D + j] = acc[k] + lin[k];
-  }
+  if (half == 1) meet_s[j] = acc;
+  __syncthreads();
+  if (half == 0) out[(sq * n_q_heads + kv * group + h) * D + j] = acc + meet_s[j];
 }
 
 // Row-wise softmax in place (the attention weights of Sec. 2.1): one workgroup per row, three passes; 16-byte
@@ -299,7 +283,7 @@ hipError_t eoq_launch_attend(const EoqLaunch& L, eoq_packed values, int64_t n_se
   const int group = n_q_heads / n_kv_heads;
   if (L.ev) (void)hipEventRecord(L.ev[8], L.stream);
   if (blocks_per_head == 0) {  // nothing stored yet: the finishing kernel with no runs writes zeros
-    hipLaunchKernelGGL(eoq_attend_finish_kernel, dim3((unsigned)sg_total), dim3(THREADS), 0, L.stream, n_kv_heads, group, 0,
+    hipLaunchKernelGGL(eoq_attend_finish_kernel, dim3((unsigned)sg_total, (unsigned)group), dim3(THREADS), 0, L.stream, n_kv_heads, group, 0,
                        L.pi, partial, out, weights, weight_stride, tail_offset, tail, tail_capacity, tail_len);
     if (L.ev) (void)hipEventRecord(L.ev[9], L.stream);
     return hipGetLastError();
@@ -328,7 +312,7 @@ hipError_t eoq_launch_attend(const EoqLaunch& L, eoq_packed values, int64_t n_se
 #undef EOQ_ATTEND
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(eoq_attend_finish_kernel, dim3((unsigned)sg_total), block, 0, L.stream, n_kv_heads, group,
+  hipLaunchKernelGGL(eoq_attend_finish_kernel, dim3((unsigned)sg_total, (unsigned)group), block, 0, L.stream, n_kv_heads, group,
                      (int)runs, L.pi, partial, out, weights, weight_stride, tail_offset, tail, tail_capacity, tail_len);
   if (L.ev) (void)hipEventRecord(L.ev[9], L.stream);
   return hipGetLastError();
