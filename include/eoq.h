@@ -132,8 +132,8 @@ size_t     eoq_workspace_bytes(const eoq_ctx* ctx, int64_t B);
 /* Copy the rotation Pi (row-major [d][d], z = Pi u) into HOST memory, as the float32 table the kernels use. */
 eoq_status eoq_rotation(const eoq_ctx* ctx, float* host_out);
 
-/* Copy the Gaussian projection Phi of TQ_prod (Alg. 1 REQUIRE; iid N(0,1) drawn from rot_seed + 1, row-major
- * [d][d], w = Phi r) into HOST memory, as the float32 table the kernels use. */
+/* Copy the Gaussian projection Phi of TQ_prod (Alg. 1 REQUIRE; iid N(0,1) drawn from rot_seed + 1 and rounded to
+ * binary16, row-major [d][d], w = Phi r) into HOST memory, as float32 values of the binary16 table the kernels use. */
 eoq_status eoq_projection(const eoq_ctx* ctx, float* host_out);
 
 /* Copy the N(0,1) codebook into HOST memory: 2^bits ascending centroids and 2^bits-1 midpoints (float32). */

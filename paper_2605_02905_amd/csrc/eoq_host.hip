@@ -185,9 +185,11 @@ eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, 
       ctx->pi_host[(size_t)c * d + j] = v;
       pit[(size_t)j * d + c] = v;
     }
-  // Phi of TQ_prod: iid N(0,1) from the same generator, seeded with rot_seed + 1; used as a float32 table
+  // Phi of TQ_prod: iid N(0,1) from the same generator, seeded with rot_seed + 1, rounded to binary16: that is the
+  // table (nothing in the estimator depends on more digits of a random Gaussian matrix, and one matrix-core pass
+  // multiplies by it exactly)
   ctx->phi_host.resize((size_t)d * d);
-  for (int i = 0; i < d * d; ++i) ctx->phi_host[i] = (float)gaussian_draw(rot_seed + 1, (uint64_t)i);
+  for (int i = 0; i < d * d; ++i) ctx->phi_host[i] = (float)(_Float16)gaussian_draw(rot_seed + 1, (uint64_t)i);
   std::vector<double> cent, bnd;
   lloyd_max(4, cent, bnd);
   for (int i = 0; i < 8; ++i) ctx->gauss16[i] = cent[8 + i];

@@ -325,8 +325,10 @@ __global__ __launch_bounds__(THREADS, 1) void eoq_qjl_kernel(
   __shared__ __align__(16) uint16_t Ct[CHUNK * CLD];    // low-rank coefficients, [token][component]
   __shared__ __align__(16) float rho_s[CHUNK];          // rho / sqrt(d)
   __shared__ __align__(16) uint4 mask_tab[256];
-  __shared__ __align__(16) uint16_t Eh[32 * ZLD];       // residual tile of 32 tokens, hi
-  __shared__ __align__(16) uint16_t El[32 * ZLD];       // and lo
+  // residual tiles of 64 tokens (two tiles of 32), hi and lo, double-buffered: while the products with Phi read one
+  // pair the next two tiles are written into the other, so one barrier per 64 tokens is enough
+  __shared__ __align__(16) uint16_t Eh[2][64 * ZLD];
+  __shared__ __align__(16) uint16_t El[2][64 * ZLD];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
@@ -340,27 +342,31 @@ __global__ __launch_bounds__(THREADS, 1) void eoq_qjl_kernel(
   mg.load(tab);
   const uint16_t* pit_hi = pih + 2 * D * D;
   const uint16_t* pit_lo = pih + 3 * D * D;
-  H8 Bhi[8], Blo[8];
+  // stationary operands: columns of Pi^T (hi + lo) and rows of Phi (binary16 as it is) of this lane
+  H8 Bhi[8], Blo[8], Fhi[8];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
     Bhi[kk].u = *reinterpret_cast<const uint4*>(pit_hi + jcol * D + 16 * kk + 8 * hf);
     Blo[kk].u = *reinterpret_cast<const uint4*>(pit_lo + jcol * D + 16 * kk + 8 * hf);
-  }
-  // Phi rows i = 32 wave + l32 as the second stationary operand (one workgroup per CU: the register file allows it)
-  H8 Fhi[8], Flo[8];
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
     Fhi[kk].u = *reinterpret_cast<const uint4*>(phih + jcol * D + 16 * kk + 8 * hf);
-    Flo[kk].u = *reinterpret_cast<const uint4*>(phih + D * D + jcol * D + 16 * kk + 8 * hf);
   }
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   DecodeFetch<BITS> cur;
   H8 Bv[2];
   const int r = min(max(rank_in[blk], 0), r_max);
   decode_fetch_v(Bv, blk, r, r_max, jcol, hf, rfac);
+  int eb = 0;   // residual buffer of the current pair of tiles
 
   for (int t0 = 0; t0 < n; t0 += CHUNK) {
     decode_fetch<BITS>(cur, blk, t0, n, r_max, tid, tl, codes, norms, rank_in, lfac);
+    // the block's own entries S[row][jcol] of the first pair of tiles
+    uint16_t sv[2][16];
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2) {
+      const uint16_t* srow = blocks + (blk * (size_t)n + t0 + 32 * h2) * D + jcol;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sv[h2][v] = srow[(size_t)(8 * (v >> 2) + 4 * hf + (v & 3)) * D];
+    }
     __syncthreads();  // previous chunk consumed; orders the mask table and the cleared Ct before first use
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
@@ -387,72 +393,82 @@ __global__ __launch_bounds__(THREADS, 1) void eoq_qjl_kernel(
       }
     }
     __syncthreads();
-    // the block's own entries S[row][jcol] of a tile, requested one tile ahead
-    uint16_t sv[16], svn[16];
-    {
-      const uint16_t* srow = blocks + (blk * (size_t)n + t0) * D + jcol;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sv[v] = srow[(size_t)(8 * (v >> 2) + 4 * hf + (v & 3)) * D];
-    }
 #pragma unroll 1
-    for (int tau = 0; tau < CHUNK / 32; ++tau) {
-      if (tau + 1 < CHUNK / 32) {
-        const uint16_t* srow = blocks + (blk * (size_t)n + t0 + 32 * (tau + 1)) * D + jcol;
+    for (int tau = 0; tau < CHUNK / 32; tau += 2) {
+      uint16_t svn[2][16];
+      if (tau + 2 < CHUNK / 32) {   // the next pair's entries of S, requested before this pair's products
 #pragma unroll
-        for (int v = 0; v < 16; ++v) svn[v] = srow[(size_t)(8 * (v >> 2) + 4 * hf + (v & 3)) * D];
+        for (int h2 = 0; h2 < 2; ++h2) {
+          const uint16_t* srow = blocks + (blk * (size_t)n + t0 + 32 * (tau + 2 + h2)) * D + jcol;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) svn[h2][v] = srow[(size_t)(8 * (v >> 2) + 4 * hf + (v & 3)) * D];
+        }
       }
-      // ---- x_hat of tokens 32 tau .. 32 tau + 31, columns 32 wave .. 32 wave + 31 ----
-      float16v acc;
+      // ---- x_hat of tokens 32 tau .. 32 tau + 63, columns 32 wave .. 32 wave + 31: two independent chains ----
+      float16v acc[2];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+      for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.0f;
       const int arow = 32 * tau + l32;
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
-        H8 a0, a1;
+        H8 a0, a1, b0, b1;
         a0.u = *reinterpret_cast<const uint4*>(&Z[arow * ZLD + 16 * kk + 8 * hf]);
+        b0.u = *reinterpret_cast<const uint4*>(&Z[(arow + 32) * ZLD + 16 * kk + 8 * hf]);
         a1.u = *reinterpret_cast<const uint4*>(&Zl[arow * ZLD + 16 * kk + 8 * hf]);
-        acc = mfma16(a0, Bhi[kk], acc);
-        acc = mfma16(a0, Blo[kk], acc);
-        acc = mfma16(a1, Bhi[kk], acc);
+        b1.u = *reinterpret_cast<const uint4*>(&Zl[(arow + 32) * ZLD + 16 * kk + 8 * hf]);
+        acc[0] = mfma16(a0, Bhi[kk], acc[0]);
+        acc[1] = mfma16(b0, Bhi[kk], acc[1]);
+        acc[0] = mfma16(a0, Blo[kk], acc[0]);
+        acc[1] = mfma16(b0, Blo[kk], acc[1]);
+        acc[0] = mfma16(a1, Bhi[kk], acc[0]);
+        acc[1] = mfma16(b1, Bhi[kk], acc[1]);
       }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 s = *reinterpret_cast<const float4*>(&rho_s[32 * tau + 8 * q + 4 * hf]);
-        acc[4 * q + 0] *= s.x;
-        acc[4 * q + 1] *= s.y;
-        acc[4 * q + 2] *= s.z;
-        acc[4 * q + 3] *= s.w;
-      }
+      for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 s = *reinterpret_cast<const float4*>(&rho_s[32 * (tau + h2) + 8 * q + 4 * hf]);
+          acc[h2][4 * q + 0] *= s.x;
+          acc[h2][4 * q + 1] *= s.y;
+          acc[h2][4 * q + 2] *= s.z;
+          acc[h2][4 * q + 3] *= s.w;
+        }
       if (r > 0) {
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2) {
           if (16 * k2 < r) {
-            H8 a0;
+            H8 a0, b0;
             a0.u = *reinterpret_cast<const uint4*>(&Ct[arow * CLD + 16 * k2 + 8 * hf]);
-            acc = mfma16(a0, Bv[k2], acc);
+            b0.u = *reinterpret_cast<const uint4*>(&Ct[(arow + 32) * CLD + 16 * k2 + 8 * hf]);
+            acc[0] = mfma16(a0, Bv[k2], acc[0]);
+            acc[1] = mfma16(b0, Bv[k2], acc[1]);
           }
         }
       }
-      // ---- r_x = S - x_hat into the tile, hi + lo ----
+      // ---- r_x = S - x_hat into the pair's buffer, hi + lo ----
+      uint16_t* eh = Eh[eb];
+      uint16_t* el = El[eb];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = 8 * (v >> 2) + 4 * hf + (v & 3);
-        const float e = half_bits_to_float(sv[v]) - acc[v];
-        uint16_t hi, lo;
-        split_half(e, hi, lo);
-        Eh[row * ZLD + jcol] = hi;
-        El[row * ZLD + jcol] = lo;
-      }
-      __syncthreads();  // the tile is complete
-      // ---- norms: 8 lanes per token, 16 columns each ----
+      for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = 32 * h2 + 8 * (v >> 2) + 4 * hf + (v & 3);
+          const float e = half_bits_to_float(sv[h2][v]) - acc[h2][v];
+          uint16_t hi, lo;
+          split_half(e, hi, lo);
+          eh[row * ZLD + jcol] = hi;
+          el[row * ZLD + jcol] = lo;
+        }
+      __syncthreads();  // the pair is complete; the other buffer was last read before the previous barrier
+      // ---- norms: 4 lanes per token, 32 columns each ----
       {
-        const int row = tid >> 3, seg = tid & 7;
+        const int row = tid >> 2, seg = tid & 3;
         float ss = 0.0f;
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
+        for (int h4 = 0; h4 < 4; ++h4) {
           H8 a, b;
-          a.u = *reinterpret_cast<const uint4*>(&Eh[row * ZLD + 16 * seg + 8 * h2]);
-          b.u = *reinterpret_cast<const uint4*>(&El[row * ZLD + 16 * seg + 8 * h2]);
+          a.u = *reinterpret_cast<const uint4*>(&eh[row * ZLD + 32 * seg + 8 * h4]);
+          b.u = *reinterpret_cast<const uint4*>(&el[row * ZLD + 32 * seg + 8 * h4]);
 #pragma unroll
           for (int x = 0; x < 8; ++x) {
             const float e = half_bits_to_float(a.s[x]) + half_bits_to_float(b.s[x]);
@@ -461,34 +477,41 @@ __global__ __launch_bounds__(THREADS, 1) void eoq_qjl_kernel(
         }
         ss += dpp_mov<0xB1>(ss);
         ss += dpp_mov<0x4E>(ss);
-        ss += dpp_mov<0x141>(ss);   // lane -> 7 - lane inside each group of 8
         if (seg == 0) qnorms[blk * (size_t)n + t0 + 32 * tau + row] = float_to_half_bits(sqrtf(ss));
       }
-      // ---- Phi r_x for outputs i = 32 wave + l32, signs only ----
-      float16v pr;
+      // ---- Phi r_x for outputs i = 32 wave + l32 of both tiles, signs only ----
+      float16v pr[2];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) pr[v] = 0.0f;
+      for (int v = 0; v < 16; ++v) pr[0][v] = pr[1][v] = 0.0f;
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
-        H8 a0, a1;
-        a0.u = *reinterpret_cast<const uint4*>(&Eh[l32 * ZLD + 16 * kk + 8 * hf]);
-        a1.u = *reinterpret_cast<const uint4*>(&El[l32 * ZLD + 16 * kk + 8 * hf]);
-        pr = mfma16(a0, Fhi[kk], pr);
-        pr = mfma16(a0, Flo[kk], pr);
-        pr = mfma16(a1, Fhi[kk], pr);
+        H8 a0, a1, b0, b1;
+        a0.u = *reinterpret_cast<const uint4*>(&eh[l32 * ZLD + 16 * kk + 8 * hf]);
+        b0.u = *reinterpret_cast<const uint4*>(&eh[(l32 + 32) * ZLD + 16 * kk + 8 * hf]);
+        a1.u = *reinterpret_cast<const uint4*>(&el[l32 * ZLD + 16 * kk + 8 * hf]);
+        b1.u = *reinterpret_cast<const uint4*>(&el[(l32 + 32) * ZLD + 16 * kk + 8 * hf]);
+        pr[0] = mfma16(a0, Fhi[kk], pr[0]);
+        pr[1] = mfma16(b0, Fhi[kk], pr[1]);
+        pr[0] = mfma16(a1, Fhi[kk], pr[0]);
+        pr[1] = mfma16(b1, Fhi[kk], pr[1]);
       }
-      uint32_t outw = 0u;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const unsigned long long m = __ballot(pr[v] >= 0.0f);
-        const int row_lo = 8 * (v >> 2) + (v & 3);   // token of the low word; the high word is row_lo + 4
-        outw = (lane == row_lo) ? (uint32_t)m : ((lane == row_lo + 4) ? (uint32_t)(m >> 32) : outw);
+      for (int h2 = 0; h2 < 2; ++h2) {
+        uint32_t outw = 0u;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const unsigned long long m = __ballot(pr[h2][v] >= 0.0f);
+          const int row_lo = 8 * (v >> 2) + (v & 3);   // token of the low word; the high word is row_lo + 4
+          outw = (lane == row_lo) ? (uint32_t)m : ((lane == row_lo + 4) ? (uint32_t)(m >> 32) : outw);
+        }
+        if (lane < 32)
+          *reinterpret_cast<uint32_t*>(qsigns + (blk * (size_t)n + t0 + 32 * (tau + h2) + lane) * (D / 8) + 4 * wave) = outw;
       }
-      if (lane < 32)
-        *reinterpret_cast<uint32_t*>(qsigns + (blk * (size_t)n + t0 + 32 * tau + lane) * (D / 8) + 4 * wave) = outw;
-      __syncthreads();  // the tile may be overwritten
+      eb ^= 1;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) sv[v] = svn[v];
+      for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sv[h2][v] = svn[h2][v];
     }
   }
 }
@@ -527,9 +550,11 @@ __device__ __forceinline__ void rotate_query(const uint16_t* __restrict__ tab_hi
     for (int ks = 0; ks < 4; ++ks) {
       H8 bh, bl;
       bh.u = *reinterpret_cast<const uint4*>(tab_hi + c * D + 32 * ks + 8 * g);
-      bl.u = *reinterpret_cast<const uint4*>(tab_lo + c * D + 32 * ks + 8 * g);
       acc = mfma32(a[ks], bh, acc);
-      acc = mfma32(a[ks], bl, acc);
+      if (tab_lo) {   // uniform: a table that is binary16 to begin with has no low part
+        bl.u = *reinterpret_cast<const uint4*>(tab_lo + c * D + 32 * ks + 8 * g);
+        acc = mfma32(a[ks], bl, acc);
+      }
     }
 #pragma unroll
     for (int v = 0; v < 4; ++v)
@@ -608,7 +633,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   H8 Ap_hi[QJL ? 4 : 1], Ap_lo[QJL ? 4 : 1];
   if constexpr (QJL) {
     __syncthreads();  // qrot has been read: reuse it for Phi q
-    rotate_query(phih, phih + D * D, q + q0, group, qrot, wave, l16, g);
+    rotate_query(phih, nullptr, q + q0, group, qrot, wave, l16, g);
     __syncthreads();
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)

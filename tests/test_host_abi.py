@@ -80,9 +80,9 @@ def test_workspace_size_and_host_only_context(lib):
 
 
 def test_projection_table_matches_the_oracle_stream():
-    """Phi of TQ_prod: the library's own generator (seed rot_seed + 1) against the oracle's, as float32 tables."""
+    """Phi of TQ_prod: the library's own generator (seed rot_seed + 1) against the oracle's, as binary16 tables."""
     ctx = eoq.Context(n=128, bits=2, rot_seed=77)
     got = ctx.eoq_projection()
-    want = oracle.gaussian_projection(128, 78).astype(np.float32)
-    assert got.shape == (128, 128) and np.max(np.abs(got - want)) <= 4e-7 * np.max(np.abs(want))
-    assert np.count_nonzero(got != want) <= 0.01 * got.size     # libm differences in the last bit at most
+    want = oracle.gaussian_projection(128, 78).astype(np.float16).astype(np.float32)
+    assert got.shape == (128, 128) and np.array_equal(got, got.astype(np.float16).astype(np.float32))
+    assert np.count_nonzero(got != want) <= 2     # a libm difference in the last bit can only show at a rounding boundary
