@@ -263,10 +263,11 @@ def _subset(rec, idx):
                                                          rec.rfac, rec.flags)))
 
 
-@pytest.mark.parametrize("cfg,stride", [(2, 37), (5, 331), (6, 29)])
+@pytest.mark.parametrize("cfg,stride", [(2, 37), (3, 397), (4, 41), (5, 331), (6, 29)])
 def test_full_size_batches_in_the_bench_launch_configuration(cfg, stride):
     """The whole batch of a benchmark workload in ONE eoq_compress / eoq_decompress / eoq_scores launch each, as
-    bench.py issues them (config 2: 1024 blocks, config 5: 16384 blocks, config 6: 4096 blocks of 128 x 128); a strided
+    bench.py issues them (config 2: 1024 blocks, config 3: 32768, config 4: 2048 of 1024 tokens, config 5: 16384,
+    config 6: 4096 blocks of 128 x 128); a strided
     sample of the blocks is checked
     against the oracle to the same bars, and every block against properties that hold at any size."""
     spec = synth.config(cfg)
