@@ -1046,3 +1046,40 @@ def test_maximum_block_length_through_every_call():
         bad += int((oracle.unpack_signs(qj.signs[b].cpu().numpy(), 128) != oq.signs).sum())
         assert np.all(np.abs(qj.norms[b].double().cpu().numpy() - oq.gamma16) <= np.spacing(oq.gamma16.astype(np.float16)).astype(np.float64))
     assert bad <= 1e-3 * B * n * 128
+
+
+def test_graph_replays_of_the_bench_step_back_to_back():
+    """The step bench.py replays (config 2, whole batch: compress, decompress, scores) captured once and replayed
+    several times without any host synchronisation in between: every kernel must still see the finished output of the
+    one before it, so the final record, reconstruction and logits equal the eager step's bit for bit."""
+    spec = synth.config(2)
+    blocks, _ = synth.make_blocks(spec, device=DEV)
+    B, n, bits, n_kv, group, bph = blocks.shape[0], spec.n, 2, 8, 4, spec.blocks_per_tensor
+    ctx = eoq.Context(n=n, bits=bits)
+    rec = eoq.Packed.empty(B, n, 128, bits, ctx.r_max, DEV)
+    ws = torch.empty(ctx.eoq_workspace_bytes(B), dtype=torch.uint8, device=DEV)
+    xhat = torch.empty(B, n, 128, dtype=torch.float16, device=DEV)
+    keys = eoq.Packed(*(getattr(rec, f)[:n_kv * bph] for f in _FIELDS))
+    q = synth.make_queries(1, n_kv * group, device=DEV)
+    sc = torch.empty(1, n_kv * group, bph * n, dtype=torch.float32, device=DEV)
+
+    def step():
+        ctx.eoq_compress(blocks, rec, ws)
+        ctx.eoq_decompress(rec, xhat)
+        ctx.eoq_scores(keys, q, n_kv, sc)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (rec.codes, rec.norms.view(torch.int16), rec.rank, rec.lfac.view(torch.int16),
+                                xhat.view(torch.int16), sc)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for t in (rec.codes, rec.norms, rec.lfac, xhat, sc):
+        t.zero_()
+    for _ in range(5):
+        graph.replay()
+    torch.cuda.synchronize()
+    have = (rec.codes, rec.norms.view(torch.int16), rec.rank, rec.lfac.view(torch.int16), xhat.view(torch.int16), sc)
+    for a, b in zip(have, want):
+        assert torch.equal(a, b)
