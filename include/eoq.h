@@ -10,8 +10,10 @@
  * Every pointer argument is documented as HOST or DEVICE.  Device buffers are
  * owned by the caller (e.g. torch tensors); the library allocates device
  * memory only in eoq_create (rotation and codebook tables) and frees it in
- * eoq_destroy.  eoq_compress / eoq_decompress / eoq_scores launch kernels on
- * the given HIP stream and return without synchronising; they never allocate.
+ * eoq_destroy.  The hot calls (eoq_compress*, eoq_expand_factors, eoq_qjl_encode,
+ * eoq_decompress, eoq_scores*, eoq_softmax, eoq_attend*) launch kernels on the
+ * given HIP stream and return without synchronising; they never allocate and can
+ * be captured into a HIP graph (with the profiling of eoq_profile off).
  * All device pointers must be 16-byte aligned.  Functions return EOQ_OK or an
  * error code; they never abort.  A human-readable reason for the last failure
  * is kept per context (eoq_last_error).
