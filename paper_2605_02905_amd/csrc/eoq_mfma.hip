@@ -571,20 +571,31 @@ struct ScoreFetch {
   uint32_t sword[2];
   uint16_t gam[2];
 };
+// Buffer addressing: a resource descriptor in scalar registers (base of this workgroup's run of blocks, size of the
+// run: reads past it return zero instead of faulting), a scalar byte offset that moves from pass to pass and a per-lane
+// 32-bit offset that never changes -- no vector arithmetic per load.
+struct ScoreBuffers {
+  __amdgpu_buffer_rsrc_t codes, norms, lfac, qsigns, qnorms;
+};
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(const void* base, size_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(bytes > 0x7FFFFFFFu ? 0x7FFFFFFFu : bytes),
+                                           0x00020000);
+}
+// `tokr` (first token of the first tile, counted from the start of the run) is wave-uniform.
 template <int BITS, bool QJL>
-__device__ __forceinline__ void score_fetch(ScoreFetch<BITS, QJL>& f, size_t blk, int n, int tile, int l16, int g,
-                                            const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
-                                            const uint8_t* __restrict__ qsigns, const uint16_t* __restrict__ qnorms) {
+__device__ __forceinline__ void score_fetch(ScoreFetch<BITS, QJL>& f, const ScoreBuffers& sb, int tokr, uint32_t lane_c,
+                                            uint32_t lane_s, uint32_t lane_n) {
   constexpr int ROWB = BITS * D / 8;
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    const size_t tok = blk * (size_t)n + 16 * (tile + u * (THREADS / 64)) + l16;
+    const int tok = tokr + 16 * u * (THREADS / 64);   // uniform
 #pragma unroll
-    for (int p = 0; p < BITS; ++p) f.word[u][p] = *reinterpret_cast<const uint32_t*>(codes + tok * ROWB + p * 16 + 4 * g);
-    f.rho[u] = norms[tok];
+    for (int p = 0; p < BITS; ++p)
+      f.word[u][p] = __builtin_amdgcn_raw_buffer_load_b32(sb.codes, lane_c, tok * ROWB + p * 16, 0);
+    f.rho[u] = __builtin_amdgcn_raw_buffer_load_b16(sb.norms, lane_n, tok * 2, 0);
     if constexpr (QJL) {
-      f.sword[u] = *reinterpret_cast<const uint32_t*>(qsigns + tok * (D / 8) + 4 * g);
-      f.gam[u] = qnorms[tok];
+      f.sword[u] = __builtin_amdgcn_raw_buffer_load_b32(sb.qsigns, lane_s, tok * (D / 8), 0);
+      f.gam[u] = __builtin_amdgcn_raw_buffer_load_b16(sb.qnorms, lane_n, tok * 2, 0);
     }
   }
 }
@@ -605,7 +616,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   __shared__ int rank_s[SC_RUN_MAX];
   __shared__ __align__(16) uint4 mask_tab[256];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave: scalar
   const int l16 = lane & 15, g = lane >> 4;
   const size_t sg = blockIdx.y;
   const size_t sq = sg / n_kv_heads, kv = sg % n_kv_heads;
@@ -686,11 +697,22 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   }
   __syncthreads();
 
+  const uint32_t lane_c = (uint32_t)(l16 * (BITS * D / 8) + 4 * g);   // into the codes of a tile
+  const uint32_t lane_s = (uint32_t)(l16 * (D / 8) + 4 * g);          // into the sign planes of a tile
+  const uint32_t lane_n = (uint32_t)(2 * l16);                        // into the norms / a coefficient row of a tile
+  ScoreBuffers sb;
+  sb.codes = buffer_of(codes + blk0 * (size_t)n * (BITS * D / 8), (size_t)nblk * n * (BITS * D / 8));
+  sb.norms = buffer_of(norms + blk0 * (size_t)n, (size_t)nblk * n * 2);
+  sb.lfac = buffer_of(lfac + blk0 * (size_t)r_max * n, (size_t)nblk * r_max * n * 2);
+  if constexpr (QJL) {
+    sb.qsigns = buffer_of(qsigns + blk0 * (size_t)n * (D / 8), (size_t)nblk * n * (D / 8));
+    sb.qnorms = buffer_of(qnorms + blk0 * (size_t)n, (size_t)nblk * n * 2);
+  }
   ScoreFetch<BITS, QJL> ring[SC_DEPTH];
   uint16_t cbr[2][2][4];   // [parity of the pass][tile][component of the group of four]
   int fb = 0, fq = 0;      // block and pass-in-block of the next pass to request
   auto request = [&](ScoreFetch<BITS, QJL>& f) __attribute__((always_inline)) {
-    score_fetch<BITS, QJL>(f, blk0 + fb, n, wave + 8 * fq, l16, g, codes, norms, qsigns, qnorms);
+    score_fetch<BITS, QJL>(f, sb, fb * n + 16 * (wave + 8 * fq), lane_c, lane_s, lane_n);
     if (++fq == ppb) {
       fq = 0;
       ++fb;
@@ -698,13 +720,14 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
   };
   // coefficients C[i][token] of the first four components of pass (cb_b, cb_q); row 0 is read when the rank is 0
   auto request_cb = [&](uint16_t (&cb)[2][4], int cb_b, int cb_q) __attribute__((always_inline)) {
-    const size_t bk = blk0 + cb_b;
-    const int rr = max(rank_s[cb_b], 1);
+    const int rr = __builtin_amdgcn_readfirstlane(max(rank_s[cb_b], 1));
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int a = 0; a < 4; ++a)
-        cb[u][a] = lfac[(bk * r_max + min(a, rr - 1)) * (size_t)n + 16 * (wave + 8 * cb_q + 4 * u) + l16];
+      for (int a = 0; a < 4; ++a) {
+        const int row = (cb_b * r_max + min(a, rr - 1)) * n + 16 * (wave + 8 * cb_q + 4 * u);   // uniform, in entries
+        cb[u][a] = __builtin_amdgcn_raw_buffer_load_b16(sb.lfac, lane_n, row * 2, 0);
+      }
   };
   if (P > 0) request_cb(cbr[0], 0, 0);
 #pragma unroll
