@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "eoq.h"
 
 namespace eoqdev {
@@ -105,6 +107,28 @@ __device__ __forceinline__ void load8(const void* base, int dtype, size_t elem, 
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
     v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
   }
+}
+
+// Compile-time loop: every index into a per-lane register array must be a constant before the optimiser
+// first looks at the array, otherwise the array is kept in (scratch) memory.
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+#define EOQ_SFOR(var, n, ...) eoqdev::static_for<0, n>([&](auto var##_ic) __attribute__((always_inline)) { \
+  constexpr int var = decltype(var##_ic)::value; __VA_ARGS__ })
+
+// old with lane LANE (a constant) replaced by the wave-uniform value val: one instruction (v_writelane_b32) where a
+// compare and a select per lane would be two.  Reached through the compiler's own intrinsic, not inline assembly:
+// a vector compare that has just written the scalar operand must be two instructions away, and only the compiler
+// sees both.
+extern "C" __device__ uint32_t eoq_llvm_writelane(uint32_t val, uint32_t lane, uint32_t old) __asm("llvm.amdgcn.writelane.i32");
+template <int LANE>
+__device__ __forceinline__ uint32_t write_lane(uint32_t old, uint32_t val) {
+  return eoq_llvm_writelane(val, LANE, old);
 }
 
 }  // namespace eoqdev

@@ -35,6 +35,12 @@ union H8 {
   uint16_t s[8];
 };
 
+// Buffer descriptor over `bytes` bytes at `base` (raw addressing: loads past the end return zero).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(const void* base, size_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(bytes > 0x7FFFFFFFu ? 0x7FFFFFFFu : bytes),
+                                           0x00020000);
+}
+
 __device__ __forceinline__ float16v mfma16(const H8& a, const H8& b, float16v c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, c, 0, 0, 0);
 }
@@ -131,32 +137,46 @@ struct DecodeFetch {
   int r;           // rank of the block the chunk belongs to
 };
 template <int BITS>
-__device__ __forceinline__ void decode_fetch(DecodeFetch<BITS>& f, int64_t blk, int t0, int n, int r_max, int tid, int tl,
+__device__ __forceinline__ void decode_fetch(DecodeFetch<BITS>& f, int64_t blk, int t0, int n, int r, int r_max, int tid, int tl,
                                              const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
-                                             const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac) {
+                                             const uint16_t* __restrict__ lfac) {
   constexpr int ROWB = BITS * D / 8;
   const size_t tok = (size_t)blk * n + t0 + tl;
-  f.r = min(max(rank_in[blk], 0), r_max);   // records may come from storage: never index past r_max rows
+  f.r = r;
 #pragma unroll
   for (int p = 0; p < BITS; ++p) f.pl[p] = *reinterpret_cast<const uint4*>(codes + tok * ROWB + p * 16);
   f.rho = norms[tok];
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int i = (tid + THREADS * u) >> 4, seg = tid & 15;
-    f.cf[u] = (i < f.r) ? *reinterpret_cast<const uint4*>(lfac + ((size_t)blk * r_max + i) * n + t0 + 8 * seg)
-                        : make_uint4(0u, 0u, 0u, 0u);
+    f.cf[u] = (i < r) ? *reinterpret_cast<const uint4*>(lfac + ((size_t)blk * r_max + i) * n + t0 + 8 * seg)
+                      : make_uint4(0u, 0u, 0u, 0u);
   }
 }
-// right factors of a block as B operand of the low-rank product: V[i][jcol], i = 16 k2 + 8 hf + e
-__device__ __forceinline__ void decode_fetch_v(H8 (&Bv)[2], int64_t blk, int r, int r_max, int jcol, int hf,
+// right factors of a block as B operand of the low-rank product: V[i][jcol], i = 16 k2 + 8 hf + e.  The sixteen
+// two-byte loads land in registers of their own and are packed by pack_v once they are needed, so that issuing
+// them waits for nothing.
+__device__ __forceinline__ void decode_fetch_v(uint32_t (&raw)[16], int64_t blk, int r, int r_max, int jcol, int hf,
                                                const uint16_t* __restrict__ rfac) {
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int i = 16 * (q >> 3) + 8 * hf + (q & 7);
+    raw[q] = (i < r) ? (uint32_t)rfac[((size_t)blk * r_max + i) * D + jcol] : 0u;
+  }
+}
+__device__ __forceinline__ void pack_v(H8 (&Bv)[2], const uint32_t (&raw)[16]) {
 #pragma unroll
   for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int i = 16 * k2 + 8 * hf + e;
-      Bv[k2].s[e] = (i < r) ? rfac[((size_t)blk * r_max + i) * D + jcol] : (uint16_t)0;
-    }
+    for (int w = 0; w < 4; ++w) Bv[k2].w[w] = raw[8 * k2 + 2 * w] | (raw[8 * k2 + 2 * w + 1] << 16);
+}
+// Rank of block blk as a vector load (zero past the end of the array): a scalar load would share its counter with
+// the LDS traffic and be waited for at the next LDS wait, a vector load is waited for where its value is read.
+__device__ __forceinline__ int rank_request(__amdgpu_buffer_rsrc_t ranks, int64_t blk) {
+  return __builtin_amdgcn_raw_buffer_load_b32(ranks, 0, (int)(blk * 4), 0);
+}
+__device__ __forceinline__ int rank_value(int raw, int r_max) {
+  return min(max(__builtin_amdgcn_readfirstlane(raw), 0), r_max);   // records may come from storage
 }
 
 template <int BITS>
@@ -192,13 +212,26 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
   }
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
 
+  // the rank of the block after the next one is requested while the next one's first chunk is, so that request
+  // finds its rank in a register
+  const __amdgpu_buffer_rsrc_t ranks = buffer_of(rank_in, (size_t)B * 4);
+  const int64_t step = gridDim.x;
+  int rk_n = rank_request(ranks, min((int64_t)blockIdx.x + step, B));
   DecodeFetch<BITS> cur, nxt;
-  H8 Bv[2], Bvn[2];
-  if ((int64_t)blockIdx.x < B) {
-    decode_fetch<BITS>(cur, blockIdx.x, 0, n, r_max, tid, tl, codes, norms, rank_in, lfac);
-    decode_fetch_v(Bv, blockIdx.x, cur.r, r_max, jcol, hf, rfac);
+  H8 Bv[2];
+  uint32_t vraw[16];
+  {
+    const int r0 = rank_value(rank_request(ranks, min((int64_t)blockIdx.x, B)), r_max);
+    if ((int64_t)blockIdx.x < B) {
+      decode_fetch<BITS>(cur, blockIdx.x, 0, n, r0, r_max, tid, tl, codes, norms, lfac);
+      decode_fetch_v(vraw, blockIdx.x, r0, r_max, jcol, hf, rfac);
+    }
+    pack_v(Bv, vraw);
   }
-  for (int64_t blk = blockIdx.x; blk < B; blk += gridDim.x) {
+  // nothing of the set-up is left in flight: inside the loop a wait then only ever covers what the loop itself
+  // requested (the next chunk's bytes must not be waited for before the matrix products of this one)
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+  for (int64_t blk = blockIdx.x; blk < B; blk += step) {
     const int r = cur.r;
     for (int t0 = 0; t0 < n; t0 += CHUNK) {
       __syncthreads();  // previous chunk consumed; also orders the mask table and the cleared Ct before first use
@@ -228,16 +261,19 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
       // ---- request the next chunk (of this block or of the next one) ----
       const bool last = (t0 + CHUNK >= n);
       {
-        const int64_t nb = last ? blk + gridDim.x : blk;
+        const int64_t nb = last ? blk + step : blk;
         if (nb < B) {
-          decode_fetch<BITS>(nxt, nb, last ? 0 : t0 + CHUNK, n, r_max, tid, tl, codes, norms, rank_in, lfac);
-          if (last) decode_fetch_v(Bvn, nb, nxt.r, r_max, jcol, hf, rfac);
+          const int rn = last ? rank_value(rk_n, r_max) : r;
+          if (last) rk_n = rank_request(ranks, min(blk + 2 * step, B));
+          decode_fetch<BITS>(nxt, nb, last ? 0 : t0 + CHUNK, n, rn, r_max, tid, tl, codes, norms, lfac);
+          if (last) decode_fetch_v(vraw, nb, rn, r_max, jcol, hf, rfac);
         }
       }
       __syncthreads();
       // ---- phase 2: wave w produces columns 32w .. 32w+31 of every tile; two tiles at a time so that consecutive
-      // matrix instructions never wait for each other's accumulator ----
-#pragma unroll 1
+      // matrix instructions never wait for each other's accumulator.  Unrolled: in front of a loop with stores
+      // in it the compiler would wait for the bytes requested above. ----
+#pragma unroll
       for (int tau = 0; tau < CHUNK / 32; tau += 2) {
         float16v acc[2];
 #pragma unroll
@@ -299,10 +335,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
         }
       }
       cur = nxt;
-      if (last) {
-        Bv[0] = Bvn[0];
-        Bv[1] = Bvn[1];
-      }
+      if (last) pack_v(Bv, vraw);
     }
   }
 }
@@ -354,11 +387,15 @@ __global__ __launch_bounds__(THREADS, 1) void eoq_qjl_kernel(
   DecodeFetch<BITS> cur;
   H8 Bv[2];
   const int r = min(max(rank_in[blk], 0), r_max);
-  decode_fetch_v(Bv, blk, r, r_max, jcol, hf, rfac);
+  {
+    uint32_t vraw[16];
+    decode_fetch_v(vraw, blk, r, r_max, jcol, hf, rfac);
+    pack_v(Bv, vraw);
+  }
   int eb = 0;   // residual buffer of the current pair of tiles
 
   for (int t0 = 0; t0 < n; t0 += CHUNK) {
-    decode_fetch<BITS>(cur, blk, t0, n, r_max, tid, tl, codes, norms, rank_in, lfac);
+    decode_fetch<BITS>(cur, blk, t0, n, r, r_max, tid, tl, codes, norms, lfac);
     // the block's own entries S[row][jcol] of the first pair of tiles
     uint16_t sv[2][16];
 #pragma unroll
@@ -577,10 +614,6 @@ struct ScoreFetch {
 struct ScoreBuffers {
   __amdgpu_buffer_rsrc_t codes, norms, lfac, qsigns, qnorms;
 };
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(const void* base, size_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(bytes > 0x7FFFFFFFu ? 0x7FFFFFFFu : bytes),
-                                           0x00020000);
-}
 // `tokr` (first token of the first tile, counted from the start of the run) is wave-uniform.
 template <int BITS, bool QJL>
 __device__ __forceinline__ void score_fetch(ScoreFetch<BITS, QJL>& f, const ScoreBuffers& sb, int tokr, uint32_t lane_c,
@@ -973,6 +1006,13 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
   const size_t slot = map.slot(blk);
   const int r = rank_in[slot];
   constexpr int ROWB = BITS * D / 8;
+  // the 32 rows x 256 B of this wave's tokens, 16 B per lane and load (4 rows per instruction), are requested one
+  // chunk ahead: the first chunk's here, before the tables
+  const size_t tok = (size_t)map.token_stride;
+  const uint16_t* src0 = blocks + map.in_base(blk) + (size_t)(32 * wave) * tok;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 pre[8];
+  EOQ_SFOR(it, 8, pre[it] = *reinterpret_cast<const u32x4*>(src0 + (4 * it + (lane >> 4)) * tok + (lane & 15) * 8););
 
   // stationary rotation operand: rows c = 32w + l32 of Pi, hi and lo
   H8 Bhi[8], Blo[8];
@@ -991,36 +1031,43 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
   // factors of the block: W = V diag(phi/sigma) split into hi + lo, and V16^T.  Only the rows below the rank
   // rounded up to a multiple of 8 are ever multiplied with something that is not forced to zero (see Cneg)
   const int r_up = (r + 7) & ~7;
-  for (int e = tid; e < r_up * D; e += THREADS) {
-    const int i = e >> 7, j = e & (D - 1);
-    uint16_t hi = 0, lo = 0, v16 = 0;
-    if (i < r) {
-      if constexpr (!FQ) split_half(wfac[(blk * r_max + i) * D + j], hi, lo);
-      v16 = rfac[(slot * r_max + i) * D + j];
+  // thread (i0, j) = (tid / 128, tid % 128) takes the rows i0, i0 + 2, ...; four rows per round, their loads
+  // issued together (rows at and above the rank read row r - 1 instead and store zeros)
+  for (int i4 = 0; i4 < r_up; i4 += 8) {
+    const int j = tid & (D - 1);
+    float wv[4];
+    uint16_t vv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int ic = min(i4 + 2 * u + (tid >> 7), r - 1);
+      if constexpr (!FQ) wv[u] = wfac[(blk * r_max + ic) * D + j];
+      vv[u] = rfac[(slot * r_max + ic) * D + j];
     }
-    if constexpr (!FQ) {
-      Wh[i * ZLD + j] = hi;
-      Wl[i * ZLD + j] = lo;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i4 + 2 * u + (tid >> 7);
+      const bool live = i < r;
+      if constexpr (!FQ) {
+        uint16_t hi, lo;
+        split_half(wv[u], hi, lo);
+        Wh[i * ZLD + j] = live ? hi : (uint16_t)0;
+        Wl[i * ZLD + j] = live ? lo : (uint16_t)0;
+      }
+      VT[j * VLD + i] = live ? vv[u] : (uint16_t)0;
     }
-    VT[j * VLD + i] = v16;
   }
   const float sqrt_d = sqrtf((float)D);
+  const __amdgpu_buffer_rsrc_t lbuf = buffer_of(lfac + slot * r_max * (size_t)n, (size_t)r * n * 2);
+  const __amdgpu_buffer_rsrc_t cbuf = buffer_of(codes + slot * (size_t)n * ROWB, (size_t)n * ROWB);
 
   for (int t0 = 0; t0 < n; t0 += CHUNK) {
     __syncthreads();  // previous chunk's tiles consumed (and the factor tables written)
     // ---- phase 1 ----
     {
       uint16_t* tile = X + 32 * wave * ZLD;
-      const size_t tok = (size_t)map.token_stride;
-      const uint16_t* src = blocks + map.in_base(blk) + (size_t)(t0 + 32 * wave) * tok;
-      // 32 rows x 256 B, 16 B per lane and load: 4 rows per instruction
-#pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int row = 4 * it + (lane >> 4), col = (lane & 15) * 8;
-        const uint4 v = *reinterpret_cast<const uint4*>(src + row * tok + col);
-        *reinterpret_cast<uint4*>(tile + row * ZLD + col) = v;
-      }
-      __builtin_amdgcn_s_waitcnt(0);   // the tile is private to this wave: wait for its own LDS writes
+      EOQ_SFOR(it, 8, *reinterpret_cast<u32x4*>(tile + (4 * it + (lane >> 4)) * ZLD + (lane & 15) * 8) = pre[it];);
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the tile is private to this wave, wait for its own LDS writes
       __builtin_amdgcn_wave_barrier();
       H4 Sreg[16];
 #pragma unroll
@@ -1032,13 +1079,17 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
         for (int v = 0; v < 16; ++v) Racc[mt][v] = (float)Sreg[4 * mt + (v >> 2)].h[v & 3];
       if (r > 0) {
         H4 Cneg[4];
-        const size_t tg = (size_t)t0 + 32 * wave + l32;
+        // coefficient (i, token) of the block through a buffer descriptor that ends after row r - 1: the lane's part
+        // of the offset in a register, the rest wave-uniform; loads from rows at and above the rank return zero and
+        // stores to them are dropped
+        const int cf_lane = (4 * hf * n + t0 + 32 * wave + l32) * 2;
         if constexpr (FQ) {
           // the stored coefficients of this token, negated: the next B operand
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
-            Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(lfac[(slot * r_max + i) * (size_t)n + tg] ^ 0x8000u) : (uint16_t)0;
+            const uint16_t c = __builtin_amdgcn_raw_buffer_load_b16(lbuf, cf_lane, (8 * (v >> 2) + (v & 3)) * n * 2, 0);
+            Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(c ^ 0x8000u) : (uint16_t)0;
           }
         } else {
           float16v Cacc;
@@ -1057,7 +1108,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
           for (int v = 0; v < 16; ++v) {
             const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
             const uint16_t hb = float_to_half_bits(Cacc[v]);
-            if (i < r) lfac[(slot * r_max + i) * (size_t)n + tg] = hb;
+            __builtin_amdgcn_raw_buffer_store_b16(hb, lbuf, cf_lane, (8 * (v >> 2) + (v & 3)) * n * 2, 0);
             Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(hb ^ 0x8000u) : (uint16_t)0;  // rows >= r of W are not initialised
           }
         }
@@ -1093,9 +1144,17 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
           *reinterpret_cast<uint2*>(tile + l32 * ZLD + 32 * mt + 8 * q + 4 * hf) = u.u;
         }
     }
+    // the next chunk's rows travel while this one is rotated and quantised (requested here and not earlier: phase 1
+    // has no registers to spare)
+    __builtin_amdgcn_sched_barrier(0);
+    if (t0 + CHUNK < n) {
+      const uint16_t* src = src0 + (size_t)(t0 + CHUNK) * tok;
+      EOQ_SFOR(it, 8, pre[it] = *reinterpret_cast<const u32x4*>(src + (4 * it + (lane >> 4)) * tok + (lane & 15) * 8););
+    }
     __syncthreads();
-    // ---- phase 2 ----
-#pragma unroll 1
+    // ---- phase 2 ---- (unrolled: a loop with stores in it would make the compiler wait for the rows requested above
+    // before entering it)
+#pragma unroll
     for (int tau = 0; tau < CHUNK / 32; ++tau) {
       float16v acc;
 #pragma unroll
@@ -1112,8 +1171,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
       uint32_t outw[BITS];
 #pragma unroll
       for (int p = 0; p < BITS; ++p) outw[p] = 0u;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
+      EOQ_SFOR(v, 16,
         const float z = acc[v];
         unsigned long long m[BITS];
         if constexpr (BITS == 1) {
@@ -1141,17 +1199,21 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
           const float lo1 = b3 ? (b2 ? bnd[14] : bnd[10]) : (b2 ? bnd[6] : bnd[2]);
           m[0] = __ballot(z >= (b1 ? lo1 : lo0));
         }
-        const int row_lo = 8 * (v >> 2) + (v & 3);   // token of the low word; the high word is row_lo + 4
+        constexpr int row_lo = 8 * (v >> 2) + (v & 3);   // token of the low word; the high word is row_lo + 4
+        EOQ_SFOR(p, BITS,
+          outw[p] = write_lane<row_lo>(outw[p], (uint32_t)m[p]);
+          outw[p] = write_lane<row_lo + 4>(outw[p], (uint32_t)(m[p] >> 32));
+        );
+      );
+      // lane t < 32 stores the words of token t; the other lanes aim past the end of the descriptor and are dropped
+      // (no branch: after a branch around the stores the compiler could not count them when it waits for the rows
+      // requested above, and would wait for everything)
+      {
+        const int off = (lane < 32) ? (t0 + 32 * tau + lane) * ROWB + 4 * wave : 0x7FFFFFF0;
 #pragma unroll
-        for (int p = 0; p < BITS; ++p) {
-          outw[p] = (lane == row_lo) ? (uint32_t)m[p] : ((lane == row_lo + 4) ? (uint32_t)(m[p] >> 32) : outw[p]);
-        }
+        for (int p = 0; p < BITS; ++p) __builtin_amdgcn_raw_buffer_store_b32(outw[p], cbuf, off, p * 16, 0);
       }
-      if (lane < 32) {
-        uint8_t* dst = codes + (slot * (size_t)n + t0 + 32 * tau + lane) * ROWB + 4 * wave;
-#pragma unroll
-        for (int p = 0; p < BITS; ++p) *reinterpret_cast<uint32_t*>(dst + p * 16) = outw[p];
-      }
+      __builtin_amdgcn_sched_barrier(0);   // one tile at a time: keeps the registers of the rows in flight free
     }
   }
 }

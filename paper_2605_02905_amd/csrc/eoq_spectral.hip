@@ -28,18 +28,6 @@ constexpr int THREADS = 256;
 // ---------------------------------------------------------------------------------------------
 constexpr int STAGE_ROWS = 32;
 
-// Compile-time loop: every index into a per-lane register array must be a constant before the optimiser
-// first looks at the array, otherwise the array is kept in (scratch) memory.
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-#define EOQ_SFOR(var, n, ...) static_for<0, n>([&](auto var##_ic) __attribute__((always_inline)) { \
-  constexpr int var = decltype(var##_ic)::value; __VA_ARGS__ })
-
 __device__ __forceinline__ void gram_tile(const void* __restrict__ blocks, int dtype, size_t base_elem, size_t tok, int n,
                                           float* stage, int tid, double (&acc)[64]) {
   const int ty = tid >> 4, tx = tid & 15;
