@@ -290,7 +290,10 @@ constexpr int PAIR_B[28] = {1, 2, 3, 4, 5, 6, 7, 2, 3, 4, 5, 6, 7, 3, 4, 5, 6, 7
 __device__ __forceinline__ int refl_off(int k) { return k * (D - 1) - (k * (k - 1)) / 2; }
 constexpr int REFL_LEN = (D - 1) * D / 2;  // 8128
 constexpr int GRID_POINTS = 256;           // first localisation: one Sturm count per lane on a uniform grid
-constexpr int MULTISECT_ITERS = 26;        // then trisection: 3^26 * 257 > 2^49 (the reduction itself is good to ~2^-48)
+constexpr int MULTISECT_ITERS = 17;        // then trisection, two lanes per eigenvalue: 3^17 * 257 > 2^34.9
+constexpr int REFINE_COUNT = 32;           // the largest eigenvalues (all that can be retained) go on with eight lanes
+constexpr int REFINE_ITERS = 5;            // each, 9-section: 9^5 * 3^17 * 257 > 2^50 (the reduction itself is good to ~2^-48)
+static_assert(REFINE_COUNT * 8 == THREADS && REFINE_COUNT >= EOQ_RMAX_CAP, "eight lanes per refined eigenvalue");
 constexpr int EV_BATCH = 8;                // eigenvectors per twisted-factorisation pass
 constexpr int U1_BYTES = EV_BATCH * 4 * D * 8;  // 32 KB: twisted-factorisation scratch; also the Gram strip (16 KB)
 constexpr double CLUSTER_TOL = 1e-10;      // relative gap below which retained eigenvalues count as repeated
@@ -888,6 +891,30 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       }
     }
     if (sub == 0) lam_s[D - 1 - j] = fmax(0.5 * (lo + hi), 0.0) / sc;   // descending order, unscaled
+    // The eigenvalues below the largest REFINE_COUNT stay at that width (3e-11 of the largest): they only enter sums
+    // and the bulk edge.  The others feed the twisted factorisations and the shrinker and are taken to full
+    // precision, eight lanes each: the interval is cut in nine at eight points x_s = lo + (s + 1) w and the new
+    // bounds are recomputed by every lane from the same expression, so the eight lanes stay identical.
+    __syncthreads();   // the grid counts in `atoms` are no longer read
+    if (sub == 0 && j >= D - REFINE_COUNT) {
+      atoms[2 * (j - (D - REFINE_COUNT))] = lo;
+      atoms[2 * (j - (D - REFINE_COUNT)) + 1] = hi;
+    }
+    __syncthreads();
+    {
+      const int jj = tid >> 3, s8 = tid & 7, jr = D - REFINE_COUNT + jj;
+      double rlo = atoms[2 * jj], rhi = atoms[2 * jj + 1];
+#pragma unroll 1
+      for (int it = 0; it < REFINE_ITERS; ++it) {
+        const double w = (rhi - rlo) * (1.0 / 9.0);
+        const int c = sturm_count(sde, fma((double)(s8 + 1), w, rlo));
+        const unsigned long long below = __ballot(c <= jr);   // points not above the eigenvalue: a prefix of the eight
+        const int mcount = __popc((unsigned)(below >> (tid & 56)) & 0xFFu);
+        rhi = (mcount == 8) ? rhi : fma((double)(mcount + 1), w, rlo);
+        rlo = fma((double)mcount, w, rlo);
+      }
+      if (s8 == 0) lam_s[D - 1 - jr] = fmax(0.5 * (rlo + rhi), 0.0) / sc;
+    }
   }
   __syncthreads();
 
