@@ -295,7 +295,11 @@ constexpr int REFINE_COUNT = 32;           // the largest eigenvalues (all that 
 constexpr int REFINE_ITERS = 5;            // each, 9-section: 9^5 * 3^17 * 257 > 2^50 (the reduction itself is good to ~2^-48)
 static_assert(REFINE_COUNT * 8 == THREADS && REFINE_COUNT >= EOQ_RMAX_CAP, "eight lanes per refined eigenvalue");
 constexpr int EV_BATCH = 8;                // eigenvectors per twisted-factorisation pass
-constexpr int U1_BYTES = EV_BATCH * 4 * D * 8;  // 32 KB: twisted-factorisation scratch; also the Gram strip (16 KB)
+// Twisted-factorisation scratch: per eigenvector of a batch two arrays of D pairs, F then Bk.  The arrays are D + 1
+// pairs apart: lanes that walk different arrays in step (one per array, same row) then fall into different banks;
+// at a stride of D pairs = 2048 bytes all sixteen would hit the same ones.
+constexpr int TW_STRIDE = D + 1;
+constexpr int U1_BYTES = EV_BATCH * 2 * TW_STRIDE * 16;  // 33 KB; also the Gram strip (16 KB)
 constexpr double CLUSTER_TOL = 1e-10;      // relative gap below which retained eigenvalues count as repeated
 constexpr int REFL_SLACK = 16;             // floats in front of the reflectors (masked reads may reach them)
 constexpr int REFL_BYTES = (REFL_LEN + REFL_SLACK) * 4;   // 32576 (a multiple of 16)
@@ -759,6 +763,68 @@ __device__ __forceinline__ void backtransform_stage(double (&y)[8], const float*
   }
 }
 
+// Minors of T - mu I by the three-term recurrence, from the top (UP = false: p_i, stored with p_{i-1}) or from the
+// bottom (UP = true: q_i, stored with q_{i+1}); de[i] = (d_i, e_{i-1}^2), de[D] = 0.  Eight steps per group, then
+// both running values are rescaled by a power of two (the ratios of consecutive minors are what is used).
+template <bool UP>
+__device__ __forceinline__ void minors_sweep(const double2* de, double mu, double2* out) {
+  double pm = 0.0, p = 1.0;
+#pragma unroll 2
+  for (int s0 = 0; s0 < D; s0 += 8) {
+    double dmu[8], e2[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const int i = UP ? D - 1 - (s0 + s) : s0 + s;
+      dmu[s] = de[i].x - mu;
+      e2[s] = de[i + (UP ? 1 : 0)].y;  // e_{i-1}^2 going down, e_i^2 going up
+    }
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const int i = UP ? D - 1 - (s0 + s) : s0 + s;
+      const double pn = fma(dmu[s], p, -(e2[s] * pm));
+      out[i] = make_double2(pn, p);
+      pm = p;
+      p = pn;
+    }
+    const int e = __builtin_amdgcn_frexp_exp(p);
+    p = ldexp(p, -e);
+    pm = ldexp(pm, -e);
+  }
+}
+
+// Entries of the twisted-factorisation vector on one side of the twist index rt (z_rt = 1): z_i = -mult_i z_{i+1}
+// for i < rt (UP = false, multipliers e_i / D+_i in M[i].x) or z_i = -mult_i z_{i-1} for i > rt (UP = true,
+// e_{i-1} / D-_i); z_i goes to F[i].y, the sum of their squares to *ssq_out.  Whole groups of eight rows first
+// (constant offsets from one moving base, nothing conditional), then the rest row by row.
+template <bool UP>
+__device__ __forceinline__ void twisted_chain(double2* F, const double2* M, int rt, double* ssq_out) {
+  const int count = UP ? D - 1 - rt : rt;
+  double z = 1.0, ssq = 0.0;
+  if (!UP) F[rt].y = 1.0;
+  int s0 = 0;
+#pragma unroll 1
+  for (; s0 + 8 <= count; s0 += 8) {
+    const int i0 = UP ? rt + s0 + 1 : rt - s0 - 8;   // lowest row of the group
+    double mlt[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) mlt[s] = M[i0 + (UP ? s : 7 - s)].x;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      z = -mlt[s] * z;
+      F[i0 + (UP ? s : 7 - s)].y = z;
+      ssq = fma(z, z, ssq);
+    }
+  }
+#pragma unroll 1
+  for (; s0 < count; ++s0) {
+    const int i = UP ? rt + s0 + 1 : rt - s0 - 1;
+    z = -M[i].x * z;
+    F[i].y = z;
+    ssq = fma(z, z, ssq);
+  }
+  *ssq_out = ssq;
+}
+
 __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     const void* __restrict__ blocks, EoqBlockMap map, int dtype, int n, int k_pilot, double rank_thr, int r_max,
     int* __restrict__ fb_list, int* __restrict__ fb_count, double* __restrict__ lam_out, float* __restrict__ wfac,
@@ -775,6 +841,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   __shared__ double dT[D], eT[D], betaT[D];
   __shared__ double cW[(D / 4) * 6];  // inner products of the reflectors inside each group of four
   __shared__ double norm_s[EV_BATCH];
+  __shared__ double chain_s[EV_BATCH][2];  // sums of squares of the two halves of each vector
   __shared__ int twist_s[EV_BATCH];
   __shared__ double lam_s[D], atoms[D];
   __shared__ double scale_s[EOQ_RMAX_CAP];
@@ -810,8 +877,9 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   // them (u_1 = v_{4b+3} .. u_4 = v_{4b}): c21 c31 c32 c41 c42 c43; one row of 16 lanes per product
   {
     const int row = tid >> 4, l = tid & 15;
-#pragma unroll 1
-    for (int q = row; q < (D / 4) * 6; q += THREADS / 16) {
+#pragma unroll 4   // the products are independent: four in flight hide the LDS and reduction latencies
+    for (int t = 0; t < (D / 4) * 6 / (THREADS / 16); ++t) {
+      const int q = row + t * (THREADS / 16);
       const int bb = q / 6, pr = q - 6 * bb;
       const int a = (pr == 0) ? 2 : ((pr < 3) ? 3 : 4), b2 = (pr == 0) ? 1 : ((pr < 3) ? pr : pr - 2);
       const int ka = 4 * bb + 4 - a, kb = 4 * bb + 4 - b2;  // ka < kb
@@ -947,41 +1015,21 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
 #pragma unroll 1
   for (int b0 = 0; b0 < r; b0 += EV_BATCH) {
     __syncthreads();
-    // (1) minors: lane pair (top-down, bottom-up) per eigenvector; F[i] = (p_i, p_{i-1}), Bk[i] = (q_i, q_{i+1})
-    if (tid < 2 * EV_BATCH && b0 + (tid >> 1) < r) {
-      const int ev = tid >> 1, role = tid & 1;
-      const double mu = lam_s[b0 + ev] * sc;
-      double2* out = tw + (ev * 2 + role) * D;
-      double pm = 0.0, p = 1.0;
-#pragma unroll 1
-      for (int s0 = 0; s0 < D; s0 += 8) {
-        double dmu[8], e2[8];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          const int i = role ? D - 1 - (s0 + s) : s0 + s;
-          dmu[s] = de[i].x - mu;
-          e2[s] = de[i + role].y;  // e_{i-1}^2 going down, e_i^2 going up (de[D].y = 0)
-        }
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          const int i = role ? D - 1 - (s0 + s) : s0 + s;
-          const double pn = fma(dmu[s], p, -(e2[s] * pm));
-          out[i] = make_double2(pn, p);
-          pm = p;
-          p = pn;
-        }
-        const int e = __builtin_amdgcn_frexp_exp(p);  // the ratios are unchanged by a common factor
-        p = ldexp(p, -e);
-        pm = ldexp(pm, -e);
-      }
+    // (1) minors: wave 0 runs the top-down recurrences, wave 1 the bottom-up ones, one lane per eigenvector (the
+    // direction is then the same for a whole wave: constant offsets, no selects); F[i] = (p_i, p_{i-1}),
+    // Bk[i] = (q_i, q_{i+1})
+    if (wave < 2 && lane < EV_BATCH && b0 + lane < r) {
+      const double mu = lam_s[b0 + lane] * sc;
+      if (wave == 0) minors_sweep<false>(de, mu, tw + (lane * 2) * TW_STRIDE);
+      else minors_sweep<true>(de, mu, tw + (lane * 2 + 1) * TW_STRIDE);
     }
     __syncthreads();
     // (2) pivots, multipliers and twist index: 16 lanes per eigenvector, rows i = l + 16 m
     if (tid < 16 * EV_BATCH && b0 + (tid >> 4) < r) {
       const int ev = tid >> 4, l = tid & 15;
       const double mu = lam_s[b0 + ev] * sc;
-      double2* F = tw + ev * 2 * D;
-      double2* Bk = F + D;
+      double2* F = tw + ev * 2 * TW_STRIDE;
+      double2* Bk = F + TW_STRIDE;
       const double piv = 0x1.0p-100;  // smallest pivot magnitude (the matrix is scaled to norm <= 1)
       double best = INFINITY;
 #pragma unroll
@@ -1009,42 +1057,18 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       if (l == 0) twist_s[ev] = __double2loint(best) & 127;
     }
     __syncthreads();
-    // (3) the vector itself, upwards and downwards from the twist index; z_i goes to F[i].y
-    if (tid < 2 * EV_BATCH && b0 + (tid >> 1) < r) {
-      const int ev = tid >> 1, role = tid & 1;
-      double2* F = tw + ev * 2 * D;
-      const double2* Bk = F + D;
-      const int rt = twist_s[ev];
-      const int count = role ? D - 1 - rt : rt;
-      const int dir = role ? 1 : -1;
-      double z = 1.0, ssq = 0.0;
-      if (role) {
-        F[rt].y = 1.0;
-        ssq = 1.0;
-      }
-#pragma unroll 1
-      for (int s0 = 0; s0 < count; s0 += 4) {
-        double mlt[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const int i = min(max(rt + dir * (s0 + s + 1), 0), D - 1);
-          mlt[s] = role ? Bk[i].x : F[i].x;
-        }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const int i = rt + dir * (s0 + s + 1);
-          if (s0 + s < count) {
-            z = -mlt[s] * z;
-            F[i].y = z;
-            ssq = fma(z, z, ssq);
-          }
-        }
-      }
-      ssq = pair_sum(ssq);
-      if (role == 0) {
-        norm_s[ev] = ssq;
-        if (!(ssq > 0.0) || !isfinite(ssq)) atomicOr(&flag_s, EOQ_FLAG_NO_CONVERGE);
-      }
+    // (3) the vector itself, upwards (wave 0) and downwards (wave 1) from the twist index; z_i goes to F[i].y
+    if (wave < 2 && lane < EV_BATCH && b0 + lane < r) {
+      double2* F = tw + lane * 2 * TW_STRIDE;
+      const int rt = twist_s[lane];
+      if (wave == 0) twisted_chain<false>(F, F, rt, &chain_s[lane][0]);
+      else twisted_chain<true>(F, F + TW_STRIDE, rt, &chain_s[lane][1]);
+    }
+    __syncthreads();
+    if (tid < EV_BATCH && b0 + tid < r) {
+      const double ssq = 1.0 + chain_s[tid][0] + chain_s[tid][1];
+      norm_s[tid] = ssq;
+      if (!(ssq > 0.0) || !isfinite(ssq)) atomicOr(&flag_s, EOQ_FLAG_NO_CONVERGE);
     }
     __syncthreads();
     // (4) back-transformation v = H_0 H_1 ... H_125 z, four reflectors at a time: 16 lanes per eigenvector, 8
@@ -1054,7 +1078,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     if (tid < 16 * EV_BATCH) {
       const int ev = tid >> 4, l = tid & 15;
       const bool live = (b0 + ev < r);
-      const double2* F = tw + ev * 2 * D;
+      const double2* F = tw + ev * 2 * TW_STRIDE;
       double y[8];
       {
         const double ssq = live ? norm_s[ev] : 1.0;
