@@ -382,13 +382,15 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
   const ushort2v r = __builtin_elementwise_max(*reinterpret_cast<ushort2v*>(&a), *reinterpret_cast<ushort2v*>(&b));
   return *reinterpret_cast<const uint32_t*>(&r);
 }
-// byte K of x0 .. x3 -> one word
-template <int K>
-__device__ __forceinline__ uint32_t gather_bytes(int x0, int x1, int x2, int x3) {
-  constexpr uint32_t sel = 0x0c0c0000u | ((4u + K) << 8) | (uint32_t)K;
-  const uint32_t t01 = __builtin_amdgcn_perm((uint32_t)x1, (uint32_t)x0, sel);
-  const uint32_t t23 = __builtin_amdgcn_perm((uint32_t)x3, (uint32_t)x2, sel);
-  return t01 | (t23 << 16);
+// The four bytes of each of x0 .. x3, transposed: out[k] = bytes k of x0, x1, x2, x3 (x0 lowest).  Eight byte
+// permutes: pairs first (bytes 0/1 and 2/3 of two words interleaved), then the halves of the pairs.
+__device__ __forceinline__ void transpose_bytes(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3, uint32_t (&out)[4]) {
+  const uint32_t a01 = __builtin_amdgcn_perm(x1, x0, 0x05010400u), b01 = __builtin_amdgcn_perm(x1, x0, 0x07030602u);
+  const uint32_t a23 = __builtin_amdgcn_perm(x3, x2, 0x05010400u), b23 = __builtin_amdgcn_perm(x3, x2, 0x07030602u);
+  out[0] = __builtin_amdgcn_perm(a23, a01, 0x05040100u);
+  out[1] = __builtin_amdgcn_perm(a23, a01, 0x07060302u);
+  out[2] = __builtin_amdgcn_perm(b23, b01, 0x05040100u);
+  out[3] = __builtin_amdgcn_perm(b23, b01, 0x07060302u);
 }
 
 __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size_t tok, int n, unsigned char* pool, int tid,
@@ -433,23 +435,23 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size
       const int ef = max((int)(hmax >> 10), 1);               // biased exponent of the column maximum (subnormals: 1)
       const float scale = __int_as_float((171 - ef) << 23);   // 2^(29 - (ef - 15))
       if (q == 0) cexp[8 * m + c] = ef - 44;                  // one integer unit = 2^(ef - 15 - 29)
-      int i0[4]; int i1[4]; int i2[4]; int i3[4];
+      // I = sum_k d_k 256^k with balanced digits d_k in [-128, 127]: adding 128 to every digit place makes them the
+      // plain bytes of I + 0x80808080 (|I| < 2^30: no carry out of the top), and flipping the top bit of each byte
+      // takes the 128 off again, as a two's-complement byte.  The four planes are those bytes.
+      uint32_t dg[4];
       EOQ_SFOR(it, 4,
         const uint32_t w = (c >> 1) == 0 ? raw[it].x : ((c >> 1) == 1 ? raw[it].y : ((c >> 1) == 2 ? raw[it].z : raw[it].w));
         const uint16_t hb = (uint16_t)(w >> (16 * (c & 1)));
         const int I = (int)(half_bits_to_float(hb) * scale);   // truncation towards zero
-        const int r1 = I - __builtin_amdgcn_sbfe(I, 0, 8);     // multiple of 2^8
-        const int r2 = r1 - (__builtin_amdgcn_sbfe(r1, 8, 8) << 8);    // multiple of 2^16
-        i0[it] = I;
-        i1[it] = r1;
-        i2[it] = r2;
-        i3[it] = r2 - (__builtin_amdgcn_sbfe(r2, 16, 8) << 16);        // multiple of 2^24
+        dg[it] = ((uint32_t)I + 0x80808080u) ^ 0x80808080u;
       );
+      uint32_t pl[4];
+      transpose_bytes(dg[0], dg[1], dg[2], dg[3], pl);
       unsigned char* dst = pool + (8 * m + c) * GI_ROW + 4 * q;
-      *reinterpret_cast<uint32_t*>(dst) = gather_bytes<0>(i0[0], i0[1], i0[2], i0[3]);
-      *reinterpret_cast<uint32_t*>(dst + GI_PLANE) = gather_bytes<1>(i1[0], i1[1], i1[2], i1[3]);
-      *reinterpret_cast<uint32_t*>(dst + 2 * GI_PLANE) = gather_bytes<2>(i2[0], i2[1], i2[2], i2[3]);
-      *reinterpret_cast<uint32_t*>(dst + 3 * GI_PLANE) = gather_bytes<3>(i3[0], i3[1], i3[2], i3[3]);
+      *reinterpret_cast<uint32_t*>(dst) = pl[0];
+      *reinterpret_cast<uint32_t*>(dst + GI_PLANE) = pl[1];
+      *reinterpret_cast<uint32_t*>(dst + 2 * GI_PLANE) = pl[2];
+      *reinterpret_cast<uint32_t*>(dst + 3 * GI_PLANE) = pl[3];
     );
     if (t0 + GI_TOK < n) {  // next pass on its way during the products
 #pragma unroll
