@@ -876,27 +876,20 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   }
   __syncthreads();
   // inner products of the reflectors of each group {4b, .., 4b+3}, in the order the back-transformation applies
-  // them (u_1 = v_{4b+3} .. u_4 = v_{4b}): c21 c31 c32 c41 c42 c43; one row of 16 lanes per product
-  {
-    const int row = tid >> 4, l = tid & 15;
-#pragma unroll 4   // the products are independent: four in flight hide the LDS and reduction latencies
-    for (int t = 0; t < (D / 4) * 6 / (THREADS / 16); ++t) {
-      const int q = row + t * (THREADS / 16);
-      const int bb = q / 6, pr = q - 6 * bb;
-      const int a = (pr == 0) ? 2 : ((pr < 3) ? 3 : 4), b2 = (pr == 0) ? 1 : ((pr < 3) ? pr : pr - 2);
-      const int ka = 4 * bb + 4 - a, kb = 4 * bb + 4 - b2;  // ka < kb
-      const int roa = refl_off(ka) - (ka + 1), rob = refl_off(kb) - (kb + 1);
-      double acc = 0.0;
-#pragma unroll
-      for (int m = 0; m < 8; ++m) {
-        const int i = l + 16 * m;
-        const float ra = refl[min(max(roa + i, 0), REFL_LEN - 1)], rb = refl[min(max(rob + i, 0), REFL_LEN - 1)];
-        const bool in = (kb < D - 2 && i > kb);  // both factors masked: what lies outside a reflector is arbitrary
-        acc = fma(in ? (double)ra : 0.0, in ? (double)rb : 0.0, acc);
-      }
-      acc = row16_sum_uniform(acc);
-      if (l == 0) cW[q] = acc;
+  // them (u_1 = v_{4b+3} .. u_4 = v_{4b}): c21 c31 c32 c41 c42 c43; one product per lane, over the rows where both
+  // reflectors live (i > kb; what lies outside a reflector is arbitrary)
+  if (tid < (D / 4) * 6) {
+    const int q = tid, bb = q / 6, pr = q - 6 * bb;
+    const int a = (pr == 0) ? 2 : ((pr < 3) ? 3 : 4), b2 = (pr == 0) ? 1 : ((pr < 3) ? pr : pr - 2);
+    const int ka = 4 * bb + 4 - a, kb = 4 * bb + 4 - b2;  // ka < kb
+    const float* pa = refl + refl_off(ka) - (ka + 1);      // entry i of reflector ka at pa[i]
+    const float* pb = refl + refl_off(kb) - (kb + 1);
+    double acc = 0.0;
+    if (kb < D - 2) {
+#pragma unroll 4
+      for (int i = kb + 1; i < D; ++i) acc = fma((double)pa[i], (double)pb[i], acc);
     }
+    cW[q] = acc;
   }
 
   // ---- eigenvalues of T by Sturm-count multisection: lane pair j brackets the j-th smallest ----
