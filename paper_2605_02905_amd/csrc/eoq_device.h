@@ -81,8 +81,10 @@ __device__ __forceinline__ uint16_t double_to_half_bits(double x) {
   half_t h = (half_t)f;
   return *reinterpret_cast<uint16_t*>(&h);
 }
+// float -> binary16, round to nearest even, saturating at the largest finite value (one median-of-three, then the
+// conversion)
 __device__ __forceinline__ uint16_t float_to_half_bits(float f) {
-  f = fminf(fmaxf(f, -65504.0f), 65504.0f);
+  f = __builtin_amdgcn_fmed3f(f, -65504.0f, 65504.0f);
   half_t h = (half_t)f;
   return *reinterpret_cast<uint16_t*>(&h);
 }
