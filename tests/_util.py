@@ -84,7 +84,8 @@ def rel_fro(a: np.ndarray, b: np.ndarray) -> float:
 def compare_compress(blocks64: np.ndarray, rec, lam_gpu: np.ndarray, recs, bits: int, r_max: int = 32,
                      lowrank_tol: float = 5e-3):
     """Parity of eoq_compress against oracle records.  Returns a dict of statistics; asserts the bars:
-    ranks bit-exact, shrunk values within 1e-3 relative, code mismatches <= 0.1 % of entries."""
+    ranks bit-exact, eigenvalues within 1e-9 of the largest (the r_max largest within 1e-12), shrunk values within
+    1e-3 relative, code mismatches <= 0.1 % of entries."""
     B, n, d = blocks64.shape
     rank_g = rec.rank.cpu().numpy()
     rank_o = np.array([r.rank for r in recs])
@@ -101,11 +102,14 @@ def compare_compress(blocks64: np.ndarray, rec, lam_gpu: np.ndarray, recs, bits:
     norms_g = rec.norms.cpu().numpy().astype(np.float64)
     lfac_g = rec.lfac.cpu().numpy().astype(np.float64)
     rfac_g = rec.rfac.cpu().numpy().astype(np.float64)
-    stats = dict(max_phi_rel=0.0, max_sigma_rel=0.0, max_lam_rel=0.0, mismatches=0, entries=0, max_lowrank_abs=0.0,
+    stats = dict(max_phi_rel=0.0, max_sigma_rel=0.0, max_lam_rel=0.0, max_lam_top_rel=0.0, mismatches=0, entries=0, max_lowrank_abs=0.0,
                  norm_ulp_diffs=0, max_sweeps=int(stats_sweeps.max()), mean_sweeps=float(stats_sweeps.mean()))
     for b, r in enumerate(recs):
         lam_o = r.lam
         stats["max_lam_rel"] = max(stats["max_lam_rel"], float(np.max(np.abs(lam_gpu[b] - lam_o)) / lam_o[0]) if lam_o[0] > 0 else 0.0)
+        # the largest eigenvalues (every one that can be retained) feed the shrinker and the eigenvector solves
+        stats["max_lam_top_rel"] = max(stats["max_lam_top_rel"],
+                                       float(np.max(np.abs(lam_gpu[b][:r_max] - lam_o[:r_max])) / lam_o[0]) if lam_o[0] > 0 else 0.0)
         if r.rank:
             stats["max_phi_rel"] = max(stats["max_phi_rel"], float(np.max(np.abs(phi_g[b, :r.rank] - r.phi) / np.maximum(r.phi, 1e-300))))
             stats["max_sigma_rel"] = max(stats["max_sigma_rel"], float(np.max(np.abs(sig_g[b, :r.rank] - r.sigma) / r.sigma)))
@@ -120,6 +124,8 @@ def compare_compress(blocks64: np.ndarray, rec, lam_gpu: np.ndarray, recs, bits:
         dn = np.abs(norms_g[b] - r.rho16)
         stats["norm_ulp_diffs"] += int(np.count_nonzero(dn > 0))
         assert np.all(dn <= 2e-3 * np.maximum(r.rho16, 1e-30) + 1e-7), b
+    assert stats["max_lam_rel"] <= 1e-9, stats
+    assert stats["max_lam_top_rel"] <= 1e-12, stats
     assert stats["max_phi_rel"] <= 1e-3, stats
     assert stats["max_sigma_rel"] <= 1e-3, stats
     assert stats["mismatches"] <= 1e-3 * stats["entries"], stats
