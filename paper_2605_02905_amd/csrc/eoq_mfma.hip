@@ -1024,9 +1024,10 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
       Blo[kk].u = *reinterpret_cast<const uint4*>(pih + D * D + c * D + 16 * kk + 8 * hf);
     }
   }
-  float bnd[(1 << BITS) - 1];
-#pragma unroll
-  for (int i = 0; i < (1 << BITS) - 1; ++i) bnd[i] = tab[16 + i];
+  // the decision boundaries, held as one register vector: a plain array indexed by a selected constant can end up
+  // in scratch memory (the compiler turns a select of two elements into an element at a selected index)
+  float16v bnd;
+  EOQ_SFOR(i, 16, bnd[i] = (i < (1 << BITS) - 1) ? tab[16 + i] : 0.0f;);
 
   // factors of the block: W = V diag(phi/sigma) split into hi + lo, and V16^T.  Only the rows below the rank
   // rounded up to a multiple of 8 are ever multiplied with something that is not forced to zero (see Cneg)
@@ -1085,12 +1086,11 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
         const int cf_lane = (4 * hf * n + t0 + 32 * wave + l32) * 2;
         if constexpr (FQ) {
           // the stored coefficients of this token, negated: the next B operand
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
+          EOQ_SFOR(v, 16,
             const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
             const uint16_t c = __builtin_amdgcn_raw_buffer_load_b16(lbuf, cf_lane, (8 * (v >> 2) + (v & 3)) * n * 2, 0);
             Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(c ^ 0x8000u) : (uint16_t)0;
-          }
+          );
         } else {
           float16v Cacc;
 #pragma unroll

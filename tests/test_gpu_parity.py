@@ -417,6 +417,14 @@ def test_q4_shapes_rank0_and_clamp(n, B, r_max, rank_hi):
     _q4_case(blocks, 2, n, r_max, f"q4-n{n}-rmax{r_max}")
 
 
+@pytest.mark.parametrize("bits", [1, 4])
+def test_q4_with_the_other_code_widths(bits):
+    """4-bit factors under 1-bit and 4-bit residual codes (the encoder is compiled per width)."""
+    spec = synth.BlockSpec("q4bits", n=256, n_tensors=1, blocks_per_tensor=8, rank_lo=1, rank_hi=9)
+    blocks, _ = synth.make_blocks(spec, seed=43)
+    _q4_case(blocks, bits, 256, 32, f"q4-n256-b{bits}")
+
+
 def test_q4_argument_errors():
     ctx = eoq.Context(n=512, bits=2)
     x32 = torch.zeros(1, 512, 128, dtype=torch.float32, device=DEV)
