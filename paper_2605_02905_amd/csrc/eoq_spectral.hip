@@ -291,9 +291,10 @@ __device__ __forceinline__ int refl_off(int k) { return k * (D - 1) - (k * (k - 
 constexpr int REFL_LEN = (D - 1) * D / 2;  // 8128
 constexpr int GRID_POINTS = 256;           // first localisation: one Sturm count per lane on a uniform grid
 constexpr int MULTISECT_ITERS = 17;        // then trisection, two lanes per eigenvalue: 3^17 * 257 > 2^34.9
-constexpr int REFINE_COUNT = 32;           // the largest eigenvalues (all that can be retained) go on with eight lanes
-constexpr int REFINE_ITERS = 5;            // each, 9-section: 9^5 * 3^17 * 257 > 2^50 (the reduction itself is good to ~2^-48)
-static_assert(REFINE_COUNT * 8 == THREADS && REFINE_COUNT >= EOQ_RMAX_CAP, "eight lanes per refined eigenvalue");
+constexpr int REFINE_COUNT = 32;           // at most this many eigenvalues go on to full precision (the reduction
+                                           // itself is good to ~2^-48), with 256 / 32 = 8 lanes each or more
+constexpr int REFINE_KEEP = 48;            // brackets of the largest eigenvalues kept for that second phase
+static_assert(REFINE_COUNT * 8 == THREADS && REFINE_COUNT >= EOQ_RMAX_CAP && 2 * REFINE_KEEP <= D, "second phase layout");
 constexpr int EV_BATCH = 8;                // eigenvectors per twisted-factorisation pass
 // Twisted-factorisation scratch: per eigenvector of a batch two arrays of D pairs, F then Bk.  The arrays are D + 1
 // pairs apart: lanes that walk different arrays in step (one per array, same row) then fall into different banks;
@@ -954,29 +955,53 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       }
     }
     if (sub == 0) lam_s[D - 1 - j] = fmax(0.5 * (lo + hi), 0.0) / sc;   // descending order, unscaled
-    // The eigenvalues below the largest REFINE_COUNT stay at that width (3e-11 of the largest): they only enter sums
-    // and the bulk edge.  The others feed the twisted factorisations and the shrinker and are taken to full
-    // precision, eight lanes each: the interval is cut in nine at eight points x_s = lo + (s + 1) w and the new
-    // bounds are recomputed by every lane from the same expression, so the eight lanes stay identical.
-    __syncthreads();   // the grid counts in `atoms` are no longer read
-    if (sub == 0 && j >= D - REFINE_COUNT) {
-      atoms[2 * (j - (D - REFINE_COUNT))] = lo;
-      atoms[2 * (j - (D - REFINE_COUNT)) + 1] = hi;
-    }
-    __syncthreads();
+    // Most eigenvalues stay at that width (3e-11 of the largest): they only enter sums.  Full precision is for those
+    // that feed the twisted factorisations, the shrinker and the rank rule: with the rank rt that the eigenvalues
+    // at hand give, the rt + 1 largest (the retained ones and the first one below them) and the two of the bulk-edge
+    // estimate (Alg. 2 step 1: numbers k + 1 and 2k + 1).  They share the 256 lanes, G = 8 .. 64 lanes each: the
+    // interval is cut in G + 1 at the points x_s = lo + (s + 1) w and the new bounds are recomputed by every lane
+    // of a group from the same expression, so the lanes of a group stay identical.
+    __syncthreads();   // the grid counts in `atoms` are no longer read; every lam_s is written
     {
-      const int jj = tid >> 3, s8 = tid & 7, jr = D - REFINE_COUNT + jj;
-      double rlo = atoms[2 * jj], rhi = atoms[2 * jj + 1];
+      const int i_desc = D - 1 - j;
+      if (sub == 0 && i_desc < REFINE_KEEP) {
+        atoms[2 * i_desc] = lo;
+        atoms[2 * i_desc + 1] = hi;
+      }
+    }
+    int rt;
+    {
+      const double edge_coef = 1.0 / (cbrt(4.0) - 1.0);
+      const double lam_k1 = lam_s[k_pilot], lam_2k1 = lam_s[2 * k_pilot];
+      const double lam_plus = lam_k1 + edge_coef * (lam_k1 - lam_2k1);
+      rt = __syncthreads_count((tid < D && lam_s[tid] / lam_plus - 1.0 > rank_thr) ? 1 : 0);   // also orders `atoms`
+    }
+    {
+      // rt + 3 eigenvalues when they fit 32 groups, else the 32 largest (all that can be retained)
+      const bool wide = rt + 3 <= REFINE_COUNT && 2 * k_pilot < REFINE_KEEP;
+      const int count = wide ? rt + 3 : REFINE_COUNT;
+      const int lg = !wide ? 3 : (count > 16 ? 3 : (count > 8 ? 4 : (count > 4 ? 5 : 6)));   // log2 of the group size
+      const int G = 1 << lg;
+      const int iters = (lg == 3) ? 5 : ((lg == 4) ? 4 : 3);   // (G + 1)^iters * 3^17 * 257 > 2^49
+      const double inv = (lg == 3) ? 1.0 / 9.0 : ((lg == 4) ? 1.0 / 17.0 : ((lg == 5) ? 1.0 / 33.0 : 1.0 / 65.0));
+      const int jj = tid >> lg, sg = tid & (G - 1);
+      const bool act = jj < count;
+      // descending index of this group's eigenvalue
+      const int i_desc = !act ? 0 : (!wide ? jj : (jj <= rt ? jj : (jj == rt + 1 ? k_pilot : 2 * k_pilot)));
+      const int jr = D - 1 - i_desc;
+      double rlo = atoms[2 * i_desc], rhi = atoms[2 * i_desc + 1];
+      const int shift = (tid & 63) & ~(G - 1);
+      const unsigned long long gmask = (lg == 6) ? ~0ull : ((1ull << G) - 1ull);
 #pragma unroll 1
-      for (int it = 0; it < REFINE_ITERS; ++it) {
-        const double w = (rhi - rlo) * (1.0 / 9.0);
-        const int c = sturm_count(sde, fma((double)(s8 + 1), w, rlo));
-        const unsigned long long below = __ballot(c <= jr);   // points not above the eigenvalue: a prefix of the eight
-        const int mcount = __popc((unsigned)(below >> (tid & 56)) & 0xFFu);
-        rhi = (mcount == 8) ? rhi : fma((double)(mcount + 1), w, rlo);
+      for (int it = 0; it < iters; ++it) {
+        const double w = (rhi - rlo) * inv;
+        const int c = sturm_count(sde, fma((double)(sg + 1), w, rlo));
+        const unsigned long long below = __ballot(c <= jr);   // points not above the eigenvalue: a prefix of the group
+        const int mcount = __popcll((below >> shift) & gmask);
+        rhi = (mcount == G) ? rhi : fma((double)(mcount + 1), w, rlo);
         rlo = fma((double)mcount, w, rlo);
       }
-      if (s8 == 0) lam_s[D - 1 - jr] = fmax(0.5 * (rlo + rhi), 0.0) / sc;
+      if (act && sg == 0) lam_s[i_desc] = fmax(0.5 * (rlo + rhi), 0.0) / sc;
     }
   }
   __syncthreads();
