@@ -151,7 +151,9 @@ eoq_status eoq_codebook(const eoq_ctx* ctx, float* host_centroids, float* host_b
  *              except lfac/rfac rows >= rank[b].
  *   workspace  DEVICE, >= eoq_workspace_bytes(ctx, B) bytes.  After the call
  *              completes its first B*d doubles hold every block's Gram
- *              eigenvalues sigma_i^2 in descending order (diagnostic).
+ *              eigenvalues sigma_i^2 in descending order (diagnostic: the
+ *              retained ones and the next are resolved to rounding level,
+ *              the others to within 1e-10 of the largest).
  *   hip_stream hipStream_t (NULL = default stream).
  */
 eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B,
