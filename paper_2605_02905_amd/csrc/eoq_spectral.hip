@@ -676,6 +676,92 @@ __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, doub
   }
 }
 
+// Sum over eight consecutive lanes (an aligned group of a DPP row): butterfly of commutative pair sums
+// (lane^1, lane^2, 7-lane), bit-identical in the eight lanes.
+__device__ __forceinline__ double oct_sum_uniform(double v) {
+  v += dpp_mov<0xB1>(v);
+  v += dpp_mov<0x4E>(v);
+  v += dpp_mov<0x141>(v);
+  return v;
+}
+
+// The last 30 steps of the reduction (k = 96 .. 125) on the trailing 32 x 32 matrix, by ONE wave: lane (ly, lx) =
+// (lane / 8, lane % 8) holds T[a][b] = M[ly + 8 a][lx + 8 b], a, b < 4 (rows and columns counted from 96).  With
+// the four waves on it a step of this size costs as many instructions per wave as a step on the full matrix
+// (reductions, exchanges and two barriers); here the other three waves issue nothing, the exchanges go through
+// LDS without a barrier (operations of one wave complete in order) and the sums run over eight lanes.
+// Steps 8 AO .. 8 AO + 7 (the last stage stops after local row 29): rows and columns below 8 AO are dead.
+template <int AO>
+__device__ __forceinline__ void tail32_stage(double (&T)[16], int lane, double* vb, double* pb, float* refl, double* dT,
+                                             double* eT, double* betaT) {
+  const int ly = lane >> 3, lx = lane & 7;
+  constexpr int KEND = (AO == 3) ? 6 : 8;
+#pragma unroll 1
+  for (int kk = 0; kk < KEND; ++kk) {
+    const int kq = 8 * AO + kk, k = 96 + kq;
+    // ---- v, beta from row kq: every group of eight lanes runs the arithmetic on its own row, the owner stores ----
+    const bool owner = (ly == kk);
+    double x[4];
+    EOQ_SFOR(b, 4, x[b] = (b >= AO) ? T[AO * 4 + b] : 0.0;);
+    if (owner && lx == kk) dT[k] = x[AO];
+    x[AO] = (lx > kk) ? x[AO] : 0.0;   // columns lx + 8 b > kq only
+    double ss = 0.0;
+    EOQ_SFOR(b, 4, if constexpr (b >= AO) ss = fma(x[b], x[b], ss););
+    ss = oct_sum_uniform(ss);
+    double xsel = x[AO];
+    if constexpr (AO < 3) xsel = (kk == 7) ? x[AO + 1] : xsel;
+    const double x0 = readlane_f64(xsel, 8 * kk + ((kk + 1) & 7));   // M[kq][kq + 1]
+    double alpha = 0.0, beta = 0.0;
+    if (ss > 0x1.0p-960) {
+      const double sigma = newton_sqrt(ss);
+      alpha = (x0 >= 0.0) ? -sigma : sigma;
+      beta = newton_rcp(fma(sigma, fabs(x0), ss));
+    }
+    if (owner) {
+      EOQ_SFOR(b, 4,
+        const int c = lx + 8 * b;
+        const double v = (b >= AO) ? x[b] - ((c == kq + 1) ? alpha : 0.0) : 0.0;
+        vb[c] = v;
+        if (b >= AO && c > kq) refl[refl_off(k) + c - kq - 1] = (float)v;
+      );
+      if (lx == 0) {
+        eT[k] = alpha;
+        betaT[k] = beta;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();   // one wave: its LDS operations complete in order
+    const double bq = readlane_f64(beta, 8 * kk);
+    double vc[4], vr[4];
+    EOQ_SFOR(b, 4, vc[b] = (b >= AO) ? vb[lx + 8 * b] : 0.0;);
+    EOQ_SFOR(a, 4, vr[a] = (a >= AO) ? vb[ly + 8 * a] : 0.0;);
+    // ---- p = beta M v: row sums over the eight lanes of a group; the column view goes through LDS ----
+    double pr[4];
+    EOQ_SFOR(a, 4,
+      if constexpr (a >= AO) {
+        double acc = 0.0;
+        EOQ_SFOR(b, 4, if constexpr (b >= AO) acc = fma(T[a * 4 + b], vc[b], acc););
+        pr[a] = bq * oct_sum_uniform(acc);
+      } else {
+        pr[a] = 0.0;
+      });
+    if (lx == 0) { EOQ_SFOR(a, 4, if constexpr (a >= AO) pb[ly + 8 * a] = pr[a];); }
+    __builtin_amdgcn_wave_barrier();
+    double pc[4];
+    EOQ_SFOR(b, 4, pc[b] = (b >= AO) ? pb[lx + 8 * b] : 0.0;);
+    double dl = 0.0;
+    EOQ_SFOR(b, 4, if constexpr (b >= AO) dl = fma(vc[b], pc[b], dl););
+    const double K = 0.5 * bq * oct_sum_uniform(dl);
+    // ---- M <- M - v w^T - w v^T, w = p - K v ----
+    double wc[4], wr[4];
+    EOQ_SFOR(b, 4, wc[b] = (b >= AO) ? fma(-K, vc[b], pc[b]) : 0.0;);
+    EOQ_SFOR(a, 4, wr[a] = (a >= AO) ? fma(-K, vr[a], pr[a]) : 0.0;);
+    EOQ_SFOR(e, 16,
+      if constexpr ((e >> 2) >= AO && (e & 3) >= AO)
+        T[e] = fma(-vr[e >> 2], wc[e & 3], fma(-wr[e >> 2], vc[e & 3], T[e])););
+    __builtin_amdgcn_wave_barrier();   // vb and pb are rewritten by the next step
+  }
+}
+
 // Number of eigenvalues of the (scaled) tridiagonal matrix below x: sign changes of the leading principal minors
 // p_i(x) = (d_i - x) p_{i-1} - e_{i-1}^2 p_{i-2}.  de[2 i] = d_i, de[2 i + 1] = e_{i-1}^2 (e_{-1} = 0), read from
 // global memory with wave-uniform addresses (scalar loads: the operands cost no vector or LDS bandwidth).
@@ -868,12 +954,25 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     else
       gram_cyclic(blocks, dtype, map.in_base(blk), (size_t)map.token_stride, n, reinterpret_cast<float*>(u1), tid, A);
     __syncthreads();  // the pool changes hands
-    EOQ_SFOR(s, 8, householder_stage<s>(A, tid, vbuf, pbuf, refl, dT, eT, betaT););
-    // the last 2x2 block of T: rows and columns 126, 127 sit in the sub-tile (7, 7) of lanes ty, tx >= 14
-    const int ty = tid >> 4, tx = tid & 15;
-    if (ty == 14 && tx == 14) dT[D - 2] = A[63];
-    if (ty == 15 && tx == 14) eT[D - 2] = A[63];
-    if (ty == 15 && tx == 15) dT[D - 1] = A[63];
+    EOQ_SFOR(s, 6, householder_stage<s>(A, tid, vbuf, pbuf, refl, dT, eT, betaT););
+    // the trailing 32 x 32 matrix (rows and columns 96 .. 127: sub-tiles a, b = 6, 7 of every lane) changes hands:
+    // through LDS into the 64 lanes of wave 0, which finishes the reduction alone
+    double* Ms = reinterpret_cast<double*>(u1);   // [32][33]
+    {
+      const int ty = tid >> 4, tx = tid & 15;
+      EOQ_SFOR(a, 2, EOQ_SFOR(b, 2, Ms[(ty + 16 * a) * 33 + tx + 16 * b] = A[(6 + a) * 8 + 6 + b];););
+    }
+    __syncthreads();
+    if (wave == 0) {
+      const int ly = lane >> 3, lx = lane & 7;
+      double T[16];
+      EOQ_SFOR(e, 16, T[e] = Ms[(ly + 8 * (e >> 2)) * 33 + lx + 8 * (e & 3)];);
+      EOQ_SFOR(ao, 4, tail32_stage<ao>(T, lane, vbuf[0], pbuf, refl, dT, eT, betaT););
+      // the last 2x2 block of T: rows and columns 126, 127 = local 30, 31 = (ly, lx) in {6, 7}, a = b = 3
+      if (ly == 6 && lx == 6) dT[D - 2] = T[15];
+      if (ly == 7 && lx == 6) eT[D - 2] = T[15];
+      if (ly == 7 && lx == 7) dT[D - 1] = T[15];
+    }
   }
   __syncthreads();
   // inner products of the reflectors of each group {4b, .., 4b+3}, in the order the back-transformation applies
