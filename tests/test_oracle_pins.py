@@ -237,25 +237,37 @@ def test_rank_threshold_is_strict_and_relative():
 
 
 # ------------------------------------------------ Alg. 2 Step 2: imputation
-def test_imputation_reproduces_a_square_root_edge():
-    k, r = 11, 3
-    L, c = 50.0, 0.2
+def test_imputation_follows_the_square_root_edge_law_exactly():
+    """Alg. 2 Step 2 is the square-root edge law lam_j ~ L - c (j-1)^{2/3} of the noise bulk, extrapolated from its
+    (k+1)-th and (2k+1)-th atoms.  On a spectrum that obeys the law exactly -- r outliers in front, noise atom j
+    (1-based) at L - c (j-1)^{2/3}, so the first noise atom sits on the edge L -- the printed rule must return
+    L - c j^{2/3} for j = 1..k: imputed atom j is the true atom j+1 (the printed indices, kept as they are), whatever
+    r, L and c.  This is the closed form of the law, not the rule's own expression; reading either eigenvalue one
+    position off misses it by far more than the bar."""
     N = 128
-    noise = L - c * np.arange(0, N - r, dtype=float) ** (2.0 / 3.0)     # noise atom j (1-based) at (j-1)... see below
-    # build an observed spectrum: r outliers, then noise atoms whose 1-based index j sits at offset j^{2/3}
-    jj = np.arange(1, N - r + 1, dtype=float)
-    noise = L - c * jj ** (2.0 / 3.0)
-    lam = np.r_[[500.0, 300.0, 200.0], noise]
-    atoms = oracle.impute_noise_spectrum(lam, r, k)
-    assert atoms.shape == (N - r,)
-    # the printed rule extrapolates from atoms k+1 and 2k+1 with offsets (k, 2k): atom j is placed at
-    # lam_{k+r+1} + c' (k^{2/3} - j^{2/3}); check the closed form and that untouched atoms are copied
-    a, b = lam[k + r], lam[2 * k + r]
-    for j in range(1, k + 1):
-        assert abs(atoms[j - 1] - (a + (1 - (j / k) ** (2 / 3)) * oracle.EDGE_COEF * (a - b))) < 1e-12
-    assert np.array_equal(atoms[k:], lam[r + k:])
-    assert abs(atoms[k - 1] - lam[k + r]) < 1e-12               # j = k reproduces lam_{k+r+1} (as printed)
-    assert np.all(np.diff(atoms[:k]) < 0)
+    for k, r, L, c in [(11, 3, 50.0, 0.2), (11, 0, 7.0, 0.01), (7, 5, 1e4, 30.0), (11, 32, 2.5, 0.004)]:
+        jj = np.arange(1, N - r + 1, dtype=float)
+        noise = L - c * (jj - 1.0) ** (2.0 / 3.0)
+        lam = np.r_[L * (10.0 + np.arange(r, 0, -1)), noise]
+        atoms = oracle.impute_noise_spectrum(lam, r, k)
+        assert atoms.shape == (N - r,)
+        want = L - c * np.arange(1, k + 1, dtype=float) ** (2.0 / 3.0)
+        assert np.max(np.abs(atoms[:k] - want)) < 1e-12 * L
+        assert np.max(np.abs(atoms[:k] - noise[1:k + 1])) < 1e-12 * L       # imputed atom j = true atom j + 1
+        assert np.array_equal(atoms[k:], lam[r + k:])                        # the rest is copied
+        # non-increasing; the single tie is atom k, which the printed rule places on the first copied atom
+        dd = np.diff(atoms)
+        assert np.all(dd[:k - 1] < 0) and abs(dd[k - 1]) < 1e-12 * L and np.all(dd[k:] < 0)
+        # the same rule fed with a neighbouring eigenvalue (an off-by-one in either index, or r forgotten) is off by
+        # more than 1e-3 c in some atom
+        def rule(a, b):
+            j = np.arange(1, k + 1, dtype=float)
+            return a + (1.0 - (j / k) ** (2.0 / 3.0)) * oracle.EDGE_COEF * (a - b)
+        for da, db in [(-1, 0), (1, 0), (0, -1), (0, 1), (-1, -1), (1, 1)]:
+            wrong = rule(lam[k + r + da], lam[2 * k + r + db])
+            assert np.max(np.abs(wrong - want)) > 1e-3 * c, (k, r, da, db)
+        if r:
+            assert np.max(np.abs(rule(lam[k], lam[2 * k]) - want)) > 1e-3 * c
 
 
 # --------------------------------------------------- Alg. 2 Step 3: shrinker
@@ -286,6 +298,57 @@ def test_shrinker_matches_white_noise_closed_form_and_true_overlaps():
     # the two overlaps differ by much more than the tolerance, so a swapped labelling fails
     assert np.all(np.array(rows)[:, 9:12].mean(0) + 0.0 < 0.01)
     assert (es.a2 - es.a1).min() > 0.015
+
+
+def _white_noise_closed_forms(y, n, d):
+    """Textbook white-noise (A = B = I) quantities for an observed singular value y of an n x d matrix, n >= d, with
+    unit-variance noise: the signal strength x behind y, the asymptotic overlaps on the long side (left vectors, R^n)
+    and on the short side (right vectors, R^d), with beta = d / n and everything in units of sqrt(n):
+      y^2 = (x^2 + 1)(x^2 + beta) / x^2,   a_long = (x^4 - beta)/(x^4 + x^2),   a_short = (x^4 - beta)/(x^4 + beta x^2)."""
+    beta = d / n
+    y2 = y * y / n
+    x2 = 0.5 * ((y2 - beta - 1.0) + np.sqrt((y2 - beta - 1.0) ** 2 - 4.0 * beta))
+    a_long = (x2 * x2 - beta) / (x2 * x2 + x2)
+    a_short = (x2 * x2 - beta) / (x2 * x2 + beta * x2)
+    return np.sqrt(x2 * n), a_long, a_short
+
+
+def test_operator_and_nuclear_shrinkers_match_their_white_noise_closed_forms():
+    """Eq. (shrinkers), cases 2 and 3, in the white-noise special case where strength and overlaps have closed forms:
+    operator  x sqrt(a_long / a_short)  (the long side has the smaller overlap), nuclear
+    x (sqrt(a_long a_short) - sqrt((1 - a_long)(1 - a_short))).  Also what holds for any spectrum:
+    phi_op <= d_hat, phi_nuc <= phi_fro <= phi_op, and all three share d_hat, a_1, a_2."""
+    n, d = 512, 128
+    ratios = {"operator": [], "nuclear": []}
+    for seed in range(24):
+        rng = np.random.default_rng(seed)
+        S, _, _ = _spiked(rng, n, d, (6.0, 4.0, 2.5))
+        fro = oracle.eoptshrink(S)
+        x, a_long, a_short = _white_noise_closed_forms(fro.sigma, n, d)
+        closed = {"operator": x * np.sqrt(a_long / a_short),
+                  "nuclear": x * (np.sqrt(a_long * a_short) - np.sqrt((1 - a_long) * (1 - a_short)))}
+        # the closed forms themselves reproduce the Frobenius pin of the test above
+        y = fro.sigma
+        assert np.allclose(x * np.sqrt(a_long * a_short), np.sqrt((y ** 2 - n - d) ** 2 - 4 * n * d) / y, rtol=1e-12)
+        for loss in ("operator", "nuclear"):
+            es = oracle.eoptshrink(S, loss=loss)
+            assert es.rank == 3 and es.flags == 0
+            assert np.array_equal(es.d_hat, fro.d_hat) and np.array_equal(es.a1, fro.a1) and np.array_equal(es.a2, fro.a2)
+            ratios[loss].append(es.phi / closed[loss])
+            if loss == "operator":
+                assert np.all(es.phi <= es.d_hat) and np.all(es.phi >= fro.phi)
+                # the printed ratio is min/max: with the overlaps swapped or the root dropped it moves by several percent
+                assert np.all(np.abs(es.phi / (es.d_hat * np.sqrt(es.a1 / es.a2)) - 1.0) < 1e-12) and np.all(es.a1 < es.a2)
+            else:
+                assert np.all(es.phi <= fro.phi) and np.all(es.phi > 0)
+    for loss in ratios:
+        m = np.mean(ratios[loss], axis=0)
+        assert np.all(np.abs(m - 1.0) < 0.008), (loss, m)
+    # a component whose overlaps are small gets a negative nuclear expression: shrunk to zero, not below
+    phi, dh, a1, a2, ok = oracle.shrink(1.02 * 1152.0, np.linspace(1152.0, 100.0, 125), 512, 128, "nuclear")
+    assert ok and phi == 0.0 and a1 * a2 < (1 - a1) * (1 - a2)
+    with pytest.raises(ValueError):
+        oracle.shrink(2000.0, np.linspace(1152.0, 100.0, 125), 512, 128, "huber")
 
 
 def test_shrinker_tall_and_wide_blocks_agree():
