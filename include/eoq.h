@@ -40,10 +40,14 @@ typedef enum {
 
 typedef enum { EOQ_F16 = 0, EOQ_F32 = 1 } eoq_dtype;
 
+/* Loss whose optimal shrinker Alg. 2 Step 3 evaluates (Eq. (shrinkers)); the paper's experiments use the first. */
+typedef enum { EOQ_LOSS_FROBENIUS = 0, EOQ_LOSS_OPERATOR = 1, EOQ_LOSS_NUCLEAR = 2 } eoq_loss;
+
 /* Flag bits of eoq_packed.flags[b]. */
 #define EOQ_FLAG_RANK_CLAMPED 1u /* estimated rank exceeded r_max and was cut to r_max */
 #define EOQ_FLAG_SHRINK_GUARD 2u /* a D-transform estimate was degenerate; that component got phi = 0 */
 #define EOQ_FLAG_NO_CONVERGE  4u /* the eigensolver hit its sweep limit or produced a non-finite vector */
+#define EOQ_FLAG_NONFINITE    16u /* the block holds an Inf or NaN entry: it is stored with rank 0, its other outputs are meaningless */
 #define EOQ_FLAG_SWEEPS_SHIFT 8  /* bits 8..15: Jacobi sweeps run on this block (0: tridiagonal solver) (diagnostic) */
 
 /*
@@ -153,7 +157,7 @@ eoq_status eoq_codebook(const eoq_ctx* ctx, float* host_centroids, float* host_b
  *              completes its first B*d doubles hold every block's Gram
  *              eigenvalues sigma_i^2 in descending order (diagnostic: the
  *              retained ones and the next are resolved to rounding level,
- *              the others to within 1e-10 of the largest).
+ *              the others to within 1e-9 of the largest).
  *   hip_stream hipStream_t (NULL = default stream).
  */
 eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B,
@@ -309,6 +313,16 @@ eoq_status eoq_attend_stream(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, int
 eoq_status eoq_set_solver(eoq_ctx* ctx, int solver);
 
 /*
+ * Loss function L of Alg. 2 (REQUIRE, Step 3): which case of Eq. (shrinkers) turns the D-transform estimates d, a_1,
+ * a_2 of a retained component into its shrunk singular value: Frobenius d sqrt(a_1 a_2) (default; Remark 3.1),
+ * operator norm d sqrt(min(a_1, a_2) / max(a_1, a_2)), nuclear norm d (sqrt(a_1 a_2) - sqrt((1 - a_1)(1 - a_2))).
+ * For the last two the overlap estimates are clipped to [0, 1] first; every result is clipped to [0, sigma_i], so a
+ * component whose nuclear-norm value would be negative is stored with phi = 0.  Rank, eigenvalues and vectors do not
+ * depend on the loss.  Applies to the eoq_compress* calls that follow.  Other values: EOQ_ERR_UNSUPPORTED.
+ */
+eoq_status eoq_set_loss(eoq_ctx* ctx, eoq_loss loss);
+
+/*
  * Per-kernel timing for benchmarks (not part of the paper's method).  With profiling enabled every
  * hot call records HIP events on its stream around each kernel it launches; eoq_stage_ms waits for
  * those events and returns the duration, in milliseconds, of the kernels of the most recent
@@ -319,6 +333,23 @@ eoq_status eoq_set_solver(eoq_ctx* ctx, int solver);
  */
 eoq_status eoq_profile(eoq_ctx* ctx, int enable);
 eoq_status eoq_stage_ms(eoq_ctx* ctx, float* out);
+
+/*
+ * Measured ceilings of the device, for benchmark reports (not part of the paper's method): runs one micro-benchmark
+ * and waits for it.  kind 0: plain copy of the first half of `device_buf` onto its second half (16-byte accesses);
+ * 1: independent double-precision FMA chains on the vector ALUs; 2 / 3 / 4: chains of the matrix instructions the
+ * kernels use (f16 32x32x16, i8 16x16x64, f64 16x16x4); 5: 32-bit vector instructions; 10..15: two of these streams
+ * side by side on the two waves of every SIMD (10: f64 matrix + f64 FMA, 11: i8 matrix + 32-bit vector, 12: f64 matrix
+ * + 32-bit vector, 13: f64 FMA + 32-bit vector, 14: f16 matrix + f64 FMA, 15: i8 matrix + f64 FMA); 21 / 23 / 24 / 25:
+ * stream 1 / 3 / 4 / 5 on one wave per SIMD only; 31..34 / 41..44: the f64 FMA / 32-bit vector stream on 1..4 waves
+ * per SIMD (the first wave's work in out[1], the others' in out[2]).  `iters` is the loop count per wave (kinds >= 1).
+ *   device_buf  DEVICE scratch, 16-byte aligned, buf_bytes >= 64 (kind 0 moves buf_bytes/2 in each direction).
+ *   out         HOST, 4 doubles: milliseconds of one launch; work of the first stream (bytes moved for kind 0, flops
+ *               or integer operations, wave instructions for the 32-bit vector stream); work of the second stream;
+ *               compute units of the device.
+ * Allocates two events, runs on the default stream and synchronises: not a hot call.
+ */
+eoq_status eoq_ceiling(eoq_ctx* ctx, int kind, void* device_buf, size_t buf_bytes, int iters, double* out);
 
 /* Reason for the last error on this context (HOST string owned by the context); "" if none. */
 const char* eoq_last_error(const eoq_ctx* ctx);

@@ -1,5 +1,5 @@
 // Host side of the eOptShrinkQ library: context, table construction, argument
-// checks and the C ABI.  Kernels live in eoq_kernels.hip.
+// checks and the C ABI.  The kernels live in the other .hip files of this folder (see eoq_internal.h).
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -142,6 +142,7 @@ EoqLaunch make_launch(const eoq_ctx* ctx, void* stream) {
   L.stream = static_cast<hipStream_t>(stream);
   L.ev = ctx->profile ? ctx->ev : nullptr;
   L.solver = ctx->solver;
+  L.loss = ctx->loss;
   L.map = eoq_dense_map(ctx->n);
   return L;
 }
@@ -608,6 +609,15 @@ eoq_status eoq_set_solver(eoq_ctx* ctx, int solver) {
   ctx->err.clear();
   if (solver != 0 && solver != 1) return fail(ctx, EOQ_ERR_UNSUPPORTED, "solver must be 0 or 1");
   ctx->solver = solver;
+  return EOQ_OK;
+}
+
+eoq_status eoq_set_loss(eoq_ctx* ctx, eoq_loss loss) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (loss != EOQ_LOSS_FROBENIUS && loss != EOQ_LOSS_OPERATOR && loss != EOQ_LOSS_NUCLEAR)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "loss must be EOQ_LOSS_FROBENIUS, EOQ_LOSS_OPERATOR or EOQ_LOSS_NUCLEAR");
+  ctx->loss = (int)loss;
   return EOQ_OK;
 }
 

@@ -33,6 +33,7 @@ struct eoq_ctx {
   uint16_t* d_phih = nullptr;    // device binary16: Phi hi [i][j], Phi lo [i][j]
   std::string err;
   double gauss16[8] = {};  // Lloyd-Max magnitudes of N(0,1) at 16 levels: start of the per-block factor codebooks
+  int loss = 0;    // eoq_loss: which case of Eq. (shrinkers) Alg. 2 Step 3 evaluates
   int solver = 0;  // 0: tridiagonal eigensolver with Jacobi for repeated eigenvalues, 1: Jacobi for every block
   // optional per-kernel timing: events [2*i], [2*i+1] bracket stage i (spectral, encode, decode, scores, attend,
   // softmax)
@@ -69,6 +70,7 @@ struct EoqLaunch {
   hipStream_t stream;
   const hipEvent_t* ev;  // null unless profiling
   int solver;
+  int loss;
 };
 
 // Workspace layout for B blocks: lam[B][128] f64, then wfac[B][r_max][128] f32 (right singular vectors

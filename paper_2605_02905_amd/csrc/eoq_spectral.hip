@@ -61,7 +61,7 @@ __device__ __forceinline__ void gram_tile(const void* __restrict__ blocks, int d
 // bits, returns the (clamped) rank to every lane.  Must be called by all 256 lanes.
 // ---------------------------------------------------------------------------------------------
 __device__ int rank_and_shrink(const double* lam_s, double* atoms, double* scale_s, unsigned* flag_s, int n, int k,
-                               double rank_thr, int r_max, size_t blk, size_t slot, double* __restrict__ lam_out,
+                               double rank_thr, int r_max, int loss, size_t blk, size_t slot, double* __restrict__ lam_out,
                                float* __restrict__ phi_out, float* __restrict__ sigma_out) {
   const int tid = threadIdx.x;
   if (tid < D) lam_out[blk * D + tid] = lam_s[tid];
@@ -72,6 +72,7 @@ __device__ int rank_and_shrink(const double* lam_s, double* atoms, double* scale
   const double lam_plus = lam_k1 + edge_coef * (lam_k1 - lam_2k1);
   const int above = (tid < D) ? ((lam_s[tid] / lam_plus - 1.0 > rank_thr) ? 1 : 0) : 0;
   int r = __syncthreads_count(above);
+  if (*flag_s & EOQ_FLAG_NONFINITE) r = 0;   // Inf or NaN in the block (set by the Gram stage, before several barriers)
   if (r > r_max) {
     r = r_max;
     if (tid == 0) atomicOr(flag_s, EOQ_FLAG_RANK_CLAMPED);
@@ -92,7 +93,7 @@ __device__ int rank_and_shrink(const double* lam_s, double* atoms, double* scale
   }
   __syncthreads();
 
-  // Step 3: Stieltjes transforms of the noise measure at each outlier, D-transform, Frobenius shrinker
+  // Step 3: Stieltjes transforms of the noise measure at each outlier, D-transform, shrinker of the chosen loss
   {
     const int wave = tid >> 6, lane = tid & 63;
     const double beta = (n >= D) ? (double)D / (double)n : (double)n / (double)D;
@@ -117,11 +118,24 @@ __device__ int rank_and_shrink(const double* lam_s, double* atoms, double* scale
         double phi = 0.0;
         bool ok = isfinite(T) && isfinite(dT) && T > 0.0 && dT < 0.0;
         if (ok) {
-          // phi = d sqrt(a_1 a_2) with d = T^{-1/2}, a_x = m_x / (d^2 T')
+          // d = T^{-1/2}, a_x = m_x / (d^2 T'); Eq. (shrinkers): Frobenius d sqrt(a_1 a_2), operator
+          // d sqrt(min(a)/max(a)), nuclear d (sqrt(a_1 a_2) - sqrt((1 - a_1)(1 - a_2))), the overlaps clipped to [0, 1]
+          // before the last two take their roots
           const double dh = 1.0 / sqrt(T);
           const double a1 = m_l / (dh * dh * dT), a2 = m_s / (dh * dh * dT);
-          phi = dh * sqrt(a1 * a2);
-          ok = isfinite(phi);
+          if (loss == EOQ_LOSS_FROBENIUS) {
+            phi = dh * sqrt(a1 * a2);
+          } else {
+            ok = isfinite(a1) && isfinite(a2);
+            const double c1 = fmin(fmax(a1, 0.0), 1.0), c2 = fmin(fmax(a2, 0.0), 1.0);
+            if (loss == EOQ_LOSS_OPERATOR) {
+              const double hi = fmax(c1, c2);
+              phi = (hi > 0.0) ? dh * sqrt(fmin(c1, c2) / hi) : 0.0;
+            } else {
+              phi = dh * (sqrt(c1 * c2) - sqrt((1.0 - c1) * (1.0 - c2)));
+            }
+          }
+          ok = ok && isfinite(phi);
           if (ok) phi = fmin(fmax(phi, 0.0), sig);
         }
         if (!ok) {
@@ -152,7 +166,7 @@ constexpr double JACOBI_TOL = 5e-14;  // a pair is orthogonal when |<a_p,a_q>| <
 // With `list` non-null the workgroups walk the block numbers list[0 .. *count) (grid-stride); otherwise
 // workgroup b handles block b.
 __global__ __launch_bounds__(THREADS) void eoq_spectral_jacobi_kernel(
-    const void* __restrict__ blocks, EoqBlockMap map, int dtype, int n, int k, double rank_thr, int r_max, int64_t B,
+    const void* __restrict__ blocks, EoqBlockMap map, int dtype, int n, int k, double rank_thr, int r_max, int loss, int64_t B,
     const int* __restrict__ list, const int* __restrict__ count, double* __restrict__ lam_out,
     float* __restrict__ wfac, int32_t* __restrict__ rank_out, float* __restrict__ phi_out,
     float* __restrict__ sigma_out, uint16_t* __restrict__ rfac, uint32_t* __restrict__ flags_out) {
@@ -176,6 +190,9 @@ __global__ __launch_bounds__(THREADS) void eoq_spectral_jacobi_kernel(
     {
       double acc[64];
       gram_tile(blocks, dtype, map.in_base(blk), (size_t)map.token_stride, n, stage, tid, acc);
+      bool bad = false;
+      EOQ_SFOR(e, 64, bad |= !(fabs(acc[e]) < INFINITY););
+      if (bad) atomicOr(&flag_s, EOQ_FLAG_NONFINITE);
       const int ty = tid >> 4, tx = tid & 15;
       EOQ_SFOR(e, 64, A[(tx * 8 + (e & 7)) * LDA + ty * 8 + (e >> 3)] = acc[e];);
     }
@@ -252,7 +269,7 @@ __global__ __launch_bounds__(THREADS) void eoq_spectral_jacobi_kernel(
     }
     __syncthreads();
 
-    const int r = rank_and_shrink(lam_s, atoms, scale_s, &flag_s, n, k, rank_thr, r_max, blk, slot, lam_out, phi_out,
+    const int r = rank_and_shrink(lam_s, atoms, scale_s, &flag_s, n, k, rank_thr, r_max, loss, blk, slot, lam_out, phi_out,
                                   sigma_out);
 
     // right singular vectors v_i = a_slot / lambda_i of the retained components
@@ -309,7 +326,7 @@ constexpr int POOL_BYTES = REFL_BYTES + U1_BYTES;
 // G = S^T S in the cyclic layout.  Only the sub-tiles a <= b are accumulated (36 of 64 products per block row);
 // the others are mirrored from the lane that holds the transposed position, through LDS.
 __device__ __forceinline__ void gram_cyclic(const void* __restrict__ blocks, int dtype, size_t base_elem, size_t tok, int n,
-                                            float* stage, int tid, double (&A)[64]) {
+                                            float* stage, int tid, double (&A)[64], unsigned* flag_s) {
   const int ty = tid >> 4, tx = tid & 15;
   EOQ_SFOR(i, 64, A[i] = 0.0;);
   float nxt[2][8];
@@ -339,6 +356,11 @@ __device__ __forceinline__ void gram_cyclic(const void* __restrict__ blocks, int
       const double b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
       EOQ_SFOR(e, 64, if constexpr ((e >> 3) <= (e & 7)) A[e] = fma(a[e >> 3], b[e & 7], A[e]););
     }
+  }
+  {
+    bool bad = false;   // an Inf or NaN entry of the block reaches the diagonal of G
+    EOQ_SFOR(i, 8, bad |= !(fabs(A[i * 9]) < INFINITY););
+    if (bad) atomicOr(flag_s, EOQ_FLAG_NONFINITE);
   }
   // mirror: G[ty+16b][tx+16a] (a < b) is what lane (tx, ty) accumulated as its sub-tile (a, b)
   double* X = reinterpret_cast<double*>(stage);
@@ -395,7 +417,7 @@ __device__ __forceinline__ void transpose_bytes(uint32_t x0, uint32_t x1, uint32
 }
 
 __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size_t tok, int n, unsigned char* pool, int tid,
-                                          double (&A)[64]) {
+                                          double (&A)[64], unsigned* flag_s) {
   const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m = tid & 15, q = tid >> 4;  // loader: columns 8m .. 8m+7, tokens 4q .. 4q+3 of the pass
@@ -404,6 +426,7 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size
   double Gacc[9][4];  // tile number wave + 4 s, rows 4 kg + v, column l16
   EOQ_SFOR(s, 9, EOQ_SFOR(v, 4, Gacc[s][v] = 0.0;););
 
+  uint32_t top = 0u;  // largest |binary16 pattern| this lane has seen in its columns: 0x7C00 and above is Inf / NaN
   uint4 raw[4];
 #pragma unroll
   for (int it = 0; it < 4; ++it) raw[it] = *reinterpret_cast<const uint4*>(src + (size_t)(4 * q + it) * tok + 8 * m);
@@ -430,6 +453,7 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size
       mx[2] = pk_max_u16(mx[2], o.z);
       mx[3] = pk_max_u16(mx[3], o.w);
     }
+    top = pk_max_u16(top, pk_max_u16(pk_max_u16(mx[0], mx[1]), pk_max_u16(mx[2], mx[3])));
     // ---- integers, byte planes ----
     EOQ_SFOR(c, 8,
       const uint32_t hmax = (mx[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
@@ -493,6 +517,8 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size
       );
     );
   }
+  // a column maximum with all exponent bits set: the integer conversion of that pass saturated, G is meaningless
+  if (q == 0 && (((top & 0xFFFFu) >= 0x7C00u) || ((top >> 16) >= 0x7C00u))) atomicOr(flag_s, EOQ_FLAG_NONFINITE);
   // ---- tiles change lanes: three rounds of twelve tiles through LDS; lane (ty, tx) takes element (ty, tx) of tile
   // (a, b) as A[a * 8 + b] and, for a < b, element (tx, ty) as A[b * 8 + a] ----
   double* Tl = reinterpret_cast<double*>(pool);
@@ -915,7 +941,7 @@ __device__ __forceinline__ void twisted_chain(double2* F, const double2* M, int 
 }
 
 __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
-    const void* __restrict__ blocks, EoqBlockMap map, int dtype, int n, int k_pilot, double rank_thr, int r_max,
+    const void* __restrict__ blocks, EoqBlockMap map, int dtype, int n, int k_pilot, double rank_thr, int r_max, int loss,
     int* __restrict__ fb_list, int* __restrict__ fb_count, double* __restrict__ lam_out, float* __restrict__ wfac,
     double* __restrict__ tri, int32_t* __restrict__ rank_out, float* __restrict__ phi_out, float* __restrict__ sigma_out,
     uint16_t* __restrict__ rfac, uint32_t* __restrict__ flags_out) {
@@ -950,9 +976,9 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   {
     double A[64];
     if (dtype == EOQ_F16)
-      gram_int8(static_cast<const uint16_t*>(blocks) + map.in_base(blk), (size_t)map.token_stride, n, pool, tid, A);
+      gram_int8(static_cast<const uint16_t*>(blocks) + map.in_base(blk), (size_t)map.token_stride, n, pool, tid, A, &flag_s);
     else
-      gram_cyclic(blocks, dtype, map.in_base(blk), (size_t)map.token_stride, n, reinterpret_cast<float*>(u1), tid, A);
+      gram_cyclic(blocks, dtype, map.in_base(blk), (size_t)map.token_stride, n, reinterpret_cast<float*>(u1), tid, A, &flag_s);
     __syncthreads();  // the pool changes hands
     EOQ_SFOR(s, 6, householder_stage<s>(A, tid, vbuf, pbuf, refl, dT, eT, betaT););
     // the trailing 32 x 32 matrix (rows and columns 96 .. 127: sub-tiles a, b = 6, 7 of every lane) changes hands:
@@ -1105,8 +1131,8 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   }
   __syncthreads();
 
-  const int r = rank_and_shrink(lam_s, atoms, scale_s, &flag_s, n, k_pilot, rank_thr, r_max, blk, slot, lam_out, phi_out,
-                                sigma_out);
+  const int r = rank_and_shrink(lam_s, atoms, scale_s, &flag_s, n, k_pilot, rank_thr, r_max, loss, blk, slot, lam_out,
+                                phi_out, sigma_out);
 
   // repeated retained eigenvalues: leave the block to the Jacobi solver
   bool repeated = false;
@@ -1237,16 +1263,16 @@ hipError_t eoq_launch_spectral(const EoqLaunch& L, const void* blocks, int dtype
   if (L.ev) (void)hipEventRecord(L.ev[0], L.stream);
   if (L.solver == 1) {
     hipLaunchKernelGGL(eoq_spectral_jacobi_kernel, dim3((unsigned)B), dim3(THREADS), 0, L.stream, blocks, L.map, dtype, L.n,
-                       L.k, L.rank_thr, L.r_max, B, (const int*)nullptr, (const int*)nullptr, lam, wfac, out.rank,
+                       L.k, L.rank_thr, L.r_max, L.loss, B, (const int*)nullptr, (const int*)nullptr, lam, wfac, out.rank,
                        out.phi, out.sigma, out.rfac, out.flags);
   } else {
     hipLaunchKernelGGL(eoq_zero_counter_kernel, dim3(1), dim3(64), 0, L.stream, fb_count);
     hipLaunchKernelGGL(eoq_spectral_tridiag_kernel, dim3((unsigned)B), dim3(THREADS), 0, L.stream, blocks, L.map, dtype, L.n,
-                       L.k, L.rank_thr, L.r_max, fb_list, fb_count, lam, wfac, tri, out.rank, out.phi, out.sigma, out.rfac,
+                       L.k, L.rank_thr, L.r_max, L.loss, fb_list, fb_count, lam, wfac, tri, out.rank, out.phi, out.sigma, out.rfac,
                        out.flags);
     const unsigned grid = (unsigned)((B < 256) ? B : 256);
     hipLaunchKernelGGL(eoq_spectral_jacobi_kernel, dim3(grid), dim3(THREADS), 0, L.stream, blocks, L.map, dtype, L.n, L.k,
-                       L.rank_thr, L.r_max, B, (const int*)fb_list, (const int*)fb_count, lam, wfac, out.rank, out.phi,
+                       L.rank_thr, L.r_max, L.loss, B, (const int*)fb_list, (const int*)fb_count, lam, wfac, out.rank, out.phi,
                        out.sigma, out.rfac, out.flags);
   }
   if (L.ev) (void)hipEventRecord(L.ev[1], L.stream);

@@ -15,11 +15,12 @@ LIB_PATH = os.path.join(_HERE, "libeoq.so")
 
 EOQ_OK, EOQ_ERR_ARG, EOQ_ERR_UNSUPPORTED, EOQ_ERR_WORKSPACE, EOQ_ERR_HIP = range(5)
 EOQ_F16, EOQ_F32 = 0, 1
-FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE = 1, 2, 4
+EOQ_LOSS_FROBENIUS, EOQ_LOSS_OPERATOR, EOQ_LOSS_NUCLEAR = 0, 1, 2
+FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE, FLAG_NONFINITE = 1, 2, 4, 16
 
 EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_projection",
            "eoq_codebook", "eoq_qjl_encode", "eoq_scores_prod",
-           "eoq_compress", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_softmax", "eoq_attend_workspace_bytes", "eoq_attend", "eoq_attend_stream", "eoq_set_solver", "eoq_profile", "eoq_stage_ms", "eoq_last_error"]
+           "eoq_compress", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_softmax", "eoq_attend_workspace_bytes", "eoq_attend", "eoq_attend_stream", "eoq_set_solver", "eoq_set_loss", "eoq_profile", "eoq_stage_ms", "eoq_ceiling", "eoq_last_error"]
 
 
 class EoqError(RuntimeError):
@@ -108,10 +109,14 @@ def lib():
         L.eoq_attend_stream.restype = C.c_int
         L.eoq_set_solver.argtypes = [C.c_void_p, C.c_int]
         L.eoq_set_solver.restype = C.c_int
+        L.eoq_set_loss.argtypes = [C.c_void_p, C.c_int]
+        L.eoq_set_loss.restype = C.c_int
         L.eoq_profile.argtypes = [C.c_void_p, C.c_int]
         L.eoq_profile.restype = C.c_int
         L.eoq_stage_ms.argtypes = [C.c_void_p, C.c_void_p]
         L.eoq_stage_ms.restype = C.c_int
+        L.eoq_ceiling.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
+        L.eoq_ceiling.restype = C.c_int
         L.eoq_last_error.argtypes = [C.c_void_p]
         L.eoq_last_error.restype = C.c_char_p
         _lib = L
@@ -424,6 +429,10 @@ class Context:
     def eoq_set_solver(self, solver: int):
         self._check(lib().eoq_set_solver(self._h, solver))
 
+    def eoq_set_loss(self, loss: int):
+        """EOQ_LOSS_FROBENIUS (0), EOQ_LOSS_OPERATOR (1) or EOQ_LOSS_NUCLEAR (2)."""
+        self._check(lib().eoq_set_loss(self._h, loss))
+
     def eoq_profile(self, enable: bool = True):
         self._check(lib().eoq_profile(self._h, 1 if enable else 0))
 
@@ -431,6 +440,13 @@ class Context:
         out = (C.c_float * 6)()
         self._check(lib().eoq_stage_ms(self._h, out))
         return dict(zip(("spectral", "encode", "decode", "scores", "attend", "softmax"), (float(x) for x in out)))
+
+    def eoq_ceiling(self, kind: int, buf: torch.Tensor, iters: int = 1) -> dict:
+        """One micro-benchmark of include/eoq.h's eoq_ceiling on the device buffer `buf` (uint8)."""
+        assert buf.is_cuda and buf.is_contiguous()
+        out = (C.c_double * 4)()
+        self._check(lib().eoq_ceiling(self._h, kind, buf.data_ptr(), buf.numel() * buf.element_size(), iters, out))
+        return {"ms": out[0], "work_a": out[1], "work_b": out[2], "compute_units": int(out[3])}
 
     def spectrum(self, workspace: torch.Tensor, B: int) -> torch.Tensor:
         """Gram eigenvalues [B, d] (float64) that eoq_compress leaves at the head of its workspace."""
