@@ -164,6 +164,23 @@ eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64
                         eoq_packed out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * eoq_compress for callers that cannot allocate device memory or hand in a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation): the same kernels on the same arguments, with the workspace
+ * in a 16 MiB array that is part of the library's device image (one copy per GPU, held until the process ends).
+ * The call allocates nothing, frees nothing and does not synchronise.
+ *   B          at most eoq_static_max_blocks(ctx) (861 blocks at r_max = 32, 2339 at r_max = 8); more blocks:
+ *              EOQ_ERR_WORKSPACE, nothing is launched.
+ *   blocks, dtype, out, hip_stream   as eoq_compress; the record is bit-identical to eoq_compress's.
+ * The diagnostic eigenvalues of eoq_compress stay inside the library.  Every call on a GPU, from any context, uses
+ * that GPU's one array and leaves its contents behind (the call clears what must start at zero itself): two calls
+ * that overlap in time on one GPU (different streams, or replays of graphs that contain them) race; calls on one
+ * stream, or ordered by events, are safe.
+ */
+int64_t    eoq_static_max_blocks(const eoq_ctx* ctx);
+eoq_status eoq_compress_static(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_packed out,
+                               void* hip_stream);
+
+/*
  * eoq_compress with the SVD factors stored at 4 bits (see eoq_factor_codes): the residual is taken against
  * the expanded 4-bit factors (closed loop), which are also left in out.lfac / out.rfac.  binary16 blocks only
  * (dtype must be EOQ_F16) and n * r_max <= 32768 (the left vectors of a block are fitted in LDS), otherwise

@@ -7,7 +7,19 @@
 
 #include "eoq_internal.h"
 
+// ---------------------------------------------------------------------------
+// Scratch of eoq_compress_static: the workspace of eoq_compress (eigenvalues, projection operands, hand-over list,
+// tridiagonal matrices) for callers that cannot hand one in.  One copy per GPU, held until the process ends.  In host
+// code the name below is only a stand-in for the symbol: the device address comes from hipGetSymbolAddress, once per
+// device (eoq_create, with that device current), and only that pointer is ever passed to a kernel.
+// ---------------------------------------------------------------------------
+constexpr size_t EOQ_STATIC_SCRATCH_BYTES = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[EOQ_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int EOQ_MAX_DEVICES = 64;
+void* g_scratch_ptr[EOQ_MAX_DEVICES] = {};   // device address of `scratch` on each GPU this process has used
 
 // ---------------------------------------------------------------------------
 // Seeded Gaussian stream: SplitMix64 evaluated at a counter, Box-Muller cosine
@@ -210,6 +222,11 @@ eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, 
     return EOQ_OK;
   }
   hipError_t e = hipGetDevice(&ctx->device);
+  if (e == hipSuccess && ctx->device >= 0 && ctx->device < EOQ_MAX_DEVICES && !g_scratch_ptr[ctx->device]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // this device's copy of the array
+    if (e == hipSuccess) g_scratch_ptr[ctx->device] = p;
+  }
   const size_t mat_bytes = (size_t)d * d * sizeof(float);
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pi, mat_bytes);
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pit, mat_bytes);
@@ -357,6 +374,28 @@ eoq_status eoq_compress(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64
   if (!ctx) return EOQ_ERR_ARG;
   return compress_impl(ctx, blocks, dtype, B, eoq_dense_map(ctx->n), out, nullptr, workspace, workspace_bytes,
                        hip_stream);
+}
+
+int64_t eoq_static_max_blocks(const eoq_ctx* ctx) {
+  if (!ctx) return 0;
+  int64_t lo = 0, hi = (int64_t)(EOQ_STATIC_SCRATCH_BYTES / (EOQ_D * sizeof(double))) + 1;   // eoq_workspace_bytes grows with B
+  while (hi - lo > 1) {
+    const int64_t mid = lo + (hi - lo) / 2;
+    if (eoq_workspace_bytes(ctx, mid) <= EOQ_STATIC_SCRATCH_BYTES) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+eoq_status eoq_compress_static(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_packed out,
+                               void* hip_stream) {
+  if (!ctx) return EOQ_ERR_ARG;
+  ctx->err.clear();
+  if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
+  if (B > eoq_static_max_blocks(ctx))
+    return fail(ctx, EOQ_ERR_WORKSPACE, "eoq_compress_static: more blocks than the built-in scratch holds (eoq_static_max_blocks)");
+  void* ws = (ctx->device < EOQ_MAX_DEVICES) ? g_scratch_ptr[ctx->device] : nullptr;
+  if (!ws) return fail(ctx, EOQ_ERR_HIP, "eoq_compress_static: no scratch address for this device");
+  return compress_impl(ctx, blocks, dtype, B, eoq_dense_map(ctx->n), out, nullptr, ws, EOQ_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 eoq_status eoq_compress_q4(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int64_t B, eoq_packed out,

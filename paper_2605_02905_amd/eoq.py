@@ -20,7 +20,7 @@ FLAG_RANK_CLAMPED, FLAG_SHRINK_GUARD, FLAG_NO_CONVERGE, FLAG_NONFINITE = 1, 2, 4
 
 EXPORTS = ["eoq_create", "eoq_destroy", "eoq_pilot_k", "eoq_workspace_bytes", "eoq_rotation", "eoq_projection",
            "eoq_codebook", "eoq_qjl_encode", "eoq_scores_prod",
-           "eoq_compress", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_softmax", "eoq_attend_workspace_bytes", "eoq_attend", "eoq_attend_stream", "eoq_set_solver", "eoq_set_loss", "eoq_profile", "eoq_stage_ms", "eoq_ceiling", "eoq_last_error"]
+           "eoq_compress", "eoq_compress_static", "eoq_static_max_blocks", "eoq_compress_q4", "eoq_compress_chunk", "eoq_expand_factors", "eoq_decompress", "eoq_scores", "eoq_scores_stream", "eoq_softmax", "eoq_attend_workspace_bytes", "eoq_attend", "eoq_attend_stream", "eoq_set_solver", "eoq_set_loss", "eoq_profile", "eoq_stage_ms", "eoq_ceiling", "eoq_last_error"]
 
 
 class EoqError(RuntimeError):
@@ -80,6 +80,10 @@ def lib():
         L.eoq_compress.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, _Packed, C.c_void_p, C.c_size_t,
                                    C.c_void_p]
         L.eoq_compress.restype = C.c_int
+        L.eoq_compress_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, _Packed, C.c_void_p]
+        L.eoq_compress_static.restype = C.c_int
+        L.eoq_static_max_blocks.argtypes = [C.c_void_p]
+        L.eoq_static_max_blocks.restype = C.c_int64
         L.eoq_compress_q4.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, _Packed, _FactorCodes, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
         L.eoq_compress_q4.restype = C.c_int
@@ -262,6 +266,17 @@ class Context:
         self._check(lib().eoq_compress(self._h, blocks.data_ptr(), dtype, B, out.c_struct(), workspace.data_ptr(),
                                        workspace.numel(), _stream_ptr(blocks.device)))
         return out, workspace
+
+    def eoq_static_max_blocks(self) -> int:
+        return lib().eoq_static_max_blocks(self._h)
+
+    def eoq_compress_static(self, blocks: torch.Tensor, out: Packed) -> Packed:
+        """eoq_compress with the workspace inside the library (no allocation: `out` must be given)."""
+        assert blocks.is_cuda and blocks.is_contiguous() and blocks.shape[1:] == (self.n, self.d)
+        dtype = {torch.float16: EOQ_F16, torch.float32: EOQ_F32}[blocks.dtype]
+        self._check(lib().eoq_compress_static(self._h, blocks.data_ptr(), dtype, blocks.shape[0], out.c_struct(),
+                                              _stream_ptr(blocks.device)))
+        return out
 
     def eoq_compress_q4(self, blocks: torch.Tensor, out: Packed | None = None, fq: FactorCodes | None = None,
                         workspace: torch.Tensor | None = None):
