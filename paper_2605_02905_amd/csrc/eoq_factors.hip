@@ -360,6 +360,16 @@ __global__ __launch_bounds__(THREADS) void eoq_factor_expand_kernel(
 
 }  // namespace
 
+// Largest LDS tables the two variants are ever launched with (n * r_max <= 32768, n <= 4096): raised once per device
+// at context creation, so that the hot call sets no function attribute.
+hipError_t eoq_factor_quant_prepare() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(eoq_factor_quant_kernel<8>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 8 * (4096 + D) * (int)sizeof(float));
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(eoq_factor_quant_kernel<32>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (32768 + EOQ_RMAX_CAP * D) * (int)sizeof(float));
+}
+
 hipError_t eoq_launch_factor_quant(const EoqLaunch& L, const void* blocks_fp16, int64_t B, const float* wfac,
                                    eoq_packed out, eoq_factor_codes fq, const double* gauss_levels) {
   GaussLevels g;
@@ -368,19 +378,12 @@ hipError_t eoq_launch_factor_quant(const EoqLaunch& L, const void* blocks_fp16, 
   // sized for 8 components (most blocks: many workgroups per CU) or for r_max
   const size_t lds8 = (size_t)std::min(8, L.r_max) * (L.n + D) * sizeof(float);
   hipError_t e = hipSuccess;
-  if (lds8 > 48 * 1024)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(eoq_factor_quant_kernel<8>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds8);
-  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(eoq_factor_quant_kernel<8>, dim3((unsigned)B), dim3(THREADS), lds8, L.stream,
                      static_cast<const uint16_t*>(blocks_fp16), L.map, B, L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
                      out.rfac, out.lfac, fq.lcodes, fq.rcodes, fq.fbook, fq.phi16);
   e = hipGetLastError();
   if (e != hipSuccess || L.r_max <= 8) return e;
   const size_t lds = (size_t)L.r_max * (L.n + D) * sizeof(float);
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(eoq_factor_quant_kernel<32>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(eoq_factor_quant_kernel<32>, dim3((unsigned)(B < 512 ? B : 512)), dim3(THREADS), lds, L.stream,
                      static_cast<const uint16_t*>(blocks_fp16), L.map, B, L.n, L.r_max, g, out.rank, out.phi, out.sigma, wfac,
                      out.rfac, out.lfac, fq.lcodes, fq.rcodes, fq.fbook, fq.phi16);

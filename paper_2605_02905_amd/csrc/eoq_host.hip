@@ -227,6 +227,7 @@ eoq_status eoq_create(eoq_ctx** out, int n, int d, int bits, uint64_t rot_seed, 
     e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // this device's copy of the array
     if (e == hipSuccess) g_scratch_ptr[ctx->device] = p;
   }
+  if (e == hipSuccess) e = eoq_factor_quant_prepare();
   const size_t mat_bytes = (size_t)d * d * sizeof(float);
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pi, mat_bytes);
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_pit, mat_bytes);
@@ -336,6 +337,8 @@ eoq_status compress_impl(eoq_ctx* ctx, const void* blocks, eoq_dtype dtype, int6
   if (eoq_status st = check_packed(ctx, out)) return st;
   if (fq && (!fq->lcodes || !fq->rcodes || !fq->fbook || !fq->phi16))
     return fail(ctx, EOQ_ERR_ARG, "eoq_factor_codes has a null member");
+  if (fq && !(aligned16(fq->lcodes) && aligned16(fq->rcodes) && aligned16(fq->fbook) && aligned16(fq->phi16)))
+    return fail(ctx, EOQ_ERR_ARG, "eoq_factor_codes member not 16-byte aligned");
   if (workspace_bytes < eoq_workspace_bytes(ctx, B)) return fail(ctx, EOQ_ERR_WORKSPACE, "workspace too small");
   if (B > (int64_t)1 << 24) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
 
@@ -428,6 +431,8 @@ eoq_status eoq_expand_factors(eoq_ctx* ctx, eoq_packed rec, eoq_factor_codes fq,
   if (B == 0) return EOQ_OK;
   if (eoq_status st = check_packed(ctx, rec)) return st;
   if (!fq.lcodes || !fq.rcodes || !fq.fbook || !fq.phi16) return fail(ctx, EOQ_ERR_ARG, "eoq_factor_codes has a null member");
+  if (!(aligned16(fq.lcodes) && aligned16(fq.rcodes) && aligned16(fq.fbook) && aligned16(fq.phi16)))
+    return fail(ctx, EOQ_ERR_ARG, "eoq_factor_codes member not 16-byte aligned");
   const EoqLaunch L = make_launch(ctx, hip_stream);
   const hipError_t e = eoq_launch_factor_expand(L, rec, fq, B);
   if (e != hipSuccess) {
@@ -529,7 +534,7 @@ eoq_status eoq_softmax(eoq_ctx* ctx, float* scores, int64_t rows, int64_t len, i
   if (ctx->device < 0) return fail(ctx, EOQ_ERR_HIP, "context was created without a HIP device");
   if (rows < 0 || len < 0 || row_stride < len) return fail(ctx, EOQ_ERR_ARG, "negative size or rows that overlap");
   if (rows == 0 || len == 0) return EOQ_OK;
-  if (!scores) return fail(ctx, EOQ_ERR_ARG, "null score pointer");
+  if (!scores || !aligned16(scores)) return fail(ctx, EOQ_ERR_ARG, "null or misaligned score pointer");
   if (rows > 0x7FFFFFFF) return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^31 - 1 rows");
   const EoqLaunch L = make_launch(ctx, hip_stream);
   const hipError_t e = eoq_launch_softmax(L, scores, rows, len, row_stride);
@@ -558,7 +563,8 @@ static eoq_status attend_impl(eoq_ctx* ctx, eoq_packed values, int64_t n_seq, in
   if (n_q_heads % n_kv_heads != 0 || n_q_heads / n_kv_heads > 8)
     return fail(ctx, EOQ_ERR_UNSUPPORTED, "query heads must be a multiple (1..8) of KV heads");
   if (n_seq == 0) return EOQ_OK;
-  if (!weights || !out || !aligned16(out)) return fail(ctx, EOQ_ERR_ARG, "null or misaligned weight/output pointer");
+  if (!weights || !out || !aligned16(out) || !aligned16(weights))
+    return fail(ctx, EOQ_ERR_ARG, "null or misaligned weight/output pointer");
   if (blocks_filled > 0) {
     if (eoq_status st = check_packed(ctx, values)) return st;
     if (!workspace || !aligned16(workspace)) return fail(ctx, EOQ_ERR_ARG, "null or misaligned workspace");

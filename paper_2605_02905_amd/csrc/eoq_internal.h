@@ -91,6 +91,7 @@ hipError_t eoq_launch_encode_f16(const EoqLaunch& L, const void* blocks, int64_t
                                  eoq_packed out, bool stored_factors = false);
 hipError_t eoq_launch_factor_quant(const EoqLaunch& L, const void* blocks_fp16, int64_t B, const float* wfac,
                                    eoq_packed out, eoq_factor_codes fq, const double* gauss_levels);
+hipError_t eoq_factor_quant_prepare();   // function attributes (dynamic LDS limits), once per device
 hipError_t eoq_launch_factor_expand(const EoqLaunch& L, eoq_packed rec, eoq_factor_codes fq, int64_t B);
 hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void* out_fp16);
 // block_capacity / score_stride <= 0: the dense case (blocks_per_head slots per head, rows of blocks_per_head * n);

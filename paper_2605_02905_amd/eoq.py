@@ -11,7 +11,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libeoq.so")
+# EOQ_LIB_PATH names another build of the same library (e.g. the host-sanitizer build the README describes)
+LIB_PATH = os.environ.get("EOQ_LIB_PATH") or os.path.join(_HERE, "libeoq.so")
 
 EOQ_OK, EOQ_ERR_ARG, EOQ_ERR_UNSUPPORTED, EOQ_ERR_WORKSPACE, EOQ_ERR_HIP = range(5)
 EOQ_F16, EOQ_F32 = 0, 1

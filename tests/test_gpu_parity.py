@@ -858,7 +858,7 @@ def test_qjl_side_information_of_oracle_records(n, bits, B, rank_hi):
     # the binary16 table of the library against the oracle's generator: equal, or one binary16 unit apart where the
     # two libm's differ in the last bit of the float64 draw right at a rounding boundary
     assert np.count_nonzero(ctx.eoq_projection().astype(np.float64) != _oracle_phi(ctx)) <= 2
-    Phi = ctx.eoq_projection().astype(np.float64)
+    Phi = _oracle_phi(ctx)                     # the oracle's own table (<= 2 entries one binary16 unit from the library's)
     packed = U.records_to_packed(recs, 32, DEV)
     qj = ctx.eoq_qjl_encode(blocks.to(DEV).contiguous(), packed)
     torch.cuda.synchronize()
@@ -889,7 +889,7 @@ def test_scores_prod_of_oracle_records():
     Pi, cb = U.oracle_tables(bits)
     recs = U.oracle_compress(b64, bits)
     ctx = eoq.Context(n=n, bits=bits)
-    Phi = ctx.eoq_projection().astype(np.float64)
+    Phi = _oracle_phi(ctx)
     oqs = [oracle.qjl_encode(b64[b], r, Pi, cb, Phi) for b, r in enumerate(recs)]
     packed = U.records_to_packed(recs, 32, DEV)
     qj = eoq.Qjl(torch.from_numpy(np.stack([oracle.pack_signs(o.signs) for o in oqs])).to(DEV),
@@ -926,7 +926,7 @@ def test_tq_prod_end_to_end_in_the_bench_launch_configuration():
     qj = ctx.eoq_qjl_encode(blocks, rec)
     torch.cuda.synchronize()
     Pi, cb = U.oracle_tables(bits)
-    Phi = ctx.eoq_projection().astype(np.float64)
+    Phi = _oracle_phi(ctx)
     idx = list(range(0, B, 173))
     b64 = blocks[idx].double().cpu().numpy()
     srecs = U.packed_to_records(rec, idx, bits)
@@ -1119,7 +1119,7 @@ def test_maximum_block_length_through_every_call():
     packed = U.records_to_packed(recs, r_max, DEV)
     q = synth.make_queries(1, 4)
     sg = ctx.eoq_scores(packed, q.to(DEV), n_kv_heads=1)
-    Phi = ctx.eoq_projection().astype(np.float64)
+    Phi = _oracle_phi(ctx)
     qj = ctx.eoq_qjl_encode(dev_blocks, packed)
     gen = torch.Generator().manual_seed(1)
     w = torch.softmax(torch.randn(1, 4, B * n, generator=gen).double() * 2.0, dim=-1).float()
