@@ -111,6 +111,17 @@ __device__ __forceinline__ void load8(const void* base, int dtype, size_t elem, 
   }
 }
 
+// The four bytes of each of x0 .. x3, transposed: out[k] = bytes k of x0, x1, x2, x3 (x0 lowest).  Eight byte
+// permutes: pairs first (bytes 0/1 and 2/3 of two words interleaved), then the halves of the pairs.
+__device__ __forceinline__ void transpose_bytes(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3, uint32_t (&out)[4]) {
+  const uint32_t a01 = __builtin_amdgcn_perm(x1, x0, 0x05010400u), b01 = __builtin_amdgcn_perm(x1, x0, 0x07030602u);
+  const uint32_t a23 = __builtin_amdgcn_perm(x3, x2, 0x05010400u), b23 = __builtin_amdgcn_perm(x3, x2, 0x07030602u);
+  out[0] = __builtin_amdgcn_perm(a23, a01, 0x05040100u);
+  out[1] = __builtin_amdgcn_perm(a23, a01, 0x07060302u);
+  out[2] = __builtin_amdgcn_perm(b23, b01, 0x05040100u);
+  out[3] = __builtin_amdgcn_perm(b23, b01, 0x07060302u);
+}
+
 // Compile-time loop: every index into a per-lane register array must be a constant before the optimiser
 // first looks at the array, otherwise the array is kept in (scratch) memory.
 template <int I, int N, typename F>

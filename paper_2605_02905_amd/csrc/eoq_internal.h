@@ -1,5 +1,5 @@
 // Internal declarations shared by the host part (eoq_host.hip) and the kernel files (eoq_spectral.hip: Gram,
-// eigensolvers, rank and shrinkage; eoq_mfma.hip: matrix-core encoder, decoder, scores, TQ_prod; eoq_codec.hip:
+// eigensolvers, rank and shrinkage; eoq_mfma.hip: matrix-core encoder, decoder, TQ_prod; eoq_scores.hip: decode scoring; eoq_codec.hip:
 // float32 encoder; eoq_factors.hip: 4-bit factors; eoq_attend.hip: softmax and attention output) of the
 // eOptShrinkQ library.  Not part of the public ABI.
 #pragma once

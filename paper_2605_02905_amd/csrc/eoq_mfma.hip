@@ -2,7 +2,7 @@
 //   encode : projection, residual against the stored factors, norm, rotation, Lloyd-Max index, packing
 //            (Alg. 3 with Alg. 1 lines 3-5)
 //   decode : x_hat = (rho/sqrt(d)) z_hat Pi + C V^T  (Alg. 1 line 6 plus the stored low-rank part)
-//   scores : <q, x_hat>/sqrt(d) from the record without forming x_hat (Sec. 2.1, Remark 6.5)
+//   qjl    : TQ_prod side information of stored records (Alg. 1 optional lines)
 //
 // Operand convention of v_mfma_f32_32x32x16_f16 (wave64): for D = A(32xK) * B(Kx32) + C, lane l supplies
 // A[row = l%32][k = 8*(l/32) .. +7] and B[k = 8*(l/32) .. +7][col = l%32]; it receives
@@ -554,418 +554,6 @@ __global__ __launch_bounds__(THREADS, 1) void eoq_qjl_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// scores: one workgroup per (sequence, KV head, run of blocks).  v_mfma_f32_16x16x32_f16: lane l supplies
-// A[row = l%16][k = 8*(l/16) .. +7] and B[k = 8*(l/16) .. +7][col = l%16], receives D[row = 4*(l/16)+v][col = l%16].
-// Rows are the query heads of the group (padded to 16), columns are 16 tokens; the 128 coordinates are
-// visited in the order c = 32*(l/16) + 8*kk + e so that a lane needs exactly one 32-bit word of each bit-plane.
-// ---------------------------------------------------------------------------------------------
-typedef float float4v __attribute__((ext_vector_type(4)));
-constexpr int SC_MAXG = 8;
-constexpr int SC_DEPTH = 2;     // passes of record bytes in flight per wave
-constexpr int SC_RUN_MAX = 16;  // most blocks per workgroup (the run is shortened until the grid fills the chip)
-
-__device__ __forceinline__ float4v mfma32(const H8& a, const H8& b, float4v c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c, 0, 0, 0);
-}
-
-// out[h][c] = sum_j table[c][j] q[h][j] for the heads of one group (rows above the group are zero), the table given as
-// binary16 hi + lo parts [c][j]: the query side of the rotation (<q, Pi^T z> = <Pi q, z>) and of the projection Phi q.
-// q is binary16, so every product is exact; 16 matrix instructions and 20 sixteen-byte loads per wave, all in flight
-// together.  `out` is LDS, [SC_MAXG][D]; the caller synchronises.
-__device__ __forceinline__ void rotate_query(const uint16_t* __restrict__ tab_hi, const uint16_t* __restrict__ tab_lo,
-                                             const uint16_t* __restrict__ qg, int group, float* out, int wave, int l16,
-                                             int g) {
-  H8 a[4];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks)
-    a[ks].u = (l16 < group) ? *reinterpret_cast<const uint4*>(qg + l16 * D + 32 * ks + 8 * g) : make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-  for (int tt = 0; tt < 2; ++tt) {
-    const int c = 16 * (2 * wave + tt) + l16;
-    float4v acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      H8 bh, bl;
-      bh.u = *reinterpret_cast<const uint4*>(tab_hi + c * D + 32 * ks + 8 * g);
-      acc = mfma32(a[ks], bh, acc);
-      if (tab_lo) {   // uniform: a table that is binary16 to begin with has no low part
-        bl.u = *reinterpret_cast<const uint4*>(tab_lo + c * D + 32 * ks + 8 * g);
-        acc = mfma32(a[ks], bl, acc);
-      }
-    }
-#pragma unroll
-    for (int v = 0; v < 4; ++v)
-      if (4 * g + v < SC_MAXG) out[(4 * g + v) * D + c] = acc[v];
-  }
-}
-
-// What a lane requests of one pass of the scores kernel: for its token of each of the two tiles the 32-bit word g of
-// every bit-plane and the stored norm (with QJL also the sign word and the residual norm).
-template <int BITS, bool QJL>
-struct ScoreFetch {
-  uint32_t word[2][BITS];
-  uint16_t rho[2];
-  uint32_t sword[2];
-  uint16_t gam[2];
-};
-// Buffer addressing: a resource descriptor in scalar registers (base of this workgroup's run of blocks, size of the
-// run: reads past it return zero instead of faulting), a scalar byte offset that moves from pass to pass and a per-lane
-// 32-bit offset that never changes -- no vector arithmetic per load.
-struct ScoreBuffers {
-  __amdgpu_buffer_rsrc_t codes, norms, lfac, qsigns, qnorms;
-};
-// `tokr` (first token of the first tile, counted from the start of the run) is wave-uniform.
-template <int BITS, bool QJL>
-__device__ __forceinline__ void score_fetch(ScoreFetch<BITS, QJL>& f, const ScoreBuffers& sb, int tokr, uint32_t lane_c,
-                                            uint32_t lane_s, uint32_t lane_n) {
-  constexpr int ROWB = BITS * D / 8;
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int tok = tokr + 16 * u * (THREADS / 64);   // uniform
-#pragma unroll
-    for (int p = 0; p < BITS; ++p)
-      f.word[u][p] = __builtin_amdgcn_raw_buffer_load_b32(sb.codes, lane_c, tok * ROWB + p * 16, 0);
-    f.rho[u] = __builtin_amdgcn_raw_buffer_load_b16(sb.norms, lane_n, tok * 2, 0);
-    if constexpr (QJL) {
-      f.sword[u] = __builtin_amdgcn_raw_buffer_load_b32(sb.qsigns, lane_s, tok * (D / 8), 0);
-      f.gam[u] = __builtin_amdgcn_raw_buffer_load_b16(sb.qnorms, lane_n, tok * 2, 0);
-    }
-  }
-}
-
-// QJL: the logits get the correction of Eq. (qjl), |r_x| sqrt(pi/2)/d <Phi q, sign(Phi r_x)>, from one more bit-plane
-// (the signs, expanded to +-1) and the stored residual norm; Phi q is formed once per workgroup like Pi q.
-template <int BITS, bool QJL>
-__global__ __launch_bounds__(THREADS) void eoq_scores_mfma_kernel(
-    int n, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, int64_t block_capacity, int64_t score_stride,
-    int run, const uint16_t* __restrict__ pih,
-    const float* __restrict__ tab, const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
-    const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac,
-    const uint16_t* __restrict__ q, float* __restrict__ scores, const uint16_t* __restrict__ phih,
-    const uint8_t* __restrict__ qsigns, const uint16_t* __restrict__ qnorms) {
-  __shared__ float qraw[SC_MAXG * D];
-  __shared__ float qrot[SC_MAXG * D];
-  __shared__ __align__(16) float wbuf[SC_RUN_MAX * EOQ_RMAX_CAP * SC_MAXG];   // [block of the run][component][head]: <v_i, q_h>
-  __shared__ int rank_s[SC_RUN_MAX];
-  __shared__ __align__(16) uint4 mask_tab[256];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave: scalar
-  const int l16 = lane & 15, g = lane >> 4;
-  const size_t sg = blockIdx.y;
-  const size_t sq = sg / n_kv_heads, kv = sg % n_kv_heads;
-  const int n_q_heads = n_kv_heads * group;
-  const size_t q0 = (sq * n_q_heads + kv * group) * D;
-  const size_t T = (size_t)score_stride;   // entries per score row (>= blocks_per_head * n)
-  constexpr int ROWB = BITS * D / 8;
-
-  build_mask_table(mask_tab, tid);
-  Mags<BITS> mg;
-  mg.load(tab);
-  for (int e = tid; e < SC_MAXG * D; e += THREADS) qraw[e] = (e < group * D) ? half_bits_to_float(q[q0 + e]) : 0.0f;
-  __syncthreads();
-  // q' = Pi q (the rotation moved to the query side: <q, Pi^T z> = <Pi q, z>)
-  rotate_query(pih, pih + D * D, q + q0, group, qrot, wave, l16, g);
-  __syncthreads();
-  H8 Aq_hi[4], Aq_lo[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float v = (l16 < group) ? qrot[l16 * D + 32 * g + 8 * kk + e] : 0.0f;
-      split_half(v, Aq_hi[kk].s[e], Aq_lo[kk].s[e]);
-    }
-  H8 Ap_hi[QJL ? 4 : 1], Ap_lo[QJL ? 4 : 1];
-  if constexpr (QJL) {
-    __syncthreads();  // qrot has been read: reuse it for Phi q
-    rotate_query(phih, nullptr, q + q0, group, qrot, wave, l16, g);
-    __syncthreads();
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float v = (l16 < group) ? qrot[l16 * D + 32 * g + 8 * kk + e] : 0.0f;
-        split_half(v, Ap_hi[kk].s[e], Ap_lo[kk].s[e]);
-      }
-  }
-  const float qjl_scale = sqrtf(1.5707963267948966f) / (float)D;
-  // inner positive centroid and the step to the outer one (tab: 2^BITS ascending centroids of N(0,1))
-  const float cent_in = tab[(1 << BITS) / 2];
-  const float cent_step = (BITS >= 2) ? tab[(1 << BITS) / 2 + 1] - tab[(1 << BITS) / 2] : 0.0f;
-
-  const float inv_sqrt_d = 1.0f / sqrtf((float)D);
-  // The work of this workgroup as a flat list of passes: pass p covers two tiles of 16 tokens per wave (tiles
-  // wave + 8 q and wave + 8 q + 4 of block jb0 + p / ppb, q = p % ppb).  The record bytes of a pass are requested
-  // SC_DEPTH passes ahead into a ring of registers (the loop is unrolled over the ring, so nothing is copied and a pass
-  // only waits for its own bytes), the stored coefficients one pass ahead.
-  const int64_t jb0 = (int64_t)blockIdx.x * run;
-  const int nblk = (int)(min(jb0 + run, blocks_per_head) - jb0);
-  const int ppb = n / 128;
-  const int P = nblk * ppb;
-  const size_t blk0 = sg * (size_t)block_capacity + jb0;   // the store holds block_capacity slots per head
-
-  // w[b][i][h] = <v_i, q_h> of every block of the run, up front (the low-rank term is <C_t, w_h>): all loads of the
-  // set-up are in flight together and the pass loop below has no barrier.  16 lanes per (component, head): one
-  // 16-byte load of eight entries of v_i each, then a sum over the DPP row.
-  if (tid < nblk) rank_s[tid] = min(max(rank_in[blk0 + tid], 0), r_max);   // records may come from storage: never index past r_max rows
-  __syncthreads();
-  int rtop = 0;
-  for (int b = 0; b < nblk; ++b) rtop = max(rtop, rank_s[b]);
-  for (int e0 = 0; e0 < nblk * rtop * (SC_MAXG * 16); e0 += THREADS) {   // uniform trip count: whole rows reduce together
-    const int e = e0 + tid;
-    const int seg = e & 15, h = (e >> 4) & (SC_MAXG - 1);
-    const int bi = e >> 7, b = bi / rtop, i = bi - b * rtop;
-    const int rb = rank_s[min(b, nblk - 1)];
-    float acc = 0.0f;
-    if (b < nblk && i < rb) {
-      float v[8];
-      load8(rfac, EOQ_F16, ((blk0 + b) * r_max + i) * (size_t)D + 8 * seg, v);
-#pragma unroll
-      for (int x = 0; x < 8; ++x) acc = fmaf(v[x], qraw[h * D + 8 * seg + x], acc);
-    }
-    acc += dpp_mov<0xB1>(acc);
-    acc += dpp_mov<0x4E>(acc);
-    acc += dpp_mov<0x141>(acc);
-    acc += dpp_mov<0x140>(acc);
-    if (seg == 0 && b < nblk && i < rb) wbuf[(b * EOQ_RMAX_CAP + i) * SC_MAXG + h] = acc;
-  }
-  __syncthreads();
-
-  const uint32_t lane_c = (uint32_t)(l16 * (BITS * D / 8) + 4 * g);   // into the codes of a tile
-  const uint32_t lane_s = (uint32_t)(l16 * (D / 8) + 4 * g);          // into the sign planes of a tile
-  const uint32_t lane_n = (uint32_t)(2 * l16);                        // into the norms / a coefficient row of a tile
-  ScoreBuffers sb;
-  sb.codes = buffer_of(codes + blk0 * (size_t)n * (BITS * D / 8), (size_t)nblk * n * (BITS * D / 8));
-  sb.norms = buffer_of(norms + blk0 * (size_t)n, (size_t)nblk * n * 2);
-  sb.lfac = buffer_of(lfac + blk0 * (size_t)r_max * n, (size_t)nblk * r_max * n * 2);
-  if constexpr (QJL) {
-    sb.qsigns = buffer_of(qsigns + blk0 * (size_t)n * (D / 8), (size_t)nblk * n * (D / 8));
-    sb.qnorms = buffer_of(qnorms + blk0 * (size_t)n, (size_t)nblk * n * 2);
-  }
-  ScoreFetch<BITS, QJL> ring[SC_DEPTH];
-  uint16_t cbr[2][2][4];   // [parity of the pass][tile][component of the group of four]
-  int fb = 0, fq = 0;      // block and pass-in-block of the next pass to request
-  auto request = [&](ScoreFetch<BITS, QJL>& f) __attribute__((always_inline)) {
-    score_fetch<BITS, QJL>(f, sb, fb * n + 16 * (wave + 8 * fq), lane_c, lane_s, lane_n);
-    if (++fq == ppb) {
-      fq = 0;
-      ++fb;
-    }
-  };
-  // coefficients C[i][token] of the first four components of pass (cb_b, cb_q); row 0 is read when the rank is 0
-  auto request_cb = [&](uint16_t (&cb)[2][4], int cb_b, int cb_q) __attribute__((always_inline)) {
-    const int rr = __builtin_amdgcn_readfirstlane(max(rank_s[cb_b], 1));
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const int row = (cb_b * r_max + min(a, rr - 1)) * n + 16 * (wave + 8 * cb_q + 4 * u);   // uniform, in entries
-        cb[u][a] = __builtin_amdgcn_raw_buffer_load_b16(sb.lfac, lane_n, row * 2, 0);
-      }
-  };
-  if (P > 0) request_cb(cbr[0], 0, 0);
-#pragma unroll
-  for (int dd = 0; dd < SC_DEPTH; ++dd)
-    if (dd < P) request(ring[dd]);
-
-  int cb_blk = 0, cq = 0;   // block and pass-in-block of the pass being worked on
-  int r = 0;
-  size_t blk = blk0;
-  const float* wrow = wbuf;
-  auto work = [&](ScoreFetch<BITS, QJL>& cur, uint16_t (&cb)[2][4], uint16_t (&cbn)[2][4], bool more) __attribute__((always_inline)) {
-    if (cq == 0) {
-      blk = blk0 + cb_blk;
-      r = rank_s[cb_blk];
-      wrow = wbuf + cb_blk * (EOQ_RMAX_CAP * SC_MAXG);
-    }
-    const int tile = wave + 8 * cq;
-    const int64_t jb = jb0 + cb_blk;
-    // the coefficients of the next pass go out before this pass's matrix products
-    {
-      int nb = cb_blk, nq = cq + 1;
-      if (nq == ppb) {
-        nq = 0;
-        ++nb;
-      }
-      if (more) request_cb(cbn, nb, nq);
-    }
-    uint32_t word[2][BITS];
-    uint32_t sword[2] = {0u, 0u};
-    float gam[2] = {0.0f, 0.0f};
-    float rho[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-#pragma unroll
-      for (int p = 0; p < BITS; ++p) word[u][p] = cur.word[u][p];
-      rho[u] = half_bits_to_float(cur.rho[u]) * inv_sqrt_d;
-      if constexpr (QJL) {
-        sword[u] = cur.sword[u];
-        gam[u] = half_bits_to_float(cur.gam[u]) * qjl_scale;
-      }
-    }
-    float4v acc1[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, acc2[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-    if constexpr (BITS <= 2) {
-      // The codebook is symmetric: centroid = s (c_0 + (c_1 - c_0) m) with s = +-1 from the top plane and m = 1 on
-      // the outer level.  <q', z_hat> = c_0 <q', s> + (c_1 - c_0) <q', s m>: the operands +-1 and 0 are exact in
-      // binary16 and cost two logic operations per register instead of a centroid selection with a low part.
-      float4v accS[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, accT[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        H8 sg2[2], tm[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          H8 top, low;
-          top.u = mask_tab[(word[u][BITS - 1] >> (8 * kk)) & 0xFFu];
-          if constexpr (BITS == 2) low.u = mask_tab[(word[u][0] >> (8 * kk)) & 0xFFu];
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            sg2[u].w[w] = (top.w[w] & 0x80008000u) ^ 0xBC00BC00u;          // plane bit set: +1.0, clear: -1.0
-            if constexpr (BITS == 2) tm[u].w[w] = sg2[u].w[w] & ~(low.w[w] ^ top.w[w]);   // outer level only
-          }
-        }
-        accS[0] = mfma32(Aq_hi[kk], sg2[0], accS[0]);
-        accS[1] = mfma32(Aq_hi[kk], sg2[1], accS[1]);
-        accS[0] = mfma32(Aq_lo[kk], sg2[0], accS[0]);
-        accS[1] = mfma32(Aq_lo[kk], sg2[1], accS[1]);
-        if constexpr (BITS == 2) {
-          accT[0] = mfma32(Aq_hi[kk], tm[0], accT[0]);
-          accT[1] = mfma32(Aq_hi[kk], tm[1], accT[1]);
-          accT[0] = mfma32(Aq_lo[kk], tm[0], accT[0]);
-          accT[1] = mfma32(Aq_lo[kk], tm[1], accT[1]);
-        }
-      }
-      const float c0 = cent_in, dc = cent_step;
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) acc1[u][v] = (BITS == 2) ? fmaf(dc, accT[u][v], c0 * accS[u][v]) : c0 * accS[u][v];
-    } else {
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        H8 bhi[2], blo[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          uint32_t byte[BITS];
-#pragma unroll
-          for (int p = 0; p < BITS; ++p) byte[p] = (word[u][p] >> (8 * kk)) & 0xFFu;
-          bhi[u] = centroids_of<BITS, true>(byte, mask_tab, mg, &blo[u]);
-        }
-        acc1[0] = mfma32(Aq_hi[kk], bhi[0], acc1[0]);
-        acc1[1] = mfma32(Aq_hi[kk], bhi[1], acc1[1]);
-        acc1[0] = mfma32(Aq_lo[kk], bhi[0], acc1[0]);
-        acc1[1] = mfma32(Aq_lo[kk], bhi[1], acc1[1]);
-        acc1[0] = mfma32(Aq_hi[kk], blo[0], acc1[0]);
-        acc1[1] = mfma32(Aq_hi[kk], blo[1], acc1[1]);
-      }
-    }
-    // low-rank term on the vector ALU: lane (token, g) has C[i][token] and reads w[i][heads 4g .. 4g+3]
-    if (r > 0) {
-      for (int i0 = 0; i0 < r; i0 += 4) {
-        uint16_t cx[2][4];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int a = 0; a < 4; ++a)
-            cx[u][a] = (i0 == 0) ? cb[u][a]
-                                 : lfac[(blk * r_max + min(i0 + a, r - 1)) * (size_t)n + 16 * (tile + 4 * u) + l16];
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          float4 w = *reinterpret_cast<const float4*>(wrow + min(i0 + a, r - 1) * SC_MAXG + 4 * g);
-          if (i0 + a >= r) w = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const float cv = half_bits_to_float(cx[u][a]);
-            acc2[u][0] = fmaf(w.x, cv, acc2[u][0]);
-            acc2[u][1] = fmaf(w.y, cv, acc2[u][1]);
-            acc2[u][2] = fmaf(w.z, cv, acc2[u][2]);
-            acc2[u][3] = fmaf(w.w, cv, acc2[u][3]);
-          }
-        }
-      }
-    }
-    if constexpr (QJL) {
-      float4v acc3[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          H8 m, sgn;
-          m.u = mask_tab[(sword[u] >> (8 * kk)) & 0xFFu];
-#pragma unroll
-          for (int w = 0; w < 4; ++w) sgn.w[w] = (m.w[w] & 0x80008000u) ^ 0xBC00BC00u;   // bit set: +1.0, clear: -1.0
-          acc3[u] = mfma32(Ap_hi[kk], sgn, acc3[u]);
-          acc3[u] = mfma32(Ap_lo[kk], sgn, acc3[u]);
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) acc2[u][v] = fmaf(acc3[u][v], gam[u], acc2[u][v]);
-    }
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int t = 16 * (tile + 4 * u) + l16;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int h = 4 * g + v;
-        if (h < group)
-          scores[(sq * n_q_heads + kv * group + h) * T + (size_t)jb * n + t] = fmaf(acc1[u][v], rho[u], acc2[u][v]) * inv_sqrt_d;
-      }
-    }
-    if (++cq == ppb) {
-      cq = 0;
-      ++cb_blk;
-    }
-  };
-
-  // the ring has SC_DEPTH stages and the coefficient buffers two: the loop is unrolled over 2 * SC_DEPTH passes
-  static_assert(SC_DEPTH == 2, "the stages below are written out for a ring of two");
-#define EOQ_SC_STAGE(dd)                                                                       \
-  {                                                                                            \
-    const int p = p0 + dd;                                                                     \
-    if (p < P) {                                                                               \
-      work(ring[dd % SC_DEPTH], cbr[dd & 1], cbr[(dd + 1) & 1], p + 1 < P);                    \
-      if (p + SC_DEPTH < P) request(ring[dd % SC_DEPTH]);                                      \
-    }                                                                                          \
-  }
-  for (int p0 = 0; p0 < P; p0 += SC_DEPTH) {
-    EOQ_SC_STAGE(0)
-    EOQ_SC_STAGE(1)
-  }
-#undef EOQ_SC_STAGE
-}
-
-// Scores of the uncompressed tail (the newest tokens of every head, binary16, not yet a full block):
-// scores[s][h][offset + t] = <q[s][h], tail[s][g][t]> / sqrt(d).  One workgroup per (sequence, KV head); 16 lanes
-// share a token (16 bytes each), float32 accumulation of exact binary16 products.
-__global__ __launch_bounds__(THREADS) void eoq_scores_tail_kernel(
-    int n_kv_heads, int group, int64_t tail_capacity, int tail_len, const uint16_t* __restrict__ tail,
-    const uint16_t* __restrict__ q, float* __restrict__ scores, int64_t score_stride, int64_t offset) {
-  __shared__ float qs[SC_MAXG * D];
-  const int tid = threadIdx.x, l16 = tid & 15;
-  const size_t sg = blockIdx.x;
-  const size_t sq = sg / n_kv_heads, kv = sg % n_kv_heads;
-  const int n_q_heads = n_kv_heads * group;
-  for (int e = tid; e < group * D; e += THREADS) qs[e] = half_bits_to_float(q[(sq * n_q_heads + kv * group) * D + e]);
-  __syncthreads();
-  const float inv_sqrt_d = 1.0f / sqrtf((float)D);
-  for (int t0 = 0; t0 < tail_len; t0 += THREADS / 16) {   // uniform trip count: the row sums need whole rows
-    const int t = t0 + (tid >> 4);
-    float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (t < tail_len) load8(tail, EOQ_F16, (sg * (size_t)tail_capacity + t) * D + 8 * l16, x);
-    for (int h = 0; h < group; ++h) {
-      float acc = 0.0f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc = fmaf(x[e], qs[h * D + 8 * l16 + e], acc);
-      acc += dpp_mov<0xB1>(acc);
-      acc += dpp_mov<0x4E>(acc);
-      acc += dpp_mov<0x141>(acc);
-      acc += dpp_mov<0x140>(acc);
-      if (l16 == 0 && t < tail_len) scores[(sq * n_q_heads + kv * group + h) * (size_t)score_stride + offset + t] = acc * inv_sqrt_d;
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
 // encode (binary16 blocks): one workgroup per block, 128 tokens per pass.
 //   phase 1 (wave w, its own 32 tokens, v_mfma_f32_32x32x8_f16 so that every result feeds the next product
 //            without leaving the registers):
@@ -1240,70 +828,6 @@ hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void*
 #undef EOQ_DECODE
   if (L.ev) (void)hipEventRecord(L.ev[5], L.stream);
   return hipGetLastError();
-}
-
-namespace {
-hipError_t launch_scores_impl(const EoqLaunch& L, eoq_packed keys, const eoq_qjl* qjl, int64_t n_seq, int n_kv_heads,
-                              int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
-                              int64_t block_capacity, int64_t score_stride, const void* tail_fp16,
-                              int64_t tail_capacity, int tail_len) {
-  const int64_t sg_total = n_seq * n_kv_heads;
-  if (block_capacity <= 0) block_capacity = blocks_per_head;
-  if (score_stride <= 0) score_stride = blocks_per_head * L.n;
-  if (L.ev) (void)hipEventRecord(L.ev[6], L.stream);
-  if (tail_len > 0)
-    hipLaunchKernelGGL(eoq_scores_tail_kernel, dim3((unsigned)sg_total), dim3(THREADS), 0, L.stream, n_kv_heads,
-                       n_q_heads / n_kv_heads, tail_capacity, tail_len, static_cast<const uint16_t*>(tail_fp16),
-                       static_cast<const uint16_t*>(q_fp16), scores, score_stride, blocks_per_head * L.n);
-  if (blocks_per_head == 0) {
-    if (L.ev) (void)hipEventRecord(L.ev[7], L.stream);
-    return hipGetLastError();
-  }
-  // blocks per workgroup: up to 16 (the query set-up is paid once per workgroup), shorter when that leaves fewer than ~16
-  // workgroups per compute unit
-  int64_t run = (sg_total * blocks_per_head) / 4096;
-  run = run < 1 ? 1 : (run > SC_RUN_MAX ? SC_RUN_MAX : run);
-  const int64_t runs = (blocks_per_head + run - 1) / run;
-  if (sg_total > 65535 || runs > 0x7FFFFFFF) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)runs, (unsigned)sg_total), block(THREADS);
-  const uint16_t* q = static_cast<const uint16_t*>(q_fp16);
-#define EOQ_SCORES(BITS)                                                                                            \
-  do {                                                                                                              \
-    if (qjl)                                                                                                        \
-      hipLaunchKernelGGL((eoq_scores_mfma_kernel<BITS, true>), grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads,  \
-                         n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pih,    \
-                         L.tab, keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, q, scores, L.phih,         \
-                         qjl->signs, qjl->norms);                                                                   \
-    else                                                                                                            \
-      hipLaunchKernelGGL((eoq_scores_mfma_kernel<BITS, false>), grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads, \
-                         n_q_heads / n_kv_heads, blocks_per_head, block_capacity, score_stride, (int)run, L.pih,    \
-                         L.tab, keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, q, scores,                 \
-                         (const uint16_t*)nullptr, (const uint8_t*)nullptr, (const uint16_t*)nullptr);              \
-  } while (0)
-  switch (L.bits) {
-    case 1: EOQ_SCORES(1); break;
-    case 2: EOQ_SCORES(2); break;
-    case 3: EOQ_SCORES(3); break;
-    default: EOQ_SCORES(4); break;
-  }
-#undef EOQ_SCORES
-  if (L.ev) (void)hipEventRecord(L.ev[7], L.stream);
-  return hipGetLastError();
-}
-}  // namespace
-
-hipError_t eoq_launch_scores(const EoqLaunch& L, eoq_packed keys, int64_t n_seq, int n_kv_heads,
-                             int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores,
-                             int64_t block_capacity, int64_t score_stride, const void* tail_fp16,
-                             int64_t tail_capacity, int tail_len) {
-  return launch_scores_impl(L, keys, nullptr, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores,
-                            block_capacity, score_stride, tail_fp16, tail_capacity, tail_len);
-}
-
-hipError_t eoq_launch_scores_prod(const EoqLaunch& L, eoq_packed keys, eoq_qjl qjl, int64_t n_seq, int n_kv_heads,
-                                  int64_t blocks_per_head, const void* q_fp16, int n_q_heads, float* scores) {
-  return launch_scores_impl(L, keys, &qjl, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores, 0, 0, nullptr,
-                            0, 0);
 }
 
 hipError_t eoq_launch_qjl(const EoqLaunch& L, const void* blocks_fp16, int64_t B, eoq_packed rec, eoq_qjl out) {

@@ -405,17 +405,6 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
   const ushort2v r = __builtin_elementwise_max(*reinterpret_cast<ushort2v*>(&a), *reinterpret_cast<ushort2v*>(&b));
   return *reinterpret_cast<const uint32_t*>(&r);
 }
-// The four bytes of each of x0 .. x3, transposed: out[k] = bytes k of x0, x1, x2, x3 (x0 lowest).  Eight byte
-// permutes: pairs first (bytes 0/1 and 2/3 of two words interleaved), then the halves of the pairs.
-__device__ __forceinline__ void transpose_bytes(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3, uint32_t (&out)[4]) {
-  const uint32_t a01 = __builtin_amdgcn_perm(x1, x0, 0x05010400u), b01 = __builtin_amdgcn_perm(x1, x0, 0x07030602u);
-  const uint32_t a23 = __builtin_amdgcn_perm(x3, x2, 0x05010400u), b23 = __builtin_amdgcn_perm(x3, x2, 0x07030602u);
-  out[0] = __builtin_amdgcn_perm(a23, a01, 0x05040100u);
-  out[1] = __builtin_amdgcn_perm(a23, a01, 0x07060302u);
-  out[2] = __builtin_amdgcn_perm(b23, b01, 0x05040100u);
-  out[3] = __builtin_amdgcn_perm(b23, b01, 0x07060302u);
-}
-
 __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size_t tok, int n, unsigned char* pool, int tid,
                                           double (&A)[64], unsigned* flag_s) {
   const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
