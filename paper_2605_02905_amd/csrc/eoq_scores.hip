@@ -6,13 +6,14 @@
 // magnitude that is a multilinear function of the magnitude bits m_p (index bit p of the code, inverted on the negative
 // half):  z_hat_j = s_j sum_M coef[M] prod_{p in M} m_pj over the subsets M of the b-1 magnitude bits (b = 2: c_0 + (c_1 -
 // c_0) m_0).  Every term is an inner product of q' = Pi q with a vector of entries in {-1, 0, +1}: exact in int8.  q' is
-// held in 32-bit fixed point per head (a power-of-two unit, four balanced signed bytes), so the rows of the A operand of
-// v_mfma_i32_16x16x64_i8 are the four byte planes of four query heads and all sixteen rows do work; the columns are sixteen
-// tokens, the int32 sums are exact, and the four planes of a head meet again in float32 through two lane swaps.
+// multiplied by the coefficient of its term and held in 32-bit fixed point per head (a power-of-two unit, four balanced
+// signed bytes), so the rows of the A operand of v_mfma_i32_16x16x64_i8 are the four byte planes of four query heads and
+// all sixteen rows do work, the terms of a coordinate sit side by side along k (one int32 accumulator takes the whole
+// sum, exactly), the columns are sixteen tokens, and the four planes of a head meet again through three lane swaps.
 // Operand convention of v_mfma_i32_16x16x64_i8 (wave64): lane l supplies A[row = l%16][k = 16*(l/16) .. +15] and
 // B[k = 16*(l/16) .. +15][col = l%16] and receives D[row = 4*(l/16) + v][col = l%16] in accumulator register v.
 // The {-1, 0, +1} operands come out of a 256-entry LDS table indexed by one nibble of the sign plane and one nibble of a
-// magnitude plane: four coordinates of two operand kinds per 8-byte read, no select logic.
+// magnitude plane: four coordinates of two terms per 8-byte read, in the order the matrix instruction takes them.
 #include "eoq_device.h"
 #include "eoq_internal.h"
 
@@ -25,6 +26,7 @@ constexpr int THREADS = 256;
 constexpr int SC_MAXG = 8;      // most query heads per KV head
 constexpr int SC_DEPTH = 2;     // passes of record bytes in flight per wave
 constexpr int SC_RUN_MAX = 16;  // most blocks per workgroup (the run is shortened until the grid fills the chip)
+constexpr int SC_CBP = 8;       // stored coefficients of this many components are requested one pass ahead
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
@@ -76,48 +78,61 @@ __device__ __forceinline__ void rotate_query(const uint16_t* __restrict__ tab_hi
   }
 }
 
-// Rows of `rows` ([SC_MAXG][D] float, LDS) to 32-bit fixed point: per row the unit is 2^(E - 29) with E the exponent
-// of the row's largest magnitude, so |integer| <= 2^30; the integer is cut into four balanced signed bytes (the bytes of
-// I + 0x80808080 with the top bit of each flipped) and byte plane p of row h goes to dig[(4 h + p) * D + coordinate].
-// unit[h] = value of one integer unit (0 for a row that is zero, below 2^-87 or not finite).  All 256 lanes; barriers
-// inside, the last one after the planes are written.
-__device__ __forceinline__ void fixed_point_rows(const float* rows, unsigned char* dig, unsigned* max_s, float* unit, int tid) {
+// Rows of `rows` ([SC_MAXG][D] float, LDS), each multiplied by the NT coefficients coef[0 .. NT-1], to 32-bit fixed
+// point: per row the unit is 2^(E - 29) with E the exponent of the largest |coef| |entry| of the row, so |integer| <=
+// 2^30; the integer is cut into four balanced signed bytes (the bytes of I + 0x80808080 with the top bit of each flipped)
+// and byte plane p of row h goes to dig[(4 h + p) * NT * D + ...] with the NT terms of four consecutive coordinates side
+// by side: byte ((c / 4) * NT + term) * 4 + c % 4 -- the order of k in the matrix instructions.  unit[h] = value of one
+// integer unit (0 for a row that is zero, below 2^-87 or not finite).  All 256 lanes; barriers inside, the last one
+// after the planes are written.
+template <int NT>
+__device__ __forceinline__ void fixed_point_rows(const float* rows, const float (&coef)[NT], unsigned char* dig, unsigned* max_s,
+                                                 float* unit, int tid) {
   if (tid < SC_MAXG) max_s[tid] = 0u;
   __syncthreads();
   const int h = tid >> 5, c0 = 4 * (tid & 31);
+  float cmax = 0.0f;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) cmax = fmaxf(cmax, fabsf(coef[t]));
   float v[4];
   unsigned m = 0u;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     v[e] = rows[h * D + c0 + e];
-    m = max(m, (unsigned)__float_as_uint(fabsf(v[e])));
+    m = max(m, (unsigned)__float_as_uint(fabsf(v[e]) * cmax));
   }
   atomicMax(&max_s[h], m);
   __syncthreads();
   const int eb = (int)(max_s[h] >> 23);   // biased exponent of the row maximum
   const bool live = eb >= 40 && eb < 255;
-  const float up = live ? __uint_as_float((unsigned)(283 - eb) << 23) : 0.0f;   // 2^(29 - (eb - 127))
-  uint32_t dg[4];
+  const double up = live ? (double)__uint_as_float((unsigned)(283 - eb) << 23) : 0.0;   // 2^(29 - (eb - 127))
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int I = live ? __float2int_rn(v[e] * up) : 0;
-    dg[e] = ((uint32_t)I + 0x80808080u) ^ 0x80808080u;
+  for (int t = 0; t < NT; ++t) {
+    uint32_t dg[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int I = live ? __double2int_rn((double)v[e] * (double)coef[t] * up) : 0;   // one rounding, |I| <= 2^30
+      dg[e] = ((uint32_t)I + 0x80808080u) ^ 0x80808080u;
+    }
+    uint32_t pl[4];
+    transpose_bytes(dg[0], dg[1], dg[2], dg[3], pl);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) *reinterpret_cast<uint32_t*>(dig + (size_t)(4 * h + p) * NT * D + ((c0 >> 2) * NT + t) * 4) = pl[p];
   }
-  uint32_t pl[4];
-  transpose_bytes(dg[0], dg[1], dg[2], dg[3], pl);
-#pragma unroll
-  for (int p = 0; p < 4; ++p) *reinterpret_cast<uint32_t*>(dig + (4 * h + p) * D + c0) = pl[p];
   if ((tid & 31) == 0) unit[h] = live ? __uint_as_float((unsigned)(eb - 29) << 23) : 0.0f;
   __syncthreads();
 }
 
 // The {-1, 0, +1} operands of one token for this lane's 32 coordinates (bits 0..31 of the lane's word of every bit
-// plane), as B operands of two matrix instructions (coordinates 0..15 and 16..31 of the word): B[slice][M] for the subset
-// M of the magnitude bits; M = 0 is the sign alone.  Nibble k of the words (coordinates 4k .. 4k+3) is one table read:
-// entry (sign nibble | magnitude nibble << 4) = (four sign bytes, the same bytes where the magnitude bit is set).
+// plane), in the order of k that fixed_point_rows gives the query side: for every nibble (four coordinates) the terms
+// M = 0 .. TYPES-1 (M = subset of the magnitude bits, M = 0 the sign alone), four bytes each.  B[i] is the operand of
+// matrix instruction i of the 2 TYPES that cover the word.  One table read per nibble and magnitude plane: entry (sign
+// nibble | magnitude nibble << 4) = (the four sign bytes, the same bytes where the magnitude bit is set).
 template <int BITS>
-__device__ __forceinline__ void sign_operands(const uint32_t (&word)[BITS], const uint2* nib_tab, v4i (&B)[2][1 << (BITS - 1)]) {
+__device__ __forceinline__ void term_operands(const uint32_t (&word)[BITS], const uint2* nib_tab, v4i (&B)[2 << (BITS - 1)]) {
+  constexpr int TYPES = 1 << (BITS - 1);
   const uint32_t top = word[BITS - 1];
+  uint32_t term[8][TYPES];   // [nibble][term]
 #pragma unroll
   for (int p = 0; p < (BITS > 1 ? BITS - 1 : 1); ++p) {
     // magnitude bit p of a code is plane p where the sign plane is set and its complement where it is clear
@@ -128,69 +143,92 @@ __device__ __forceinline__ void sign_operands(const uint32_t (&word)[BITS], cons
     for (int k = 0; k < 8; ++k) {
       const uint32_t idx = (((k & 1) ? odd : even) >> (8 * (k >> 1))) & 0xFFu;
       if (p == 0) {
-        const uint2 e = nib_tab[idx];
-        B[k >> 2][0][k & 3] = (int)e.x;
-        if constexpr (BITS > 1) B[k >> 2][1][k & 3] = (int)e.y;
+        if constexpr (BITS > 1) {
+          const uint2 e = nib_tab[idx];
+          term[k][0] = e.x;
+          term[k][1] = e.y;
+        } else {
+          term[k][0] = nib_tab[idx].x;
+        }
       } else {
-        B[k >> 2][1 << p][k & 3] = (int)nib_tab[idx].y;
+        term[k][(1 << p) % TYPES] = nib_tab[idx].y;
       }
     }
   }
   // products of several magnitude bits: bytes are 0 or the sign byte, so the product is the bitwise AND
 #pragma unroll
-  for (int M = 3; M < (1 << (BITS - 1)); ++M) {
+  for (int M = 3; M < TYPES; ++M) {
     if ((M & (M - 1)) != 0) {
       const int low = M & -M;
 #pragma unroll
-      for (int s = 0; s < 2; ++s) B[s][M] = B[s][low] & B[s][M ^ low];
+      for (int k = 0; k < 8; ++k) term[k][M] = term[k][low] & term[k][M ^ low];
     }
   }
+#pragma unroll
+  for (int i = 0; i < 2 * TYPES; ++i)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int flat = 4 * i + w;   // dword number along k: nibble flat / TYPES, term flat % TYPES
+      B[i][w] = (int)term[flat / TYPES][flat % TYPES];
+    }
 }
 
-// Sum of the four lanes l%16 + 16 g, g = 0..3, of value v[g'] for g' = 0..3, transposing: lane group g returns the total
-// of v[g].  v_permlane32_swap exchanges the upper half of its first operand with the lower half of its second,
-// v_permlane16_swap the odd 16-lane rows of the first with the even rows of the second.
-__device__ __forceinline__ float fold_planes(float v0, float v1, float v2, float v3) {
+// The four accumulator registers of a lane are four heads of byte plane g = lane / 16.  Joins the planes: lane group g
+// returns sum_p 256^p (register g of plane p), the value of head g in integer units.  v_permlane16_swap exchanges the odd
+// 16-lane rows of its first operand with the even rows of its second, v_permlane32_swap the upper half of the first with
+// the lower half of the second; planes 2k and 2k + 1 are joined exactly in int32 (|register| < 2^18), the two halves in
+// float32.
+__device__ __forceinline__ float join_planes(const v4i& acc) {
   typedef unsigned int u2 __attribute__((ext_vector_type(2)));
-  const u2 a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v0), __float_as_uint(v2), false, false);
-  const u2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v1), __float_as_uint(v3), false, false);
-  const float ra = __uint_as_float(a[0]) + __uint_as_float(a[1]);   // lower half: value 0, upper half: value 2
-  const float rb = __uint_as_float(b[0]) + __uint_as_float(b[1]);   // lower half: value 1, upper half: value 3
-  const u2 c = __builtin_amdgcn_permlane16_swap(__float_as_uint(ra), __float_as_uint(rb), false, false);
-  return __uint_as_float(c[0]) + __uint_as_float(c[1]);
+  const u2 a = __builtin_amdgcn_permlane16_swap((unsigned)acc[0], (unsigned)acc[1], false, false);
+  const u2 b = __builtin_amdgcn_permlane16_swap((unsigned)acc[2], (unsigned)acc[3], false, false);
+  // even rows: (own plane, head r | plane + 1, head r), odd rows: (plane - 1, head r | own plane, head r); r = row parity
+  const int ta = (int)a[0] + (int)a[1] * 256;   // head r,     planes 2k, 2k + 1
+  const int tb = (int)b[0] + (int)b[1] * 256;   // head 2 + r, planes 2k, 2k + 1
+  const u2 c = __builtin_amdgcn_permlane32_swap((unsigned)ta, (unsigned)tb, false, false);
+  // lower half: (planes 0-1 of head r, planes 2-3 of head r); upper half: (planes 0-1 of head 2 + r, planes 2-3 of it)
+  return fmaf((float)(int)c[1], 65536.0f, (float)(int)c[0]);
 }
 
-// What a lane requests of one pass (32 consecutive tokens per wave): lane (l16, g) works on tokens 2 l16 and 2 l16 + 1
-// of the pass: word g of every bit plane of both, their two stored norms as one word (with QJL also the sign words and
-// the residual norms).
+// 4 x 4 transpose across the four lane groups: on entry lane group g holds r0 .. r3, on return lane group s holds
+// out[g] = (r_s of lane group g).
+__device__ __forceinline__ void transpose_groups(float r0, float r1, float r2, float r3, float (&out)[4]) {
+  typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+  const u2 a = __builtin_amdgcn_permlane32_swap(__float_as_uint(r0), __float_as_uint(r2), false, false);
+  const u2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(r1), __float_as_uint(r3), false, false);
+  const u2 c = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
+  const u2 d = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
+  out[0] = __uint_as_float(c[0]);
+  out[1] = __uint_as_float(c[1]);
+  out[2] = __uint_as_float(d[0]);
+  out[3] = __uint_as_float(d[1]);
+}
+
+// What a lane requests of one chunk of 128 consecutive tokens (the unit of work of a wave): piece i of the chunk's codes
+// (bytes 1024 i + 16 lane .. + 15: every load instruction covers 1 KB without gaps), the stored norms and the stored
+// coefficients of ITS OWN two tokens 2 lane and 2 lane + 1 of the chunk (with QJL also the sign planes and residual norms).
 template <int BITS, bool QJL>
-struct ScoreFetch {
-  uint32_t word[2][BITS];
+struct ChunkFetch {
+  uint4 code[2 * BITS];
   uint32_t rho2;
-  uint32_t sword[2];
+  uint32_t cf[SC_CBP];
+  uint4 sign[QJL ? 2 : 1];
   uint32_t gam2;
 };
 // Buffer addressing: a resource descriptor in scalar registers (base of this workgroup's run of blocks, size of the
-// run: reads past it return zero instead of faulting), a scalar byte offset that moves from pass to pass and a per-lane
+// run: reads past it return zero instead of faulting), a scalar byte offset that moves from chunk to chunk and a per-lane
 // 32-bit offset that never changes -- no vector arithmetic per load.
 struct ScoreBuffers {
   __amdgpu_buffer_rsrc_t codes, norms, lfac, qsigns, qnorms;
 };
-// `tokb` (first token of the pass, counted from the start of the run) is wave-uniform.
-template <int BITS, bool QJL>
-__device__ __forceinline__ void score_fetch(ScoreFetch<BITS, QJL>& f, const ScoreBuffers& sb, int tokb, uint32_t lane_c,
-                                            uint32_t lane_s, uint32_t lane_n) {
-  constexpr int ROWB = BITS * D / 8;
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-#pragma unroll
-    for (int p = 0; p < BITS; ++p)
-      f.word[u][p] = __builtin_amdgcn_raw_buffer_load_b32(sb.codes, lane_c + u * ROWB + p * 16, tokb * ROWB, 0);
-    if constexpr (QJL) f.sword[u] = __builtin_amdgcn_raw_buffer_load_b32(sb.qsigns, lane_s + u * (D / 8), tokb * (D / 8), 0);
-  }
-  f.rho2 = __builtin_amdgcn_raw_buffer_load_b32(sb.norms, lane_n, tokb * 2, 0);
-  if constexpr (QJL) f.gam2 = __builtin_amdgcn_raw_buffer_load_b32(sb.qnorms, lane_n, tokb * 2, 0);
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_b128(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, int soffset) {
+  const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voffset, soffset, 0);
+  return make_uint4(v[0], v[1], v[2], v[3]);
 }
+// LDS staging of a chunk's codes: 16 bytes of padding after every 256, so that the sixteen token pairs a matrix
+// instruction's lanes read side by side (64 BITS/2 bytes apart) fall into different banks while 16-byte pieces stay aligned.
+__host__ __device__ constexpr int stage_pad(int a) { return a + ((a >> 8) << 4); }
 
 // One workgroup per (sequence, KV head, run of blocks).  NSETS = sets of four query heads (1 for groups up to 4).
 // QJL: the logits get the correction of Eq. (qjl), |r_x| sqrt(pi/2)/d <Phi q, sign(Phi r_x)>, from one more bit plane
@@ -209,7 +247,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
   __shared__ __align__(16) float wbuf[SC_RUN_MAX * EOQ_RMAX_CAP * SC_MAXG];   // [block of the run][component][head]: <v_i, q_h>/sqrt(d)
   __shared__ int rank_s[SC_RUN_MAX];
   __shared__ __align__(16) uint2 nib_tab[256];
-  __shared__ __align__(16) unsigned char qdig[SC_MAXG * 4 * D];               // byte planes of Pi q, [head][plane][coordinate]
+  __shared__ __align__(16) unsigned char qdig[SC_MAXG * 4 * TYPES * D];       // byte planes of coef[M] Pi q, [head][plane][k]
   __shared__ __align__(16) unsigned char pdig[QJL ? SC_MAXG * 4 * D : 16];    // byte planes of Phi q
   __shared__ unsigned max_s[SC_MAXG];
   __shared__ float qunit[SC_MAXG], punit[SC_MAXG];
@@ -237,35 +275,6 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
   }
   for (int e = tid; e < SC_MAXG * D; e += THREADS) qraw[e] = (e < group * D) ? half_bits_to_float(q[q0 + e]) : 0.0f;
   __syncthreads();
-  // q' = Pi q (the rotation moved to the query side: <q, Pi^T z> = <Pi q, z>), then its fixed-point byte planes
-  rotate_query(pih, pih + D * D, q + q0, group, qrot, wave, l16, g);
-  __syncthreads();
-  fixed_point_rows(qrot, qdig, max_s, qunit, tid);
-  if constexpr (QJL) {
-    rotate_query(phih, nullptr, q + q0, group, qrot, wave, l16, g);
-    __syncthreads();
-    fixed_point_rows(qrot, pdig, max_s, punit, tid);
-  }
-  // A operands: row l16 = byte plane l16 / 4 of head 4 hs + l16 % 4; slice s covers the coordinates 32 g + 16 s .. + 15.
-  // K[hs][v]: what one unit of accumulator register v (head 4 hs + v, plane g) is worth in the logit.
-  v4i Aq[NSETS][2], Ap[QJL ? NSETS : 1][2];
-  float Kq[NSETS][4], Kp[QJL ? NSETS : 1][4];
-  const float qjl_scale = sqrtf(1.5707963267948966f) / (float)D;
-  const float plane_w = (float)(1u << (8 * g));
-#pragma unroll
-  for (int hs = 0; hs < NSETS; ++hs) {
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const int off = (4 * (4 * hs + (l16 & 3)) + (l16 >> 2)) * D + 32 * g + 16 * s;
-      Aq[hs][s] = *reinterpret_cast<const v4i*>(qdig + off);
-      if constexpr (QJL) Ap[hs][s] = *reinterpret_cast<const v4i*>(pdig + off);
-    }
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      Kq[hs][v] = qunit[4 * hs + v] * plane_w * (1.0f / (float)D);   // z_hat = centroid / sqrt(d), logit = <q, x_hat> / sqrt(d)
-      if constexpr (QJL) Kp[hs][v] = punit[4 * hs + v] * plane_w * (qjl_scale * inv_sqrt_d);
-    }
-  }
   // coefficients of the multilinear form of the magnitudes: level number sum_p m_p 2^p is centroid L/2 + level of the
   // ascending N(0,1) table; coef[M] = sum over subsets S of M of (-1)^(|M| - |S|) centroid[L/2 + S]
   float coef[TYPES];
@@ -277,19 +286,53 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
       if ((S & M) == S) c += ((__builtin_popcount(M ^ S) & 1) ? -1.0f : 1.0f) * tab[TYPES + S];
     coef[M] = c;
   }
+  // q' = Pi q (the rotation moved to the query side: <q, Pi^T z> = <Pi q, z>), then the byte planes of coef[M] q'
+  rotate_query(pih, pih + D * D, q + q0, group, qrot, wave, l16, g);
+  __syncthreads();
+  fixed_point_rows<TYPES>(qrot, coef, qdig, max_s, qunit, tid);
+  if constexpr (QJL) {
+    rotate_query(phih, nullptr, q + q0, group, qrot, wave, l16, g);
+    __syncthreads();
+    const float one[1] = {1.0f};
+    fixed_point_rows<1>(qrot, one, pdig, max_s, punit, tid);
+  }
+  // A operands: row l16 = byte plane l16 / 4 of head 4 hs + l16 % 4; instruction i of a token covers the 16 bytes of k
+  // from 16 i of lane group g's 32 coordinates (32 TYPES bytes).  Kq / Kp: what one integer unit of head 4 hs + v is
+  // worth in the logit.
+  v4i Aq[NSETS][2 * TYPES], Ap[QJL ? NSETS : 1][2];
+  float Kq[NSETS][4], Kp[QJL ? NSETS : 1][4];
+  const float qjl_scale = sqrtf(1.5707963267948966f) / (float)D;
+#pragma unroll
+  for (int hs = 0; hs < NSETS; ++hs) {
+    const int row = 4 * (4 * hs + (l16 & 3)) + (l16 >> 2);
+#pragma unroll
+    for (int i = 0; i < 2 * TYPES; ++i) Aq[hs][i] = *reinterpret_cast<const v4i*>(qdig + ((size_t)row * D + 32 * g) * TYPES + 16 * i);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) Kq[hs][v] = qunit[4 * hs + v] * (1.0f / (float)D);   // z_hat = centroid / sqrt(d), logit = <q, x_hat> / sqrt(d)
+    if constexpr (QJL) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) Ap[hs][i] = *reinterpret_cast<const v4i*>(pdig + row * D + 32 * g + 16 * i);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Kp[hs][v] = punit[4 * hs + v] * (qjl_scale * inv_sqrt_d);
+    }
+  }
 
-  // The work of this workgroup as a flat list of passes: pass p of a wave covers the 32 tokens from 32 (wave + 4 q) of
-  // block jb0 + p / ppb, q = p % ppb.  The record bytes of a pass are requested SC_DEPTH passes ahead into a ring of
-  // registers (the loop is unrolled over the ring, so nothing is copied and a pass only waits for its own bytes), the
-  // stored coefficients one pass ahead.
+  // The work of this workgroup as a flat list of chunks of 128 tokens: chunk u of the run is tokens 128 (u % cpb) ..
+  // of block jb0 + u / cpb; wave w takes the chunks w, w + 4, ...  The record bytes of a chunk are requested one chunk
+  // ahead into registers; the codes then pass through a wave-private LDS buffer, which hands every lane of a matrix
+  // instruction the words of its token pair, in four sub-passes of 32 tokens (tile u of sub-pass s: tokens 32 s + 2 c + u
+  // in column c).  After the four sub-passes a lane group holds one head of all four; a 4 x 4 transpose across the lane
+  // groups gives lane L all heads of its own tokens 2 L and 2 L + 1, which it scales by its own stored norms, completes
+  // with the low-rank term from its own stored coefficients and stores as 8 bytes per head: 512 contiguous bytes per wave
+  // and score row.
   const int64_t jb0 = (int64_t)blockIdx.x * run;
   const int nblk = (int)(min(jb0 + run, blocks_per_head) - jb0);
-  const int ppb = n / 128;
-  const int P = nblk * ppb;
+  const int cpb = n / 128;
+  const int NCH = nblk * cpb;
   const size_t blk0 = sg * (size_t)block_capacity + jb0;   // the store holds block_capacity slots per head
 
   // w[b][i][h] = <v_i, q_h>/sqrt(d) of every block of the run, up front (the low-rank term is <C_t, w_h>): all loads of
-  // the set-up are in flight together and the pass loop below has no barrier.  16 lanes per (component, head): one
+  // the set-up are in flight together and the chunk loop below has no barrier.  16 lanes per (component, head): one
   // 16-byte load of eight entries of v_i each, then a sum over the DPP row.
   if (tid < nblk) rank_s[tid] = min(max(rank_in[blk0 + tid], 0), r_max);   // records may come from storage: never index past r_max rows
   __syncthreads();
@@ -315,9 +358,6 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
   }
   __syncthreads();
 
-  const uint32_t lane_c = (uint32_t)(2 * l16 * ROWB + 4 * g);      // into the codes of a pass
-  const uint32_t lane_s = (uint32_t)(2 * l16 * (D / 8) + 4 * g);   // into the sign planes of a pass
-  const uint32_t lane_n = (uint32_t)(4 * l16);                     // into the norms / a coefficient row of a pass
   ScoreBuffers sb;
   sb.codes = buffer_of(codes + blk0 * (size_t)n * ROWB, (size_t)nblk * n * ROWB);
   sb.norms = buffer_of(norms + blk0 * (size_t)n, (size_t)nblk * n * 2);
@@ -326,147 +366,182 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
     sb.qsigns = buffer_of(qsigns + blk0 * (size_t)n * (D / 8), (size_t)nblk * n * (D / 8));
     sb.qnorms = buffer_of(qnorms + blk0 * (size_t)n, (size_t)nblk * n * 2);
   }
-  ScoreFetch<BITS, QJL> ring[SC_DEPTH];
-  uint32_t cbr[2][4];      // [parity of the pass][component of the first four]: coefficients of the lane's two tokens
-  int fb = 0, fq = 0;      // block and pass-in-block of the next pass to request
-  auto request = [&](ScoreFetch<BITS, QJL>& f) __attribute__((always_inline)) {
-    score_fetch<BITS, QJL>(f, sb, fb * n + 32 * (wave + 4 * fq), lane_c, lane_s, lane_n);
-    if (++fq == ppb) {
-      fq = 0;
-      ++fb;
+  // chunk u: block u / cpb of the run, tokens 128 (u % cpb) ..; rows at and above the rank are asked for at an offset
+  // past the end of the buffer: those loads return zero without touching memory
+  auto request = [&](ChunkFetch<BITS, QJL>& f, int u) __attribute__((always_inline)) {
+    const int b = u / cpb, c = u - b * cpb;
+    const int tokb = b * n + 128 * c;   // uniform: first token of the chunk, counted from the start of the run
+#pragma unroll
+    for (int i = 0; i < 2 * BITS; ++i) f.code[i] = load_b128(sb.codes, 16u * lane, tokb * ROWB + 1024 * i);
+    f.rho2 = __builtin_amdgcn_raw_buffer_load_b32(sb.norms, 4u * lane, tokb * 2, 0);
+    const int rr = __builtin_amdgcn_readfirstlane(rank_s[b]);
+#pragma unroll
+    for (int a = 0; a < SC_CBP; ++a) {
+      const int row = (b * r_max + a) * n + 128 * c;   // uniform, in entries
+      f.cf[a] = __builtin_amdgcn_raw_buffer_load_b32(sb.lfac, 4u * lane, (a < rr) ? row * 2 : 0x7FFFFF00, 0);
+    }
+    if constexpr (QJL) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) f.sign[i] = load_b128(sb.qsigns, 16u * lane, tokb * (D / 8) + 1024 * i);
+      f.gam2 = __builtin_amdgcn_raw_buffer_load_b32(sb.qnorms, 4u * lane, tokb * 2, 0);
     }
   };
-  // coefficients C[i][tokens] of the first four components of pass (cb_b, cb_q); row 0 is read when the rank is 0
-  auto request_cb = [&](uint32_t (&cb)[4], int cb_b, int cb_q) __attribute__((always_inline)) {
-    const int rr = __builtin_amdgcn_readfirstlane(max(rank_s[cb_b], 1));
-#pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const int row = (cb_b * r_max + min(a, rr - 1)) * n + 32 * (wave + 4 * cb_q);   // uniform, in entries
-      cb[a] = __builtin_amdgcn_raw_buffer_load_b32(sb.lfac, lane_n, row * 2, 0);
-    }
-  };
-  if (P > 0) request_cb(cbr[0], 0, 0);
-#pragma unroll
-  for (int dd = 0; dd < SC_DEPTH; ++dd)
-    if (dd < P) request(ring[dd]);
 
-  int cb_blk = 0, cq = 0;   // block and pass-in-block of the pass being worked on
-  int r = 0;
-  size_t blk = blk0;
-  const float* wrow = wbuf;
-  const bool even_stride = (T & 1) == 0;
-  auto work = [&](ScoreFetch<BITS, QJL>& cur, uint32_t (&cb)[4], uint32_t (&cbn)[4], bool more) __attribute__((always_inline)) {
-    if (cq == 0) {
-      blk = blk0 + cb_blk;
-      r = rank_s[cb_blk];
-      wrow = wbuf + cb_blk * (EOQ_RMAX_CAP * SC_MAXG);
-    }
-    const int tok0 = 32 * (wave + 4 * cq);   // first token of the pass inside its block
-    const int64_t jb = jb0 + cb_blk;
-    // the coefficients of the next pass go out before this pass's matrix products
-    {
-      int nb = cb_blk, nq = cq + 1;
-      if (nq == ppb) {
-        nq = 0;
-        ++nb;
-      }
-      if (more) request_cb(cbn, nb, nq);
-    }
-    float res[2][NSETS];
+  // this wave's staging buffers and the lane's read addresses in them (sub-pass 0; sub-pass s is a constant further on)
+  constexpr int CODE_STAGE = stage_pad(128 * ROWB), SIGN_STAGE = stage_pad(128 * (D / 8));
+  __shared__ __align__(16) unsigned char stage_s[4 * (CODE_STAGE + (QJL ? SIGN_STAGE : 0))];
+  unsigned char* stage_c = stage_s + wave * (CODE_STAGE + (QJL ? SIGN_STAGE : 0));
+  unsigned char* stage_q = stage_c + CODE_STAGE;
+  int rd_c[2][BITS], rd_q[2];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      v4i B[2][TYPES];
-      sign_operands<BITS>(cur.word[u], nib_tab, B);
-      const float rho = half_bits_to_float((uint16_t)(u ? (cur.rho2 >> 16) : (cur.rho2 & 0xFFFFu)));
+  for (int u = 0; u < 2; ++u) {
+#pragma unroll
+    for (int p = 0; p < BITS; ++p) rd_c[u][p] = stage_pad((2 * l16 + u) * ROWB + 16 * p + 4 * g);
+    rd_q[u] = stage_pad((2 * l16 + u) * (D / 8) + 4 * g);
+  }
+  constexpr int SUB_C = stage_pad(32 * ROWB), SUB_Q = stage_pad(32 * (D / 8));   // one sub-pass further (multiples of 256 before padding)
+  const int wr = stage_pad(16 * lane);                                           // where the lane's piece of 1 KB number 0 goes
+
+  const bool even_stride = (T & 1) == 0;
+  auto work = [&](ChunkFetch<BITS, QJL>& cur, int u_chunk) __attribute__((always_inline)) {
+    const int cb_blk = u_chunk / cpb, cq = u_chunk - cb_blk * cpb;
+    const size_t blk = blk0 + cb_blk;
+    const int r = rank_s[cb_blk];
+    const float* wrow = wbuf + cb_blk * (EOQ_RMAX_CAP * SC_MAXG);
+    const int64_t jb = jb0 + cb_blk;
+    // ---- the codes change lanes through LDS (the buffer is this wave's own: its LDS operations complete in order) ----
+#pragma unroll
+    for (int i = 0; i < 2 * BITS; ++i) *reinterpret_cast<uint4*>(stage_c + wr + stage_pad(1024) * i) = cur.code[i];
+    if constexpr (QJL) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4*>(stage_q + wr + stage_pad(1024) * i) = cur.sign[i];
+    }
+    __builtin_amdgcn_wave_barrier();
+    float tq[4][2][NSETS], tp[QJL ? 4 : 1][2][NSETS];   // [sub-pass][tile][set]: head 4 hs + g in integer units
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp) {
+      v4i B[2][2 * TYPES];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        uint32_t word[BITS];
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) word[p] = *reinterpret_cast<const uint32_t*>(stage_c + rd_c[u][p] + SUB_C * sp);
+        term_operands<BITS>(word, nib_tab, B[u]);
+      }
 #pragma unroll
       for (int hs = 0; hs < NSETS; ++hs) {
-        v4i acc[TYPES];
+        v4i acc[2];
 #pragma unroll
-        for (int M = 0; M < TYPES; ++M) {
-          acc[M] = v4i{0, 0, 0, 0};
-          acc[M] = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aq[hs][0], B[0][M], acc[M], 0, 0, 0);
-          acc[M] = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aq[hs][1], B[1][M], acc[M], 0, 0, 0);
+        for (int u = 0; u < 2; ++u) {
+          acc[u] = v4i{0, 0, 0, 0};
+#pragma unroll
+          for (int i = 0; i < 2 * TYPES; ++i) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aq[hs][i], B[u][i], acc[u], 0, 0, 0);
         }
-        float val[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          float s = coef[0] * (float)acc[0][v];
-#pragma unroll
-          for (int M = 1; M < TYPES; ++M) s = fmaf(coef[M], (float)acc[M][v], s);
-          val[v] = s * Kq[hs][v];
-        }
-        res[u][hs] = fold_planes(val[0], val[1], val[2], val[3]) * rho;   // head 4 hs + g
+        for (int u = 0; u < 2; ++u) tq[sp][u][hs] = join_planes(acc[u]);
       }
       if constexpr (QJL) {
         // sign(Phi r_x) is one more plane of +-1: the table's first entry kind with the magnitude nibble at zero
-        const uint32_t sw = cur.sword[u];
-        v4i Bs[2];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) Bs[k >> 2][k & 3] = (int)nib_tab[(sw >> (4 * k)) & 0xFu].x;
-        const float gam = half_bits_to_float((uint16_t)(u ? (cur.gam2 >> 16) : (cur.gam2 & 0xFFFFu)));
+        for (int u = 0; u < 2; ++u) {
+          const uint32_t sw = *reinterpret_cast<const uint32_t*>(stage_q + rd_q[u] + SUB_Q * sp);
+          v4i Bs[2];
 #pragma unroll
-        for (int hs = 0; hs < NSETS; ++hs) {
-          v4i acc = {0, 0, 0, 0};
-          acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(Ap[hs][0], Bs[0], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(Ap[hs][1], Bs[1], acc, 0, 0, 0);
-          const float t = fold_planes((float)acc[0] * Kp[hs][0], (float)acc[1] * Kp[hs][1], (float)acc[2] * Kp[hs][2],
-                                      (float)acc[3] * Kp[hs][3]);
-          res[u][hs] = fmaf(t, gam, res[u][hs]);
+          for (int k = 0; k < 8; ++k) Bs[k >> 2][k & 3] = (int)nib_tab[(sw >> (4 * k)) & 0xFu].x;
+#pragma unroll
+          for (int hs = 0; hs < NSETS; ++hs) {
+            v4i acc = {0, 0, 0, 0};
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(Ap[hs][0], Bs[0], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(Ap[hs][1], Bs[1], acc, 0, 0, 0);
+            tp[sp][u][hs] = join_planes(acc);
+          }
         }
       }
     }
-    // low-rank term on the vector ALU: the lane has C[i][its two tokens] and reads w[i][head 4 hs + g]
-    if (r > 0) {
-      for (int i0 = 0; i0 < r; i0 += 4) {
+    __builtin_amdgcn_wave_barrier();   // the staging buffer is rewritten by the next chunk
+    // ---- to the lanes that own the tokens: lane group sp takes sub-pass sp, register index becomes the head ----
+    const float rho[2] = {half_bits_to_float((uint16_t)(cur.rho2 & 0xFFFFu)), half_bits_to_float((uint16_t)(cur.rho2 >> 16))};
+    float gam[2] = {0.0f, 0.0f};
+    if constexpr (QJL) {
+      gam[0] = half_bits_to_float((uint16_t)(cur.gam2 & 0xFFFFu));
+      gam[1] = half_bits_to_float((uint16_t)(cur.gam2 >> 16));
+    }
+    float res[4][2][NSETS];   // [head of the set][token][set]
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          const int i = min(i0 + a, r - 1);
-          const uint32_t cx = (i0 == 0) ? cb[a]
-                                        : *reinterpret_cast<const uint32_t*>(lfac + (blk * r_max + i) * (size_t)n + tok0 + 2 * l16);
-          const float c0 = half_bits_to_float((uint16_t)(cx & 0xFFFFu)), c1 = half_bits_to_float((uint16_t)(cx >> 16));
+    for (int hs = 0; hs < NSETS; ++hs)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        float h4[4];
+        transpose_groups(tq[0][u][hs], tq[1][u][hs], tq[2][u][hs], tq[3][u][hs], h4);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) res[v][u][hs] = h4[v] * (Kq[hs][v] * rho[u]);
+        if constexpr (QJL) {
+          transpose_groups(tp[0][u][hs], tp[1][u][hs], tp[2][u][hs], tp[3][u][hs], h4);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) res[v][u][hs] = fmaf(h4[v], Kp[hs][v] * gam[u], res[v][u][hs]);
+        }
+      }
+    // ---- low-rank term from the lane's own coefficients: sum_i C[i][token] w[i][head] ----
+    if (r > 0) {
+#pragma unroll
+      for (int a = 0; a < SC_CBP; ++a) {
+        if (a < r) {   // uniform
+          const float c0 = half_bits_to_float((uint16_t)(cur.cf[a] & 0xFFFFu)), c1 = half_bits_to_float((uint16_t)(cur.cf[a] >> 16));
 #pragma unroll
           for (int hs = 0; hs < NSETS; ++hs) {
-            const float w = (i0 + a < r) ? wrow[i * SC_MAXG + 4 * hs + g] : 0.0f;
-            res[0][hs] = fmaf(w, c0, res[0][hs]);
-            res[1][hs] = fmaf(w, c1, res[1][hs]);
+            const float4 w = *reinterpret_cast<const float4*>(wrow + a * SC_MAXG + 4 * hs);
+            const float wv[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              res[v][0][hs] = fmaf(wv[v], c0, res[v][0][hs]);
+              res[v][1][hs] = fmaf(wv[v], c1, res[v][1][hs]);
+            }
+          }
+        }
+      }
+      for (int i = SC_CBP; i < r; ++i) {   // ranks above SC_CBP: read in place
+        const uint32_t cx = *reinterpret_cast<const uint32_t*>(lfac + (blk * r_max + i) * (size_t)n + 128 * cq + 2 * lane);
+        const float c0 = half_bits_to_float((uint16_t)(cx & 0xFFFFu)), c1 = half_bits_to_float((uint16_t)(cx >> 16));
+#pragma unroll
+        for (int hs = 0; hs < NSETS; ++hs) {
+          const float4 w = *reinterpret_cast<const float4*>(wrow + i * SC_MAXG + 4 * hs);
+          const float wv[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            res[v][0][hs] = fmaf(wv[v], c0, res[v][0][hs]);
+            res[v][1][hs] = fmaf(wv[v], c1, res[v][1][hs]);
           }
         }
       }
     }
 #pragma unroll
-    for (int hs = 0; hs < NSETS; ++hs) {
-      const int h = 4 * hs + g;
-      if (h < group) {
-        float* dst = scores + (sq * n_q_heads + kv * group + h) * T + (size_t)jb * n + tok0 + 2 * l16;
-        if (even_stride) {
-          *reinterpret_cast<float2*>(dst) = make_float2(res[0][hs], res[1][hs]);
-        } else {
-          dst[0] = res[0][hs];
-          dst[1] = res[1][hs];
+    for (int hs = 0; hs < NSETS; ++hs)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int h = 4 * hs + v;
+        if (h < group) {   // uniform
+          float* dst = scores + (sq * n_q_heads + kv * group + h) * T + (size_t)jb * n + 128 * cq + 2 * lane;
+          if (even_stride) {
+            *reinterpret_cast<float2*>(dst) = make_float2(res[v][0][hs], res[v][1][hs]);
+          } else {
+            dst[0] = res[v][0][hs];
+            dst[1] = res[v][1][hs];
+          }
         }
       }
-    }
-    if (++cq == ppb) {
-      cq = 0;
-      ++cb_blk;
-    }
   };
 
-  // the ring has SC_DEPTH stages and the coefficient buffers two: the loop is unrolled over 2 passes
-  static_assert(SC_DEPTH == 2, "the stages below are written out for a ring of two");
-#define EOQ_SC_STAGE(dd)                                                                       \
-  {                                                                                            \
-    const int p = p0 + dd;                                                                     \
-    if (p < P) {                                                                               \
-      work(ring[dd % SC_DEPTH], cbr[dd & 1], cbr[(dd + 1) & 1], p + 1 < P);                    \
-      if (p + SC_DEPTH < P) request(ring[dd % SC_DEPTH]);                                      \
-    }                                                                                          \
+  // two register sets in turn: the next chunk is requested before this one is worked on
+  ChunkFetch<BITS, QJL> fa, fb;
+  if (wave < NCH) request(fa, wave);
+  for (int u0 = wave; u0 < NCH; u0 += 8) {
+    if (u0 + 4 < NCH) request(fb, u0 + 4);
+    work(fa, u0);
+    if (u0 + 4 < NCH) {
+      if (u0 + 8 < NCH) request(fa, u0 + 8);
+      work(fb, u0 + 4);
+    }
   }
-  for (int p0 = 0; p0 < P; p0 += SC_DEPTH) {
-    EOQ_SC_STAGE(0)
-    EOQ_SC_STAGE(1)
-  }
-#undef EOQ_SC_STAGE
 }
 
 // Scores of the uncompressed tail (the newest tokens of every head, binary16, not yet a full block):
