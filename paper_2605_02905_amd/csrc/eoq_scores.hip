@@ -242,13 +242,21 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
     const uint16_t* __restrict__ q, float* __restrict__ scores, const uint16_t* __restrict__ phih,
     const uint8_t* __restrict__ qsigns, const uint16_t* __restrict__ qnorms) {
   constexpr int TYPES = 1 << (BITS - 1);
-  __shared__ float qraw[SC_MAXG * D];
-  __shared__ float qrot[SC_MAXG * D];
-  __shared__ __align__(16) float wbuf[SC_RUN_MAX * EOQ_RMAX_CAP * SC_MAXG];   // [block of the run][component][head]: <v_i, q_h>/sqrt(d)
+  constexpr int WH = 4 * NSETS;   // heads the run's w table holds
+  // One pool, used in turn: during the set-up the query (float), its rotation, and the byte planes of coef[M] Pi q
+  // ([head][plane][k]) and of Phi q; in the chunk loop the four waves' staging buffers.  The barrier behind the w table
+  // separates the two uses.
+  constexpr int CODE_STAGE = stage_pad(128 * (BITS * D / 8)), SIGN_STAGE = QJL ? stage_pad(128 * (D / 8)) : 0;
+  constexpr int SETUP_BYTES = 2 * SC_MAXG * D * 4 + SC_MAXG * 4 * TYPES * D + (QJL ? SC_MAXG * 4 * D : 0);
+  constexpr int LOOP_BYTES = 4 * (CODE_STAGE + SIGN_STAGE);
+  __shared__ __align__(16) unsigned char pool[SETUP_BYTES > LOOP_BYTES ? SETUP_BYTES : LOOP_BYTES];
+  float* qraw = reinterpret_cast<float*>(pool);
+  float* qrot = qraw + SC_MAXG * D;
+  unsigned char* qdig = pool + 2 * SC_MAXG * D * 4;
+  unsigned char* pdig = qdig + SC_MAXG * 4 * TYPES * D;
+  __shared__ __align__(16) float wbuf[SC_RUN_MAX * EOQ_RMAX_CAP * WH];   // [block of the run][component][head]: <v_i, q_h>/sqrt(d)
   __shared__ int rank_s[SC_RUN_MAX];
   __shared__ __align__(16) uint2 nib_tab[256];
-  __shared__ __align__(16) unsigned char qdig[SC_MAXG * 4 * TYPES * D];       // byte planes of coef[M] Pi q, [head][plane][k]
-  __shared__ __align__(16) unsigned char pdig[QJL ? SC_MAXG * 4 * D : 16];    // byte planes of Phi q
   __shared__ unsigned max_s[SC_MAXG];
   __shared__ float qunit[SC_MAXG], punit[SC_MAXG];
 
@@ -338,10 +346,10 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
   __syncthreads();
   int rtop = 0;
   for (int b = 0; b < nblk; ++b) rtop = max(rtop, rank_s[b]);
-  for (int e0 = 0; e0 < nblk * rtop * (SC_MAXG * 16); e0 += THREADS) {   // uniform trip count: whole rows reduce together
+  for (int e0 = 0; e0 < nblk * rtop * (WH * 16); e0 += THREADS) {   // uniform trip count: whole rows reduce together
     const int e = e0 + tid;
-    const int seg = e & 15, h = (e >> 4) & (SC_MAXG - 1);
-    const int bi = e >> 7, b = bi / rtop, i = bi - b * rtop;
+    const int seg = e & 15, h = (e >> 4) & (WH - 1);
+    const int bi = e / (WH * 16), b = bi / rtop, i = bi - b * rtop;
     const int rb = rank_s[min(b, nblk - 1)];
     float acc = 0.0f;
     if (b < nblk && i < rb) {
@@ -354,7 +362,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
     acc += dpp_mov<0x4E>(acc);
     acc += dpp_mov<0x141>(acc);
     acc += dpp_mov<0x140>(acc);
-    if (seg == 0 && b < nblk && i < rb) wbuf[(b * EOQ_RMAX_CAP + i) * SC_MAXG + h] = acc * inv_sqrt_d;
+    if (seg == 0 && b < nblk && i < rb) wbuf[(b * EOQ_RMAX_CAP + i) * WH + h] = acc * inv_sqrt_d;
   }
   __syncthreads();
 
@@ -388,9 +396,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
   };
 
   // this wave's staging buffers and the lane's read addresses in them (sub-pass 0; sub-pass s is a constant further on)
-  constexpr int CODE_STAGE = stage_pad(128 * ROWB), SIGN_STAGE = stage_pad(128 * (D / 8));
-  __shared__ __align__(16) unsigned char stage_s[4 * (CODE_STAGE + (QJL ? SIGN_STAGE : 0))];
-  unsigned char* stage_c = stage_s + wave * (CODE_STAGE + (QJL ? SIGN_STAGE : 0));
+  unsigned char* stage_c = pool + wave * (CODE_STAGE + SIGN_STAGE);
   unsigned char* stage_q = stage_c + CODE_STAGE;
   int rd_c[2][BITS], rd_q[2];
 #pragma unroll
@@ -407,7 +413,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
     const int cb_blk = u_chunk / cpb, cq = u_chunk - cb_blk * cpb;
     const size_t blk = blk0 + cb_blk;
     const int r = rank_s[cb_blk];
-    const float* wrow = wbuf + cb_blk * (EOQ_RMAX_CAP * SC_MAXG);
+    const float* wrow = wbuf + cb_blk * (EOQ_RMAX_CAP * WH);
     const int64_t jb = jb0 + cb_blk;
     // ---- the codes change lanes through LDS (the buffer is this wave's own: its LDS operations complete in order) ----
 #pragma unroll
@@ -489,7 +495,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
           const float c0 = half_bits_to_float((uint16_t)(cur.cf[a] & 0xFFFFu)), c1 = half_bits_to_float((uint16_t)(cur.cf[a] >> 16));
 #pragma unroll
           for (int hs = 0; hs < NSETS; ++hs) {
-            const float4 w = *reinterpret_cast<const float4*>(wrow + a * SC_MAXG + 4 * hs);
+            const float4 w = *reinterpret_cast<const float4*>(wrow + a * WH + 4 * hs);
             const float wv[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -504,7 +510,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
         const float c0 = half_bits_to_float((uint16_t)(cx & 0xFFFFu)), c1 = half_bits_to_float((uint16_t)(cx >> 16));
 #pragma unroll
         for (int hs = 0; hs < NSETS; ++hs) {
-          const float4 w = *reinterpret_cast<const float4*>(wrow + i * SC_MAXG + 4 * hs);
+          const float4 w = *reinterpret_cast<const float4*>(wrow + i * WH + 4 * hs);
           const float wv[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
@@ -591,9 +597,9 @@ hipError_t launch_scores_impl(const EoqLaunch& L, eoq_packed keys, const eoq_qjl
     if (L.ev) (void)hipEventRecord(L.ev[7], L.stream);
     return hipGetLastError();
   }
-  // blocks per workgroup: up to 16 (the query set-up is paid once per workgroup), shorter when that leaves fewer than ~16
-  // workgroups per compute unit
-  int64_t run = (sg_total * blocks_per_head) / 4096;
+  // blocks per workgroup: the query set-up is paid once per workgroup, so runs are as long as they can be (16) while the
+  // grid still has a workgroup for each of the 4 x 256 places on the chip
+  int64_t run = (sg_total * blocks_per_head + 1023) / 1024;
   run = run < 1 ? 1 : (run > SC_RUN_MAX ? SC_RUN_MAX : run);
   const int64_t runs = (blocks_per_head + run - 1) / run;
   if (sg_total > 65535 || runs > 0x7FFFFFFF) return hipErrorInvalidValue;
