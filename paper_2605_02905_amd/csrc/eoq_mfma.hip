@@ -1,7 +1,9 @@
 // Matrix-core (MFMA, gfx950) kernels of the residual coder for binary16 blocks:
 //   encode : projection, residual against the stored factors, norm, rotation, Lloyd-Max index, packing
 //            (Alg. 3 with Alg. 1 lines 3-5)
-//   decode : x_hat = (rho/sqrt(d)) z_hat Pi + C V^T  (Alg. 1 line 6 plus the stored low-rank part)
+//   decode : x_hat = (rho/sqrt(d)) z_hat Pi + C V^T  (Alg. 1 line 6 plus the stored low-rank part); the rotation enters
+//            as its binary16 rounding (one matrix-core pass): |error| <= 2^-11 rho |z_hat| per entry, the size of the
+//            binary16 rounding of the result itself
 //   qjl    : TQ_prod side information of stored records (Alg. 1 optional lines)
 //
 // Operand convention of v_mfma_f32_32x32x16_f16 (wave64): for D = A(32xK) * B(Kx32) + C, lane l supplies
@@ -57,6 +59,24 @@ __device__ __forceinline__ void build_mask_table(uint4* tab, int tid) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) x.s[e] = ((tid >> e) & 1) ? 0xFFFFu : 0u;
     tab[tid] = x.u;
+  }
+}
+
+// Direct table for codes of 1 or 2 bits: entry (nibble of plane 0 | nibble of plane 1 << 4) -> the binary16 centroids of
+// the four coordinates of that nibble (code of coordinate e = bit e of plane 0 + 2 * bit e of plane 1; index 0 is the most
+// negative centroid of the ascending N(0,1) table).
+template <int BITS>
+__device__ __forceinline__ void build_centroid_table(uint2* tab4, const float* __restrict__ cent, int tid) {
+  static_assert(BITS <= 2, "one nibble of two planes at most");
+  if (tid < 256) {
+    const int n0 = tid & 15, n1 = tid >> 4;
+    uint16_t h[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int code = ((n0 >> e) & 1) | ((BITS == 2) ? (((n1 >> e) & 1) << 1) : 0);
+      h[e] = float_to_half_bits(cent[code]);
+    }
+    tab4[tid] = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
   }
 }
 
@@ -187,29 +207,27 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
   __shared__ __align__(16) uint16_t Z[CHUNK * ZLD];    // centroid values of the chunk, [token][coordinate]
   __shared__ __align__(16) uint16_t Ct[CHUNK * CLD];   // low-rank coefficients, [token][component]
   __shared__ __align__(16) float rho_s[CHUNK];         // rho / sqrt(d)
-  __shared__ __align__(16) uint4 mask_tab[256];
+  __shared__ __align__(16) uint4 mask_tab[256];        // BITS >= 3: plane byte -> halfword masks; BITS <= 2: the direct table
   __shared__ __align__(16) uint16_t Ot[4 * 32 * OLD];  // per wave: one output tile, [token][column]
+  uint2* cen_tab = reinterpret_cast<uint2*>(mask_tab);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
   const int jcol = 32 * wave + l32;  // output column of this lane
   const int tl = 32 * wave + l32;    // token of the chunk this lane unpacks
 
-  build_mask_table(mask_tab, tid);
+  if constexpr (BITS <= 2) build_centroid_table<BITS>(cen_tab, tab, tid);
+  else build_mask_table(mask_tab, tid);
   // components beyond a block's rank meet a zero right factor: whatever Ct holds there only has to be finite
   for (int e = tid; e < CHUNK * CLD / 8; e += THREADS) *reinterpret_cast<uint4*>(&Ct[e * 8]) = make_uint4(0u, 0u, 0u, 0u);
   Mags<BITS> mg;
   mg.load(tab);
 
-  // stationary operands: Pi^T rows j (hi, lo)
+  // stationary operand: Pi^T rows j, rounded to binary16
   const uint16_t* pit_hi = pih + 2 * D * D;
-  const uint16_t* pit_lo = pih + 3 * D * D;
-  H8 Bhi[8], Blo[8];
+  H8 Bhi[8];
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    Bhi[kk].u = *reinterpret_cast<const uint4*>(pit_hi + jcol * D + 16 * kk + 8 * hf);
-    Blo[kk].u = *reinterpret_cast<const uint4*>(pit_lo + jcol * D + 16 * kk + 8 * hf);
-  }
+  for (int kk = 0; kk < 8; ++kk) Bhi[kk].u = *reinterpret_cast<const uint4*>(pit_hi + jcol * D + 16 * kk + 8 * hf);
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
 
   // the rank of the block after the next one is requested while the next one's first chunk is, so that request
@@ -236,16 +254,34 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
     for (int t0 = 0; t0 < n; t0 += CHUNK) {
       __syncthreads();  // previous chunk consumed; also orders the mask table and the cleared Ct before first use
       // ---- phase 1: wave w prepares tile w (tokens t0 + 32w + l32) from the prefetched record bytes ----
+      if constexpr (BITS <= 2) {
+        // lane (token, hf) takes the coordinates 64 hf .. 64 hf + 63: two words of every plane, eight nibbles each,
+        // one read of the direct table per nibble (four centroids)
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        uint32_t byte[BITS];
+        for (int wq = 0; wq < 2; ++wq) {
+          const uint32_t w0 = hf ? (wq ? cur.pl[0].w : cur.pl[0].z) : (wq ? cur.pl[0].y : cur.pl[0].x);
+          uint32_t w1 = 0u;
+          if constexpr (BITS == 2) w1 = hf ? (wq ? cur.pl[1].w : cur.pl[1].z) : (wq ? cur.pl[1].y : cur.pl[1].x);
+          const uint32_t even = bfi(0x0F0F0F0Fu, w0, w1 << 4);   // byte j: nibbles 2j of (plane 0, plane 1)
+          const uint32_t odd = bfi(0x0F0F0F0Fu, w0 >> 4, w1);    // byte j: nibbles 2j + 1
 #pragma unroll
-        for (int p = 0; p < BITS; ++p) {
-          const uint32_t wsel = (kk < 2) ? cur.pl[p].x : (kk < 4) ? cur.pl[p].y : (kk < 6) ? cur.pl[p].z : cur.pl[p].w;
-          byte[p] = (wsel >> (16 * (kk & 1) + 8 * hf)) & 0xFFu;   // plane byte 2 kk + hf
+          for (int j = 0; j < 4; ++j) {
+            const uint2 lo4 = cen_tab[(even >> (8 * j)) & 0xFFu], hi4 = cen_tab[(odd >> (8 * j)) & 0xFFu];
+            *reinterpret_cast<uint4*>(&Z[tl * ZLD + 64 * hf + 32 * wq + 8 * j]) = make_uint4(lo4.x, lo4.y, hi4.x, hi4.y);
+          }
         }
-        const H8 c = centroids_of<BITS>(byte, mask_tab, mg);
-        *reinterpret_cast<uint4*>(&Z[tl * ZLD + 16 * kk + 8 * hf]) = c.u;
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+          uint32_t byte[BITS];
+#pragma unroll
+          for (int p = 0; p < BITS; ++p) {
+            const uint32_t wsel = (kk < 2) ? cur.pl[p].x : (kk < 4) ? cur.pl[p].y : (kk < 6) ? cur.pl[p].z : cur.pl[p].w;
+            byte[p] = (wsel >> (16 * (kk & 1) + 8 * hf)) & 0xFFu;   // plane byte 2 kk + hf
+          }
+          const H8 c = centroids_of<BITS>(byte, mask_tab, mg);
+          *reinterpret_cast<uint4*>(&Z[tl * ZLD + 16 * kk + 8 * hf]) = c.u;
+        }
       }
       if (hf == 0) rho_s[tl] = half_bits_to_float(cur.rho) * inv_sqrt_d;
 #pragma unroll
@@ -286,8 +322,6 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
           a1.u = *reinterpret_cast<const uint4*>(&Z[(arow + 32) * ZLD + 16 * kk + 8 * hf]);
           acc[0] = mfma16(a0, Bhi[kk], acc[0]);
           acc[1] = mfma16(a1, Bhi[kk], acc[1]);
-          acc[0] = mfma16(a0, Blo[kk], acc[0]);
-          acc[1] = mfma16(a1, Blo[kk], acc[1]);
         }
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) {
