@@ -58,8 +58,9 @@ def measure_ceilings(ctx, torch, dev):
     buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     buf.zero_()
     out = {}
-    r = ctx.eoq_ceiling(0, buf, 1)
-    out["copy_GBps"] = r["work_a"] / (r["ms"] * 1e-3) / 1e9
+    for key, kind in (("copy_GBps", 0), ("read_GBps", 6), ("write_GBps", 7)):
+        r = ctx.eoq_ceiling(kind, buf, 1)
+        out[key] = r["work_a"] / (r["ms"] * 1e-3) / 1e9
     for key, kind, scale in (("fp64_fma_TFLOPs", 1, 1e12), ("mfma_f16_TFLOPs", 2, 1e12), ("mfma_i8_TOPs", 3, 1e12),
                              ("mfma_f64_TFLOPs", 4, 1e12)):
         r = ctx.eoq_ceiling(kind, buf, 4000)

@@ -355,7 +355,8 @@ eoq_status eoq_stage_ms(eoq_ctx* ctx, float* out);
  * Measured ceilings of the device, for benchmark reports (not part of the paper's method): runs one micro-benchmark
  * and waits for it.  kind 0: plain copy of the first half of `device_buf` onto its second half (16-byte accesses);
  * 1: independent double-precision FMA chains on the vector ALUs; 2 / 3 / 4: chains of the matrix instructions the
- * kernels use (f16 32x32x16, i8 16x16x64, f64 16x16x4); 5: 32-bit vector instructions; 10..15: two of these streams
+ * kernels use (f16 32x32x16, i8 16x16x64, f64 16x16x4); 5: 32-bit vector instructions; 6 / 7: read-only / write-only
+ * stream over `device_buf`; 10..15: two of these streams
  * side by side on the two waves of every SIMD (10: f64 matrix + f64 FMA, 11: i8 matrix + 32-bit vector, 12: f64 matrix
  * + 32-bit vector, 13: f64 FMA + 32-bit vector, 14: f16 matrix + f64 FMA, 15: i8 matrix + f64 FMA); 21 / 23 / 24 / 25:
  * stream 1 / 3 / 4 / 5 on one wave per SIMD only; 31..34 / 41..44: the f64 FMA / 32-bit vector stream on 1..4 waves

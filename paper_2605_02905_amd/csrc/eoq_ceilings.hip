@@ -138,9 +138,30 @@ __global__ __launch_bounds__(1024) void eoq_ceiling_kernel(int iters, double* si
   else run_stream<B>(iters, lane, sink);
 }
 
+// Plain copy, 16 bytes per lane and access (unrolling it to four accesses in flight per lane measured slower).
 __global__ __launch_bounds__(256) void eoq_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t count) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) dst[i] = src[i];
+}
+// Read-only and write-only streams of the same shape (the read sum is kept so that the loads stay).
+__global__ __launch_bounds__(256) void eoq_read_kernel(const uint4* __restrict__ src, uint4* __restrict__ sink, size_t count) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+  for (; i + 3 * stride < count; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc.x ^= a.x ^ b.x ^ c.x ^ d.x;
+    acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
+    acc.z ^= a.z ^ b.z ^ c.z ^ d.z;
+    acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+  }
+  for (; i < count; i += stride) acc.x ^= src[i].x;
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = acc;
+}
+__global__ __launch_bounds__(256) void eoq_write_kernel(uint4* __restrict__ dst, size_t count) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const uint4 v = make_uint4(threadIdx.x, blockIdx.x, 3u, 4u);
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) dst[i] = v;
 }
 
 template <int A, int B>
@@ -184,6 +205,19 @@ extern "C" eoq_status eoq_ceiling(eoq_ctx* ctx, int kind, void* device_buf, size
         units_a = 2.0 * (double)half;
         break;
       }
+      case 6: {   // read only
+        const size_t bytes = buf_bytes & ~(size_t)15;
+        hipLaunchKernelGGL(eoq_read_kernel, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4*>(device_buf),
+                           static_cast<uint4*>(device_buf), bytes / 16);
+        units_a = (double)bytes;
+        break;
+      }
+      case 7: {   // write only
+        const size_t bytes = buf_bytes & ~(size_t)15;
+        hipLaunchKernelGGL(eoq_write_kernel, dim3(cus * 8), dim3(256), 0, st, static_cast<uint4*>(device_buf), bytes / 16);
+        units_a = (double)bytes;
+        break;
+      }
       case 1: sa = S_FMA64; launch_pair<S_FMA64, S_FMA64>(grid, iters, sink, st); sb = sa; break;
       case 2: sa = S_MFMA_F16; launch_pair<S_MFMA_F16, S_MFMA_F16>(grid, iters, sink, st); sb = sa; break;
       case 3: sa = S_MFMA_I8; launch_pair<S_MFMA_I8, S_MFMA_I8>(grid, iters, sink, st); sb = sa; break;
@@ -225,7 +259,7 @@ extern "C" eoq_status eoq_ceiling(eoq_ctx* ctx, int kind, void* device_buf, size
     ctx->err = std::string("HIP: ") + hipGetErrorString(e);
     return EOQ_ERR_HIP;
   }
-  if (kind != 0) {
+  if (kind != 0 && kind != 6 && kind != 7) {
     // per launch: `grid` workgroups, four waves per stream
     units_a = units_per_iter(sa) * 4.0 * grid * iters;
     units_b = units_per_iter(sb) * 4.0 * (waves - 1) * grid * iters;
