@@ -80,6 +80,28 @@ __device__ __forceinline__ void build_centroid_table(uint2* tab4, const float* _
   }
 }
 
+// Tables for codes of 3 bits: entry (nibble of m_0 | nibble of m_1 << 4) -> the binary16 magnitudes of four coordinates
+// (m_p = magnitude bit p of the code: plane p where the sign plane is set, its complement where it is clear; level
+// m_0 + 2 m_1 is centroid L/2 + level of the ascending table), and behind them 16 entries (nibble of the sign plane) ->
+// the sign bits of the four halfwords (set where the plane bit is clear: negative).
+__device__ __forceinline__ void build_magnitude_table3(uint2* tab4, const float* __restrict__ cent, int tid) {
+  if (tid < 256) {
+    const int n0 = tid & 15, n1 = tid >> 4;
+    uint16_t h[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) h[e] = float_to_half_bits(cent[4 + (((n0 >> e) & 1) | (((n1 >> e) & 1) << 1))]);
+    tab4[tid] = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+    if (tid < 16) {
+      uint32_t lo = 0u, hi = 0u;
+      if (!(tid & 1)) lo |= 0x8000u;
+      if (!(tid & 2)) lo |= 0x80000000u;
+      if (!(tid & 4)) hi |= 0x8000u;
+      if (!(tid & 8)) hi |= 0x80000000u;
+      tab4[256 + tid] = make_uint2(lo, hi);
+    }
+  }
+}
+
 // Centroid magnitudes of the symmetric codebook as duplicated binary16 pairs: mag[m] = (h << 16) | h with
 // h = binary16(centroid[L/2 + m]), m = 0 .. L/2-1.
 template <int BITS>
@@ -207,7 +229,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
   __shared__ __align__(16) uint16_t Z[CHUNK * ZLD];    // centroid values of the chunk, [token][coordinate]
   __shared__ __align__(16) uint16_t Ct[CHUNK * CLD];   // low-rank coefficients, [token][component]
   __shared__ __align__(16) float rho_s[CHUNK];         // rho / sqrt(d)
-  __shared__ __align__(16) uint4 mask_tab[256];        // BITS >= 3: plane byte -> halfword masks; BITS <= 2: the direct table
+  __shared__ __align__(16) uint4 mask_tab[256];        // BITS = 4: plane byte -> halfword masks; BITS <= 3: the nibble tables
   __shared__ __align__(16) uint16_t Ot[4 * 32 * OLD];  // per wave: one output tile, [token][column]
   uint2* cen_tab = reinterpret_cast<uint2*>(mask_tab);
 
@@ -217,6 +239,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
   const int tl = 32 * wave + l32;    // token of the chunk this lane unpacks
 
   if constexpr (BITS <= 2) build_centroid_table<BITS>(cen_tab, tab, tid);
+  else if constexpr (BITS == 3) build_magnitude_table3(cen_tab, tab, tid);
   else build_mask_table(mask_tab, tid);
   // components beyond a block's rank meet a zero right factor: whatever Ct holds there only has to be finite
   for (int e = tid; e < CHUNK * CLD / 8; e += THREADS) *reinterpret_cast<uint4*>(&Ct[e * 8]) = make_uint4(0u, 0u, 0u, 0u);
@@ -268,6 +291,24 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
           for (int j = 0; j < 4; ++j) {
             const uint2 lo4 = cen_tab[(even >> (8 * j)) & 0xFFu], hi4 = cen_tab[(odd >> (8 * j)) & 0xFFu];
             *reinterpret_cast<uint4*>(&Z[tl * ZLD + 64 * hf + 32 * wq + 8 * j]) = make_uint4(lo4.x, lo4.y, hi4.x, hi4.y);
+          }
+        }
+      } else if constexpr (BITS == 3) {
+        // the same split of the work; per nibble one read of the magnitude table and one of the sign table
+#pragma unroll
+        for (int wq = 0; wq < 2; ++wq) {
+          uint32_t w[3];
+#pragma unroll
+          for (int p = 0; p < 3; ++p) w[p] = hf ? (wq ? cur.pl[p].w : cur.pl[p].z) : (wq ? cur.pl[p].y : cur.pl[p].x);
+          const uint32_t m0 = ~(w[0] ^ w[2]), m1 = ~(w[1] ^ w[2]);
+          const uint32_t even = bfi(0x0F0F0F0Fu, m0, m1 << 4), odd = bfi(0x0F0F0F0Fu, m0 >> 4, m1);
+          const uint32_t seven = w[2] & 0x0F0F0F0Fu, sodd = (w[2] >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint2 lo4 = cen_tab[(even >> (8 * j)) & 0xFFu], hi4 = cen_tab[(odd >> (8 * j)) & 0xFFu];
+            const uint2 ls = cen_tab[256 + ((seven >> (8 * j)) & 0xFFu)], hs = cen_tab[256 + ((sodd >> (8 * j)) & 0xFFu)];
+            *reinterpret_cast<uint4*>(&Z[tl * ZLD + 64 * hf + 32 * wq + 8 * j]) =
+                make_uint4(lo4.x | ls.x, lo4.y | ls.y, hi4.x | hs.x, hi4.y | hs.y);
           }
         }
       } else {
