@@ -1100,6 +1100,43 @@ def test_hot_calls_replay_from_a_captured_graph():
             assert torch.equal(a, b), seed
 
 
+def test_graph_replays_see_new_inputs_through_every_cache():
+    """One captured compress step over 2048 blocks of 128 x 128 (eight rounds of workgroups per compute unit), replayed
+    with the input buffer overwritten in place by other blocks between the replays: ranks, eigenvalues, codes and norms
+    of every replay equal the eager call on the same data.  The tridiagonal matrix of a block is written with vector
+    stores and read back through the scalar cache inside the spectral kernel at the same workspace address in every
+    replay: a line kept from the previous replay would show here as the previous data's eigenvalues."""
+    spec = synth.BlockSpec("replay", n=128, n_tensors=8, blocks_per_tensor=256, rank_lo=1, rank_hi=6)
+    ctx = eoq.Context(n=128, bits=2)
+    B = spec.n_blocks
+    blocks = torch.empty(B, 128, 128, dtype=torch.float16, device=DEV)
+    rec = eoq.Packed.empty(B, 128, 128, 2, 32, DEV)
+    ws = torch.empty(ctx.eoq_workspace_bytes(B), dtype=torch.uint8, device=DEV)
+    first, _ = synth.make_blocks(spec, seed=70, device=DEV)
+    blocks.copy_(first)
+    ctx.eoq_compress(blocks, rec, ws)            # eager warm-up before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.eoq_compress(blocks, rec, ws)
+    last_lam = None
+    for seed in (71, 72, 73):
+        new, _ = synth.make_blocks(spec, seed=seed, device=DEV)
+        blocks.copy_(new)
+        ctx2 = eoq.Context(n=128, bits=2)
+        want, ws2 = ctx2.eoq_compress(new)       # eager, own record and workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        lam_have, lam_want = ctx.spectrum(ws, B), ctx2.spectrum(ws2, B)
+        assert torch.equal(lam_have, lam_want), seed
+        for f in ("codes", "norms", "rank", "phi", "flags"):
+            assert _bits_equal(getattr(rec, f), getattr(want, f)), (seed, f)
+        if last_lam is not None:
+            assert not torch.equal(lam_have, last_lam)
+        last_lam = lam_have.clone()
+
+
 def test_maximum_block_length_through_every_call():
     """n = 4096 (the longest block the library takes), r_max = 8 so that the 4-bit factor table is at its limit
     n * r_max = 32768: compress (both factor formats), decompress, scores, TQ_prod side information and the attention
