@@ -687,10 +687,13 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
       Blo[kk].u = *reinterpret_cast<const uint4*>(pih + D * D + c * D + 16 * kk + 8 * hf);
     }
   }
-  // the decision boundaries, held as one register vector: a plain array indexed by a selected constant can end up
-  // in scratch memory (the compiler turns a select of two elements into an element at a selected index)
-  float16v bnd;
-  EOQ_SFOR(i, 16, bnd[i] = (i < (1 << BITS) - 1) ? tab[16 + i] : 0.0f;);
+  // the decision boundaries as separate values, not an array or a vector: the compiler turns a select between two
+  // elements into an element at a selected index (scratch memory for an array, a chain of sixteen selects for a
+  // register vector)
+#define EOQ_BND(i) const float bnd##i = ((i) < (1 << BITS) - 1) ? tab[16 + (i)] : 0.0f
+  EOQ_BND(0); EOQ_BND(1); EOQ_BND(2); EOQ_BND(3); EOQ_BND(4); EOQ_BND(5); EOQ_BND(6); EOQ_BND(7);
+  EOQ_BND(8); EOQ_BND(9); EOQ_BND(10); EOQ_BND(11); EOQ_BND(12); EOQ_BND(13); EOQ_BND(14);
+#undef EOQ_BND
 
   // factors of the block: W = V diag(phi/sigma) split into hi + lo, and V16^T.  Only the rows below the rank
   // rounded up to a multiple of 8 are ever multiplied with something that is not forced to zero (see Cneg)
@@ -838,28 +841,30 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
         const float z = acc[v];
         unsigned long long m[BITS];
         if constexpr (BITS == 1) {
-          m[0] = __ballot(z >= bnd[0]);
+          m[0] = __ballot(z >= bnd0);
         } else if constexpr (BITS == 2) {
-          const bool b1 = z >= bnd[1];
+          const bool b1 = z >= bnd1;
           m[1] = __ballot(b1);
-          m[0] = __ballot(z >= (b1 ? bnd[2] : bnd[0]));
+          m[0] = __ballot(z >= (b1 ? bnd2 : bnd0));
         } else if constexpr (BITS == 3) {
-          const bool b2 = z >= bnd[3];
+          // the candidates of the later levels are selected by the earlier decisions as soon as those are known, so
+          // the last comparison waits for one select only
+          const bool b2 = z >= bnd3;
           m[2] = __ballot(b2);
-          const bool b1 = z >= (b2 ? bnd[5] : bnd[1]);
+          const float lo0 = b2 ? bnd4 : bnd0, lo1 = b2 ? bnd6 : bnd2;
+          const bool b1 = z >= (b2 ? bnd5 : bnd1);
           m[1] = __ballot(b1);
-          const float t0b = b2 ? (b1 ? bnd[6] : bnd[4]) : (b1 ? bnd[2] : bnd[0]);
-          m[0] = __ballot(z >= t0b);
+          m[0] = __ballot(z >= (b1 ? lo1 : lo0));
         } else {
-          const bool b3 = z >= bnd[7];
+          const bool b3 = z >= bnd7;
           m[3] = __ballot(b3);
-          const bool b2 = z >= (b3 ? bnd[11] : bnd[3]);
+          const float q0 = b3 ? bnd8 : bnd0, q1 = b3 ? bnd10 : bnd2, q2 = b3 ? bnd12 : bnd4, q3 = b3 ? bnd14 : bnd6;
+          const float h0 = b3 ? bnd9 : bnd1, h1 = b3 ? bnd13 : bnd5;
+          const bool b2 = z >= (b3 ? bnd11 : bnd3);
           m[2] = __ballot(b2);
-          const float t1 = b3 ? (b2 ? bnd[13] : bnd[9]) : (b2 ? bnd[5] : bnd[1]);
-          const bool b1 = z >= t1;
+          const float lo0 = b2 ? q2 : q0, lo1 = b2 ? q3 : q1;
+          const bool b1 = z >= (b2 ? h1 : h0);
           m[1] = __ballot(b1);
-          const float lo0 = b3 ? (b2 ? bnd[12] : bnd[8]) : (b2 ? bnd[4] : bnd[0]);
-          const float lo1 = b3 ? (b2 ? bnd[14] : bnd[10]) : (b2 ? bnd[6] : bnd[2]);
           m[0] = __ballot(z >= (b1 ? lo1 : lo0));
         }
         constexpr int row_lo = 8 * (v >> 2) + (v & 3);   // token of the low word; the high word is row_lo + 4
