@@ -390,11 +390,17 @@ typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
 
 constexpr int GI_TOK = 64;                       // tokens per pass = depth of one matrix instruction
 constexpr int GI_ROW = GI_TOK + 16;              // bytes per (plane, column): 16 consecutive columns -> 16 distinct 16-byte bank groups
-constexpr int GI_PLANE = D * GI_ROW;             // 10240
+// Every tile of 16 columns starts 16 bytes further than the row pitch alone would put it: the loaders' stores (lane m
+// writes columns 8 m .. 8 m + 7, so 16 lanes are 8 rows = 160 words apart) then fall into sixteen different bank
+// groups instead of two.
+constexpr int GI_SKEW = 16;
+constexpr int GI_PLANE = D * GI_ROW + (D / 16) * GI_SKEW;   // 10368
 constexpr int GI_NPLANE = 4;
-constexpr int GI_CMAX_OFF = GI_NPLANE * GI_PLANE;  // 16 x 64 words: per-loader column maxima
-constexpr int GI_CEXP_OFF = GI_CMAX_OFF + 4096;  // 128 ints: exponent of the integer unit of each column
+constexpr int GI_CMAX_LD = 68;                   // words per loader row of the column maxima (64 + 4: rows in different banks)
+constexpr int GI_CMAX_OFF = GI_NPLANE * GI_PLANE;  // 16 x 68 words: per-loader column maxima
+constexpr int GI_CEXP_OFF = GI_CMAX_OFF + 16 * GI_CMAX_LD * 4;  // 128 ints: exponent of the integer unit of each column
 constexpr int GI_BYTES = GI_CEXP_OFF + 512;
+static_assert(GI_BYTES <= POOL_BYTES && GI_PLANE % 16 == 0 && GI_CEXP_OFF % 16 == 0, "Gram planes inside the pool");
 constexpr int GI_TILES = 36;                     // upper tiles, row-major: (0,0) .. (0,7), (1,1) .. (7,7)
 constexpr int UT_I[GI_TILES] = {0, 0, 0, 0, 0, 0, 0, 0, 1, 1, 1, 1, 1, 1, 1, 2, 2, 2, 2, 2, 2, 3, 3, 3, 3, 3, 4, 4, 4, 4, 5, 5, 5, 6, 6, 7};
 constexpr int UT_J[GI_TILES] = {0, 1, 2, 3, 4, 5, 6, 7, 1, 2, 3, 4, 5, 6, 7, 2, 3, 4, 5, 6, 7, 3, 4, 5, 6, 7, 4, 5, 6, 7, 5, 6, 7, 6, 7, 7};
@@ -432,11 +438,11 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size
       mx[3] = pk_max_u16(mx[3], raw[it].w & 0x7FFF7FFFu);
     }
     __syncthreads();  // the previous pass no longer reads planes, maxima or exponents
-    *reinterpret_cast<uint4*>(cmax + q * 64 + m * 4) = make_uint4(mx[0], mx[1], mx[2], mx[3]);
+    *reinterpret_cast<uint4*>(cmax + q * GI_CMAX_LD + m * 4) = make_uint4(mx[0], mx[1], mx[2], mx[3]);
     __syncthreads();
 #pragma unroll
     for (int rr = 0; rr < 16; ++rr) {
-      const uint4 o = *reinterpret_cast<const uint4*>(cmax + rr * 64 + m * 4);
+      const uint4 o = *reinterpret_cast<const uint4*>(cmax + rr * GI_CMAX_LD + m * 4);
       mx[0] = pk_max_u16(mx[0], o.x);
       mx[1] = pk_max_u16(mx[1], o.y);
       mx[2] = pk_max_u16(mx[2], o.z);
@@ -461,7 +467,7 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size
       );
       uint32_t pl[4];
       transpose_bytes(dg[0], dg[1], dg[2], dg[3], pl);
-      unsigned char* dst = pool + (8 * m + c) * GI_ROW + 4 * q;
+      unsigned char* dst = pool + (8 * m + c) * GI_ROW + (m >> 1) * GI_SKEW + 4 * q;
       *reinterpret_cast<uint32_t*>(dst) = pl[0];
       *reinterpret_cast<uint32_t*>(dst + GI_PLANE) = pl[1];
       *reinterpret_cast<uint32_t*>(dst + 2 * GI_PLANE) = pl[2];
@@ -479,8 +485,8 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size
       const int tI = ut_i_dev[tile]; const int tJ = ut_j_dev[tile];
       v4i acc[7];  // acc[c]: plane pairs (p, q) with p + q = c, weight 2^(8 c)
       EOQ_SFOR(cc, 7, EOQ_SFOR(v, 4, acc[cc][v] = 0;););
-      const unsigned char* pa = pool + (16 * tI + l16) * GI_ROW + 16 * kg;
-      const unsigned char* pb = pool + (16 * tJ + l16) * GI_ROW + 16 * kg;
+      const unsigned char* pa = pool + (16 * tI + l16) * GI_ROW + tI * GI_SKEW + 16 * kg;
+      const unsigned char* pb = pool + (16 * tJ + l16) * GI_ROW + tJ * GI_SKEW + 16 * kg;
       v4i a[4]; v4i b[4];
       EOQ_SFOR(pl, 4,
         a[pl] = *reinterpret_cast<const v4i*>(pa + pl * GI_PLANE);
