@@ -614,6 +614,9 @@ __device__ __forceinline__ double newton_rcp(double s) {
 // H_k = I - beta_k v_k v_k^T.  Per step: the 16 lanes that own row k form v and beta (the other lanes wait),
 // all lanes multiply p = beta A v over their live sub-tile (partial sums folded across the DPP row), then apply
 // A <- A - v w^T - w v^T with w = p - (beta/2)(v^T p) v.
+// p = beta A v in LDS: entry i = l + 16 g at pbuf[l + PB_LD g].  Its writers are four consecutive rows l of up to eight
+// groups g per wave; at a pitch of 20 doubles the groups start in eight different sets of eight banks.
+constexpr int PB_LD = 20;
 template <int S>
 __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, double (*vbuf)[D], double* pbuf,
                                                   float* refl, double* dT, double* eT, double* betaT) {
@@ -674,13 +677,13 @@ __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, doub
           part[a] = 0.0;
         });
       const double tot = row16_fold<S>(part, tx);
-      if (fold_writer<S>(tx)) pbuf[ty + 16 * fold_index<S>(tx)] = beta * tot;
+      if (fold_writer<S>(tx)) pbuf[ty + PB_LD * fold_index<S>(tx)] = beta * tot;
     }
     __syncthreads();
     // v^T p from the column entries this lane holds anyway, summed over its DPP row (every row of 16 lanes covers
     // all 128 columns and gets the same bits)
     double wj[8], vi[8], wi[8];
-    EOQ_SFOR(b, 8, wj[b] = (b >= S) ? pbuf[tx + 16 * b] : 0.0;);
+    EOQ_SFOR(b, 8, wj[b] = (b >= S) ? pbuf[tx + PB_LD * b] : 0.0;);
     double dl0 = 0.0, dl1 = 0.0;
     EOQ_SFOR(b, 8,
       if constexpr (b >= S) {
@@ -690,7 +693,7 @@ __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, doub
     const double K = 0.5 * beta * row16_sum_uniform(dl0 + dl1);
     EOQ_SFOR(b, 8, if constexpr (b >= S) wj[b] = fma(-K, vj[b], wj[b]););
     EOQ_SFOR(a, 8, vi[a] = (a >= S) ? vb[ty + 16 * a] : 0.0;);
-    EOQ_SFOR(a, 8, wi[a] = (a >= S) ? fma(-K, vi[a], pbuf[ty + 16 * a]) : 0.0;);
+    EOQ_SFOR(a, 8, wi[a] = (a >= S) ? fma(-K, vi[a], pbuf[ty + PB_LD * a]) : 0.0;);
     EOQ_SFOR(e, 64,
       if constexpr ((e >> 3) >= S && (e & 7) >= S)
         A[e] = fma(-vi[e >> 3], wj[e & 7], fma(-wi[e >> 3], vj[e & 7], A[e])););
@@ -946,7 +949,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   float* refl = reinterpret_cast<float*>(pool) + REFL_SLACK;
   unsigned char* u1 = pool + REFL_BYTES;
   __shared__ __align__(16) double vbuf[2][D];
-  __shared__ __align__(16) double pbuf[D];
+  __shared__ __align__(16) double pbuf[8 * PB_LD];
   __shared__ __align__(16) double2 de[D + 1];  // (d_i, e_{i-1}^2) of the scaled tridiagonal matrix; de[D] = 0
   __shared__ double dT[D], eT[D], betaT[D];
   __shared__ double cW[(D / 4) * 6];  // inner products of the reflectors inside each group of four
