@@ -300,6 +300,43 @@ def test_shrinker_matches_white_noise_closed_form_and_true_overlaps():
     assert (es.a2 - es.a1).min() > 0.015
 
 
+def test_noise_measure_is_normalised_by_its_number_of_atoms():
+    """Eq. (Fe) prints a sum over n ^ d indices with 1/(n ^ d) in front although the r outliers have been discarded:
+    either the weight is 1/(n ^ d) and the measure has mass 1 - r/(n ^ d), or it is 1/M over the M = n ^ d - r atoms
+    that exist.  What decides: the estimator must recover a planted strength without bias.  Over 96 independent
+    white-noise blocks with three planted components the mean of d_hat / (true singular value of the signal) is 1 to
+    a quarter of a percent with 1/M, and 1.5 % high (about ten standard errors) with 1/(n ^ d).  The alternative is
+    written out here from Eq. (d_transform); the oracle's own d_hat must be the 1/M one."""
+    n, d = 512, 128
+    beta = d / n
+
+    def strength(z, atoms, weight):
+        m_s = weight * np.sum(1.0 / (atoms - z))
+        m_l = beta * m_s - (1.0 - beta) / z
+        return 1.0 / math.sqrt(z * m_s * m_l)
+
+    by_atoms, by_size = [], []
+    for seed in range(96):
+        rng = np.random.default_rng(seed)
+        S, sig, _ = _spiked(rng, n, d, (6.0, 4.0, 2.5))
+        true = np.linalg.svd(sig, compute_uv=False)[:3]
+        es = oracle.eoptshrink(S)
+        assert es.rank == 3
+        lam = np.linalg.svd(S, compute_uv=False) ** 2
+        atoms = oracle.impute_noise_spectrum(lam, 3, oracle.pilot_k(d))
+        assert atoms.shape[0] == d - 3
+        dm = np.array([strength(z, atoms, 1.0 / atoms.shape[0]) for z in lam[:3]])
+        dn = np.array([strength(z, atoms, 1.0 / d) for z in lam[:3]])
+        assert np.allclose(dm, es.d_hat, rtol=1e-10)
+        by_atoms.append(dm / true - 1.0)
+        by_size.append(dn / true - 1.0)
+    by_atoms, by_size = np.array(by_atoms), np.array(by_size)
+    sem = by_atoms.std(axis=0) / math.sqrt(by_atoms.shape[0])
+    assert np.all(sem < 0.0025)
+    assert np.all(np.abs(by_atoms.mean(axis=0)) < 3.0 * sem + 5e-4), by_atoms.mean(axis=0)
+    assert np.all(by_size.mean(axis=0) > 0.012) and np.all(by_size.mean(axis=0) > 6.0 * sem), by_size.mean(axis=0)
+
+
 def _white_noise_closed_forms(y, n, d):
     """Textbook white-noise (A = B = I) quantities for an observed singular value y of an n x d matrix, n >= d, with
     unit-variance noise: the signal strength x behind y, the asymptotic overlaps on the long side (left vectors, R^n)
