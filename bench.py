@@ -284,7 +284,7 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true",
                     help="time the eager step instead of its replay from a captured HIP graph")
     ap.add_argument("--cpu-blocks", type=int, default=1024, help="blocks in the CPU-baseline sample (0 = skip)")
-    ap.add_argument("--cpu-passes", type=int, default=24, help="passes of the oracle over that sample (about 10-20 s of CPU work)")
+    ap.add_argument("--cpu-passes", type=int, default=40, help="passes of the oracle over that sample (about 10-20 s of CPU work)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary figures (config 3 at b = 3, one config-4 layer, TQ_prod, attention output, ceilings)")
     ap.add_argument("--copy-calibration", action="store_true",
