@@ -11,8 +11,9 @@
 // D[row = 8*(v/4) + 4*(l/32) + v%4][col = l%32] in accumulator register v = 0..15.
 //
 // Layout of the work: the rotation is the stationary operand.  Wave w of a workgroup keeps the 32 columns
-// j = 32w .. 32w+31 of Pi (as B operand, binary16 hi + lo parts) in registers for the whole block; the tokens
-// stream through LDS in tiles of 32 (A operand), each tile prepared by one wave and consumed by all four.
+// j = 32w .. 32w+31 of Pi (as B operand: binary16 hi + lo parts in the encoder and the qjl kernel, the binary16
+// rounding alone in the decoder) in registers for the whole block; the tokens stream through LDS in tiles of 32
+// (A operand), each tile prepared by one wave and consumed by all four.
 #include "eoq_device.h"
 #include "eoq_internal.h"
 
@@ -417,10 +418,10 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
 
 // ---------------------------------------------------------------------------------------------
 // TQ_prod side information (Alg. 1 lines "TQ_prod"): one workgroup per block.  The reconstruction of the record is
-// formed as in the decoder, tile by tile in float32 accumulators (centroids as binary16 hi + lo here: the residual
-// is a small difference), r_x = S - x_hat goes to LDS as binary16 hi + lo, its norm is taken there, and one more
-// product with the stationary-free operand Phi (hi + lo, read through the caches) gives Phi r_x, of which only the
-// signs are kept, packed like one more bit-plane.
+// formed as in the decoder, tile by tile in float32 accumulators (centroids and rotation as binary16 hi + lo here:
+// the residual is a small difference), r_x = S - x_hat goes to LDS as binary16 hi + lo, its norm is taken there, and
+// one more product with Phi (binary16 by definition, stationary in registers like the rotation) gives Phi r_x, of
+// which only the signs are kept, packed like one more bit-plane.
 // ---------------------------------------------------------------------------------------------
 template <int BITS>
 __global__ __launch_bounds__(THREADS, 1) void eoq_qjl_kernel(
