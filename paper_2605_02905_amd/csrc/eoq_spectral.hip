@@ -666,13 +666,10 @@ __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, doub
       double part[8];
       EOQ_SFOR(a, 8,
         if constexpr (a >= S) {
-          double s0 = 0.0, s1 = 0.0;
-          EOQ_SFOR(b, 8,
-            if constexpr (b >= S) {
-              if constexpr ((b & 1) == 0) s0 = fma(A[a * 8 + b], vj[b], s0);
-              else s1 = fma(A[a * 8 + b], vj[b], s1);
-            });
-          part[a] = s0 + s1;
+          // one chain per row: the chains of the live rows interleave, which is independent work enough
+          double s0 = 0.0;
+          EOQ_SFOR(b, 8, if constexpr (b >= S) s0 = fma(A[a * 8 + b], vj[b], s0););
+          part[a] = s0;
         } else {
           part[a] = 0.0;
         });
