@@ -59,8 +59,11 @@ def measure_ceilings(ctx, torch, dev):
     buf.zero_()
     out = {}
     for key, kind in (("copy_GBps", 0), ("read_GBps", 6), ("write_GBps", 7)):
-        r = ctx.eoq_ceiling(kind, buf, 1)
-        out[key] = r["work_a"] / (r["ms"] * 1e-3) / 1e9
+        best = 0.0
+        for _ in range(3):      # a ceiling: the best of three launches
+            r = ctx.eoq_ceiling(kind, buf, 1)
+            best = max(best, r["work_a"] / (r["ms"] * 1e-3) / 1e9)
+        out[key] = best
     for key, kind, scale in (("fp64_fma_TFLOPs", 1, 1e12), ("mfma_f16_TFLOPs", 2, 1e12), ("mfma_i8_TOPs", 3, 1e12),
                              ("mfma_f64_TFLOPs", 4, 1e12)):
         r = ctx.eoq_ceiling(kind, buf, 4000)

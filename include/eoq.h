@@ -353,7 +353,8 @@ eoq_status eoq_stage_ms(eoq_ctx* ctx, float* out);
 
 /*
  * Measured ceilings of the device, for benchmark reports (not part of the paper's method): runs one micro-benchmark
- * and waits for it.  kind 0: plain copy of the first half of `device_buf` onto its second half (16-byte accesses);
+ * and waits for it.  kind 0: plain copy of the first half of `device_buf` onto its second half (16-byte accesses;
+ * the memory streams of kinds 0, 6 and 7 walk whole chunks of 32 KB per workgroup and leave a shorter rest alone);
  * 1: independent double-precision FMA chains on the vector ALUs; 2 / 3 / 4: chains of the matrix instructions the
  * kernels use (f16 32x32x16, i8 16x16x64, f64 16x16x4); 5: 32-bit vector instructions; 6 / 7: read-only / write-only
  * stream over `device_buf`; 10..15: two of these streams
@@ -361,7 +362,7 @@ eoq_status eoq_stage_ms(eoq_ctx* ctx, float* out);
  * + 32-bit vector, 13: f64 FMA + 32-bit vector, 14: f16 matrix + f64 FMA, 15: i8 matrix + f64 FMA); 21 / 23 / 24 / 25:
  * stream 1 / 3 / 4 / 5 on one wave per SIMD only; 31..34 / 41..44: the f64 FMA / 32-bit vector stream on 1..4 waves
  * per SIMD (the first wave's work in out[1], the others' in out[2]).  `iters` is the loop count per wave (kinds >= 1).
- *   device_buf  DEVICE scratch, 16-byte aligned, buf_bytes >= 64 (kind 0 moves buf_bytes/2 in each direction).
+ *   device_buf  DEVICE scratch, 16-byte aligned, buf_bytes >= 64 KB (kind 0 moves buf_bytes/2 in each direction).
  *   out         HOST, 4 doubles: milliseconds of one launch; work of the first stream (bytes moved for kind 0, flops
  *               or integer operations, wave instructions for the 32-bit vector stream); work of the second stream;
  *               compute units of the device.

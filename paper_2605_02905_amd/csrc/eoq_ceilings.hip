@@ -138,30 +138,36 @@ __global__ __launch_bounds__(1024) void eoq_ceiling_kernel(int iters, double* si
   else run_stream<B>(iters, lane, sink);
 }
 
-// Plain copy, 16 bytes per lane and access (unrolling it to four accesses in flight per lane measured slower).
-__global__ __launch_bounds__(256) void eoq_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t count) {
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) dst[i] = src[i];
-}
-// Read-only and write-only streams of the same shape (the read sum is kept so that the loads stay).
-__global__ __launch_bounds__(256) void eoq_read_kernel(const uint4* __restrict__ src, uint4* __restrict__ sink, size_t count) {
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-  for (; i + 3 * stride < count; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc.x ^= a.x ^ b.x ^ c.x ^ d.x;
-    acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
-    acc.z ^= a.z ^ b.z ^ c.z ^ d.z;
-    acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+// Memory streams.  Every workgroup walks contiguous chunks of 32 KB (chunk number += grid size), 16 bytes per lane
+// and access, 4 KB per workgroup and step: on this device that order is 10-20 % faster than one grid-wide stride
+// over the whole buffer (copy 5.4 against 4.8 TB/s, read 6.4 against 5.6, write 6.0 against 5.1), so it is the one
+// quoted as the ceiling.  What lies beyond the last whole chunk is not touched (and not counted).
+constexpr int STREAM_CHUNK_U4 = 2048;   // 32 KB
+enum StreamMode { STREAM_READ = 0, STREAM_COPY = 1, STREAM_WRITE = 2 };
+template <int MODE>
+__global__ __launch_bounds__(256) void eoq_stream_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t chunks,
+                                                         uint4* __restrict__ sink) {
+  uint4 acc = make_uint4(threadIdx.x, blockIdx.x, 3u, 4u);
+  for (size_t c = blockIdx.x; c < chunks; c += gridDim.x) {
+#pragma unroll 4
+    for (int t = 0; t < STREAM_CHUNK_U4 / 256; ++t) {
+      const size_t i = c * STREAM_CHUNK_U4 + t * 256 + threadIdx.x;
+      if constexpr (MODE == STREAM_WRITE) {
+        dst[i] = acc;
+      } else {
+        const uint4 v = src[i];
+        if constexpr (MODE == STREAM_COPY) {
+          dst[i] = v;
+        } else {   // the sum is kept so that the loads stay
+          acc.x ^= v.x;
+          acc.y ^= v.y;
+          acc.z ^= v.z;
+          acc.w ^= v.w;
+        }
+      }
+    }
   }
-  for (; i < count; i += stride) acc.x ^= src[i].x;
-  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = acc;
-}
-__global__ __launch_bounds__(256) void eoq_write_kernel(uint4* __restrict__ dst, size_t count) {
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  const uint4 v = make_uint4(threadIdx.x, blockIdx.x, 3u, 4u);
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) dst[i] = v;
+  if (MODE == STREAM_READ && (acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = acc;
 }
 
 template <int A, int B>
@@ -180,7 +186,7 @@ extern "C" eoq_status eoq_ceiling(eoq_ctx* ctx, int kind, void* device_buf, size
     ctx->err = "context was created without a HIP device";
     return EOQ_ERR_HIP;
   }
-  if (!device_buf || (reinterpret_cast<uintptr_t>(device_buf) & 15u) || buf_bytes < 64 || iters < 1) {
+  if (!device_buf || (reinterpret_cast<uintptr_t>(device_buf) & 15u) || buf_bytes < 65536 || iters < 1) {
     ctx->err = "eoq_ceiling: null or misaligned buffer, or no iterations";
     return EOQ_ERR_ARG;
   }
@@ -198,24 +204,26 @@ extern "C" eoq_status eoq_ceiling(eoq_ctx* ctx, int kind, void* device_buf, size
   for (int rep = 0; rep < reps; ++rep) {   // the last repetition is the one timed
     if (rep == reps - 1) (void)hipEventRecord(e0, st);
     switch (kind) {
-      case 0: {
-        const size_t half = (buf_bytes / 2) & ~(size_t)15;
-        hipLaunchKernelGGL(eoq_copy_kernel, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4*>(device_buf),
-                           reinterpret_cast<uint4*>(static_cast<char*>(device_buf) + half), half / 16);
+      case 0: {   // copy: first half of the buffer to the second
+        const size_t chunks = buf_bytes / 2 / (STREAM_CHUNK_U4 * 16);
+        const size_t half = chunks * STREAM_CHUNK_U4 * 16;
+        hipLaunchKernelGGL(eoq_stream_kernel<STREAM_COPY>, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4*>(device_buf),
+                           reinterpret_cast<uint4*>(static_cast<char*>(device_buf) + half), chunks, static_cast<uint4*>(nullptr));
         units_a = 2.0 * (double)half;
         break;
       }
-      case 6: {   // read only
-        const size_t bytes = buf_bytes & ~(size_t)15;
-        hipLaunchKernelGGL(eoq_read_kernel, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4*>(device_buf),
-                           static_cast<uint4*>(device_buf), bytes / 16);
-        units_a = (double)bytes;
+      case 6: {   // read only (a match of the running sum, which does not occur, would write 16 bytes at the front)
+        const size_t chunks = buf_bytes / (STREAM_CHUNK_U4 * 16);
+        hipLaunchKernelGGL(eoq_stream_kernel<STREAM_READ>, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4*>(device_buf),
+                           static_cast<uint4*>(nullptr), chunks, static_cast<uint4*>(device_buf));
+        units_a = (double)chunks * STREAM_CHUNK_U4 * 16;
         break;
       }
       case 7: {   // write only
-        const size_t bytes = buf_bytes & ~(size_t)15;
-        hipLaunchKernelGGL(eoq_write_kernel, dim3(cus * 8), dim3(256), 0, st, static_cast<uint4*>(device_buf), bytes / 16);
-        units_a = (double)bytes;
+        const size_t chunks = buf_bytes / (STREAM_CHUNK_U4 * 16);
+        hipLaunchKernelGGL(eoq_stream_kernel<STREAM_WRITE>, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4*>(nullptr),
+                           static_cast<uint4*>(device_buf), chunks, static_cast<uint4*>(nullptr));
+        units_a = (double)chunks * STREAM_CHUNK_U4 * 16;
         break;
       }
       case 1: sa = S_FMA64; launch_pair<S_FMA64, S_FMA64>(grid, iters, sink, st); sb = sa; break;

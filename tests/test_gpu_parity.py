@@ -1137,6 +1137,26 @@ def test_graph_replays_see_new_inputs_through_every_cache():
         last_lam = lam_have.clone()
 
 
+def test_device_ceiling_loops_run_and_report_their_work():
+    """eoq_ceiling (benchmark support, not the paper's method): the memory streams and one arithmetic loop run, report
+    the bytes / flops they did and a positive time; a buffer below one chunk per stream is refused."""
+    ctx = eoq.Context(n=512, bits=2)
+    buf = torch.zeros(64 << 20, dtype=torch.uint8, device=DEV)
+    for kind, work in ((0, float(64 << 20)), (6, float(64 << 20)), (7, float(64 << 20))):
+        r = ctx.eoq_ceiling(kind, buf, 1)
+        assert r["ms"] > 0 and r["work_a"] == work and r["compute_units"] > 0, (kind, r)
+    r = ctx.eoq_ceiling(1, buf, 200)
+    assert r["ms"] > 0 and r["work_a"] > 0 and r["work_b"] > 0
+    # the copy moves the first half onto the second
+    buf[: 32 << 20] = 7
+    buf[32 << 20:] = 0
+    ctx.eoq_ceiling(0, buf, 1)
+    assert bool((buf[32 << 20:] == 7).all())
+    with pytest.raises(eoq.EoqError):
+        ctx.eoq_ceiling(0, buf[:4096], 1)
+    torch.cuda.synchronize()
+
+
 def test_maximum_block_length_through_every_call():
     """n = 4096 (the longest block the library takes), r_max = 8 so that the 4-bit factor table is at its limit
     n * r_max = 32768: compress (both factor formats), decompress, scores, TQ_prod side information and the attention
