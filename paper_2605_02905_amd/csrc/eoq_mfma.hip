@@ -222,196 +222,292 @@ __device__ __forceinline__ int rank_value(int raw, int r_max) {
   return min(max(__builtin_amdgcn_readfirstlane(raw), 0), r_max);   // records may come from storage
 }
 
+// ---------------------------------------------------------------------------------------------
+// decode kernel proper: every wave is a worker of its own.  A unit of work is a run of consecutive 32-token tiles of
+// one block (the whole block when the batch is large); wave g of the grid takes the units g, g + waves, ...  The whole
+// of Pi^T (binary16) is stationary in the wave's registers as the A operand (4 column blocks x 8 instructions), the
+// centroid values of a token go from the bit-planes straight into the B operand of the lane that owns the token, and
+// the product comes out transposed: D[output column][token], so a lane holds 4 x 4 consecutive columns of ITS token
+// per column block, scales them by its own rho, rounds them in pairs and hands them to a wave-private LDS tile from
+// which the 32 rows leave as 16-byte stores, 1 KB contiguous per instruction.  No barrier after the set-up.
+// The contraction index is permuted so that lane half hf owns coordinates 64 hf .. 64 hf + 63 (8 consecutive bytes
+// of every bit-plane): slot e of instruction kk is coordinate 64 hf + 8 kk + e on both operands.
+// ---------------------------------------------------------------------------------------------
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+
+// What a lane requests of a tile: lane (l32, hf) owns token l32 of the tile.
+template <int BITS>
+struct TileFetch {
+  u32x2 pl[BITS];   // bytes 8 hf .. 8 hf + 7 of every bit-plane of the token
+  uint32_t rho;     // the token's stored norm (binary16 in the low half)
+  u32x4 cf;         // lane L: stored coefficients C[tokens 8 (L % 4) .. + 7 of the tile][component L / 4]; zero at and above the rank
+};
+// Buffer descriptors of the block a tile belongs to (scalar registers).  Everything that must read as zero does so by
+// the range check of the descriptor, which covers the per-lane offset: rows at and above the rank lie past the end of
+// `lfac`, and a request behind the last tile goes through descriptors of size zero.
+struct TileSource {
+  __amdgpu_buffer_rsrc_t codes, norms, lfac;
+};
+__device__ __forceinline__ uint32_t pack_half2(float a, float b) {
+  const float2v v = {a, b};
+  const half2v h = __builtin_convertvector(v, half2v);   // v_cvt_pk_f16_f32, round to nearest even
+  return *reinterpret_cast<const uint32_t*>(&h);
+}
+constexpr int CTLD = 32 + 8;   // row stride (halfs) of a tile's coefficient rows in LDS, [component][token]
+
 template <int BITS>
 __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
-    int n, int r_max, int64_t B, const uint16_t* __restrict__ pih, const float* __restrict__ tab,
+    int n, int r_max, int64_t B, int parts_log2, const uint16_t* __restrict__ pih, const float* __restrict__ tab,
     const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms, const int32_t* __restrict__ rank_in,
     const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac, uint16_t* __restrict__ out) {
-  __shared__ __align__(16) uint16_t Z[CHUNK * ZLD];    // centroid values of the chunk, [token][coordinate]
-  __shared__ __align__(16) uint16_t Ct[CHUNK * CLD];   // low-rank coefficients, [token][component]
-  __shared__ __align__(16) float rho_s[CHUNK];         // rho / sqrt(d)
-  __shared__ __align__(16) uint4 mask_tab[256];        // BITS = 4: plane byte -> halfword masks; BITS <= 3: the nibble tables
-  __shared__ __align__(16) uint16_t Ot[4 * 32 * OLD];  // per wave: one output tile, [token][column]
+  __shared__ __align__(16) uint4 mask_tab[256];            // BITS = 4: plane byte -> halfword masks; BITS <= 3: the nibble tables
+  __shared__ __align__(16) uint16_t Ot[4 * 32 * ZLD];      // per wave: one output tile, [token][column]
+  __shared__ __align__(16) uint16_t Cs[4 * 2 * 16 * CTLD]; // per wave: coefficient rows 0..15 and 16..31 of a tile
+  __shared__ __align__(16) uint4 V2[4 * 4 * 64];           // per wave: operands of components 16..31 (blocks of rank > 16)
   uint2* cen_tab = reinterpret_cast<uint2*>(mask_tab);
+  constexpr int ROWB = BITS * D / 8;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
-  const int jcol = 32 * wave + l32;  // output column of this lane
-  const int tl = 32 * wave + l32;    // token of the chunk this lane unpacks
+
+  // binary16 results that overflow become the largest finite value instead of infinity (mode bit FP16_OVFL): the
+  // output saturates like every other binary16 quantity of the record, without a clamp per element
+  __builtin_amdgcn_s_setreg(1 | (23 << 6) | (0 << 11), 1);
 
   if constexpr (BITS <= 2) build_centroid_table<BITS>(cen_tab, tab, tid);
   else if constexpr (BITS == 3) build_magnitude_table3(cen_tab, tab, tid);
   else build_mask_table(mask_tab, tid);
-  // components beyond a block's rank meet a zero right factor: whatever Ct holds there only has to be finite
-  for (int e = tid; e < CHUNK * CLD / 8; e += THREADS) *reinterpret_cast<uint4*>(&Ct[e * 8]) = make_uint4(0u, 0u, 0u, 0u);
   Mags<BITS> mg;
-  mg.load(tab);
+  if constexpr (BITS == 4) mg.load(tab);
+  __syncthreads();   // the only one: from here on the waves do not meet again
 
-  // stationary operand: Pi^T rows j, rounded to binary16
+  const int tiles_per_unit = (n / 32) >> parts_log2;
+  const int part_mask = (1 << parts_log2) - 1;
+  const int64_t U = B << parts_log2;
+  const int64_t GW = (int64_t)gridDim.x * 4;
+  int64_t u = (int64_t)blockIdx.x * 4 + wave;
+  if (u >= U) return;
+
+  // stationary operand: rows j = 32 cb + l32 of Pi^T rounded to binary16, contraction slots in the permuted order
   const uint16_t* pit_hi = pih + 2 * D * D;
-  H8 Bhi[8];
+  H8 Ap[4][8];
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) Bhi[kk].u = *reinterpret_cast<const uint4*>(pit_hi + jcol * D + 16 * kk + 8 * hf);
+  for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      Ap[cb][kk].u = *reinterpret_cast<const uint4*>(pit_hi + (32 * cb + l32) * D + 64 * hf + 8 * kk);
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
 
-  // the rank of the block after the next one is requested while the next one's first chunk is, so that request
-  // finds its rank in a register
   const __amdgpu_buffer_rsrc_t ranks = buffer_of(rank_in, (size_t)B * 4);
-  const int64_t step = gridDim.x;
-  int rk_n = rank_request(ranks, min((int64_t)blockIdx.x + step, B));
-  DecodeFetch<BITS> cur, nxt;
-  H8 Bv[2];
-  uint32_t vraw[16];
-  {
-    const int r0 = rank_value(rank_request(ranks, min((int64_t)blockIdx.x, B)), r_max);
-    if ((int64_t)blockIdx.x < B) {
-      decode_fetch<BITS>(cur, blockIdx.x, 0, n, r0, r_max, tid, tl, codes, norms, lfac);
-      decode_fetch_v(vraw, blockIdx.x, r0, r_max, jcol, hf, rfac);
+  // per-lane parts of the offsets (they never change)
+  const uint32_t vo_code = (uint32_t)(l32 * ROWB + 8 * hf);
+  const uint32_t vo_norm = (uint32_t)(2 * l32);
+  const uint32_t vo_cf = (uint32_t)(((lane >> 2) * n + (lane & 3) * 8) * 2);   // row L / 4 of the coefficients: range-checked per row
+  const uint32_t vo_row = (uint32_t)((lane >> 4) * (D * 2) + (lane & 15) * 16);   // 16-byte piece of row L / 16 of a [.][128] binary16 array
+  uint16_t* ot = Ot + wave * (32 * ZLD);
+  uint16_t* cs = Cs + wave * (2 * 16 * CTLD);
+  uint4* v2 = V2 + wave * (4 * 64);
+
+  auto source_of = [&](int64_t blk, int r, bool valid) __attribute__((always_inline)) {
+    TileSource s;
+    s.codes = buffer_of(codes + (size_t)blk * n * ROWB, valid ? (size_t)n * ROWB : 0);
+    s.norms = buffer_of(norms + (size_t)blk * n, valid ? (size_t)n * 2 : 0);
+    s.lfac = buffer_of(lfac + (size_t)blk * r_max * n, valid ? (size_t)r * n * 2 : 0);
+    return s;
+  };
+  auto request = [&](TileFetch<BITS>& f, const TileSource& s, int t0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int p = 0; p < BITS; ++p) f.pl[p] = __builtin_amdgcn_raw_buffer_load_b64(s.codes, vo_code + 16 * p, t0 * ROWB, 0);
+    f.rho = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(s.norms, vo_norm, t0 * 2, 0);
+    f.cf = __builtin_amdgcn_raw_buffer_load_b128(s.lfac, vo_cf, t0 * 2, 0);
+  };
+  // V[8 hf + e + 16 k2][32 cb + l32], e = 0 .. 7, of the rows staged in the wave's LDS tile: an A operand of the low-rank product
+  auto v_operand = [&](int cb) __attribute__((always_inline)) {
+    H8 x;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t a = ot[(8 * hf + 2 * w) * ZLD + 32 * cb + l32], b = ot[(8 * hf + 2 * w + 1) * ZLD + 32 * cb + l32];
+      x.w[w] = a | (b << 16);
     }
-    pack_v(Bv, vraw);
-  }
+    return x;
+  };
+  // C[token l32][8 hf + e + 16 k2] of the rows staged in the wave's coefficient tile: the B operand of that product
+  auto c_operand = [&](int k2) __attribute__((always_inline)) {
+    H8 x;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t a = cs[(16 * k2 + 8 * hf + 2 * w) * CTLD + l32], b = cs[(16 * k2 + 8 * hf + 2 * w + 1) * CTLD + l32];
+      x.w[w] = a | (b << 16);
+    }
+    return x;
+  };
+
+  // state of the unit being worked on and of the one after it
+  int64_t blk = u >> parts_log2;
+  int part = (int)u & part_mask;
+  int r = rank_value(rank_request(ranks, blk), r_max);
+  int rk_next = rank_request(ranks, (u + GW < U) ? ((u + GW) >> parts_log2) : B);   // past the end: reads zero
+  TileSource src = source_of(blk, r, true);
+  TileFetch<BITS> cur, nxt;
+  request(cur, src, 32 * part * tiles_per_unit);
+  H8 Bv[4];   // right factors of the unit's block as A operand of the low-rank product: V[8 hf + e][32 cb + l32]
+  __amdgpu_buffer_rsrc_t obuf = buffer_of(out, 0);
+  int ti = 0;
   // nothing of the set-up is left in flight: inside the loop a wait then only ever covers what the loop itself
-  // requested (the next chunk's bytes must not be waited for before the matrix products of this one)
+  // requested, and never the stores of the tile before
   __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
-  for (int64_t blk = blockIdx.x; blk < B; blk += step) {
-    const int r = cur.r;
-    for (int t0 = 0; t0 < n; t0 += CHUNK) {
-      __syncthreads();  // previous chunk consumed; also orders the mask table and the cleared Ct before first use
-      // ---- phase 1: wave w prepares tile w (tokens t0 + 32w + l32) from the prefetched record bytes ----
-      if constexpr (BITS <= 2) {
-        // lane (token, hf) takes the coordinates 64 hf .. 64 hf + 63: two words of every plane, eight nibbles each,
-        // one read of the direct table per nibble (four centroids)
+  for (;;) {
+    if (ti == 0) {
+      // rows of the block's right factors travel as 16-byte pieces (rows at and above the rank read zero), change
+      // lanes through the wave's LDS tile and are read back one binary16 at a time in operand order; rows 16 .. 31
+      // (blocks of rank > 16, rare) are kept in LDS as finished operands
+      const __amdgpu_buffer_rsrc_t vbuf = buffer_of(rfac + (size_t)blk * r_max * D, (size_t)r * D * 2);
+      for (int k2 = (r > 16) ? 1 : 0; k2 >= 0; --k2) {   // uniform
+        u32x4 vrow[4];
 #pragma unroll
-        for (int wq = 0; wq < 2; ++wq) {
-          const uint32_t w0 = hf ? (wq ? cur.pl[0].w : cur.pl[0].z) : (wq ? cur.pl[0].y : cur.pl[0].x);
-          uint32_t w1 = 0u;
-          if constexpr (BITS == 2) w1 = hf ? (wq ? cur.pl[1].w : cur.pl[1].z) : (wq ? cur.pl[1].y : cur.pl[1].x);
-          const uint32_t even = bfi(0x0F0F0F0Fu, w0, w1 << 4);   // byte j: nibbles 2j of (plane 0, plane 1)
-          const uint32_t odd = bfi(0x0F0F0F0Fu, w0 >> 4, w1);    // byte j: nibbles 2j + 1
+        for (int k = 0; k < 4; ++k) vrow[k] = __builtin_amdgcn_raw_buffer_load_b128(vbuf, vo_row + (16 * k2 + 4 * k) * (D * 2), 0, 0);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const uint2 lo4 = cen_tab[(even >> (8 * j)) & 0xFFu], hi4 = cen_tab[(odd >> (8 * j)) & 0xFFu];
-            *reinterpret_cast<uint4*>(&Z[tl * ZLD + 64 * hf + 32 * wq + 8 * j]) = make_uint4(lo4.x, lo4.y, hi4.x, hi4.y);
-          }
+        for (int k = 0; k < 4; ++k) *reinterpret_cast<u32x4*>(ot + (4 * k + (lane >> 4)) * ZLD + (lane & 15) * 8) = vrow[k];
+        __builtin_amdgcn_wave_barrier();
+        if (k2 == 1) {
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb) v2[cb * 64 + lane] = v_operand(cb).u;
+        } else {
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb) Bv[cb] = v_operand(cb);
         }
-      } else if constexpr (BITS == 3) {
-        // the same split of the work; per nibble one read of the magnitude table and one of the sign table
+        __builtin_amdgcn_wave_barrier();
+      }
+      obuf = buffer_of(out + (size_t)blk * n * D, (size_t)n * D * 2);
+    }
+    const int t0 = 32 * (part * tiles_per_unit + ti);
+    // ---- request the next tile: of this unit, or the first one of the wave's next unit ----
+    const bool unit_ends = ti + 1 == tiles_per_unit;
+    const int64_t un = u + GW;
+    const bool more = un < U;
+    int64_t blk_n = blk;
+    int part_n = part, r_n = r, t_n = t0 + 32;
+    if (unit_ends) {   // uniform
+      blk_n = more ? (un >> parts_log2) : blk;
+      part_n = (int)un & part_mask;
+      r_n = rank_value(rk_next, r_max);
+      rk_next = rank_request(ranks, (un + GW < U) ? ((un + GW) >> parts_log2) : B);
+      src = source_of(blk_n, r_n, more);
+      t_n = 32 * part_n * tiles_per_unit;
+    }
+    request(nxt, src, t_n);
+
+    // ---- this tile ----
+    const float rs = half_bits_to_float((uint16_t)cur.rho) * inv_sqrt_d;
+    H8 Cop;   // C[token][8 hf + e], the B operand of the low-rank product
+    if (r > 0) {   // uniform
+      // lane L holds eight tokens of component L / 4: row L / 4 of the coefficient tile
+      *reinterpret_cast<u32x4*>(cs + (lane >> 2) * CTLD + (lane & 3) * 8) = cur.cf;
+      __builtin_amdgcn_wave_barrier();
+      Cop = c_operand(0);
+    }
+    // nibble words of the lane's 64 coordinates (BITS <= 3): byte kk of word set [kk / 4] is instruction kk
+    uint32_t even[2], odd[2], seven[2], sodd[2];
+    if constexpr (BITS <= 3) {
 #pragma unroll
-        for (int wq = 0; wq < 2; ++wq) {
-          uint32_t w[3];
-#pragma unroll
-          for (int p = 0; p < 3; ++p) w[p] = hf ? (wq ? cur.pl[p].w : cur.pl[p].z) : (wq ? cur.pl[p].y : cur.pl[p].x);
-          const uint32_t m0 = ~(w[0] ^ w[2]), m1 = ~(w[1] ^ w[2]);
-          const uint32_t even = bfi(0x0F0F0F0Fu, m0, m1 << 4), odd = bfi(0x0F0F0F0Fu, m0 >> 4, m1);
-          const uint32_t seven = w[2] & 0x0F0F0F0Fu, sodd = (w[2] >> 4) & 0x0F0F0F0Fu;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const uint2 lo4 = cen_tab[(even >> (8 * j)) & 0xFFu], hi4 = cen_tab[(odd >> (8 * j)) & 0xFFu];
-            const uint2 ls = cen_tab[256 + ((seven >> (8 * j)) & 0xFFu)], hs = cen_tab[256 + ((sodd >> (8 * j)) & 0xFFu)];
-            *reinterpret_cast<uint4*>(&Z[tl * ZLD + 64 * hf + 32 * wq + 8 * j]) =
-                make_uint4(lo4.x | ls.x, lo4.y | ls.y, hi4.x | hs.x, hi4.y | hs.y);
-          }
+      for (int wq = 0; wq < 2; ++wq) {
+        uint32_t a, b;
+        if constexpr (BITS == 1) {
+          a = cur.pl[0][wq];
+          b = 0u;
+        } else if constexpr (BITS == 2) {
+          a = cur.pl[0][wq];
+          b = cur.pl[1][wq];
+        } else {
+          // magnitude bit p of a code: plane p where the sign plane is set, its complement where it is clear
+          a = ~(cur.pl[0][wq] ^ cur.pl[2][wq]);
+          b = ~(cur.pl[1][wq] ^ cur.pl[2][wq]);
+          seven[wq] = cur.pl[2][wq] & 0x0F0F0F0Fu;
+          sodd[wq] = (cur.pl[2][wq] >> 4) & 0x0F0F0F0Fu;
+        }
+        even[wq] = bfi(0x0F0F0F0Fu, a, b << 4);   // byte j: low nibbles of byte j of the two planes
+        odd[wq] = bfi(0x0F0F0F0Fu, a >> 4, b);    // byte j: high nibbles
+      }
+    }
+    auto operand = [&](auto kk_ic) __attribute__((always_inline)) {
+      constexpr int kk = decltype(kk_ic)::value;
+      H8 z;
+      if constexpr (BITS <= 3) {
+        const uint2 lo4 = cen_tab[(even[kk >> 2] >> (8 * (kk & 3))) & 0xFFu], hi4 = cen_tab[(odd[kk >> 2] >> (8 * (kk & 3))) & 0xFFu];
+        z.u = make_uint4(lo4.x, lo4.y, hi4.x, hi4.y);
+        if constexpr (BITS == 3) {
+          const uint2 ls = cen_tab[256 + ((seven[kk >> 2] >> (8 * (kk & 3))) & 0xFFu)];
+          const uint2 hs = cen_tab[256 + ((sodd[kk >> 2] >> (8 * (kk & 3))) & 0xFFu)];
+          z.u = make_uint4(lo4.x | ls.x, lo4.y | ls.y, hi4.x | hs.x, hi4.y | hs.y);
         }
       } else {
+        uint32_t byte[BITS];
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          uint32_t byte[BITS];
-#pragma unroll
-          for (int p = 0; p < BITS; ++p) {
-            const uint32_t wsel = (kk < 2) ? cur.pl[p].x : (kk < 4) ? cur.pl[p].y : (kk < 6) ? cur.pl[p].z : cur.pl[p].w;
-            byte[p] = (wsel >> (16 * (kk & 1) + 8 * hf)) & 0xFFu;   // plane byte 2 kk + hf
-          }
-          const H8 c = centroids_of<BITS>(byte, mask_tab, mg);
-          *reinterpret_cast<uint4*>(&Z[tl * ZLD + 16 * kk + 8 * hf]) = c.u;
-        }
+        for (int p = 0; p < BITS; ++p) byte[p] = (cur.pl[p][kk >> 2] >> (8 * (kk & 3))) & 0xFFu;
+        z = centroids_of<BITS>(byte, mask_tab, mg);
       }
-      if (hf == 0) rho_s[tl] = half_bits_to_float(cur.rho) * inv_sqrt_d;
+      return z;
+    };
+    float16v acc[4];
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int i = (tid + THREADS * u) >> 4, seg = tid & 15;
-        if (i < r) {
-          H8 c;
-          c.u = cur.cf[u];
+    for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-          for (int x = 0; x < 8; ++x) Ct[(8 * seg + x) * CLD + i] = c.s[x];
-        }
+      for (int v = 0; v < 16; ++v) acc[cb][v] = 0.0f;
+    EOQ_SFOR(kk, 8,
+      const H8 z = operand(std::integral_constant<int, kk>{});
+      EOQ_SFOR(cb, 4, acc[cb] = mfma16(Ap[cb][kk], z, acc[cb]););
+    );
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[cb][v] *= rs;
+    if (r > 0) {   // uniform
+      EOQ_SFOR(cb, 4, acc[cb] = mfma16(Bv[cb], Cop, acc[cb]););
+      if (r > 16) {
+        // components 16 .. 31: their coefficient rows of this tile are fetched here, nothing of them is kept
+        const __amdgpu_buffer_rsrc_t lbuf = buffer_of(lfac + (size_t)blk * r_max * n, (size_t)r * n * 2);
+        const u32x4 c2 = __builtin_amdgcn_raw_buffer_load_b128(lbuf, vo_cf + (uint32_t)(16 * n * 2), t0 * 2, 0);
+        *reinterpret_cast<u32x4*>(cs + (16 + (lane >> 2)) * CTLD + (lane & 3) * 8) = c2;
+        __builtin_amdgcn_wave_barrier();
+        const H8 c2op = c_operand(1);
+        EOQ_SFOR(cb, 4,
+          H8 va;
+          va.u = v2[cb * 64 + lane];
+          acc[cb] = mfma16(va, c2op, acc[cb]);
+        );
       }
-      // ---- request the next chunk (of this block or of the next one) ----
-      const bool last = (t0 + CHUNK >= n);
-      {
-        const int64_t nb = last ? blk + step : blk;
-        if (nb < B) {
-          const int rn = last ? rank_value(rk_n, r_max) : r;
-          if (last) rk_n = rank_request(ranks, min(blk + 2 * step, B));
-          decode_fetch<BITS>(nxt, nb, last ? 0 : t0 + CHUNK, n, rn, r_max, tid, tl, codes, norms, lfac);
-          if (last) decode_fetch_v(vraw, nb, rn, r_max, jcol, hf, rfac);
-        }
+    }
+    // register v of column block cb is column 32 cb + 8 (v / 4) + 4 hf + v % 4 of the lane's token
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint2 pk = make_uint2(pack_half2(acc[cb][4 * q], acc[cb][4 * q + 1]), pack_half2(acc[cb][4 * q + 2], acc[cb][4 * q + 3]));
+        *reinterpret_cast<uint2*>(ot + l32 * ZLD + 32 * cb + 8 * q + 4 * hf) = pk;
       }
-      __syncthreads();
-      // ---- phase 2: wave w produces columns 32w .. 32w+31 of every tile; two tiles at a time so that consecutive
-      // matrix instructions never wait for each other's accumulator.  Unrolled: in front of a loop with stores
-      // in it the compiler would wait for the bytes requested above. ----
+    // the tile leaves by rows: lane L stores 16 bytes of row 4 ps + L / 16 (one wave's LDS operations complete in order)
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int tau = 0; tau < CHUNK / 32; tau += 2) {
-        float16v acc[2];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.0f;
-        const int arow = 32 * tau + l32;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          H8 a0, a1;
-          a0.u = *reinterpret_cast<const uint4*>(&Z[arow * ZLD + 16 * kk + 8 * hf]);
-          a1.u = *reinterpret_cast<const uint4*>(&Z[(arow + 32) * ZLD + 16 * kk + 8 * hf]);
-          acc[0] = mfma16(a0, Bhi[kk], acc[0]);
-          acc[1] = mfma16(a1, Bhi[kk], acc[1]);
-        }
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const float4 s = *reinterpret_cast<const float4*>(&rho_s[32 * (tau + h2) + 8 * q + 4 * hf]);
-            acc[h2][4 * q + 0] *= s.x;
-            acc[h2][4 * q + 1] *= s.y;
-            acc[h2][4 * q + 2] *= s.z;
-            acc[h2][4 * q + 3] *= s.w;
-          }
-        }
-        if (r > 0) {
-#pragma unroll
-          for (int k2 = 0; k2 < 2; ++k2) {
-            if (16 * k2 < r) {
-              H8 a0, a1;
-              a0.u = *reinterpret_cast<const uint4*>(&Ct[arow * CLD + 16 * k2 + 8 * hf]);
-              a1.u = *reinterpret_cast<const uint4*>(&Ct[(arow + 32) * CLD + 16 * k2 + 8 * hf]);
-              acc[0] = mfma16(a0, Bv[k2], acc[0]);
-              acc[1] = mfma16(a1, Bv[k2], acc[1]);
-            }
-          }
-        }
-        // through a wave-private LDS tile so that a lane stores 16 bytes (8 columns of one token): 2 store
-        // instructions per tile instead of 16 two-byte ones
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-          uint16_t* ot = Ot + wave * (32 * OLD);
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = 8 * (v >> 2) + 4 * hf + (v & 3);
-            ot[row * OLD + l32] = float_to_half_bits(acc[h2][v]);
-          }
-          __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the tile is private to this wave
-          __builtin_amdgcn_wave_barrier();
-          uint16_t* dst = out + ((size_t)blk * n + t0 + 32 * (tau + h2)) * D + 32 * wave;
-#pragma unroll
-          for (int ps = 0; ps < 2; ++ps) {
-            const int row = 16 * ps + (lane >> 2), cg = (lane & 3) * 8;
-            const uint4 val = *reinterpret_cast<const uint4*>(ot + row * OLD + cg);
-            *reinterpret_cast<uint4*>(dst + (size_t)row * D + cg) = val;
-          }
-          __builtin_amdgcn_wave_barrier();
-        }
-      }
-      cur = nxt;
-      if (last) pack_v(Bv, vraw);
+    for (int ps = 0; ps < 8; ++ps) {
+      const uint4 val = *reinterpret_cast<const uint4*>(ot + (4 * ps + (lane >> 4)) * ZLD + (lane & 15) * 8);
+      const u32x4 vv = {val.x, val.y, val.z, val.w};
+      __builtin_amdgcn_raw_buffer_store_b128(vv, obuf, vo_row, (t0 + 4 * ps) * (D * 2), 0);
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    cur = nxt;
+    if (unit_ends) {
+      if (!more) break;
+      u = un;
+      blk = blk_n;
+      part = part_n;
+      r = r_n;
+      ti = 0;
+    } else {
+      ++ti;
     }
   }
 }
@@ -894,12 +990,21 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
 // ---------------------------------------------------------------------------------------------
 hipError_t eoq_launch_decode(const EoqLaunch& L, eoq_packed in, int64_t B, void* out_fp16) {
   if (L.ev) (void)hipEventRecord(L.ev[4], L.stream);
-  // persistent workgroups: two per compute unit, each walks the blocks with that stride
-  const dim3 grid((unsigned)(B < 512 ? B : 512)), block(THREADS);
+  if (B <= 0) {
+    if (L.ev) (void)hipEventRecord(L.ev[5], L.stream);
+    return hipGetLastError();
+  }
+  // Every wave is a worker; two workgroups of four per compute unit (2048 waves).  A unit of work is a whole block
+  // when that leaves every wave at least two of them, otherwise a half or a quarter of a block's 32-token tiles.
+  const int tiles = L.n / 32;
+  int parts_log2 = 0;
+  while (parts_log2 < 2 && (B << parts_log2) < 4096 && tiles % (2 << parts_log2) == 0) ++parts_log2;
+  const int64_t units = B << parts_log2;
+  const dim3 grid((unsigned)(units < 2048 ? (units + 3) / 4 : 512)), block(THREADS);
   uint16_t* out = static_cast<uint16_t*>(out_fp16);
 #define EOQ_DECODE(BITS)                                                                                             \
-  hipLaunchKernelGGL(eoq_decode_mfma_kernel<BITS>, grid, block, 0, L.stream, L.n, L.r_max, B, L.pih, L.tab, in.codes, \
-                     in.norms, in.rank, in.lfac, in.rfac, out)
+  hipLaunchKernelGGL(eoq_decode_mfma_kernel<BITS>, grid, block, 0, L.stream, L.n, L.r_max, B, parts_log2, L.pih, L.tab,   \
+                     in.codes, in.norms, in.rank, in.lfac, in.rfac, out)
   switch (L.bits) {
     case 1: EOQ_DECODE(1); break;
     case 2: EOQ_DECODE(2); break;
