@@ -10,10 +10,10 @@
 // A[row = l%32][k = 8*(l/32) .. +7] and B[k = 8*(l/32) .. +7][col = l%32]; it receives
 // D[row = 8*(v/4) + 4*(l/32) + v%4][col = l%32] in accumulator register v = 0..15.
 //
-// Layout of the work: the rotation is the stationary operand.  Wave w of a workgroup keeps the 32 columns
-// j = 32w .. 32w+31 of Pi (as B operand: binary16 hi + lo parts in the encoder and the qjl kernel, the binary16
-// rounding alone in the decoder) in registers for the whole block; the tokens stream through LDS in tiles of 32
-// (A operand), each tile prepared by one wave and consumed by all four.
+// Layout of the work: the rotation is the stationary operand.  In the encoder and the qjl kernel wave w of a workgroup
+// keeps the 32 columns j = 32w .. 32w+31 of Pi (binary16 hi + lo parts, B operand) in registers for the whole block; the
+// tokens stream through LDS in tiles of 32 (A operand), each tile prepared by one wave and consumed by all four.  In the
+// decoder every wave keeps the whole of Pi^T (binary16 rounding, A operand) and works on tiles of its own.
 #include "eoq_device.h"
 #include "eoq_internal.h"
 
@@ -166,9 +166,7 @@ __device__ __forceinline__ H8 centroids_of(const uint32_t (&byte)[BITS], const u
 }
 
 // ---------------------------------------------------------------------------------------------
-// decode: persistent workgroups, each walking blocks blockIdx.x, blockIdx.x + gridDim.x, ...  The rotation
-// operands are loaded once per workgroup; the record bytes of the next 128 tokens (of this block or the next) are
-// requested while the current 128 go through the matrix cores, so reads stay in flight across the barriers.
+// Record fetches of the workgroup-per-block kernels (TQ_prod side information below).
 // ---------------------------------------------------------------------------------------------
 // What one thread requests of a chunk of 128 tokens: lane (l32, hf) of wave w unpacks half of token 32 w + l32;
 // thread tid also carries 8 tokens of row (tid + 256 u) / 16 of the left factors, u = 0, 1.
@@ -451,43 +449,51 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
       }
       return z;
     };
-    float16v acc[4];
+    // all four column blocks at once (every unpacked operand feeds four matrix instructions); at 4 bits, where the
+    // unpacking itself needs more registers, one at a time in four passes
+    constexpr int NCB = (BITS == 4) ? 1 : 4;
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
+    for (int pass = 0; pass < 4 / NCB; ++pass) {
+      float16v acc[NCB];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[cb][v] = 0.0f;
-    EOQ_SFOR(kk, 8,
-      const H8 z = operand(std::integral_constant<int, kk>{});
-      EOQ_SFOR(cb, 4, acc[cb] = mfma16(Ap[cb][kk], z, acc[cb]););
-    );
+      for (int c = 0; c < NCB; ++c)
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.0f;
+      EOQ_SFOR(kk, 8,
+        const H8 z = operand(std::integral_constant<int, kk>{});
+        EOQ_SFOR(c, NCB, acc[c] = mfma16(Ap[NCB * pass + c][kk], z, acc[c]););
+      );
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[cb][v] *= rs;
-    if (r > 0) {   // uniform
-      EOQ_SFOR(cb, 4, acc[cb] = mfma16(Bv[cb], Cop, acc[cb]););
-      if (r > 16) {
-        // components 16 .. 31: their coefficient rows of this tile are fetched here, nothing of them is kept
-        const __amdgpu_buffer_rsrc_t lbuf = buffer_of(lfac + (size_t)blk * r_max * n, (size_t)r * n * 2);
-        const u32x4 c2 = __builtin_amdgcn_raw_buffer_load_b128(lbuf, vo_cf + (uint32_t)(16 * n * 2), t0 * 2, 0);
-        *reinterpret_cast<u32x4*>(cs + (16 + (lane >> 2)) * CTLD + (lane & 3) * 8) = c2;
-        __builtin_amdgcn_wave_barrier();
-        const H8 c2op = c_operand(1);
-        EOQ_SFOR(cb, 4,
-          H8 va;
-          va.u = v2[cb * 64 + lane];
-          acc[cb] = mfma16(va, c2op, acc[cb]);
-        );
+      for (int c = 0; c < NCB; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] *= rs;
+      if (r > 0) {   // uniform
+        EOQ_SFOR(c, NCB, acc[c] = mfma16(Bv[NCB * pass + c], Cop, acc[c]););
+        if (r > 16) {
+          // components 16 .. 31: their coefficient rows of this tile are fetched here, nothing of them is kept
+          if (pass == 0) {
+            const __amdgpu_buffer_rsrc_t lbuf = buffer_of(lfac + (size_t)blk * r_max * n, (size_t)r * n * 2);
+            const u32x4 c2 = __builtin_amdgcn_raw_buffer_load_b128(lbuf, vo_cf + (uint32_t)(16 * n * 2), t0 * 2, 0);
+            *reinterpret_cast<u32x4*>(cs + (16 + (lane >> 2)) * CTLD + (lane & 3) * 8) = c2;
+            __builtin_amdgcn_wave_barrier();
+          }
+          const H8 c2op = c_operand(1);
+          EOQ_SFOR(c, NCB,
+            H8 va;
+            va.u = v2[(NCB * pass + c) * 64 + lane];
+            acc[c] = mfma16(va, c2op, acc[c]);
+          );
+        }
       }
+      // register v of column block cb is column 32 cb + 8 (v / 4) + 4 hf + v % 4 of the lane's token
+#pragma unroll
+      for (int c = 0; c < NCB; ++c)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint2 pk = make_uint2(pack_half2(acc[c][4 * q], acc[c][4 * q + 1]), pack_half2(acc[c][4 * q + 2], acc[c][4 * q + 3]));
+          *reinterpret_cast<uint2*>(ot + l32 * ZLD + 32 * (NCB * pass + c) + 8 * q + 4 * hf) = pk;
+        }
     }
-    // register v of column block cb is column 32 cb + 8 (v / 4) + 4 hf + v % 4 of the lane's token
-#pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const uint2 pk = make_uint2(pack_half2(acc[cb][4 * q], acc[cb][4 * q + 1]), pack_half2(acc[cb][4 * q + 2], acc[cb][4 * q + 3]));
-        *reinterpret_cast<uint2*>(ot + l32 * ZLD + 32 * cb + 8 * q + 4 * hf) = pk;
-      }
     // the tile leaves by rows: lane L stores 16 bytes of row 4 ps + L / 16 (one wave's LDS operations complete in order)
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
