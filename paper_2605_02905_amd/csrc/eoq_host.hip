@@ -476,6 +476,8 @@ eoq_status eoq_scores(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n_kv_hea
   if (eoq_status st = check_packed(ctx, keys)) return st;
   if (n_seq * n_kv_heads * blocks_per_head > (int64_t)1 << 24)
     return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  if ((int64_t)(n_q_heads / n_kv_heads) * blocks_per_head * ctx->n * 4 > 0x7FFFFFFF)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "the score rows of one KV head exceed 2 GiB");
   const EoqLaunch L = make_launch(ctx, hip_stream);
   hipError_t e = eoq_launch_scores(L, keys, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores);
   if (ctx->profile) ctx->ev_valid[3] = (e == hipSuccess);
@@ -510,6 +512,8 @@ eoq_status eoq_scores_stream(eoq_ctx* ctx, eoq_packed keys, int64_t n_seq, int n
     if (eoq_status st = check_packed(ctx, keys)) return st;
   if (n_seq * n_kv_heads * block_capacity > (int64_t)1 << 24)
     return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  if ((int64_t)(n_q_heads / n_kv_heads) * score_stride * 4 > 0x7FFFFFFF)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "the score rows of one KV head exceed 2 GiB");
   const EoqLaunch L = make_launch(ctx, hip_stream);
   hipError_t e = eoq_launch_scores(L, keys, n_seq, n_kv_heads, blocks_filled, q_fp16, n_q_heads, scores, block_capacity,
                                    score_stride, tail_fp16, tail_capacity, (int)tail_len);
@@ -624,6 +628,8 @@ eoq_status eoq_scores_prod(eoq_ctx* ctx, eoq_packed keys, eoq_qjl qjl, int64_t n
     return fail(ctx, EOQ_ERR_ARG, "eoq_qjl has a null or misaligned member");
   if (n_seq * n_kv_heads * blocks_per_head > (int64_t)1 << 24)
     return fail(ctx, EOQ_ERR_UNSUPPORTED, "more than 2^24 blocks in one call");
+  if ((int64_t)(n_q_heads / n_kv_heads) * blocks_per_head * ctx->n * 4 > 0x7FFFFFFF)
+    return fail(ctx, EOQ_ERR_UNSUPPORTED, "the score rows of one KV head exceed 2 GiB");
   const EoqLaunch L = make_launch(ctx, hip_stream);
   const hipError_t e = eoq_launch_scores_prod(L, keys, qjl, n_seq, n_kv_heads, blocks_per_head, q_fp16, n_q_heads, scores);
   if (ctx->profile) ctx->ev_valid[3] = (e == hipSuccess);

@@ -7,13 +7,19 @@
 // half):  z_hat_j = s_j sum_M coef[M] prod_{p in M} m_pj over the subsets M of the b-1 magnitude bits (b = 2: c_0 + (c_1 -
 // c_0) m_0).  Every term is an inner product of q' = Pi q with a vector of entries in {-1, 0, +1}: exact in int8.  q' is
 // multiplied by the coefficient of its term and held in 32-bit fixed point per head (a power-of-two unit, four balanced
-// signed bytes), so the rows of the A operand of v_mfma_i32_16x16x64_i8 are the four byte planes of four query heads and
-// all sixteen rows do work, the terms of a coordinate sit side by side along k (one int32 accumulator takes the whole
-// sum, exactly), the columns are sixteen tokens, and the four planes of a head meet again through three lane swaps.
-// Operand convention of v_mfma_i32_16x16x64_i8 (wave64): lane l supplies A[row = l%16][k = 16*(l/16) .. +15] and
-// B[k = 16*(l/16) .. +15][col = l%16] and receives D[row = 4*(l/16) + v][col = l%16] in accumulator register v.
+// signed bytes): the 32 rows of the A operand of v_mfma_i32_32x32x32_i8 are the four byte planes of eight query heads,
+// the terms of a coordinate sit side by side along k (one int32 accumulator takes the whole sum, exactly) and the
+// columns are 32 tokens.
+// Operand convention of v_mfma_i32_32x32x32_i8 (wave64): lane l supplies A[row = l%32][k = 16*(l/32) .. +15] and
+// B[k = 16*(l/32) .. +15][col = l%32] and receives D[row = 8*(v/4) + 4*(l/32) + v%4][col = l%32] in accumulator
+// register v.  Row 8 q + 4 f + e is byte plane e of head 2 q + f: lane (token, f) receives all four planes of the heads
+// f, 2 + f, 4 + f, 6 + f of ITS token, joins them, scales by its own stored norm and stores -- nothing changes lanes.
+// The low-rank term rides the f16 matrix cores the same way: rows e = 0 / 1 of head 2 q + f hold the binary16 hi / lo
+// parts of w_h = V_r^T q_h / sqrt(d), the B operand the token's stored coefficients.
 // The {-1, 0, +1} operands come out of a 256-entry LDS table indexed by one nibble of the sign plane and one nibble of a
-// magnitude plane: four coordinates of two terms per 8-byte read, in the order the matrix instruction takes them.
+// magnitude plane: four coordinates of two terms per 8-byte read, in the order the matrix instruction takes them; the
+// lane that owns a token reads its 8 bytes of every bit-plane straight from the record (lane half f: coordinates 64 f ..
+// 64 f + 63).
 #include "eoq_device.h"
 #include "eoq_internal.h"
 
@@ -24,9 +30,7 @@ using namespace eoqdev;
 constexpr int D = EOQ_D;
 constexpr int THREADS = 256;
 constexpr int SC_MAXG = 8;      // most query heads per KV head
-constexpr int SC_DEPTH = 2;     // passes of record bytes in flight per wave
 constexpr int SC_RUN_MAX = 16;  // most blocks per workgroup (the run is shortened until the grid fills the chip)
-constexpr int SC_CBP = 8;       // stored coefficients of this many components are requested one pass ahead
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
@@ -34,6 +38,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 union H8 {
   half8 h;
   uint4 u;
+  uint32_t w[4];
   uint16_t s[8];
 };
 
@@ -123,118 +128,29 @@ __device__ __forceinline__ void fixed_point_rows(const float* rows, const float 
   __syncthreads();
 }
 
-// The {-1, 0, +1} operands of one token for this lane's 32 coordinates (bits 0..31 of the lane's word of every bit
-// plane), in the order of k that fixed_point_rows gives the query side: for every nibble (four coordinates) the terms
-// M = 0 .. TYPES-1 (M = subset of the magnitude bits, M = 0 the sign alone), four bytes each.  B[i] is the operand of
-// matrix instruction i of the 2 TYPES that cover the word.  One table read per nibble and magnitude plane: entry (sign
-// nibble | magnitude nibble << 4) = (the four sign bytes, the same bytes where the magnitude bit is set).
-template <int BITS>
-__device__ __forceinline__ void term_operands(const uint32_t (&word)[BITS], const uint2* nib_tab, v4i (&B)[2 << (BITS - 1)]) {
-  constexpr int TYPES = 1 << (BITS - 1);
-  const uint32_t top = word[BITS - 1];
-  uint32_t term[8][TYPES];   // [nibble][term]
-#pragma unroll
-  for (int p = 0; p < (BITS > 1 ? BITS - 1 : 1); ++p) {
-    // magnitude bit p of a code is plane p where the sign plane is set and its complement where it is clear
-    const uint32_t x = (BITS > 1) ? ~(word[BITS > 1 ? p : 0] ^ top) : 0u;
-    const uint32_t even = bfi(0x0F0F0F0Fu, top, x << 4);   // byte j: nibbles 2j of (top, x)
-    const uint32_t odd = bfi(0x0F0F0F0Fu, top >> 4, x);    // byte j: nibbles 2j + 1
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const uint32_t idx = (((k & 1) ? odd : even) >> (8 * (k >> 1))) & 0xFFu;
-      if (p == 0) {
-        if constexpr (BITS > 1) {
-          const uint2 e = nib_tab[idx];
-          term[k][0] = e.x;
-          term[k][1] = e.y;
-        } else {
-          term[k][0] = nib_tab[idx].x;
-        }
-      } else {
-        term[k][(1 << p) % TYPES] = nib_tab[idx].y;
-      }
-    }
-  }
-  // products of several magnitude bits: bytes are 0 or the sign byte, so the product is the bitwise AND
-#pragma unroll
-  for (int M = 3; M < TYPES; ++M) {
-    if ((M & (M - 1)) != 0) {
-      const int low = M & -M;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) term[k][M] = term[k][low] & term[k][M ^ low];
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < 2 * TYPES; ++i)
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int flat = 4 * i + w;   // dword number along k: nibble flat / TYPES, term flat % TYPES
-      B[i][w] = (int)term[flat / TYPES][flat % TYPES];
-    }
-}
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+constexpr int CTLD = 32 + 8;   // row stride (halfs) of a tile's coefficient rows in LDS, [component][token]
 
-// The four accumulator registers of a lane are four heads of byte plane g = lane / 16.  Joins the planes: lane group g
-// returns sum_p 256^p (register g of plane p), the value of head g in integer units.  v_permlane16_swap exchanges the odd
-// 16-lane rows of its first operand with the even rows of its second, v_permlane32_swap the upper half of the first with
-// the lower half of the second; planes 2k and 2k + 1 are joined exactly in int32 (|register| < 2^18), the two halves in
-// float32.
-__device__ __forceinline__ float join_planes(const v4i& acc) {
-  typedef unsigned int u2 __attribute__((ext_vector_type(2)));
-  const u2 a = __builtin_amdgcn_permlane16_swap((unsigned)acc[0], (unsigned)acc[1], false, false);
-  const u2 b = __builtin_amdgcn_permlane16_swap((unsigned)acc[2], (unsigned)acc[3], false, false);
-  // even rows: (own plane, head r | plane + 1, head r), odd rows: (plane - 1, head r | own plane, head r); r = row parity
-  const int ta = (int)a[0] + (int)a[1] * 256;   // head r,     planes 2k, 2k + 1
-  const int tb = (int)b[0] + (int)b[1] * 256;   // head 2 + r, planes 2k, 2k + 1
-  const u2 c = __builtin_amdgcn_permlane32_swap((unsigned)ta, (unsigned)tb, false, false);
-  // lower half: (planes 0-1 of head r, planes 2-3 of head r); upper half: (planes 0-1 of head 2 + r, planes 2-3 of it)
-  return fmaf((float)(int)c[1], 65536.0f, (float)(int)c[0]);
-}
-
-// 4 x 4 transpose across the four lane groups: on entry lane group g holds r0 .. r3, on return lane group s holds
-// out[g] = (r_s of lane group g).
-__device__ __forceinline__ void transpose_groups(float r0, float r1, float r2, float r3, float (&out)[4]) {
-  typedef unsigned int u2 __attribute__((ext_vector_type(2)));
-  const u2 a = __builtin_amdgcn_permlane32_swap(__float_as_uint(r0), __float_as_uint(r2), false, false);
-  const u2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(r1), __float_as_uint(r3), false, false);
-  const u2 c = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
-  const u2 d = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
-  out[0] = __uint_as_float(c[0]);
-  out[1] = __uint_as_float(c[1]);
-  out[2] = __uint_as_float(d[0]);
-  out[3] = __uint_as_float(d[1]);
-}
-
-// What a lane requests of one chunk of 128 consecutive tokens (the unit of work of a wave): piece i of the chunk's codes
-// (bytes 1024 i + 16 lane .. + 15: every load instruction covers 1 KB without gaps), the stored norms and the stored
-// coefficients of ITS OWN two tokens 2 lane and 2 lane + 1 of the chunk (with QJL also the sign planes and residual norms).
+// What a lane requests of a tile of 32 consecutive tokens: lane (l32, hf) owns token l32.
 template <int BITS, bool QJL>
-struct ChunkFetch {
-  uint4 code[2 * BITS];
-  uint32_t rho2;
-  uint32_t cf[SC_CBP];
-  uint4 sign[QJL ? 2 : 1];
-  uint32_t gam2;
+struct TileFetch {
+  u32x2 pl[BITS];            // bytes 8 hf .. 8 hf + 7 of every bit-plane of the token
+  uint32_t rho;              // the token's stored norm (binary16 in the low half)
+  u32x4 cf;                  // lane L: stored coefficients C[tokens 8 (L % 4) .. + 7][component L / 4]; zero at and above the rank
+  u32x2 sg[QJL ? 1 : 0];     // the same bytes of sign(Phi r_x)
+  uint32_t gam[QJL ? 1 : 0]; // the token's stored residual norm
 };
-// Buffer addressing: a resource descriptor in scalar registers (base of this workgroup's run of blocks, size of the
-// run: reads past it return zero instead of faulting), a scalar byte offset that moves from chunk to chunk and a per-lane
-// 32-bit offset that never changes -- no vector arithmetic per load.
-struct ScoreBuffers {
-  __amdgpu_buffer_rsrc_t codes, norms, lfac, qsigns, qnorms;
-};
-typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 load_b128(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, int soffset) {
-  const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voffset, soffset, 0);
-  return make_uint4(v[0], v[1], v[2], v[3]);
-}
-// LDS staging of a chunk's codes: 16 bytes of padding after every 256, so that the sixteen token pairs a matrix
-// instruction's lanes read side by side (64 BITS/2 bytes apart) fall into different banks while 16-byte pieces stay aligned.
-__host__ __device__ constexpr int stage_pad(int a) { return a + ((a >> 8) << 4); }
 
-// One workgroup per (sequence, KV head, run of blocks).  NSETS = sets of four query heads (1 for groups up to 4).
+// One workgroup per (sequence, KV head, run of blocks); every wave works on 32-token tiles of its own (tile u of the
+// run: tokens 32 (u % tpb) .. of block u / tpb; wave w takes the tiles w, w + 4, ...), the record bytes of the next
+// tile on their way while this one is worked on.  NQ = query heads a lane finishes per token (2 for groups up to 4).
 // QJL: the logits get the correction of Eq. (qjl), |r_x| sqrt(pi/2)/d <Phi q, sign(Phi r_x)>, from one more bit plane
 // (the signs) and the stored residual norm; Phi q goes through the same fixed-point form as Pi q.
-template <int BITS, bool QJL, int NSETS>
-__global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
+template <int BITS, bool QJL, int NQ>
+__global__ __launch_bounds__(THREADS, (BITS <= 2 && !QJL) ? 4 : 1) void eoq_scores_i8_kernel(
     int n, int r_max, int n_kv_heads, int group, int64_t blocks_per_head, int64_t block_capacity, int64_t score_stride,
     int run, const uint16_t* __restrict__ pih,
     const float* __restrict__ tab, const uint8_t* __restrict__ codes, const uint16_t* __restrict__ norms,
@@ -242,13 +158,13 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
     const uint16_t* __restrict__ q, float* __restrict__ scores, const uint16_t* __restrict__ phih,
     const uint8_t* __restrict__ qsigns, const uint16_t* __restrict__ qnorms) {
   constexpr int TYPES = 1 << (BITS - 1);
-  constexpr int WH = 4 * NSETS;   // heads the run's w table holds
+  constexpr int NMM = 4 * TYPES;   // matrix instructions per tile: 64 coordinates x TYPES bytes per lane, 16 at a time
+  constexpr int WH = 2 * NQ;       // heads the run's w table holds
   // One pool, used in turn: during the set-up the query (float), its rotation, and the byte planes of coef[M] Pi q
-  // ([head][plane][k]) and of Phi q; in the chunk loop the four waves' staging buffers.  The barrier behind the w table
-  // separates the two uses.
-  constexpr int CODE_STAGE = stage_pad(128 * (BITS * D / 8)), SIGN_STAGE = QJL ? stage_pad(128 * (D / 8)) : 0;
+  // ([head][plane][k]) and of Phi q; in the tile loop the four waves' coefficient tiles.  The barrier behind the w
+  // table separates the two uses.
   constexpr int SETUP_BYTES = 2 * SC_MAXG * D * 4 + SC_MAXG * 4 * TYPES * D + (QJL ? SC_MAXG * 4 * D : 0);
-  constexpr int LOOP_BYTES = 4 * (CODE_STAGE + SIGN_STAGE);
+  constexpr int LOOP_BYTES = 4 * 2 * 16 * CTLD * 2;
   __shared__ __align__(16) unsigned char pool[SETUP_BYTES > LOOP_BYTES ? SETUP_BYTES : LOOP_BYTES];
   float* qraw = reinterpret_cast<float*>(pool);
   float* qrot = qraw + SC_MAXG * D;
@@ -262,6 +178,7 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave: scalar
   const int l16 = lane & 15, g = lane >> 4;
+  const int l32 = lane & 31, hf = lane >> 5;
   const size_t sg = blockIdx.y;
   const size_t sq = sg / n_kv_heads, kv = sg % n_kv_heads;
   const int n_q_heads = n_kv_heads * group;
@@ -304,43 +221,32 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
     const float one[1] = {1.0f};
     fixed_point_rows<1>(qrot, one, pdig, max_s, punit, tid);
   }
-  // A operands: row l16 = byte plane l16 / 4 of head 4 hs + l16 % 4; instruction i of a token covers the 16 bytes of k
-  // from 16 i of lane group g's 32 coordinates (32 TYPES bytes).  Kq / Kp: what one integer unit of head 4 hs + v is
-  // worth in the logit.
-  v4i Aq[NSETS][2 * TYPES], Ap[QJL ? NSETS : 1][2];
-  float Kq[NSETS][4], Kp[QJL ? NSETS : 1][4];
+  // A operands: row l32 = byte plane l32 % 4 of head 2 (l32 / 8) + (l32 / 4) % 2; instruction i covers the 16 bytes of k
+  // from 16 i of lane half hf's 64 coordinates (64 TYPES bytes: per nibble of four coordinates the TYPES terms).  Kq / Kp:
+  // what one integer unit of head 2 qq + hf is worth in the logit.
+  const int arow = 4 * (2 * (l32 >> 3) + ((l32 >> 2) & 1)) + (l32 & 3);   // row of the byte planes: 4 head + plane
+  v4i Aq[NMM], Ap[QJL ? 4 : 1];
+  float Kq[NQ], Kp[QJL ? NQ : 1];
   const float qjl_scale = sqrtf(1.5707963267948966f) / (float)D;
 #pragma unroll
-  for (int hs = 0; hs < NSETS; ++hs) {
-    const int row = 4 * (4 * hs + (l16 & 3)) + (l16 >> 2);
+  for (int i = 0; i < NMM; ++i) Aq[i] = *reinterpret_cast<const v4i*>(qdig + ((size_t)arow * D + 64 * hf) * TYPES + 16 * i);
 #pragma unroll
-    for (int i = 0; i < 2 * TYPES; ++i) Aq[hs][i] = *reinterpret_cast<const v4i*>(qdig + ((size_t)row * D + 32 * g) * TYPES + 16 * i);
+  for (int qq = 0; qq < NQ; ++qq) Kq[qq] = qunit[2 * qq + hf] * (1.0f / (float)D);   // z_hat = centroid / sqrt(d), logit = <q, x_hat> / sqrt(d)
+  if constexpr (QJL) {
 #pragma unroll
-    for (int v = 0; v < 4; ++v) Kq[hs][v] = qunit[4 * hs + v] * (1.0f / (float)D);   // z_hat = centroid / sqrt(d), logit = <q, x_hat> / sqrt(d)
-    if constexpr (QJL) {
+    for (int i = 0; i < 4; ++i) Ap[i] = *reinterpret_cast<const v4i*>(pdig + arow * D + 64 * hf + 16 * i);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) Ap[hs][i] = *reinterpret_cast<const v4i*>(pdig + row * D + 32 * g + 16 * i);
-#pragma unroll
-      for (int v = 0; v < 4; ++v) Kp[hs][v] = punit[4 * hs + v] * (qjl_scale * inv_sqrt_d);
-    }
+    for (int qq = 0; qq < NQ; ++qq) Kp[qq] = punit[2 * qq + hf] * (qjl_scale * inv_sqrt_d);
   }
 
-  // The work of this workgroup as a flat list of chunks of 128 tokens: chunk u of the run is tokens 128 (u % cpb) ..
-  // of block jb0 + u / cpb; wave w takes the chunks w, w + 4, ...  The record bytes of a chunk are requested one chunk
-  // ahead into registers; the codes then pass through a wave-private LDS buffer, which hands every lane of a matrix
-  // instruction the words of its token pair, in four sub-passes of 32 tokens (tile u of sub-pass s: tokens 32 s + 2 c + u
-  // in column c).  After the four sub-passes a lane group holds one head of all four; a 4 x 4 transpose across the lane
-  // groups gives lane L all heads of its own tokens 2 L and 2 L + 1, which it scales by its own stored norms, completes
-  // with the low-rank term from its own stored coefficients and stores as 8 bytes per head: 512 contiguous bytes per wave
-  // and score row.
   const int64_t jb0 = (int64_t)blockIdx.x * run;
   const int nblk = (int)(min(jb0 + run, blocks_per_head) - jb0);
-  const int cpb = n / 128;
-  const int NCH = nblk * cpb;
+  const int tpb = n / 32;
+  const int NT = nblk * tpb;
   const size_t blk0 = sg * (size_t)block_capacity + jb0;   // the store holds block_capacity slots per head
 
   // w[b][i][h] = <v_i, q_h>/sqrt(d) of every block of the run, up front (the low-rank term is <C_t, w_h>): all loads of
-  // the set-up are in flight together and the chunk loop below has no barrier.  16 lanes per (component, head): one
+  // the set-up are in flight together and the tile loop below has no barrier.  16 lanes per (component, head): one
   // 16-byte load of eight entries of v_i each, then a sum over the DPP row.
   if (tid < nblk) rank_s[tid] = min(max(rank_in[blk0 + tid], 0), r_max);   // records may come from storage: never index past r_max rows
   __syncthreads();
@@ -365,186 +271,197 @@ __global__ __launch_bounds__(THREADS) void eoq_scores_i8_kernel(
     if (seg == 0 && b < nblk && i < rb) wbuf[(b * EOQ_RMAX_CAP + i) * WH + h] = acc * inv_sqrt_d;
   }
   __syncthreads();
+  if (wave >= NT) return;
 
-  ScoreBuffers sb;
-  sb.codes = buffer_of(codes + blk0 * (size_t)n * ROWB, (size_t)nblk * n * ROWB);
-  sb.norms = buffer_of(norms + blk0 * (size_t)n, (size_t)nblk * n * 2);
-  sb.lfac = buffer_of(lfac + blk0 * (size_t)r_max * n, (size_t)nblk * r_max * n * 2);
+  // Buffer addressing: a resource descriptor in scalar registers, a scalar byte offset that moves from tile to tile and
+  // a per-lane 32-bit offset that never changes -- no vector arithmetic per load.  The descriptors of the codes and
+  // norms cover the run (reads past it return zero); the coefficients get a descriptor per block that ends behind row
+  // rank - 1, and the range check covers the per-lane part of the offset, which holds the row: rows at and above the
+  // rank read zero.
+  const __amdgpu_buffer_rsrc_t bcodes = buffer_of(codes + blk0 * (size_t)n * ROWB, (size_t)nblk * n * ROWB);
+  const __amdgpu_buffer_rsrc_t bnorms = buffer_of(norms + blk0 * (size_t)n, (size_t)nblk * n * 2);
+  __amdgpu_buffer_rsrc_t bsigns = bcodes, bgam = bnorms;
   if constexpr (QJL) {
-    sb.qsigns = buffer_of(qsigns + blk0 * (size_t)n * (D / 8), (size_t)nblk * n * (D / 8));
-    sb.qnorms = buffer_of(qnorms + blk0 * (size_t)n, (size_t)nblk * n * 2);
+    bsigns = buffer_of(qsigns + blk0 * (size_t)n * (D / 8), (size_t)nblk * n * (D / 8));
+    bgam = buffer_of(qnorms + blk0 * (size_t)n, (size_t)nblk * n * 2);
   }
-  // chunk u: block u / cpb of the run, tokens 128 (u % cpb) ..; rows at and above the rank are asked for at an offset
-  // past the end of the buffer: those loads return zero without touching memory
-  auto request = [&](ChunkFetch<BITS, QJL>& f, int u) __attribute__((always_inline)) {
-    const int b = u / cpb, c = u - b * cpb;
-    const int tokb = b * n + 128 * c;   // uniform: first token of the chunk, counted from the start of the run
+  // score rows of this (sequence, KV head): row h at h T floats; lane (token, hf) stores head 2 qq + hf
+  const __amdgpu_buffer_rsrc_t bout = buffer_of(scores + (sq * n_q_heads + kv * group) * T, (size_t)group * T * 4);
+  const uint32_t vo_code = (uint32_t)(l32 * ROWB + 8 * hf);
+  const uint32_t vo_sign = (uint32_t)(l32 * (D / 8) + 8 * hf);
+  const uint32_t vo_norm = (uint32_t)(2 * l32);
+  const uint32_t vo_cf = (uint32_t)(((lane >> 2) * n + (lane & 3) * 8) * 2);
+  const uint32_t vo_out = (uint32_t)((hf * T + l32) * 4);
+  uint16_t* cs = reinterpret_cast<uint16_t*>(pool) + wave * (2 * 16 * CTLD);
+
+  auto coef_buffer = [&](int b) __attribute__((always_inline)) {
+    return buffer_of(lfac + (blk0 + b) * (size_t)r_max * n, (size_t)rank_s[b] * n * 2);
+  };
+  // tile u < NT: block u / tpb of the run, tokens 32 (u % tpb) ..
+  auto request = [&](TileFetch<BITS, QJL>& f, int u) __attribute__((always_inline)) {
+    const int b = u / tpb, c = u - b * tpb;
+    const int tokb = b * n + 32 * c;   // uniform: first token of the tile, counted from the start of the run
 #pragma unroll
-    for (int i = 0; i < 2 * BITS; ++i) f.code[i] = load_b128(sb.codes, 16u * lane, tokb * ROWB + 1024 * i);
-    f.rho2 = __builtin_amdgcn_raw_buffer_load_b32(sb.norms, 4u * lane, tokb * 2, 0);
-    const int rr = __builtin_amdgcn_readfirstlane(rank_s[b]);
+    for (int p = 0; p < BITS; ++p) f.pl[p] = __builtin_amdgcn_raw_buffer_load_b64(bcodes, vo_code + 16 * p, tokb * ROWB, 0);
+    f.rho = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bnorms, vo_norm, tokb * 2, 0);
+    f.cf = __builtin_amdgcn_raw_buffer_load_b128(coef_buffer(b), vo_cf, 32 * c * 2, 0);
+    if constexpr (QJL) {
+      f.sg[0] = __builtin_amdgcn_raw_buffer_load_b64(bsigns, vo_sign, tokb * (D / 8), 0);
+      f.gam[0] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bgam, vo_norm, tokb * 2, 0);
+    }
+  };
+  // A operand of the low-rank product for block b of the run, components 16 k2 + 8 hf + e: row 8 qq + 4 f of the matrix
+  // instruction holds binary16(w) of head 2 qq + f, the row after it what that rounding lost, the other two rows zero
+  auto w_operand = [&](int b, int k2) __attribute__((always_inline)) {
+    const int h = 2 * (l32 >> 3) + ((l32 >> 2) & 1), part = l32 & 3;
+    const int rb = rank_s[b];
+    H8 x;
 #pragma unroll
-    for (int a = 0; a < SC_CBP; ++a) {
-      const int row = (b * r_max + a) * n + 128 * c;   // uniform, in entries
-      f.cf[a] = __builtin_amdgcn_raw_buffer_load_b32(sb.lfac, 4u * lane, (a < rr) ? row * 2 : 0x7FFFFF00, 0);
+    for (int e = 0; e < 8; ++e) {
+      const int i = 16 * k2 + 8 * hf + e;
+      const float w = (i < rb && h < WH && part < 2) ? wbuf[(b * EOQ_RMAX_CAP + i) * WH + (h & (WH - 1))] : 0.0f;
+      const uint16_t hi = float_to_half_bits(w);
+      x.s[e] = part == 0 ? hi : float_to_half_bits(w - half_bits_to_float(hi));
+    }
+    return x;
+  };
+  // C[token l32][16 k2 + 8 hf + e] of the rows staged in the wave's coefficient tile: the B operand of that product
+  auto c_operand = [&](int k2) __attribute__((always_inline)) {
+    H8 x;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t a = cs[(16 * k2 + 8 * hf + 2 * w) * CTLD + l32], b = cs[(16 * k2 + 8 * hf + 2 * w + 1) * CTLD + l32];
+      x.w[w] = a | (b << 16);
+    }
+    return x;
+  };
+
+  int wb = -1;   // block of the run whose w operand the wave holds
+  H8 Aw;
+  Aw.u = make_uint4(0u, 0u, 0u, 0u);
+  auto work = [&](TileFetch<BITS, QJL>& cur, int u) __attribute__((always_inline)) {
+    const int b = u / tpb, c = u - b * tpb;
+    const int r = rank_s[b];
+    if (b != wb) {   // uniform
+      Aw = w_operand(b, 0);
+      wb = b;
+    }
+    // ---- the integer term: the lane's 64 coordinates, byte kk of every plane at a time ----
+    const uint32_t top0 = cur.pl[BITS - 1][0], top1 = cur.pl[BITS - 1][1];
+    v16i acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0;
+    if constexpr (BITS <= 2) {
+      // even / odd: byte j = (sign nibble | magnitude nibble << 4) of the low / high nibbles of byte j of the planes;
+      // one table read gives the four sign bytes and the same bytes where the magnitude bit is set: 8 of the 16 bytes
+      // of an instruction (BITS = 1: the sign bytes alone, 4 of 16)
+      uint32_t even[2], odd[2];
+#pragma unroll
+      for (int wq = 0; wq < 2; ++wq) {
+        const uint32_t t = wq ? top1 : top0;
+        const uint32_t x = (BITS == 2) ? ~(cur.pl[0][wq] ^ t) : 0u;   // magnitude bit: plane 0 where the sign plane is set, its complement elsewhere
+        even[wq] = bfi(0x0F0F0F0Fu, t, x << 4);
+        odd[wq] = bfi(0x0F0F0F0Fu, t >> 4, x);
+      }
+      if constexpr (BITS == 2) {
+        EOQ_SFOR(kk, 8,
+          const uint2 lo = nib_tab[(even[kk >> 2] >> (8 * (kk & 3))) & 0xFFu], hi = nib_tab[(odd[kk >> 2] >> (8 * (kk & 3))) & 0xFFu];
+          const v4i B = {(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(Aq[kk], B, acc, 0, 0, 0);
+        );
+      } else {
+        EOQ_SFOR(i, 4,
+          const v4i B = {(int)nib_tab[(even[i >> 1] >> (16 * (i & 1))) & 0xFFu].x, (int)nib_tab[(odd[i >> 1] >> (16 * (i & 1))) & 0xFFu].x,
+                         (int)nib_tab[(even[i >> 1] >> (16 * (i & 1) + 8)) & 0xFFu].x, (int)nib_tab[(odd[i >> 1] >> (16 * (i & 1) + 8)) & 0xFFu].x};
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(Aq[i], B, acc, 0, 0, 0);
+        );
+      }
+    } else {
+      // per nibble of four coordinates the TYPES terms, four bytes each: term 0 the signs, term 2^p from the table read
+      // of magnitude plane p, the other terms (products of magnitude bits) as bitwise ANDs of those
+      EOQ_SFOR(nb, 16,
+        constexpr int wq = nb >> 3, sh = 4 * (nb & 7);
+        const uint32_t t = wq ? top1 : top0;
+        uint32_t term[TYPES];
+        EOQ_SFOR(p, BITS - 1,
+          const uint32_t x = ~(cur.pl[p][wq] ^ t);
+          const uint2 e = nib_tab[((t >> sh) & 0xFu) | (((x >> sh) & 0xFu) << 4)];
+          term[0] = e.x;
+          term[1 << p] = e.y;
+        );
+        EOQ_SFOR(M, TYPES,
+          if constexpr ((M & (M - 1)) != 0) term[M] = term[M & -M] & term[M ^ (M & -M)];
+        );
+        EOQ_SFOR(i, TYPES / 4,
+          const v4i B = {(int)term[4 * i], (int)term[4 * i + 1], (int)term[4 * i + 2], (int)term[4 * i + 3]};
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(Aq[nb * (TYPES / 4) + i], B, acc, 0, 0, 0);
+        );
+      );
+    }
+    // ---- the planes of a head meet in the lane: registers 4 qq .. 4 qq + 3 are head 2 qq + hf; planes 0-1 and 2-3
+    // are joined exactly in int32 (|register| < 2^18), the halves in float32 ----
+    const float rho = half_bits_to_float((uint16_t)cur.rho);
+    float res[NQ];
+#pragma unroll
+    for (int qq = 0; qq < NQ; ++qq) {
+      const int lo = acc[4 * qq] + (acc[4 * qq + 1] << 8), hi = acc[4 * qq + 2] + (acc[4 * qq + 3] << 8);
+      res[qq] = fmaf((float)hi, 65536.0f, (float)lo) * (Kq[qq] * rho);
     }
     if constexpr (QJL) {
+      // sign(Phi r_x) is one more plane of +-1: the table's first entry kind with the magnitude nibble at zero
+      v16i ac2;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) f.sign[i] = load_b128(sb.qsigns, 16u * lane, tokb * (D / 8) + 1024 * i);
-      f.gam2 = __builtin_amdgcn_raw_buffer_load_b32(sb.qnorms, 4u * lane, tokb * 2, 0);
+      for (int v = 0; v < 16; ++v) ac2[v] = 0;
+      EOQ_SFOR(i, 4,
+        const uint32_t sw = cur.sg[0][i >> 1] >> (16 * (i & 1));
+        const v4i B = {(int)nib_tab[sw & 0xFu].x, (int)nib_tab[(sw >> 4) & 0xFu].x, (int)nib_tab[(sw >> 8) & 0xFu].x, (int)nib_tab[(sw >> 12) & 0xFu].x};
+        ac2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ap[i], B, ac2, 0, 0, 0);
+      );
+      const float gam = half_bits_to_float((uint16_t)cur.gam[0]);
+#pragma unroll
+      for (int qq = 0; qq < NQ; ++qq) {
+        const int lo = ac2[4 * qq] + (ac2[4 * qq + 1] << 8), hi = ac2[4 * qq + 2] + (ac2[4 * qq + 3] << 8);
+        res[qq] = fmaf(fmaf((float)hi, 65536.0f, (float)lo), Kp[qq] * gam, res[qq]);
+      }
+    }
+    // ---- low-rank term sum_i C[i][token] w[i][head] on the f16 matrix cores: the coefficients change lanes through the
+    // wave's LDS tile (one wave's LDS operations complete in order) ----
+    if (r > 0) {   // uniform
+      *reinterpret_cast<u32x4*>(cs + (lane >> 2) * CTLD + (lane & 3) * 8) = cur.cf;
+      __builtin_amdgcn_wave_barrier();
+      float16v lr;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) lr[v] = 0.0f;
+      lr = __builtin_amdgcn_mfma_f32_32x32x16_f16(Aw.h, c_operand(0).h, lr, 0, 0, 0);
+      if (r > 16) {
+        // components 16 .. 31 (rare): fetched and prepared here, nothing of them is kept
+        const u32x4 c2 = __builtin_amdgcn_raw_buffer_load_b128(coef_buffer(b), vo_cf + (uint32_t)(16 * n * 2), 32 * c * 2, 0);
+        *reinterpret_cast<u32x4*>(cs + (16 + (lane >> 2)) * CTLD + (lane & 3) * 8) = c2;
+        __builtin_amdgcn_wave_barrier();
+        lr = __builtin_amdgcn_mfma_f32_32x32x16_f16(w_operand(b, 1).h, c_operand(1).h, lr, 0, 0, 0);
+      }
+      __builtin_amdgcn_wave_barrier();   // the tile is rewritten by the next one
+#pragma unroll
+      for (int qq = 0; qq < NQ; ++qq) res[qq] += lr[4 * qq] + lr[4 * qq + 1];
+    }
+    const int64_t jb = jb0 + b;
+#pragma unroll
+    for (int qq = 0; qq < NQ; ++qq) {
+      // head 2 qq + hf of the group: lanes of a head that the group does not have aim behind the descriptor
+      const bool live = 2 * qq + hf < group;
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(res[qq]), bout, live ? vo_out : 0xFFFFFFF0u,
+                                            (int)((2 * qq * T + (size_t)jb * n + 32 * c) * 4), 0);
     }
   };
 
-  // this wave's staging buffers and the lane's read addresses in them (sub-pass 0; sub-pass s is a constant further on)
-  unsigned char* stage_c = pool + wave * (CODE_STAGE + SIGN_STAGE);
-  unsigned char* stage_q = stage_c + CODE_STAGE;
-  int rd_c[2][BITS], rd_q[2];
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-#pragma unroll
-    for (int p = 0; p < BITS; ++p) rd_c[u][p] = stage_pad((2 * l16 + u) * ROWB + 16 * p + 4 * g);
-    rd_q[u] = stage_pad((2 * l16 + u) * (D / 8) + 4 * g);
-  }
-  constexpr int SUB_C = stage_pad(32 * ROWB), SUB_Q = stage_pad(32 * (D / 8));   // one sub-pass further (multiples of 256 before padding)
-  const int wr = stage_pad(16 * lane);                                           // where the lane's piece of 1 KB number 0 goes
-
-  const bool even_stride = (T & 1) == 0;
-  auto work = [&](ChunkFetch<BITS, QJL>& cur, int u_chunk) __attribute__((always_inline)) {
-    const int cb_blk = u_chunk / cpb, cq = u_chunk - cb_blk * cpb;
-    const size_t blk = blk0 + cb_blk;
-    const int r = rank_s[cb_blk];
-    const float* wrow = wbuf + cb_blk * (EOQ_RMAX_CAP * WH);
-    const int64_t jb = jb0 + cb_blk;
-    // ---- the codes change lanes through LDS (the buffer is this wave's own: its LDS operations complete in order) ----
-#pragma unroll
-    for (int i = 0; i < 2 * BITS; ++i) *reinterpret_cast<uint4*>(stage_c + wr + stage_pad(1024) * i) = cur.code[i];
-    if constexpr (QJL) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4*>(stage_q + wr + stage_pad(1024) * i) = cur.sign[i];
-    }
-    __builtin_amdgcn_wave_barrier();
-    float tq[4][2][NSETS], tp[QJL ? 4 : 1][2][NSETS];   // [sub-pass][tile][set]: head 4 hs + g in integer units
-#pragma unroll
-    for (int sp = 0; sp < 4; ++sp) {
-      v4i B[2][2 * TYPES];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        uint32_t word[BITS];
-#pragma unroll
-        for (int p = 0; p < BITS; ++p) word[p] = *reinterpret_cast<const uint32_t*>(stage_c + rd_c[u][p] + SUB_C * sp);
-        term_operands<BITS>(word, nib_tab, B[u]);
-      }
-#pragma unroll
-      for (int hs = 0; hs < NSETS; ++hs) {
-        v4i acc[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          acc[u] = v4i{0, 0, 0, 0};
-#pragma unroll
-          for (int i = 0; i < 2 * TYPES; ++i) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aq[hs][i], B[u][i], acc[u], 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u) tq[sp][u][hs] = join_planes(acc[u]);
-      }
-      if constexpr (QJL) {
-        // sign(Phi r_x) is one more plane of +-1: the table's first entry kind with the magnitude nibble at zero
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const uint32_t sw = *reinterpret_cast<const uint32_t*>(stage_q + rd_q[u] + SUB_Q * sp);
-          v4i Bs[2];
-#pragma unroll
-          for (int k = 0; k < 8; ++k) Bs[k >> 2][k & 3] = (int)nib_tab[(sw >> (4 * k)) & 0xFu].x;
-#pragma unroll
-          for (int hs = 0; hs < NSETS; ++hs) {
-            v4i acc = {0, 0, 0, 0};
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(Ap[hs][0], Bs[0], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(Ap[hs][1], Bs[1], acc, 0, 0, 0);
-            tp[sp][u][hs] = join_planes(acc);
-          }
-        }
-      }
-    }
-    __builtin_amdgcn_wave_barrier();   // the staging buffer is rewritten by the next chunk
-    // ---- to the lanes that own the tokens: lane group sp takes sub-pass sp, register index becomes the head ----
-    const float rho[2] = {half_bits_to_float((uint16_t)(cur.rho2 & 0xFFFFu)), half_bits_to_float((uint16_t)(cur.rho2 >> 16))};
-    float gam[2] = {0.0f, 0.0f};
-    if constexpr (QJL) {
-      gam[0] = half_bits_to_float((uint16_t)(cur.gam2 & 0xFFFFu));
-      gam[1] = half_bits_to_float((uint16_t)(cur.gam2 >> 16));
-    }
-    float res[4][2][NSETS];   // [head of the set][token][set]
-#pragma unroll
-    for (int hs = 0; hs < NSETS; ++hs)
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        float h4[4];
-        transpose_groups(tq[0][u][hs], tq[1][u][hs], tq[2][u][hs], tq[3][u][hs], h4);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) res[v][u][hs] = h4[v] * (Kq[hs][v] * rho[u]);
-        if constexpr (QJL) {
-          transpose_groups(tp[0][u][hs], tp[1][u][hs], tp[2][u][hs], tp[3][u][hs], h4);
-#pragma unroll
-          for (int v = 0; v < 4; ++v) res[v][u][hs] = fmaf(h4[v], Kp[hs][v] * gam[u], res[v][u][hs]);
-        }
-      }
-    // ---- low-rank term from the lane's own coefficients: sum_i C[i][token] w[i][head] ----
-    if (r > 0) {
-#pragma unroll
-      for (int a = 0; a < SC_CBP; ++a) {
-        if (a < r) {   // uniform
-          const float c0 = half_bits_to_float((uint16_t)(cur.cf[a] & 0xFFFFu)), c1 = half_bits_to_float((uint16_t)(cur.cf[a] >> 16));
-#pragma unroll
-          for (int hs = 0; hs < NSETS; ++hs) {
-            const float4 w = *reinterpret_cast<const float4*>(wrow + a * WH + 4 * hs);
-            const float wv[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              res[v][0][hs] = fmaf(wv[v], c0, res[v][0][hs]);
-              res[v][1][hs] = fmaf(wv[v], c1, res[v][1][hs]);
-            }
-          }
-        }
-      }
-      for (int i = SC_CBP; i < r; ++i) {   // ranks above SC_CBP: read in place
-        const uint32_t cx = *reinterpret_cast<const uint32_t*>(lfac + (blk * r_max + i) * (size_t)n + 128 * cq + 2 * lane);
-        const float c0 = half_bits_to_float((uint16_t)(cx & 0xFFFFu)), c1 = half_bits_to_float((uint16_t)(cx >> 16));
-#pragma unroll
-        for (int hs = 0; hs < NSETS; ++hs) {
-          const float4 w = *reinterpret_cast<const float4*>(wrow + i * WH + 4 * hs);
-          const float wv[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            res[v][0][hs] = fmaf(wv[v], c0, res[v][0][hs]);
-            res[v][1][hs] = fmaf(wv[v], c1, res[v][1][hs]);
-          }
-        }
-      }
-    }
-#pragma unroll
-    for (int hs = 0; hs < NSETS; ++hs)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int h = 4 * hs + v;
-        if (h < group) {   // uniform
-          float* dst = scores + (sq * n_q_heads + kv * group + h) * T + (size_t)jb * n + 128 * cq + 2 * lane;
-          if (even_stride) {
-            *reinterpret_cast<float2*>(dst) = make_float2(res[v][0][hs], res[v][1][hs]);
-          } else {
-            dst[0] = res[v][0][hs];
-            dst[1] = res[v][1][hs];
-          }
-        }
-      }
-  };
-
-  // two register sets in turn: the next chunk is requested before this one is worked on
-  ChunkFetch<BITS, QJL> fa, fb;
-  if (wave < NCH) request(fa, wave);
-  for (int u0 = wave; u0 < NCH; u0 += 8) {
-    if (u0 + 4 < NCH) request(fb, u0 + 4);
+  // two register sets in turn: the next tile is requested before this one is worked on
+  TileFetch<BITS, QJL> fa, fb;
+  request(fa, wave);
+  for (int u0 = wave; u0 < NT; u0 += 8) {
+    if (u0 + 4 < NT) request(fb, u0 + 4);
     work(fa, u0);
-    if (u0 + 4 < NCH) {
-      if (u0 + 8 < NCH) request(fa, u0 + 8);
+    if (u0 + 4 < NT) {
+      if (u0 + 8 < NT) request(fa, u0 + 8);
       work(fb, u0 + 4);
     }
   }
@@ -609,25 +526,25 @@ hipError_t launch_scores_impl(const EoqLaunch& L, eoq_packed keys, const eoq_qjl
 #define EOQ_SCORES_ARGS                                                                                              \
   grid, block, 0, L.stream, L.n, L.r_max, n_kv_heads, group, blocks_per_head, block_capacity, score_stride, (int)run, \
       L.pih, L.tab, keys.codes, keys.norms, keys.rank, keys.lfac, keys.rfac, q, scores
-#define EOQ_SCORES(BITS, NSETS)                                                                                      \
+#define EOQ_SCORES(BITS, NQ)                                                                                         \
   do {                                                                                                               \
     if (qjl)                                                                                                         \
-      hipLaunchKernelGGL((eoq_scores_i8_kernel<BITS, true, NSETS>), EOQ_SCORES_ARGS, L.phih, qjl->signs, qjl->norms); \
+      hipLaunchKernelGGL((eoq_scores_i8_kernel<BITS, true, NQ>), EOQ_SCORES_ARGS, L.phih, qjl->signs, qjl->norms); \
     else                                                                                                             \
-      hipLaunchKernelGGL((eoq_scores_i8_kernel<BITS, false, NSETS>), EOQ_SCORES_ARGS, (const uint16_t*)nullptr,      \
+      hipLaunchKernelGGL((eoq_scores_i8_kernel<BITS, false, NQ>), EOQ_SCORES_ARGS, (const uint16_t*)nullptr,      \
                          (const uint8_t*)nullptr, (const uint16_t*)nullptr);                                         \
   } while (0)
-#define EOQ_SCORES_BITS(NSETS)              \
+#define EOQ_SCORES_BITS(NQ)                 \
   switch (L.bits) {                         \
-    case 1: EOQ_SCORES(1, NSETS); break;    \
-    case 2: EOQ_SCORES(2, NSETS); break;    \
-    case 3: EOQ_SCORES(3, NSETS); break;    \
-    default: EOQ_SCORES(4, NSETS); break;   \
+    case 1: EOQ_SCORES(1, NQ); break;    \
+    case 2: EOQ_SCORES(2, NQ); break;    \
+    case 3: EOQ_SCORES(3, NQ); break;    \
+    default: EOQ_SCORES(4, NQ); break;   \
   }
   if (group <= 4) {
-    EOQ_SCORES_BITS(1)
-  } else {
     EOQ_SCORES_BITS(2)
+  } else {
+    EOQ_SCORES_BITS(4)
   }
 #undef EOQ_SCORES_BITS
 #undef EOQ_SCORES

@@ -335,27 +335,41 @@ def test_decompress_saturates_at_the_largest_binary16():
     assert np.array_equal(x[1], np.full((n, 128), 0.75))
 
 
-def test_scores_of_oracle_records():
-    """Config-5 layout in small: 2 sequences x 2 KV heads x 3 blocks, 4 query heads per KV head."""
-    n_seq, n_kv, bph, group = 2, 2, 3, 4
-    spec = synth.BlockSpec("keys", n=512, n_tensors=n_seq * n_kv, blocks_per_tensor=bph, rank_lo=2, rank_hi=8)
+@pytest.mark.parametrize("bits,group,n,high_rank", [(2, 4, 512, False), (1, 1, 256, False), (3, 3, 128, False),
+                                                     (4, 8, 256, False), (2, 8, 512, True), (3, 4, 256, True)])
+def test_scores_of_oracle_records(bits, group, n, high_rank):
+    """Config-5 layout in small: 2 sequences x 2 KV heads x 3 blocks, `group` query heads per KV head, at every code
+    width, for groups on both sides of 4 (a lane finishes two or four heads per token) and at ranks on both sides of
+    16 (the low-rank term takes a second matrix instruction there)."""
+    n_seq, n_kv, bph = 2, 2, 3
+    spec = synth.BlockSpec("keys", n=n, n_tensors=n_seq * n_kv, blocks_per_tensor=bph, rank_lo=2, rank_hi=8)
     blocks, _ = synth.make_blocks(spec, seed=123)
-    Pi, cb = U.oracle_tables(2)
-    recs = U.oracle_compress(blocks.double().numpy(), 2)
-    ctx = eoq.Context(n=512, bits=2)
+    Pi, cb = U.oracle_tables(bits)
+    recs = U.oracle_compress(blocks.double().numpy(), bits)
+    if high_rank:
+        # Alg. 2 does not return such ranks on these blocks, and scoring only reads the record: stored factors of ranks
+        # 0 .. 32 (binary16 values), every third block above 16
+        rng = np.random.default_rng(11)
+        for b, r in enumerate(recs):
+            r.rank = (0, 5, 17, 16, 32, 9, 24)[b % 7]
+            r.lfac = rng.standard_normal((r.rank, n)).astype(np.float16).astype(np.float64)
+            r.rfac = (rng.standard_normal((r.rank, 128)) / 11.3).astype(np.float16).astype(np.float64)
+            r.phi = np.ones(r.rank)
+            r.sigma = np.ones(r.rank)
+    ctx = eoq.Context(n=n, bits=bits)
     packed = U.records_to_packed(recs, 32, DEV)
     q = synth.make_queries(n_seq, n_kv * group)
     sg = ctx.eoq_scores(packed, q.to(DEV), n_kv_heads=n_kv)
     torch.cuda.synchronize()
     sg = sg.cpu().numpy().astype(np.float64)
-    assert sg.shape == (n_seq, n_kv * group, bph * 512)
+    assert sg.shape == (n_seq, n_kv * group, bph * n)
     q64 = q.double().numpy()
     for s in range(n_seq):
         for g in range(n_kv):
             for j in range(bph):
                 r = recs[(s * n_kv + g) * bph + j]
                 so = oracle.score_block(q64[s, g * group:(g + 1) * group], r, Pi, cb)
-                got = sg[s, g * group:(g + 1) * group, j * 512:(j + 1) * 512]
+                got = sg[s, g * group:(g + 1) * group, j * n:(j + 1) * n]
                 assert np.max(np.abs(got - so)) <= 1e-5 * max(1.0, np.max(np.abs(so))), (s, g, j)
 
 
@@ -930,10 +944,11 @@ def test_qjl_side_information_of_oracle_records(n, bits, B, rank_hi):
     U.log_stats(f"qjl-n{n}-b{bits}", dict(sign_mismatches=bad, sign_bits=total))
 
 
-def test_scores_prod_of_oracle_records():
+@pytest.mark.parametrize("bits,group,n", [(2, 4, 256), (3, 8, 128), (1, 2, 256)])
+def test_scores_prod_of_oracle_records(bits, group, n):
     """eoq_scores_prod fed with oracle records and oracle side information against Eq. (qjl) written out in the
     oracle; the same call without correction equals eoq_scores."""
-    n_seq, n_kv, bph, group, n, bits = 2, 2, 3, 4, 256, 2
+    n_seq, n_kv, bph = 2, 2, 3
     spec = synth.BlockSpec("pkeys", n=n, n_tensors=n_seq * n_kv, blocks_per_tensor=bph, rank_lo=1, rank_hi=6)
     blocks, _ = synth.make_blocks(spec, seed=31)
     b64 = blocks.double().numpy()
