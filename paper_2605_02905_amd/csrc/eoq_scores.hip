@@ -164,7 +164,8 @@ __global__ __launch_bounds__(THREADS, (BITS <= 2 && !QJL) ? 4 : 1) void eoq_scor
   // ([head][plane][k]) and of Phi q; in the tile loop the four waves' coefficient tiles.  The barrier behind the w
   // table separates the two uses.
   constexpr int SETUP_BYTES = 2 * SC_MAXG * D * 4 + SC_MAXG * 4 * TYPES * D + (QJL ? SC_MAXG * 4 * D : 0);
-  constexpr int LOOP_BYTES = 4 * 2 * 16 * CTLD * 2;
+  constexpr int CS_BYTES = 4 * 2 * 16 * CTLD * 2;            // the four waves' coefficient tiles
+  constexpr int LOOP_BYTES = CS_BYTES + SC_RUN_MAX * 32 * 16;   // and the run's low-rank operands
   __shared__ __align__(16) unsigned char pool[SETUP_BYTES > LOOP_BYTES ? SETUP_BYTES : LOOP_BYTES];
   float* qraw = reinterpret_cast<float*>(pool);
   float* qrot = qraw + SC_MAXG * D;
@@ -271,22 +272,39 @@ __global__ __launch_bounds__(THREADS, (BITS <= 2 && !QJL) ? 4 : 1) void eoq_scor
     if (seg == 0 && b < nblk && i < rb) wbuf[(b * EOQ_RMAX_CAP + i) * WH + h] = acc * inv_sqrt_d;
   }
   __syncthreads();
+  // A operands of the low-rank product, components 0 .. 15, for every block of the run: row 8 qq + 4 f of the matrix
+  // instruction holds binary16(w) of head 2 qq + f, the row after it what that rounding lost, the other two rows are
+  // zero and not stored.  Entry (b, ci): lane half ci / 16 (components 8 hf + e), row group (ci / 2) % 8, part ci % 2.
+  uint4* wop = reinterpret_cast<uint4*>(pool + CS_BYTES);
+  for (int e = tid; e < nblk * 32; e += THREADS) {
+    const int b = e >> 5, ci = e & 31;
+    const int ohf = ci >> 4, l4 = (ci >> 1) & 7, part = ci & 1;
+    const int h = 2 * (l4 >> 1) + (l4 & 1), rb = rank_s[b];
+    H8 x;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int i = 8 * ohf + k;
+      const float w = (i < rb && h < WH) ? wbuf[(b * EOQ_RMAX_CAP + i) * WH + (h & (WH - 1))] : 0.0f;
+      const uint16_t hi = float_to_half_bits(w);
+      x.s[k] = part == 0 ? hi : float_to_half_bits(w - half_bits_to_float(hi));
+    }
+    wop[e] = x.u;
+  }
+  __syncthreads();
   if (wave >= NT) return;
 
   // Buffer addressing: a resource descriptor in scalar registers, a scalar byte offset that moves from tile to tile and
-  // a per-lane 32-bit offset that never changes -- no vector arithmetic per load.  The descriptors of the codes and
-  // norms cover the run (reads past it return zero); the coefficients get a descriptor per block that ends behind row
-  // rank - 1, and the range check covers the per-lane part of the offset, which holds the row: rows at and above the
-  // rank read zero.
-  const __amdgpu_buffer_rsrc_t bcodes = buffer_of(codes + blk0 * (size_t)n * ROWB, (size_t)nblk * n * ROWB);
-  const __amdgpu_buffer_rsrc_t bnorms = buffer_of(norms + blk0 * (size_t)n, (size_t)nblk * n * 2);
-  __amdgpu_buffer_rsrc_t bsigns = bcodes, bgam = bnorms;
-  if constexpr (QJL) {
-    bsigns = buffer_of(qsigns + blk0 * (size_t)n * (D / 8), (size_t)nblk * n * (D / 8));
-    bgam = buffer_of(qnorms + blk0 * (size_t)n, (size_t)nblk * n * 2);
-  }
+  // a per-lane 32-bit offset that never changes -- no vector arithmetic per load.  The coefficients get a descriptor per
+  // block that ends behind row rank - 1, and the range check covers the per-lane part of the offset, which holds the
+  // row: rows at and above the rank read zero.  A request or a store for a tile behind the wave's last one goes through
+  // descriptors of size zero (nothing is read or written), so every pass of the loop below issues the same memory
+  // instructions and a wait can name exactly the loads it needs.
+  const uint8_t* codes0 = codes + blk0 * (size_t)n * ROWB;
+  const uint16_t* norms0 = norms + blk0 * (size_t)n;
+  const uint8_t* qsigns0 = QJL ? qsigns + blk0 * (size_t)n * (D / 8) : nullptr;
+  const uint16_t* qnorms0 = QJL ? qnorms + blk0 * (size_t)n : nullptr;
   // score rows of this (sequence, KV head): row h at h T floats; lane (token, hf) stores head 2 qq + hf
-  const __amdgpu_buffer_rsrc_t bout = buffer_of(scores + (sq * n_q_heads + kv * group) * T, (size_t)group * T * 4);
+  float* scores0 = scores + (sq * n_q_heads + kv * group) * T;
   const uint32_t vo_code = (uint32_t)(l32 * ROWB + 8 * hf);
   const uint32_t vo_sign = (uint32_t)(l32 * (D / 8) + 8 * hf);
   const uint32_t vo_norm = (uint32_t)(2 * l32);
@@ -294,27 +312,37 @@ __global__ __launch_bounds__(THREADS, (BITS <= 2 && !QJL) ? 4 : 1) void eoq_scor
   const uint32_t vo_out = (uint32_t)((hf * T + l32) * 4);
   uint16_t* cs = reinterpret_cast<uint16_t*>(pool) + wave * (2 * 16 * CTLD);
 
+  // The scalar unit is shared by the whole compute unit, so what a tile costs in scalar instructions counts: the
+  // descriptors of the run are built once, a tile is addressed by its first token counted from the start of the run
+  // (the wave's tiles are 128 tokens apart, also across a block boundary), the ranks of the run's blocks sit in the
+  // lanes of one register, and the descriptor of a block's coefficients is rebuilt only when the block changes.
+  const __amdgpu_buffer_rsrc_t bcodes = buffer_of(codes0, (size_t)nblk * n * ROWB);
+  const __amdgpu_buffer_rsrc_t bnorms = buffer_of(norms0, (size_t)nblk * n * 2);
+  const __amdgpu_buffer_rsrc_t bsigns = buffer_of(qsigns0, QJL ? (size_t)nblk * n * (D / 8) : 0);
+  const __amdgpu_buffer_rsrc_t bgam = buffer_of(qnorms0, QJL ? (size_t)nblk * n * 2 : 0);
+  const __amdgpu_buffer_rsrc_t bout = buffer_of(scores0 + (size_t)jb0 * n, ((size_t)group * T - (size_t)jb0 * n) * 4);
+  const __amdgpu_buffer_rsrc_t bnone = buffer_of(scores0, 0);
+  const int rk_all = rank_s[min(lane, nblk - 1)];
+  auto rank_of = [&](int b) __attribute__((always_inline)) { return __builtin_amdgcn_readlane(rk_all, b); };
   auto coef_buffer = [&](int b) __attribute__((always_inline)) {
-    return buffer_of(lfac + (blk0 + b) * (size_t)r_max * n, (size_t)rank_s[b] * n * 2);
+    return buffer_of(lfac + (blk0 + b) * (size_t)r_max * n, (size_t)rank_of(b) * n * 2);
   };
-  // tile u < NT: block u / tpb of the run, tokens 32 (u % tpb) ..
-  auto request = [&](TileFetch<BITS, QJL>& f, int u) __attribute__((always_inline)) {
-    const int b = u / tpb, c = u - b * tpb;
-    const int tokb = b * n + 32 * c;   // uniform: first token of the tile, counted from the start of the run
+  // the tile whose first token is number tok of the run, in block b (first token b n), coefficients through cfd
+  auto request = [&](TileFetch<BITS, QJL>& f, int tok, int b, __amdgpu_buffer_rsrc_t cfd) __attribute__((always_inline)) {
 #pragma unroll
-    for (int p = 0; p < BITS; ++p) f.pl[p] = __builtin_amdgcn_raw_buffer_load_b64(bcodes, vo_code + 16 * p, tokb * ROWB, 0);
-    f.rho = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bnorms, vo_norm, tokb * 2, 0);
-    f.cf = __builtin_amdgcn_raw_buffer_load_b128(coef_buffer(b), vo_cf, 32 * c * 2, 0);
+    for (int p = 0; p < BITS; ++p) f.pl[p] = __builtin_amdgcn_raw_buffer_load_b64(bcodes, vo_code + 16 * p, tok * ROWB, 0);
+    f.rho = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bnorms, vo_norm, tok * 2, 0);
+    f.cf = __builtin_amdgcn_raw_buffer_load_b128(cfd, vo_cf, (tok - b * n) * 2, 0);
     if constexpr (QJL) {
-      f.sg[0] = __builtin_amdgcn_raw_buffer_load_b64(bsigns, vo_sign, tokb * (D / 8), 0);
-      f.gam[0] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bgam, vo_norm, tokb * 2, 0);
+      f.sg[0] = __builtin_amdgcn_raw_buffer_load_b64(bsigns, vo_sign, tok * (D / 8), 0);
+      f.gam[0] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bgam, vo_norm, tok * 2, 0);
     }
   };
   // A operand of the low-rank product for block b of the run, components 16 k2 + 8 hf + e: row 8 qq + 4 f of the matrix
   // instruction holds binary16(w) of head 2 qq + f, the row after it what that rounding lost, the other two rows zero
   auto w_operand = [&](int b, int k2) __attribute__((always_inline)) {
     const int h = 2 * (l32 >> 3) + ((l32 >> 2) & 1), part = l32 & 3;
-    const int rb = rank_s[b];
+    const int rb = rank_of(b);
     H8 x;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -339,11 +367,9 @@ __global__ __launch_bounds__(THREADS, (BITS <= 2 && !QJL) ? 4 : 1) void eoq_scor
   int wb = -1;   // block of the run whose w operand the wave holds
   H8 Aw;
   Aw.u = make_uint4(0u, 0u, 0u, 0u);
-  auto work = [&](TileFetch<BITS, QJL>& cur, int u) __attribute__((always_inline)) {
-    const int b = u / tpb, c = u - b * tpb;
-    const int r = rank_s[b];
+  auto work = [&](TileFetch<BITS, QJL>& cur, int tok, int b, int r, bool valid) __attribute__((always_inline)) {
     if (b != wb) {   // uniform
-      Aw = w_operand(b, 0);
+      Aw.u = ((l32 & 3) < 2) ? wop[b * 32 + 16 * hf + 2 * (l32 >> 2) + (l32 & 1)] : make_uint4(0u, 0u, 0u, 0u);
       wb = b;
     }
     // ---- the integer term: the lane's 64 coordinates, byte kk of every plane at a time ----
@@ -435,7 +461,7 @@ __global__ __launch_bounds__(THREADS, (BITS <= 2 && !QJL) ? 4 : 1) void eoq_scor
       lr = __builtin_amdgcn_mfma_f32_32x32x16_f16(Aw.h, c_operand(0).h, lr, 0, 0, 0);
       if (r > 16) {
         // components 16 .. 31 (rare): fetched and prepared here, nothing of them is kept
-        const u32x4 c2 = __builtin_amdgcn_raw_buffer_load_b128(coef_buffer(b), vo_cf + (uint32_t)(16 * n * 2), 32 * c * 2, 0);
+        const u32x4 c2 = __builtin_amdgcn_raw_buffer_load_b128(coef_buffer(b), vo_cf + (uint32_t)(16 * n * 2), (tok - b * n) * 2, 0);
         *reinterpret_cast<u32x4*>(cs + (16 + (lane >> 2)) * CTLD + (lane & 3) * 8) = c2;
         __builtin_amdgcn_wave_barrier();
         lr = __builtin_amdgcn_mfma_f32_32x32x16_f16(w_operand(b, 1).h, c_operand(1).h, lr, 0, 0, 0);
@@ -444,27 +470,52 @@ __global__ __launch_bounds__(THREADS, (BITS <= 2 && !QJL) ? 4 : 1) void eoq_scor
 #pragma unroll
       for (int qq = 0; qq < NQ; ++qq) res[qq] += lr[4 * qq] + lr[4 * qq + 1];
     }
-    const int64_t jb = jb0 + b;
+    // head 2 qq + hf of the group: lanes of a head that the group does not have aim behind the descriptor, and a pass
+    // behind the wave's last tile stores through the empty descriptor
+    const __amdgpu_buffer_rsrc_t bo = valid ? bout : bnone;
 #pragma unroll
     for (int qq = 0; qq < NQ; ++qq) {
-      // head 2 qq + hf of the group: lanes of a head that the group does not have aim behind the descriptor
       const bool live = 2 * qq + hf < group;
-      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(res[qq]), bout, live ? vo_out : 0xFFFFFFF0u,
-                                            (int)((2 * qq * T + (size_t)jb * n + 32 * c) * 4), 0);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(res[qq]), bo, live ? vo_out : 0xFFFFFFF0u,
+                                            (int)((2 * qq * T + tok) * 4), 0);
     }
   };
 
-  // two register sets in turn: the next tile is requested before this one is worked on
-  TileFetch<BITS, QJL> fa, fb;
-  request(fa, wave);
-  for (int u0 = wave; u0 < NT; u0 += 8) {
-    if (u0 + 4 < NT) request(fb, u0 + 4);
-    work(fa, u0);
-    if (u0 + 4 < NT) {
-      if (u0 + 8 < NT) request(fa, u0 + 8);
-      work(fb, u0 + 4);
-    }
+  // Two register sets in turn: the next tile is on its way while this one is worked on.  The loop body has no branch
+  // around a memory instruction (a wait can then name exactly the loads it needs): behind the wave's last tile a
+  // request fetches that tile once more and a pass stores nothing.
+  TileFetch<BITS, QJL> f0, f1;
+  const int count = (NT - wave + 3) / 4;        // tiles of this wave: wave, wave + 4, ...
+  const int tok_last = 32 * (wave + 4 * (count - 1));
+  int tok_r = 32 * wave, b_r = 0, end_r = n;                  // next tile to request: first token, block, end of the block
+  int tok_w = 32 * wave, b_w = 0, end_w = n, r_w = rank_of(0), nwk = 0;   // next tile to work on
+  __amdgpu_buffer_rsrc_t cfd = coef_buffer(0);
+#define EOQ_SC_REQUEST(F)                    \
+  if (tok_r >= end_r) {                      \
+    ++b_r;                                   \
+    end_r += n;                              \
+    cfd = coef_buffer(b_r);                  \
+  }                                          \
+  request(F, tok_r, b_r, cfd);               \
+  tok_r = min(tok_r + 128, tok_last);
+#define EOQ_SC_WORK(F)                       \
+  if (tok_w >= end_w) {                      \
+    ++b_w;                                   \
+    end_w += n;                              \
+    r_w = rank_of(b_w);                      \
+  }                                          \
+  work(F, tok_w, b_w, r_w, nwk < count);     \
+  tok_w = min(tok_w + 128, tok_last);        \
+  ++nwk;
+  EOQ_SC_REQUEST(f0)
+  for (int it = 0; it < (count + 1) / 2; ++it) {
+    EOQ_SC_REQUEST(f1)
+    EOQ_SC_WORK(f0)
+    EOQ_SC_REQUEST(f0)
+    EOQ_SC_WORK(f1)
   }
+#undef EOQ_SC_REQUEST
+#undef EOQ_SC_WORK
 }
 
 // Scores of the uncompressed tail (the newest tokens of every head, binary16, not yet a full block):
