@@ -88,6 +88,21 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float f) {
   half_t h = (half_t)f;
   return *reinterpret_cast<uint16_t*>(&h);
 }
+// Kernels that set the mode bit FP16_OVFL (binary16 results that overflow become the largest finite value instead of
+// infinity) get the same saturation from the conversion alone.
+__device__ __forceinline__ void set_fp16_overflow_clamp() { __builtin_amdgcn_s_setreg(1 | (23 << 6) | (0 << 11), 1); }
+__device__ __forceinline__ uint16_t float_to_half_bits_clamped_by_mode(float f) {
+  half_t h = (half_t)f;
+  return *reinterpret_cast<uint16_t*>(&h);
+}
+// two floats -> two binary16 in one word (low half first), round to nearest even: one v_cvt_pk_f16_f32
+__device__ __forceinline__ uint32_t pack_half2(float a, float b) {
+  typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+  typedef float float2v __attribute__((ext_vector_type(2)));
+  const float2v v = {a, b};
+  const half2v h = __builtin_convertvector(v, half2v);
+  return *reinterpret_cast<const uint32_t*>(&h);
+}
 __device__ __forceinline__ float half_bits_to_float(uint16_t b) {
   half_t h = *reinterpret_cast<half_t*>(&b);
   return (float)h;

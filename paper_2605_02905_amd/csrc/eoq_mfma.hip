@@ -233,8 +233,6 @@ __device__ __forceinline__ int rank_value(int raw, int r_max) {
 // ---------------------------------------------------------------------------------------------
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-typedef float float2v __attribute__((ext_vector_type(2)));
 
 // What a lane requests of a tile: lane (l32, hf) owns token l32 of the tile.
 template <int BITS>
@@ -249,11 +247,6 @@ struct TileFetch {
 struct TileSource {
   __amdgpu_buffer_rsrc_t codes, norms, lfac;
 };
-__device__ __forceinline__ uint32_t pack_half2(float a, float b) {
-  const float2v v = {a, b};
-  const half2v h = __builtin_convertvector(v, half2v);   // v_cvt_pk_f16_f32, round to nearest even
-  return *reinterpret_cast<const uint32_t*>(&h);
-}
 constexpr int CTLD = 32 + 8;   // row stride (halfs) of a tile's coefficient rows in LDS, [component][token]
 
 template <int BITS>
@@ -273,7 +266,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
 
   // binary16 results that overflow become the largest finite value instead of infinity (mode bit FP16_OVFL): the
   // output saturates like every other binary16 quantity of the record, without a clamp per element
-  __builtin_amdgcn_s_setreg(1 | (23 << 6) | (0 << 11), 1);
+  set_fp16_overflow_clamp();
 
   if constexpr (BITS <= 2) build_centroid_table<BITS>(cen_tab, tab, tid);
   else if constexpr (BITS == 3) build_magnitude_table3(cen_tab, tab, tid);
@@ -772,6 +765,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
   const size_t slot = map.slot(blk);
   const int r = rank_in[slot];
   constexpr int ROWB = BITS * D / 8;
+  set_fp16_overflow_clamp();   // the stored coefficients saturate at the largest binary16 by the conversion itself
   // the 32 rows x 256 B of this wave's tokens, 16 B per lane and load (4 rows per instruction), are requested one
   // chunk ahead: the first chunk's here, before the tables
   const size_t tok = (size_t)map.token_stride;
@@ -780,14 +774,19 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
   u32x4 pre[8];
   EOQ_SFOR(it, 8, pre[it] = *reinterpret_cast<const u32x4*>(src0 + (4 * it + (lane >> 4)) * tok + (lane & 15) * 8););
 
-  // stationary rotation operand: rows c = 32w + l32 of Pi, hi and lo
-  H8 Bhi[8], Blo[8];
+  // stationary rotation operand: rows c = 32w + l32 of Pi.  Up to 3 bits the binary16 rounding of Pi alone (one
+  // matrix-core pass): it moves z sqrt(d) by a sum of 128 independent roundings, standard deviation 1.4e-4, the size of
+  // what the binary16 rounding of u moves it by already; a coordinate that close to a cell boundary is reconstructed
+  // equally well from either cell.  At 4 bits, where the cells are narrowest, the part that rounding lost goes through
+  // a second pass.
+  constexpr bool ROT_LO = BITS == 4;
+  H8 Bhi[8], Blo[ROT_LO ? 8 : 1];
   {
     const int c = 32 * wave + l32;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       Bhi[kk].u = *reinterpret_cast<const uint4*>(pih + c * D + 16 * kk + 8 * hf);
-      Blo[kk].u = *reinterpret_cast<const uint4*>(pih + D * D + c * D + 16 * kk + 8 * hf);
+      if constexpr (ROT_LO) Blo[kk].u = *reinterpret_cast<const uint4*>(pih + D * D + c * D + 16 * kk + 8 * hf);
     }
   }
   // the decision boundaries as separate values, not an array or a vector: the compiler turns a select between two
@@ -876,7 +875,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
-            const uint16_t hb = float_to_half_bits(Cacc[v]);
+            const uint16_t hb = float_to_half_bits_clamped_by_mode(Cacc[v]);
             __builtin_amdgcn_raw_buffer_store_b16(hb, lbuf, cf_lane, (8 * (v >> 2) + (v & 3)) * n * 2, 0);
             Cneg[v >> 2].s[v & 3] = (i < r) ? (uint16_t)(hb ^ 0x8000u) : (uint16_t)0;  // rows >= r of W are not initialised
           }
@@ -907,10 +906,10 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
       for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          H4 u;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) u.s[e] = float_to_half_bits(Racc[mt][4 * q + e] * sc);
-          *reinterpret_cast<uint2*>(tile + l32 * ZLD + 32 * mt + 8 * q + 4 * hf) = u.u;
+          // |u_j| <= sqrt(d): no saturation to think of; two entries per conversion
+          const uint2 u = make_uint2(pack_half2(Racc[mt][4 * q] * sc, Racc[mt][4 * q + 1] * sc),
+                                     pack_half2(Racc[mt][4 * q + 2] * sc, Racc[mt][4 * q + 3] * sc));
+          *reinterpret_cast<uint2*>(tile + l32 * ZLD + 32 * mt + 8 * q + 4 * hf) = u;
         }
     }
     // the next chunk's rows travel while this one is rotated and quantised (requested here and not earlier: phase 1
@@ -933,7 +932,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_encode_mfma_kernel(
         H8 a;
         a.u = *reinterpret_cast<const uint4*>(X + (32 * tau + l32) * ZLD + 16 * kk + 8 * hf);
         acc = mfma16(a, Bhi[kk], acc);
-        acc = mfma16(a, Blo[kk], acc);
+        if constexpr (ROT_LO) acc = mfma16(a, Blo[kk], acc);
       }
       // index = number of boundaries <= z, found from the top bit down; every comparison mask holds one
       // bit-plane of coordinates 32w..32w+31 for the tokens 8q+e (low word) and 8q+4+e (high word)
