@@ -340,7 +340,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
   int64_t blk = u >> parts_log2;
   int part = (int)u & part_mask;
   int r = rank_value(rank_request(ranks, blk), r_max);
-  int rk_next = rank_request(ranks, (u + GW < U) ? ((u + GW) >> parts_log2) : B);   // past the end: reads zero
+  int rk_next = rank_request(ranks, min((u + GW) >> parts_log2, B - 1));   // behind the last unit: not used
   TileSource src = source_of(blk, r, true);
   TileFetch<BITS> cur, nxt;
   request(cur, src, 32 * part * tiles_per_unit);
@@ -385,7 +385,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_decode_mfma_kernel(
       blk_n = more ? (un >> parts_log2) : blk;
       part_n = (int)un & part_mask;
       r_n = rank_value(rk_next, r_max);
-      rk_next = rank_request(ranks, (un + GW < U) ? ((un + GW) >> parts_log2) : B);
+      rk_next = rank_request(ranks, min((un + GW) >> parts_log2, B - 1));
       src = source_of(blk_n, r_n, more);
       t_n = 32 * part_n * tiles_per_unit;
     }
