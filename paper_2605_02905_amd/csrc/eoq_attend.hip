@@ -19,8 +19,12 @@ constexpr int THREADS = 256;
 constexpr int MAXG = 8;      // query heads per KV head
 constexpr int CHUNK = 128;   // tokens staged per pass (n is a multiple of 128)
 
-// One workgroup: blocks [blockIdx.x * run, ...) of (sequence, KV head) blockIdx.y.  Lane (c, th) = (tid % 128,
-// tid / 128) owns coordinate c and the tokens of parity-half th of every chunk.
+// One workgroup: blocks [blockIdx.x * run, ...) of (sequence, KV head) blockIdx.y.
+// Codebook term: lane (cg, tg) = (tid % 32, tid / 32) owns the four coordinates 4 cg .. 4 cg + 3 and the tokens tg,
+// tg + 8, ... of every chunk.  Per token it reads one byte of every bit-plane, and for codes of up to 2 bits one entry
+// of a 256-entry table indexed by (nibble of plane 0 | nibble of plane 1 << 4) gives the four centroids at once; the
+// weights of the token's heads are one or two 16-byte reads shared by the whole token group; 4 x GH multiply-adds.
+// Low-rank term: lane (c, th) = (tid % 128, tid / 128) owns output coordinate c.
 // GH: heads accumulated per lane (4 when the group has at most four query heads: half the multiply-adds and LDS reads).
 template <int BITS, int GH>
 __global__ __launch_bounds__(THREADS) void eoq_attend_partial_kernel(
@@ -29,126 +33,230 @@ __global__ __launch_bounds__(THREADS) void eoq_attend_partial_kernel(
     const int32_t* __restrict__ rank_in, const uint16_t* __restrict__ lfac, const uint16_t* __restrict__ rfac,
     const float* __restrict__ weights, float* __restrict__ partial) {
   constexpr int ROWB = BITS * D / 8;
-  __shared__ __align__(16) uint8_t code_s[CHUNK * ROWB];
-  __shared__ __align__(16) float wr_s[CHUNK * MAXG];     // [t][h]: w_ht rho_t / sqrt(d)
-  __shared__ __align__(16) float w_s[MAXG * CHUNK];      // [h][t]: w_ht
-  __shared__ __align__(16) uint16_t cf_s[EOQ_RMAX_CAP * CHUNK];   // [i][t]: stored coefficients C_ti of the chunk
+  // staging of a chunk; after the last chunk the same memory takes the four waves' sums of the codebook term
+  constexpr int STAGE_BYTES = CHUNK * ROWB + 2 * CHUNK * MAXG * 4 + EOQ_RMAX_CAP * CHUNK * 2;
+  constexpr int FOLD_BYTES = 4 * GH * D * 4;
+  __shared__ __align__(16) uint8_t stage_s[STAGE_BYTES > FOLD_BYTES ? STAGE_BYTES : FOLD_BYTES];
+  uint8_t* code_s = stage_s;
+  float* wr_s = reinterpret_cast<float*>(stage_s + CHUNK * ROWB);                        // [t][h]: w_ht rho_t / sqrt(d)
+  float* w_s = wr_s + CHUNK * MAXG;                                                      // [h][t]: w_ht
+  uint16_t* cf_s = reinterpret_cast<uint16_t*>(w_s + MAXG * CHUNK);                      // [i][t]: stored coefficients C_ti of the chunk
+  float* fold4_s = reinterpret_cast<float*>(stage_s);                                    // [wave][h][c]
+  __shared__ __align__(16) float4 cen4_s[BITS <= 2 ? 256 : 1];
   __shared__ float cent_s[1 << BITS];
-  __shared__ float bsum_s[MAXG * EOQ_RMAX_CAP];          // [h][i]: sum_t w_ht C_ti of the current block
-  __shared__ float fold_s[2 * MAXG * D];
+  __shared__ float bsum_s[4 * MAXG * EOQ_RMAX_CAP];      // [token segment][h][i]: sum_t w_ht C_ti of the current block
+  __shared__ float fold_s[MAXG * D];
 
   const int tid = threadIdx.x;
   const int c = tid & (D - 1), th = tid >> 7;
+  const int cg = tid & 31, tg = tid >> 5;
   const size_t sg = blockIdx.y;
   const size_t sq = sg / n_kv_heads, kv = sg % n_kv_heads;
   const int n_q_heads = n_kv_heads * group;
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   if (tid < (1 << BITS)) cent_s[tid] = tab[tid];
-
-  float rot[GH], lin[GH];
+  if constexpr (BITS <= 2) {
+    const int n0 = tid & 15, n1 = tid >> 4;
+    float cv[4];
 #pragma unroll
-  for (int h = 0; h < GH; ++h) rot[h] = lin[h] = 0.0f;
+    for (int e = 0; e < 4; ++e) cv[e] = tab[((n0 >> e) & 1) | ((BITS == 2) ? (((n1 >> e) & 1) << 1) : 0)];
+    cen4_s[tid] = make_float4(cv[0], cv[1], cv[2], cv[3]);
+  }
 
-  const int64_t j_end = min((int64_t)(blockIdx.x + 1) * run, blocks_per_head);
-  for (int64_t jb = (int64_t)blockIdx.x * run; jb < j_end; ++jb) {
+  float rot[GH][4], lin[GH];
+#pragma unroll
+  for (int h = 0; h < GH; ++h) {
+    lin[h] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) rot[h][e] = 0.0f;
+  }
+
+  // What a lane fetches of a chunk of 128 tokens; the next chunk's (of this block or the next) is requested before
+  // this one is worked on, so the loads travel during the arithmetic instead of in front of a barrier.
+  constexpr int NC = (CHUNK * ROWB / 16 + THREADS - 1) / THREADS;   // 16-byte pieces of the codes per lane
+  struct Fetch {
+    uint4 code[NC];
+    float w[4];      // weights of heads th, 2 + th, 4 + th, 6 + th at token tid % 128
+    uint16_t rho;    // stored norm of that token
+    uint4 cf[2];     // stored coefficients: piece tid + 256 k of the chunk's [component][token] rows
+  };
+  __shared__ int rank_s[16];
+  const int64_t j_begin = (int64_t)blockIdx.x * run;
+  const int64_t j_end = min(j_begin + run, blocks_per_head);
+  if (tid < (int)(j_end - j_begin)) rank_s[tid] = min(max(rank_in[sg * (size_t)block_capacity + j_begin + tid], 0), r_max);
+  __syncthreads();
+  auto fetch = [&](Fetch& f, int64_t jb, int t0) __attribute__((always_inline)) {
     const size_t blk = sg * (size_t)block_capacity + jb;
-    const int r = min(max(rank_in[blk], 0), r_max);
-    // low-rank weights of this block: lane (i, h) = (tid / 8, tid % 8)
-    const int bi = tid >> 3, bh = tid & 7;
-    float bacc = 0.0f;
+    const int r = rank_s[jb - j_begin];
+#pragma unroll
+    for (int k = 0; k < NC; ++k) {
+      const int e = tid + THREADS * k;
+      f.code[k] = (e < CHUNK * ROWB / 16) ? reinterpret_cast<const uint4*>(codes + (blk * (size_t)n + t0) * ROWB)[e] : make_uint4(0u, 0u, 0u, 0u);
+    }
+    const int t = tid & (CHUNK - 1);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int h = 2 * k + th;
+      f.w[k] = (h < group) ? weights[(sq * n_q_heads + kv * group + h) * (size_t)weight_stride + (size_t)jb * n + t0 + t] : 0.0f;
+    }
+    f.rho = norms[blk * (size_t)n + t0 + t];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int e = tid + THREADS * k, i = e >> 4;
+      f.cf[k] = (i < r) ? *reinterpret_cast<const uint4*>(lfac + (blk * r_max + i) * (size_t)n + t0 + 8 * (e & 15)) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+  Fetch cur, nxt;
+  if (j_begin < j_end) fetch(cur, j_begin, 0);
+  for (int64_t jb = j_begin; jb < j_end; ++jb) {
+    const size_t blk = sg * (size_t)block_capacity + jb;
+    const int r = rank_s[jb - j_begin];
+    // low-rank weights of this block: lane (segment, i, h) = (tid / 64, (tid / 8) % 8, tid % 8) sums the 32 tokens
+    // 32 segment .. of every chunk for the components i, i + 8, ... and head h
+    const int bs = tid >> 6, bi = (tid >> 3) & 7, bh = tid & 7;
+    float bacc[EOQ_RMAX_CAP / 8];
+#pragma unroll
+    for (int g = 0; g < EOQ_RMAX_CAP / 8; ++g) bacc[g] = 0.0f;
     for (int t0 = 0; t0 < n; t0 += CHUNK) {
       __syncthreads();  // the previous chunk has been consumed
-      // stage the chunk: codes, weights, weights times norm
-      for (int e = tid; e < CHUNK * ROWB / 16; e += THREADS)
-        reinterpret_cast<uint4*>(code_s)[e] = reinterpret_cast<const uint4*>(codes + (blk * (size_t)n + t0) * ROWB)[e];
-      for (int e = tid; e < group * CHUNK; e += THREADS) {
-        const int h = e / CHUNK, t = e - h * CHUNK;
-        const float w = weights[(sq * n_q_heads + kv * group + h) * (size_t)weight_stride + (size_t)jb * n + t0 + t];
-        const float rho = half_bits_to_float(norms[blk * (size_t)n + t0 + t]);
-        w_s[h * CHUNK + t] = w;
-        wr_s[t * MAXG + h] = w * rho * inv_sqrt_d;
-      }
-      for (int e = tid; e < r * (CHUNK / 8); e += THREADS) {
-        const int i = e / (CHUNK / 8), seg = e - i * (CHUNK / 8);
-        reinterpret_cast<uint4*>(cf_s)[e] = *reinterpret_cast<const uint4*>(lfac + (blk * r_max + i) * (size_t)n + t0 + 8 * seg);
-      }
-      if (group < MAXG)
-        for (int e = tid; e < (MAXG - group) * CHUNK; e += THREADS) {
-          const int h = group + e / CHUNK, t = e % CHUNK;
-          w_s[h * CHUNK + t] = 0.0f;
-          wr_s[t * MAXG + h] = 0.0f;
-        }
-      __syncthreads();
-      // codebook term: this lane's coordinate, half of the chunk's tokens
-      const int word = (c >> 5) * 4, bit = c & 31;
-#pragma unroll 4
-      for (int t = th * (CHUNK / 2); t < (th + 1) * (CHUNK / 2); ++t) {
-        uint32_t idx = 0;
+      // stage the chunk: codes, weights, weights times norm, coefficients
 #pragma unroll
-        for (int p = 0; p < BITS; ++p) {
-          const uint32_t w32 = *reinterpret_cast<const uint32_t*>(code_s + t * ROWB + p * 16 + word);
-          idx |= ((w32 >> bit) & 1u) << p;
+      for (int k = 0; k < NC; ++k) {
+        const int e = tid + THREADS * k;
+        if (e < CHUNK * ROWB / 16) reinterpret_cast<uint4*>(code_s)[e] = cur.code[k];
+      }
+      {
+        const int t = tid & (CHUNK - 1);
+        const float rs = half_bits_to_float(cur.rho) * inv_sqrt_d;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int h = 2 * k + th;
+          w_s[h * CHUNK + t] = cur.w[k];
+          wr_s[t * MAXG + h] = cur.w[k] * rs;
         }
-        const float cv = cent_s[idx];
+      }
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int e = tid + THREADS * k;
+        if ((e >> 4) < r) reinterpret_cast<uint4*>(cf_s)[e] = cur.cf[k];
+      }
+      // the next chunk's bytes are requested here
+      {
+        const bool last_chunk = t0 + CHUNK >= n;
+        const int64_t jn = last_chunk ? jb + 1 : jb;
+        if (jn < j_end) fetch(nxt, jn, last_chunk ? 0 : t0 + CHUNK);
+      }
+      __syncthreads();
+      // codebook term: this lane's four coordinates, every eighth token of the chunk
+      const int cbyte = cg >> 1, cshift = 4 * (cg & 1);
+#pragma unroll 4
+      for (int t = tg; t < CHUNK; t += 8) {
+        float cv[4];
+        if constexpr (BITS <= 2) {
+          uint32_t idx = ((uint32_t)code_s[t * ROWB + cbyte] >> cshift) & 0xFu;
+          if constexpr (BITS == 2) idx |= (((uint32_t)code_s[t * ROWB + 16 + cbyte] >> cshift) & 0xFu) << 4;
+          const float4 c4 = cen4_s[idx];
+          cv[0] = c4.x; cv[1] = c4.y; cv[2] = c4.z; cv[3] = c4.w;
+        } else {
+          uint32_t nib[BITS];
+#pragma unroll
+          for (int p = 0; p < BITS; ++p) nib[p] = ((uint32_t)code_s[t * ROWB + 16 * p + cbyte] >> cshift) & 0xFu;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            uint32_t idx = 0;
+#pragma unroll
+            for (int p = 0; p < BITS; ++p) idx |= ((nib[p] >> e) & 1u) << p;
+            cv[e] = cent_s[idx];
+          }
+        }
         const float4 wa = *reinterpret_cast<const float4*>(wr_s + t * MAXG);
-        rot[0] = fmaf(wa.x, cv, rot[0]);
-        rot[1] = fmaf(wa.y, cv, rot[1]);
-        rot[2] = fmaf(wa.z, cv, rot[2]);
-        rot[3] = fmaf(wa.w, cv, rot[3]);
+        const float wv[4] = {wa.x, wa.y, wa.z, wa.w};
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) rot[h][e] = fmaf(wv[h], cv[e], rot[h][e]);
         if constexpr (GH == 8) {
           const float4 wb = *reinterpret_cast<const float4*>(wr_s + t * MAXG + 4);
-          rot[4] = fmaf(wb.x, cv, rot[4]);
-          rot[5] = fmaf(wb.y, cv, rot[5]);
-          rot[6] = fmaf(wb.z, cv, rot[6]);
-          rot[7] = fmaf(wb.w, cv, rot[7]);
+          const float wu[4] = {wb.x, wb.y, wb.z, wb.w};
+#pragma unroll
+          for (int h = 0; h < 4; ++h)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) rot[4 + h][e] = fmaf(wu[h], cv[e], rot[4 + h][e]);
         }
       }
-      // low-rank weights: component bi, head bh, 8 tokens per load
-      if (bi < r) {
-        const uint16_t* crow = cf_s + bi * CHUNK;
-#pragma unroll 4
-        for (int t = 0; t < CHUNK; t += 8) {
-          float cf[8];
-          load8(crow, EOQ_F16, t, cf);
-          const float4 wa = *reinterpret_cast<const float4*>(w_s + bh * CHUNK + t);
-          const float4 wb = *reinterpret_cast<const float4*>(w_s + bh * CHUNK + t + 4);
-          bacc = fmaf(wa.x, cf[0], bacc);
-          bacc = fmaf(wa.y, cf[1], bacc);
-          bacc = fmaf(wa.z, cf[2], bacc);
-          bacc = fmaf(wa.w, cf[3], bacc);
-          bacc = fmaf(wb.x, cf[4], bacc);
-          bacc = fmaf(wb.y, cf[5], bacc);
-          bacc = fmaf(wb.z, cf[6], bacc);
-          bacc = fmaf(wb.w, cf[7], bacc);
+      // low-rank weights: components bi + 8 g, head bh, the segment's 32 tokens, 8 per load
+#pragma unroll
+      for (int g = 0; g < EOQ_RMAX_CAP / 8; ++g) {
+        if (8 * g < r) {   // uniform
+          const int i = bi + 8 * g;
+          if (i < r) {
+            const uint16_t* crow = cf_s + i * CHUNK;
+#pragma unroll
+            for (int t = 32 * bs; t < 32 * bs + 32; t += 8) {
+              float cf[8];
+              load8(crow, EOQ_F16, t, cf);
+              const float4 wa = *reinterpret_cast<const float4*>(w_s + bh * CHUNK + t);
+              const float4 wb = *reinterpret_cast<const float4*>(w_s + bh * CHUNK + t + 4);
+              bacc[g] = fmaf(wa.x, cf[0], bacc[g]);
+              bacc[g] = fmaf(wa.y, cf[1], bacc[g]);
+              bacc[g] = fmaf(wa.z, cf[2], bacc[g]);
+              bacc[g] = fmaf(wa.w, cf[3], bacc[g]);
+              bacc[g] = fmaf(wb.x, cf[4], bacc[g]);
+              bacc[g] = fmaf(wb.y, cf[5], bacc[g]);
+              bacc[g] = fmaf(wb.z, cf[6], bacc[g]);
+              bacc[g] = fmaf(wb.w, cf[7], bacc[g]);
+            }
+          }
         }
       }
+      cur = nxt;
     }
     // low-rank term of the block: lin_h[c] += sum_i bsum[h][i] V[i][c]; the two lane halves take alternate components
     __syncthreads();
-    bsum_s[bh * EOQ_RMAX_CAP + bi] = bacc;
+#pragma unroll
+    for (int g = 0; g < EOQ_RMAX_CAP / 8; ++g) bsum_s[(bs * MAXG + bh) * EOQ_RMAX_CAP + bi + 8 * g] = bacc[g];
     __syncthreads();
     for (int i = th; i < r; i += 2) {
       const float v = half_bits_to_float(rfac[(blk * r_max + i) * D + c]);
 #pragma unroll
-      for (int h = 0; h < GH; ++h) lin[h] = fmaf(bsum_s[h * EOQ_RMAX_CAP + i], v, lin[h]);
+      for (int h = 0; h < GH; ++h) {
+        // the four token segments in order
+        const float bsum = ((bsum_s[(0 * MAXG + h) * EOQ_RMAX_CAP + i] + bsum_s[(1 * MAXG + h) * EOQ_RMAX_CAP + i]) +
+                            bsum_s[(2 * MAXG + h) * EOQ_RMAX_CAP + i]) + bsum_s[(3 * MAXG + h) * EOQ_RMAX_CAP + i];
+        lin[h] = fmaf(bsum, v, lin[h]);
+      }
     }
   }
-  // fold the two lane halves and write the partial sums of this run: [rot | lin][h][c]
-  __syncthreads();
+  // The codebook term: the two token groups of a wave meet in registers (lane ^ 32: both get the same sum), the four
+  // waves through LDS, added in wave order.  The low-rank term: the two lane halves through LDS.  Then the partial sums
+  // of this run are written: [rot | lin][h][c].
+  __syncthreads();   // the staging memory is free
+#pragma unroll
+  for (int h = 0; h < GH; ++h)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) rot[h][e] += __shfl_xor(rot[h][e], 32, 64);
+  if ((tid & 32) == 0) {
+#pragma unroll
+    for (int h = 0; h < GH; ++h)
+      *reinterpret_cast<float4*>(fold4_s + ((tid >> 6) * GH + h) * D + 4 * cg) = make_float4(rot[h][0], rot[h][1], rot[h][2], rot[h][3]);
+  }
   if (th == 1) {
 #pragma unroll
-    for (int h = 0; h < GH; ++h) {
-      fold_s[h * D + c] = rot[h];
-      fold_s[(MAXG + h) * D + c] = lin[h];
-    }
+    for (int h = 0; h < GH; ++h) fold_s[h * D + c] = lin[h];
   }
   __syncthreads();
   if (th == 0) {
     float* dst = partial + ((sg * gridDim.x + blockIdx.x) * 2 * MAXG) * D;
 #pragma unroll
     for (int h = 0; h < MAXG; ++h) {   // heads past GH are written as zeros: the finishing kernel sums all eight
-      dst[h * D + c] = (h < GH) ? rot[h < GH ? h : 0] + fold_s[h * D + c] : 0.0f;
-      dst[(MAXG + h) * D + c] = (h < GH) ? lin[h < GH ? h : 0] + fold_s[(MAXG + h) * D + c] : 0.0f;
+      float rsum = 0.0f, lsum = 0.0f;
+      if (h < GH) {
+        const int hh = h < GH ? h : 0;
+        rsum = ((fold4_s[(0 * GH + hh) * D + c] + fold4_s[(1 * GH + hh) * D + c]) + fold4_s[(2 * GH + hh) * D + c]) + fold4_s[(3 * GH + hh) * D + c];
+        lsum = lin[hh] + fold_s[hh * D + c];
+      }
+      dst[h * D + c] = rsum;
+      dst[(MAXG + h) * D + c] = lsum;
     }
   }
 }
