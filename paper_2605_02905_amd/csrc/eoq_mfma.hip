@@ -26,7 +26,6 @@ constexpr int THREADS = 256;
 constexpr int CHUNK = 128;          // tokens per pass of a workgroup: one tile of 32 per wave
 constexpr int ZLD = D + 8;          // row stride (halfs) of the token tiles in LDS: 272 B, conflict-free b128 reads
 constexpr int CLD = EOQ_RMAX_CAP + 8;
-constexpr int OLD = 32 + 8;         // row stride (halfs) of an output tile in LDS: 80 B, 16-byte aligned rows
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));

@@ -390,6 +390,11 @@ def test_argument_errors_on_device():
     q = torch.zeros(1, 6, 128, dtype=torch.float16, device=DEV)
     out = torch.zeros(1, 6, 1024, device=DEV)
     assert L.eoq_scores(ctx._h, rec.c_struct(), 1, 4, 1, q.data_ptr(), 6, out.data_ptr(), None) == eoq.EOQ_ERR_UNSUPPORTED
+    # the score rows of one KV head are addressed with 32-bit offsets: 8 heads x 2^26 floats is past what they reach
+    q8 = torch.zeros(1, 8, 128, dtype=torch.float16, device=DEV)
+    assert L.eoq_scores_stream(ctx._h, rec.c_struct(), 1, 1, 2, 1, None, 0, 0, q8.data_ptr(), 8, out.data_ptr(), 1 << 26,
+                               None) == eoq.EOQ_ERR_UNSUPPORTED
+    assert b"2 GiB" in L.eoq_last_error(ctx._h)
     torch.cuda.synchronize()
 
 
