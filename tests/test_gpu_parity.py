@@ -266,7 +266,7 @@ def test_repeated_singular_values_go_to_the_jacobi_solver():
 
 
 @pytest.mark.parametrize("bits,rank_lo,rank_hi,n", [(2, 2, 8, 512), (3, 2, 8, 512), (1, 1, 6, 256), (4, 2, 8, 256),
-                                                     (2, 17, 24, 512), (3, 9, 20, 128)])
+                                                     (2, 17, 24, 512), (3, 9, 20, 128), (2, 1, 12, 1024)])
 def test_decompress_of_oracle_records_elementwise(bits, rank_lo, rank_hi, n):
     """eoq_decompress fed with records produced by the oracle, element by element, at every code width, at ranks on
     both sides of 16 (the kernel keeps the first sixteen components in registers and fetches the others per tile)
