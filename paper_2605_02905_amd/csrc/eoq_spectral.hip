@@ -306,8 +306,9 @@ constexpr int PAIR_B[28] = {1, 2, 3, 4, 5, 6, 7, 2, 3, 4, 5, 6, 7, 3, 4, 5, 6, 7
 // packed reflector storage: reflector k has entries i = k+1 .. 127
 __device__ __forceinline__ int refl_off(int k) { return k * (D - 1) - (k * (k - 1)) / 2; }
 constexpr int REFL_LEN = (D - 1) * D / 2;  // 8128
-constexpr int GRID_POINTS = 256;           // first localisation: one Sturm count per lane on a uniform grid
-constexpr int MULTISECT_ITERS = 17;        // then trisection, two lanes per eigenvalue: 3^17 * 257 > 2^34.9
+constexpr int GRID_POINTS = 256;           // first localisation: one Sturm count per lane on a grid (cubically spaced)
+constexpr int MULTISECT_ITERS = 17;        // then two lanes per eigenvalue down to the width of 17 trisections of a uniform
+                                           // grid cell, 3^-17 / 257 < 2^-34.9 (plain trisection would take 18 rounds at most)
 constexpr int REFINE_COUNT = 32;           // at most this many eigenvalues go on to full precision (the reduction
                                            // itself is good to ~2^-48), with 256 / 32 = 8 lanes each or more
 constexpr int REFINE_KEEP = 48;            // brackets of the largest eigenvalues kept for that second phase
@@ -798,15 +799,17 @@ __device__ __forceinline__ void sturm_steps4(const double (&t)[8], double x, dou
     p = pn;
   }
 }
-__device__ __forceinline__ void sturm_renorm(double& pm, double& p) {  // |p| into [1/2, 1), same factor on both
+__device__ __forceinline__ int sturm_renorm(double& pm, double& p) {  // |p| into [1/2, 1), same factor on both
   const int e = __builtin_amdgcn_frexp_exp(p);
   p = ldexp(p, -e);
   pm = ldexp(pm, -e);
+  return e;
 }
-__device__ __forceinline__ int sturm_count(sc_double* de, double x) {
+// The count, and the value of the last minor p_{D-1}(x) = det(T - x I) as val * 2^vexp (|val| in [1/2, 1) or zero).
+__device__ __forceinline__ int sturm_count(sc_double* de, double x, double* val = nullptr, int* vexp = nullptr) {
   double pm = 0.0, p = 1.0;  // p_{-2}, p_{-1}
   unsigned m = 0u;           // sign history, newest in bit 0; p_{-1} > 0
-  int cnt = 0;
+  int cnt = 0, esum = 0;
   // operands in groups of four steps (64 bytes), requested two groups ahead: three buffers in rotation
   double t0[8], t1[8], t2[8];
 #pragma unroll
@@ -826,12 +829,17 @@ __device__ __forceinline__ int sturm_count(sc_double* de, double x) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) t1[q] = g[32 + q];
     sturm_steps4(t2, x, pm, p, m);
-    sturm_renorm(pm, p);
+    esum += sturm_renorm(pm, p);
     cnt += __popc((m ^ (m >> 1)) & 0xFFFu);  // bit 12 is the sign that preceded these twelve
   }
   sturm_steps4(t0, x, pm, p, m);  // groups 30 and 31
   sturm_steps4(t1, x, pm, p, m);
   cnt += __popc((m ^ (m >> 1)) & 0xFFu);
+  if (val) {
+    esum += sturm_renorm(pm, p);
+    *val = p;
+    *vexp = esum;
+  }
   return cnt;
 }
 
@@ -1043,36 +1051,90 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     sc_double* sde = reinterpret_cast<sc_double*>(tri_addr);
     const int j = tid >> 1, sub = tid & 1;
     double lo = -0x1.0p-40, hi = 1.0 + 0x1.0p-40;   // G is positive semi-definite; Gershgorin bounds the top by 1
+    // What is known about the two ends: the count there (c_lo <= j < c_hi always: every update below follows the
+    // counts, so the bracket holds eigenvalue j whatever else happens) and, once an end is a point that was evaluated,
+    // the value of det(T - x I) there as f * 2^e, f in float32 (its sign and a few digits are all that is used).
+    // One word per end: e << 8 | count; f = 0 stands for "no value".
+    int ce_lo = 0, ce_hi = D;
+    float f_lo = 0.0f, f_hi = 0.0f;
     {
       // every lane counts at one point of a uniform grid; each eigenvalue then starts from its grid cell
-      int* cnt_s = reinterpret_cast<int*>(atoms);
+      int* ce_s = reinterpret_cast<int*>(atoms);
+      float* gval_s = reinterpret_cast<float*>(&vbuf[0][0]);   // the reduction's buffers are free by now
+      // grid point g at ((g + 1) / 257)^3: most eigenvalues of a block are noise eigenvalues far below the largest
+      // one, so the points crowd towards zero (a cell near the top is 3 / 257 wide, a cell at 0.03 is 0.001 wide)
       const double step = 1.0 / (GRID_POINTS + 1);
-      cnt_s[tid] = sturm_count(sde, (tid + 1) * step);
+      auto grid_x = [&](int g) __attribute__((always_inline)) {
+        const double t = (g + 1) * step;
+        return t * t * t;
+      };
+      double gv;
+      int ge;
+      const int gc = sturm_count(sde, grid_x(tid), &gv, &ge);
+      ce_s[tid] = (ge << 8) | gc;
+      gval_s[tid] = (float)gv;
       __syncthreads();
       int gl = -1, gh = GRID_POINTS;  // counts at these grid points: <= j and > j
 #pragma unroll
       for (int b = 0; b < 8; ++b) {
         const int mid = (gl + gh) >> 1;
-        if (cnt_s[mid] > j) gh = mid; else gl = mid;
+        if ((ce_s[mid] & 0xFF) > j) gh = mid; else gl = mid;
       }
-      if (gl >= 0) lo = (gl + 1) * step;
-      if (gh < GRID_POINTS) hi = (gh + 1) * step;
+      if (gl >= 0) {
+        lo = grid_x(gl);
+        ce_lo = ce_s[gl];
+        f_lo = gval_s[gl];
+      }
+      if (gh < GRID_POINTS) {
+        hi = grid_x(gh);
+        ce_hi = ce_s[gh];
+        f_hi = gval_s[gh];
+      }
     }
+    // Rounds of two points per eigenvalue (one per lane of the pair) until every bracket of the wave is at most
+    // 3^-17 / 257 wide (what 17 trisections of a grid cell give; the second phase counts on it).  A bracket that holds
+    // exactly one eigenvalue and has values of det(T - x I) of opposite signs at its ends puts the two points at
+    // t -+ delta around the secant point t; a hit leaves 2 delta of the width and delta shrinks fourfold for the
+    // next round (the secant point of a smooth function with one root in the bracket is off by a fraction of the
+    // width that is itself proportional to the width); a miss is followed by a round of plain thirds, so two rounds
+    // together always leave at most a third.  Brackets with several eigenvalues are cut in thirds.
+    constexpr double WIDTH_TARGET = 1.0 / (129140163.0 * 257.0);
+    float delta = 0.125f;
+    bool thirds_next = false;
 #pragma unroll 1
-    for (int it = 0; it < MULTISECT_ITERS; ++it) {
-      const double third = (hi - lo) * (1.0 / 3.0);
-      const double x1 = lo + third, x2 = hi - third;
-      const int mine = sturm_count(sde, sub ? x2 : x1);
-      const int other = dpp_mov<0xB1>(mine);
-      const int c1 = sub ? other : mine, c2 = sub ? mine : other;
-      if (c1 > j) {
-        hi = x1;
-      } else if (c2 > j) {
-        lo = x1;
-        hi = x2;
-      } else {
-        lo = x2;
-      }
+    for (int it = 0; it < 2 * MULTISECT_ITERS + 2; ++it) {
+      const double w = hi - lo;
+      if (__ballot(w > WIDTH_TARGET) == 0ull) break;   // wave-uniform
+      // f_lo / (f_lo - f_hi) with the two values brought to one exponent
+      const int ediff = min(max((ce_hi >> 8) - (ce_lo >> 8), -100), 100);
+      const float fh = ldexpf(f_hi, ediff);
+      const float ratio = f_lo * __builtin_amdgcn_rcpf(f_lo - fh);
+      const bool secant = !thirds_next && ((ce_hi - ce_lo) & 0xFF) == 1 && f_lo * fh < 0.0f && ratio > 0.0f && ratio < 1.0f;
+      const float tc = fminf(fmaxf(ratio, 2.0f * delta), 1.0f - 2.0f * delta);
+      const float tsel = secant ? (sub ? tc + delta : tc - delta) : (sub ? (2.0f / 3.0f) : (1.0f / 3.0f));
+      const float toth = secant ? (sub ? tc - delta : tc + delta) : (sub ? (1.0f / 3.0f) : (2.0f / 3.0f));
+      const double xm = fma((double)tsel, w, lo), xo = fma((double)toth, w, lo);   // this lane's point, the partner's
+      double fv;
+      int fe;
+      const int mine = sturm_count(sde, xm, &fv, &fe);
+      const int cem = (fe << 8) | mine;
+      const float fm = (float)fv;
+      const int ceo = dpp_mov<0xB1>(cem);
+      const float fo = dpp_mov<0xB1>(fm);
+      const double x1 = sub ? xo : xm, x2 = sub ? xm : xo;
+      const int ce1 = sub ? ceo : cem, ce2 = sub ? cem : ceo;
+      const float f1 = sub ? fo : fm, f2 = sub ? fm : fo;
+      const bool a1 = (ce1 & 0xFF) > j, a2 = (ce2 & 0xFF) > j;   // the eigenvalue lies below x1 / below x2
+      // below x1: [lo, x1]; between: [x1, x2]; above x2: [x2, hi]
+      hi = a1 ? x1 : (a2 ? x2 : hi);
+      ce_hi = a1 ? ce1 : (a2 ? ce2 : ce_hi);
+      f_hi = a1 ? f1 : (a2 ? f2 : f_hi);
+      lo = a1 ? lo : (a2 ? x1 : x2);
+      ce_lo = a1 ? ce_lo : (a2 ? ce1 : ce2);
+      f_lo = a1 ? f_lo : (a2 ? f1 : f2);
+      const bool hit = a2 && !a1;
+      thirds_next = secant && !hit;
+      delta = !secant ? delta : (hit ? fmaxf(0.25f * delta, 0x1.0p-12f) : fminf(4.0f * delta, 0.125f));
     }
     if (sub == 0) lam_s[D - 1 - j] = fmax(0.5 * (lo + hi), 0.0) / sc;   // descending order, unscaled
     // Most eigenvalues stay at that width (3e-11 of the largest): they only enter sums.  Full precision is for those
