@@ -1092,24 +1092,25 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       }
     }
     // Rounds of two points per eigenvalue (one per lane of the pair) until every bracket of the wave is at most
-    // 3^-17 / 257 wide (what 17 trisections of a grid cell give; the second phase counts on it).  A bracket that holds
-    // exactly one eigenvalue and has values of det(T - x I) of opposite signs at its ends puts the two points at
-    // t -+ delta around the secant point t; a hit leaves 2 delta of the width and delta shrinks fourfold for the
-    // next round (the secant point of a smooth function with one root in the bracket is off by a fraction of the
-    // width that is itself proportional to the width); a miss is followed by a round of plain thirds, so two rounds
-    // together always leave at most a third.  Brackets with several eigenvalues are cut in thirds.
+    // 3^-17 / 257 wide (what 17 trisections of a uniform grid cell give; the second phase counts on it).  A bracket
+    // that holds exactly one eigenvalue and has values of det(T - x I) of opposite signs at its ends puts the two points
+    // at t -+ delta around the secant point t (t kept 2 delta away from the ends).  delta starts at 1/6 -- thirds
+    // centred on the secant point -- and a hit, which leaves 2 delta of the width, shrinks it fourfold for the next
+    // round (the secant point of a smooth function with one root in the bracket is off by a fraction of the width that
+    // is itself proportional to the width); a miss puts it back to 1/6, where either outcome leaves at most half.
+    // Brackets with several eigenvalues are cut in thirds.  The loop bound is never reached: from the third round
+    // after a miss at the latest every round halves the bracket.
     constexpr double WIDTH_TARGET = 1.0 / (129140163.0 * 257.0);
-    float delta = 0.125f;
-    bool thirds_next = false;
+    float delta = 1.0f / 6.0f;
 #pragma unroll 1
-    for (int it = 0; it < 2 * MULTISECT_ITERS + 2; ++it) {
+    for (int it = 0; it < 80; ++it) {
       const double w = hi - lo;
       if (__ballot(w > WIDTH_TARGET) == 0ull) break;   // wave-uniform
       // f_lo / (f_lo - f_hi) with the two values brought to one exponent
       const int ediff = min(max((ce_hi >> 8) - (ce_lo >> 8), -100), 100);
       const float fh = ldexpf(f_hi, ediff);
       const float ratio = f_lo * __builtin_amdgcn_rcpf(f_lo - fh);
-      const bool secant = !thirds_next && ((ce_hi - ce_lo) & 0xFF) == 1 && f_lo * fh < 0.0f && ratio > 0.0f && ratio < 1.0f;
+      const bool secant = ((ce_hi - ce_lo) & 0xFF) == 1 && f_lo * fh < 0.0f && ratio > 0.0f && ratio < 1.0f;
       const float tc = fminf(fmaxf(ratio, 2.0f * delta), 1.0f - 2.0f * delta);
       const float tsel = secant ? (sub ? tc + delta : tc - delta) : (sub ? (2.0f / 3.0f) : (1.0f / 3.0f));
       const float toth = secant ? (sub ? tc - delta : tc + delta) : (sub ? (1.0f / 3.0f) : (2.0f / 3.0f));
@@ -1133,8 +1134,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       ce_lo = a1 ? ce_lo : (a2 ? ce1 : ce2);
       f_lo = a1 ? f_lo : (a2 ? f1 : f2);
       const bool hit = a2 && !a1;
-      thirds_next = secant && !hit;
-      delta = !secant ? delta : (hit ? fmaxf(0.25f * delta, 0x1.0p-12f) : fminf(4.0f * delta, 0.125f));
+      delta = !secant ? delta : (hit ? fmaxf(0.25f * delta, 0x1.0p-12f) : 1.0f / 6.0f);
     }
     if (sub == 0) lam_s[D - 1 - j] = fmax(0.5 * (lo + hi), 0.0) / sc;   // descending order, unscaled
     // Most eigenvalues stay at that width (3e-11 of the largest): they only enter sums.  Full precision is for those
