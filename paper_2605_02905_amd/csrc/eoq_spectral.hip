@@ -789,12 +789,13 @@ __device__ __forceinline__ void tail32_stage(double (&T)[16], int lane, double* 
 // global memory with wave-uniform addresses (scalar loads: the operands cost no vector or LDS bandwidth).
 // The signs are shifted into a mask, 32 per word, and the changes counted per word.
 typedef __attribute__((address_space(4))) const double sc_double;
-// four steps of the recurrence with the operands t[2 s] = d, t[2 s + 1] = e^2
+// four steps of the recurrence with the operands t[2 s] = d, t[2 s + 1] = e^2; SIGNS: the signs go into the mask
+template <bool SIGNS>
 __device__ __forceinline__ void sturm_steps4(const double (&t)[8], double x, double& pm, double& p, unsigned& m) {
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     const double pn = fma(t[2 * s] - x, p, -(t[2 * s + 1] * pm));
-    m = __builtin_amdgcn_alignbit(m, (unsigned)__double2hiint(pn), 31);  // m = (m << 1) | sign(pn)
+    if constexpr (SIGNS) m = __builtin_amdgcn_alignbit(m, (unsigned)__double2hiint(pn), 31);  // m = (m << 1) | sign(pn)
     pm = p;
     p = pn;
   }
@@ -806,6 +807,8 @@ __device__ __forceinline__ int sturm_renorm(double& pm, double& p) {  // |p| int
   return e;
 }
 // The count, and the value of the last minor p_{D-1}(x) = det(T - x I) as val * 2^vexp (|val| in [1/2, 1) or zero).
+// SIGNS = false: the value alone (three instructions per step instead of four), the return value is meaningless.
+template <bool SIGNS = true>
 __device__ __forceinline__ int sturm_count(sc_double* de, double x, double* val = nullptr, int* vexp = nullptr) {
   double pm = 0.0, p = 1.0;  // p_{-2}, p_{-1}
   unsigned m = 0u;           // sign history, newest in bit 0; p_{-1} > 0
@@ -822,19 +825,19 @@ __device__ __forceinline__ int sturm_count(sc_double* de, double x, double* val 
     sc_double* g = de + 24 * c;
 #pragma unroll
     for (int q = 0; q < 8; ++q) t2[q] = g[16 + q];
-    sturm_steps4(t0, x, pm, p, m);
+    sturm_steps4<SIGNS>(t0, x, pm, p, m);
 #pragma unroll
     for (int q = 0; q < 8; ++q) t0[q] = g[24 + q];
-    sturm_steps4(t1, x, pm, p, m);
+    sturm_steps4<SIGNS>(t1, x, pm, p, m);
 #pragma unroll
     for (int q = 0; q < 8; ++q) t1[q] = g[32 + q];
-    sturm_steps4(t2, x, pm, p, m);
+    sturm_steps4<SIGNS>(t2, x, pm, p, m);
     esum += sturm_renorm(pm, p);
-    cnt += __popc((m ^ (m >> 1)) & 0xFFFu);  // bit 12 is the sign that preceded these twelve
+    if constexpr (SIGNS) cnt += __popc((m ^ (m >> 1)) & 0xFFFu);  // bit 12 is the sign that preceded these twelve
   }
-  sturm_steps4(t0, x, pm, p, m);  // groups 30 and 31
-  sturm_steps4(t1, x, pm, p, m);
-  cnt += __popc((m ^ (m >> 1)) & 0xFFu);
+  sturm_steps4<SIGNS>(t0, x, pm, p, m);  // groups 30 and 31
+  sturm_steps4<SIGNS>(t1, x, pm, p, m);
+  if constexpr (SIGNS) cnt += __popc((m ^ (m >> 1)) & 0xFFu);
   if (val) {
     esum += sturm_renorm(pm, p);
     *val = p;
@@ -1117,7 +1120,17 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       const double xm = fma((double)tsel, w, lo), xo = fma((double)toth, w, lo);   // this lane's point, the partner's
       double fv;
       int fe;
-      const int mine = sturm_count(sde, xm, &fv, &fe);
+      int mine;
+      // Once every bracket of the wave holds one eigenvalue and has a value at either end, the sign of det(T - x I)
+      // alone says on which side of the point the eigenvalue lies (it changes sign once in the bracket): the count is
+      // the lower end's, plus one where the sign differs from the one there.
+      const bool by_sign = __ballot(((ce_hi - ce_lo) & 0xFF) != 1 || f_lo == 0.0f || f_hi == 0.0f) == 0ull;   // wave-uniform
+      if (by_sign) {
+        (void)sturm_count<false>(sde, xm, &fv, &fe);
+        mine = (ce_lo & 0xFF) + (((__double2hiint(fv) ^ __float_as_int(f_lo)) < 0) ? 1 : 0);
+      } else {
+        mine = sturm_count(sde, xm, &fv, &fe);
+      }
       const int cem = (fe << 8) | mine;
       const float fm = (float)fv;
       const int ceo = dpp_mov<0xB1>(cem);
