@@ -376,32 +376,31 @@ __device__ __forceinline__ void gram_cyclic(const void* __restrict__ blocks, int
 // ---------------------------------------------------------------------------------------------
 // Gram matrix of a binary16 block by exact integer arithmetic on the matrix cores.
 //
-// Per pass of 64 tokens every column j gets the exponent E_j of its largest entry and its entries become
+// Per group of 128 tokens every column j gets the exponent E_j of its largest entry and its entries become
 // integers I = trunc(x 2^(29 - E_j)), |I| < 2^30: exact for every entry within a factor 2^19 of the column
 // maximum (binary16 carries 11 significant bits), truncated below 2^(E_j - 29) otherwise.  I is split into four
 // signed bytes, I = s0 + 2^8 s1 + 2^16 s2 + 2^24 s3, and the byte planes are multiplied with
-// v_mfma_i32_16x16x64_i8 (exact int32 sums over the 64 tokens); the sixteen plane pairs go to seven accumulators,
-// one per weight 2^(8 (p + q)).  The pass result, scaled by 2^(E_i + E_j - 58), is added to a double-precision
-// accumulator.  Only the 36 tiles of 16 x 16 on and above the diagonal are computed, nine per wave.  Element
-// (ty, tx) of tile (a, b) is entry A[a * 8 + b] of lane (ty, tx) in the cyclic layout, so at the end the tiles
-// only change lanes (through LDS), the mirrored ones read transposed.
+// v_mfma_i32_16x16x64_i8, two instructions deep per plane pair (exact int32 sums over the 128 tokens); the sixteen
+// plane pairs go to seven accumulators, one per weight 2^(8 (p + q)).  The group result, scaled by
+// 2^(E_i + E_j - 58), is added to a double-precision accumulator: one conversion per 128 tokens.  Only the 36
+// tiles of 16 x 16 on and above the diagonal are computed, nine per wave.  Element (ty, tx) of tile (a, b) is entry
+// A[a * 8 + b] of lane (ty, tx) in the cyclic layout, so at the end the tiles only change lanes (through LDS), the
+// mirrored ones read transposed.
 // ---------------------------------------------------------------------------------------------
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
 
-constexpr int GI_TOK = 64;                       // tokens per pass = depth of one matrix instruction
-constexpr int GI_ROW = GI_TOK + 16;              // bytes per (plane, column): 16 consecutive columns -> 16 distinct 16-byte bank groups
-// Every tile of 16 columns starts 16 bytes further than the row pitch alone would put it: the loaders' stores (lane m
-// writes columns 8 m .. 8 m + 7, so 16 lanes are 8 rows = 160 words apart) then fall into sixteen different bank
-// groups instead of two.
-constexpr int GI_SKEW = 16;
-constexpr int GI_PLANE = D * GI_ROW + (D / 16) * GI_SKEW;   // 10368
+constexpr int GI_TOK = 128;                      // tokens per group = two matrix instructions deep
+constexpr int GI_ROW = GI_TOK;                   // bytes per (plane, column): eight chunks of 16 tokens
+constexpr int GI_PLANE = D * GI_ROW;             // 16384
 constexpr int GI_NPLANE = 4;
-constexpr int GI_CMAX_LD = 68;                   // words per loader row of the column maxima (64 + 4: rows in different banks)
-constexpr int GI_CMAX_OFF = GI_NPLANE * GI_PLANE;  // 16 x 68 words: per-loader column maxima
-constexpr int GI_CEXP_OFF = GI_CMAX_OFF + 16 * GI_CMAX_LD * 4;  // 128 ints: exponent of the integer unit of each column
-constexpr int GI_BYTES = GI_CEXP_OFF + 512;
-static_assert(GI_BYTES <= POOL_BYTES && GI_PLANE % 16 == 0 && GI_CEXP_OFF % 16 == 0, "Gram planes inside the pool");
+constexpr int GI_BYTES = GI_NPLANE * GI_PLANE;   // 64 KB: the four planes fill the pool
+static_assert(GI_BYTES <= POOL_BYTES && GI_PLANE % 16 == 0, "Gram planes inside the pool");
+// A row is exactly as wide as the banks, so the chunks of a row are stored permuted: chunk c of column col sits at
+// position c ^ col ^ (col >> 3) (low three bits).  The sixteen lanes that read chunk c of sixteen consecutive
+// columns (operand loads) and the sixteen loaders that write chunk c of columns 8 m + const both touch every
+// position twice, which is what a 16-byte access of sixteen lanes needs anyway.
+__device__ __forceinline__ int gi_chunk_off(int col, int c) { return ((c ^ col ^ (col >> 3)) & 7) << 4; }
 constexpr int GI_TILES = 36;                     // upper tiles, row-major: (0,0) .. (0,7), (1,1) .. (7,7)
 constexpr int UT_I[GI_TILES] = {0, 0, 0, 0, 0, 0, 0, 0, 1, 1, 1, 1, 1, 1, 1, 2, 2, 2, 2, 2, 2, 3, 3, 3, 3, 3, 4, 4, 4, 4, 5, 5, 5, 6, 6, 7};
 constexpr int UT_J[GI_TILES] = {0, 1, 2, 3, 4, 5, 6, 7, 1, 2, 3, 4, 5, 6, 7, 2, 3, 4, 5, 6, 7, 3, 4, 5, 6, 7, 4, 5, 6, 7, 5, 6, 7, 6, 7, 7};
@@ -412,38 +411,44 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
   const ushort2v r = __builtin_elementwise_max(*reinterpret_cast<ushort2v*>(&a), *reinterpret_cast<ushort2v*>(&b));
   return *reinterpret_cast<const uint32_t*>(&r);
 }
-__device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size_t tok, int n, unsigned char* pool, int tid,
-                                          double (&A)[64], unsigned* flag_s) {
+// cmax: 4 x 64 words (the waves' column maxima), cexp: 128 ints (exponent of the integer unit of each column); both
+// outside the pool, which the planes fill.  n is a multiple of 128.
+__device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size_t tok, int n, unsigned char* pool,
+                                          uint32_t* cmax, int* cexp, int tid, double (&A)[64], unsigned* flag_s) {
   const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int m = tid & 15, q = tid >> 4;  // loader: columns 8m .. 8m+7, tokens 4q .. 4q+3 of the pass
-  uint32_t* cmax = reinterpret_cast<uint32_t*>(pool + GI_CMAX_OFF);
-  int* cexp = reinterpret_cast<int*>(pool + GI_CEXP_OFF);
+  const int m = tid & 15, q = tid >> 4;  // loader: columns 8m .. 8m+7, tokens 64 h + 4q .. 64 h + 4q + 3 of the group
   double Gacc[9][4];  // tile number wave + 4 s, rows 4 kg + v, column l16
   EOQ_SFOR(s, 9, EOQ_SFOR(v, 4, Gacc[s][v] = 0.0;););
 
   uint32_t top = 0u;  // largest |binary16 pattern| this lane has seen in its columns: 0x7C00 and above is Inf / NaN
-  uint4 raw[4];
+  uint4 raw[8];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) raw[it] = *reinterpret_cast<const uint4*>(src + (size_t)(4 * q + it) * tok + 8 * m);
+  for (int i = 0; i < 8; ++i)
+    raw[i] = *reinterpret_cast<const uint4*>(src + (size_t)(64 * (i >> 2) + 4 * q + (i & 3)) * tok + 8 * m);
 
 #pragma unroll 1
   for (int t0 = 0; t0 < n; t0 += GI_TOK) {
-    // ---- column maxima of the pass ----
+    // ---- column maxima of the group: over the lane's eight tokens, the wave's four loader rows, the four waves ----
     uint32_t mx[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      mx[0] = pk_max_u16(mx[0], raw[it].x & 0x7FFF7FFFu);
-      mx[1] = pk_max_u16(mx[1], raw[it].y & 0x7FFF7FFFu);
-      mx[2] = pk_max_u16(mx[2], raw[it].z & 0x7FFF7FFFu);
-      mx[3] = pk_max_u16(mx[3], raw[it].w & 0x7FFF7FFFu);
+    for (int i = 0; i < 8; ++i) {
+      mx[0] = pk_max_u16(mx[0], raw[i].x & 0x7FFF7FFFu);
+      mx[1] = pk_max_u16(mx[1], raw[i].y & 0x7FFF7FFFu);
+      mx[2] = pk_max_u16(mx[2], raw[i].z & 0x7FFF7FFFu);
+      mx[3] = pk_max_u16(mx[3], raw[i].w & 0x7FFF7FFFu);
     }
-    __syncthreads();  // the previous pass no longer reads planes, maxima or exponents
-    *reinterpret_cast<uint4*>(cmax + q * GI_CMAX_LD + m * 4) = make_uint4(mx[0], mx[1], mx[2], mx[3]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      mx[i] = pk_max_u16(mx[i], (uint32_t)__shfl_xor((int)mx[i], 16, 64));
+      mx[i] = pk_max_u16(mx[i], (uint32_t)__shfl_xor((int)mx[i], 32, 64));
+    }
+    __syncthreads();  // the previous group no longer reads planes, maxima or exponents
+    if (kg == 0) *reinterpret_cast<uint4*>(cmax + wave * 64 + m * 4) = make_uint4(mx[0], mx[1], mx[2], mx[3]);
     __syncthreads();
 #pragma unroll
-    for (int rr = 0; rr < 16; ++rr) {
-      const uint4 o = *reinterpret_cast<const uint4*>(cmax + rr * GI_CMAX_LD + m * 4);
+    for (int w = 0; w < 4; ++w) {
+      const uint4 o = *reinterpret_cast<const uint4*>(cmax + w * 64 + m * 4);
       mx[0] = pk_max_u16(mx[0], o.x);
       mx[1] = pk_max_u16(mx[1], o.y);
       mx[2] = pk_max_u16(mx[2], o.z);
@@ -459,53 +464,62 @@ __device__ __forceinline__ void gram_int8(const uint16_t* __restrict__ src, size
       // I = sum_k d_k 256^k with balanced digits d_k in [-128, 127]: adding 128 to every digit place makes them the
       // plain bytes of I + 0x80808080 (|I| < 2^30: no carry out of the top), and flipping the top bit of each byte
       // takes the 128 off again, as a two's-complement byte.  The four planes are those bytes.
-      uint32_t dg[4];
-      EOQ_SFOR(it, 4,
-        const uint32_t w = (c >> 1) == 0 ? raw[it].x : ((c >> 1) == 1 ? raw[it].y : ((c >> 1) == 2 ? raw[it].z : raw[it].w));
-        const uint16_t hb = (uint16_t)(w >> (16 * (c & 1)));
-        const int I = (int)(half_bits_to_float(hb) * scale);   // truncation towards zero
-        dg[it] = ((uint32_t)I + 0x80808080u) ^ 0x80808080u;
+      EOQ_SFOR(h, 2,
+        uint32_t dg[4];
+        EOQ_SFOR(it, 4,
+          const uint4 rw = raw[4 * h + it];
+          const uint32_t w = (c >> 1) == 0 ? rw.x : ((c >> 1) == 1 ? rw.y : ((c >> 1) == 2 ? rw.z : rw.w));
+          const uint16_t hb = (uint16_t)(w >> (16 * (c & 1)));
+          const int I = (int)(half_bits_to_float(hb) * scale);   // truncation towards zero
+          dg[it] = ((uint32_t)I + 0x80808080u) ^ 0x80808080u;
+        );
+        uint32_t pl[4];
+        transpose_bytes(dg[0], dg[1], dg[2], dg[3], pl);
+        unsigned char* dst = pool + (8 * m + c) * GI_ROW + gi_chunk_off(8 * m + c, 4 * h + (q >> 2)) + 4 * (q & 3);
+        *reinterpret_cast<uint32_t*>(dst) = pl[0];
+        *reinterpret_cast<uint32_t*>(dst + GI_PLANE) = pl[1];
+        *reinterpret_cast<uint32_t*>(dst + 2 * GI_PLANE) = pl[2];
+        *reinterpret_cast<uint32_t*>(dst + 3 * GI_PLANE) = pl[3];
       );
-      uint32_t pl[4];
-      transpose_bytes(dg[0], dg[1], dg[2], dg[3], pl);
-      unsigned char* dst = pool + (8 * m + c) * GI_ROW + (m >> 1) * GI_SKEW + 4 * q;
-      *reinterpret_cast<uint32_t*>(dst) = pl[0];
-      *reinterpret_cast<uint32_t*>(dst + GI_PLANE) = pl[1];
-      *reinterpret_cast<uint32_t*>(dst + 2 * GI_PLANE) = pl[2];
-      *reinterpret_cast<uint32_t*>(dst + 3 * GI_PLANE) = pl[3];
     );
-    if (t0 + GI_TOK < n) {  // next pass on its way during the products
+    if (t0 + GI_TOK < n) {  // next group on its way during the products
 #pragma unroll
-      for (int it = 0; it < 4; ++it)
-        raw[it] = *reinterpret_cast<const uint4*>(src + (size_t)(t0 + GI_TOK + 4 * q + it) * tok + 8 * m);
+      for (int i = 0; i < 8; ++i)
+        raw[i] = *reinterpret_cast<const uint4*>(src + (size_t)(t0 + GI_TOK + 64 * (i >> 2) + 4 * q + (i & 3)) * tok + 8 * m);
     }
     __syncthreads();
-    // ---- products, one tile at a time: lane supplies row / column l16 of the tile, tokens 16 kg .. 16 kg + 15 ----
+    // ---- products, one tile at a time: lane supplies row / column l16 of the tile, tokens 64 h + 16 kg .. + 15 ----
     EOQ_SFOR(s, 9,
       const int tile = wave + 4 * s;
       const int tI = ut_i_dev[tile]; const int tJ = ut_j_dev[tile];
       v4i acc[7];  // acc[c]: plane pairs (p, q) with p + q = c, weight 2^(8 c)
       EOQ_SFOR(cc, 7, EOQ_SFOR(v, 4, acc[cc][v] = 0;););
-      const unsigned char* pa = pool + (16 * tI + l16) * GI_ROW + tI * GI_SKEW + 16 * kg;
-      const unsigned char* pb = pool + (16 * tJ + l16) * GI_ROW + tJ * GI_SKEW + 16 * kg;
-      v4i a[4]; v4i b[4];
-      EOQ_SFOR(pl, 4,
-        a[pl] = *reinterpret_cast<const v4i*>(pa + pl * GI_PLANE);
-        b[pl] = *reinterpret_cast<const v4i*>(pb + pl * GI_PLANE);
-      );
-      // order: consecutive instructions hit different accumulators
-      EOQ_SFOR(rot, 4,
+      const int ca = 16 * tI + l16, cb = 16 * tJ + l16;
+      EOQ_SFOR(h, 2,
+        const unsigned char* pa = pool + ca * GI_ROW + gi_chunk_off(ca, 4 * h + kg);
+        const unsigned char* pb = pool + cb * GI_ROW + gi_chunk_off(cb, 4 * h + kg);
+        v4i a[4]; v4i b[4];
         EOQ_SFOR(pl, 4,
-          constexpr int ql = (pl + rot) & 3;
-          acc[pl + ql] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[pl], b[ql], acc[pl + ql], 0, 0, 0);
+          a[pl] = *reinterpret_cast<const v4i*>(pa + pl * GI_PLANE);
+          b[pl] = *reinterpret_cast<const v4i*>(pb + pl * GI_PLANE);
+        );
+        // order: consecutive instructions hit different accumulators
+        EOQ_SFOR(rot, 4,
+          EOQ_SFOR(pl, 4,
+            constexpr int ql = (pl + rot) & 3;
+            acc[pl + ql] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[pl], b[ql], acc[pl + ql], 0, 0, 0);
+          );
         );
       );
       // into double precision with the exponents of rows 4 kg + v (tile I) and column l16 (tile J)
       const int ej = cexp[16 * tJ + l16];
       const int4 ei = *reinterpret_cast<const int4*>(cexp + 16 * tI + 4 * kg);
       const int eiv[4] = {ei.x, ei.y, ei.z, ei.w};
-      // neighbouring weights are merged in int32 first (a class holds at most 4 * 64 * 128 * 128 < 2^23 in magnitude,
-      // so c_even + 2^8 c_odd stays below 2^31), then four conversions and a Horner pass in double
+      // Neighbouring weights are merged in int32 first, then four conversions and a Horner pass in double.  A digit
+      // is at most 128 in magnitude and the top digit at most 64 (|I| < 2^30), so over 128 tokens the classes are
+      // bounded by |c_0| <= 2^21, |c_1| <= 2^22, |c_2| <= 3 2^21, |c_3| <= 128 (2^15 + 2^14) = 3 2^21, |c_4| <=
+      // 128 (2^14 + 2^14) = 2^22, |c_5| <= 2^21, and every c_even + 2^8 c_odd stays below 2^31 (the largest,
+      // c_2 + 2^8 c_3, below 1.62e9).
       EOQ_SFOR(v, 4,
         const int m01 = acc[0][v] + (acc[1][v] << 8), m23 = acc[2][v] + (acc[3][v] << 8), m45 = acc[4][v] + (acc[5][v] << 8);
         const double val = fma(fma(fma((double)acc[6][v], 65536.0, (double)m45), 65536.0, (double)m23), 65536.0, (double)m01);
@@ -982,7 +996,8 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
   {
     double A[64];
     if (dtype == EOQ_F16)
-      gram_int8(static_cast<const uint16_t*>(blocks) + map.in_base(blk), (size_t)map.token_stride, n, pool, tid, A, &flag_s);
+      gram_int8(static_cast<const uint16_t*>(blocks) + map.in_base(blk), (size_t)map.token_stride, n, pool,
+                reinterpret_cast<uint32_t*>(lam_s), reinterpret_cast<int*>(atoms), tid, A, &flag_s);
     else
       gram_cyclic(blocks, dtype, map.in_base(blk), (size_t)map.token_stride, n, reinterpret_cast<float*>(u1), tid, A, &flag_s);
     __syncthreads();  // the pool changes hands
