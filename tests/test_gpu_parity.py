@@ -207,6 +207,51 @@ def test_degenerate_blocks():
     assert np.all(codes0 == 2)
 
 
+def test_integer_gram_over_a_wide_dynamic_range():
+    """The Gram matrix of binary16 blocks is formed in integers with one exponent per column and group of 128 tokens,
+    exact for every entry within 2^19 of that group's column maximum.  (a) Columns whose scale jumps by powers of two
+    from one group of tokens to the next (2^-6 .. 2^6 per group and column) and one token 128 times larger than the
+    rest stay inside that range: every bar of the ordinary comparison holds, the retained eigenvalues to 1e-12 of
+    the largest.  (b) Entries further than 2^19 below their column's maximum are cut off at 2^-29 of it: with m such
+    entries the eigenvalues move by at most ||dG||_F <= 2 sqrt(m) 2^-29 max|S| sqrt(lambda_1)."""
+    spec = synth.config(2)
+    blocks, _ = synth.make_blocks(spec, tensors=range(1))
+    blocks = blocks[:6].clone().float()
+    gen = torch.Generator().manual_seed(11)
+    B, n, d = blocks.shape
+    k = torch.randint(-6, 7, (B, n // 128, 1, d), generator=gen).float()
+    blocks = (blocks.view(B, n // 128, 128, d) * torch.exp2(k)).view(B, n, d)
+    blocks[:, 0] *= 128.0
+    assert float(blocks.abs().max()) < 60000.0
+    blocks = blocks.to(torch.float16)
+    b64 = blocks.double().numpy()
+    recs = U.oracle_compress(b64, 2)
+    ctx, rec, lam = _gpu_compress(blocks, 2, spec.n)
+    st = U.compare_compress(b64, rec, lam, recs, 2)
+    U.log_stats("gram-dynamic-range", st)
+    assert st["max_lam_top_rel"] <= 1e-12
+
+    # (b) forty entries per block between 2^-24 and 2^-20 of their column's largest entry in the block
+    tiny = blocks.clone()
+    m = 40
+    for b in range(B):
+        colmax = tiny[b].abs().amax(dim=0).float()
+        rows = torch.randint(1, n, (m,), generator=gen)
+        cols = torch.randint(0, d, (m,), generator=gen)
+        scale = torch.exp2(-20.0 - 4.0 * torch.rand(m, generator=gen))
+        tiny[b, rows, cols] = (colmax[cols] * scale * (1.0 + torch.rand(m, generator=gen))).to(torch.float16)
+    t64 = tiny.double().numpy()
+    assert np.all(np.abs(t64[np.nonzero(t64)]) > 0)
+    _, rec_t, lam_t = _gpu_compress(tiny, 2, spec.n)
+    for b in range(B):
+        lam_o = np.linalg.svd(t64[b], compute_uv=False) ** 2
+        bound = 2.0 * math.sqrt(m) * 2.0 ** -29 * np.abs(t64[b]).max() * math.sqrt(lam_o[0])
+        dev = np.max(np.abs(lam_t[b] - lam_o))
+        assert dev <= bound + 1e-9 * lam_o[0] * 0.05, (b, dev, bound)   # + the resolution of the bulk eigenvalues (5e-11)
+        assert dev <= 1e-9 * lam_o[0], (b, dev / lam_o[0])
+    assert not np.any(rec_t.flags.cpu().numpy() & eoq.FLAG_NONFINITE)
+
+
 @pytest.mark.parametrize("dtype,solver", [(torch.float16, 0), (torch.float32, 0), (torch.float16, 1)])
 def test_blocks_with_inf_or_nan_are_flagged_and_stored_with_rank_zero(dtype, solver):
     """A block that holds an Inf or a NaN (binary16: any entry with all exponent bits set) comes back with
