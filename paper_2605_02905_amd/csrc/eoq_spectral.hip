@@ -629,13 +629,25 @@ __device__ __forceinline__ double newton_rcp(double s) {
 // H_k = I - beta_k v_k v_k^T.  Per step: the 16 lanes that own row k form v and beta (the other lanes wait),
 // all lanes multiply p = beta A v over their live sub-tile (partial sums folded across the DPP row), then apply
 // A <- A - v w^T - w v^T with w = p - (beta/2)(v^T p) v.
+// A wave issues an instruction every eight cycles or so whatever the instructions are (two waves per SIMD: one every
+// five between them), so what a step costs is the number of instructions of the wave the others wait for.  The wave
+// that forms the reflector therefore does nothing else: the row goes to LDS as it is (one entry less alpha), and the
+// float copy of the reflector for the back-transformation is made one step later by the next wave, which would wait
+// otherwise.
 // p = beta A v in LDS: entry i = l + 16 g at pbuf[l + PB_LD g].  Its writers are four consecutive rows l of up to eight
 // groups g per wave; at a pitch of 20 doubles the groups start in eight different sets of eight banks.
 constexpr int PB_LD = 20;
+// float copy of reflector k (entries k + 1 .. 127 of v, in LDS as doubles) into the packed store, by one wave
+__device__ __forceinline__ void stash_reflector(const double* v, int k, int lane, float* refl) {
+  float* dst = refl + refl_off(k) - (k + 1);   // entry j at dst[j]
+  if (lane > k) dst[lane] = (float)v[lane];
+  if (lane + 64 > k) dst[lane + 64] = (float)v[lane + 64];
+}
 template <int S>
 __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, double (*vbuf)[D], double* pbuf,
                                                   float* refl, double* dT, double* eT, double* betaT) {
-  const int lane = tid & 63, wave = tid >> 6, ty = tid >> 4, tx = tid & 15;
+  const int lane = tid & 63, ty = tid >> 4, tx = tid & 15;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   constexpr int KK_END = (S == 7) ? 14 : 16;
 #pragma unroll 1
   for (int kk = 0; kk < KK_END; ++kk) {
@@ -644,15 +656,16 @@ __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, doub
     if (wave == (kk >> 2)) {
       // every 16-lane row of this wave runs the arithmetic on its own matrix row; only the row k stores
       const bool owner = ((lane >> 4) == (kk & 3));
-      double x[8];
-      EOQ_SFOR(b, 8, x[b] = (b >= S) ? A[S * 8 + b] : 0.0;);
-      if (owner && tx == kk) dT[k] = x[S];
-      x[S] = (tx > kk) ? x[S] : 0.0;  // columns j = tx + 16 b > k only
-      double ss = 0.0;
-      EOQ_SFOR(b, 8, if constexpr (b >= S) ss = fma(x[b], x[b], ss););
-      ss = row16_sum(ss);
-      double xsel = x[S];
-      if constexpr (S < 7) xsel = (kk == 15) ? x[S + 1] : xsel;
+      const double xs = (tx > kk) ? A[S * 8 + S] : 0.0;  // columns j = tx + 16 b > k only
+      double s0 = xs * xs, s1 = 0.0;
+      EOQ_SFOR(b, 8,
+        if constexpr (b > S) {
+          if constexpr (((b - S) & 1) == 0) s0 = fma(A[S * 8 + b], A[S * 8 + b], s0);
+          else s1 = fma(A[S * 8 + b], A[S * 8 + b], s1);
+        });
+      const double ss = row16_sum_uniform(s0 + s1);   // the same bits in the sixteen lanes of a row
+      double xsel = xs;
+      if constexpr (S < 7) xsel = (kk == 15) ? A[S * 8 + S + 1] : xsel;
       const double x0 = readlane_f64(xsel, 16 * (kk & 3) + ((kk + 1) & 15));  // x_{k+1} of row k
       double alpha = 0.0, beta = 0.0;
       if (ss > 0x1.0p-960) {
@@ -661,17 +674,20 @@ __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, doub
         beta = newton_rcp(fma(sigma, fabs(x0), ss));          // 2 / (v^T v), v = x - alpha e_1
       }
       if (owner) {
+        // v = x - alpha e_{k+1}: entry k + 1 sits in sub-tile S of lane kk + 1, or, at the last step of a stage, in
+        // sub-tile S + 1 of lane 0
+        const double fix = (tx == ((kk + 1) & 15)) ? alpha : 0.0;
+        vb[tx + 16 * S] = xs - ((kk < 15) ? fix : 0.0);
         EOQ_SFOR(b, 8,
-          const int j = tx + 16 * b;
-          const double v = (b >= S) ? x[b] - ((j == k + 1) ? alpha : 0.0) : 0.0;
-          vb[j] = v;
-          if (b >= S && j > k) refl[refl_off(k) + j - k - 1] = (float)v;
-        );
-        if (tx == 0) {
+          if constexpr (b > S) vb[tx + 16 * b] = (b == S + 1) ? A[S * 8 + b] - ((kk == 15) ? fix : 0.0) : A[S * 8 + b];);
+        if (tx == kk) {
+          dT[k] = A[S * 8 + S];
           eT[k] = alpha;
           betaT[k] = beta;
         }
       }
+    } else if (wave == (((kk >> 2) + 1) & 3) && k > 0) {
+      stash_reflector(vbuf[(kk + 1) & 1], k - 1, lane, refl);   // the reflector of the step before, complete since that step's first barrier
     }
     __syncthreads();
     const double beta = betaT[k];
@@ -1002,6 +1018,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       gram_cyclic(blocks, dtype, map.in_base(blk), (size_t)map.token_stride, n, reinterpret_cast<float*>(u1), tid, A, &flag_s);
     __syncthreads();  // the pool changes hands
     EOQ_SFOR(s, 6, householder_stage<s>(A, tid, vbuf, pbuf, refl, dT, eT, betaT););
+    if (wave == 1) stash_reflector(vbuf[1], 95, lane, refl);   // reflector 95: the stages stash one step behind
     // the trailing 32 x 32 matrix (rows and columns 96 .. 127: sub-tiles a, b = 6, 7 of every lane) changes hands:
     // through LDS into the 64 lanes of wave 0, which finishes the reduction alone
     double* Ms = reinterpret_cast<double*>(u1);   // [32][33]
