@@ -718,10 +718,11 @@ __device__ __forceinline__ void householder_stage(double (&A)[64], int tid, doub
         if constexpr ((b & 1) == 0) dl0 = fma(vj[b], wj[b], dl0);
         else dl1 = fma(vj[b], wj[b], dl1);
       });
-    const double K = 0.5 * beta * row16_sum_uniform(dl0 + dl1);
-    EOQ_SFOR(b, 8, if constexpr (b >= S) wj[b] = fma(-K, vj[b], wj[b]););
+    // v w^T + w v^T with w = p - K v is v p^T + q v^T with q = p - 2 K v: the correction is needed in the row view
+    // only, the column view of p goes into the update as it was read
+    const double K2 = beta * row16_sum_uniform(dl0 + dl1);
     EOQ_SFOR(a, 8, vi[a] = (a >= S) ? vb[ty + 16 * a] : 0.0;);
-    EOQ_SFOR(a, 8, wi[a] = (a >= S) ? fma(-K, vi[a], pbuf[ty + PB_LD * a]) : 0.0;);
+    EOQ_SFOR(a, 8, wi[a] = (a >= S) ? fma(-K2, vi[a], pbuf[ty + PB_LD * a]) : 0.0;);
     EOQ_SFOR(e, 64,
       if constexpr ((e >> 3) >= S && (e & 7) >= S)
         A[e] = fma(-vi[e >> 3], wj[e & 7], fma(-wi[e >> 3], vj[e & 7], A[e])););
@@ -744,7 +745,7 @@ __device__ __forceinline__ double oct_sum_uniform(double v) {
 // LDS without a barrier (operations of one wave complete in order) and the sums run over eight lanes.
 // Steps 8 AO .. 8 AO + 7 (the last stage stops after local row 29): rows and columns below 8 AO are dead.
 template <int AO>
-__device__ __forceinline__ void tail32_stage(double (&T)[16], int lane, double* vb, double* pb, float* refl, double* dT,
+__device__ __forceinline__ void tail32_stage(double (&T)[16], int lane, double* vring, double* pb, double* dT,
                                              double* eT, double* betaT) {
   const int ly = lane >> 3, lx = lane & 7;
   constexpr int KEND = (AO == 3) ? 6 : 8;
@@ -752,16 +753,16 @@ __device__ __forceinline__ void tail32_stage(double (&T)[16], int lane, double* 
   for (int kk = 0; kk < KEND; ++kk) {
     const int kq = 8 * AO + kk, k = 96 + kq;
     // ---- v, beta from row kq: every group of eight lanes runs the arithmetic on its own row, the owner stores ----
+    // (the reflector stays in LDS as doubles, every step in a slot of its own: `vring`; the float copy for the
+    // back-transformation is made afterwards by all four waves)
+    double* vb = vring + 32 * kq;
     const bool owner = (ly == kk);
-    double x[4];
-    EOQ_SFOR(b, 4, x[b] = (b >= AO) ? T[AO * 4 + b] : 0.0;);
-    if (owner && lx == kk) dT[k] = x[AO];
-    x[AO] = (lx > kk) ? x[AO] : 0.0;   // columns lx + 8 b > kq only
-    double ss = 0.0;
-    EOQ_SFOR(b, 4, if constexpr (b >= AO) ss = fma(x[b], x[b], ss););
+    const double xs = (lx > kk) ? T[AO * 4 + AO] : 0.0;   // columns lx + 8 b > kq only
+    double ss = xs * xs;
+    EOQ_SFOR(b, 4, if constexpr (b > AO) ss = fma(T[AO * 4 + b], T[AO * 4 + b], ss););
     ss = oct_sum_uniform(ss);
-    double xsel = x[AO];
-    if constexpr (AO < 3) xsel = (kk == 7) ? x[AO + 1] : xsel;
+    double xsel = xs;
+    if constexpr (AO < 3) xsel = (kk == 7) ? T[AO * 4 + AO + 1] : xsel;
     const double x0 = readlane_f64(xsel, 8 * kk + ((kk + 1) & 7));   // M[kq][kq + 1]
     double alpha = 0.0, beta = 0.0;
     if (ss > 0x1.0p-960) {
@@ -770,13 +771,14 @@ __device__ __forceinline__ void tail32_stage(double (&T)[16], int lane, double* 
       beta = newton_rcp(fma(sigma, fabs(x0), ss));
     }
     if (owner) {
+      // v = x - alpha e_{kq+1}: that entry sits in sub-tile AO of lane kk + 1, or, at the last step of a stage, in
+      // sub-tile AO + 1 of lane 0
+      const double fix = (lx == ((kk + 1) & 7)) ? alpha : 0.0;
+      vb[lx + 8 * AO] = xs - ((kk < 7) ? fix : 0.0);
       EOQ_SFOR(b, 4,
-        const int c = lx + 8 * b;
-        const double v = (b >= AO) ? x[b] - ((c == kq + 1) ? alpha : 0.0) : 0.0;
-        vb[c] = v;
-        if (b >= AO && c > kq) refl[refl_off(k) + c - kq - 1] = (float)v;
-      );
-      if (lx == 0) {
+        if constexpr (b > AO) vb[lx + 8 * b] = (b == AO + 1) ? T[AO * 4 + b] - ((kk == 7) ? fix : 0.0) : T[AO * 4 + b];);
+      if (lx == kk) {
+        dT[k] = T[AO * 4 + AO];
         eT[k] = alpha;
         betaT[k] = beta;
       }
@@ -802,15 +804,14 @@ __device__ __forceinline__ void tail32_stage(double (&T)[16], int lane, double* 
     EOQ_SFOR(b, 4, pc[b] = (b >= AO) ? pb[lx + 8 * b] : 0.0;);
     double dl = 0.0;
     EOQ_SFOR(b, 4, if constexpr (b >= AO) dl = fma(vc[b], pc[b], dl););
-    const double K = 0.5 * bq * oct_sum_uniform(dl);
-    // ---- M <- M - v w^T - w v^T, w = p - K v ----
-    double wc[4], wr[4];
-    EOQ_SFOR(b, 4, wc[b] = (b >= AO) ? fma(-K, vc[b], pc[b]) : 0.0;);
-    EOQ_SFOR(a, 4, wr[a] = (a >= AO) ? fma(-K, vr[a], pr[a]) : 0.0;);
+    const double K2 = bq * oct_sum_uniform(dl);
+    // ---- M <- M - v p^T - q v^T, q = p - 2 K v (= M - v w^T - w v^T with w = p - K v) ----
+    double wr[4];
+    EOQ_SFOR(a, 4, wr[a] = (a >= AO) ? fma(-K2, vr[a], pr[a]) : 0.0;);
     EOQ_SFOR(e, 16,
       if constexpr ((e >> 2) >= AO && (e & 3) >= AO)
-        T[e] = fma(-vr[e >> 2], wc[e & 3], fma(-wr[e >> 2], vc[e & 3], T[e])););
-    __builtin_amdgcn_wave_barrier();   // vb and pb are rewritten by the next step
+        T[e] = fma(-vr[e >> 2], pc[e & 3], fma(-wr[e >> 2], vc[e & 3], T[e])););
+    __builtin_amdgcn_wave_barrier();   // pb is rewritten by the next step
   }
 }
 
@@ -1022,6 +1023,7 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     // the trailing 32 x 32 matrix (rows and columns 96 .. 127: sub-tiles a, b = 6, 7 of every lane) changes hands:
     // through LDS into the 64 lanes of wave 0, which finishes the reduction alone
     double* Ms = reinterpret_cast<double*>(u1);   // [32][33]
+    double* vring = Ms + 32 * 33;                 // [30][32]: the reflectors of the last 30 steps as doubles
     {
       const int ty = tid >> 4, tx = tid & 15;
       EOQ_SFOR(a, 2, EOQ_SFOR(b, 2, Ms[(ty + 16 * a) * 33 + tx + 16 * b] = A[(6 + a) * 8 + 6 + b];););
@@ -1031,11 +1033,18 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       const int ly = lane >> 3, lx = lane & 7;
       double T[16];
       EOQ_SFOR(e, 16, T[e] = Ms[(ly + 8 * (e >> 2)) * 33 + lx + 8 * (e & 3)];);
-      EOQ_SFOR(ao, 4, tail32_stage<ao>(T, lane, vbuf[0], pbuf, refl, dT, eT, betaT););
+      EOQ_SFOR(ao, 4, tail32_stage<ao>(T, lane, vring, pbuf, dT, eT, betaT););
       // the last 2x2 block of T: rows and columns 126, 127 = local 30, 31 = (ly, lx) in {6, 7}, a = b = 3
       if (ly == 6 && lx == 6) dT[D - 2] = T[15];
       if (ly == 7 && lx == 6) eT[D - 2] = T[15];
       if (ly == 7 && lx == 7) dT[D - 1] = T[15];
+    }
+    __syncthreads();
+    // float copies of the last 30 reflectors (local entries c > kq of step kq), by everybody
+#pragma unroll
+    for (int e = tid; e < 30 * 32; e += THREADS) {
+      const int kq = e >> 5, c = e & 31;
+      if (c > kq) refl[refl_off(96 + kq) + c - kq - 1] = (float)vring[e];
     }
   }
   __syncthreads();
