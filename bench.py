@@ -73,6 +73,11 @@ def measure_ceilings(ctx, torch, dev):
     r = ctx.eoq_ceiling(10, buf, 4000)
     out["mfma_f64_beside_fma64_TFLOPs"] = (r["work_a"] + r["work_b"]) / (r["ms"] * 1e-3) / 1e12
     out["compute_units"] = r["compute_units"]
+    # the same f64 FMA loop on 1, 2 and 4 waves per SIMD: what one wave can issue by itself, and what the two waves per
+    # SIMD that the spectral kernel's registers allow reach between them
+    for waves in (1, 2, 4):
+        r = ctx.eoq_ceiling(30 + waves, buf, 4000)
+        out["fp64_fma_%dwave_per_simd_TFLOPs" % waves] = (r["work_a"] + r["work_b"]) / (r["ms"] * 1e-3) / 1e12
     del buf
     return out
 
