@@ -977,6 +977,23 @@ __device__ __forceinline__ void twisted_chain(double2* F, const double2* M, int 
   *ssq_out = ssq;
 }
 
+// Inner product number q of the reflectors of group q / 6 = {4b, .., 4b+3}, in the order the back-transformation applies
+// them (u_1 = v_{4b+3} .. u_4 = v_{4b}): c21 c31 c32 c41 c42 c43; one product per lane, over the rows where both
+// reflectors live (i > kb; what lies outside a reflector is arbitrary)
+__device__ __forceinline__ void reflector_product(int q, const float* refl, double* cW) {
+  const int bb = q / 6, pr = q - 6 * bb;
+  const int a = (pr == 0) ? 2 : ((pr < 3) ? 3 : 4), b2 = (pr == 0) ? 1 : ((pr < 3) ? pr : pr - 2);
+  const int ka = 4 * bb + 4 - a, kb = 4 * bb + 4 - b2;  // ka < kb
+  const float* pa = refl + refl_off(ka) - (ka + 1);      // entry i of reflector ka at pa[i]
+  const float* pb = refl + refl_off(kb) - (kb + 1);
+  double acc = 0.0;
+  if (kb < D - 2) {
+#pragma unroll 4
+    for (int i = kb + 1; i < D; ++i) acc = fma((double)pa[i], (double)pb[i], acc);
+  }
+  cW[q] = acc;
+}
+
 __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     const void* __restrict__ blocks, EoqBlockMap map, int dtype, int n, int k_pilot, double rank_thr, int r_max, int loss,
     int* __restrict__ fb_list, int* __restrict__ fb_count, double* __restrict__ lam_out, float* __restrict__ wfac,
@@ -1038,6 +1055,10 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       if (ly == 6 && lx == 6) dT[D - 2] = T[15];
       if (ly == 7 && lx == 6) eT[D - 2] = T[15];
       if (ly == 7 && lx == 7) dT[D - 1] = T[15];
+    } else if (tid - 64 < 144) {
+      // meanwhile the other waves form the inner products of the reflectors 0 .. 95 (groups 0 .. 23), whose float
+      // copies are complete
+      reflector_product(tid - 64, refl, cW);
     }
     __syncthreads();
     // float copies of the last 30 reflectors (local entries c > kq of step kq), by everybody
@@ -1048,22 +1069,8 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     }
   }
   __syncthreads();
-  // inner products of the reflectors of each group {4b, .., 4b+3}, in the order the back-transformation applies
-  // them (u_1 = v_{4b+3} .. u_4 = v_{4b}): c21 c31 c32 c41 c42 c43; one product per lane, over the rows where both
-  // reflectors live (i > kb; what lies outside a reflector is arbitrary)
-  if (tid < (D / 4) * 6) {
-    const int q = tid, bb = q / 6, pr = q - 6 * bb;
-    const int a = (pr == 0) ? 2 : ((pr < 3) ? 3 : 4), b2 = (pr == 0) ? 1 : ((pr < 3) ? pr : pr - 2);
-    const int ka = 4 * bb + 4 - a, kb = 4 * bb + 4 - b2;  // ka < kb
-    const float* pa = refl + refl_off(ka) - (ka + 1);      // entry i of reflector ka at pa[i]
-    const float* pb = refl + refl_off(kb) - (kb + 1);
-    double acc = 0.0;
-    if (kb < D - 2) {
-#pragma unroll 4
-      for (int i = kb + 1; i < D; ++i) acc = fma((double)pa[i], (double)pb[i], acc);
-    }
-    cW[q] = acc;
-  }
+  // the inner products of the reflectors 96 .. 127 (the others were formed beside the one-wave tail)
+  if (tid < 48) reflector_product(144 + tid, refl, cW);
 
   // ---- eigenvalues of T by Sturm-count multisection: lane pair j brackets the j-th smallest ----
   {
