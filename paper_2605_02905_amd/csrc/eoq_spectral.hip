@@ -629,9 +629,11 @@ __device__ __forceinline__ double newton_rcp(double s) {
 // H_k = I - beta_k v_k v_k^T.  Per step: the 16 lanes that own row k form v and beta (the other lanes wait),
 // all lanes multiply p = beta A v over their live sub-tile (partial sums folded across the DPP row), then apply
 // A <- A - v w^T - w v^T with w = p - (beta/2)(v^T p) v.
-// A wave issues an instruction every eight cycles or so whatever the instructions are (two waves per SIMD: one every
-// five between them), so what a step costs is the number of instructions of the wave the others wait for.  The wave
-// that forms the reflector therefore does nothing else: the row goes to LDS as it is (one entry less alpha), and the
+// A wave by itself issues a double-precision instruction in about seven cycles and a 32-bit or scalar one in four to
+// five, however independent they are (two waves per SIMD, which is what the registers allow: four to five cycles per
+// double-precision instruction between them), so what a step costs is the number of instructions of the wave the
+// others wait for, while the SIMDs of the waiting waves serve the other workgroup of the compute unit.  The wave
+// that forms the reflector therefore does nothing that another wave can do: the row goes to LDS as it is (one entry less alpha), and the
 // float copy of the reflector for the back-transformation is made one step later by the next wave, which would wait
 // otherwise.
 // p = beta A v in LDS: entry i = l + 16 g at pbuf[l + PB_LD g].  Its writers are four consecutive rows l of up to eight
