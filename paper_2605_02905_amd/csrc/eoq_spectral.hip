@@ -1289,37 +1289,50 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
       else minors_sweep<true>(de, mu, tw + (lane * 2 + 1) * TW_STRIDE);
     }
     __syncthreads();
-    // (2) pivots, multipliers and twist index: 16 lanes per eigenvector, rows i = l + 16 m
-    if (tid < 16 * EV_BATCH && b0 + (tid >> 4) < r) {
-      const int ev = tid >> 4, l = tid & 15;
-      const double mu = lam_s[b0 + ev] * sc;
-      double2* F = tw + ev * 2 * TW_STRIDE;
-      double2* Bk = F + TW_STRIDE;
-      const double piv = 0x1.0p-100;  // smallest pivot magnitude (the matrix is scaled to norm <= 1)
-      double best = INFINITY;
+    // (2) pivots, multipliers and twist index: rows i = l + LG m of eigenvector tid / LG, with LG = 64 lanes per
+    // eigenvector while a batch has at most four of them (the usual case: all four waves share the divisions, two
+    // rows each) and 16 lanes otherwise
+    {
+      auto pivots = [&](auto lg_ic) __attribute__((always_inline)) {
+        constexpr int LG = decltype(lg_ic)::value;
+        const int ev = tid / LG, l = tid % LG;
+        if (ev < EV_BATCH && b0 + ev < r) {
+          const double mu = lam_s[b0 + ev] * sc;
+          double2* F = tw + ev * 2 * TW_STRIDE;
+          double2* Bk = F + TW_STRIDE;
+          const double piv = 0x1.0p-100;  // smallest pivot magnitude (the matrix is scaled to norm <= 1)
+          double best = INFINITY;
 #pragma unroll
-      for (int m = 0; m < 8; ++m) {
-        const int i = l + 16 * m;
-        const double2 f = F[i], bq = Bk[i];
-        const double fn = (fabs(f.x) < piv * fabs(f.y)) ? copysign(piv * fabs(f.y), f.x) : f.x;
-        const double bn = (fabs(bq.x) < piv * fabs(bq.y)) ? copysign(piv * fabs(bq.y), bq.x) : bq.x;
-        double g = fabs(fma(fn, newton_rcp(f.y), fma(bn, newton_rcp(bq.y), -(de[i].x - mu))));
-        if (!(g == g)) g = INFINITY;
-        double lmul = (i < D - 1) ? eT[i] * sc * f.y * newton_rcp(fn) : 0.0;   // e_i / D+_i
-        double umul = (i > 0) ? eT[i - 1] * sc * bq.y * newton_rcp(bn) : 0.0;  // e_{i-1} / D-_i
-        if (!isfinite(lmul)) lmul = 0.0;
-        if (!isfinite(umul)) umul = 0.0;
-        F[i].x = lmul;
-        Bk[i].x = umul;
-        // the row index rides in the low mantissa bits: the minimum of the keys carries its own position
-        const double key = __hiloint2double(__double2hiint(g), (__double2loint(g) & ~127) | i);
-        best = fmin(best, key);
-      }
-      best = fmin(best, dpp_mov<0xB1>(best));
-      best = fmin(best, dpp_mov<0x4E>(best));
-      best = fmin(best, dpp_mov<0x141>(best));
-      best = fmin(best, dpp_mov<0x140>(best));
-      if (l == 0) twist_s[ev] = __double2loint(best) & 127;
+          for (int m = 0; m < D / LG; ++m) {
+            const int i = l + LG * m;
+            const double2 f = F[i], bq = Bk[i];
+            const double fn = (fabs(f.x) < piv * fabs(f.y)) ? copysign(piv * fabs(f.y), f.x) : f.x;
+            const double bn = (fabs(bq.x) < piv * fabs(bq.y)) ? copysign(piv * fabs(bq.y), bq.x) : bq.x;
+            double g = fabs(fma(fn, newton_rcp(f.y), fma(bn, newton_rcp(bq.y), -(de[i].x - mu))));
+            if (!(g == g)) g = INFINITY;
+            double lmul = (i < D - 1) ? eT[i] * sc * f.y * newton_rcp(fn) : 0.0;   // e_i / D+_i
+            double umul = (i > 0) ? eT[i - 1] * sc * bq.y * newton_rcp(bn) : 0.0;  // e_{i-1} / D-_i
+            if (!isfinite(lmul)) lmul = 0.0;
+            if (!isfinite(umul)) umul = 0.0;
+            F[i].x = lmul;
+            Bk[i].x = umul;
+            // the row index rides in the low mantissa bits: the minimum of the keys carries its own position
+            const double key = __hiloint2double(__double2hiint(g), (__double2loint(g) & ~127) | i);
+            best = fmin(best, key);
+          }
+          best = fmin(best, dpp_mov<0xB1>(best));
+          best = fmin(best, dpp_mov<0x4E>(best));
+          best = fmin(best, dpp_mov<0x141>(best));
+          best = fmin(best, dpp_mov<0x140>(best));
+          if constexpr (LG == 64) {
+            best = fmin(best, __shfl_xor(best, 16, 64));
+            best = fmin(best, __shfl_xor(best, 32, 64));
+          }
+          if (l == 0) twist_s[ev] = __double2loint(best) & 127;
+        }
+      };
+      if (r - b0 <= 4) pivots(std::integral_constant<int, 64>{});
+      else pivots(std::integral_constant<int, 16>{});
     }
     __syncthreads();
     // (3) the vector itself, upwards (wave 0) and downwards (wave 1) from the twist index; z_i goes to F[i].y
