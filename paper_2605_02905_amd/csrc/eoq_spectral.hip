@@ -1071,8 +1071,9 @@ __global__ __launch_bounds__(THREADS, 2) void eoq_spectral_tridiag_kernel(
     }
   }
   __syncthreads();
-  // the inner products of the reflectors 96 .. 127 (the others were formed beside the one-wave tail)
-  if (tid < 48) reflector_product(144 + tid, refl, cW);
+  // the inner products of the reflectors 96 .. 127 (the others were formed beside the one-wave tail): by the last wave,
+  // while the first scales the tridiagonal matrix
+  if (tid >= THREADS - 48) reflector_product(144 + tid - (THREADS - 48), refl, cW);
 
   // ---- eigenvalues of T by Sturm-count multisection: lane pair j brackets the j-th smallest ----
   {
